@@ -1,0 +1,268 @@
+/*
+ * RelServe layer-step ORACLE -- test infrastructure, not product code.
+ * See relserve_oracle.h for what is computed, the readings taken where the
+ * paper is silent, and the precision.  Everything below is the definition
+ * written out: no tiling, no online softmax, no fusion.
+ */
+#include "relserve_oracle.h"
+
+#include <math.h>
+#include <stdlib.h>
+#include <string.h>
+
+#ifdef ORACLE_ACC_F64
+typedef double acc_t;
+#else
+typedef float acc_t;
+#endif
+
+int32_t oracle_acc_is_f64(void) { return (int32_t)(sizeof(acc_t) == sizeof(double)); }
+
+float oracle_bf16_to_f32(uint16_t b)
+{
+    uint32_t u = (uint32_t)b << 16;
+    float f;
+    memcpy(&f, &u, sizeof f);
+    return f;
+}
+
+uint16_t oracle_f32_to_bf16(float f)
+{
+    uint32_t u;
+    memcpy(&u, &f, sizeof u);
+    if ((u & 0x7fffffffu) > 0x7f800000u)        /* NaN stays NaN, quiet */
+        return (uint16_t)((u >> 16) | 0x0040u);
+    uint32_t lsb = (u >> 16) & 1u;              /* ties go to the even mantissa */
+    u += 0x7fffu + lsb;
+    return (uint16_t)(u >> 16);
+}
+
+/* R2: x_i * w_i / sqrt(mean(x^2) + eps) */
+void oracle_rmsnorm(const float* x, const uint16_t* w, float eps,
+                    int32_t n_rows, int32_t H, float* out)
+{
+    for (int32_t t = 0; t < n_rows; ++t) {
+        const float* xr = x + (size_t)t * H;
+        acc_t ss = 0;
+        for (int32_t i = 0; i < H; ++i) ss += (acc_t)xr[i] * (acc_t)xr[i];
+        float inv = (float)(1.0 / sqrt((double)ss / (double)H + (double)eps));
+        for (int32_t i = 0; i < H; ++i)
+            out[(size_t)t * H + i] = xr[i] * inv * oracle_bf16_to_f32(w[i]);
+    }
+}
+
+/* out[t, n] = <W[n, :], in[t, :]>  (Eq. 3; R8 for the orientation) */
+void oracle_linear(const uint16_t* W, int32_t N, int32_t K,
+                   const float* in, int32_t n_rows, float* out)
+{
+#pragma omp parallel for schedule(static)
+    for (int32_t n = 0; n < N; ++n) {
+        const uint16_t* wr = W + (size_t)n * K;
+        for (int32_t t = 0; t < n_rows; ++t) {
+            const float* xr = in + (size_t)t * K;
+            acc_t acc = 0;
+#pragma omp simd reduction(+ : acc)
+            for (int32_t k = 0; k < K; ++k)
+                acc += (acc_t)oracle_bf16_to_f32(wr[k]) * (acc_t)xr[k];
+            out[(size_t)t * N + n] = (float)acc;
+        }
+    }
+}
+
+/* R3: (v_i, v_{i+d/2}) rotated by angle pos * base^(-2i/d) */
+void oracle_rope(float* vec, int32_t d, int32_t pos, float base)
+{
+    int32_t half = d / 2;
+    for (int32_t i = 0; i < half; ++i) {
+        double theta = pow((double)base, -2.0 * (double)i / (double)d);
+        double ang = (double)pos * theta;
+        float c = (float)cos(ang), s = (float)sin(ang);
+        float a = vec[i], b = vec[i + half];
+        vec[i]        = a * c - b * s;
+        vec[i + half] = a * s + b * c;
+    }
+}
+
+/* R9: where the token at position pos of request r lives */
+static int64_t slot_of(const oracle_config* c, const oracle_batch* b, int32_t r, int32_t pos)
+{
+    int32_t page = b->block_table[(size_t)r * b->max_blocks + pos / c->page_size];
+    return (int64_t)page * c->page_size + pos % c->page_size;
+}
+
+int32_t oracle_kv_append(const oracle_config* c, const oracle_batch* b,
+                         const uint16_t* k, const uint16_t* v,
+                         uint16_t* k_pages, uint16_t* v_pages, int32_t num_pages,
+                         int32_t* slots_out)
+{
+    size_t row = (size_t)c->n_kv_heads * c->head_dim;
+    for (int32_t r = 0; r < b->num_reqs; ++r) {
+        int32_t q_len = b->q_start[r + 1] - b->q_start[r];
+        int32_t past = b->ctx_len[r] - q_len;
+        for (int32_t j = 0; j < q_len; ++j) {
+            int32_t t = b->q_start[r] + j;
+            int64_t slot = slot_of(c, b, r, past + j);
+            if (slot < 0 || slot >= (int64_t)num_pages * c->page_size) return -1;
+            memcpy(k_pages + (size_t)slot * row, k + (size_t)t * row, row * sizeof(uint16_t));
+            memcpy(v_pages + (size_t)slot * row, v + (size_t)t * row, row * sizeof(uint16_t));
+            if (slots_out) slots_out[t] = (int32_t)slot;
+        }
+    }
+    return 0;
+}
+
+/* Eq. 4, then the weighted value sum of Eq. 5, for every query head of one token */
+void oracle_attention_token(const oracle_config* c, const oracle_batch* b,
+                            int32_t r, int32_t pos, const float* q,
+                            const uint16_t* k_pages, const uint16_t* v_pages,
+                            float* out)
+{
+    int32_t d = c->head_dim, n_kv = c->n_kv_heads;
+    int32_t group = c->n_q_heads / n_kv;                       /* R7 */
+    float scale = (float)(1.0 / sqrt((double)d));              /* R4 */
+    int32_t n_keys = pos + 1;                                  /* R5: j <= i */
+    float* s = (float*)malloc((size_t)n_keys * sizeof(float));
+
+    for (int32_t a = 0; a < c->n_q_heads; ++a) {
+        int32_t kvh = a / group;
+        const float* qa = q + (size_t)a * d;
+        float m = -INFINITY;
+        for (int32_t j = 0; j < n_keys; ++j) {
+            const uint16_t* kj = k_pages + ((size_t)slot_of(c, b, r, j) * n_kv + kvh) * d;
+            acc_t dot = 0;
+            for (int32_t i = 0; i < d; ++i) dot += (acc_t)qa[i] * (acc_t)oracle_bf16_to_f32(kj[i]);
+            s[j] = (float)dot * scale;
+            if (s[j] > m) m = s[j];
+        }
+        acc_t denom = 0;
+        for (int32_t j = 0; j < n_keys; ++j) {
+            s[j] = expf(s[j] - m);          /* same ratio as Eq. 4; the shift only avoids overflow */
+            denom += (acc_t)s[j];
+        }
+        acc_t o[d];
+        for (int32_t i = 0; i < d; ++i) o[i] = 0;
+        for (int32_t j = 0; j < n_keys; ++j) {
+            const uint16_t* vj = v_pages + ((size_t)slot_of(c, b, r, j) * n_kv + kvh) * d;
+            for (int32_t i = 0; i < d; ++i) o[i] += (acc_t)s[j] * (acc_t)oracle_bf16_to_f32(vj[i]);
+        }
+        for (int32_t i = 0; i < d; ++i) out[(size_t)a * d + i] = (float)(o[i] / denom);
+    }
+    free(s);
+}
+
+int32_t oracle_layer_step(const oracle_config* c, const oracle_batch* b,
+                          const oracle_weights* w, const uint16_t* x,
+                          uint16_t* k_pages, uint16_t* v_pages, int32_t num_pages,
+                          const int32_t* rows, int32_t n_rows,
+                          float* y_f32, uint16_t* y_bf16,
+                          float* tap_attn_out, float* tap_x1)
+{
+    const int32_t H = c->hidden, d = c->head_dim, n_h = c->n_q_heads, n_kv = c->n_kv_heads;
+    const int32_t I = c->mlp_dim, P = c->page_size;
+    const int32_t q_dim = n_h * d, kv_dim = n_kv * d, qkv_dim = q_dim + 2 * kv_dim;
+    if (H <= 0 || d <= 0 || (d & 1) || n_kv <= 0 || n_h % n_kv || I <= 0 || P <= 0) return -2;
+    if (b->num_reqs < 0 || b->q_start[0] != 0) return -3;
+    const int32_t T = b->q_start[b->num_reqs];
+
+    /* token -> (request, position in its own sequence) */
+    int32_t* tok_req = (int32_t*)malloc(sizeof(int32_t) * (size_t)(T > 0 ? T : 1));
+    int32_t* tok_pos = (int32_t*)malloc(sizeof(int32_t) * (size_t)(T > 0 ? T : 1));
+    for (int32_t r = 0; r < b->num_reqs; ++r) {
+        int32_t q_len = b->q_start[r + 1] - b->q_start[r];
+        int32_t past = b->ctx_len[r] - q_len;
+        if (q_len < 0 || past < 0 || (b->ctx_len[r] + P - 1) / P > b->max_blocks) {
+            free(tok_req); free(tok_pos);
+            return -3;
+        }
+        for (int32_t j = 0; j < q_len; ++j) {
+            tok_req[b->q_start[r] + j] = r;
+            tok_pos[b->q_start[r] + j] = past + j;
+        }
+    }
+    if (T == 0) { free(tok_req); free(tok_pos); return 0; }
+
+    /* widen x */
+    float* xf = (float*)malloc(sizeof(float) * (size_t)T * H);
+    for (size_t i = 0; i < (size_t)T * H; ++i) xf[i] = oracle_bf16_to_f32(x[i]);
+
+    /* 1. input norm (R2), 2. q/k/v (Eq. 3) for every token of the batch */
+    float* h = (float*)malloc(sizeof(float) * (size_t)T * H);
+    oracle_rmsnorm(xf, w->w_in_norm, c->rms_eps, T, H, h);
+    float* qkv = (float*)malloc(sizeof(float) * (size_t)T * qkv_dim);
+    oracle_linear(w->w_qkv, qkv_dim, H, h, T, qkv);
+    free(h);
+
+    /* 3. rotary embedding on q and k (R3), 4. round k, v to bf16 and append (R5, R9) */
+    uint16_t* kb = (uint16_t*)malloc(sizeof(uint16_t) * (size_t)T * kv_dim);
+    uint16_t* vb = (uint16_t*)malloc(sizeof(uint16_t) * (size_t)T * kv_dim);
+    for (int32_t t = 0; t < T; ++t) {
+        float* row = qkv + (size_t)t * qkv_dim;
+        for (int32_t a = 0; a < n_h; ++a) oracle_rope(row + (size_t)a * d, d, tok_pos[t], c->rope_base);
+        for (int32_t g = 0; g < n_kv; ++g) oracle_rope(row + q_dim + (size_t)g * d, d, tok_pos[t], c->rope_base);
+        for (int32_t i = 0; i < kv_dim; ++i) {
+            kb[(size_t)t * kv_dim + i] = oracle_f32_to_bf16(row[q_dim + i]);
+            vb[(size_t)t * kv_dim + i] = oracle_f32_to_bf16(row[q_dim + kv_dim + i]);
+        }
+    }
+    int32_t rc = oracle_kv_append(c, b, kb, vb, k_pages, v_pages, num_pages, NULL);
+    free(kb); free(vb);
+    if (rc) { free(tok_req); free(tok_pos); free(xf); free(qkv); return -4; }
+
+    /* the rows that get the rest of the layer */
+    int32_t n_out = (rows && n_rows > 0) ? n_rows : T;
+    int32_t* sel = (int32_t*)malloc(sizeof(int32_t) * (size_t)n_out);
+    for (int32_t i = 0; i < n_out; ++i) {
+        sel[i] = (rows && n_rows > 0) ? rows[i] : i;
+        if (sel[i] < 0 || sel[i] >= T) {
+            free(tok_req); free(tok_pos); free(xf); free(qkv); free(sel);
+            return -5;
+        }
+    }
+
+    /* 5. attention over the cache (Eq. 4, Eq. 5 without W_o) */
+    float* attn = (float*)malloc(sizeof(float) * (size_t)n_out * q_dim);
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int32_t i = 0; i < n_out; ++i) {
+        int32_t t = sel[i];
+        oracle_attention_token(c, b, tok_req[t], tok_pos[t], qkv + (size_t)t * qkv_dim,
+                               k_pages, v_pages, attn + (size_t)i * q_dim);
+    }
+    free(qkv);
+    if (tap_attn_out) memcpy(tap_attn_out, attn, sizeof(float) * (size_t)n_out * q_dim);
+
+    /* 6. W_o (Eq. 5) and the residual (R1) */
+    float* x1 = (float*)malloc(sizeof(float) * (size_t)n_out * H);
+    oracle_linear(w->w_o, H, q_dim, attn, n_out, x1);
+    free(attn);
+    for (int32_t i = 0; i < n_out; ++i)
+        for (int32_t j = 0; j < H; ++j)
+            x1[(size_t)i * H + j] += xf[(size_t)sel[i] * H + j];
+    free(xf);
+    if (tap_x1) memcpy(tap_x1, x1, sizeof(float) * (size_t)n_out * H);
+
+    /* 7. post norm, gate/up, silu(g) * u, down, residual (R1) */
+    float* h2 = (float*)malloc(sizeof(float) * (size_t)n_out * H);
+    oracle_rmsnorm(x1, w->w_post_norm, c->rms_eps, n_out, H, h2);
+    float* gu = (float*)malloc(sizeof(float) * (size_t)n_out * 2 * I);
+    oracle_linear(w->w_gate_up, 2 * I, H, h2, n_out, gu);
+    free(h2);
+    float* act = (float*)malloc(sizeof(float) * (size_t)n_out * I);
+    for (int32_t i = 0; i < n_out; ++i)
+        for (int32_t j = 0; j < I; ++j) {
+            float g = gu[(size_t)i * 2 * I + j], u = gu[(size_t)i * 2 * I + I + j];
+            act[(size_t)i * I + j] = g / (1.0f + expf(-g)) * u;
+        }
+    free(gu);
+    float* mlp = (float*)malloc(sizeof(float) * (size_t)n_out * H);
+    oracle_linear(w->w_down, H, I, act, n_out, mlp);
+    free(act);
+
+    /* 8. y = x1 + mlp, fp32 and (optionally) rounded to bf16 */
+    for (size_t i = 0; i < (size_t)n_out * H; ++i) {
+        float y = x1[i] + mlp[i];
+        y_f32[i] = y;
+        if (y_bf16) y_bf16[i] = oracle_f32_to_bf16(y);
+    }
+    free(mlp); free(x1); free(sel); free(tok_req); free(tok_pos);
+    return 0;
+}

@@ -1,0 +1,298 @@
+"""Seeded synthetic inputs shaped like relQuery serving batches.
+
+This module holds no arithmetic of the layer step: it only draws random
+numbers, lays out page tables and converts fp32 draws to bf16 bit patterns.
+Both the CPU oracle's tests and the GPU path's tests/benchmark take their
+inputs from here so that the two sides see the same bits.
+
+Workload structure (Sec. 2.2 Def. 2.1: the requests of one relQuery are one
+template filled with different rows, hence a long shared token prefix and a
+short private suffix; Sec. 5.1 "Datasets and Workloads": inputs of a few
+hundred tokens, outputs of 5-100 tokens, 1-100 requests per relQuery).  The
+datasets and trained weights themselves are replaced by random draws.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, field, replace
+
+import numpy as np
+
+
+# ----------------------------------------------------------------------------
+# bf16 bit patterns (format conversion only)
+# ----------------------------------------------------------------------------
+def f32_to_bf16_bits(a: np.ndarray) -> np.ndarray:
+    """Round-to-nearest-even fp32 -> bf16, returned as uint16 bit patterns."""
+    u = np.ascontiguousarray(a, dtype=np.float32).view(np.uint32)
+    lsb = (u >> np.uint32(16)) & np.uint32(1)
+    r = (u + np.uint32(0x7FFF) + lsb) >> np.uint32(16)
+    return r.astype(np.uint16)
+
+
+def bf16_bits_to_f32(b: np.ndarray) -> np.ndarray:
+    return (np.ascontiguousarray(b, dtype=np.uint16).astype(np.uint32) << np.uint32(16)).view(np.float32)
+
+
+# ----------------------------------------------------------------------------
+# shapes
+# ----------------------------------------------------------------------------
+@dataclass(frozen=True)
+class LayerShape:
+    hidden: int
+    n_q_heads: int
+    n_kv_heads: int
+    head_dim: int
+    mlp_dim: int
+    page_size: int = 16
+    rms_eps: float = 1e-5
+    rope_base: float = 10000.0
+
+    @property
+    def q_dim(self) -> int:
+        return self.n_q_heads * self.head_dim
+
+    @property
+    def kv_dim(self) -> int:
+        return self.n_kv_heads * self.head_dim
+
+    @property
+    def qkv_dim(self) -> int:
+        return self.q_dim + 2 * self.kv_dim
+
+    @property
+    def params(self) -> int:
+        H, I = self.hidden, self.mlp_dim
+        return self.qkv_dim * H + H * self.q_dim + 3 * I * H + 2 * H
+
+
+TINY = LayerShape(256, 4, 4, 64, 688)
+TINY_GQA = LayerShape(256, 8, 2, 64, 688)
+TINY_D128 = LayerShape(256, 2, 1, 128, 688)
+LLAMA_13B = LayerShape(5120, 40, 40, 128, 13824)
+LLAMA_70B = LayerShape(8192, 64, 8, 128, 28672)
+
+
+# ----------------------------------------------------------------------------
+# batch descriptor
+# ----------------------------------------------------------------------------
+@dataclass
+class Batch:
+    """Host-side batch descriptor (what the scheduler hands to the GPU worker)."""
+    q_start: np.ndarray        # int32 [B+1]
+    ctx_len: np.ndarray        # int32 [B], sequence length after this step's append
+    block_table: np.ndarray    # int32 [B, max_blocks]
+    prefix_id: np.ndarray      # int32 [B], -1 = no shared prefix
+    prefix_len: np.ndarray     # int32 [num_prefixes], multiples of the page size
+    num_pages: int
+    name: str = ""
+
+    @property
+    def num_reqs(self) -> int:
+        return int(len(self.ctx_len))
+
+    @property
+    def T(self) -> int:
+        return int(self.q_start[-1])
+
+    @property
+    def q_len(self) -> np.ndarray:
+        return np.diff(self.q_start).astype(np.int32)
+
+    @property
+    def past(self) -> np.ndarray:
+        return (self.ctx_len - self.q_len).astype(np.int32)
+
+    def select(self, reqs) -> "Batch":
+        """Sub-batch holding the given requests (same pages, same cache)."""
+        reqs = np.asarray(reqs, dtype=np.int64)
+        ql = self.q_len[reqs]
+        qs = np.zeros(len(reqs) + 1, np.int32)
+        qs[1:] = np.cumsum(ql)
+        return replace(self, q_start=qs, ctx_len=self.ctx_len[reqs].copy(),
+                       block_table=np.ascontiguousarray(self.block_table[reqs]),
+                       prefix_id=self.prefix_id[reqs].copy())
+
+    def token_rows(self, reqs) -> np.ndarray:
+        """Packed row indices (in THIS batch) of the query tokens of the given requests."""
+        out = [np.arange(self.q_start[r], self.q_start[r + 1]) for r in reqs]
+        return np.concatenate(out).astype(np.int64) if out else np.zeros(0, np.int64)
+
+
+class PagePool:
+    """Hands out page ids in a seeded random order (non-contiguous on purpose)."""
+
+    def __init__(self, num_pages: int, rng: np.random.Generator):
+        self.order = rng.permutation(num_pages).astype(np.int32)
+        self.next = 0
+        self.num_pages = num_pages
+
+    def take(self, n: int) -> np.ndarray:
+        if self.next + n > self.num_pages:
+            raise ValueError("page pool exhausted")
+        out = self.order[self.next:self.next + n]
+        self.next += n
+        return out
+
+
+def build_batch(shape: LayerShape, q_len, ctx_len, prefix_id=None, prefix_len=(), seed: int = 0,
+                spare_pages: int = 3, name: str = "") -> Batch:
+    """Lay out block tables: one page run per shared prefix, private pages for the rest."""
+    P = shape.page_size
+    q_len = np.asarray(q_len, np.int32)
+    ctx_len = np.asarray(ctx_len, np.int32)
+    B = len(q_len)
+    prefix_id = np.full(B, -1, np.int32) if prefix_id is None else np.asarray(prefix_id, np.int32)
+    prefix_len = np.asarray(prefix_len, np.int32).reshape(-1)
+    assert np.all(prefix_len % P == 0)
+    blocks = (ctx_len + P - 1) // P
+    max_blocks = int(blocks.max()) if B else 1
+    shared = prefix_len // P
+    shared_of = np.zeros(B, np.int64)
+    if len(shared):
+        shared_of = np.where(prefix_id >= 0, shared[np.maximum(prefix_id, 0)], 0)
+    priv = blocks - shared_of
+    assert np.all(priv >= 0)
+    num_pages = int(shared.sum() + priv.sum() + spare_pages)
+    rng = np.random.default_rng(seed ^ 0x5EED)
+    pool = PagePool(num_pages, rng)
+    prefix_pages = [pool.take(int(n)) for n in shared]
+    bt = np.full((B, max_blocks), -1, np.int32)
+    for r in range(B):
+        n0 = 0
+        if prefix_id[r] >= 0:
+            pp = prefix_pages[prefix_id[r]]
+            bt[r, :len(pp)] = pp
+            n0 = len(pp)
+        bt[r, n0:blocks[r]] = pool.take(int(blocks[r] - n0))
+    qs = np.zeros(B + 1, np.int32)
+    qs[1:] = np.cumsum(q_len)
+    # unused tail entries point at page 0: harmless, never dereferenced by a correct reader
+    bt[bt < 0] = 0
+    return Batch(qs, ctx_len, bt, prefix_id, prefix_len, num_pages, name)
+
+
+# ----------------------------------------------------------------------------
+# tensors
+# ----------------------------------------------------------------------------
+def make_weights(shape: LayerShape, seed: int) -> dict:
+    """bf16 bit patterns: projections ~N(0, 0.02), norm weights 1 + N(0, 0.02)."""
+    rng = np.random.default_rng(seed)
+    H, I = shape.hidden, shape.mlp_dim
+
+    def proj(n, k):
+        return f32_to_bf16_bits(rng.standard_normal((n, k), dtype=np.float32) * np.float32(0.02))
+
+    def norm():
+        return f32_to_bf16_bits(np.float32(1.0) + rng.standard_normal(H, dtype=np.float32) * np.float32(0.02))
+
+    return {"w_in_norm": norm(), "w_qkv": proj(shape.qkv_dim, H), "w_o": proj(H, shape.q_dim),
+            "w_post_norm": norm(), "w_gate_up": proj(2 * I, H), "w_down": proj(H, I)}
+
+
+def make_activations(T: int, H: int, seed: int) -> np.ndarray:
+    rng = np.random.default_rng(seed + 7919)
+    return f32_to_bf16_bits(rng.standard_normal((T, H), dtype=np.float32))
+
+
+def make_cache(shape: LayerShape, num_pages: int, seed: int, fill: bool = True):
+    """K and V page pools [num_pages, P, n_kv, d] as bf16 bits.
+
+    With fill=True every slot (used or not) holds an N(0,1) draw: it stands in
+    for the keys and values of earlier steps, and makes a read of a slot that
+    the block tables do not name show up as a mismatch.
+    """
+    shp = (num_pages, shape.page_size, shape.n_kv_heads, shape.head_dim)
+    if not fill:
+        return np.zeros(shp, np.uint16), np.zeros(shp, np.uint16)
+    rng = np.random.default_rng(seed + 104729)
+    k = f32_to_bf16_bits(rng.standard_normal(shp, dtype=np.float32))
+    v = f32_to_bf16_bits(rng.standard_normal(shp, dtype=np.float32))
+    return k, v
+
+
+# ----------------------------------------------------------------------------
+# the benchmark configurations
+# ----------------------------------------------------------------------------
+@dataclass
+class Workload:
+    name: str
+    shape: LayerShape
+    batch: Batch
+    seed: int
+    notes: str = ""
+    extra: dict = field(default_factory=dict)
+
+
+def workload_tiny(seed: int = 1000, shape: LayerShape = TINY) -> Workload:
+    """2 prefill rows of 64 tokens (no past) + 6 decode rows of context 128."""
+    q_len = [64, 64] + [1] * 6
+    ctx = [64, 64] + [128] * 6
+    b = build_batch(shape, q_len, ctx, seed=seed, name="tiny")
+    return Workload("tiny", shape, b, seed)
+
+
+def workload_tiny_prefix(seed: int = 1001, shape: LayerShape = TINY) -> Workload:
+    """Test-only: a 32-token shared prefix, continuing chunks and decode rows mixed."""
+    P = shape.page_size
+    pl = 2 * P
+    q_len = [40, 1, 17, 1, 1, 33, 5]
+    ctx = [pl + 40, pl + 9, pl + 30, pl + 1, 70, 33 + 64, pl + 5]
+    pid = [0, 0, 0, 0, -1, -1, 0]
+    b = build_batch(shape, q_len, ctx, pid, [pl], seed=seed, name="tiny_prefix")
+    return Workload("tiny_prefix", shape, b, seed)
+
+
+def workload_relquery_13b(seed: int = 1001, n_rows: int = 200, n_prefill: int = 16,
+                          prefix: int = 512, shape: LayerShape = LLAMA_13B) -> Workload:
+    """One relQuery: rows share a template prefix; a few rows prefill their suffix, the rest decode."""
+    rng = np.random.default_rng(seed)
+    suffix = rng.integers(30, 121, n_rows)
+    gen = rng.integers(1, 17, n_rows)
+    q_len = np.where(np.arange(n_rows) < n_prefill, suffix, 1)
+    ctx = np.where(np.arange(n_rows) < n_prefill, prefix + suffix, prefix + suffix + gen)
+    b = build_batch(shape, q_len, ctx, np.zeros(n_rows, np.int32), [prefix], seed=seed,
+                    name="relquery_13b")
+    return Workload("relquery_13b_16p184d", shape, b, seed)
+
+
+def workload_decode_heavy_70b(seed: int = 1002, with_chunk: bool = True, n_rel: int = 4,
+                              rows_per_rel: int = 64, prefix: int = 768, chunk: int = 2048,
+                              shape: LayerShape = LLAMA_70B) -> Workload:
+    """256 decode rows from 4 relQueries (own prefix each) and, optionally, one prefill chunk."""
+    rng = np.random.default_rng(seed)
+    n = n_rel * rows_per_rel
+    ctx = rng.integers(600, 1501, n)
+    ctx = np.maximum(ctx, prefix + 1)            # a member has left its template behind
+    pid = np.repeat(np.arange(n_rel), rows_per_rel)
+    q_len = np.ones(n, np.int64)
+    if with_chunk:
+        ctx = np.append(ctx, chunk)
+        q_len = np.append(q_len, chunk)
+        pid = np.append(pid, -1)
+    b = build_batch(shape, q_len, ctx, pid, [prefix] * n_rel, seed=seed, name="decode_heavy_70b")
+    return Workload("decode_heavy_70b" + ("_chunk2048" if with_chunk else "_decode_only"), shape, b, seed)
+
+
+def workload_prefill_only_13b(seed: int = 1003, n_req: int = 64, total: int = 8192, prefix: int = 1024,
+                              lo: int = 50, hi: int = 200, shape: LayerShape = LLAMA_13B) -> Workload:
+    """64 suffix prefills (sum 8192 tokens) behind one cached 1024-token template prefix."""
+    rng = np.random.default_rng(seed)
+    s = rng.integers(lo, hi + 1, n_req)
+    i = 0
+    while s.sum() != total:                      # nudge round-robin, inside the bounds
+        step = 1 if s.sum() < total else -1
+        if lo <= s[i % n_req] + step <= hi:
+            s[i % n_req] += step
+        i += 1
+    b = build_batch(shape, s, prefix + s, np.zeros(n_req, np.int32), [prefix], seed=seed,
+                    name="prefill_only_13b")
+    return Workload("prefill_only_13b", shape, b, seed)
+
+
+def workload_decode_plus_chunk_13b(chunk: int, seed: int = 1004, n_dec: int = 128, ctx: int = 1024,
+                                   shape: LayerShape = LLAMA_13B) -> Workload:
+    """128 decode rows of context 1024 and one prefill chunk of `chunk` tokens (0 = none)."""
+    q_len = [1] * n_dec + ([chunk] if chunk else [])
+    c = [ctx] * n_dec + ([chunk] if chunk else [])
+    b = build_batch(shape, q_len, c, seed=seed, name=f"decode128_chunk{chunk}")
+    return Workload(f"decode128_chunk{chunk}_13b", shape, b, seed)

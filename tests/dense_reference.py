@@ -1,0 +1,65 @@
+"""Third opinion used to pin the oracle: the same layer written with PyTorch CPU
+library routines in fp64 on CONTIGUOUS sequences (no pages, no cache, no batch
+descriptor).  Each request's whole sequence is recomputed from scratch, causal
+attention comes from torch's scaled_dot_product_attention.  Test helper only.
+"""
+import numpy as np
+import torch
+import torch.nn.functional as F
+
+from paper_2601_11546_amd.workloads import bf16_bits_to_f32
+
+
+def _t(bits):
+    return torch.from_numpy(bf16_bits_to_f32(bits).astype(np.float64))
+
+
+def rope_complex(v: torch.Tensor, pos: torch.Tensor, base: float) -> torch.Tensor:
+    """v: [L, heads, d]; pairs (i, i+d/2) seen as complex numbers times e^{i pos theta_i}."""
+    d = v.shape[-1]
+    half = d // 2
+    theta = torch.tensor(base, dtype=torch.float64) ** (-torch.arange(half, dtype=torch.float64) * 2.0 / d)
+    z = torch.complex(v[..., :half], v[..., half:])
+    rot = torch.polar(torch.ones_like(theta)[None, :].expand(len(pos), half).contiguous(),
+                      pos.to(torch.float64)[:, None] * theta[None, :])
+    z = z * rot[:, None, :]
+    return torch.cat([z.real, z.imag], dim=-1)
+
+
+def dense_layer(shape, weights, x_bits, round_kv_bf16=True, kv_override=None):
+    """x_bits: [L, H] one request's whole sequence.  Returns dict of fp64 tensors.
+
+    kv_override: optional (k, v) fp64 tensors [L, n_kv, d] used instead of the
+    recomputed keys/values (lets a test feed the oracle's cached bits back in).
+    """
+    H, d, nh, nkv = shape.hidden, shape.head_dim, shape.n_q_heads, shape.n_kv_heads
+    x = _t(x_bits)
+    L = x.shape[0]
+    w = {k: _t(v) for k, v in weights.items()}
+    h = F.rms_norm(x, (H,), w["w_in_norm"], eps=shape.rms_eps)
+    qkv = F.linear(h, w["w_qkv"])
+    q = qkv[:, :nh * d].reshape(L, nh, d)
+    k = qkv[:, nh * d:(nh + nkv) * d].reshape(L, nkv, d)
+    v = qkv[:, (nh + nkv) * d:].reshape(L, nkv, d)
+    pos = torch.arange(L)
+    q = rope_complex(q, pos, shape.rope_base)
+    k = rope_complex(k, pos, shape.rope_base)
+    if round_kv_bf16:
+        k = k.to(torch.float32).to(torch.bfloat16).to(torch.float64)
+        v = v.to(torch.float32).to(torch.bfloat16).to(torch.float64)
+    k_own, v_own = k, v
+    if kv_override is not None:
+        k, v = kv_override
+    rep = nh // nkv
+    kk = k.repeat_interleave(rep, dim=1)
+    vv = v.repeat_interleave(rep, dim=1)
+    o = F.scaled_dot_product_attention(q.transpose(0, 1)[None], kk.transpose(0, 1)[None],
+                                       vv.transpose(0, 1)[None], is_causal=True)[0]
+    o = o.transpose(0, 1).reshape(L, nh * d)
+    x1 = x + F.linear(o, w["w_o"])
+    h2 = F.rms_norm(x1, (H,), w["w_post_norm"], eps=shape.rms_eps)
+    gu = F.linear(h2, w["w_gate_up"])
+    I = shape.mlp_dim
+    act = F.silu(gu[:, :I]) * gu[:, I:]
+    y = x1 + F.linear(act, w["w_down"])
+    return {"y": y, "x1": x1, "attn_out": o, "k": k_own, "v": v_own, "q": q}

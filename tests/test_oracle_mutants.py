@@ -1,0 +1,78 @@
+"""Do the pins bite?  Each case plants one plausible mistake in a COPY of the
+oracle's C source (text substitution, CPU only), builds it, and requires that at
+least one pin of tests/test_oracle_pins.py fails on it.
+"""
+import inspect
+import os
+
+import pytest
+
+from oracle import relserve_oracle as ro
+from tests import test_oracle_pins as pins
+
+MUTANTS = [
+    ("eps_outside_root", "1.0 / sqrt((double)ss / (double)H + (double)eps)", "1.0 / (sqrt((double)ss / (double)H) + (double)eps)"),
+    ("norm_weight_dropped", "xr[i] * inv * oracle_bf16_to_f32(w[i])", "xr[i] * inv"),
+    ("rope_sign", "vec[i]        = a * c - b * s;", "vec[i]        = a * c + b * s;"),
+    ("rope_exponent", "-2.0 * (double)i / (double)d", "-1.0 * (double)i / (double)d"),
+    ("rope_k_position", "row + q_dim + (size_t)g * d, d, tok_pos[t]", "row + q_dim + (size_t)g * d, d, 0"),
+    ("position_ignores_past", "tok_pos[b->q_start[r] + j] = past + j;", "tok_pos[b->q_start[r] + j] = j;"),
+    ("causal_excludes_self", "int32_t n_keys = pos + 1;", "int32_t n_keys = pos > 0 ? pos : 1;"),
+    ("scale_1_over_d", "(float)(1.0 / sqrt((double)d));", "(float)(1.0 / (double)d);"),
+    ("gqa_interleaved", "int32_t kvh = a / group;", "int32_t kvh = a % n_kv;"),
+    ("slot_page_offset", "+ pos % c->page_size;", "+ (pos + 1) % c->page_size;"),
+    ("residual_attn_dropped", "x1[(size_t)i * H + j] += xf[(size_t)sel[i] * H + j];", "x1[(size_t)i * H + j] += 0.0f * xf[(size_t)sel[i] * H + j];"),
+    ("silu_sign", "g / (1.0f + expf(-g)) * u", "g / (1.0f + expf(g)) * u"),
+    ("gate_up_swapped", "float g = gu[(size_t)i * 2 * I + j], u = gu[(size_t)i * 2 * I + I + j];",
+     "float u = gu[(size_t)i * 2 * I + j], g = gu[(size_t)i * 2 * I + I + j];"),
+    ("residual_mlp_dropped", "float y = x1[i] + mlp[i];", "float y = mlp[i];"),
+    ("bf16_truncation", "u += 0x7fffu + lsb;", "(void)lsb;"),
+    ("kv_not_rounded_through_cache", "vb[(size_t)t * kv_dim + i] = oracle_f32_to_bf16(row[q_dim + kv_dim + i]);",
+     "vb[(size_t)t * kv_dim + i] = oracle_f32_to_bf16(row[q_dim + i]);"),
+    ("softmax_unnormalised", "out[(size_t)a * d + i] = (float)(o[i] / denom);", "out[(size_t)a * d + i] = (float)(o[i]);"),
+]
+
+
+def _pin_functions():
+    out = []
+    for name, fn in inspect.getmembers(pins, inspect.isfunction):
+        if not name.startswith("test_"):
+            continue
+        params = list(inspect.signature(fn).parameters)
+        extra = [p for p in params if p not in ("oracle", "oracle64")]
+        marks = [m for m in getattr(fn, "pytestmark", []) if m.name == "parametrize"]
+        if extra and not marks:
+            continue
+        cases = [{}]
+        for m in marks:
+            key, vals = m.args
+            cases = [dict(c, **{key: v}) for c in cases for v in vals]
+        out.append((name, fn, params, cases))
+    return out
+
+
+@pytest.mark.parametrize("name,old,new", MUTANTS, ids=[m[0] for m in MUTANTS])
+def test_planted_mistake_is_caught(tmp_path, name, old, new):
+    src = open(ro._SRC).read()
+    assert src.count(old) == 1, f"mutation anchor for {name} not unique in the oracle source"
+    msrc = tmp_path / "mutant.c"
+    msrc.write_text(src.replace(old, new))
+    lib = str(tmp_path / f"mutant_{name}.so")
+    ro.build(force=True, src=str(msrc), out={"f32": lib})
+    mutant = ro.Oracle(lib)
+    caught = []
+    for tname, fn, params, cases in _pin_functions():
+        for case in cases:
+            kw = dict(case)
+            if "oracle" in params:
+                kw["oracle"] = mutant
+            if "oracle64" in params:
+                kw["oracle64"] = mutant
+            try:
+                fn(**kw)
+            except (AssertionError, ValueError, FloatingPointError):
+                caught.append(tname)
+                break
+        if caught:
+            break
+    assert caught, f"no pin noticed the planted mistake '{name}'"

@@ -1,0 +1,419 @@
+"""Pins for the CPU oracle: each piece is checked against something that is not
+the oracle itself -- a PyTorch/numpy library routine in fp64, a brute-force
+evaluation of Eq. 4-5 (Sec. 2.3) on contiguous tensors, a closed form, or an
+invariant that the paper's caching statements imply (Sec. 2.3 "KV Cache",
+"Prefix Cache"; chunked prefill, Sec. 5.1 baselines).  No GPU needed.
+"""
+import numpy as np
+import pytest
+import torch
+import torch.nn.functional as F
+
+from paper_2601_11546_amd import workloads as W
+from tests.dense_reference import dense_layer, rope_complex
+from tests.flows import gather_kv, make_flow, run_flow
+
+SHAPES = {"mha": W.TINY, "gqa": W.TINY_GQA, "d128": W.TINY_D128}
+
+
+def oracle_stepper(oracle, shape, weights, k_pages, v_pages, what="y_f32"):
+    def step(batch, x):
+        res = oracle.layer_step(shape, batch, weights, x, k_pages, v_pages)
+        return getattr(res, what)
+    return step
+
+
+# ---------------------------------------------------------------------------
+# number format
+# ---------------------------------------------------------------------------
+def test_bf16_round_matches_torch(oracle):
+    rng = np.random.default_rng(0)
+    vals = np.concatenate([
+        rng.standard_normal(4000).astype(np.float32) * np.float32(10.0) ** rng.integers(-30, 30, 4000).astype(np.float32),
+        np.array([0.0, -0.0, 1.0, 1.00390625, 1.01171875, -1.00390625, 3.3895314e38, 3.4e38,
+                  np.inf, -np.inf, 1e-40, 65504.0, 1.0 + 2.0 ** -8 + 2.0 ** -20], np.float32)])
+    want = torch.from_numpy(vals).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    got = np.array([oracle.f32_to_bf16(v) for v in vals], np.uint16)
+    np.testing.assert_array_equal(got, want)
+    np.testing.assert_array_equal(W.f32_to_bf16_bits(vals), want)          # the input generator's rounding too
+    back = np.array([oracle.bf16_to_f32(b) for b in want], np.float32)
+    np.testing.assert_array_equal(back, torch.from_numpy(want.view(np.int16)).view(torch.bfloat16).float().numpy())
+    assert np.isnan(oracle.bf16_to_f32(oracle.f32_to_bf16(float("nan"))))
+
+
+# ---------------------------------------------------------------------------
+# elementwise pieces against library routines and closed forms
+# ---------------------------------------------------------------------------
+def test_rmsnorm_matches_torch_and_invariants(oracle):
+    rng = np.random.default_rng(1)
+    x = rng.standard_normal((5, 96)).astype(np.float32) * 3
+    w = W.f32_to_bf16_bits(1 + 0.1 * rng.standard_normal(96).astype(np.float32))
+    got = oracle.rmsnorm(x, w, 1e-5)
+    want = F.rms_norm(torch.from_numpy(x).double(), (96,), torch.from_numpy(W.bf16_bits_to_f32(w)).double(), eps=1e-5)
+    np.testing.assert_allclose(got, want.numpy(), rtol=2e-6, atol=1e-6)
+    # unit weights, eps -> 0: rows have unit RMS, and positive rescaling of x changes nothing
+    ones = W.f32_to_bf16_bits(np.ones(96, np.float32))
+    y = oracle.rmsnorm(x, ones, 0.0)
+    np.testing.assert_allclose(np.sqrt((y.astype(np.float64) ** 2).mean(1)), 1.0, rtol=1e-6)
+    np.testing.assert_allclose(oracle.rmsnorm(x * 7.5, ones, 0.0), y, rtol=2e-6)
+    # eps sits inside the root: a zero row stays zero and a tiny row is damped by sqrt(eps)
+    tiny = np.full((1, 96), 1e-4, np.float32)
+    np.testing.assert_allclose(oracle.rmsnorm(tiny, ones, 1e-2), 1e-4 / np.sqrt(1e-8 + 1e-2), rtol=1e-5)
+
+
+def test_linear_orientation_matches_matmul(oracle):
+    rng = np.random.default_rng(2)
+    Wt = W.f32_to_bf16_bits(rng.standard_normal((7, 13)).astype(np.float32))
+    x = rng.standard_normal((3, 13)).astype(np.float32)
+    want = x.astype(np.float64) @ W.bf16_bits_to_f32(Wt).astype(np.float64).T
+    np.testing.assert_allclose(oracle.linear(Wt, x), want, rtol=1e-5, atol=1e-5)
+    # a one-hot input row reads out one column of W
+    e = np.zeros((1, 13), np.float32)
+    e[0, 4] = 1
+    np.testing.assert_array_equal(oracle.linear(Wt, e)[0], W.bf16_bits_to_f32(Wt)[:, 4])
+
+
+@pytest.mark.parametrize("d", [8, 64, 128])
+def test_rope_closed_forms(oracle, d):
+    rng = np.random.default_rng(3)
+    q = rng.standard_normal(d).astype(np.float32)
+    k = rng.standard_normal(d).astype(np.float32)
+    base = 10000.0
+    np.testing.assert_array_equal(oracle.rope(q, 0, base), q)                       # position 0 = identity
+    for pos in (1, 17, 513, 4095):
+        r = oracle.rope(q, pos, base)
+        want = rope_complex(torch.from_numpy(q).double()[None, None], torch.tensor([pos]), base)[0, 0]
+        np.testing.assert_allclose(r, want.numpy(), rtol=0, atol=2e-6)
+        np.testing.assert_allclose(np.linalg.norm(r.astype(np.float64)), np.linalg.norm(q.astype(np.float64)), rtol=1e-6)
+    # <rope(q, m), rope(k, n)> depends only on m - n
+    a = float(oracle.rope(q, 40, base).astype(np.float64) @ oracle.rope(k, 25, base).astype(np.float64))
+    b = float(oracle.rope(q, 1015, base).astype(np.float64) @ oracle.rope(k, 1000, base).astype(np.float64))
+    assert abs(a - b) < 2e-4
+    # first pair turns by exactly pos radians (theta_0 = 1), the last pair hardly moves
+    e = np.zeros(d, np.float32)
+    e[0] = 1
+    r = oracle.rope(e, 3, base)
+    np.testing.assert_allclose([r[0], r[d // 2]], [np.cos(3.0), np.sin(3.0)], atol=1e-7)
+    e = np.zeros(d, np.float32)
+    e[d // 2 - 1] = 1
+    r = oracle.rope(e, 1, base)
+    th = base ** (-(d - 2) / d)
+    np.testing.assert_allclose([r[d // 2 - 1], r[d - 1]], [np.cos(th), np.sin(th)], atol=1e-7)
+
+
+# ---------------------------------------------------------------------------
+# cache placement
+# ---------------------------------------------------------------------------
+def test_kv_append_slots_brute_force(oracle):
+    shape = W.TINY_GQA
+    wl = W.workload_tiny_prefix(shape=shape)
+    b = wl.batch
+    rng = np.random.default_rng(4)
+    k = rng.integers(0, 2 ** 16, (b.T, shape.n_kv_heads, shape.head_dim)).astype(np.uint16)
+    v = rng.integers(0, 2 ** 16, (b.T, shape.n_kv_heads, shape.head_dim)).astype(np.uint16)
+    kp, vp = W.make_cache(shape, b.num_pages, 5)
+    kp0, vp0 = kp.copy(), vp.copy()
+    slots = oracle.kv_append(shape, b, k, v, kp, vp)
+    P = shape.page_size
+    want_k, want_v = kp0.reshape(-1, shape.n_kv_heads, shape.head_dim).copy(), vp0.reshape(-1, shape.n_kv_heads, shape.head_dim).copy()
+    seen = set()
+    for r in range(b.num_reqs):
+        for j in range(b.q_len[r]):
+            pos = int(b.past[r]) + j
+            slot = int(b.block_table[r, pos // P]) * P + pos % P
+            t = int(b.q_start[r]) + j
+            assert slots[t] == slot
+            assert slot not in seen
+            seen.add(slot)
+            want_k[slot] = k[t]
+            want_v[slot] = v[t]
+    np.testing.assert_array_equal(kp.reshape(want_k.shape), want_k)     # written slots hold the rows, all others untouched
+    np.testing.assert_array_equal(vp.reshape(want_v.shape), want_v)
+    assert len(seen) == b.T
+
+
+# ---------------------------------------------------------------------------
+# attention: brute force of Eq. 4-5 and closed forms
+# ---------------------------------------------------------------------------
+def _one_request_batch(shape, L, seed):
+    return W.build_batch(shape, [1], [L], seed=seed)
+
+
+@pytest.mark.parametrize("name", list(SHAPES))
+def test_attention_token_brute_force(oracle, name):
+    shape = SHAPES[name]
+    L = 37
+    b = _one_request_batch(shape, L, 6)
+    kp, vp = W.make_cache(shape, b.num_pages, 7)
+    rng = np.random.default_rng(8)
+    q = rng.standard_normal((shape.n_q_heads, shape.head_dim)).astype(np.float32)
+    kc, vc = gather_kv(shape, b.block_table[0], L, kp, vp)
+    K = W.bf16_bits_to_f32(kc).astype(np.float64)
+    V = W.bf16_bits_to_f32(vc).astype(np.float64)
+    g = shape.n_q_heads // shape.n_kv_heads
+    for pos in (0, 1, 15, 16, 36):
+        got = oracle.attention_token(shape, b, 0, pos, q, kp, vp)
+        for a in range(shape.n_q_heads):
+            s = K[:pos + 1, a // g] @ q[a].astype(np.float64) / np.sqrt(shape.head_dim)
+            alpha = np.exp(s) / np.exp(s).sum()                      # Eq. 4 exactly as printed (no max shift)
+            want = alpha @ V[:pos + 1, a // g]                        # Eq. 5 before W_o
+            np.testing.assert_allclose(got[a], want, rtol=2e-5, atol=2e-6)
+
+
+def test_attention_closed_forms(oracle):
+    shape = W.TINY
+    L = 20
+    b = _one_request_batch(shape, L, 9)
+    kp, vp = W.make_cache(shape, b.num_pages, 10)
+    rng = np.random.default_rng(11)
+    q = rng.standard_normal((shape.n_q_heads, shape.head_dim)).astype(np.float32)
+    kc, vc = gather_kv(shape, b.block_table[0], L, kp, vp)
+    # one visible key: output is that value exactly
+    got = oracle.attention_token(shape, b, 0, 0, q, kp, vp)
+    np.testing.assert_array_equal(got, W.bf16_bits_to_f32(vc[0]))
+    # q = 0: uniform weights, output is the mean of the visible values
+    got = oracle.attention_token(shape, b, 0, L - 1, np.zeros_like(q), kp, vp)
+    np.testing.assert_allclose(got, W.bf16_bits_to_f32(vc).astype(np.float64).mean(0), rtol=1e-5, atol=1e-6)
+    # all values equal: output is that row whatever the scores are
+    vp2 = vp.copy()
+    flat = vp2.reshape(-1, shape.n_kv_heads, shape.head_dim)
+    flat[:] = vc[3]
+    got = oracle.attention_token(shape, b, 0, L - 1, q, kp, vp2)
+    np.testing.assert_allclose(got, W.bf16_bits_to_f32(vc[3]), rtol=1e-6, atol=1e-7)
+    # two keys whose scores differ by ln 2: weights 1/3 and 2/3 (scale 1/sqrt(d) included)
+    shape2 = W.LayerShape(8, 1, 1, 4, 8, page_size=2)
+    b2 = _one_request_batch(shape2, 2, 12)
+    kp2 = np.zeros((b2.num_pages, 2, 1, 4), np.uint16)
+    vp2 = np.zeros_like(kp2)
+    P = 2
+    s0, s1 = (int(b2.block_table[0, p // P]) * P + p % P for p in (0, 1))
+    kf, vf = kp2.reshape(-1, 4), vp2.reshape(-1, 4)
+    kf[s1] = W.f32_to_bf16_bits(np.array([1, 0, 0, 0], np.float32))
+    vf[s0] = W.f32_to_bf16_bits(np.array([3, 0, 0, 0], np.float32))
+    vf[s1] = W.f32_to_bf16_bits(np.array([0, 3, 0, 0], np.float32))
+    qq = np.array([[np.log(2.0) * np.sqrt(4.0), 5, 5, 5]], np.float32)
+    got = oracle.attention_token(shape2, b2, 0, 1, qq, kp2, vp2)
+    np.testing.assert_allclose(got[0], [1.0, 2.0, 0, 0], atol=1e-6)
+
+
+# ---------------------------------------------------------------------------
+# whole step against the dense library implementation
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("name", list(SHAPES))
+def test_layer_step_matches_dense_recompute(oracle, oracle64, name):
+    """Chunked prefill then decode through the paged oracle == each request's
+    whole sequence recomputed at once with torch fp64 library routines."""
+    shape = SHAPES[name]
+    weights = W.make_weights(shape, 20)
+    seq = [41, 23, 50]
+    sched = [[(0, 30), (1, 23)], [(0, 9), (2, 17), (1, 0)][:2], [(2, 32), (0, 1)], [(0, 1), (2, 1)]]
+    flow = make_flow(shape, seq, sched, seed=21)
+    for orc, tol in ((oracle, 3e-4), (oracle64, 3e-4)):
+        kp, vp = W.make_cache(shape, flow.num_pages, 22)
+        ys = run_flow(flow, oracle_stepper(orc, shape, weights, kp, vp))
+        for r, L in enumerate(seq):
+            ref = dense_layer(shape, weights, flow.x_full[r])
+            # keys/values in the cache are the recomputed ones up to rare 1-ulp rounding flips
+            kc, vc = gather_kv(shape, flow.block_table[r], L, kp, vp)
+            for got, want in ((kc, ref["k"]), (vc, ref["v"])):
+                g = W.bf16_bits_to_f32(got).astype(np.float64)
+                wv = want.numpy()
+                assert np.mean(g == wv) > 0.995
+                np.testing.assert_allclose(g, wv, rtol=2 ** -7, atol=1e-6)   # atol: cancellation in the rotation
+            # with the oracle's own cached bits fed back, the rest must agree tightly
+            kv = (torch.from_numpy(W.bf16_bits_to_f32(kc).astype(np.float64)),
+                  torch.from_numpy(W.bf16_bits_to_f32(vc).astype(np.float64)))
+            ref2 = dense_layer(shape, weights, flow.x_full[r], kv_override=kv)
+            np.testing.assert_allclose(ys[r], ref2["y"].numpy(), rtol=tol, atol=tol)
+            # and against the fully independent recompute within the slack of those flips
+            np.testing.assert_allclose(ys[r], ref["y"].numpy(), rtol=3e-3, atol=3e-3)
+
+
+def test_taps_match_dense(oracle):
+    shape = W.TINY_GQA
+    weights = W.make_weights(shape, 30)
+    flow = make_flow(shape, [19], [[(0, 19)]], seed=31)
+    kp, vp = W.make_cache(shape, flow.num_pages, 32)
+    b = W.Batch(np.array([0, 19], np.int32), np.array([19], np.int32), flow.block_table, flow.prefix_id,
+                flow.prefix_len, flow.num_pages)
+    res = oracle.layer_step(shape, b, weights, flow.x_full[0], kp, vp)
+    kc, vc = gather_kv(shape, flow.block_table[0], 19, kp, vp)
+    kv = (torch.from_numpy(W.bf16_bits_to_f32(kc).astype(np.float64)),
+          torch.from_numpy(W.bf16_bits_to_f32(vc).astype(np.float64)))
+    ref = dense_layer(shape, weights, flow.x_full[0], kv_override=kv)
+    np.testing.assert_allclose(res.attn_out, ref["attn_out"].numpy(), rtol=1e-4, atol=1e-5)
+    np.testing.assert_allclose(res.x1, ref["x1"].numpy(), rtol=1e-4, atol=1e-5)
+    np.testing.assert_array_equal(res.y_bf16, W.f32_to_bf16_bits(res.y_f32))
+    # row selection returns the same rows
+    sel = np.array([18, 0, 7], np.int32)
+    kp2, vp2 = W.make_cache(shape, flow.num_pages, 32)
+    res2 = oracle.layer_step(shape, b, weights, flow.x_full[0], kp2, vp2, rows=sel)
+    np.testing.assert_array_equal(res2.y_f32, res.y_f32[sel])
+    np.testing.assert_array_equal(kp2, kp)
+
+
+# ---------------------------------------------------------------------------
+# invariants the paper's caching statements imply (exact in the oracle, reading R5)
+# ---------------------------------------------------------------------------
+def _run(oracle, shape, weights, flow, cache_seed=40):
+    kp, vp = W.make_cache(shape, flow.num_pages, cache_seed)
+    ys = run_flow(flow, oracle_stepper(oracle, shape, weights, kp, vp))
+    return ys, kp, vp
+
+
+@pytest.mark.parametrize("name", ["mha", "gqa"])
+def test_incremental_decode_equals_full_causal(oracle, name):
+    shape = SHAPES[name]
+    weights = W.make_weights(shape, 41)
+    L = 35
+    full, _, _ = _run(oracle, shape, weights, make_flow(shape, [L], [[(0, L)]], seed=42))
+    inc, _, _ = _run(oracle, shape, weights, make_flow(shape, [L], [[(0, 1)] for _ in range(L)], seed=42))
+    np.testing.assert_array_equal(inc[0], full[0])
+
+
+def test_chunked_prefill_equals_one_shot(oracle):
+    shape = W.TINY
+    weights = W.make_weights(shape, 43)
+    L = 128
+    one, kp1, vp1 = _run(oracle, shape, weights, make_flow(shape, [L], [[(0, L)]], seed=44))
+    for chunks in ([64, 64], [1, 127], [50, 30, 48]):
+        ys, kp, vp = _run(oracle, shape, weights, make_flow(shape, [L], [[(0, c)] for c in chunks], seed=44))
+        np.testing.assert_array_equal(ys[0], one[0])
+        np.testing.assert_array_equal(kp, kp1)
+        np.testing.assert_array_equal(vp, vp1)
+
+
+def test_page_permutation_leaves_outputs_unchanged(oracle):
+    shape = W.TINY_GQA
+    weights = W.make_weights(shape, 45)
+    seq = [40, 21, 33]
+    sched = [[(0, 40), (1, 20)], [(1, 1), (2, 33)]]
+    f1 = make_flow(shape, seq, sched, seed=46)
+    f2 = make_flow(shape, seq, sched, seed=46, page_perm_seed=999)
+    assert not np.array_equal(f1.block_table, f2.block_table)
+    y1, kp1, vp1 = _run(oracle, shape, weights, f1)
+    y2, kp2, vp2 = _run(oracle, shape, weights, f2)
+    for r, L in enumerate(seq):
+        np.testing.assert_array_equal(y1[r], y2[r])
+        a = gather_kv(shape, f1.block_table[r], L, kp1, vp1)
+        b = gather_kv(shape, f2.block_table[r], L, kp2, vp2)
+        np.testing.assert_array_equal(a[0], b[0])
+        np.testing.assert_array_equal(a[1], b[1])
+
+
+def test_page_size_independence(oracle):
+    weights = W.make_weights(W.TINY, 47)
+    outs = []
+    for P in (8, 16, 32):
+        shape = W.LayerShape(256, 4, 4, 64, 688, page_size=P)
+        ys, _, _ = _run(oracle, shape, weights, make_flow(shape, [45, 30], [[(0, 44), (1, 30)], [(0, 1)]], seed=48))
+        outs.append(ys)
+    for ys in outs[1:]:
+        for a, b in zip(ys, outs[0]):
+            np.testing.assert_array_equal(a, b)
+
+
+def test_shared_prefix_equals_private_recompute(oracle):
+    """One copy of the template's keys/values referenced by several block tables
+    gives the same outputs as every request prefilling its own copy."""
+    shape = W.TINY_GQA
+    weights = W.make_weights(shape, 49)
+    P = shape.page_size
+    pl = 2 * P
+    seq = [pl + 20, pl + 7, pl + 13]
+    # shared: request 0 writes the prefix once, the others start after it
+    shared = make_flow(shape, seq, [[(0, pl + 20)], [(1, 7), (2, 13)]], seed=50, shared_prefix=(pl, [0, 1, 2]),
+                       start=[0, pl, pl])
+    assert np.array_equal(shared.block_table[0, :2], shared.block_table[1, :2])
+    ys_s, _, _ = _run(oracle, shape, weights, shared)
+    private = make_flow(shape, seq, [[(0, pl + 20), (1, pl + 7), (2, pl + 13)]], seed=50)
+    private.x_full = shared.x_full
+    ys_p, _, _ = _run(oracle, shape, weights, private)
+    np.testing.assert_array_equal(ys_s[0], ys_p[0])
+    np.testing.assert_array_equal(ys_s[1][pl:], ys_p[1][pl:])
+    np.testing.assert_array_equal(ys_s[2][pl:], ys_p[2][pl:])
+
+
+def test_batch_order_independence(oracle):
+    shape = W.TINY
+    weights = W.make_weights(shape, 51)
+    seq = [30, 12, 25, 1]
+    y1, _, _ = _run(oracle, shape, weights, make_flow(shape, seq, [[(0, 30), (1, 12), (2, 25), (3, 1)]], seed=52))
+    y2, _, _ = _run(oracle, shape, weights, make_flow(shape, seq, [[(3, 1), (2, 25), (0, 30), (1, 12)]], seed=52))
+    for a, b in zip(y1, y2):
+        np.testing.assert_array_equal(a, b)
+
+
+def test_gqa_equals_mha_with_replicated_kv_heads(oracle):
+    gqa = W.TINY_GQA
+    mha = W.LayerShape(gqa.hidden, gqa.n_q_heads, gqa.n_q_heads, gqa.head_dim, gqa.mlp_dim)
+    wg = W.make_weights(gqa, 53)
+    d, rep = gqa.head_dim, gqa.n_q_heads // gqa.n_kv_heads
+    qkv = wg["w_qkv"]
+    wq = qkv[:gqa.q_dim]
+    wk = qkv[gqa.q_dim:gqa.q_dim + gqa.kv_dim].reshape(gqa.n_kv_heads, d, -1)
+    wv = qkv[gqa.q_dim + gqa.kv_dim:].reshape(gqa.n_kv_heads, d, -1)
+    wm = dict(wg)
+    wm["w_qkv"] = np.concatenate([wq, np.repeat(wk, rep, 0).reshape(-1, gqa.hidden),
+                                  np.repeat(wv, rep, 0).reshape(-1, gqa.hidden)], 0)
+    seq, sched = [26, 9], [[(0, 25), (1, 9)], [(0, 1)]]
+    yg, _, _ = _run(oracle, gqa, wg, make_flow(gqa, seq, sched, seed=54))
+    ym, _, _ = _run(oracle, mha, wm, make_flow(mha, seq, sched, seed=54))
+    for a, b in zip(yg, ym):
+        np.testing.assert_array_equal(a, b)
+
+
+def test_zero_weights_special_cases(oracle):
+    shape = W.TINY
+    weights = W.make_weights(shape, 55)
+    flow = make_flow(shape, [18], [[(0, 18)]], seed=56)
+    x = W.bf16_bits_to_f32(flow.x_full[0])
+    # W_o = 0 and W_down = 0: the layer is the identity on the residual stream
+    w0 = dict(weights, w_o=np.zeros_like(weights["w_o"]), w_down=np.zeros_like(weights["w_down"]))
+    ys, _, _ = _run(oracle, shape, w0, flow)
+    np.testing.assert_array_equal(ys[0], x)
+    # zero gate rows: silu(0) = 0, so y = x1
+    wgu = weights["w_gate_up"].copy()
+    wgu[:shape.mlp_dim] = 0
+    kp, vp = W.make_cache(shape, flow.num_pages, 40)
+    b = W.Batch(np.array([0, 18], np.int32), np.array([18], np.int32), flow.block_table, flow.prefix_id,
+                flow.prefix_len, flow.num_pages)
+    res = oracle.layer_step(shape, b, dict(weights, w_gate_up=wgu), flow.x_full[0], kp, vp)
+    np.testing.assert_array_equal(res.y_f32, res.x1)
+    # the full layer does move the stream (guards against the cases above passing vacuously)
+    ys, _, _ = _run(oracle, shape, weights, flow)
+    assert np.abs(ys[0] - x).max() > 1e-2
+
+
+def test_oracle_own_rounding_error_is_small(oracle, oracle64):
+    """fp32 accumulators against fp64 accumulators: the oracle's own error is far
+    below the parity tolerance (max-abs 2e-2, rel-L2 1e-2)."""
+    wl = W.workload_tiny()
+    weights = W.make_weights(wl.shape, wl.seed)
+    x = W.make_activations(wl.batch.T, wl.shape.hidden, wl.seed)
+    outs = []
+    for orc in (oracle, oracle64):
+        kp, vp = W.make_cache(wl.shape, wl.batch.num_pages, wl.seed)
+        outs.append(orc.layer_step(wl.shape, wl.batch, weights, x, kp, vp).y_f32.astype(np.float64))
+    err = np.abs(outs[0] - outs[1]).max()
+    rel = np.linalg.norm(outs[0] - outs[1]) / np.linalg.norm(outs[1])
+    assert err < 2e-4 and rel < 1e-5, (err, rel)
+
+
+def test_golden_tiny_layer_step_is_stable():
+    """The frozen oracle outputs (written by tests/golden/make_golden.py) still hold."""
+    import os
+    from tests.golden.make_golden import compute
+    res, kp, vp = compute()
+    path = os.path.join(os.path.dirname(__file__), "golden", "tiny_layer_step.txt")
+    for line in open(path):
+        if line.startswith("#"):
+            continue
+        f = line.split()
+        if f[0] == "y":
+            # libm's expf/cos may differ in the last place between machines
+            np.testing.assert_allclose(res.y_f32[int(f[1]), int(f[2])], float.fromhex(f[3]), rtol=1e-5, atol=1e-6)
+        elif f[0] == "sum_k_pages":
+            assert abs(int(kp.astype(np.uint64).sum()) - int(f[1])) < 4096
+        elif f[0] == "sum_v_pages":
+            assert abs(int(vp.astype(np.uint64).sum()) - int(f[1])) < 4096

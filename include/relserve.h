@@ -1,0 +1,221 @@
+/*
+ * relserve.h -- C ABI of the MI355X (gfx950) layer-step library.
+ *
+ * What it runs: the GPU worker's share of one serving iteration (Sec. 4.1,
+ * step 4 "Batch Processing": the scheduler hands over a batch together with
+ * its KV-cache allocation; the worker runs the forward computation and keeps
+ * the per-layer KV cache) for ONE decoder layer: input RMSNorm, q/k/v
+ * projections (Sec. 2.3, Eq. 3), rotary embedding, KV append into a paged
+ * cache (Sec. 2.3 "KV Cache"), causal softmax attention over the cached keys
+ * and values (Eq. 4-5) for prefill rows (several query tokens) and decode rows
+ * (one query token) of the same batch, with a template prefix shared by the
+ * requests of one relQuery (Sec. 2.2 Def. 2.1, Sec. 2.3 "Prefix Cache") stored
+ * once and read once per group, W_o + residual, post RMSNorm and SwiGLU MLP +
+ * residual.
+ *
+ * Conventions
+ *   - every function returns 0 (RELSERVE_OK) or a negative relserve_status;
+ *     nothing throws or aborts; a failed call launches nothing.
+ *   - "host" pointers are read during the call and not kept; "device" pointers
+ *     are HIP device memory owned by the caller and must stay valid until the
+ *     stream work that uses them has finished.
+ *   - the library owns only the opaque handles it returns (and the device
+ *     copy of the batch descriptor inside a relserve_batch).
+ *   - stream arguments are hipStream_t passed as void*; all GPU work is
+ *     enqueued there asynchronously, no call synchronises except
+ *     relserve_batch_prepare (one blocking descriptor upload) and the
+ *     relserve_profile_* readers.
+ *   - all 16-bit floating point data are bfloat16, all matrices row-major.
+ *   - layouts: activations [T, features]; weights [out_features, in_features];
+ *     w_qkv rows = [q heads | k heads | v heads]; w_gate_up rows = [gate | up];
+ *     cache pools k_pages / v_pages = [num_pages, page_size, n_kv_heads,
+ *     head_dim]; the token at position pos of request r lives in
+ *     slot = block_table[r][pos / page_size] * page_size + pos % page_size.
+ */
+#ifndef RELSERVE_H
+#define RELSERVE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    RELSERVE_OK = 0,
+    RELSERVE_ERR_NULL_POINTER = -1,
+    RELSERVE_ERR_BAD_CONFIG = -2,         /* shape the kernels do not cover */
+    RELSERVE_ERR_BAD_Q_START = -3,        /* q_start[0] != 0, not increasing, or an empty request */
+    RELSERVE_ERR_BAD_CTX_LEN = -4,        /* ctx_len[r] < number of query tokens of r */
+    RELSERVE_ERR_BLOCK_TABLE_SHORT = -5,  /* ceil(ctx_len[r] / page_size) > max_blocks */
+    RELSERVE_ERR_PAGE_RANGE = -6,         /* a used block-table entry is outside [0, num_pages) */
+    RELSERVE_ERR_BAD_PREFIX = -7,         /* prefix id/length inconsistent with the block tables */
+    RELSERVE_ERR_SLOT_ALIAS = -8,         /* two query tokens of the batch would write the same slot */
+    RELSERVE_ERR_WORKSPACE = -9,          /* workspace missing, misaligned or too small */
+    RELSERVE_ERR_HIP = -10,               /* a HIP runtime call failed */
+    RELSERVE_ERR_NO_DEVICE = -11,         /* no gfx950 device is current */
+    RELSERVE_ERR_TOO_LARGE = -12,         /* a size overflows the 32-bit indices used on the device */
+    RELSERVE_ERR_MISMATCH = -13,          /* batch prepared for another layer shape, or cache smaller than the batch's */
+    RELSERVE_ERR_BAD_ARGUMENT = -14
+} relserve_status;
+
+typedef struct relserve_layer relserve_layer;   /* opaque: one layer shape */
+typedef struct relserve_batch relserve_batch;   /* opaque: one prepared batch */
+
+/* Layer shape.  Supported: head_dim in {64, 128}; n_q_heads a multiple of
+ * n_kv_heads with ratio <= 32; hidden, mlp_dim multiples of 8; page_size a
+ * power of two in [8, 256]. */
+typedef struct {
+    int32_t hidden;       /* H */
+    int32_t n_q_heads;
+    int32_t n_kv_heads;
+    int32_t head_dim;     /* d of Eq. 4 */
+    int32_t mlp_dim;      /* I */
+    int32_t page_size;    /* P, tokens per cache page */
+    float   rms_eps;
+    float   rope_base;
+} relserve_layer_config;
+
+/* Batch descriptor; every pointer is HOST memory.
+ * Request r owns packed rows q_start[r] .. q_start[r+1]-1 of the activation
+ * matrices; its query token j sits at sequence position ctx_len[r] - q_len + j,
+ * and ctx_len[r] is the request's length AFTER this step's append.
+ * prefix_id[r] (or -1; the array may be NULL) names a template prefix of
+ * prefix_len[prefix_id[r]] tokens (a multiple of page_size, not longer than the
+ * request's past) whose pages are the leading block-table entries of every
+ * member.  It is a hint that lets members' prefix attention be computed
+ * together; results are defined by the block tables alone. */
+typedef struct {
+    int32_t        num_reqs;
+    int32_t        max_blocks;     /* row stride of block_table */
+    const int32_t* q_start;        /* [num_reqs + 1] */
+    const int32_t* ctx_len;        /* [num_reqs] */
+    const int32_t* block_table;    /* [num_reqs, max_blocks] */
+    const int32_t* prefix_id;      /* [num_reqs] or NULL */
+    int32_t        num_prefixes;
+    const int32_t* prefix_len;     /* [num_prefixes] */
+    int32_t        num_pages;      /* pages in the cache pools the batch addresses */
+} relserve_batch_desc;
+
+typedef struct {
+    void*   k_pages;     /* device, [num_pages, P, n_kv, d] bf16 */
+    void*   v_pages;     /* device, same shape */
+    int32_t num_pages;
+} relserve_kv_cache;
+
+typedef struct {          /* all device, bf16 */
+    const void* w_in_norm;     /* [H] */
+    const void* w_qkv;         /* [(n_q + 2 n_kv) d, H] */
+    const void* w_o;           /* [H, n_q d] */
+    const void* w_post_norm;   /* [H] */
+    const void* w_gate_up;     /* [2 I, H] */
+    const void* w_down;        /* [H, I] */
+} relserve_layer_weights;
+
+typedef struct {
+    int32_t num_tokens;        /* T */
+    int32_t num_reqs;
+    int32_t num_decode_rows;   /* requests with one query token */
+    int32_t num_prefill_rows;
+    int32_t num_prefix_groups; /* groups whose prefix attention is computed jointly */
+    int32_t num_attn_items;    /* workgroup-level work items of the attention kernels */
+} relserve_batch_info;
+
+int32_t     relserve_version(void);
+const char* relserve_strerror(int32_t status);
+
+/* Checks a layer shape.  Host only. */
+int32_t relserve_config_validate(const relserve_layer_config* cfg);
+
+/* Creates / destroys a layer-shape handle.  Host only, touches no device. */
+int32_t relserve_layer_create(const relserve_layer_config* cfg, relserve_layer** out);
+int32_t relserve_layer_destroy(relserve_layer* layer);
+
+/* Checks a descriptor against a layer shape: every rule named beside the
+ * relserve_status codes.  Host only, no device needed. */
+int32_t relserve_batch_validate(const relserve_layer_config* cfg, const relserve_batch_desc* desc);
+
+/* Host-only: the cache slot every query token of the batch is appended to
+ * (slots_out: host, [T]).  The placement contract, checkable without a GPU. */
+int32_t relserve_batch_slots(const relserve_layer_config* cfg, const relserve_batch_desc* desc,
+                             int32_t* slots_out);
+
+/* Validates, expands the descriptor into per-token tables (request, position,
+ * slot, rotary cos/sin), builds the attention work lists and uploads them.
+ * One prepared batch serves every layer of the model step.  Blocks until the
+ * upload has finished. */
+int32_t relserve_batch_prepare(const relserve_layer* layer, const relserve_batch_desc* desc,
+                               void* stream, relserve_batch** out);
+int32_t relserve_batch_destroy(relserve_batch* batch);
+int32_t relserve_batch_get_info(const relserve_batch* batch, relserve_batch_info* out);
+
+/* Bytes of device workspace relserve_layer_step needs for up to max_tokens
+ * packed query tokens. */
+int32_t relserve_workspace_bytes(const relserve_layer* layer, int32_t max_tokens, size_t* out);
+
+/* KV append alone (Sec. 2.3 "KV Cache"): k, v are device [T, n_kv, d] bf16,
+ * rotary embedding already applied by the caller; rows are copied bit for bit
+ * into their slots; no other byte of the pools is written. */
+int32_t relserve_kv_append(const relserve_layer* layer, const relserve_batch* batch,
+                           const void* k, const void* v, relserve_kv_cache cache, void* stream);
+
+/* The whole layer step (Eq. 3-5 and the wiring listed at the top).  x, y:
+ * device [T, H] bf16; y may alias x.  workspace: device, 256-byte aligned,
+ * at least relserve_workspace_bytes(layer, T).  The cache pools are updated
+ * in place at the batch's slots and nowhere else. */
+int32_t relserve_layer_step(const relserve_layer* layer, const relserve_batch* batch,
+                            const relserve_layer_weights* weights,
+                            const void* x, void* y, relserve_kv_cache cache,
+                            void* workspace, size_t workspace_bytes, void* stream);
+
+/* ---- single stages, exported so that each kernel can be checked alone ---- */
+
+/* out[t, :] = x[t, :] * w / sqrt(mean(x[t, :]^2) + eps); x is bf16 when
+ * x_is_f32 == 0, else fp32; out bf16. */
+int32_t relserve_rmsnorm(const void* x, int32_t x_is_f32, const void* w, float eps,
+                         int32_t n_rows, int32_t hidden, void* out, void* stream);
+
+/* out[T, N] = a[T, K] * w[N, K]^T (Eq. 3 and every other dense map), bf16 in,
+ * fp32 accumulate.  epilogue: 0 = store bf16; 1 = add residual (bf16 [T, N])
+ * and store fp32; 2 = add residual (fp32 [T, N]) and store bf16; 3 = SwiGLU:
+ * w holds [gate | up] rows (N = 2 * n_half), out[T, n_half] = silu(g) * u bf16.
+ * K must be a multiple of 8, N of 4 (of 16 for SwiGLU). */
+int32_t relserve_linear(const void* a, const void* w, int32_t T, int32_t N, int32_t K,
+                        int32_t epilogue, const void* residual, void* out, void* stream);
+
+/* Rotary embedding of q and k inside qkv [T, (n_q + 2 n_kv) d] (in place on the
+ * q part) and append of the rotated k and of v into the cache. */
+int32_t relserve_rope_append(const relserve_layer* layer, const relserve_batch* batch,
+                             void* qkv, relserve_kv_cache cache, void* stream);
+
+/* q/k/v projection (Eq. 3) of normed activations h [T, H] with the rotary embedding
+ * and the KV append fused into the GEMM epilogue: rotated q -> q_out [T, n_q d]
+ * bf16, rotated k and v -> their cache slots; each value is rounded to bf16 once. */
+int32_t relserve_qkv_rope_append(const relserve_layer* layer, const relserve_batch* batch,
+                                 const void* h, const void* w_qkv, void* q_out,
+                                 relserve_kv_cache cache, void* stream);
+
+/* Attention of every query token over its request's cached keys/values
+ * (Eq. 4, Eq. 5 before W_o).  q: device rows of pitch q_pitch elements holding
+ * [n_q, d] rotated queries; out [T, n_q d] bf16.  workspace as for the step. */
+int32_t relserve_attention(const relserve_layer* layer, const relserve_batch* batch,
+                           const void* q, int32_t q_pitch, relserve_kv_cache cache,
+                           void* out, void* workspace, size_t workspace_bytes, void* stream);
+
+/* ---- per-kernel timing with HIP events on the caller's stream ---- */
+
+#define RELSERVE_PROFILE_SLOTS 12
+/* names, in launch order, of the kernels one layer step runs */
+const char* relserve_profile_slot_name(int32_t slot);
+/* When enabled, relserve_layer_step records an event pair around each kernel
+ * and accumulates the durations at the next relserve_profile_read, which
+ * synchronises the stream.  ms_sum / launches: host arrays of
+ * RELSERVE_PROFILE_SLOTS entries. */
+int32_t relserve_profile_enable(relserve_layer* layer, int32_t enable);
+int32_t relserve_profile_read(relserve_layer* layer, double* ms_sum, int64_t* launches, int32_t reset);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

@@ -1,0 +1,285 @@
+"""Thin ctypes binding over librelserve.so (argument marshalling only).
+
+Every function here has the name of the C entry point it calls (include/relserve.h).
+Device buffers are torch tensors (PyTorch is used for device memory and streams
+only); descriptors are numpy int32 arrays.  There is no fallback: if the library
+is not built, importing this module raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "librelserve.so")
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2601_11546_amd.build` "
+                      "(there is no CPU or PyTorch fallback for the layer step)")
+_lib = C.CDLL(LIB_PATH)
+
+PROFILE_SLOTS = 12
+
+EXPORTS = ["relserve_version", "relserve_strerror", "relserve_config_validate", "relserve_layer_create",
+           "relserve_layer_destroy", "relserve_batch_validate", "relserve_batch_slots", "relserve_batch_prepare",
+           "relserve_batch_destroy", "relserve_batch_get_info", "relserve_workspace_bytes", "relserve_kv_append",
+           "relserve_layer_step", "relserve_rmsnorm", "relserve_linear", "relserve_rope_append",
+           "relserve_qkv_rope_append",
+           "relserve_attention", "relserve_profile_slot_name", "relserve_profile_enable", "relserve_profile_read"]
+
+
+class RelserveError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {relserve_strerror(status)} ({status})")
+
+
+class LayerConfig(C.Structure):
+    _fields_ = [("hidden", C.c_int32), ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32),
+                ("head_dim", C.c_int32), ("mlp_dim", C.c_int32), ("page_size", C.c_int32),
+                ("rms_eps", C.c_float), ("rope_base", C.c_float)]
+
+
+class BatchDesc(C.Structure):
+    _fields_ = [("num_reqs", C.c_int32), ("max_blocks", C.c_int32), ("q_start", C.c_void_p),
+                ("ctx_len", C.c_void_p), ("block_table", C.c_void_p), ("prefix_id", C.c_void_p),
+                ("num_prefixes", C.c_int32), ("prefix_len", C.c_void_p), ("num_pages", C.c_int32)]
+
+
+class KVCache(C.Structure):
+    _fields_ = [("k_pages", C.c_void_p), ("v_pages", C.c_void_p), ("num_pages", C.c_int32)]
+
+
+class LayerWeights(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in
+                ("w_in_norm", "w_qkv", "w_o", "w_post_norm", "w_gate_up", "w_down")]
+
+
+class BatchInfo(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("num_tokens", "num_reqs", "num_decode_rows", "num_prefill_rows",
+                                         "num_prefix_groups", "num_attn_items")]
+
+
+_lib.relserve_version.restype = C.c_int32
+_lib.relserve_strerror.restype = C.c_char_p
+_lib.relserve_strerror.argtypes = [C.c_int32]
+_lib.relserve_profile_slot_name.restype = C.c_char_p
+_lib.relserve_profile_slot_name.argtypes = [C.c_int32]
+for _n, _a in {
+    "relserve_config_validate": [C.c_void_p],
+    "relserve_layer_create": [C.c_void_p, C.c_void_p],
+    "relserve_layer_destroy": [C.c_void_p],
+    "relserve_batch_validate": [C.c_void_p, C.c_void_p],
+    "relserve_batch_slots": [C.c_void_p, C.c_void_p, C.c_void_p],
+    "relserve_batch_prepare": [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p],
+    "relserve_batch_destroy": [C.c_void_p],
+    "relserve_batch_get_info": [C.c_void_p, C.c_void_p],
+    "relserve_workspace_bytes": [C.c_void_p, C.c_int32, C.c_void_p],
+    "relserve_kv_append": [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, KVCache, C.c_void_p],
+    "relserve_layer_step": [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, KVCache,
+                            C.c_void_p, C.c_size_t, C.c_void_p],
+    "relserve_rmsnorm": [C.c_void_p, C.c_int32, C.c_void_p, C.c_float, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p],
+    "relserve_linear": [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_void_p,
+                        C.c_void_p, C.c_void_p],
+    "relserve_rope_append": [C.c_void_p, C.c_void_p, C.c_void_p, KVCache, C.c_void_p],
+    "relserve_qkv_rope_append": [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, KVCache, C.c_void_p],
+    "relserve_attention": [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, KVCache, C.c_void_p, C.c_void_p,
+                           C.c_size_t, C.c_void_p],
+    "relserve_profile_enable": [C.c_void_p, C.c_int32],
+    "relserve_profile_read": [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32],
+}.items():
+    getattr(_lib, _n).restype = C.c_int32
+    getattr(_lib, _n).argtypes = _a
+
+
+def _check(rc: int, where: str) -> None:
+    if rc != 0:
+        raise RelserveError(rc, where)
+
+
+def _ptr(t):
+    """Device pointer of a torch tensor (or None)."""
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def _stream(stream=None):
+    import torch
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return C.c_void_p(s.cuda_stream)
+
+
+def _config(shape) -> LayerConfig:
+    return LayerConfig(shape.hidden, shape.n_q_heads, shape.n_kv_heads, shape.head_dim, shape.mlp_dim,
+                       shape.page_size, shape.rms_eps, shape.rope_base)
+
+
+def _desc(batch):
+    """BatchDesc over numpy arrays; returns (desc, keepalive)."""
+    keep = [np.ascontiguousarray(batch.q_start, np.int32), np.ascontiguousarray(batch.ctx_len, np.int32),
+            np.ascontiguousarray(batch.block_table, np.int32), np.ascontiguousarray(batch.prefix_id, np.int32),
+            np.ascontiguousarray(batch.prefix_len, np.int32)]
+    bt = keep[2]
+    d = BatchDesc(len(keep[1]), bt.shape[1] if bt.ndim == 2 else 0, keep[0].ctypes.data, keep[1].ctypes.data,
+                  bt.ctypes.data if bt.size else None, keep[3].ctypes.data if keep[3].size else None,
+                  len(keep[4]), keep[4].ctypes.data if keep[4].size else None, int(batch.num_pages))
+    return d, keep
+
+
+def _cache(k_pages, v_pages) -> KVCache:
+    return KVCache(k_pages.data_ptr(), v_pages.data_ptr(), k_pages.shape[0])
+
+
+# ---- entry points, same names as the C ABI ------------------------------------------------
+def relserve_version() -> int:
+    return int(_lib.relserve_version())
+
+
+def relserve_strerror(status: int) -> str:
+    return _lib.relserve_strerror(int(status)).decode()
+
+
+def relserve_config_validate(shape) -> int:
+    cfg = _config(shape)
+    return int(_lib.relserve_config_validate(C.byref(cfg)))
+
+
+def relserve_batch_validate(shape, batch) -> int:
+    cfg = _config(shape)
+    d, keep = _desc(batch)
+    return int(_lib.relserve_batch_validate(C.byref(cfg), C.byref(d)))
+
+
+def relserve_batch_slots(shape, batch) -> np.ndarray:
+    cfg = _config(shape)
+    d, keep = _desc(batch)
+    out = np.empty(int(batch.q_start[-1]), np.int32)
+    _check(_lib.relserve_batch_slots(C.byref(cfg), C.byref(d), out.ctypes.data), "relserve_batch_slots")
+    return out
+
+
+class Layer:
+    """Owns a relserve_layer handle."""
+
+    def __init__(self, shape):
+        self.shape = shape
+        self.handle = C.c_void_p()
+        cfg = _config(shape)
+        _check(_lib.relserve_layer_create(C.byref(cfg), C.byref(self.handle)), "relserve_layer_create")
+
+    def close(self):
+        if self.handle:
+            _lib.relserve_layer_destroy(self.handle)
+            self.handle = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def relserve_layer_create(shape) -> Layer:
+    return Layer(shape)
+
+
+class PreparedBatch:
+    """Owns a relserve_batch handle."""
+
+    def __init__(self, layer: Layer, batch, stream=None):
+        self.handle = C.c_void_p()
+        d, keep = _desc(batch)
+        _check(_lib.relserve_batch_prepare(layer.handle, C.byref(d), _stream(stream), C.byref(self.handle)),
+               "relserve_batch_prepare")
+        self.T = int(batch.q_start[-1])
+
+    @property
+    def info(self) -> dict:
+        bi = BatchInfo()
+        _check(_lib.relserve_batch_get_info(self.handle, C.byref(bi)), "relserve_batch_get_info")
+        return {n: getattr(bi, n) for n, _ in BatchInfo._fields_}
+
+    def close(self):
+        if self.handle:
+            _lib.relserve_batch_destroy(self.handle)
+            self.handle = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def relserve_batch_prepare(layer: Layer, batch, stream=None) -> PreparedBatch:
+    return PreparedBatch(layer, batch, stream)
+
+
+def relserve_workspace_bytes(layer: Layer, max_tokens: int) -> int:
+    out = C.c_size_t()
+    _check(_lib.relserve_workspace_bytes(layer.handle, int(max_tokens), C.byref(out)), "relserve_workspace_bytes")
+    return int(out.value)
+
+
+def relserve_kv_append(layer, pbatch, k, v, k_pages, v_pages, stream=None) -> None:
+    _check(_lib.relserve_kv_append(layer.handle, pbatch.handle, _ptr(k), _ptr(v), _cache(k_pages, v_pages),
+                                   _stream(stream)), "relserve_kv_append")
+
+
+def _weights(w: dict) -> LayerWeights:
+    return LayerWeights(*[w[n].data_ptr() for n, _ in LayerWeights._fields_])
+
+
+def relserve_layer_step(layer, pbatch, weights: dict, x, y, k_pages, v_pages, workspace, stream=None) -> None:
+    wt = _weights(weights)
+    _check(_lib.relserve_layer_step(layer.handle, pbatch.handle, C.byref(wt), _ptr(x), _ptr(y),
+                                    _cache(k_pages, v_pages), _ptr(workspace),
+                                    workspace.numel() * workspace.element_size(), _stream(stream)),
+           "relserve_layer_step")
+
+
+def relserve_rmsnorm(x, w, eps: float, out, stream=None) -> None:
+    import torch
+    _check(_lib.relserve_rmsnorm(_ptr(x), int(x.dtype == torch.float32), _ptr(w), float(eps), x.shape[0],
+                                 x.shape[1], _ptr(out), _stream(stream)), "relserve_rmsnorm")
+
+
+def relserve_linear(a, w, epilogue: int, residual, out, stream=None) -> None:
+    _check(_lib.relserve_linear(_ptr(a), _ptr(w), a.shape[0], w.shape[0], w.shape[1], int(epilogue),
+                                _ptr(residual), _ptr(out), _stream(stream)), "relserve_linear")
+
+
+def relserve_rope_append(layer, pbatch, qkv, k_pages, v_pages, stream=None) -> None:
+    _check(_lib.relserve_rope_append(layer.handle, pbatch.handle, _ptr(qkv), _cache(k_pages, v_pages),
+                                     _stream(stream)), "relserve_rope_append")
+
+
+def relserve_qkv_rope_append(layer, pbatch, h, w_qkv, q_out, k_pages, v_pages, stream=None) -> None:
+    _check(_lib.relserve_qkv_rope_append(layer.handle, pbatch.handle, _ptr(h), _ptr(w_qkv), _ptr(q_out),
+                                         _cache(k_pages, v_pages), _stream(stream)), "relserve_qkv_rope_append")
+
+
+def relserve_attention(layer, pbatch, q, q_pitch: int, k_pages, v_pages, out, workspace, stream=None) -> None:
+    _check(_lib.relserve_attention(layer.handle, pbatch.handle, _ptr(q), int(q_pitch), _cache(k_pages, v_pages),
+                                   _ptr(out), _ptr(workspace), workspace.numel() * workspace.element_size(),
+                                   _stream(stream)), "relserve_attention")
+
+
+def relserve_profile_slot_name(slot: int) -> str:
+    return _lib.relserve_profile_slot_name(int(slot)).decode()
+
+
+def relserve_profile_enable(layer, enable: bool) -> None:
+    _check(_lib.relserve_profile_enable(layer.handle, int(bool(enable))), "relserve_profile_enable")
+
+
+def relserve_profile_read(layer, reset: bool = True) -> dict:
+    ms = (C.c_double * PROFILE_SLOTS)()
+    n = (C.c_int64 * PROFILE_SLOTS)()
+    _check(_lib.relserve_profile_read(layer.handle, ms, n, int(bool(reset))), "relserve_profile_read")
+    out = {}
+    for i in range(PROFILE_SLOTS):
+        if n[i]:
+            out[relserve_profile_slot_name(i)] = {"ms_sum": ms[i], "launches": int(n[i])}
+    return out

@@ -1,0 +1,354 @@
+// bf16 MFMA GEMM for the dense maps of the layer (Eq. 3, W_o of Eq. 5, gate/up, down):
+//   out[T, N] = a[T, K] * w[N, K]^T, fp32 accumulate, fused epilogues.
+//
+// Both operands are K-contiguous, which is the natural MFMA operand layout: a lane's 8
+// consecutive k values are one 16-byte load.  The weight rows take the MFMA row index and
+// the tokens the column index, so that an accumulator quad holds 4 consecutive output
+// features of one token (one 8/16-byte store).
+//
+// Workgroup = 4 waves in a 2 x 2 grid over a BM (tokens) x BN (features) tile, BK = 64.
+// Tiles go global -> registers -> LDS (XOR-swizzled 16-byte chunks, conflict-free for both the
+// row-wise writes and the MFMA operand reads), double buffered with one barrier per k step.
+// Workgroup ids are remapped so that each of the 8 XCDs (own L2 each) walks a contiguous run
+// of tiles, token tiles fastest: concurrent workgroups of an XCD share weight tiles.
+#include "device_utils.h"
+#include "relserve_internal.h"
+
+namespace relserve {
+
+namespace {
+
+constexpr int BK = 64;
+constexpr int NUM_XCD = 8;
+
+struct GemmArgs {
+    const uint16_t* a;
+    const uint16_t* w;
+    const void* residual;
+    void* out;
+    int32_t T, N, K;
+    int32_t n_half;  // SwiGLU: gate rows [0, n_half), up rows [n_half, 2 n_half)
+    int32_t tiles_m, tiles_n;
+    // fused q/k/v epilogue: rotary embedding + KV append (out = q buffer [T, n_q d])
+    const int32_t* tok_slot;
+    const float2* rope_cs;
+    uint16_t* k_pages;
+    uint16_t* v_pages;
+    int32_t n_q, n_kv;
+};
+
+enum { EPI_BF16 = 0, EPI_RES_BF16_OUT_F32 = 1, EPI_RES_F32_OUT_BF16 = 2, EPI_SWIGLU = 3, EPI_QKV_ROPE = 4 };
+
+__device__ __forceinline__ int remap_xcd(int bid, int num) {
+    const int per = num / NUM_XCD, rem = num % NUM_XCD;
+    const int xcd = bid % NUM_XCD, idx = bid / NUM_XCD;
+    return xcd < rem ? xcd * (per + 1) + idx : rem * (per + 1) + (xcd - rem) * per + idx;
+}
+
+template <int BM, int BN, int EPI, int D = 0>
+__global__ void __launch_bounds__(256) gemm_bf16_kernel(GemmArgs p) {
+    constexpr int TM = BM / 64, TN = BN / 64;          // 32x32 MFMA tiles per wave
+    constexpr int A_IT = BM / 32, W_IT = BN / 32;      // 16-byte chunks per thread and k step
+    constexpr int A_BYTES = BM * BK * 2, W_BYTES = BN * BK * 2, STAGE = A_BYTES + W_BYTES;
+    static_assert(EPI != EPI_SWIGLU || TN % 2 == 0, "SwiGLU needs gate and up tiles in one wave");
+    static_assert(EPI != EPI_QKV_ROPE || (BN == 256 && (D == 64 || D == 128)), "a wave must own whole heads");
+    extern __shared__ __align__(16) unsigned char smem[];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int l32 = lane & 31, g = lane >> 5;
+
+    const int tile = remap_xcd(blockIdx.x, p.tiles_m * p.tiles_n);
+    const int tile_m = tile % p.tiles_m, tile_n = tile / p.tiles_m;
+    const int t0 = tile_m * BM;
+    const int K = p.K;
+
+    // ---- global -> register staging: element offsets of this thread's chunks (-1 = zero fill)
+    const int c8 = (tid & 7) * 8, lrow = tid >> 3;
+    int a_off[A_IT], w_off[W_IT];
+#pragma unroll
+    for (int i = 0; i < A_IT; ++i) {
+        const int t = t0 + lrow + 32 * i;
+        a_off[i] = t < p.T ? t * K + c8 : -1;
+    }
+#pragma unroll
+    for (int i = 0; i < W_IT; ++i) {
+        const int lr = lrow + 32 * i;
+        int n;
+        bool ok;
+        if (EPI == EPI_SWIGLU) {
+            constexpr int HALF = BN / 2;
+            const int gi = tile_n * HALF + (lr % HALF);
+            ok = gi < p.n_half;
+            n = lr < HALF ? gi : p.n_half + gi;
+        } else {
+            n = tile_n * BN + lr;
+            ok = n < p.N;
+        }
+        w_off[i] = ok ? n * K + c8 : -1;
+    }
+    const int st_off = lrow * 128 + (((tid & 7) ^ (lrow & 7)) << 4);  // swizzled LDS store offset
+
+    uint4 a_reg[A_IT], w_reg[W_IT];
+    auto load_global = [&](int k0) {
+        const bool k_ok = k0 + c8 < K;
+#pragma unroll
+        for (int i = 0; i < A_IT; ++i)
+            a_reg[i] = (a_off[i] >= 0 && k_ok) ? *reinterpret_cast<const uint4*>(p.a + a_off[i] + k0)
+                                               : make_uint4(0, 0, 0, 0);
+#pragma unroll
+        for (int i = 0; i < W_IT; ++i)
+            w_reg[i] = (w_off[i] >= 0 && k_ok) ? *reinterpret_cast<const uint4*>(p.w + w_off[i] + k0)
+                                               : make_uint4(0, 0, 0, 0);
+    };
+    auto store_lds = [&](int buf) {
+        unsigned char* sa = smem + buf * STAGE;
+        unsigned char* sw = sa + A_BYTES;
+#pragma unroll
+        for (int i = 0; i < A_IT; ++i) *reinterpret_cast<uint4*>(sa + i * 32 * 128 + st_off) = a_reg[i];
+#pragma unroll
+        for (int i = 0; i < W_IT; ++i) *reinterpret_cast<uint4*>(sw + i * 32 * 128 + st_off) = w_reg[i];
+    };
+
+    // ---- LDS -> MFMA operand offsets
+    int a_rd[TM], w_rd[TN];
+#pragma unroll
+    for (int tm = 0; tm < TM; ++tm) a_rd[tm] = (wm * (BM / 2) + 32 * tm + l32) * 128;
+#pragma unroll
+    for (int tn = 0; tn < TN; ++tn) {
+        int row;
+        if (EPI == EPI_SWIGLU)
+            row = (tn < TN / 2 ? 0 : BN / 2) + wn * (BN / 4) + 32 * (tn % (TN / 2)) + l32;
+        else
+            row = wn * (BN / 2) + 32 * tn + l32;
+        w_rd[tn] = row * 128;
+    }
+    const int sw7 = l32 & 7;
+
+    f32x16_t acc[TN][TM];
+#pragma unroll
+    for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+        for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[tn][tm][r] = 0.f;
+
+    const int nk = (K + BK - 1) / BK;
+    load_global(0);
+    store_lds(0);
+    __syncthreads();
+    for (int kt = 0; kt < nk; ++kt) {
+        const bool more = kt + 1 < nk;
+        if (more) load_global((kt + 1) * BK);
+        const unsigned char* sa = smem + (kt & 1) * STAGE;
+        const unsigned char* sw = sa + A_BYTES;
+#pragma unroll
+        for (int ks = 0; ks < BK / 16; ++ks) {
+            const int ch = ((2 * ks + g) ^ sw7) << 4;
+            bf16x8_t wf[TN], af[TM];
+#pragma unroll
+            for (int tn = 0; tn < TN; ++tn) wf[tn] = as_bf16x8(*reinterpret_cast<const uint4*>(sw + w_rd[tn] + ch));
+#pragma unroll
+            for (int tm = 0; tm < TM; ++tm) af[tm] = as_bf16x8(*reinterpret_cast<const uint4*>(sa + a_rd[tm] + ch));
+#pragma unroll
+            for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+                for (int tm = 0; tm < TM; ++tm) acc[tn][tm] = mfma_32x32x16(wf[tn], af[tm], acc[tn][tm]);
+        }
+        if (more) store_lds((kt + 1) & 1);
+        __syncthreads();
+    }
+
+    // ---- epilogue: register r of a tile holds feature 8 (r / 4) + 4 g + r % 4, token l32
+#pragma unroll
+    for (int tm = 0; tm < TM; ++tm) {
+        const int t = t0 + wm * (BM / 2) + 32 * tm + l32;
+        if (t >= p.T) continue;
+        if (EPI == EPI_QKV_ROPE) {
+            // The wave owns features [nb, nb + 128): one head (d = 128) or two (d = 64).  The rotation
+            // partner of feature i is i + d/2: same lane, same register, D/64 tiles further on.
+            constexpr int TPH = (D > 0 ? D : 64) / 32;   // tiles per head
+            constexpr int HPW = 4 / TPH;                 // heads per wave
+            const int nb = tile_n * BN + wn * 128;
+            const int64_t slot = p.tok_slot[t];
+            const float2* cs = p.rope_cs + (int64_t)t * (D / 2);
+            const int kv_dim = p.n_kv * D;
+#pragma unroll
+            for (int hh = 0; hh < HPW; ++hh) {
+                const int head = nb / D + hh;
+                if (head >= p.n_q + 2 * p.n_kv) continue;
+                if (head < p.n_q + p.n_kv) {
+                    uint16_t* dst = head < p.n_q
+                                        ? static_cast<uint16_t*>(p.out) + (int64_t)t * (p.n_q * D) + head * D
+                                        : p.k_pages + slot * kv_dim + (head - p.n_q) * D;
+#pragma unroll
+                    for (int tl = 0; tl < TPH / 2; ++tl) {
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) {
+                            const int i = 32 * tl + 8 * q + 4 * g;
+                            const float4 c01 = *reinterpret_cast<const float4*>(cs + i);
+                            const float4 c23 = *reinterpret_cast<const float4*>(cs + i + 2);
+                            const float co[4] = {c01.x, c01.z, c23.x, c23.z}, si[4] = {c01.y, c01.w, c23.y, c23.w};
+                            float lo[4], hi[4];
+#pragma unroll
+                            for (int j = 0; j < 4; ++j) {
+                                const float a = acc[hh * TPH + tl][tm][4 * q + j];
+                                const float b = acc[hh * TPH + tl + TPH / 2][tm][4 * q + j];
+                                lo[j] = a * co[j] - b * si[j];
+                                hi[j] = a * si[j] + b * co[j];
+                            }
+                            *reinterpret_cast<uint2*>(dst + i) = make_uint2(pack_bf16x2(lo[0], lo[1]), pack_bf16x2(lo[2], lo[3]));
+                            *reinterpret_cast<uint2*>(dst + i + D / 2) =
+                                make_uint2(pack_bf16x2(hi[0], hi[1]), pack_bf16x2(hi[2], hi[3]));
+                        }
+                    }
+                } else {
+                    uint16_t* dst = p.v_pages + slot * kv_dim + (head - p.n_q - p.n_kv) * D;
+#pragma unroll
+                    for (int tl = 0; tl < TPH; ++tl) {
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) {
+                            const int i = 32 * tl + 8 * q + 4 * g;
+                            const f32x16_t& a = acc[hh * TPH + tl][tm];
+                            *reinterpret_cast<uint2*>(dst + i) = make_uint2(pack_bf16x2(a[4 * q], a[4 * q + 1]),
+                                                                            pack_bf16x2(a[4 * q + 2], a[4 * q + 3]));
+                        }
+                    }
+                }
+            }
+        } else if (EPI == EPI_SWIGLU) {
+#pragma unroll
+            for (int tn = 0; tn < TN / 2; ++tn) {
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int i = tile_n * (BN / 2) + wn * (BN / 4) + 32 * tn + 8 * q + 4 * g;
+                    if (i >= p.n_half) continue;  // n_half is a multiple of 8, i of 4: whole quad in or out
+                    float o[4];
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const float gate = acc[tn][tm][4 * q + j], up = acc[tn + TN / 2][tm][4 * q + j];
+                        o[j] = gate / (1.0f + __expf(-gate)) * up;
+                    }
+                    uint2 st = make_uint2(pack_bf16x2(o[0], o[1]), pack_bf16x2(o[2], o[3]));
+                    *reinterpret_cast<uint2*>(static_cast<uint16_t*>(p.out) + (int64_t)t * p.n_half + i) = st;
+                }
+            }
+        } else {
+#pragma unroll
+            for (int tn = 0; tn < TN; ++tn) {
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int n = tile_n * BN + wn * (BN / 2) + 32 * tn + 8 * q + 4 * g;
+                    if (n >= p.N) continue;  // N is a multiple of 4 on every path that reaches here
+                    const int64_t o = (int64_t)t * p.N + n;
+                    float v[4];
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) v[j] = acc[tn][tm][4 * q + j];
+                    if (EPI == EPI_RES_BF16_OUT_F32) {
+                        const uint2 r = *reinterpret_cast<const uint2*>(static_cast<const uint16_t*>(p.residual) + o);
+                        float4 st = make_float4(v[0] + bf16_lo(r.x), v[1] + bf16_hi(r.x), v[2] + bf16_lo(r.y),
+                                                v[3] + bf16_hi(r.y));
+                        *reinterpret_cast<float4*>(static_cast<float*>(p.out) + o) = st;
+                    } else {
+                        if (EPI == EPI_RES_F32_OUT_BF16) {
+                            const float4 r = *reinterpret_cast<const float4*>(static_cast<const float*>(p.residual) + o);
+                            v[0] += r.x; v[1] += r.y; v[2] += r.z; v[3] += r.w;
+                        }
+                        uint2 st = make_uint2(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]));
+                        *reinterpret_cast<uint2*>(static_cast<uint16_t*>(p.out) + o) = st;
+                    }
+                }
+            }
+        }
+    }
+}
+
+template <int BM, int BN, int EPI, int D = 0>
+hipError_t launch_cfg(const GemmArgs& base, hipStream_t s) {
+    GemmArgs p = base;
+    p.tiles_m = (p.T + BM - 1) / BM;
+    p.tiles_n = EPI == EPI_SWIGLU ? (p.n_half + BN / 2 - 1) / (BN / 2) : (p.N + BN - 1) / BN;
+    constexpr int smem = 2 * (BM + BN) * BK * 2;
+    static bool attr_done = false;
+    if (!attr_done) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_bf16_kernel<BM, BN, EPI, D>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+        if (e != hipSuccess) return e;
+        attr_done = true;
+    }
+    gemm_bf16_kernel<BM, BN, EPI, D><<<dim3(p.tiles_m * p.tiles_n), dim3(256), smem, s>>>(p);
+    return hipGetLastError();
+}
+
+template <int EPI>
+hipError_t launch_epi(const GemmArgs& p, hipStream_t s) {
+    // Tile choice: the largest tile that still leaves at least ~2 workgroups per CU; small
+    // problems fall back to 128 x 128 so the chip is not left idle by tile quantisation.
+    const int64_t n_eff = EPI == EPI_SWIGLU ? 2 * (int64_t)p.n_half : p.N;
+    const int64_t big = ((p.T + 255) / 256) * ((n_eff + 255) / 256);
+    if (big >= 512) return launch_cfg<256, 256, EPI>(p, s);
+    const int64_t mid = ((p.T + 127) / 128) * ((n_eff + 255) / 256);
+    if (mid >= 384) return launch_cfg<128, 256, EPI>(p, s);
+    if (p.T > 64) return launch_cfg<128, 128, EPI>(p, s);
+    return launch_cfg<64, 128, EPI>(p, s);
+}
+
+}  // namespace
+
+hipError_t launch_linear(const void* a, const void* w, int32_t T, int32_t N, int32_t K, int32_t epilogue,
+                         const void* residual, void* out, hipStream_t s) {
+    if (T == 0) return hipSuccess;
+    if ((int64_t)T * K >= ((int64_t)1 << 31) || (int64_t)N * K >= ((int64_t)1 << 31)) return hipErrorInvalidValue;
+    if (epilogue != EPI_SWIGLU && (N % 4)) return hipErrorInvalidValue;
+    if (epilogue == EPI_SWIGLU && ((N / 2) % 8)) return hipErrorInvalidValue;
+    GemmArgs p{};
+    p.a = static_cast<const uint16_t*>(a);
+    p.w = static_cast<const uint16_t*>(w);
+    p.residual = residual;
+    p.out = out;
+    p.T = T;
+    p.N = N;
+    p.K = K;
+    p.n_half = N / 2;
+    switch (epilogue) {
+        case EPI_BF16: return launch_epi<EPI_BF16>(p, s);
+        case EPI_RES_BF16_OUT_F32: return launch_epi<EPI_RES_BF16_OUT_F32>(p, s);
+        case EPI_RES_F32_OUT_BF16: return launch_epi<EPI_RES_F32_OUT_BF16>(p, s);
+        case EPI_SWIGLU: return launch_epi<EPI_SWIGLU>(p, s);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+namespace {
+template <int D>
+hipError_t launch_qkv_d(const GemmArgs& p, hipStream_t s) {
+    const int64_t big = ((p.T + 255) / 256) * ((p.N + 255) / 256);
+    if (big >= 512) return launch_cfg<256, 256, EPI_QKV_ROPE, D>(p, s);
+    if (p.T > 64) return launch_cfg<128, 256, EPI_QKV_ROPE, D>(p, s);
+    return launch_cfg<64, 256, EPI_QKV_ROPE, D>(p, s);
+}
+}  // namespace
+
+hipError_t launch_qkv_rope_append(const BatchDev& b, const relserve_layer& L, const void* h, const void* w_qkv,
+                                  void* q_out, void* k_pages, void* v_pages, hipStream_t s) {
+    if (b.T == 0) return hipSuccess;
+    const int32_t K = L.cfg.hidden;
+    if ((int64_t)b.T * K >= ((int64_t)1 << 31) || (int64_t)L.qkv_dim * K >= ((int64_t)1 << 31))
+        return hipErrorInvalidValue;
+    GemmArgs p{};
+    p.a = static_cast<const uint16_t*>(h);
+    p.w = static_cast<const uint16_t*>(w_qkv);
+    p.out = q_out;
+    p.T = b.T;
+    p.N = L.qkv_dim;
+    p.K = K;
+    p.tok_slot = b.tok_slot;
+    p.rope_cs = b.rope_cs;
+    p.k_pages = static_cast<uint16_t*>(k_pages);
+    p.v_pages = static_cast<uint16_t*>(v_pages);
+    p.n_q = L.cfg.n_q_heads;
+    p.n_kv = L.cfg.n_kv_heads;
+    return L.cfg.head_dim == 128 ? launch_qkv_d<128>(p, s) : launch_qkv_d<64>(p, s);
+}
+
+}  // namespace relserve

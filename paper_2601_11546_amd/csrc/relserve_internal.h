@@ -1,0 +1,109 @@
+// Internal declarations shared by the host boundary and the gfx950 kernels.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <vector>
+
+#include "relserve.h"
+
+namespace relserve {
+
+// ---- attention work items (one workgroup each) -------------------------------------------
+// An item is a set of query tokens that read the same run of cached keys through one
+// block-table row: either the members of a shared-prefix group against the prefix pages,
+// or consecutive query tokens of one request against that request's own keys.
+enum : int32_t {
+    ITEM_CAUSAL = 1,        // a row at position p sees keys <= p
+    ITEM_INIT_PARTIAL = 2,  // running softmax state starts from the stored prefix partial
+    ITEM_WRITE_PARTIAL = 4  // store the running state instead of the normalised output
+};
+
+struct AttnItem {
+    int32_t tok_off;    // first entry of this item in the attn_tok list
+    int32_t n_tok;      // query tokens of the item (rows = n_tok * heads per kv head)
+    int32_t bt_req;     // request whose block-table row addresses the keys
+    int32_t key_begin;  // first key position (page aligned)
+    int32_t key_end;    // one past the last key position any row may see
+    int32_t flags;
+    int32_t pad0, pad1;
+};
+
+// Device-side view of a prepared batch (all pointers into one device allocation).
+struct BatchDev {
+    int32_t T, num_reqs, max_blocks, num_pages;
+    const int32_t* tok_req;      // [T]
+    const int32_t* tok_pos;      // [T] position of the token in its own sequence
+    const int32_t* tok_slot;     // [T] cache slot the token is appended to
+    const int32_t* block_table;  // [num_reqs, max_blocks]
+    const float2* rope_cs;       // [T, head_dim / 2] (cos, sin) of pos * base^(-2i/d)
+    const int32_t* attn_tok;     // token lists of the attention items
+    const AttnItem* items_prefix;  // joint prefix passes (write partial state)
+    const AttnItem* items_tile;    // row-tiled passes (prefill rows)
+    const AttnItem* items_split;   // key-split passes (decode rows)
+    int32_t n_items_prefix, n_items_tile, n_items_split;
+};
+
+}  // namespace relserve
+
+struct relserve_layer {
+    relserve_layer_config cfg;
+    int32_t group;  // q heads per kv head
+    int32_t q_dim, kv_dim, qkv_dim;
+    std::vector<float> inv_freq;  // [head_dim / 2] base^(-2i/d), rounded from double
+    // profiling
+    bool profile = false;
+    struct Pending { int slot; hipEvent_t a, b; };
+    std::vector<Pending> pending;
+    hipStream_t pending_stream = nullptr;
+    double ms_sum[RELSERVE_PROFILE_SLOTS] = {0};
+    int64_t launches[RELSERVE_PROFILE_SLOTS] = {0};
+};
+
+struct relserve_batch {
+    relserve_layer_config cfg;  // shape it was prepared for
+    relserve::BatchDev dev;
+    void* blob = nullptr;  // the one device allocation
+    relserve_batch_info info;
+};
+
+namespace relserve {
+
+// Host-side expansion of a descriptor (no device calls); shared by validate / slots / prepare.
+struct HostBatch {
+    int32_t T = 0;
+    std::vector<int32_t> tok_req, tok_pos, tok_slot;
+    std::vector<int32_t> attn_tok;
+    std::vector<AttnItem> items_prefix, items_tile, items_split;
+    int32_t n_decode = 0, n_prefill = 0, n_groups = 0;
+};
+int32_t expand_batch(const relserve_layer_config& cfg, const relserve_batch_desc& d, bool build_items,
+                     HostBatch* out);
+
+// Rows of queries one attention workgroup covers (4 waves x 32 MFMA columns).
+constexpr int ATTN_BLOCK_M = 128;
+constexpr int ATTN_SPLIT_ROWS = 32;
+
+// ---- kernel launchers (each enqueues on `s` and returns the launch status) ----------------
+hipError_t launch_rope_table(const int32_t* tok_pos, const float* inv_freq_dev, int32_t T, int32_t half,
+                             float2* out, hipStream_t s);
+hipError_t launch_rmsnorm(const void* x, bool x_is_f32, const void* w, float eps, int32_t rows, int32_t H,
+                          void* out, hipStream_t s);
+hipError_t launch_kv_append(const BatchDev& b, const void* k, const void* v, void* k_pages, void* v_pages,
+                            int32_t row_elems, hipStream_t s);
+hipError_t launch_rope_append(const BatchDev& b, const relserve_layer& L, void* qkv, void* k_pages,
+                              void* v_pages, hipStream_t s);
+hipError_t launch_linear(const void* a, const void* w, int32_t T, int32_t N, int32_t K, int32_t epilogue,
+                         const void* residual, void* out, hipStream_t s);
+// q/k/v projection with rotary embedding and KV append fused into the epilogue: q_out [T, n_q d] bf16.
+hipError_t launch_qkv_rope_append(const BatchDev& b, const relserve_layer& L, const void* h, const void* w_qkv,
+                                  void* q_out, void* k_pages, void* v_pages, hipStream_t s);
+// Attention passes; part_o [T, n_q, d] fp32 and part_ml [T, n_q, 2] fp32 hold the prefix partials.
+hipError_t launch_attention(const BatchDev& b, const relserve_layer& L, const void* q, int32_t q_pitch,
+                            const void* k_pages, const void* v_pages, void* out, float* part_o,
+                            float* part_ml, hipStream_t s, relserve_layer* prof);
+
+void profile_mark(relserve_layer* L, int slot, hipStream_t s, bool begin);
+
+}  // namespace relserve

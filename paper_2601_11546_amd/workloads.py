@@ -174,19 +174,26 @@ def build_batch(shape: LayerShape, q_len, ctx_len, prefix_id=None, prefix_len=()
 # ----------------------------------------------------------------------------
 # tensors
 # ----------------------------------------------------------------------------
-def make_weights(shape: LayerShape, seed: int) -> dict:
-    """bf16 bit patterns: projections ~N(0, 0.02), norm weights 1 + N(0, 0.02)."""
+def make_weights(shape: LayerShape, seed: int, n_layers: int = 0) -> dict:
+    """bf16 bit patterns: projections ~N(0, 0.02), norm weights 1 + N(0, 0.02).
+
+    n_layers > 0 selects the depth-scaled random init used for the 13B / 70B shaped
+    layers: the two projections that write into the residual stream (w_o, w_down)
+    get std 0.02 / sqrt(2 n_layers), as a stack of that depth is initialised, so that
+    one layer moves the stream by a fraction of its magnitude instead of doubling it.
+    """
     rng = np.random.default_rng(seed)
     H, I = shape.hidden, shape.mlp_dim
+    out_std = 0.02 / np.sqrt(2.0 * n_layers) if n_layers > 0 else 0.02
 
-    def proj(n, k):
-        return f32_to_bf16_bits(rng.standard_normal((n, k), dtype=np.float32) * np.float32(0.02))
+    def proj(n, k, std=0.02):
+        return f32_to_bf16_bits(rng.standard_normal((n, k), dtype=np.float32) * np.float32(std))
 
     def norm():
         return f32_to_bf16_bits(np.float32(1.0) + rng.standard_normal(H, dtype=np.float32) * np.float32(0.02))
 
-    return {"w_in_norm": norm(), "w_qkv": proj(shape.qkv_dim, H), "w_o": proj(H, shape.q_dim),
-            "w_post_norm": norm(), "w_gate_up": proj(2 * I, H), "w_down": proj(H, I)}
+    return {"w_in_norm": norm(), "w_qkv": proj(shape.qkv_dim, H), "w_o": proj(H, shape.q_dim, out_std),
+            "w_post_norm": norm(), "w_gate_up": proj(2 * I, H), "w_down": proj(H, I, out_std)}
 
 
 def make_activations(T: int, H: int, seed: int) -> np.ndarray:
@@ -219,8 +226,12 @@ class Workload:
     shape: LayerShape
     batch: Batch
     seed: int
+    n_layers: int = 0          # depth of the stack the layer is cut from (0: plain N(0, 0.02) init)
     notes: str = ""
     extra: dict = field(default_factory=dict)
+
+    def weights(self) -> dict:
+        return make_weights(self.shape, self.seed, self.n_layers)
 
 
 def workload_tiny(seed: int = 1000, shape: LayerShape = TINY) -> Workload:
@@ -252,7 +263,7 @@ def workload_relquery_13b(seed: int = 1001, n_rows: int = 200, n_prefill: int = 
     ctx = np.where(np.arange(n_rows) < n_prefill, prefix + suffix, prefix + suffix + gen)
     b = build_batch(shape, q_len, ctx, np.zeros(n_rows, np.int32), [prefix], seed=seed,
                     name="relquery_13b")
-    return Workload("relquery_13b_16p184d", shape, b, seed)
+    return Workload("relquery_13b_16p184d", shape, b, seed, n_layers=40)
 
 
 def workload_decode_heavy_70b(seed: int = 1002, with_chunk: bool = True, n_rel: int = 4,
@@ -270,7 +281,7 @@ def workload_decode_heavy_70b(seed: int = 1002, with_chunk: bool = True, n_rel: 
         q_len = np.append(q_len, chunk)
         pid = np.append(pid, -1)
     b = build_batch(shape, q_len, ctx, pid, [prefix] * n_rel, seed=seed, name="decode_heavy_70b")
-    return Workload("decode_heavy_70b" + ("_chunk2048" if with_chunk else "_decode_only"), shape, b, seed)
+    return Workload("decode_heavy_70b" + ("_chunk2048" if with_chunk else "_decode_only"), shape, b, seed, n_layers=80)
 
 
 def workload_prefill_only_13b(seed: int = 1003, n_req: int = 64, total: int = 8192, prefix: int = 1024,
@@ -286,7 +297,7 @@ def workload_prefill_only_13b(seed: int = 1003, n_req: int = 64, total: int = 81
         i += 1
     b = build_batch(shape, s, prefix + s, np.zeros(n_req, np.int32), [prefix], seed=seed,
                     name="prefill_only_13b")
-    return Workload("prefill_only_13b", shape, b, seed)
+    return Workload("prefill_only_13b", shape, b, seed, n_layers=40)
 
 
 def workload_decode_plus_chunk_13b(chunk: int, seed: int = 1004, n_dec: int = 128, ctx: int = 1024,
@@ -295,4 +306,4 @@ def workload_decode_plus_chunk_13b(chunk: int, seed: int = 1004, n_dec: int = 12
     q_len = [1] * n_dec + ([chunk] if chunk else [])
     c = [ctx] * n_dec + ([chunk] if chunk else [])
     b = build_batch(shape, q_len, c, seed=seed, name=f"decode128_chunk{chunk}")
-    return Workload(f"decode128_chunk{chunk}_13b", shape, b, seed)
+    return Workload(f"decode128_chunk{chunk}_13b", shape, b, seed, n_layers=40)

@@ -53,7 +53,10 @@ def run_flow(flow: Flow, step_fn):
         ctx = np.array([done[r] + n for r, n in step], np.int32)
         qs = np.zeros(len(step) + 1, np.int32)
         qs[1:] = np.cumsum(q_len)
-        batch = W.Batch(qs, ctx, np.ascontiguousarray(flow.block_table[reqs]), flow.prefix_id[reqs].copy(),
+        # a request that is still writing its template prefix does not claim it as shared
+        pid = np.array([flow.prefix_id[r] if flow.prefix_id[r] >= 0 and done[r] >= flow.prefix_len[flow.prefix_id[r]]
+                        else -1 for r in reqs], np.int32)
+        batch = W.Batch(qs, ctx, np.ascontiguousarray(flow.block_table[reqs]), pid,
                         flow.prefix_len, flow.num_pages)
         x = np.concatenate([flow.x_full[r][done[r]:done[r] + n] for r, n in step], axis=0)
         y = np.asarray(step_fn(batch, x))

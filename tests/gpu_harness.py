@@ -1,0 +1,72 @@
+"""Helpers for the GPU parity tests: move bf16 bit patterns to the device, run one
+layer step through the C-ABI binding, compare with the oracle's tolerances."""
+import numpy as np
+import torch
+
+from paper_2601_11546_amd import workloads as W
+
+MAX_ABS = 2e-2     # spec tolerance: bf16 in, fp32 accumulate
+REL_L2 = 1e-2
+
+
+def dev_bf16(bits: np.ndarray) -> torch.Tensor:
+    return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).cuda().view(torch.bfloat16)
+
+
+def host_bits(t: torch.Tensor) -> np.ndarray:
+    return t.detach().contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+
+
+def host_f32(t: torch.Tensor) -> np.ndarray:
+    return t.detach().float().cpu().numpy()
+
+
+def assert_close(got: np.ndarray, want: np.ndarray, what: str, max_abs=MAX_ABS, rel_l2=REL_L2):
+    got = np.asarray(got, np.float64)
+    want = np.asarray(want, np.float64)
+    assert got.shape == want.shape, (what, got.shape, want.shape)
+    assert np.isfinite(got).all(), f"{what}: non-finite values"
+    err = np.abs(got - want).max() if got.size else 0.0
+    rel = np.linalg.norm(got - want) / max(np.linalg.norm(want), 1e-30) if got.size else 0.0
+    assert err <= max_abs and rel <= rel_l2, f"{what}: max-abs {err:.3e} (limit {max_abs}), rel-L2 {rel:.3e} (limit {rel_l2})"
+    return err, rel
+
+
+class GpuLayer:
+    """One layer's device state: weights, cache pools, workspace."""
+
+    def __init__(self, rs, shape, weights_bits: dict, k_pages_bits, v_pages_bits, max_tokens: int):
+        self.rs = rs
+        self.shape = shape
+        self.layer = rs.relserve_layer_create(shape)
+        self.weights = {k: dev_bf16(v) for k, v in weights_bits.items()}
+        self.k_pages = dev_bf16(k_pages_bits)
+        self.v_pages = dev_bf16(v_pages_bits)
+        self.workspace = torch.empty(rs.relserve_workspace_bytes(self.layer, max_tokens), dtype=torch.uint8, device="cuda")
+
+    def step(self, batch, x_bits):
+        rs = self.rs
+        pb = rs.relserve_batch_prepare(self.layer, batch)
+        x = dev_bf16(x_bits)
+        y = torch.empty_like(x)
+        rs.relserve_layer_step(self.layer, pb, self.weights, x, y, self.k_pages, self.v_pages, self.workspace)
+        torch.cuda.synchronize()
+        pb.close()
+        return y
+
+
+def assert_bf16_neighbours(got_bits: np.ndarray, want_bits: np.ndarray, what: str, min_exact=0.25, ulps=1.0):
+    """Two bf16 tensors rounded from nearly equal fp32 values (the GPU feeds bf16-rounded normed
+    activations to the projection, the oracle fp32 ones): many entries are
+    bit-equal, the rest differ by one unit in the last place (or by cancellation noise near 0)."""
+    g = W.bf16_bits_to_f32(got_bits).astype(np.float64)
+    w = W.bf16_bits_to_f32(want_bits).astype(np.float64)
+    assert np.isfinite(g).all(), what
+    ulp = 2.0 ** -7 * np.maximum(np.abs(w), 1e-30)
+    # before rounding the two sides differ by the bf16 rounding of the projection's input:
+    # about 1e-3 of the tensor's RMS per entry (allow 1e-2), then each side rounds once
+    bad = np.abs(g - w) > 1.001 * ulps * ulp + 1e-2 * np.sqrt(np.mean(w * w))
+    assert not bad.any(), f"{what}: {int(bad.sum())} entries off by more than one bf16 ulp, worst {np.abs(g - w).max():.3e}"
+    exact = float(np.mean(got_bits == want_bits))
+    assert exact >= min_exact, f"{what}: only {exact:.4f} of the entries are bit-equal"
+    return exact

@@ -1,0 +1,341 @@
+"""GPU-vs-oracle parity, through the C-ABI binding, element by element on the same
+seeded inputs.  Tolerances: max-abs 2e-2 and relative-L2 1e-2 against the oracle's
+fp32 output (bf16 in, fp32 accumulate); cache slot placement and the stand-alone
+append are bit-exact.
+"""
+import numpy as np
+import pytest
+import torch
+
+from paper_2601_11546_amd import workloads as W
+from tests.flows import gather_kv, make_flow, run_flow
+from tests.gpu_harness import GpuLayer, assert_bf16_neighbours, assert_close, dev_bf16, host_bits, host_f32
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def rs():
+    assert torch.cuda.is_available(), "GPU tests need a device"
+    from paper_2601_11546_amd import binding
+    return binding
+
+
+# ---------------------------------------------------------------------------
+# single stages
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("rows,H", [(1, 256), (37, 5120), (130, 8192), (3, 688)])
+def test_rmsnorm(rs, oracle, rows, H):
+    rng = np.random.default_rng(rows * 7 + H)
+    xb = W.f32_to_bf16_bits(rng.standard_normal((rows, H), dtype=np.float32) * 2)
+    wb = W.f32_to_bf16_bits(1 + 0.05 * rng.standard_normal(H, dtype=np.float32))
+    want = oracle.rmsnorm(W.bf16_bits_to_f32(xb), wb, 1e-5)
+    out = torch.empty(rows, H, dtype=torch.bfloat16, device="cuda")
+    rs.relserve_rmsnorm(dev_bf16(xb), dev_bf16(wb), 1e-5, out)
+    assert_close(host_f32(out), want, "rmsnorm bf16 in", max_abs=4e-2, rel_l2=4e-3)   # |out| reaches 8: half an ulp is 3e-2
+    xf = rng.standard_normal((rows, H), dtype=np.float32)
+    rs.relserve_rmsnorm(torch.from_numpy(xf).cuda(), dev_bf16(wb), 1e-5, out)
+    assert_close(host_f32(out), oracle.rmsnorm(xf, wb, 1e-5), "rmsnorm f32 in", max_abs=4e-2, rel_l2=4e-3)
+
+
+GEMM_CASES = [  # T, N, K: one tile, ragged tails in every dimension, several tiles of each kernel configuration
+    (1, 256, 256), (134, 768, 256), (134, 256, 688), (77, 264, 1024), (300, 520, 200),
+    (1384, 5120, 5120), (520, 15360, 512), (2304, 1024, 384), (4100, 4096, 128),
+]
+
+
+@pytest.mark.parametrize("T,N,K", GEMM_CASES)
+def test_linear_plain_and_residual_epilogues(rs, oracle, T, N, K):
+    rng = np.random.default_rng(T + N + K)
+    ab = W.f32_to_bf16_bits(rng.standard_normal((T, K), dtype=np.float32))
+    wb = W.f32_to_bf16_bits(rng.standard_normal((N, K), dtype=np.float32) * 0.05)
+    rows = np.unique(np.concatenate([np.arange(min(T, 3)), rng.integers(0, T, 24), [T - 1]]))
+    want = oracle.linear(wb, W.bf16_bits_to_f32(ab[rows]))
+    a, w = dev_bf16(ab), dev_bf16(wb)
+    out = torch.empty(T, N, dtype=torch.bfloat16, device="cuda")
+    rs.relserve_linear(a, w, 0, None, out)
+    scale = max(1.0, np.abs(want).max())
+    assert_close(host_f32(out)[rows], want, "linear", max_abs=2 ** -8 * scale, rel_l2=4e-3)
+    # + bf16 residual -> fp32 (exact in fp32 up to accumulation order)
+    resb = W.f32_to_bf16_bits(rng.standard_normal((T, N), dtype=np.float32))
+    outf = torch.empty(T, N, dtype=torch.float32, device="cuda")
+    rs.relserve_linear(a, w, 1, dev_bf16(resb), outf)
+    assert_close(host_f32(outf)[rows], want + W.bf16_bits_to_f32(resb[rows]), "linear+res(bf16)->f32",
+                 max_abs=1e-3 * scale, rel_l2=1e-4)
+    # + fp32 residual -> bf16
+    resf = rng.standard_normal((T, N), dtype=np.float32)
+    rs.relserve_linear(a, w, 2, torch.from_numpy(resf).cuda(), out)
+    assert_close(host_f32(out)[rows], want + resf[rows], "linear+res(f32)->bf16", max_abs=2 ** -8 * (scale + 4), rel_l2=4e-3)
+
+
+@pytest.mark.parametrize("T,I,K", [(134, 688, 256), (9, 128, 64), (1384, 13824, 256), (300, 1000, 512), (2100, 3072, 128)])
+def test_linear_swiglu_epilogue(rs, oracle, T, I, K):
+    rng = np.random.default_rng(T + I + K)
+    ab = W.f32_to_bf16_bits(rng.standard_normal((T, K), dtype=np.float32))
+    wb = W.f32_to_bf16_bits(rng.standard_normal((2 * I, K), dtype=np.float32) * 0.08)
+    rows = np.unique(np.concatenate([np.arange(min(T, 3)), rng.integers(0, T, 16), [T - 1]]))
+    gu = oracle.linear(wb, W.bf16_bits_to_f32(ab[rows])).astype(np.float64)
+    g, u = gu[:, :I], gu[:, I:]
+    want = g / (1 + np.exp(-g)) * u
+    out = torch.empty(T, I, dtype=torch.bfloat16, device="cuda")
+    rs.relserve_linear(dev_bf16(ab), dev_bf16(wb), 3, None, out)
+    assert_close(host_f32(out)[rows], want, "swiglu", max_abs=2 ** -8 * max(1.0, np.abs(want).max()), rel_l2=4e-3)
+
+
+@pytest.mark.parametrize("make", [W.workload_tiny, W.workload_tiny_prefix])
+@pytest.mark.parametrize("shape", [W.TINY, W.TINY_GQA, W.TINY_D128], ids=["mha", "gqa", "d128"])
+def test_kv_append_bit_exact(rs, oracle, make, shape):
+    b = make(shape=shape).batch
+    rng = np.random.default_rng(5)
+    k = rng.integers(0, 2 ** 16, (b.T, shape.n_kv_heads, shape.head_dim)).astype(np.uint16)
+    v = rng.integers(0, 2 ** 16, (b.T, shape.n_kv_heads, shape.head_dim)).astype(np.uint16)
+    kp, vp = W.make_cache(shape, b.num_pages, 6)
+    kd, vd = dev_bf16(kp), dev_bf16(vp)
+    oracle.kv_append(shape, b, k, v, kp, vp)
+    layer = rs.relserve_layer_create(shape)
+    pb = rs.relserve_batch_prepare(layer, b)
+    rs.relserve_kv_append(layer, pb, dev_bf16(k), dev_bf16(v), kd, vd)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(host_bits(kd), kp)      # written slots AND every untouched byte
+    np.testing.assert_array_equal(host_bits(vd), vp)
+
+
+@pytest.mark.parametrize("shape", [W.TINY, W.TINY_GQA, W.TINY_D128], ids=["mha", "gqa", "d128"])
+def test_rope_append(rs, oracle, shape):
+    b = W.workload_tiny_prefix(shape=shape).batch
+    rng = np.random.default_rng(8)
+    qkv_bits = W.f32_to_bf16_bits(rng.standard_normal((b.T, shape.qkv_dim), dtype=np.float32))
+    kp, vp = W.make_cache(shape, b.num_pages, 9)
+    kd, vd = dev_bf16(kp), dev_bf16(vp)
+    qkv = dev_bf16(qkv_bits)
+    layer = rs.relserve_layer_create(shape)
+    pb = rs.relserve_batch_prepare(layer, b)
+    rs.relserve_rope_append(layer, pb, qkv, kd, vd)
+    torch.cuda.synchronize()
+    f = W.bf16_bits_to_f32(qkv_bits)
+    d, nq, nkv = shape.head_dim, shape.n_q_heads, shape.n_kv_heads
+    pos = np.concatenate([np.arange(p, p + q) for p, q in zip(b.past, b.q_len)])
+    slots = rs.relserve_batch_slots(shape, b)
+    got_q = host_f32(qkv)[:, :nq * d]
+    got_k = W.bf16_bits_to_f32(host_bits(kd)).reshape(-1, nkv, d)
+    got_v = host_bits(vd).reshape(-1, nkv, d)
+    for t in range(b.T):
+        for h in range(nq):
+            want = oracle.rope(f[t, h * d:(h + 1) * d], int(pos[t]), shape.rope_base)
+            np.testing.assert_allclose(got_q[t, h * d:(h + 1) * d], want, atol=2 ** -8 * max(1, np.abs(want).max()) + 2e-3)
+        for h in range(nkv):
+            want = oracle.rope(f[t, (nq + h) * d:(nq + h + 1) * d], int(pos[t]), shape.rope_base)
+            np.testing.assert_allclose(got_k[slots[t], h], want, atol=2 ** -8 * max(1, np.abs(want).max()) + 2e-3)
+        np.testing.assert_array_equal(got_v[slots[t]].reshape(-1), qkv_bits[t, (nq + nkv) * d:])   # v is a bit copy
+    # untouched slots keep their bits
+    mask = np.ones(kp.shape[0] * shape.page_size, bool)
+    mask[slots] = False
+    np.testing.assert_array_equal(host_bits(kd).reshape(-1, nkv, d)[mask], kp.reshape(-1, nkv, d)[mask])
+    np.testing.assert_array_equal(host_bits(vd).reshape(-1, nkv, d)[mask], vp.reshape(-1, nkv, d)[mask])
+
+
+@pytest.mark.parametrize("shape,n_req", [(W.TINY, 7), (W.TINY_GQA, 7), (W.TINY_D128, 7),
+                                         (W.LayerShape(512, 4, 2, 128, 256), 40)], ids=["mha", "gqa", "d128", "d128_wide"])
+def test_qkv_rope_append_fused_epilogue(rs, oracle, shape, n_req):
+    """Projection + rotation + append in one kernel: same bf16 inputs on both sides, one
+    rounding each, so nearly every stored value is bit-equal to the oracle's."""
+    if n_req == 7:
+        b = W.workload_tiny_prefix(shape=shape).batch
+    else:
+        rng0 = np.random.default_rng(3)
+        ql = rng0.integers(1, 40, n_req)
+        b = W.build_batch(shape, ql, ql + rng0.integers(0, 300, n_req), seed=4)
+    rng = np.random.default_rng(12)
+    h_bits = W.f32_to_bf16_bits(rng.standard_normal((b.T, shape.hidden), dtype=np.float32))
+    w_bits = W.f32_to_bf16_bits(rng.standard_normal((shape.qkv_dim, shape.hidden), dtype=np.float32) * 0.05)
+    kp, vp = W.make_cache(shape, b.num_pages, 13)
+    kd, vd = dev_bf16(kp), dev_bf16(vp)
+    layer = rs.relserve_layer_create(shape)
+    pb = rs.relserve_batch_prepare(layer, b)
+    q_out = torch.zeros(b.T, shape.q_dim, dtype=torch.bfloat16, device="cuda")
+    rs.relserve_qkv_rope_append(layer, pb, dev_bf16(h_bits), dev_bf16(w_bits), q_out, kd, vd)
+    torch.cuda.synchronize()
+    qkv = oracle.linear(w_bits, W.bf16_bits_to_f32(h_bits))
+    d, nq, nkv = shape.head_dim, shape.n_q_heads, shape.n_kv_heads
+    pos = np.concatenate([np.arange(p, p + q) for p, q in zip(b.past, b.q_len)])
+    for t in range(b.T):
+        for h in range(nq + nkv):
+            qkv[t, h * d:(h + 1) * d] = oracle.rope(qkv[t, h * d:(h + 1) * d], int(pos[t]), shape.rope_base)
+    want = W.f32_to_bf16_bits(qkv)
+    slots = rs.relserve_batch_slots(shape, b)
+    assert_bf16_neighbours(host_bits(q_out), want[:, :nq * d], "q", min_exact=0.98)
+    gk = host_bits(kd).reshape(-1, nkv * d)
+    gv = host_bits(vd).reshape(-1, nkv * d)
+    assert_bf16_neighbours(gk[slots], want[:, nq * d:(nq + nkv) * d], "k in cache", min_exact=0.98)
+    assert_bf16_neighbours(gv[slots], want[:, (nq + nkv) * d:], "v in cache", min_exact=0.98)
+    mask = np.ones(gk.shape[0], bool)
+    mask[slots] = False
+    np.testing.assert_array_equal(gk[mask], kp.reshape(-1, nkv * d)[mask])      # nothing else is written
+    np.testing.assert_array_equal(gv[mask], vp.reshape(-1, nkv * d)[mask])
+
+
+@pytest.mark.parametrize("make", [W.workload_tiny, W.workload_tiny_prefix])
+@pytest.mark.parametrize("shape", [W.TINY, W.TINY_GQA, W.TINY_D128], ids=["mha", "gqa", "d128"])
+def test_attention_stage(rs, oracle, make, shape):
+    b = make(shape=shape).batch
+    rng = np.random.default_rng(10)
+    q_bits = W.f32_to_bf16_bits(rng.standard_normal((b.T, shape.q_dim), dtype=np.float32))
+    kp, vp = W.make_cache(shape, b.num_pages, 11)
+    layer = rs.relserve_layer_create(shape)
+    pb = rs.relserve_batch_prepare(layer, b)
+    ws = torch.empty(rs.relserve_workspace_bytes(layer, b.T), dtype=torch.uint8, device="cuda")
+    out = torch.zeros(b.T, shape.q_dim, dtype=torch.bfloat16, device="cuda")
+    rs.relserve_attention(layer, pb, dev_bf16(q_bits), shape.q_dim, dev_bf16(kp), dev_bf16(vp), out, ws)
+    torch.cuda.synchronize()
+    got = host_f32(out)
+    qf = W.bf16_bits_to_f32(q_bits)
+    t = 0
+    for r in range(b.num_reqs):
+        for j in range(b.q_len[r]):
+            want = oracle.attention_token(shape, b, r, int(b.past[r]) + j, qf[t].reshape(shape.n_q_heads, -1), kp, vp)
+            assert_close(got[t], want.reshape(-1), f"attention req {r} tok {j}", max_abs=2e-2, rel_l2=1e-2)
+            t += 1
+
+
+# ---------------------------------------------------------------------------
+# whole step
+# ---------------------------------------------------------------------------
+def _step_case(rs, oracle, wl, cache_seed_off=0):
+    shape, b = wl.shape, wl.batch
+    weights = wl.weights()
+    x = W.make_activations(b.T, shape.hidden, wl.seed)
+    kp, vp = W.make_cache(shape, b.num_pages, wl.seed + cache_seed_off)
+    gl = GpuLayer(rs, shape, weights, kp, vp, b.T)
+    y = gl.step(b, x)
+    res = oracle.layer_step(shape, b, weights, x, kp, vp)       # kp, vp now hold the oracle's cache
+    return gl, y, res, kp, vp
+
+
+@pytest.mark.parametrize("make", [W.workload_tiny, W.workload_tiny_prefix])
+@pytest.mark.parametrize("shape", [W.TINY, W.TINY_GQA, W.TINY_D128], ids=["mha", "gqa", "d128"])
+def test_layer_step_tiny(rs, oracle, make, shape):
+    wl = make(shape=shape)
+    gl, y, res, kp, vp = _step_case(rs, oracle, wl)
+    err, rel = assert_close(host_f32(y), res.y_f32, f"layer step {wl.name}")
+    # cache: the set of written slots is exact, their values agree to bf16 rounding, the rest is untouched
+    slots = rs.relserve_batch_slots(shape, wl.batch)
+    nkv, d = shape.n_kv_heads, shape.head_dim
+    kp0, vp0 = W.make_cache(shape, wl.batch.num_pages, wl.seed)
+    mask = np.ones(kp.shape[0] * shape.page_size, bool)
+    mask[slots] = False
+    for dev, ora, orig in ((gl.k_pages, kp, kp0), (gl.v_pages, vp, vp0)):
+        g = host_bits(dev).reshape(-1, nkv, d)
+        np.testing.assert_array_equal(g[mask], orig.reshape(-1, nkv, d)[mask])
+        assert_bf16_neighbours(g[slots], ora.reshape(-1, nkv, d)[slots], "appended kv")
+
+
+def test_layer_step_in_place_and_repeatable(rs, oracle):
+    wl = W.workload_tiny_prefix()
+    shape, b = wl.shape, wl.batch
+    weights = wl.weights()
+    x = W.make_activations(b.T, shape.hidden, wl.seed)
+    kp, vp = W.make_cache(shape, b.num_pages, wl.seed)
+    gl = GpuLayer(rs, shape, weights, kp, vp, b.T)
+    y1 = gl.step(b, x)
+    y2 = gl.step(b, x)                                           # same slots rewritten with the same values
+    assert torch.equal(y1, y2)
+    pb = rs.relserve_batch_prepare(gl.layer, b)
+    xd = dev_bf16(x)
+    rs.relserve_layer_step(gl.layer, pb, gl.weights, xd, xd, gl.k_pages, gl.v_pages, gl.workspace)   # y aliases x
+    torch.cuda.synchronize()
+    assert torch.equal(xd, y1)
+
+
+def test_empty_and_single_token_batches(rs, oracle):
+    shape = W.TINY
+    weights = W.make_weights(shape, 3)
+    kp, vp = W.make_cache(shape, 8, 3)
+    gl = GpuLayer(rs, shape, weights, kp, vp, 4)
+    e = W.Batch(np.zeros(1, np.int32), np.zeros(0, np.int32), np.zeros((0, 1), np.int32), np.zeros(0, np.int32),
+                np.zeros(0, np.int32), 8)
+    y = gl.step(e, np.zeros((0, shape.hidden), np.uint16))
+    assert y.shape[0] == 0
+    np.testing.assert_array_equal(host_bits(gl.k_pages), kp)
+    one = W.build_batch(shape, [1], [1], seed=1)
+    x = W.make_activations(1, shape.hidden, 4)
+    kp1, vp1 = W.make_cache(shape, one.num_pages, 4)
+    gl1 = GpuLayer(rs, shape, weights, kp1, vp1, 1)
+    y = gl1.step(one, x)
+    res = oracle.layer_step(shape, one, weights, x, kp1, vp1)
+    assert_close(host_f32(y), res.y_f32, "first token of a sequence")
+
+
+@pytest.mark.parametrize("shape", [W.TINY, W.TINY_GQA], ids=["mha", "gqa"])
+def test_multi_step_flow_matches_oracle(rs, oracle, shape):
+    """Chunked prefill, a shared prefix written by one request and read by others,
+    then decode steps: every step's output against the oracle run on its own cache."""
+    P = shape.page_size
+    pl = 2 * P
+    seq = [pl + 70, pl + 9, pl + 40, 150]
+    sched = [[(0, pl + 30), (3, 100)], [(0, 40), (1, 8), (2, 40), (3, 49)], [(1, 1), (3, 1)]]
+    flow = make_flow(shape, seq, sched, seed=60, shared_prefix=(pl, [0, 1, 2]), start=[0, pl, pl, 0])
+    weights = W.make_weights(shape, 61)
+    kp, vp = W.make_cache(shape, flow.num_pages, 62)
+    gl = GpuLayer(rs, shape, weights, kp, vp, 256)
+    ys_gpu = run_flow(flow, lambda b, x: host_f32(gl.step(b, x)))
+    ys_ora = run_flow(flow, lambda b, x: oracle.layer_step(shape, b, weights, x, kp, vp).y_f32)
+    for r in range(len(seq)):
+        lo = flow.start[r]
+        assert_close(ys_gpu[r][lo:], ys_ora[r][lo:], f"flow request {r}")
+
+
+# ---------------------------------------------------------------------------
+# full-size configurations, checked on sampled requests (the oracle recomputes the
+# sampled requests as a sub-batch over the same cache: requests are independent)
+# ---------------------------------------------------------------------------
+def _sampled_parity(rs, oracle, wl, reqs, max_prefill_rows=None):
+    shape, b = wl.shape, wl.batch
+    print(f"[case] {wl.name}: T={b.T} reqs={b.num_reqs} sampled={list(reqs)}", flush=True)
+    weights = wl.weights()
+    x = W.make_activations(b.T, shape.hidden, wl.seed)
+    kp, vp = W.make_cache(shape, b.num_pages, wl.seed)
+    gl = GpuLayer(rs, shape, weights, kp, vp, b.T)
+    y = host_f32(gl.step(b, x))
+    sub = b.select(reqs)
+    rows = b.token_rows(reqs)
+    sel = None
+    if max_prefill_rows is not None and len(rows) > max_prefill_rows:
+        # every decode row of the sample, the last row of every prefill request, and random prefill rows
+        rng = np.random.default_rng(1)
+        keep = set(int(sub.q_start[i + 1]) - 1 for i in range(sub.num_reqs))
+        keep |= set(int(sub.q_start[i]) for i in range(sub.num_reqs))
+        keep |= set(rng.choice(len(rows), max_prefill_rows, replace=False).tolist())
+        sel = np.array(sorted(keep), np.int32)
+    res = oracle.layer_step(shape, sub, weights, x[rows], kp, vp, rows=sel)
+    got = y[rows] if sel is None else y[rows][sel]
+    err, rel = assert_close(got, res.y_f32, wl.name)
+    # the layer's own contribution (residual input removed), so that the copied stream cannot mask an error
+    xin = W.bf16_bits_to_f32(x[rows] if sel is None else x[rows][sel])
+    derr, drel = assert_close(got - xin, res.y_f32 - xin, wl.name + " (y - x)", max_abs=2e-2, rel_l2=5e-2)
+    print(f"[parity] {wl.name}: max-abs {err:.3e} rel-L2 {rel:.3e}; y-x rel-L2 {drel:.3e} on {got.shape[0]} rows", flush=True)
+    # appended slots of the sampled requests hold what the oracle wrote (to bf16 rounding)
+    slots = rs.relserve_batch_slots(shape, sub)
+    nkv, d = shape.n_kv_heads, shape.head_dim
+    ek = assert_bf16_neighbours(host_bits(gl.k_pages).reshape(-1, nkv, d)[slots], kp.reshape(-1, nkv, d)[slots], "appended k")
+    ev = assert_bf16_neighbours(host_bits(gl.v_pages).reshape(-1, nkv, d)[slots], vp.reshape(-1, nkv, d)[slots], "appended v")
+    print(f"[parity] {wl.name}: appended k / v bit-equal fractions {ek:.4f} / {ev:.4f}", flush=True)
+
+
+def test_full_size_relquery_13b(rs, oracle):
+    wl = W.workload_relquery_13b()
+    _sampled_parity(rs, oracle, wl, [0, 7, 15, 16, 17, 99, 150, 199])
+
+
+def test_full_size_decode_heavy_70b(rs, oracle):
+    wl = W.workload_decode_heavy_70b()
+    _sampled_parity(rs, oracle, wl, [0, 63, 64, 130, 255, 256], max_prefill_rows=24)
+
+
+def test_full_size_prefill_only_13b(rs, oracle):
+    wl = W.workload_prefill_only_13b()
+    _sampled_parity(rs, oracle, wl, [0, 31, 63], max_prefill_rows=40)
+
+
+def test_full_size_decode_plus_chunk_13b(rs, oracle):
+    wl = W.workload_decode_plus_chunk_13b(512)
+    _sampled_parity(rs, oracle, wl, [0, 127, 128], max_prefill_rows=24)

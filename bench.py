@@ -1,0 +1,234 @@
+#!/usr/bin/env python3
+"""Benchmark of the mixed-batch layer step on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME]
+
+A step is one pass of the whole layer (RMSNorm, q/k/v projection + rotary + KV append,
+attention over the paged cache, W_o, SwiGLU MLP) over one synthetic relQuery batch
+that is already resident in HBM.  Consecutive steps rotate over several independent
+(weights, cache) sets, as consecutive layers of a model would, so that a layer's
+weights are not served from the last-level cache left warm by the previous step.
+Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
+
+
+def build_workload(name: str):
+    from paper_2601_11546_amd import workloads as W
+    table = {
+        "relquery_13b": W.workload_relquery_13b,                       # configs[1]: the headline workload
+        "tiny": W.workload_tiny,                                       # configs[0]
+        "decode_heavy_70b": W.workload_decode_heavy_70b,               # configs[2]
+        "decode_only_70b": lambda: W.workload_decode_heavy_70b(with_chunk=False),
+        "prefill_only_13b": W.workload_prefill_only_13b,               # configs[3]
+        "decode128_13b": lambda: W.workload_decode_plus_chunk_13b(0),  # configs[4], one layer, chunk 0
+        "decode128_chunk2048_13b": lambda: W.workload_decode_plus_chunk_13b(2048),
+    }
+    if name not in table:
+        raise SystemExit(f"unknown workload {name!r}; choose from {sorted(table)}")
+    return table[name]()
+
+
+def algorithmic_counts(shape, batch) -> dict:
+    """FLOPs and HBM bytes one step must do/move, counted from the definition."""
+    T, H, I = batch.T, shape.hidden, shape.mlp_dim
+    d, nq, nkv = shape.head_dim, shape.n_q_heads, shape.n_kv_heads
+    gemm = {"gemm_qkv_rope_append": 2 * T * shape.qkv_dim * H, "gemm_o": 2 * T * H * shape.q_dim,
+            "gemm_gate_up": 2 * T * 2 * I * H, "gemm_down": 2 * T * H * I}
+    q_len, past = batch.q_len.astype(np.int64), batch.past.astype(np.int64)
+    visible = int(sum(int(q) * int(p) + int(q) * (int(q) + 1) // 2 for q, p in zip(q_len, past)))
+    attn_flops = 4 * d * nq * visible
+    # unique KV bytes: a shared prefix once per group, every other cached key/value once
+    kv_tok = 2 * nkv * d * 2
+    pl = batch.prefix_len
+    grouped = [p for p in range(len(pl)) if int((batch.prefix_id == p).sum()) >= 2]
+    uniq_tokens = int(sum(int(pl[p]) for p in grouped))
+    own_tokens = {"decode": 0, "prefill": 0}
+    for r in range(batch.num_reqs):
+        own = int(batch.ctx_len[r]) - (int(pl[batch.prefix_id[r]]) if batch.prefix_id[r] in grouped else 0)
+        own_tokens["decode" if q_len[r] == 1 else "prefill"] += own
+    uniq_tokens += own_tokens["decode"] + own_tokens["prefill"]
+    weights = shape.params * 2
+    bytes_total = weights + uniq_tokens * kv_tok + 2 * T * H * 2 + T * kv_tok
+    return {"gemm_flops": gemm, "attn_flops": attn_flops, "flops_total": sum(gemm.values()) + attn_flops,
+            "weight_bytes": weights, "kv_unique_bytes": uniq_tokens * kv_tok, "bytes_total": bytes_total,
+            "kv_decode_own_bytes": own_tokens["decode"] * kv_tok,
+            "kv_naive_bytes": int(batch.ctx_len.astype(np.int64).sum()) * kv_tok}
+
+
+def cpu_baseline(wl, weights, x, budget_tokens: int) -> dict:
+    """The oracle, as it stands, timed on this host on a bounded sample of the same batch."""
+    from oracle import relserve_oracle
+    from paper_2601_11546_amd import workloads as W
+    orc = relserve_oracle.load("f32")
+    b = wl.batch
+    # sample: the shortest prefill request plus decode requests in batch order, up to the token budget
+    pre = sorted((r for r in range(b.num_reqs) if b.q_len[r] > 1), key=lambda r: int(b.q_len[r]))
+    dec = [r for r in range(b.num_reqs) if b.q_len[r] == 1]
+    picked = pre[:1]
+    tokens = int(b.q_len[picked[0]]) if picked else 0
+    for r in dec[:max(4, budget_tokens - tokens)]:
+        picked.append(r)
+        tokens += 1
+        if tokens >= budget_tokens and len(picked) >= 5:
+            break
+    picked.sort()
+    sub = b.select(picked)
+    rows = b.token_rows(picked)
+    kp, vp = W.make_cache(wl.shape, b.num_pages, wl.seed)
+    t0 = time.perf_counter()
+    orc.layer_step(wl.shape, sub, weights, x[rows], kp, vp)
+    dt = time.perf_counter() - t0
+    return {"value": sub.T / dt, "unit": "tokens/s", "cores": orc.num_threads, "kind": "oracle",
+            "seconds": round(dt, 3),
+            "sample": f"{len(picked)} of {b.num_reqs} requests of the same batch ({sub.T} of {b.T} query tokens: "
+                      f"{int((sub.q_len > 1).sum())} prefill rows, {int((sub.q_len == 1).sum())} decode rows), one layer step"}
+
+
+def main() -> None:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=40)
+    ap.add_argument("--warmup", type=int, default=8)
+    ap.add_argument("--workload", default="relquery_13b")
+    ap.add_argument("--layer-sets", type=int, default=0, help="independent (weights, cache) sets to rotate over (0 = auto)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-tokens", type=int, default=0, help="token budget of the oracle sample (0 = auto)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        raise SystemExit("bench.py measures the layer step on ONE MI355X; this build has no multi-GPU path "
+                         "(run with --gpus 1)")
+
+    import torch
+    from paper_2601_11546_amd import binding as rs
+    from paper_2601_11546_amd import workloads as W
+
+    assert torch.cuda.is_available(), "bench.py needs an MI355X"
+    torch.cuda.set_device(0)
+    wl = build_workload(args.workload)
+    shape, b = wl.shape, wl.batch
+    counts = algorithmic_counts(shape, b)
+
+    def dev(bits):
+        return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).cuda().view(torch.bfloat16)
+
+    # enough sets that the rotating working set exceeds the 256 MB last-level cache several times
+    n_sets = args.layer_sets or max(2, min(4, int(np.ceil(2.5e9 / counts["weight_bytes"]))))
+    weights0 = wl.weights()
+    x_bits = W.make_activations(b.T, shape.hidden, wl.seed)
+    # set 0 holds the seeded host draws; the other sets are row-rotated device copies of it
+    # (same values and distribution at other addresses), which keeps host set-up time short
+    kp, vp = W.make_cache(shape, b.num_pages, wl.seed)
+    base = ({k: dev(v) for k, v in weights0.items()}, dev(kp), dev(vp))
+    del kp, vp
+    sets = [base]
+    for i in range(1, n_sets):
+        sets.append(({k: torch.roll(v, 7 * i, 0) for k, v in base[0].items()},
+                     torch.roll(base[1].view(-1, base[1].shape[-1]), 5 * i, 0).view(base[1].shape).contiguous(),
+                     torch.roll(base[2].view(-1, base[2].shape[-1]), 5 * i, 0).view(base[2].shape).contiguous()))
+    layer = rs.relserve_layer_create(shape)
+    t0 = time.perf_counter()
+    pb = rs.relserve_batch_prepare(layer, b)
+    prepare_ms = (time.perf_counter() - t0) * 1e3
+    x = dev(x_bits)
+    y = torch.empty_like(x)
+    ws = torch.empty(rs.relserve_workspace_bytes(layer, b.T), dtype=torch.uint8, device="cuda")
+
+    def step(i):
+        wts, kd, vd = sets[i % n_sets]
+        rs.relserve_layer_step(layer, pb, wts, x, y, kd, vd, ws)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    # timed region: exactly K steps, HIP events around every kernel on the launch stream
+    rs.relserve_profile_enable(layer, True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    prof = rs.relserve_profile_read(layer, reset=True)
+    rs.relserve_profile_enable(layer, False)
+    # the same K steps without the per-kernel events, to show what the events cost
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    elapsed_plain = time.perf_counter() - t0
+
+    ms_step = elapsed / args.steps * 1e3
+    kernels = {}
+    for name, v in prof.items():
+        avg_ms = v["ms_sum"] / v["launches"]
+        k = {"avg_ms": round(avg_ms, 4), "launches": v["launches"]}
+        if name in counts["gemm_flops"]:
+            k["tflops"] = round(counts["gemm_flops"][name] / (avg_ms * 1e-3) / 1e12, 1)
+            k["frac_mfma_peak"] = round(k["tflops"] / PEAK_BF16_TFLOPS, 4)
+        kernels[name] = k
+    attn_ms = sum(kernels[n]["avg_ms"] for n in ("attn_prefix", "attn_tile", "attn_split") if n in kernels)
+    if attn_ms > 0:
+        kernels["attention_all"] = {"avg_ms": round(attn_ms, 4),
+                                    "tflops": round(counts["attn_flops"] / (attn_ms * 1e-3) / 1e12, 1),
+                                    "kv_unique_gbs": round(counts["kv_unique_bytes"] / (attn_ms * 1e-3) / 1e9, 1)}
+    if "attn_split" in kernels and counts["kv_decode_own_bytes"]:
+        gbs = counts["kv_decode_own_bytes"] / (kernels["attn_split"]["avg_ms"] * 1e-3) / 1e9
+        kernels["attn_split"]["kv_gbs"] = round(gbs, 1)
+        kernels["attn_split"]["frac_hbm_peak"] = round(gbs / PEAK_HBM_GBS, 4)
+
+    dom = max(counts["gemm_flops"], key=lambda n: kernels.get(n, {}).get("avg_ms", 0.0))
+    step_tflops = counts["flops_total"] / (ms_step * 1e-3) / 1e12
+    step_gbs = counts["bytes_total"] / (ms_step * 1e-3) / 1e9
+    hbm_bound = (counts["bytes_total"] / (PEAK_HBM_GBS * 1e9)) > (counts["flops_total"] / (PEAK_BF16_TFLOPS * 1e12))
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "traffic.json")
+    if os.path.exists(tpath):
+        traffic = json.load(open(tpath)).get(args.workload, {}).get(dom)
+    if hbm_bound:
+        roofline = {"bound": "hbm", "achieved": round(step_gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                    "frac": round(step_gbs / PEAK_HBM_GBS, 4), "traffic": traffic, "kernel": "whole step",
+                    "bytes": counts["bytes_total"]}
+    else:
+        roofline = {"bound": "mfma", "achieved": kernels[dom]["tflops"], "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                    "frac": kernels[dom]["frac_mfma_peak"], "traffic": traffic, "kernel": dom,
+                    "flops_per_launch": counts["gemm_flops"][dom], "avg_launch_ms": kernels[dom]["avg_ms"]}
+
+    out = {
+        "metric": "mixed_batch_layer_step_tokens_per_s", "value": round(b.T / (ms_step * 1e-3), 1), "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": wl.name, "layer": f"H{shape.hidden} q{shape.n_q_heads}/kv{shape.n_kv_heads}x{shape.head_dim} "
+                   f"I{shape.mlp_dim} P{shape.page_size}", "query_tokens": b.T, "requests": b.num_reqs,
+                   "prefill_rows": int((b.q_len > 1).sum()), "decode_rows": int((b.q_len == 1).sum()),
+                   "layer_sets_rotated": n_sets, "batch_info": pb.info},
+        "roofline": roofline,
+        "step": {"tflops": round(step_tflops, 1), "frac_mfma_peak": round(step_tflops / PEAK_BF16_TFLOPS, 4),
+                 "algorithmic_gbs": round(step_gbs, 1), "frac_hbm_peak": round(step_gbs / PEAK_HBM_GBS, 4),
+                 "ms_per_step_without_events": round(elapsed_plain / args.steps * 1e3, 4),
+                 "batch_prepare_ms": round(prepare_ms, 3)},
+        "kernels": kernels,
+    }
+    if not args.no_cpu_baseline:
+        budget = args.cpu_tokens or max(8, int(4.0e10 / (2 * shape.params)))   # about 40 GFLOP of dense work
+        out["cpu_baseline"] = cpu_baseline(wl, weights0, x_bits, budget)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

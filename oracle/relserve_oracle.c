@@ -18,6 +18,13 @@ typedef float acc_t;
 
 int32_t oracle_acc_is_f64(void) { return (int32_t)(sizeof(acc_t) == sizeof(double)); }
 
+#ifdef _OPENMP
+#include <omp.h>
+int32_t oracle_num_threads(void) { return (int32_t)omp_get_max_threads(); }
+#else
+int32_t oracle_num_threads(void) { return 1; }
+#endif
+
 float oracle_bf16_to_f32(uint16_t b)
 {
     uint32_t u = (uint32_t)b << 16;

@@ -132,6 +132,8 @@ int32_t oracle_layer_step(const oracle_config* c, const oracle_batch* b,
 
 /* 1 when built with double accumulators. */
 int32_t oracle_acc_is_f64(void);
+/* Threads the parallel loops (oracle_linear, the per-token attention loop) use. */
+int32_t oracle_num_threads(void);
 
 #ifdef __cplusplus
 }

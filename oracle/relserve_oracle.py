@@ -90,6 +90,7 @@ class Oracle:
         L.oracle_layer_step.restype = C.c_int32
         L.oracle_layer_step.argtypes = [C.c_void_p] * 6 + [C.c_int32, C.c_void_p, C.c_int32] + [C.c_void_p] * 4
         L.oracle_acc_is_f64.restype = C.c_int32
+        L.oracle_num_threads.restype = C.c_int32
 
     # -- marshalling helpers -------------------------------------------------
     @staticmethod
@@ -188,6 +189,10 @@ class Oracle:
             raise ValueError(f"oracle_layer_step rc={rc}")
         del keep, wk
         return StepResult(y, yb, attn, x1)
+
+    @property
+    def num_threads(self) -> int:
+        return int(self.lib.oracle_num_threads())
 
     @property
     def acc_is_f64(self) -> bool:

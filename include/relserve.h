@@ -64,7 +64,7 @@ typedef struct relserve_layer relserve_layer;   /* opaque: one layer shape */
 typedef struct relserve_batch relserve_batch;   /* opaque: one prepared batch */
 
 /* Layer shape.  Supported: head_dim in {64, 128}; n_q_heads a multiple of
- * n_kv_heads with ratio <= 32; hidden, mlp_dim multiples of 8; page_size a
+ * n_kv_heads with ratio <= 16; hidden, mlp_dim multiples of 8; page_size a
  * power of two in [8, 256]. */
 typedef struct {
     int32_t hidden;       /* H */

@@ -1,31 +1,31 @@
 // Causal softmax attention over the paged KV cache (Eq. 4, and Eq. 5 before W_o) with bf16
 // MFMA and an online (running max / running sum) softmax.
 //
-// One workgroup = one attention item (a set of query rows that read the same run of keys
-// through one block-table row) x one kv head.  A "row" is (query token, query head of the kv
-// head's group), so grouped-query heads share every K/V tile that is staged.
+// A "row" is (query token, query head of one kv head's group), so grouped-query heads share
+// every K/V tile that is staged.  Scores are computed transposed, S^T = K Q^T (keys on the
+// MFMA row index, query rows on the column index): a lane then owns ONE query row
+// (lane % 32) and 16 of each 32 keys, so the row max / row sum are in-register reductions
+// plus one exchange with lane ^ 32, and the probabilities are already laid out as the B
+// operand of O^T = V^T P^T.  V is transposed on its way into LDS (two keys packed per 32-bit
+// write, 16-byte column groups XOR-swizzled so that the MFMA operand reads are conflict free).
 //
-// Scores are computed transposed, S^T = K Q^T (keys on the MFMA row index, query rows on the
-// column index): a lane then owns ONE query row (lane % 32) and 16 of each 32 keys, so the
-// row max / row sum are in-register reductions plus one exchange with lane ^ 32, and the
-// probabilities are already laid out as the B operand of O^T = V^T P^T.  V is transposed on
-// its way into LDS (two keys packed per 32-bit write, 16-byte column groups XOR-swizzled).
-//
-// Three passes use the same kernel:
-//   prefix : rows = all query tokens of the requests sharing a template prefix, keys = the
-//            prefix pages (read once per group), no mask; stores the running state
-//            (unnormalised O, max, sum) per (token, head);
-//   tile   : rows = consecutive query tokens of one request (prefill), keys = the request's
-//            own keys after the shared prefix, causal; continues from the stored state;
-//   split  : decode rows (one token); same as tile.
+// Two kernels share the per-tile arithmetic:
+//   attn_tile_kernel   one workgroup = up to 128 rows x one kv head; the four waves own 32
+//                      rows each and share K/V blocks of 64 keys staged by all 256 threads.
+//                      Used for the joint shared-prefix pass (rows = every query token of the
+//                      requests carrying the prefix, keys = the prefix pages, read once per
+//                      group; the running state is stored) and for prefill rows (keys = the
+//                      request's own keys, causal, continuing from the stored state).
+//   attn_decode_kernel one WAVE = one decode token x one kv head (rows = the heads of the
+//                      group); each wave streams its own 32-key blocks through a private LDS
+//                      region, so a workgroup needs no barrier and short contexts still fill
+//                      the chip.  HBM-bound: the MFMA work is a few percent of the time.
 #include "device_utils.h"
 #include "relserve_internal.h"
 
 namespace relserve {
 
 namespace {
-
-constexpr int BLOCK_N = 64;  // keys per staged block
 
 struct AttnArgs {
     const AttnItem* items;
@@ -38,29 +38,170 @@ struct AttnArgs {
     uint16_t* out;
     float* part_o;
     float* part_ml;
+    int32_t n_items;
     int32_t max_blocks, page_shift, page_mask;
     int32_t q_pitch, n_q, n_kv, group;
     float scale_log2;  // log2(e) / sqrt(d)
 };
 
+// Per-lane running softmax state of one query row (shared by lanes l and l ^ 32, which hold
+// complementary halves of the keys and of the output columns).
 template <int D>
-struct Smem {
-    static constexpr int K_STRIDE = (D + 8) * 2;           // bytes per key row (16-byte pad)
+struct RowState {
+    float m, l;
+    f32x16_t o[D / 32];
+};
+
+template <int D>
+__device__ __forceinline__ void state_init(RowState<D>& st, const AttnArgs& p, const AttnItem& it, bool valid,
+                                           int64_t row_id, int g) {
+    st.m = -INFINITY;
+    st.l = 0.f;
+#pragma unroll
+    for (int td = 0; td < D / 32; ++td)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) st.o[td][r] = 0.f;
+    if ((it.flags & ITEM_INIT_PARTIAL) && valid) {
+        const float2 ml = *reinterpret_cast<const float2*>(p.part_ml + row_id * 2);
+        st.m = ml.x;
+        st.l = g == 0 ? ml.y : 0.f;
+        const float* po = p.part_o + row_id * D + 4 * g;
+#pragma unroll
+        for (int td = 0; td < D / 32; ++td)
+#pragma unroll
+            for (int q4 = 0; q4 < 4; ++q4) {
+                const float4 v = *reinterpret_cast<const float4*>(po + 32 * td + 8 * q4);
+                st.o[td][4 * q4 + 0] = v.x; st.o[td][4 * q4 + 1] = v.y;
+                st.o[td][4 * q4 + 2] = v.z; st.o[td][4 * q4 + 3] = v.w;
+            }
+    }
+}
+
+template <int D>
+__device__ __forceinline__ void state_store(const RowState<D>& st, const AttnArgs& p, const AttnItem& it,
+                                            int64_t row_id, int g) {
+    const float l_tot = st.l + __shfl_xor(st.l, 32, 64);
+    if (it.flags & ITEM_WRITE_PARTIAL) {
+        if (g == 0) *reinterpret_cast<float2*>(p.part_ml + row_id * 2) = make_float2(st.m, l_tot);
+        float* po = p.part_o + row_id * D + 4 * g;
+#pragma unroll
+        for (int td = 0; td < D / 32; ++td)
+#pragma unroll
+            for (int q4 = 0; q4 < 4; ++q4)
+                *reinterpret_cast<float4*>(po + 32 * td + 8 * q4) =
+                    make_float4(st.o[td][4 * q4], st.o[td][4 * q4 + 1], st.o[td][4 * q4 + 2], st.o[td][4 * q4 + 3]);
+    } else {
+        const float inv = 1.0f / l_tot;
+        uint16_t* orow = p.out + row_id * D + 4 * g;
+#pragma unroll
+        for (int td = 0; td < D / 32; ++td)
+#pragma unroll
+            for (int q4 = 0; q4 < 4; ++q4)
+                *reinterpret_cast<uint2*>(orow + 32 * td + 8 * q4) =
+                    make_uint2(pack_bf16x2(st.o[td][4 * q4] * inv, st.o[td][4 * q4 + 1] * inv),
+                               pack_bf16x2(st.o[td][4 * q4 + 2] * inv, st.o[td][4 * q4 + 3] * inv));
+    }
+}
+
+// One 32-key tile: S^T = K Q^T, mask, online softmax update, O^T += V^T P^T.
+//   sk : the tile's 32 key rows in LDS, K_STRIDE bytes apart, d contiguous
+//   sv : V^T in LDS, row d at sv + d * V_STRIDE; the tile's keys start at 16-byte column group
+//        cg0; group index is XORed with (d >> 3) & SW; inside each 16 keys the columns are
+//        stored with key bits 2 and 3 swapped (matches the accumulator layout of S^T)
+template <int D, int K_STRIDE, int V_STRIDE, int SW>
+__device__ __forceinline__ void attn_tile32(RowState<D>& st, const bf16x8_t (&qf)[D / 16], const unsigned char* sk,
+                                            const unsigned char* sv, int cg0, int key0, int klim, bool need_mask,
+                                            float scale_log2, int l32, int g) {
+    f32x16_t s;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) s[r] = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < D / 16; ++ks) {
+        const bf16x8_t kf = as_bf16x8(*reinterpret_cast<const uint4*>(sk + l32 * K_STRIDE + (2 * ks + g) * 16));
+        s = mfma_32x32x16(kf, qf[ks], s);
+    }
+    float mx = -INFINITY;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        float v = s[r] * scale_log2;
+        if (need_mask && key0 + 8 * (r >> 2) + 4 * g + (r & 3) >= klim) v = -INFINITY;
+        s[r] = v;
+        mx = fmaxf(mx, v);
+    }
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    const float m_new = fmaxf(st.m, mx);
+    const float m_use = m_new == -INFINITY ? 0.f : m_new;  // a row that has seen no key yet
+    const float alpha = __builtin_amdgcn_exp2f(st.m - m_use);
+    st.m = m_new;
+    float psum = 0.f;
+    bf16x8_t pf[2];
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        uint32_t w[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const float p0 = __builtin_amdgcn_exp2f(s[8 * h + 2 * j] - m_use);
+            const float p1 = __builtin_amdgcn_exp2f(s[8 * h + 2 * j + 1] - m_use);
+            psum += p0 + p1;
+            w[j] = pack_bf16x2(p0, p1);
+        }
+        pf[h] = as_bf16x8(make_uint4(w[0], w[1], w[2], w[3]));
+    }
+    st.l = st.l * alpha + psum;
+    if (__any(alpha != 1.0f)) {
+#pragma unroll
+        for (int td = 0; td < D / 32; ++td)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) st.o[td][r] *= alpha;
+    }
+#pragma unroll
+    for (int td = 0; td < D / 32; ++td) {
+        const int d = 32 * td + l32;
+        const unsigned char* vrow = sv + d * V_STRIDE;
+        const int sw = (d >> 3) & SW;
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const bf16x8_t vf = as_bf16x8(*reinterpret_cast<const uint4*>(vrow + ((cg0 + 2 * h + g) ^ sw) * 16));
+            st.o[td] = mfma_32x32x16(vf, pf[h], st.o[td]);
+        }
+    }
+}
+
+// Writes one pair of keys (even key in the low half-words) of 8 consecutive d into V^T.
+template <int V_STRIDE, int SW>
+__device__ __forceinline__ void store_vt_pair(unsigned char* sv, int kc, int pi, uint4 ve, uint4 vo) {
+    const int kp = (pi & ~6) | ((pi & 2) << 1) | ((pi & 4) >> 1);  // swap key bits 2 and 3
+    const int col = (((kp >> 2) ^ (kc & SW)) << 2) | (kp & 3);     // dword column, swizzled
+    const uint32_t e[4] = {ve.x, ve.y, ve.z, ve.w}, o[4] = {vo.x, vo.y, vo.z, vo.w};
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        const uint32_t ev = (j & 1) ? (e[j >> 1] >> 16) : (e[j >> 1] & 0xffffu);
+        const uint32_t ov = (j & 1) ? (o[j >> 1] & 0xffff0000u) : (o[j >> 1] << 16);
+        *reinterpret_cast<uint32_t*>(sv + (8 * kc + j) * V_STRIDE + col * 4) = ev | ov;
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// row-tiled kernel (prefix pass, prefill rows)
+// ------------------------------------------------------------------------------------------
+template <int D>
+struct TileSmem {
+    static constexpr int BLOCK_N = 64;
+    static constexpr int K_STRIDE = (D + 8) * 2;        // bytes per key row (16-byte pad)
     static constexpr int K_BYTES = BLOCK_N * K_STRIDE;
-    static constexpr int V_STRIDE = (BLOCK_N + 8) * 2;     // bytes per d row of V^T (36 dwords)
+    static constexpr int V_STRIDE = (BLOCK_N + 8) * 2;  // bytes per d row of V^T (36 dwords)
     static constexpr int V_BYTES = D * V_STRIDE;
     static constexpr int STAGE = K_BYTES + V_BYTES;
 };
 
 template <int D>
-__global__ void __launch_bounds__(256) attn_kernel(AttnArgs p) {
-    using SM = Smem<D>;
+__global__ void __launch_bounds__(256) attn_tile_kernel(AttnArgs p) {
+    using SM = TileSmem<D>;
+    constexpr int BLOCK_N = SM::BLOCK_N;
     constexpr int CH = D / 8;            // 16-byte chunks per K/V row
     constexpr int K_IT = CH / 4;         // K chunks per thread per block
     constexpr int V_IT = CH / 8;         // V key pairs per thread per block
     constexpr int ROWS_PER_PASS = 256 / CH;
-    constexpr int KS = D / 16;           // MFMA k steps over the head dimension
-    constexpr int TD = D / 32;           // 32-row tiles of O^T
     extern __shared__ __align__(16) unsigned char smem[];
 
     const AttnItem it = p.items[blockIdx.x];
@@ -84,36 +225,16 @@ __global__ void __launch_bounds__(256) attn_kernel(AttnArgs p) {
     }
     const bool wave_active = wave * 32 < it.n_tok * p.group;
 
-    bf16x8_t qf[KS];
+    bf16x8_t qf[D / 16];
     {
         const uint16_t* qrow = p.q + (int64_t)tok * p.q_pitch + hq * D + 8 * g;
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks)
+        for (int ks = 0; ks < D / 16; ++ks)
             qf[ks] = as_bf16x8(valid ? *reinterpret_cast<const uint4*>(qrow + 16 * ks) : make_uint4(0, 0, 0, 0));
     }
-
-    // ---- running state
-    float m_run = -INFINITY, l_run = 0.f;
-    f32x16_t o_acc[TD];
-#pragma unroll
-    for (int td = 0; td < TD; ++td)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) o_acc[td][r] = 0.f;
     const int64_t row_id = (int64_t)tok * p.n_q + hq;
-    if ((it.flags & ITEM_INIT_PARTIAL) && valid) {
-        const float2 ml = *reinterpret_cast<const float2*>(p.part_ml + row_id * 2);
-        m_run = ml.x;
-        l_run = g == 0 ? ml.y : 0.f;
-        const float* po = p.part_o + row_id * D + 4 * g;
-#pragma unroll
-        for (int td = 0; td < TD; ++td)
-#pragma unroll
-            for (int q4 = 0; q4 < 4; ++q4) {
-                const float4 v = *reinterpret_cast<const float4*>(po + 32 * td + 8 * q4);
-                o_acc[td][4 * q4 + 0] = v.x; o_acc[td][4 * q4 + 1] = v.y;
-                o_acc[td][4 * q4 + 2] = v.z; o_acc[td][4 * q4 + 3] = v.w;
-            }
-    }
+    RowState<D> st;
+    state_init<D>(st, p, it, valid, row_id, g);
 
     // ---- staging: K rows as they are, V transposed
     const int32_t* bt = p.block_table + (int64_t)it.bt_req * p.max_blocks;
@@ -148,20 +269,8 @@ __global__ void __launch_bounds__(256) attn_kernel(AttnArgs p) {
         for (int i = 0; i < K_IT; ++i)
             *reinterpret_cast<uint4*>(sk + (krow0 + ROWS_PER_PASS * i) * SM::K_STRIDE + kc * 16) = k_reg[i];
 #pragma unroll
-        for (int i = 0; i < V_IT; ++i) {
-            const int pi = krow0 + ROWS_PER_PASS * i;                             // key pair index 0..31
-            const int kp = (pi & ~6) | ((pi & 2) << 1) | ((pi & 4) >> 1);         // swap key bits 2 and 3
-            const uint32_t e[4] = {v_reg[i][0].x, v_reg[i][0].y, v_reg[i][0].z, v_reg[i][0].w};
-            const uint32_t o[4] = {v_reg[i][1].x, v_reg[i][1].y, v_reg[i][1].z, v_reg[i][1].w};
-#pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                const int d = 8 * kc + j;
-                const uint32_t ev = (j & 1) ? (e[j >> 1] >> 16) : (e[j >> 1] & 0xffffu);
-                const uint32_t ov = (j & 1) ? (o[j >> 1] & 0xffff0000u) : (o[j >> 1] << 16);
-                const int col = (((kp >> 2) ^ (kc & 7)) << 2) | (kp & 3);          // dword column, swizzled
-                *reinterpret_cast<uint32_t*>(sv + d * SM::V_STRIDE + col * 4) = ev | ov;
-            }
-        }
+        for (int i = 0; i < V_IT; ++i)
+            store_vt_pair<SM::V_STRIDE, 7>(sv, kc, krow0 + ROWS_PER_PASS * i, v_reg[i][0], v_reg[i][1]);
     };
 
     const int n_blocks = (it.key_end - it.key_begin + BLOCK_N - 1) / BLOCK_N;
@@ -177,125 +286,233 @@ __global__ void __launch_bounds__(256) attn_kernel(AttnArgs p) {
         if (wave_active && kb0 < wave_klim_max) {
             const unsigned char* sk = smem + (b & 1) * SM::STAGE;
             const unsigned char* sv = sk + SM::K_BYTES;
-            // S^T = K Q^T for two 32-key tiles
-            f32x16_t s[2];
-#pragma unroll
-            for (int t = 0; t < 2; ++t) {
-#pragma unroll
-                for (int r = 0; r < 16; ++r) s[t][r] = 0.f;
-#pragma unroll
-                for (int ks = 0; ks < KS; ++ks) {
-                    const bf16x8_t kf = as_bf16x8(*reinterpret_cast<const uint4*>(
-                        sk + (32 * t + l32) * SM::K_STRIDE + (2 * ks + g) * 16));
-                    s[t] = mfma_32x32x16(kf, qf[ks], s[t]);
-                }
-            }
-            // scale to log2 units, mask, running max
             const bool need_mask = kb0 + BLOCK_N > wave_klim_min;
-            float mx = -INFINITY;
 #pragma unroll
             for (int t = 0; t < 2; ++t)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    float v = s[t][r] * p.scale_log2;
-                    if (need_mask) {
-                        const int key = kb0 + 32 * t + 8 * (r >> 2) + 4 * g + (r & 3);
-                        if (key >= klim) v = -INFINITY;
-                    }
-                    s[t][r] = v;
-                    mx = fmaxf(mx, v);
-                }
-            mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-            const float m_new = fmaxf(m_run, mx);
-            const float m_use = m_new == -INFINITY ? 0.f : m_new;   // a row that has seen no key yet
-            const float alpha = __builtin_amdgcn_exp2f(m_run - m_use);
-            m_run = m_new;
-            float psum = 0.f;
-            bf16x8_t pf[2][2];
-#pragma unroll
-            for (int t = 0; t < 2; ++t)
-#pragma unroll
-                for (int h = 0; h < 2; ++h) {
-                    uint32_t w[4];
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) {
-                        const float p0 = __builtin_amdgcn_exp2f(s[t][8 * h + 2 * j] - m_use);
-                        const float p1 = __builtin_amdgcn_exp2f(s[t][8 * h + 2 * j + 1] - m_use);
-                        psum += p0 + p1;
-                        w[j] = pack_bf16x2(p0, p1);
-                    }
-                    pf[t][h] = as_bf16x8(make_uint4(w[0], w[1], w[2], w[3]));
-                }
-            l_run = l_run * alpha + psum;
-            if (__any(alpha != 1.0f)) {
-#pragma unroll
-                for (int td = 0; td < TD; ++td)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) o_acc[td][r] *= alpha;
-            }
-            // O^T += V^T P^T
-#pragma unroll
-            for (int td = 0; td < TD; ++td) {
-                const int d = 32 * td + l32;
-                const unsigned char* vrow = sv + d * SM::V_STRIDE;
-                const int sw = (d >> 3) & 7;
-#pragma unroll
-                for (int t = 0; t < 2; ++t)
-#pragma unroll
-                    for (int h = 0; h < 2; ++h) {
-                        const int cg = (4 * t + 2 * h + g) ^ sw;
-                        const bf16x8_t vf = as_bf16x8(*reinterpret_cast<const uint4*>(vrow + cg * 16));
-                        o_acc[td] = mfma_32x32x16(vf, pf[t][h], o_acc[td]);
-                    }
-            }
+                attn_tile32<D, SM::K_STRIDE, SM::V_STRIDE, 7>(st, qf, sk + 32 * t * SM::K_STRIDE, sv, 4 * t,
+                                                              kb0 + 32 * t, klim, need_mask, p.scale_log2, l32, g);
         }
         if (more) stage_store((b + 1) & 1);
         __syncthreads();
     }
-
-    if (!valid) return;
-    const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
-    if (it.flags & ITEM_WRITE_PARTIAL) {
-        if (g == 0) *reinterpret_cast<float2*>(p.part_ml + row_id * 2) = make_float2(m_run, l_tot);
-        float* po = p.part_o + row_id * D + 4 * g;
-#pragma unroll
-        for (int td = 0; td < TD; ++td)
-#pragma unroll
-            for (int q4 = 0; q4 < 4; ++q4)
-                *reinterpret_cast<float4*>(po + 32 * td + 8 * q4) =
-                    make_float4(o_acc[td][4 * q4], o_acc[td][4 * q4 + 1], o_acc[td][4 * q4 + 2], o_acc[td][4 * q4 + 3]);
-    } else {
-        const float inv = 1.0f / l_tot;
-        uint16_t* orow = p.out + row_id * D + 4 * g;
-#pragma unroll
-        for (int td = 0; td < TD; ++td)
-#pragma unroll
-            for (int q4 = 0; q4 < 4; ++q4)
-                *reinterpret_cast<uint2*>(orow + 32 * td + 8 * q4) =
-                    make_uint2(pack_bf16x2(o_acc[td][4 * q4] * inv, o_acc[td][4 * q4 + 1] * inv),
-                               pack_bf16x2(o_acc[td][4 * q4 + 2] * inv, o_acc[td][4 * q4 + 3] * inv));
-    }
+    if (valid) state_store<D>(st, p, it, row_id, g);
 }
 
-hipError_t launch_items(const AttnArgs& base, const AttnItem* items, int32_t n_items, int32_t d, hipStream_t s) {
-    if (n_items == 0) return hipSuccess;
-    AttnArgs p = base;
-    p.items = items;
-    const dim3 grid(n_items, p.n_kv);
+// ------------------------------------------------------------------------------------------
+// wave-per-item kernel (decode rows)
+// ------------------------------------------------------------------------------------------
+// Uses the 16x16x32 MFMA (A[i = l % 16][k = 8 (l / 16) ..+7], B[k][j = l % 16], accumulator
+// register r = D[4 (l / 16) + r][l % 16]): 16 query rows are enough for the heads of one kv
+// group, and accumulators, query fragments and scores take half the registers of the 32-wide
+// form, which is what lets two of these waves share a SIMD.
+template <int D>
+struct DecodeSmem {
+    static constexpr int BLOCK_N = 32;
+    static constexpr int K_STRIDE = (D + 8) * 2;
+    static constexpr int K_BYTES = BLOCK_N * K_STRIDE;
+    static constexpr int V_STRIDE = (BLOCK_N + 8) * 2;  // 20 dwords: 8 consecutive rows hit distinct bank groups
+    static constexpr int V_BYTES = D * V_STRIDE;
+    static constexpr int WAVE_BYTES = K_BYTES + V_BYTES;
+};
+
+template <int D>
+__global__ void __launch_bounds__(256) attn_decode_kernel(AttnArgs p) {
+    using SM = DecodeSmem<D>;
+    constexpr int CH = D / 8;
+    constexpr int ROWS_PER_PASS = 64 / CH;       // key rows one wave-wide load covers
+    constexpr int K_IT = 32 / ROWS_PER_PASS;     // K loads per lane per block
+    constexpr int V_IT = 16 / ROWS_PER_PASS;     // V key pairs per lane per block
+    constexpr int KS = D / 32, TD = D / 16;
+    extern __shared__ __align__(16) unsigned char smem[];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int l16 = lane & 15, gq = lane >> 4;
+    const int item_idx = blockIdx.x * 4 + wave;
+    if (item_idx >= p.n_items) return;           // whole wave leaves; the kernel has no workgroup barrier
+    const AttnItem it = p.items[item_idx];
+    const int kvh = blockIdx.y;
+    unsigned char* sk = smem + wave * SM::WAVE_BYTES;
+    unsigned char* sv = sk + SM::K_BYTES;
+
+    // a decode item is one token (pad0) whose last visible key is its own: klim = key_end
+    const int tok = it.pad0;
+    const bool valid = l16 < p.group;
+    const int hq = kvh * p.group + (valid ? l16 : 0);
+    const int klim = it.key_end;
+
+    bf16x8_t qf[KS];
+    {
+        const uint16_t* qrow = p.q + (int64_t)tok * p.q_pitch + hq * D + 8 * gq;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks)
+            qf[ks] = as_bf16x8(valid ? *reinterpret_cast<const uint4*>(qrow + 32 * ks) : make_uint4(0, 0, 0, 0));
+    }
+    const int64_t row_id = (int64_t)tok * p.n_q + hq;
+    float m_run = -INFINITY, l_run = 0.f;
+    f32x4_t o_acc[TD];
+#pragma unroll
+    for (int td = 0; td < TD; ++td) o_acc[td] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    if ((it.flags & ITEM_INIT_PARTIAL) && valid) {
+        const float2 ml = *reinterpret_cast<const float2*>(p.part_ml + row_id * 2);
+        m_run = ml.x;
+        l_run = gq == 0 ? ml.y : 0.f;
+        const float* po = p.part_o + row_id * D + 4 * gq;
+#pragma unroll
+        for (int td = 0; td < TD; ++td) {
+            const float4 v = *reinterpret_cast<const float4*>(po + 16 * td);
+            o_acc[td] = f32x4_t{v.x, v.y, v.z, v.w};
+        }
+    }
+
+    const int32_t* bt = p.block_table + (int64_t)it.bt_req * p.max_blocks;
+    const int kc = lane % CH, krow0 = lane / CH;
+    uint4 k_reg[K_IT], v_reg[V_IT][2];
+    auto slot_of = [&](int key) -> int64_t {
+        return ((int64_t)bt[key >> p.page_shift] << p.page_shift) + (key & p.page_mask);
+    };
+    auto stage_load = [&](int kb0) {
+#pragma unroll
+        for (int i = 0; i < K_IT; ++i) {
+            const int key = kb0 + krow0 + ROWS_PER_PASS * i;
+            k_reg[i] = make_uint4(0, 0, 0, 0);
+            if (key < it.key_end)
+                k_reg[i] = *reinterpret_cast<const uint4*>(p.k_pages + (slot_of(key) * p.n_kv + kvh) * D + kc * 8);
+        }
+#pragma unroll
+        for (int i = 0; i < V_IT; ++i) {
+            const int key = kb0 + 2 * (krow0 + ROWS_PER_PASS * i);
+#pragma unroll
+            for (int e = 0; e < 2; ++e) {
+                v_reg[i][e] = make_uint4(0, 0, 0, 0);  // keys past the end contribute exact zeros
+                if (key + e < it.key_end)
+                    v_reg[i][e] = *reinterpret_cast<const uint4*>(p.v_pages + (slot_of(key + e) * p.n_kv + kvh) * D + kc * 8);
+            }
+        }
+    };
+    // V^T column of key k (0..31): 8 ((k >> 2) & 3) + 4 (k >> 4) + (k & 3), so that lane group gq
+    // finds the 8 keys it holds probabilities for (4 gq .. +3 and 16 + 4 gq .. +3) side by side.
+    auto stage_store = [&]() {
+#pragma unroll
+        for (int i = 0; i < K_IT; ++i)
+            *reinterpret_cast<uint4*>(sk + (krow0 + ROWS_PER_PASS * i) * SM::K_STRIDE + kc * 16) = k_reg[i];
+#pragma unroll
+        for (int i = 0; i < V_IT; ++i) {
+            const int pi = krow0 + ROWS_PER_PASS * i;                              // key pair 0..15
+            const int kp = (((pi >> 1) & 3) << 2) | ((pi >> 3) << 1) | (pi & 1);   // dword column before swizzle
+            const int col = (((kp >> 2) ^ (kc & 3)) << 2) | (kp & 3);
+            const uint32_t e[4] = {v_reg[i][0].x, v_reg[i][0].y, v_reg[i][0].z, v_reg[i][0].w};
+            const uint32_t o[4] = {v_reg[i][1].x, v_reg[i][1].y, v_reg[i][1].z, v_reg[i][1].w};
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const uint32_t ev = (j & 1) ? (e[j >> 1] >> 16) : (e[j >> 1] & 0xffffu);
+                const uint32_t ov = (j & 1) ? (o[j >> 1] & 0xffff0000u) : (o[j >> 1] << 16);
+                *reinterpret_cast<uint32_t*>(sv + (8 * kc + j) * SM::V_STRIDE + col * 4) = ev | ov;
+            }
+        }
+    };
+    // LDS traffic of one wave is processed in order; the fences keep the compiler from moving
+    // the tile reads across the tile writes of the other lanes.
+    auto wave_sync = [&]() {
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    };
+
+    const int n_blocks = (it.key_end - it.key_begin + SM::BLOCK_N - 1) / SM::BLOCK_N;
+    if (n_blocks > 0) stage_load(it.key_begin);
+    for (int b = 0; b < n_blocks; ++b) {
+        const int kb0 = it.key_begin + b * SM::BLOCK_N;
+        wave_sync();     // every lane is done reading the previous tile
+        stage_store();
+        wave_sync();     // the tile is complete
+        if (b + 1 < n_blocks) stage_load(kb0 + SM::BLOCK_N);
+
+        // S^T = K Q^T for two 16-key tiles; lane holds keys kb0 + 16 t + 4 gq + r of query row l16
+        f32x4_t s[2];
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            s[t] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                const bf16x8_t kf = as_bf16x8(*reinterpret_cast<const uint4*>(
+                    sk + (16 * t + l16) * SM::K_STRIDE + (4 * ks + gq) * 16));
+                s[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf, qf[ks], s[t], 0, 0, 0);
+            }
+        }
+        const bool need_mask = kb0 + SM::BLOCK_N > klim;
+        float mx = -INFINITY;
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                float v = s[t][r] * p.scale_log2;
+                if (need_mask && kb0 + 16 * t + 4 * gq + r >= klim) v = -INFINITY;
+                s[t][r] = v;
+                mx = fmaxf(mx, v);
+            }
+        mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+        const float m_new = fmaxf(m_run, mx);
+        const float m_use = m_new == -INFINITY ? 0.f : m_new;
+        const float alpha = __builtin_amdgcn_exp2f(m_run - m_use);
+        m_run = m_new;
+        float pv[8];
+        float psum = 0.f;
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                pv[4 * t + r] = __builtin_amdgcn_exp2f(s[t][r] - m_use);
+                psum += pv[4 * t + r];
+            }
+        const bf16x8_t pf = as_bf16x8(make_uint4(pack_bf16x2(pv[0], pv[1]), pack_bf16x2(pv[2], pv[3]),
+                                                 pack_bf16x2(pv[4], pv[5]), pack_bf16x2(pv[6], pv[7])));
+        l_run = l_run * alpha + psum;
+        if (__any(alpha != 1.0f)) {
+#pragma unroll
+            for (int td = 0; td < TD; ++td) o_acc[td] *= alpha;
+        }
+        // O^T += V^T P^T: rows d = 16 td + l16, contraction over the block's 32 keys
+#pragma unroll
+        for (int td = 0; td < TD; ++td) {
+            const int d = 16 * td + l16;
+            const bf16x8_t vf = as_bf16x8(*reinterpret_cast<const uint4*>(
+                sv + d * SM::V_STRIDE + ((gq ^ ((d >> 3) & 3)) << 4)));
+            o_acc[td] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pf, o_acc[td], 0, 0, 0);
+        }
+    }
+    if (!valid) return;
+    float l_tot = l_run + __shfl_xor(l_run, 16, 64);
+    l_tot += __shfl_xor(l_tot, 32, 64);
+    const float inv = 1.0f / l_tot;
+    uint16_t* orow = p.out + row_id * D + 4 * gq;
+#pragma unroll
+    for (int td = 0; td < TD; ++td)
+        *reinterpret_cast<uint2*>(orow + 16 * td) =
+            make_uint2(pack_bf16x2(o_acc[td][0] * inv, o_acc[td][1] * inv),
+                       pack_bf16x2(o_acc[td][2] * inv, o_acc[td][3] * inv));
+}
+
+template <int D>
+hipError_t launch_d(const AttnArgs& base, const AttnItem* items, int32_t n_items, bool decode, hipStream_t s) {
     static bool attr_done = false;
+    constexpr int tile_smem = 2 * TileSmem<D>::STAGE, dec_smem = 4 * DecodeSmem<D>::WAVE_BYTES;
     if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_kernel<128>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, 2 * Smem<128>::STAGE);
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_tile_kernel<D>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, tile_smem);
         if (e == hipSuccess)
-            e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_kernel<64>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, 2 * Smem<64>::STAGE);
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_decode_kernel<D>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, dec_smem);
         if (e != hipSuccess) return e;
         attr_done = true;
     }
-    if (d == 128)
-        attn_kernel<128><<<grid, dim3(256), 2 * Smem<128>::STAGE, s>>>(p);
+    AttnArgs p = base;
+    p.items = items;
+    p.n_items = n_items;
+    if (decode)
+        attn_decode_kernel<D><<<dim3((n_items + 3) / 4, p.n_kv), dim3(256), dec_smem, s>>>(p);
     else
-        attn_kernel<64><<<grid, dim3(256), 2 * Smem<64>::STAGE, s>>>(p);
+        attn_tile_kernel<D><<<dim3(n_items, p.n_kv), dim3(256), tile_smem, s>>>(p);
     return hipGetLastError();
 }
 
@@ -322,16 +539,16 @@ hipError_t launch_attention(const BatchDev& b, const relserve_layer& L, const vo
     p.n_kv = L.cfg.n_kv_heads;
     p.group = L.group;
     p.scale_log2 = (float)(1.4426950408889634 / sqrt((double)L.cfg.head_dim));
-    const int d = L.cfg.head_dim;
+    const bool d128 = L.cfg.head_dim == 128;
     hipError_t e = hipSuccess;
-    struct Pass { int slot; const AttnItem* items; int32_t n; };
-    const Pass passes[3] = {{3, b.items_prefix, b.n_items_prefix},
-                            {4, b.items_tile, b.n_items_tile},
-                            {5, b.items_split, b.n_items_split}};
+    struct Pass { int slot; const AttnItem* items; int32_t n; bool decode; };
+    const Pass passes[3] = {{3, b.items_prefix, b.n_items_prefix, false},
+                            {4, b.items_tile, b.n_items_tile, false},
+                            {5, b.items_split, b.n_items_split, true}};
     for (const Pass& ps : passes) {
         if (e != hipSuccess || ps.n == 0) continue;
         profile_mark(prof, ps.slot, s, true);
-        e = launch_items(p, ps.items, ps.n, d, s);
+        e = d128 ? launch_d<128>(p, ps.items, ps.n, ps.decode, s) : launch_d<64>(p, ps.items, ps.n, ps.decode, s);
         profile_mark(prof, ps.slot, s, false);
     }
     return e;

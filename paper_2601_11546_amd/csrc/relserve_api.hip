@@ -185,6 +185,7 @@ int32_t relserve::expand_batch(const relserve_layer_config& cfg, const relserve_
                 it.tok_off = (int32_t)hb.attn_tok.size();
                 hb.attn_tok.push_back(d.q_start[r]);
                 it.n_tok = 1;
+                it.pad0 = d.q_start[r];  // the decode kernel takes its single token from here
                 it.bt_req = r;
                 it.key_begin = kb;
                 it.key_end = d.ctx_len[r];
@@ -249,7 +250,7 @@ int32_t relserve_config_validate(const relserve_layer_config* c) {
     if (c->mlp_dim <= 0 || c->mlp_dim % 8) return RELSERVE_ERR_BAD_CONFIG;
     if (c->head_dim != 64 && c->head_dim != 128) return RELSERVE_ERR_BAD_CONFIG;
     if (c->n_kv_heads <= 0 || c->n_q_heads <= 0 || c->n_q_heads % c->n_kv_heads) return RELSERVE_ERR_BAD_CONFIG;
-    if (c->n_q_heads / c->n_kv_heads > ATTN_SPLIT_ROWS) return RELSERVE_ERR_BAD_CONFIG;
+    if (c->n_q_heads / c->n_kv_heads > ATTN_SPLIT_ROWS) return RELSERVE_ERR_BAD_CONFIG;  // one wave's query rows
     if (ATTN_BLOCK_M % (c->n_q_heads / c->n_kv_heads)) return RELSERVE_ERR_BAD_CONFIG;
     if (!is_pow2(c->page_size) || c->page_size < 8 || c->page_size > 256) return RELSERVE_ERR_BAD_CONFIG;
     if (!(c->rms_eps >= 0.0f) || !(c->rope_base > 0.0f)) return RELSERVE_ERR_BAD_CONFIG;

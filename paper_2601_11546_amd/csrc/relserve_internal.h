@@ -27,7 +27,8 @@ struct AttnItem {
     int32_t key_begin;  // first key position (page aligned)
     int32_t key_end;    // one past the last key position any row may see
     int32_t flags;
-    int32_t pad0, pad1;
+    int32_t pad0;       // decode items: the query token
+    int32_t pad1;
 };
 
 // Device-side view of a prepared batch (all pointers into one device allocation).
@@ -83,7 +84,7 @@ int32_t expand_batch(const relserve_layer_config& cfg, const relserve_batch_desc
 
 // Rows of queries one attention workgroup covers (4 waves x 32 MFMA columns).
 constexpr int ATTN_BLOCK_M = 128;
-constexpr int ATTN_SPLIT_ROWS = 32;
+constexpr int ATTN_SPLIT_ROWS = 16;   // query heads per kv head the decode kernel's 16-column MFMA holds
 
 // ---- kernel launchers (each enqueues on `s` and returns the launch status) ----------------
 hipError_t launch_rope_table(const int32_t* tok_pos, const float* inv_freq_dev, int32_t T, int32_t half,

@@ -40,7 +40,7 @@ def test_config_validation(rs):
     from dataclasses import replace
     bad = [replace(ok, head_dim=96), replace(ok, n_q_heads=6, n_kv_heads=4), replace(ok, page_size=12),
            replace(ok, page_size=4), replace(ok, hidden=250), replace(ok, mlp_dim=100), replace(ok, n_kv_heads=0),
-           replace(ok, rope_base=0.0), replace(ok, n_q_heads=64, n_kv_heads=1)]
+           replace(ok, rope_base=0.0), replace(ok, n_q_heads=32, n_kv_heads=1)]
     for b in bad:
         assert rs.relserve_config_validate(b) == -2, b
     for good in (W.TINY_GQA, W.TINY_D128, W.LLAMA_13B, W.LLAMA_70B, replace(ok, page_size=256)):

@@ -11,6 +11,8 @@
 // row-wise writes and the MFMA operand reads), double buffered with one barrier per k step.
 // Workgroup ids are remapped so that each of the 8 XCDs (own L2 each) walks a contiguous run
 // of tiles, token tiles fastest: concurrent workgroups of an XCD share weight tiles.
+#include <cstdlib>
+
 #include "device_utils.h"
 #include "relserve_internal.h"
 
@@ -37,12 +39,132 @@ struct GemmArgs {
     int32_t n_q, n_kv;
 };
 
+#ifndef RELSERVE_DMA_BK
+#define RELSERVE_DMA_BK 64
+#endif
+#ifndef RELSERVE_DMA_NS
+#define RELSERVE_DMA_NS 2
+#endif
+
+// Test hook: route every shape through the register-staged kernel (set from RELSERVE_GEMM_GENERIC=1).
+bool g_force_generic = getenv("RELSERVE_GEMM_GENERIC") != nullptr;
+
 enum { EPI_BF16 = 0, EPI_RES_BF16_OUT_F32 = 1, EPI_RES_F32_OUT_BF16 = 2, EPI_SWIGLU = 3, EPI_QKV_ROPE = 4 };
 
 __device__ __forceinline__ int remap_xcd(int bid, int num) {
     const int per = num / NUM_XCD, rem = num % NUM_XCD;
     const int xcd = bid % NUM_XCD, idx = bid / NUM_XCD;
     return xcd < rem ? xcd * (per + 1) + idx : rem * (per + 1) + (xcd - rem) * per + idx;
+}
+
+// Epilogue shared by both GEMM kernels: register r of accumulator tile (tn, tm) holds feature
+// 32 tn + 8 (r / 4) + 4 g + r % 4 of the wave's feature range and token 32 tm + l32 of its token range.
+template <int BM, int BN, int EPI, int D>
+__device__ __forceinline__ void gemm_epilogue(const f32x16_t (&acc)[BN / 64][BM / 64], const GemmArgs& p, int tile_m,
+                                              int tile_n, int wm, int wn, int l32, int g) {
+    constexpr int TM = BM / 64, TN = BN / 64;
+    const int t0 = tile_m * BM;
+#pragma unroll
+    for (int tm = 0; tm < TM; ++tm) {
+        const int t = t0 + wm * (BM / 2) + 32 * tm + l32;
+        if (t >= p.T) continue;
+        if (EPI == EPI_QKV_ROPE) {
+            // The wave owns features [nb, nb + 128): one head (d = 128) or two (d = 64).  The rotation
+            // partner of feature i is i + d/2: same lane, same register, D/64 tiles further on.
+            constexpr int TPH = (D > 0 ? D : 64) / 32;   // tiles per head
+            constexpr int HPW = 4 / TPH;                 // heads per wave
+            const int nb = tile_n * BN + wn * 128;
+            const int64_t slot = p.tok_slot[t];
+            const float2* cs = p.rope_cs + (int64_t)t * (D / 2);
+            const int kv_dim = p.n_kv * D;
+#pragma unroll
+            for (int hh = 0; hh < HPW; ++hh) {
+                const int head = nb / D + hh;
+                if (head >= p.n_q + 2 * p.n_kv) continue;
+                if (head < p.n_q + p.n_kv) {
+                    uint16_t* dst = head < p.n_q
+                                        ? static_cast<uint16_t*>(p.out) + (int64_t)t * (p.n_q * D) + head * D
+                                        : p.k_pages + slot * kv_dim + (head - p.n_q) * D;
+#pragma unroll
+                    for (int tl = 0; tl < TPH / 2; ++tl) {
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) {
+                            const int i = 32 * tl + 8 * q + 4 * g;
+                            const float4 c01 = *reinterpret_cast<const float4*>(cs + i);
+                            const float4 c23 = *reinterpret_cast<const float4*>(cs + i + 2);
+                            const float co[4] = {c01.x, c01.z, c23.x, c23.z}, si[4] = {c01.y, c01.w, c23.y, c23.w};
+                            float lo[4], hi[4];
+#pragma unroll
+                            for (int j = 0; j < 4; ++j) {
+                                const float a = acc[hh * TPH + tl][tm][4 * q + j];
+                                const float b = acc[hh * TPH + tl + TPH / 2][tm][4 * q + j];
+                                lo[j] = a * co[j] - b * si[j];
+                                hi[j] = a * si[j] + b * co[j];
+                            }
+                            *reinterpret_cast<uint2*>(dst + i) = make_uint2(pack_bf16x2(lo[0], lo[1]), pack_bf16x2(lo[2], lo[3]));
+                            *reinterpret_cast<uint2*>(dst + i + D / 2) =
+                                make_uint2(pack_bf16x2(hi[0], hi[1]), pack_bf16x2(hi[2], hi[3]));
+                        }
+                    }
+                } else {
+                    uint16_t* dst = p.v_pages + slot * kv_dim + (head - p.n_q - p.n_kv) * D;
+#pragma unroll
+                    for (int tl = 0; tl < TPH; ++tl) {
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) {
+                            const int i = 32 * tl + 8 * q + 4 * g;
+                            const f32x16_t& a = acc[hh * TPH + tl][tm];
+                            *reinterpret_cast<uint2*>(dst + i) = make_uint2(pack_bf16x2(a[4 * q], a[4 * q + 1]),
+                                                                            pack_bf16x2(a[4 * q + 2], a[4 * q + 3]));
+                        }
+                    }
+                }
+            }
+        } else if (EPI == EPI_SWIGLU) {
+#pragma unroll
+            for (int tn = 0; tn < TN / 2; ++tn) {
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int i = tile_n * (BN / 2) + wn * (BN / 4) + 32 * tn + 8 * q + 4 * g;
+                    if (i >= p.n_half) continue;  // n_half is a multiple of 8, i of 4: whole quad in or out
+                    float o[4];
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const float gate = acc[tn][tm][4 * q + j], up = acc[tn + TN / 2][tm][4 * q + j];
+                        o[j] = gate / (1.0f + __expf(-gate)) * up;
+                    }
+                    uint2 st = make_uint2(pack_bf16x2(o[0], o[1]), pack_bf16x2(o[2], o[3]));
+                    *reinterpret_cast<uint2*>(static_cast<uint16_t*>(p.out) + (int64_t)t * p.n_half + i) = st;
+                }
+            }
+        } else {
+#pragma unroll
+            for (int tn = 0; tn < TN; ++tn) {
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int n = tile_n * BN + wn * (BN / 2) + 32 * tn + 8 * q + 4 * g;
+                    if (n >= p.N) continue;  // N is a multiple of 4 on every path that reaches here
+                    const int64_t o = (int64_t)t * p.N + n;
+                    float v[4];
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) v[j] = acc[tn][tm][4 * q + j];
+                    if (EPI == EPI_RES_BF16_OUT_F32) {
+                        const uint2 r = *reinterpret_cast<const uint2*>(static_cast<const uint16_t*>(p.residual) + o);
+                        float4 st = make_float4(v[0] + bf16_lo(r.x), v[1] + bf16_hi(r.x), v[2] + bf16_lo(r.y),
+                                                v[3] + bf16_hi(r.y));
+                        *reinterpret_cast<float4*>(static_cast<float*>(p.out) + o) = st;
+                    } else {
+                        if (EPI == EPI_RES_F32_OUT_BF16) {
+                            const float4 r = *reinterpret_cast<const float4*>(static_cast<const float*>(p.residual) + o);
+                            v[0] += r.x; v[1] += r.y; v[2] += r.z; v[3] += r.w;
+                        }
+                        uint2 st = make_uint2(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]));
+                        *reinterpret_cast<uint2*>(static_cast<uint16_t*>(p.out) + o) = st;
+                    }
+                }
+            }
+        }
+    }
 }
 
 template <int BM, int BN, int EPI, int D = 0>
@@ -158,109 +280,178 @@ __global__ void __launch_bounds__(256) gemm_bf16_kernel(GemmArgs p) {
         if (more) store_lds((kt + 1) & 1);
         __syncthreads();
     }
+    gemm_epilogue<BM, BN, EPI, D>(acc, p, tile_m, tile_n, wm, wn, l32, g);
+}
 
-    // ---- epilogue: register r of a tile holds feature 8 (r / 4) + 4 g + r % 4, token l32
+// ------------------------------------------------------------------------------------------
+// Main kernel for K % 64 == 0: tiles go global -> LDS directly (global_load_lds_dwordx4, no
+// register staging and no LDS store instructions), two LDS stages, operand fragments double
+// buffered in registers.  The barrier that hands over a stage sits one k step BEFORE the stage
+// boundary: the last 16 MFMAs of a stage run while the first fragments of the next stage are
+// being read, and the loads of the stage after that are issued at once, so they have a whole
+// k iteration to land.
+// ------------------------------------------------------------------------------------------
+// 64 lanes x 16 bytes from (base + per-lane byte offset) to 1 KB of LDS starting at lds_addr.
+__device__ __forceinline__ void dma16(const void* base, uint32_t voff, uint32_t lds_addr) {
+    asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(base), "s"(lds_addr) : "memory");
+}
+
+// BKD = k extent of one LDS stage (64 or 32), NS = stages in the ring (NS - 1 are in flight).
+template <int BM, int BN, int EPI, int D, int BKD, int NS>
+__global__ void __launch_bounds__(256) gemm_dma_kernel(GemmArgs p) {
+    constexpr int TM = BM / 64, TN = BN / 64;
+    constexpr int ROWB = BKD * 2;                        // bytes per LDS row
+    constexpr int CPR = BKD / 8;                         // 16-byte chunks per row
+    constexpr int RPI = 1024 / ROWB;                     // rows one 1 KB wave load covers
+    constexpr int A_IT = BM / (4 * RPI), W_IT = BN / (4 * RPI);
+    constexpr int A_BYTES = BM * ROWB, W_BYTES = BN * ROWB, STAGE = A_BYTES + W_BYTES;
+    constexpr int KSTEPS = BKD / 16;
+    constexpr int LOADS = A_IT + W_IT;                   // wave loads per stage
+    static_assert(BKD == 64 || BKD == 32, "stage depth");
+    static_assert((NS - 1) * LOADS < 64, "vmcnt field");
+    static_assert(EPI != EPI_SWIGLU || TN % 2 == 0, "SwiGLU needs gate and up tiles in one wave");
+    static_assert(EPI != EPI_QKV_ROPE || (BN == 256 && (D == 64 || D == 128)), "a wave must own whole heads");
+    extern __shared__ __align__(16) unsigned char smem[];
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave >> 1, wn = wave & 1;
+    const int l32 = lane & 31, g = lane >> 5;
+
+    const int tile = remap_xcd(blockIdx.x, p.tiles_m * p.tiles_n);
+    const int tile_m = tile % p.tiles_m, tile_n = tile / p.tiles_m;
+    const int t0 = tile_m * BM;
+    const int K = p.K;
+
+    // ---- per-lane source offsets: wave load j of this wave fills LDS rows (4 j + wave) * RPI .. ;
+    // lane l owns row l / CPR of those and slot l % CPR, which holds the row's chunk slot ^ swz(row).
+    // The LDS has 64 four-byte banks and serves a 16-byte-per-lane read 16 lanes at a time, so the
+    // 16 consecutive rows those lanes read must cover all 64 banks once: swz = (row >> 1) & 7 for
+    // 128-byte rows (row parity picks the bank half), (row >> 2) & 3 for 64-byte rows.
+    // Rows past the end of a matrix re-read its last row: their products are never stored.
+    const uint32_t lrow = lane / CPR;
+    const uint32_t row_lo = (uint32_t)(wave * RPI) + lrow;   // LDS row modulo 4 * RPI (>= 32): all the swizzle needs
+    const uint32_t chunk = (lane % CPR) ^ (BKD == 64 ? ((row_lo >> 1) & 7) : ((row_lo >> 2) & 3));
+    uint32_t a_voff[A_IT], w_voff[W_IT];
 #pragma unroll
-    for (int tm = 0; tm < TM; ++tm) {
-        const int t = t0 + wm * (BM / 2) + 32 * tm + l32;
-        if (t >= p.T) continue;
-        if (EPI == EPI_QKV_ROPE) {
-            // The wave owns features [nb, nb + 128): one head (d = 128) or two (d = 64).  The rotation
-            // partner of feature i is i + d/2: same lane, same register, D/64 tiles further on.
-            constexpr int TPH = (D > 0 ? D : 64) / 32;   // tiles per head
-            constexpr int HPW = 4 / TPH;                 // heads per wave
-            const int nb = tile_n * BN + wn * 128;
-            const int64_t slot = p.tok_slot[t];
-            const float2* cs = p.rope_cs + (int64_t)t * (D / 2);
-            const int kv_dim = p.n_kv * D;
-#pragma unroll
-            for (int hh = 0; hh < HPW; ++hh) {
-                const int head = nb / D + hh;
-                if (head >= p.n_q + 2 * p.n_kv) continue;
-                if (head < p.n_q + p.n_kv) {
-                    uint16_t* dst = head < p.n_q
-                                        ? static_cast<uint16_t*>(p.out) + (int64_t)t * (p.n_q * D) + head * D
-                                        : p.k_pages + slot * kv_dim + (head - p.n_q) * D;
-#pragma unroll
-                    for (int tl = 0; tl < TPH / 2; ++tl) {
-#pragma unroll
-                        for (int q = 0; q < 4; ++q) {
-                            const int i = 32 * tl + 8 * q + 4 * g;
-                            const float4 c01 = *reinterpret_cast<const float4*>(cs + i);
-                            const float4 c23 = *reinterpret_cast<const float4*>(cs + i + 2);
-                            const float co[4] = {c01.x, c01.z, c23.x, c23.z}, si[4] = {c01.y, c01.w, c23.y, c23.w};
-                            float lo[4], hi[4];
-#pragma unroll
-                            for (int j = 0; j < 4; ++j) {
-                                const float a = acc[hh * TPH + tl][tm][4 * q + j];
-                                const float b = acc[hh * TPH + tl + TPH / 2][tm][4 * q + j];
-                                lo[j] = a * co[j] - b * si[j];
-                                hi[j] = a * si[j] + b * co[j];
-                            }
-                            *reinterpret_cast<uint2*>(dst + i) = make_uint2(pack_bf16x2(lo[0], lo[1]), pack_bf16x2(lo[2], lo[3]));
-                            *reinterpret_cast<uint2*>(dst + i + D / 2) =
-                                make_uint2(pack_bf16x2(hi[0], hi[1]), pack_bf16x2(hi[2], hi[3]));
-                        }
-                    }
-                } else {
-                    uint16_t* dst = p.v_pages + slot * kv_dim + (head - p.n_q - p.n_kv) * D;
-#pragma unroll
-                    for (int tl = 0; tl < TPH; ++tl) {
-#pragma unroll
-                        for (int q = 0; q < 4; ++q) {
-                            const int i = 32 * tl + 8 * q + 4 * g;
-                            const f32x16_t& a = acc[hh * TPH + tl][tm];
-                            *reinterpret_cast<uint2*>(dst + i) = make_uint2(pack_bf16x2(a[4 * q], a[4 * q + 1]),
-                                                                            pack_bf16x2(a[4 * q + 2], a[4 * q + 3]));
-                        }
-                    }
-                }
-            }
-        } else if (EPI == EPI_SWIGLU) {
-#pragma unroll
-            for (int tn = 0; tn < TN / 2; ++tn) {
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const int i = tile_n * (BN / 2) + wn * (BN / 4) + 32 * tn + 8 * q + 4 * g;
-                    if (i >= p.n_half) continue;  // n_half is a multiple of 8, i of 4: whole quad in or out
-                    float o[4];
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) {
-                        const float gate = acc[tn][tm][4 * q + j], up = acc[tn + TN / 2][tm][4 * q + j];
-                        o[j] = gate / (1.0f + __expf(-gate)) * up;
-                    }
-                    uint2 st = make_uint2(pack_bf16x2(o[0], o[1]), pack_bf16x2(o[2], o[3]));
-                    *reinterpret_cast<uint2*>(static_cast<uint16_t*>(p.out) + (int64_t)t * p.n_half + i) = st;
-                }
-            }
-        } else {
-#pragma unroll
-            for (int tn = 0; tn < TN; ++tn) {
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const int n = tile_n * BN + wn * (BN / 2) + 32 * tn + 8 * q + 4 * g;
-                    if (n >= p.N) continue;  // N is a multiple of 4 on every path that reaches here
-                    const int64_t o = (int64_t)t * p.N + n;
-                    float v[4];
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) v[j] = acc[tn][tm][4 * q + j];
-                    if (EPI == EPI_RES_BF16_OUT_F32) {
-                        const uint2 r = *reinterpret_cast<const uint2*>(static_cast<const uint16_t*>(p.residual) + o);
-                        float4 st = make_float4(v[0] + bf16_lo(r.x), v[1] + bf16_hi(r.x), v[2] + bf16_lo(r.y),
-                                                v[3] + bf16_hi(r.y));
-                        *reinterpret_cast<float4*>(static_cast<float*>(p.out) + o) = st;
-                    } else {
-                        if (EPI == EPI_RES_F32_OUT_BF16) {
-                            const float4 r = *reinterpret_cast<const float4*>(static_cast<const float*>(p.residual) + o);
-                            v[0] += r.x; v[1] += r.y; v[2] += r.z; v[3] += r.w;
-                        }
-                        uint2 st = make_uint2(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]));
-                        *reinterpret_cast<uint2*>(static_cast<uint16_t*>(p.out) + o) = st;
-                    }
-                }
-            }
-        }
+    for (int j = 0; j < A_IT; ++j) {
+        const int t = min(t0 + (4 * j + wave) * RPI + (int)lrow, p.T - 1);
+        a_voff[j] = ((uint32_t)t * (uint32_t)K + chunk * 8) * 2;
     }
+#pragma unroll
+    for (int j = 0; j < W_IT; ++j) {
+        const int lr = (4 * j + wave) * RPI + (int)lrow;
+        int n;
+        if (EPI == EPI_SWIGLU) {
+            constexpr int HALF = BN / 2;
+            const int gi = min(tile_n * HALF + (lr % HALF), p.n_half - 1);
+            n = lr < HALF ? gi : p.n_half + gi;
+        } else {
+            n = min(tile_n * BN + lr, p.N - 1);
+        }
+        w_voff[j] = ((uint32_t)n * (uint32_t)K + chunk * 8) * 2;
+    }
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem;
+    auto issue_stage = [&](int stage, int k0) {
+        const char* abase = reinterpret_cast<const char*>(p.a) + (size_t)k0 * 2;
+        const char* wbase = reinterpret_cast<const char*>(p.w) + (size_t)k0 * 2;
+        const uint32_t la = lds0 + stage * STAGE + wave * 1024;
+#pragma unroll
+        for (int j = 0; j < A_IT; ++j) dma16(abase, a_voff[j], la + j * 4096);
+#pragma unroll
+        for (int j = 0; j < W_IT; ++j) dma16(wbase, w_voff[j], la + A_BYTES + j * 4096);
+    };
+
+    // ---- LDS -> MFMA operand offsets
+    int a_rd[TM], w_rd[TN];
+#pragma unroll
+    for (int tm = 0; tm < TM; ++tm) a_rd[tm] = (wm * (BM / 2) + 32 * tm + l32) * ROWB;
+#pragma unroll
+    for (int tn = 0; tn < TN; ++tn) {
+        int row;
+        if (EPI == EPI_SWIGLU)
+            row = (tn < TN / 2 ? 0 : BN / 2) + wn * (BN / 4) + 32 * (tn % (TN / 2)) + l32;
+        else
+            row = wn * (BN / 2) + 32 * tn + l32;
+        w_rd[tn] = A_BYTES + row * ROWB;
+    }
+    const int swz = BKD == 64 ? ((l32 >> 1) & 7) : ((l32 >> 2) & 3);
+
+    f32x16_t acc[TN][TM];
+#pragma unroll
+    for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+        for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[tn][tm][r] = 0.f;
+
+    bf16x8_t wf[2][TN], af[2][TM];
+    auto load_frags = [&](int buf, int stage, int ks) {
+        const unsigned char* st = smem + stage * STAGE;
+        const int ch = ((2 * ks + g) ^ swz) << 4;
+#pragma unroll
+        for (int tn = 0; tn < TN; ++tn) wf[buf][tn] = as_bf16x8(*reinterpret_cast<const uint4*>(st + w_rd[tn] + ch));
+#pragma unroll
+        for (int tm = 0; tm < TM; ++tm) af[buf][tm] = as_bf16x8(*reinterpret_cast<const uint4*>(st + a_rd[tm] + ch));
+    };
+
+    const int nk = K / BKD;
+    // prologue: fill the whole ring, wait for stage 0 only
+#pragma unroll
+    for (int s = 0; s < NS; ++s)
+        if (s < nk) issue_stage(s, s * BKD);
+    if (nk >= NS)
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NS - 1) * LOADS) : "memory");
+    else
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    load_frags(0, 0, 0);
+    int cur = 0;  // stage being computed
+    for (int kt = 0; kt < nk; ++kt) {
+        const int nxt = cur + 1 == NS ? 0 : cur + 1;
+#pragma unroll
+        for (int ks = 0; ks < KSTEPS; ++ks) {
+            if (ks + 1 < KSTEPS) {
+#ifndef RELSERVE_EXP_NO_LDS
+                load_frags((ks + 1) & 1, cur, ks + 1);
+#endif
+            } else if (kt + 1 < nk) {
+                // Every fragment of this stage is in registers.  Wait for the next stage (the NS - 2
+                // younger ones may stay in flight), hand over, refill this stage's buffer with the
+                // stage NS iterations ahead, and start reading the next stage.
+#ifdef RELSERVE_EXP_NO_VMWAIT   // timing experiment only: results are wrong, every access stays in bounds
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+#else
+                if (kt + NS - 1 < nk)
+                    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"((NS - 2) * LOADS) : "memory");
+                else
+                    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+#endif
+                __syncthreads();
+#ifndef RELSERVE_EXP_NO_DMA
+                if (kt + NS < nk) issue_stage(cur, (kt + NS) * BKD);
+#endif
+                load_frags((ks + 1) & 1, nxt, 0);
+                // keep this step's MFMAs behind the hand-over: they cover the latency of the reads above
+                __builtin_amdgcn_sched_barrier(0);
+            }
+#pragma unroll
+            for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+                for (int tm = 0; tm < TM; ++tm)
+                    acc[tn][tm] = mfma_32x32x16(wf[ks & 1][tn], af[ks & 1][tm], acc[tn][tm]);
+#ifdef RELSERVE_EXP_INTERLEAVE
+            // spread the fragment reads of the next step between this step's MFMAs
+#pragma unroll
+            for (int i = 0; i < TN + TM; ++i) {
+                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                     // one LDS read
+                __builtin_amdgcn_sched_group_barrier(0x008, TN * TM / (TN + TM), 0);   // a share of the MFMAs
+            }
+#endif
+        }
+        cur = nxt;
+    }
+    gemm_epilogue<BM, BN, EPI, D>(acc, p, tile_m, tile_n, wm, wn, l32, g);
 }
 
 template <int BM, int BN, int EPI, int D = 0>
@@ -269,14 +460,23 @@ hipError_t launch_cfg(const GemmArgs& base, hipStream_t s) {
     p.tiles_m = (p.T + BM - 1) / BM;
     p.tiles_n = EPI == EPI_SWIGLU ? (p.n_half + BN / 2 - 1) / (BN / 2) : (p.N + BN - 1) / BN;
     constexpr int smem = 2 * (BM + BN) * BK * 2;
+    // ring of the direct-to-LDS kernel: as many 32-deep stages as fit beside nothing else
+    constexpr int DMA_BK = RELSERVE_DMA_BK, DMA_NS = RELSERVE_DMA_NS;
+    constexpr int dma_smem = DMA_NS * (BM + BN) * DMA_BK * 2;
     static bool attr_done = false;
     if (!attr_done) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_bf16_kernel<BM, BN, EPI, D>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_dma_kernel<BM, BN, EPI, D, DMA_BK, DMA_NS>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, dma_smem);
         if (e != hipSuccess) return e;
         attr_done = true;
     }
-    gemm_bf16_kernel<BM, BN, EPI, D><<<dim3(p.tiles_m * p.tiles_n), dim3(256), smem, s>>>(p);
+    if (p.K % 64 == 0 && !g_force_generic)
+        gemm_dma_kernel<BM, BN, EPI, D, DMA_BK, DMA_NS><<<dim3(p.tiles_m * p.tiles_n), dim3(256), dma_smem, s>>>(p);
+    else
+        gemm_bf16_kernel<BM, BN, EPI, D><<<dim3(p.tiles_m * p.tiles_n), dim3(256), smem, s>>>(p);
     return hipGetLastError();
 }
 

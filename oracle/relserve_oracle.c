@@ -273,3 +273,34 @@ int32_t oracle_layer_step(const oracle_config* c, const oracle_batch* b,
     free(mlp); free(x1); free(sel); free(tok_req); free(tok_pos);
     return 0;
 }
+
+/* Embedding -> n_layers x layer step -> final norm -> output layer on each request's last token */
+int32_t oracle_model_step(const oracle_config* c, const oracle_model* m, const oracle_batch* b,
+                          const int32_t* token_ids, uint16_t* const* k_pages, uint16_t* const* v_pages,
+                          int32_t num_pages, float* logits, uint16_t* hidden_out)
+{
+    const int32_t H = c->hidden, T = b->q_start[b->num_reqs];
+    if (T == 0) return 0;
+    uint16_t* x = (uint16_t*)malloc(sizeof(uint16_t) * (size_t)T * H);
+    float* y = (float*)malloc(sizeof(float) * (size_t)T * H);
+    for (int32_t t = 0; t < T; ++t) {
+        if (token_ids[t] < 0 || token_ids[t] >= m->vocab) { free(x); free(y); return -6; }
+        memcpy(x + (size_t)t * H, m->embedding + (size_t)token_ids[t] * H, sizeof(uint16_t) * (size_t)H);
+    }
+    for (int32_t l = 0; l < m->n_layers; ++l) {      /* R11: x <- bf16(layer(x)) */
+        int32_t rc = oracle_layer_step(c, b, &m->layers[l], x, k_pages[l], v_pages[l], num_pages,
+                                       NULL, 0, y, x, NULL, NULL);
+        if (rc) { free(x); free(y); return rc; }
+    }
+    if (hidden_out) memcpy(hidden_out, x, sizeof(uint16_t) * (size_t)T * H);
+    /* R13: the last query token of every request; R12: final norm, then the output layer */
+    float* last = (float*)malloc(sizeof(float) * (size_t)b->num_reqs * H);
+    float* normed = (float*)malloc(sizeof(float) * (size_t)b->num_reqs * H);
+    for (int32_t r = 0; r < b->num_reqs; ++r)
+        for (int32_t i = 0; i < H; ++i)
+            last[(size_t)r * H + i] = oracle_bf16_to_f32(x[(size_t)(b->q_start[r + 1] - 1) * H + i]);
+    oracle_rmsnorm(last, m->w_final_norm, c->rms_eps, b->num_reqs, H, normed);
+    oracle_linear(m->w_lm_head, m->vocab, H, normed, b->num_reqs, logits);
+    free(last); free(normed); free(x); free(y);
+    return 0;
+}

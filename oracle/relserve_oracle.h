@@ -130,6 +130,29 @@ int32_t oracle_layer_step(const oracle_config* c, const oracle_batch* b,
                           float* y_f32, uint16_t* y_bf16,
                           float* tap_attn_out, float* tap_x1);
 
+/* A stack of identical-shape layers between an embedding table and an output
+ * layer (Sec. 2.3 "LLM Inference": embedding layer, Transformer layers, output
+ * layer that turns the final hidden representation of the LAST token into
+ * logits for the next token).  Readings: R11 the residual stream is rounded to
+ * bf16 between layers (it is the layer step's bf16 output); R12 a final RMSNorm
+ * (R2) precedes the output layer; R13 logits are produced for the last query
+ * token of every request of the batch, in fp32. */
+typedef struct {
+    int32_t n_layers;
+    int32_t vocab;
+    const uint16_t* embedding;        /* [vocab, H] */
+    const oracle_weights* layers;     /* [n_layers] */
+    const uint16_t* w_final_norm;     /* [H] */
+    const uint16_t* w_lm_head;        /* [vocab, H] */
+} oracle_model;
+
+/* token_ids [T]; k_pages / v_pages: one pool per layer; logits [num_reqs, vocab];
+ * hidden_out (optional) [T, H] bf16 = the last layer's output.  Returns 0 or a
+ * negative code (-6: token id outside the vocabulary). */
+int32_t oracle_model_step(const oracle_config* c, const oracle_model* m, const oracle_batch* b,
+                          const int32_t* token_ids, uint16_t* const* k_pages, uint16_t* const* v_pages,
+                          int32_t num_pages, float* logits, uint16_t* hidden_out);
+
 /* 1 when built with double accumulators. */
 int32_t oracle_acc_is_f64(void);
 /* Threads the parallel loops (oracle_linear, the per-token attention loop) use. */

@@ -50,6 +50,11 @@ class _Weights(C.Structure):
                 ("w_in_norm", "w_qkv", "w_o", "w_post_norm", "w_gate_up", "w_down")]
 
 
+class _Model(C.Structure):
+    _fields_ = [("n_layers", C.c_int32), ("vocab", C.c_int32), ("embedding", C.c_void_p),
+                ("layers", C.c_void_p), ("w_final_norm", C.c_void_p), ("w_lm_head", C.c_void_p)]
+
+
 def _ptr(a):
     return None if a is None else a.ctypes.data_as(C.c_void_p)
 
@@ -90,6 +95,8 @@ class Oracle:
         L.oracle_layer_step.restype = C.c_int32
         L.oracle_layer_step.argtypes = [C.c_void_p] * 6 + [C.c_int32, C.c_void_p, C.c_int32] + [C.c_void_p] * 4
         L.oracle_acc_is_f64.restype = C.c_int32
+        L.oracle_model_step.restype = C.c_int32
+        L.oracle_model_step.argtypes = [C.c_void_p] * 6 + [C.c_int32, C.c_void_p, C.c_void_p]
         L.oracle_num_threads.restype = C.c_int32
 
     # -- marshalling helpers -------------------------------------------------
@@ -189,6 +196,35 @@ class Oracle:
             raise ValueError(f"oracle_layer_step rc={rc}")
         del keep, wk
         return StepResult(y, yb, attn, x1)
+
+    def model_step(self, shape, batch, model: dict, token_ids, k_pages: list, v_pages: list):
+        """model = {"embedding", "layers": [weights dict, ...], "w_final_norm", "w_lm_head"}.
+        Per-layer cache pools are updated in place.  Returns (logits [B, V] fp32, hidden [T, H] bf16 bits)."""
+        cfg = self._cfg(shape)
+        b, keep = self._batch(batch)
+        n_layers = len(model["layers"])
+        lw = (_Weights * n_layers)()
+        keep_w = []
+        for i, wd in enumerate(model["layers"]):
+            wk = {k: _chk(np.ascontiguousarray(v), np.uint16, k) for k, v in wd.items()}
+            keep_w.append(wk)
+            lw[i] = _Weights(*[_ptr(wk[n]) for n, _ in _Weights._fields_])
+        emb = _chk(np.ascontiguousarray(model["embedding"]), np.uint16, "embedding")
+        fin = _chk(np.ascontiguousarray(model["w_final_norm"]), np.uint16, "w_final_norm")
+        head = _chk(np.ascontiguousarray(model["w_lm_head"]), np.uint16, "w_lm_head")
+        m = _Model(n_layers, emb.shape[0], _ptr(emb), C.cast(lw, C.c_void_p), _ptr(fin), _ptr(head))
+        ids = _chk(np.ascontiguousarray(token_ids, dtype=np.int32), np.int32, "token_ids")
+        kp = (C.c_void_p * n_layers)(*[_chk(a, np.uint16, "k_pages").ctypes.data for a in k_pages])
+        vp = (C.c_void_p * n_layers)(*[_chk(a, np.uint16, "v_pages").ctypes.data for a in v_pages])
+        T = int(batch.q_start[-1])
+        logits = np.empty((len(batch.ctx_len), emb.shape[0]), np.float32)
+        hidden = np.empty((T, shape.hidden), np.uint16)
+        rc = self.lib.oracle_model_step(C.byref(cfg), C.byref(m), C.byref(b), _ptr(ids), kp, vp,
+                                        k_pages[0].shape[0], _ptr(logits), _ptr(hidden))
+        if rc:
+            raise ValueError(f"oracle_model_step rc={rc}")
+        del keep, keep_w
+        return logits, hidden
 
     @property
     def num_threads(self) -> int:

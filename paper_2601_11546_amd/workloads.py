@@ -196,6 +196,22 @@ def make_weights(shape: LayerShape, seed: int, n_layers: int = 0) -> dict:
             "w_post_norm": norm(), "w_gate_up": proj(2 * I, H), "w_down": proj(H, I, out_std)}
 
 
+def make_model(shape: LayerShape, n_layers: int, vocab: int, seed: int, scaled: bool = True) -> dict:
+    """Random-init stack: embedding ~N(0, 1) (so that the residual stream has unit scale like the
+    activations of the single-layer workloads), layers as make_weights, output layer ~N(0, 0.02)."""
+    rng = np.random.default_rng(seed + 31337)
+    H = shape.hidden
+    emb = f32_to_bf16_bits(rng.standard_normal((vocab, H), dtype=np.float32))
+    head = f32_to_bf16_bits(rng.standard_normal((vocab, H), dtype=np.float32) * np.float32(0.02))
+    fin = f32_to_bf16_bits(np.float32(1.0) + rng.standard_normal(H, dtype=np.float32) * np.float32(0.02))
+    layers = [make_weights(shape, seed + 101 * (i + 1), n_layers if scaled else 0) for i in range(n_layers)]
+    return {"embedding": emb, "layers": layers, "w_final_norm": fin, "w_lm_head": head}
+
+
+def make_token_ids(T: int, vocab: int, seed: int) -> np.ndarray:
+    return np.random.default_rng(seed + 4242).integers(0, vocab, T).astype(np.int32)
+
+
 def make_activations(T: int, H: int, seed: int) -> np.ndarray:
     rng = np.random.default_rng(seed + 7919)
     return f32_to_bf16_bits(rng.standard_normal((T, H), dtype=np.float32))

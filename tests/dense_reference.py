@@ -26,6 +26,17 @@ def rope_complex(v: torch.Tensor, pos: torch.Tensor, base: float) -> torch.Tenso
     return torch.cat([z.real, z.imag], dim=-1)
 
 
+def dense_model_logits(shape, model, token_ids):
+    """Whole stack on one request's full token sequence: logits of its last token (fp64)."""
+    x_bits = model["embedding"][np.asarray(token_ids)]
+    for wts in model["layers"]:
+        y = dense_layer(shape, wts, x_bits)["y"]
+        x_bits = y.to(torch.float32).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    last = _t(x_bits[-1:])
+    h = F.rms_norm(last, (shape.hidden,), _t(model["w_final_norm"]), eps=shape.rms_eps)
+    return F.linear(h, _t(model["w_lm_head"]))[0]
+
+
 def dense_layer(shape, weights, x_bits, round_kv_bf16=True, kv_override=None):
     """x_bits: [L, H] one request's whole sequence.  Returns dict of fp64 tensors.
 

@@ -77,3 +77,27 @@ def gather_kv(shape, block_table_row, L, k_pages, v_pages):
     kf = k_pages.reshape(-1, shape.n_kv_heads, shape.head_dim)
     vf = v_pages.reshape(-1, shape.n_kv_heads, shape.head_dim)
     return kf[slots], vf[slots]
+
+
+def run_model_flow(flow: Flow, token_ids: list, model_step_fn):
+    """Like run_flow for a whole stack: model_step_fn(batch, ids[T]) -> logits [B, V].
+    Returns, per request, the logits produced by the step that consumed its LAST token."""
+    R = len(flow.seq_len)
+    done = list(flow.start) if flow.start else [0] * R
+    final = [None] * R
+    for step in flow.schedule:
+        reqs = [r for r, _ in step]
+        q_len = np.array([n for _, n in step], np.int32)
+        ctx = np.array([done[r] + n for r, n in step], np.int32)
+        qs = np.zeros(len(step) + 1, np.int32)
+        qs[1:] = np.cumsum(q_len)
+        pid = np.array([flow.prefix_id[r] if flow.prefix_id[r] >= 0 and done[r] >= flow.prefix_len[flow.prefix_id[r]]
+                        else -1 for r in reqs], np.int32)
+        batch = W.Batch(qs, ctx, np.ascontiguousarray(flow.block_table[reqs]), pid, flow.prefix_len, flow.num_pages)
+        ids = np.concatenate([token_ids[r][done[r]:done[r] + n] for r, n in step]).astype(np.int32)
+        logits = np.asarray(model_step_fn(batch, ids))
+        for i, (r, n) in enumerate(step):
+            done[r] += n
+            if done[r] == flow.seq_len[r]:
+                final[r] = logits[i]
+    return final

@@ -29,6 +29,11 @@ MUTANTS = [
     ("bf16_truncation", "u += 0x7fffu + lsb;", "(void)lsb;"),
     ("kv_not_rounded_through_cache", "vb[(size_t)t * kv_dim + i] = oracle_f32_to_bf16(row[q_dim + kv_dim + i]);",
      "vb[(size_t)t * kv_dim + i] = oracle_f32_to_bf16(row[q_dim + i]);"),
+    ("logits_from_first_token", "x[(size_t)(b->q_start[r + 1] - 1) * H + i]", "x[(size_t)(b->q_start[r]) * H + i]"),
+    ("final_norm_dropped", "oracle_linear(m->w_lm_head, m->vocab, H, normed, b->num_reqs, logits);",
+     "oracle_linear(m->w_lm_head, m->vocab, H, last, b->num_reqs, logits);"),
+    ("layers_share_one_cache", "x, k_pages[l], v_pages[l], num_pages,", "x, k_pages[0], v_pages[0], num_pages,"),
+    ("stream_not_rounded_between_layers", "NULL, 0, y, x, NULL, NULL);", "NULL, 0, y, NULL, NULL, NULL); for (size_t i = 0; i < (size_t)T * H; ++i) x[i] = (uint16_t)(oracle_f32_to_bf16(y[i]) & 0xfff0u);"),
     ("softmax_unnormalised", "out[(size_t)a * d + i] = (float)(o[i] / denom);", "out[(size_t)a * d + i] = (float)(o[i]);"),
 ]
 

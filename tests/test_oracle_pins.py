@@ -10,8 +10,8 @@ import torch
 import torch.nn.functional as F
 
 from paper_2601_11546_amd import workloads as W
-from tests.dense_reference import dense_layer, rope_complex
-from tests.flows import gather_kv, make_flow, run_flow
+from tests.dense_reference import dense_layer, dense_model_logits, rope_complex
+from tests.flows import gather_kv, make_flow, run_flow, run_model_flow
 
 SHAPES = {"mha": W.TINY, "gqa": W.TINY_GQA, "d128": W.TINY_D128}
 
@@ -398,6 +398,68 @@ def test_oracle_own_rounding_error_is_small(oracle, oracle64):
     err = np.abs(outs[0] - outs[1]).max()
     rel = np.linalg.norm(outs[0] - outs[1]) / np.linalg.norm(outs[1])
     assert err < 2e-4 and rel < 1e-5, (err, rel)
+
+
+# ---------------------------------------------------------------------------
+# the stack: embedding -> layers -> final norm -> output layer on the last token
+# ---------------------------------------------------------------------------
+def _model_caches(shape, flow, n_layers, seed):
+    ks, vs = [], []
+    for l in range(n_layers):
+        k, v = W.make_cache(shape, flow.num_pages, seed + l)
+        ks.append(k)
+        vs.append(v)
+    return ks, vs
+
+
+@pytest.mark.parametrize("name", ["mha", "gqa"])
+def test_model_step_matches_dense_stack(oracle, name):
+    """Chunked prefill + decode through the paged 3-layer oracle == torch fp64 recompute of
+    each request's whole token sequence (next-token logits of the last token)."""
+    shape = SHAPES[name]
+    n_layers, vocab = 3, 211
+    model = W.make_model(shape, n_layers, vocab, seed=70)
+    seq = [29, 18, 33]
+    sched = [[(0, 20), (1, 18)], [(0, 8), (2, 33)], [(0, 1)]]
+    flow = make_flow(shape, seq, sched, seed=71)
+    ids = [W.make_token_ids(L, vocab, 72 + r) for r, L in enumerate(seq)]
+    ks, vs = _model_caches(shape, flow, n_layers, 73)
+    final = run_model_flow(flow, ids, lambda b, t: oracle.model_step(shape, b, model, t, ks, vs)[0])
+    for r in range(len(seq)):
+        want = dense_model_logits(shape, model, ids[r]).numpy()
+        # slack: rare one-ulp bf16 flips of cached k/v and of the stream between layers
+        np.testing.assert_allclose(final[r], want, rtol=0, atol=2e-2 * np.abs(want).max())
+        assert np.corrcoef(final[r], want)[0, 1] > 0.9999
+
+
+def test_model_step_is_the_composition_of_pinned_pieces(oracle):
+    """Exact identity: model step == embedding rows -> layer step (bf16 out) per layer ->
+    rmsnorm -> linear on each request's last row, all of them pinned above."""
+    shape = W.TINY_GQA
+    n_layers, vocab = 2, 97
+    model = W.make_model(shape, n_layers, vocab, seed=80)
+    wl = W.workload_tiny_prefix(shape=shape)
+    b = wl.batch
+    ids = W.make_token_ids(b.T, vocab, 81)
+    flowless_k = [W.make_cache(shape, b.num_pages, 82 + l) for l in range(n_layers)]
+    ks, vs = [k.copy() for k, _ in flowless_k], [v.copy() for _, v in flowless_k]
+    logits, hidden = oracle.model_step(shape, b, model, ids, ks, vs)
+    x = model["embedding"][ids]
+    ks2, vs2 = [k.copy() for k, _ in flowless_k], [v.copy() for _, v in flowless_k]
+    for l in range(n_layers):
+        x = oracle.layer_step(shape, b, model["layers"][l], x, ks2[l], vs2[l]).y_bf16
+    np.testing.assert_array_equal(hidden, x)
+    last = W.bf16_bits_to_f32(x[b.q_start[1:] - 1])
+    want = oracle.linear(model["w_lm_head"], oracle.rmsnorm(last, model["w_final_norm"], shape.rms_eps))
+    np.testing.assert_array_equal(logits, want)
+    for l in range(n_layers):
+        np.testing.assert_array_equal(ks[l], ks2[l])
+        np.testing.assert_array_equal(vs[l], vs2[l])
+    # a token id outside the vocabulary is refused
+    bad = ids.copy()
+    bad[3] = vocab
+    with pytest.raises(ValueError):
+        oracle.model_step(shape, b, model, bad, ks, vs)
 
 
 def test_golden_tiny_layer_step_is_stable():

@@ -169,6 +169,35 @@ int32_t relserve_layer_step(const relserve_layer* layer, const relserve_batch* b
                             const void* x, void* y, relserve_kv_cache cache,
                             void* workspace, size_t workspace_bytes, void* stream);
 
+/* A stack of n_layers identical-shape layers between an embedding table and an
+ * output layer (Sec. 2.3 "LLM Inference": the output layer turns the final
+ * hidden representation of a request's LAST token into next-token logits).
+ * `layers` and `caches` are HOST arrays of n_layers entries holding device
+ * pointers; the other pointers are device bf16.  vocab must be a multiple of 4. */
+typedef struct {
+    int32_t n_layers;
+    int32_t vocab;
+    const void* embedding;                  /* [vocab, H] */
+    const relserve_layer_weights* layers;   /* host array [n_layers] */
+    const relserve_kv_cache* caches;        /* host array [n_layers], one pool pair per layer */
+    const void* w_final_norm;               /* [H] */
+    const void* w_lm_head;                  /* [vocab, H] */
+} relserve_model;
+
+/* Workspace of relserve_model_step: one layer's workspace plus the residual
+ * stream [T, H] and the gathered last rows [num_reqs, H]. */
+int32_t relserve_model_workspace_bytes(const relserve_layer* layer, int32_t max_tokens, int32_t max_reqs,
+                                       size_t* out);
+
+/* One model step over a prepared batch: x = embedding[token_ids] (ids outside
+ * [0, vocab) are clamped, never dereferenced out of range), n_layers layer
+ * steps with the stream rounded to bf16 between layers, final RMSNorm and the
+ * output layer on the last query token of every request.  token_ids: device
+ * int32 [T]; logits: device fp32 [num_reqs, vocab]. */
+int32_t relserve_model_step(const relserve_layer* layer, const relserve_batch* batch,
+                            const relserve_model* model, const int32_t* token_ids, void* logits,
+                            void* workspace, size_t workspace_bytes, void* stream);
+
 /* ---- single stages, exported so that each kernel can be checked alone ---- */
 
 /* out[t, :] = x[t, :] * w / sqrt(mean(x[t, :]^2) + eps); x is bf16 when
@@ -177,8 +206,8 @@ int32_t relserve_rmsnorm(const void* x, int32_t x_is_f32, const void* w, float e
                          int32_t n_rows, int32_t hidden, void* out, void* stream);
 
 /* out[T, N] = a[T, K] * w[N, K]^T (Eq. 3 and every other dense map), bf16 in,
- * fp32 accumulate.  epilogue: 0 = store bf16; 1 = add residual (bf16 [T, N])
- * and store fp32; 2 = add residual (fp32 [T, N]) and store bf16; 3 = SwiGLU:
+ * fp32 accumulate.  epilogue: 0 = store bf16; 1 = add residual (bf16 [T, N],
+ * or none when NULL) and store fp32; 2 = add residual (fp32 [T, N]) and store bf16; 3 = SwiGLU:
  * w holds [gate | up] rows (N = 2 * n_half), out[T, n_half] = silu(g) * u bf16.
  * K must be a multiple of 8, N of 4 (of 16 for SwiGLU). */
 int32_t relserve_linear(const void* a, const void* w, int32_t T, int32_t N, int32_t K,

@@ -25,7 +25,7 @@ PROFILE_SLOTS = 12
 EXPORTS = ["relserve_version", "relserve_strerror", "relserve_config_validate", "relserve_layer_create",
            "relserve_layer_destroy", "relserve_batch_validate", "relserve_batch_slots", "relserve_batch_prepare",
            "relserve_batch_destroy", "relserve_batch_get_info", "relserve_workspace_bytes", "relserve_kv_append",
-           "relserve_layer_step", "relserve_rmsnorm", "relserve_linear", "relserve_rope_append",
+           "relserve_layer_step", "relserve_model_workspace_bytes", "relserve_model_step", "relserve_rmsnorm", "relserve_linear", "relserve_rope_append",
            "relserve_qkv_rope_append",
            "relserve_attention", "relserve_profile_slot_name", "relserve_profile_enable", "relserve_profile_read"]
 
@@ -57,6 +57,11 @@ class LayerWeights(C.Structure):
                 ("w_in_norm", "w_qkv", "w_o", "w_post_norm", "w_gate_up", "w_down")]
 
 
+class Model(C.Structure):
+    _fields_ = [("n_layers", C.c_int32), ("vocab", C.c_int32), ("embedding", C.c_void_p), ("layers", C.c_void_p),
+                ("caches", C.c_void_p), ("w_final_norm", C.c_void_p), ("w_lm_head", C.c_void_p)]
+
+
 class BatchInfo(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("num_tokens", "num_reqs", "num_decode_rows", "num_prefill_rows",
                                          "num_prefix_groups", "num_attn_items")]
@@ -80,6 +85,9 @@ for _n, _a in {
     "relserve_kv_append": [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, KVCache, C.c_void_p],
     "relserve_layer_step": [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, KVCache,
                             C.c_void_p, C.c_size_t, C.c_void_p],
+    "relserve_model_workspace_bytes": [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p],
+    "relserve_model_step": [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t,
+                            C.c_void_p],
     "relserve_rmsnorm": [C.c_void_p, C.c_int32, C.c_void_p, C.c_float, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p],
     "relserve_linear": [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_void_p,
                         C.c_void_p, C.c_void_p],
@@ -237,6 +245,26 @@ def relserve_layer_step(layer, pbatch, weights: dict, x, y, k_pages, v_pages, wo
                                     _cache(k_pages, v_pages), _ptr(workspace),
                                     workspace.numel() * workspace.element_size(), _stream(stream)),
            "relserve_layer_step")
+
+
+def relserve_model_workspace_bytes(layer: Layer, max_tokens: int, max_reqs: int) -> int:
+    out = C.c_size_t()
+    _check(_lib.relserve_model_workspace_bytes(layer.handle, int(max_tokens), int(max_reqs), C.byref(out)),
+           "relserve_model_workspace_bytes")
+    return int(out.value)
+
+
+def relserve_model_step(layer, pbatch, model: dict, token_ids, logits, workspace, stream=None) -> None:
+    """model = {"embedding", "layers": [weights dict], "caches": [(k_pages, v_pages)], "w_final_norm", "w_lm_head"}
+    of torch tensors."""
+    n = len(model["layers"])
+    lw = (LayerWeights * n)(*[_weights(w) for w in model["layers"]])
+    lc = (KVCache * n)(*[_cache(k, v) for k, v in model["caches"]])
+    m = Model(n, model["embedding"].shape[0], model["embedding"].data_ptr(), C.cast(lw, C.c_void_p),
+              C.cast(lc, C.c_void_p), model["w_final_norm"].data_ptr(), model["w_lm_head"].data_ptr())
+    _check(_lib.relserve_model_step(layer.handle, pbatch.handle, C.byref(m), _ptr(token_ids), _ptr(logits),
+                                    _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream)),
+           "relserve_model_step")
 
 
 def relserve_rmsnorm(x, w, eps: float, out, stream=None) -> None:

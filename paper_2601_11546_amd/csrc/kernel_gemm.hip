@@ -149,7 +149,8 @@ __device__ __forceinline__ void gemm_epilogue(const f32x16_t (&acc)[BN / 64][BM 
 #pragma unroll
                     for (int j = 0; j < 4; ++j) v[j] = acc[tn][tm][4 * q + j];
                     if (EPI == EPI_RES_BF16_OUT_F32) {
-                        const uint2 r = *reinterpret_cast<const uint2*>(static_cast<const uint16_t*>(p.residual) + o);
+                        uint2 r = make_uint2(0, 0);  // no residual given: plain fp32 output
+                        if (p.residual) r = *reinterpret_cast<const uint2*>(static_cast<const uint16_t*>(p.residual) + o);
                         float4 st = make_float4(v[0] + bf16_lo(r.x), v[1] + bf16_hi(r.x), v[2] + bf16_lo(r.y),
                                                 v[3] + bf16_hi(r.y));
                         *reinterpret_cast<float4*>(static_cast<float*>(p.out) + o) = st;

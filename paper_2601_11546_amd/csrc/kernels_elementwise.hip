@@ -29,8 +29,10 @@ hipError_t launch_rope_table(const int32_t* tok_pos, const float* inv_freq_dev, 
 // ---- RMSNorm: one workgroup per row --------------------------------------------------------
 template <bool IN_F32>
 __global__ void __launch_bounds__(256) rmsnorm_kernel(const void* __restrict__ xv, const uint16_t* __restrict__ w,
-                                                      float eps, int32_t H, uint16_t* __restrict__ out) {
-    const int64_t row = blockIdx.x;
+                                                      float eps, int32_t H, uint16_t* __restrict__ out,
+                                                      const int32_t* __restrict__ row_index) {
+    const int64_t orow = blockIdx.x;
+    const int64_t row = row_index ? row_index[orow] : orow;  // optional gather of the input row
     const int tid = threadIdx.x;
     __shared__ float red[4];
     float ss = 0.f;
@@ -66,19 +68,38 @@ __global__ void __launch_bounds__(256) rmsnorm_kernel(const void* __restrict__ x
         o.y = pack_bf16x2(v[2] * inv * bf16_lo(wu.y), v[3] * inv * bf16_hi(wu.y));
         o.z = pack_bf16x2(v[4] * inv * bf16_lo(wu.z), v[5] * inv * bf16_hi(wu.z));
         o.w = pack_bf16x2(v[6] * inv * bf16_lo(wu.w), v[7] * inv * bf16_hi(wu.w));
-        *reinterpret_cast<uint4*>(out + row * H + (int64_t)c * 8) = o;
+        *reinterpret_cast<uint4*>(out + orow * H + (int64_t)c * 8) = o;
     }
 }
 
 hipError_t launch_rmsnorm(const void* x, bool x_is_f32, const void* w, float eps, int32_t rows, int32_t H,
-                          void* out, hipStream_t s) {
+                          void* out, hipStream_t s, const int32_t* row_index) {
     if (rows == 0) return hipSuccess;
     if (x_is_f32)
         rmsnorm_kernel<true><<<dim3(rows), dim3(256), 0, s>>>(x, static_cast<const uint16_t*>(w), eps, H,
-                                                              static_cast<uint16_t*>(out));
+                                                              static_cast<uint16_t*>(out), row_index);
     else
         rmsnorm_kernel<false><<<dim3(rows), dim3(256), 0, s>>>(x, static_cast<const uint16_t*>(w), eps, H,
-                                                               static_cast<uint16_t*>(out));
+                                                               static_cast<uint16_t*>(out), row_index);
+    return hipGetLastError();
+}
+
+// ---- embedding gather: x[t, :] = table[clamp(id[t]), :] -----------------------------------
+__global__ void embedding_kernel(const int32_t* __restrict__ ids, const uint4* __restrict__ table, int32_t vocab,
+                                 int32_t row_chunks, int32_t T, uint4* __restrict__ out) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= (int64_t)T * row_chunks) return;
+    const int32_t t = (int32_t)(i / row_chunks), c = (int32_t)(i % row_chunks);
+    const int32_t id = min(max(ids[t], 0), vocab - 1);  // ids are the caller's contract; never read outside the table
+    out[i] = table[(int64_t)id * row_chunks + c];
+}
+
+hipError_t launch_embedding(const int32_t* ids, const void* table, int32_t vocab, int32_t H, int32_t T, void* out,
+                            hipStream_t s) {
+    const int64_t n = (int64_t)T * (H / 8);
+    if (n == 0) return hipSuccess;
+    embedding_kernel<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s>>>(
+        ids, static_cast<const uint4*>(table), vocab, H / 8, T, static_cast<uint4*>(out));
     return hipGetLastError();
 }
 

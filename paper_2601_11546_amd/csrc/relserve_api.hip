@@ -326,6 +326,7 @@ int32_t relserve_batch_prepare(const relserve_layer* L, const relserve_batch_des
     auto reserve = [&](size_t bytes) { size_t o = off; off += align_up(bytes ? bytes : 1); return o; };
     const size_t o_req = reserve(sizeof(int32_t) * T), o_pos = reserve(sizeof(int32_t) * T);
     const size_t o_slot = reserve(sizeof(int32_t) * T);
+    const size_t o_last = reserve(sizeof(int32_t) * B);
     const size_t o_bt = reserve(sizeof(int32_t) * (size_t)B * desc->max_blocks);
     const size_t o_tok = reserve(sizeof(int32_t) * hb.attn_tok.size());
     const size_t o_ip = reserve(sizeof(AttnItem) * hb.items_prefix.size());
@@ -341,6 +342,11 @@ int32_t relserve_batch_prepare(const relserve_layer* L, const relserve_batch_des
     put(o_req, hb.tok_req.data(), sizeof(int32_t) * T);
     put(o_pos, hb.tok_pos.data(), sizeof(int32_t) * T);
     put(o_slot, hb.tok_slot.data(), sizeof(int32_t) * T);
+    {
+        std::vector<int32_t> last(B);
+        for (int32_t r = 0; r < B; ++r) last[r] = desc->q_start[r + 1] - 1;
+        put(o_last, last.data(), sizeof(int32_t) * B);
+    }
     put(o_bt, desc->block_table, sizeof(int32_t) * (size_t)B * desc->max_blocks);
     put(o_tok, hb.attn_tok.data(), sizeof(int32_t) * hb.attn_tok.size());
     put(o_ip, hb.items_prefix.data(), sizeof(AttnItem) * hb.items_prefix.size());
@@ -364,6 +370,7 @@ int32_t relserve_batch_prepare(const relserve_layer* L, const relserve_batch_des
     dv.tok_req = reinterpret_cast<int32_t*>(base + o_req);
     dv.tok_pos = reinterpret_cast<int32_t*>(base + o_pos);
     dv.tok_slot = reinterpret_cast<int32_t*>(base + o_slot);
+    dv.last_tok = reinterpret_cast<int32_t*>(base + o_last);
     dv.block_table = reinterpret_cast<int32_t*>(base + o_bt);
     dv.attn_tok = reinterpret_cast<int32_t*>(base + o_tok);
     dv.items_prefix = reinterpret_cast<AttnItem*>(base + o_ip);
@@ -437,7 +444,7 @@ int32_t relserve_linear(const void* a, const void* w, int32_t T, int32_t N, int3
     if ((int64_t)T * K >= ((int64_t)1 << 31) || (int64_t)N * K >= ((int64_t)1 << 31)) return RELSERVE_ERR_TOO_LARGE;
     if (T == 0) return RELSERVE_OK;
     if (!a || !w || !out) return RELSERVE_ERR_NULL_POINTER;
-    if ((epilogue == 1 || epilogue == 2) && !residual) return RELSERVE_ERR_NULL_POINTER;
+    if (epilogue == 2 && !residual) return RELSERVE_ERR_NULL_POINTER;
     hipError_t e = launch_linear(a, w, T, N, K, epilogue, residual, out, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? RELSERVE_OK : RELSERVE_ERR_HIP;
 }
@@ -515,6 +522,50 @@ int32_t relserve_layer_step(const relserve_layer* L, const relserve_batch* b, co
     run(S_GU, [&] { return launch_linear(w.h, wt->w_gate_up, T, 2 * c.mlp_dim, c.hidden, 3, nullptr, w.act, s); });
     run(S_DOWN, [&] { return launch_linear(w.act, wt->w_down, T, c.hidden, c.mlp_dim, 2, w.x1, y, s); });
     return e == hipSuccess ? RELSERVE_OK : RELSERVE_ERR_HIP;
+}
+
+int32_t relserve_model_workspace_bytes(const relserve_layer* L, int32_t max_tokens, int32_t max_reqs, size_t* out) {
+    if (!L || !out) return RELSERVE_ERR_NULL_POINTER;
+    if (max_tokens < 0 || max_reqs < 0) return RELSERVE_ERR_BAD_ARGUMENT;
+    *out = carve(*L, max_tokens, nullptr).total + align_up((size_t)max_tokens * L->cfg.hidden * 2) +
+           align_up((size_t)max_reqs * L->cfg.hidden * 2) + kAlign;
+    return RELSERVE_OK;
+}
+
+int32_t relserve_model_step(const relserve_layer* L, const relserve_batch* b, const relserve_model* m,
+                            const int32_t* token_ids, void* logits, void* workspace, size_t workspace_bytes,
+                            void* stream) {
+    if (int32_t rc = check_pair(L, b)) return rc;
+    if (!m) return RELSERVE_ERR_NULL_POINTER;
+    if (m->n_layers < 0 || m->vocab <= 0 || m->vocab % 4) return RELSERVE_ERR_BAD_ARGUMENT;
+    const int32_t T = b->dev.T, B = b->dev.num_reqs, H = L->cfg.hidden;
+    if (T == 0) return RELSERVE_OK;
+    if (!token_ids || !logits || !m->embedding || !m->w_final_norm || !m->w_lm_head) return RELSERVE_ERR_NULL_POINTER;
+    if (m->n_layers > 0 && (!m->layers || !m->caches)) return RELSERVE_ERR_NULL_POINTER;
+    for (int32_t l = 0; l < m->n_layers; ++l) {
+        const relserve_layer_weights& w = m->layers[l];
+        if (!w.w_in_norm || !w.w_qkv || !w.w_o || !w.w_post_norm || !w.w_gate_up || !w.w_down)
+            return RELSERVE_ERR_NULL_POINTER;
+        if (int32_t rc = check_cache(b, m->caches[l])) return rc;
+    }
+    if ((int64_t)m->vocab * H >= ((int64_t)1 << 31)) return RELSERVE_ERR_TOO_LARGE;
+    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) % kAlign)) return RELSERVE_ERR_WORKSPACE;
+    const size_t layer_ws = carve(*L, T, nullptr).total;
+    const size_t x_bytes = align_up((size_t)T * H * 2), last_bytes = align_up((size_t)B * H * 2);
+    if (layer_ws + x_bytes + last_bytes > workspace_bytes) return RELSERVE_ERR_WORKSPACE;
+    char* x = static_cast<char*>(workspace) + layer_ws;
+    char* h_last = x + x_bytes;
+
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (launch_embedding(token_ids, m->embedding, m->vocab, H, T, x, s) != hipSuccess) return RELSERVE_ERR_HIP;
+    for (int32_t l = 0; l < m->n_layers; ++l)   // the residual stream stays in x, rounded to bf16 between layers
+        if (int32_t rc = relserve_layer_step(L, b, &m->layers[l], x, x, m->caches[l], workspace, layer_ws, stream))
+            return rc;
+    if (launch_rmsnorm(x, false, m->w_final_norm, L->cfg.rms_eps, B, H, h_last, s, b->dev.last_tok) != hipSuccess)
+        return RELSERVE_ERR_HIP;
+    if (launch_linear(h_last, m->w_lm_head, B, m->vocab, H, 1, nullptr, logits, s) != hipSuccess)
+        return RELSERVE_ERR_HIP;
+    return RELSERVE_OK;
 }
 
 // ---- profiling ---------------------------------------------------------------------------

@@ -37,6 +37,7 @@ struct BatchDev {
     const int32_t* tok_req;      // [T]
     const int32_t* tok_pos;      // [T] position of the token in its own sequence
     const int32_t* tok_slot;     // [T] cache slot the token is appended to
+    const int32_t* last_tok;     // [num_reqs] packed row of each request's last query token
     const int32_t* block_table;  // [num_reqs, max_blocks]
     const float2* rope_cs;       // [T, head_dim / 2] (cos, sin) of pos * base^(-2i/d)
     const int32_t* attn_tok;     // token lists of the attention items
@@ -90,7 +91,9 @@ constexpr int ATTN_SPLIT_ROWS = 16;   // query heads per kv head the decode kern
 hipError_t launch_rope_table(const int32_t* tok_pos, const float* inv_freq_dev, int32_t T, int32_t half,
                              float2* out, hipStream_t s);
 hipError_t launch_rmsnorm(const void* x, bool x_is_f32, const void* w, float eps, int32_t rows, int32_t H,
-                          void* out, hipStream_t s);
+                          void* out, hipStream_t s, const int32_t* row_index = nullptr);
+hipError_t launch_embedding(const int32_t* ids, const void* table, int32_t vocab, int32_t H, int32_t T, void* out,
+                            hipStream_t s);
 hipError_t launch_kv_append(const BatchDev& b, const void* k, const void* v, void* k_pages, void* v_pages,
                             int32_t row_elems, hipStream_t s);
 hipError_t launch_rope_append(const BatchDev& b, const relserve_layer& L, void* qkv, void* k_pages,

@@ -339,3 +339,63 @@ def test_full_size_prefill_only_13b(rs, oracle):
 def test_full_size_decode_plus_chunk_13b(rs, oracle):
     wl = W.workload_decode_plus_chunk_13b(512)
     _sampled_parity(rs, oracle, wl, [0, 127, 128], max_prefill_rows=24)
+
+
+# ---------------------------------------------------------------------------
+# model step: embedding -> layer stack -> final norm -> output layer on last tokens
+# ---------------------------------------------------------------------------
+def _gpu_model(rs, shape, model_bits, caches_bits):
+    return {"embedding": dev_bf16(model_bits["embedding"]),
+            "layers": [{k: dev_bf16(v) for k, v in w.items()} for w in model_bits["layers"]],
+            "caches": [(dev_bf16(k), dev_bf16(v)) for k, v in caches_bits],
+            "w_final_norm": dev_bf16(model_bits["w_final_norm"]), "w_lm_head": dev_bf16(model_bits["w_lm_head"])}
+
+
+def _model_case(rs, oracle, shape, batch, n_layers, vocab, seed, scaled, what):
+    model = W.make_model(shape, n_layers, vocab, seed, scaled=scaled)
+    ids = W.make_token_ids(batch.T, vocab, seed)
+    caches = [W.make_cache(shape, batch.num_pages, seed + 7 * l) for l in range(n_layers)]
+    gm = _gpu_model(rs, shape, model, caches)
+    layer = rs.relserve_layer_create(shape)
+    pb = rs.relserve_batch_prepare(layer, batch)
+    ws = torch.empty(rs.relserve_model_workspace_bytes(layer, batch.T, batch.num_reqs), dtype=torch.uint8, device="cuda")
+    logits = torch.empty(batch.num_reqs, vocab, dtype=torch.float32, device="cuda")
+    rs.relserve_model_step(layer, pb, gm, torch.from_numpy(ids).cuda(), logits, ws)
+    torch.cuda.synchronize()
+    ks, vs = [k for k, _ in caches], [v for _, v in caches]
+    want, _ = oracle.model_step(shape, batch, model, ids, ks, vs)
+    got = logits.cpu().numpy()
+    # logits are fp32 sums over H products of a stream that went through n_layers bf16 roundings on
+    # both sides: the criterion is the relative-L2 bound (1e-2); the largest single deviation among
+    # ~1e5 logits is bounded at six times the RMS deviation that bound allows
+    scale = float(np.sqrt(np.mean(want.astype(np.float64) ** 2)))
+    err, rel = assert_close(got, want, what, max_abs=6e-2 * scale, rel_l2=1e-2)
+    assert (got.argmax(1) == want.argmax(1)).mean() >= 0.9       # next-token choice survives bf16 noise (ties aside)
+    print(f"[parity] {what}: logits max-abs {err:.3e} (scale {scale:.2f}) rel-L2 {rel:.3e}", flush=True)
+    # every layer's cache received the appended rows where the oracle put them
+    slots = rs.relserve_batch_slots(shape, batch)
+    nkv, d = shape.n_kv_heads, shape.head_dim
+    for l in range(n_layers):
+        gk = host_bits(gm["caches"][l][0]).reshape(-1, nkv, d)[slots]
+        wk = ks[l].reshape(-1, nkv, d)[slots]
+        if l == 0:      # same bf16 inputs on both sides: one rounding apart
+            assert_bf16_neighbours(gk, wk, "layer 0 appended k", min_exact=0.15)
+        else:           # the incoming stream already differs by bf16 roundings of earlier layers
+            wf = W.bf16_bits_to_f32(wk)
+            assert_close(W.bf16_bits_to_f32(gk), wf, f"layer {l} appended k",
+                         max_abs=6e-2 * float(np.sqrt(np.mean(wf.astype(np.float64) ** 2))), rel_l2=1e-2)
+
+
+@pytest.mark.parametrize("shape", [W.TINY, W.TINY_GQA, W.TINY_D128], ids=["mha", "gqa", "d128"])
+def test_model_step_tiny(rs, oracle, shape):
+    _model_case(rs, oracle, shape, W.workload_tiny_prefix(shape=shape).batch, 3, 212, 90, False, "model step tiny_prefix")
+    _model_case(rs, oracle, shape, W.workload_tiny(shape=shape).batch, 2, 1000, 91, False, "model step tiny")
+
+
+def test_model_step_13b_two_layer_slice(rs, oracle):
+    """Two layers of the 13B-shaped stack with the 32000-entry vocabulary: 128 decode rows of
+    context 1024 plus a 128-token prefill chunk; checked on sampled requests."""
+    wl = W.workload_decode_plus_chunk_13b(128)
+    reqs = [0, 77, 127, 128]
+    print(f"[case] 2-layer 13B model step, requests {reqs} of {wl.batch.num_reqs}", flush=True)
+    _model_case(rs, oracle, wl.shape, wl.batch.select(reqs), 2, 32000, 92, True, "model step 13B x2")

@@ -240,27 +240,37 @@ __global__ void __launch_bounds__(256) attn_tile_kernel(AttnArgs p) {
     const int32_t* bt = p.block_table + (int64_t)it.bt_req * p.max_blocks;
     const int kc = tid % CH, krow0 = tid / CH;
     uint4 k_reg[K_IT], v_reg[V_IT][2];
+    // Branch-free and in two phases (all block-table entries first, then all K/V rows), so that the
+    // loads of a block are in flight together instead of one dependent pair after the other.  Keys
+    // past the end read the last valid key and are replaced by exact zeros.
+    const int last_key = it.key_end - 1;
     auto slot_of = [&](int key) -> int64_t {
         return ((int64_t)bt[key >> p.page_shift] << p.page_shift) + (key & p.page_mask);
     };
     auto stage_load = [&](int kb0) {
+        int64_t ks[K_IT], vs[V_IT][2];
 #pragma unroll
-        for (int i = 0; i < K_IT; ++i) {
-            const int key = kb0 + krow0 + ROWS_PER_PASS * i;
-            k_reg[i] = make_uint4(0, 0, 0, 0);
-            if (key < it.key_end)
-                k_reg[i] = *reinterpret_cast<const uint4*>(p.k_pages + (slot_of(key) * p.n_kv + kvh) * D + kc * 8);
-        }
+        for (int i = 0; i < K_IT; ++i) ks[i] = slot_of(min(kb0 + krow0 + ROWS_PER_PASS * i, last_key));
 #pragma unroll
-        for (int i = 0; i < V_IT; ++i) {
-            const int key = kb0 + 2 * (krow0 + ROWS_PER_PASS * i);
+        for (int i = 0; i < V_IT; ++i)
 #pragma unroll
-            for (int e = 0; e < 2; ++e) {
-                v_reg[i][e] = make_uint4(0, 0, 0, 0);  // keys past the end contribute exact zeros
-                if (key + e < it.key_end)
-                    v_reg[i][e] = *reinterpret_cast<const uint4*>(p.v_pages + (slot_of(key + e) * p.n_kv + kvh) * D + kc * 8);
-            }
-        }
+            for (int e = 0; e < 2; ++e) vs[i][e] = slot_of(min(kb0 + 2 * (krow0 + ROWS_PER_PASS * i) + e, last_key));
+#pragma unroll
+        for (int i = 0; i < K_IT; ++i)
+            k_reg[i] = *reinterpret_cast<const uint4*>(p.k_pages + (ks[i] * p.n_kv + kvh) * D + kc * 8);
+#pragma unroll
+        for (int i = 0; i < V_IT; ++i)
+#pragma unroll
+            for (int e = 0; e < 2; ++e)
+                v_reg[i][e] = *reinterpret_cast<const uint4*>(p.v_pages + (vs[i][e] * p.n_kv + kvh) * D + kc * 8);
+#pragma unroll
+        for (int i = 0; i < K_IT; ++i)
+            if (kb0 + krow0 + ROWS_PER_PASS * i > last_key) k_reg[i] = make_uint4(0, 0, 0, 0);
+#pragma unroll
+        for (int i = 0; i < V_IT; ++i)
+#pragma unroll
+            for (int e = 0; e < 2; ++e)   // keys past the end contribute exact zeros
+                if (kb0 + 2 * (krow0 + ROWS_PER_PASS * i) + e > last_key) v_reg[i][e] = make_uint4(0, 0, 0, 0);
     };
     auto stage_store = [&](int buf) {
         unsigned char* sk = smem + buf * SM::STAGE;
@@ -367,27 +377,37 @@ __global__ void __launch_bounds__(256) attn_decode_kernel(AttnArgs p) {
     const int32_t* bt = p.block_table + (int64_t)it.bt_req * p.max_blocks;
     const int kc = lane % CH, krow0 = lane / CH;
     uint4 k_reg[K_IT], v_reg[V_IT][2];
+    // Branch-free and in two phases (all block-table entries first, then all K/V rows), so that the
+    // loads of a block are in flight together instead of one dependent pair after the other.  Keys
+    // past the end read the last valid key and are replaced by exact zeros.
+    const int last_key = it.key_end - 1;
     auto slot_of = [&](int key) -> int64_t {
         return ((int64_t)bt[key >> p.page_shift] << p.page_shift) + (key & p.page_mask);
     };
     auto stage_load = [&](int kb0) {
+        int64_t ks[K_IT], vs[V_IT][2];
 #pragma unroll
-        for (int i = 0; i < K_IT; ++i) {
-            const int key = kb0 + krow0 + ROWS_PER_PASS * i;
-            k_reg[i] = make_uint4(0, 0, 0, 0);
-            if (key < it.key_end)
-                k_reg[i] = *reinterpret_cast<const uint4*>(p.k_pages + (slot_of(key) * p.n_kv + kvh) * D + kc * 8);
-        }
+        for (int i = 0; i < K_IT; ++i) ks[i] = slot_of(min(kb0 + krow0 + ROWS_PER_PASS * i, last_key));
 #pragma unroll
-        for (int i = 0; i < V_IT; ++i) {
-            const int key = kb0 + 2 * (krow0 + ROWS_PER_PASS * i);
+        for (int i = 0; i < V_IT; ++i)
 #pragma unroll
-            for (int e = 0; e < 2; ++e) {
-                v_reg[i][e] = make_uint4(0, 0, 0, 0);  // keys past the end contribute exact zeros
-                if (key + e < it.key_end)
-                    v_reg[i][e] = *reinterpret_cast<const uint4*>(p.v_pages + (slot_of(key + e) * p.n_kv + kvh) * D + kc * 8);
-            }
-        }
+            for (int e = 0; e < 2; ++e) vs[i][e] = slot_of(min(kb0 + 2 * (krow0 + ROWS_PER_PASS * i) + e, last_key));
+#pragma unroll
+        for (int i = 0; i < K_IT; ++i)
+            k_reg[i] = *reinterpret_cast<const uint4*>(p.k_pages + (ks[i] * p.n_kv + kvh) * D + kc * 8);
+#pragma unroll
+        for (int i = 0; i < V_IT; ++i)
+#pragma unroll
+            for (int e = 0; e < 2; ++e)
+                v_reg[i][e] = *reinterpret_cast<const uint4*>(p.v_pages + (vs[i][e] * p.n_kv + kvh) * D + kc * 8);
+#pragma unroll
+        for (int i = 0; i < K_IT; ++i)
+            if (kb0 + krow0 + ROWS_PER_PASS * i > last_key) k_reg[i] = make_uint4(0, 0, 0, 0);
+#pragma unroll
+        for (int i = 0; i < V_IT; ++i)
+#pragma unroll
+            for (int e = 0; e < 2; ++e)   // keys past the end contribute exact zeros
+                if (kb0 + 2 * (krow0 + ROWS_PER_PASS * i) + e > last_key) v_reg[i][e] = make_uint4(0, 0, 0, 0);
     };
     // V^T column of key k (0..31): 8 ((k >> 2) & 3) + 4 (k >> 4) + (k & 3), so that lane group gq
     // finds the 8 keys it holds probabilities for (4 gq .. +3 and 16 + 4 gq .. +3) side by side.

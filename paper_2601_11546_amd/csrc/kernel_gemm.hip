@@ -11,6 +11,7 @@
 // row-wise writes and the MFMA operand reads), double buffered with one barrier per k step.
 // Workgroup ids are remapped so that each of the 8 XCDs (own L2 each) walks a contiguous run
 // of tiles, token tiles fastest: concurrent workgroups of an XCD share weight tiles.
+#include <algorithm>
 #include <cstdlib>
 
 #include "device_utils.h"
@@ -37,6 +38,10 @@ struct GemmArgs {
     uint16_t* k_pages;
     uint16_t* v_pages;
     int32_t n_q, n_kv;
+    // split-K (skinny T): workgroup b handles tile b % tiles and k steps [split * k_per_split, ...) of
+    // that tile and adds its partial sums into accum [T, N] fp32 (zero on entry)
+    float* accum;
+    int32_t k_per_split;   // in units of 64; 0 = no split
 };
 
 #ifndef RELSERVE_DMA_BK
@@ -49,7 +54,7 @@ struct GemmArgs {
 // Test hook: route every shape through the register-staged kernel (set from RELSERVE_GEMM_GENERIC=1).
 bool g_force_generic = getenv("RELSERVE_GEMM_GENERIC") != nullptr;
 
-enum { EPI_BF16 = 0, EPI_RES_BF16_OUT_F32 = 1, EPI_RES_F32_OUT_BF16 = 2, EPI_SWIGLU = 3, EPI_QKV_ROPE = 4 };
+enum { EPI_BF16 = 0, EPI_RES_BF16_OUT_F32 = 1, EPI_RES_F32_OUT_BF16 = 2, EPI_SWIGLU = 3, EPI_QKV_ROPE = 4, EPI_ATOMIC = 5 };
 
 __device__ __forceinline__ int remap_xcd(int bid, int num) {
     const int per = num / NUM_XCD, rem = num % NUM_XCD;
@@ -64,11 +69,30 @@ __device__ __forceinline__ void gemm_epilogue(const f32x16_t (&acc)[BN / 64][BM 
                                               int tile_n, int wm, int wn, int l32, int g) {
     constexpr int TM = BM / 64, TN = BN / 64;
     const int t0 = tile_m * BM;
+    if (EPI == EPI_ATOMIC) {
+        // Split-K partial sums.  These tiles were accumulated with the operands swapped: register r
+        // holds token 8 (r / 4) + 4 g + r % 4 and feature l32, so one atomic instruction adds two
+        // runs of 32 consecutive floats.
+#pragma unroll
+        for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+            for (int tn = 0; tn < TN; ++tn) {
+                const int n = tile_n * BN + wn * (BN / 2) + 32 * tn + l32;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int t = t0 + wm * (BM / 2) + 32 * tm + 8 * (r >> 2) + 4 * g + (r & 3);
+                    if (t < p.T && n < p.N) unsafeAtomicAdd(p.accum + (int64_t)t * p.N + n, acc[tn][tm][r]);
+                }
+            }
+        return;
+    }
 #pragma unroll
     for (int tm = 0; tm < TM; ++tm) {
         const int t = t0 + wm * (BM / 2) + 32 * tm + l32;
         if (t >= p.T) continue;
-        if (EPI == EPI_QKV_ROPE) {
+        if (EPI == EPI_ATOMIC) {
+            // handled before this loop (transposed accumulator layout)
+        } else if (EPI == EPI_QKV_ROPE) {
             // The wave owns features [nb, nb + 128): one head (d = 128) or two (d = 64).  The rotation
             // partner of feature i is i + d/2: same lane, same register, D/64 tiles further on.
             constexpr int TPH = (D > 0 ? D : 64) / 32;   // tiles per head
@@ -319,7 +343,9 @@ __global__ void __launch_bounds__(256) gemm_dma_kernel(GemmArgs p) {
     const int wm = wave >> 1, wn = wave & 1;
     const int l32 = lane & 31, g = lane >> 5;
 
-    const int tile = remap_xcd(blockIdx.x, p.tiles_m * p.tiles_n);
+    const int n_tiles = p.tiles_m * p.tiles_n;
+    const int tile = remap_xcd(blockIdx.x % n_tiles, n_tiles);
+    const int split = blockIdx.x / n_tiles;
     const int tile_m = tile % p.tiles_m, tile_n = tile / p.tiles_m;
     const int t0 = tile_m * BM;
     const int K = p.K;
@@ -396,11 +422,13 @@ __global__ void __launch_bounds__(256) gemm_dma_kernel(GemmArgs p) {
         for (int tm = 0; tm < TM; ++tm) af[buf][tm] = as_bf16x8(*reinterpret_cast<const uint4*>(st + a_rd[tm] + ch));
     };
 
-    const int nk = K / BKD;
+    // k range of this workgroup (the whole K unless the launch splits it)
+    const int kbeg = EPI == EPI_ATOMIC ? split * p.k_per_split * (64 / BKD) : 0;
+    const int nk = EPI == EPI_ATOMIC ? min(p.k_per_split * (64 / BKD), K / BKD - kbeg) : K / BKD;
     // prologue: fill the whole ring, wait for stage 0 only
 #pragma unroll
     for (int s = 0; s < NS; ++s)
-        if (s < nk) issue_stage(s, s * BKD);
+        if (s < nk) issue_stage(s, (kbeg + s) * BKD);
     if (nk >= NS)
         asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NS - 1) * LOADS) : "memory");
     else
@@ -430,7 +458,7 @@ __global__ void __launch_bounds__(256) gemm_dma_kernel(GemmArgs p) {
 #endif
                 __syncthreads();
 #ifndef RELSERVE_EXP_NO_DMA
-                if (kt + NS < nk) issue_stage(cur, (kt + NS) * BKD);
+                if (kt + NS < nk) issue_stage(cur, (kbeg + kt + NS) * BKD);
 #endif
                 load_frags((ks + 1) & 1, nxt, 0);
                 // keep this step's MFMAs behind the hand-over: they cover the latency of the reads above
@@ -440,7 +468,8 @@ __global__ void __launch_bounds__(256) gemm_dma_kernel(GemmArgs p) {
             for (int tn = 0; tn < TN; ++tn)
 #pragma unroll
                 for (int tm = 0; tm < TM; ++tm)
-                    acc[tn][tm] = mfma_32x32x16(wf[ks & 1][tn], af[ks & 1][tm], acc[tn][tm]);
+                    acc[tn][tm] = EPI == EPI_ATOMIC ? mfma_32x32x16(af[ks & 1][tm], wf[ks & 1][tn], acc[tn][tm])
+                                                    : mfma_32x32x16(wf[ks & 1][tn], af[ks & 1][tm], acc[tn][tm]);
 #ifdef RELSERVE_EXP_INTERLEAVE
             // spread the fragment reads of the next step between this step's MFMAs
 #pragma unroll
@@ -453,6 +482,146 @@ __global__ void __launch_bounds__(256) gemm_dma_kernel(GemmArgs p) {
         cur = nxt;
     }
     gemm_epilogue<BM, BN, EPI, D>(acc, p, tile_m, tile_n, wm, wn, l32, g);
+}
+
+// ------------------------------------------------------------------------------------------
+// Split-K companion kernels: clear the fp32 accumulator, and turn it into the final output with
+// the same epilogues as the fused path (each thread owns 4 consecutive features of one token and
+// writes zeros back, so the accumulator is clean for the next GEMM of the step).
+// ------------------------------------------------------------------------------------------
+__global__ void fill_zero_kernel(float4* p, int64_t n4) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n4) p[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+}
+
+template <int EPI, int D>
+__global__ void __launch_bounds__(256) gemm_finish_kernel(GemmArgs p) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const float4 zero = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (EPI == EPI_SWIGLU) {
+        const int q_per_row = p.n_half / 4;
+        if (i >= (int64_t)p.T * q_per_row) return;
+        const int t = (int)(i / q_per_row), c = (int)(i % q_per_row) * 4;
+        float4* ga = reinterpret_cast<float4*>(p.accum + (int64_t)t * p.N + c);
+        float4* ua = reinterpret_cast<float4*>(p.accum + (int64_t)t * p.N + p.n_half + c);
+        const float4 gt = *ga, up = *ua;
+        *ga = zero;
+        *ua = zero;
+        const float o0 = gt.x / (1.0f + __expf(-gt.x)) * up.x, o1 = gt.y / (1.0f + __expf(-gt.y)) * up.y;
+        const float o2 = gt.z / (1.0f + __expf(-gt.z)) * up.z, o3 = gt.w / (1.0f + __expf(-gt.w)) * up.w;
+        *reinterpret_cast<uint2*>(static_cast<uint16_t*>(p.out) + (int64_t)t * p.n_half + c) =
+            make_uint2(pack_bf16x2(o0, o1), pack_bf16x2(o2, o3));
+    } else if (EPI == EPI_QKV_ROPE) {
+        // units per token: rotated heads need (lo, hi) quads: (n_q + n_kv) * D / 8; v heads: n_kv * D / 4
+        constexpr int HALF = (D > 0 ? D : 64) / 2;
+        const int rot_units = (p.n_q + p.n_kv) * (HALF / 4), v_units = p.n_kv * (2 * HALF / 4);
+        const int units = rot_units + v_units;
+        if (i >= (int64_t)p.T * units) return;
+        const int t = (int)(i / units), u = (int)(i % units);
+        const int64_t slot = p.tok_slot[t];
+        const int kv_dim = p.n_kv * 2 * HALF;
+        float* row = p.accum + (int64_t)t * p.N;
+        if (u < rot_units) {
+            const int head = u / (HALF / 4), i0 = (u % (HALF / 4)) * 4;
+            float4* lp = reinterpret_cast<float4*>(row + head * 2 * HALF + i0);
+            float4* hp = reinterpret_cast<float4*>(row + head * 2 * HALF + HALF + i0);
+            const float4 lo = *lp, hi = *hp;
+            *lp = zero;
+            *hp = zero;
+            const float2* cs = p.rope_cs + (int64_t)t * HALF + i0;
+            const float4 c01 = *reinterpret_cast<const float4*>(cs), c23 = *reinterpret_cast<const float4*>(cs + 2);
+            const float a[4] = {lo.x, lo.y, lo.z, lo.w}, b[4] = {hi.x, hi.y, hi.z, hi.w};
+            const float co[4] = {c01.x, c01.z, c23.x, c23.z}, si[4] = {c01.y, c01.w, c23.y, c23.w};
+            float l2[4], h2[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                l2[j] = a[j] * co[j] - b[j] * si[j];
+                h2[j] = a[j] * si[j] + b[j] * co[j];
+            }
+            uint16_t* dst = head < p.n_q ? static_cast<uint16_t*>(p.out) + (int64_t)t * (p.n_q * 2 * HALF) + head * 2 * HALF
+                                         : p.k_pages + slot * kv_dim + (head - p.n_q) * 2 * HALF;
+            *reinterpret_cast<uint2*>(dst + i0) = make_uint2(pack_bf16x2(l2[0], l2[1]), pack_bf16x2(l2[2], l2[3]));
+            *reinterpret_cast<uint2*>(dst + HALF + i0) = make_uint2(pack_bf16x2(h2[0], h2[1]), pack_bf16x2(h2[2], h2[3]));
+        } else {
+            const int c = (u - rot_units) * 4;
+            float4* vp = reinterpret_cast<float4*>(row + (p.n_q + p.n_kv) * 2 * HALF + c);
+            const float4 v = *vp;
+            *vp = zero;
+            *reinterpret_cast<uint2*>(p.v_pages + slot * kv_dim + c) = make_uint2(pack_bf16x2(v.x, v.y), pack_bf16x2(v.z, v.w));
+        }
+    } else {
+        const int q_per_row = p.N / 4;
+        if (i >= (int64_t)p.T * q_per_row) return;
+        const int64_t o = i * 4;
+        float4* ap = reinterpret_cast<float4*>(p.accum + o);
+        float4 v = *ap;
+        *ap = zero;
+        if (EPI == EPI_RES_BF16_OUT_F32) {
+            if (p.residual) {
+                const uint2 r = *reinterpret_cast<const uint2*>(static_cast<const uint16_t*>(p.residual) + o);
+                v.x += bf16_lo(r.x); v.y += bf16_hi(r.x); v.z += bf16_lo(r.y); v.w += bf16_hi(r.y);
+            }
+            *reinterpret_cast<float4*>(static_cast<float*>(p.out) + o) = v;
+        } else {
+            if (EPI == EPI_RES_F32_OUT_BF16) {
+                const float4 r = *reinterpret_cast<const float4*>(static_cast<const float*>(p.residual) + o);
+                v.x += r.x; v.y += r.y; v.z += r.z; v.w += r.w;
+            }
+            *reinterpret_cast<uint2*>(static_cast<uint16_t*>(p.out) + o) = make_uint2(pack_bf16x2(v.x, v.y), pack_bf16x2(v.z, v.w));
+        }
+    }
+}
+
+// Skinny path: T <= 256.  The weights are streamed once; to fill 256 CUs the k range of every
+// 128 x 256 (or 64 x 256) tile is split over several workgroups.  3-stage LDS ring: two stages of
+// weights (2 x 32 KB) are in flight per CU.
+template <int BM, int EPI, int D>
+hipError_t launch_split(GemmArgs p, int splits, hipStream_t s) {
+    constexpr int BN = 256, NS = 3;
+    constexpr int smem = NS * (BM + BN) * 64 * 2;
+    static bool attr_done = false;
+    if (!attr_done) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_dma_kernel<BM, BN, EPI_ATOMIC, 0, 64, NS>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+        if (e != hipSuccess) return e;
+        attr_done = true;
+    }
+    p.tiles_m = (p.T + BM - 1) / BM;
+    p.tiles_n = (p.N + BN - 1) / BN;
+    const int nk = p.K / 64;
+    p.k_per_split = (nk + splits - 1) / splits;
+    splits = (nk + p.k_per_split - 1) / p.k_per_split;   // no empty split
+    gemm_dma_kernel<BM, BN, EPI_ATOMIC, 0, 64, NS><<<dim3(p.tiles_m * p.tiles_n * splits), dim3(256), smem, s>>>(p);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    int64_t units;
+    if (EPI == EPI_SWIGLU)
+        units = (int64_t)p.T * (p.n_half / 4);
+    else if (EPI == EPI_QKV_ROPE)
+        units = (int64_t)p.T * ((p.n_q + p.n_kv) * (D / 8) + p.n_kv * (D / 4));
+    else
+        units = (int64_t)p.T * (p.N / 4);
+    gemm_finish_kernel<EPI, D><<<dim3((unsigned)((units + 255) / 256)), dim3(256), 0, s>>>(p);
+    return hipGetLastError();
+}
+
+// Number of k splits for a skinny GEMM: enough workgroups for every CU, at least 4 k steps each.
+int choose_splits(int T, int N, int K, int BM) {
+    const int tiles = ((T + BM - 1) / BM) * ((N + 255) / 256);
+    const int nk = K / 64;
+    int splits = 256 / tiles;   // one workgroup per CU (144 KB of LDS each): a single full round
+    splits = std::min(splits, std::max(1, nk / 4));
+    return std::max(1, splits);
+}
+
+template <int EPI, int D>
+hipError_t launch_skinny(const GemmArgs& p, hipStream_t s) {
+    if (p.T <= 64) return launch_split<64, EPI, D>(p, choose_splits(p.T, p.N, p.K, 64), s);
+    return launch_split<128, EPI, D>(p, choose_splits(p.T, p.N, p.K, 128), s);
+}
+
+bool skinny_applies(int T, int N, int K, const float* accum) {
+    return accum != nullptr && T <= 256 && K % 64 == 0 && N % 4 == 0 && !g_force_generic;
 }
 
 template <int BM, int BN, int EPI, int D = 0>
@@ -496,8 +665,15 @@ hipError_t launch_epi(const GemmArgs& p, hipStream_t s) {
 
 }  // namespace
 
+hipError_t launch_fill_zero(float* ptr, int64_t n_floats, hipStream_t s) {
+    const int64_t n4 = (n_floats + 3) / 4;
+    if (n4 == 0) return hipSuccess;
+    fill_zero_kernel<<<dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, s>>>(reinterpret_cast<float4*>(ptr), n4);
+    return hipGetLastError();
+}
+
 hipError_t launch_linear(const void* a, const void* w, int32_t T, int32_t N, int32_t K, int32_t epilogue,
-                         const void* residual, void* out, hipStream_t s) {
+                         const void* residual, void* out, hipStream_t s, float* accum) {
     if (T == 0) return hipSuccess;
     if ((int64_t)T * K >= ((int64_t)1 << 31) || (int64_t)N * K >= ((int64_t)1 << 31)) return hipErrorInvalidValue;
     if (epilogue != EPI_SWIGLU && (N % 4)) return hipErrorInvalidValue;
@@ -511,6 +687,16 @@ hipError_t launch_linear(const void* a, const void* w, int32_t T, int32_t N, int
     p.N = N;
     p.K = K;
     p.n_half = N / 2;
+    p.accum = accum;
+    if (skinny_applies(T, N, K, accum)) {
+        switch (epilogue) {
+            case EPI_BF16: return launch_skinny<EPI_BF16, 0>(p, s);
+            case EPI_RES_BF16_OUT_F32: return launch_skinny<EPI_RES_BF16_OUT_F32, 0>(p, s);
+            case EPI_RES_F32_OUT_BF16: return launch_skinny<EPI_RES_F32_OUT_BF16, 0>(p, s);
+            case EPI_SWIGLU: return launch_skinny<EPI_SWIGLU, 0>(p, s);
+            default: return hipErrorInvalidValue;
+        }
+    }
     switch (epilogue) {
         case EPI_BF16: return launch_epi<EPI_BF16>(p, s);
         case EPI_RES_BF16_OUT_F32: return launch_epi<EPI_RES_BF16_OUT_F32>(p, s);
@@ -531,7 +717,7 @@ hipError_t launch_qkv_d(const GemmArgs& p, hipStream_t s) {
 }  // namespace
 
 hipError_t launch_qkv_rope_append(const BatchDev& b, const relserve_layer& L, const void* h, const void* w_qkv,
-                                  void* q_out, void* k_pages, void* v_pages, hipStream_t s) {
+                                  void* q_out, void* k_pages, void* v_pages, hipStream_t s, float* accum) {
     if (b.T == 0) return hipSuccess;
     const int32_t K = L.cfg.hidden;
     if ((int64_t)b.T * K >= ((int64_t)1 << 31) || (int64_t)L.qkv_dim * K >= ((int64_t)1 << 31))
@@ -549,6 +735,9 @@ hipError_t launch_qkv_rope_append(const BatchDev& b, const relserve_layer& L, co
     p.v_pages = static_cast<uint16_t*>(v_pages);
     p.n_q = L.cfg.n_q_heads;
     p.n_kv = L.cfg.n_kv_heads;
+    p.accum = accum;
+    if (skinny_applies(p.T, p.N, p.K, accum))
+        return L.cfg.head_dim == 128 ? launch_skinny<EPI_QKV_ROPE, 128>(p, s) : launch_skinny<EPI_QKV_ROPE, 64>(p, s);
     return L.cfg.head_dim == 128 ? launch_qkv_d<128>(p, s) : launch_qkv_d<64>(p, s);
 }
 

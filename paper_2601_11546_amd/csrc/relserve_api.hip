@@ -27,6 +27,8 @@ struct Workspace {
     char* act;       // [T, I] bf16
     float* part_o;   // [T, n_q, d] fp32
     float* part_ml;  // [T, n_q, 2] fp32
+    float* accum;    // [min(T, 256), widest GEMM output] fp32 split-K accumulator
+    size_t accum_floats;
     size_t total;
 };
 
@@ -46,6 +48,8 @@ Workspace carve(const relserve_layer& L, int64_t T, void* base) {
     w.act = take((size_t)T * c.mlp_dim * 2);
     w.part_o = reinterpret_cast<float*>(take((size_t)T * L.q_dim * 4));
     w.part_ml = reinterpret_cast<float*>(take((size_t)T * c.n_q_heads * 2 * 4));
+    w.accum_floats = (size_t)std::min<int64_t>(T, SKINNY_MAX_T) * std::max({L.qkv_dim, 2 * c.mlp_dim, c.hidden});
+    w.accum = reinterpret_cast<float*>(take(w.accum_floats * 4));
     w.total = off;
     return w;
 }
@@ -510,17 +514,20 @@ int32_t relserve_layer_step(const relserve_layer* L, const relserve_batch* b, co
         e = launch();
         profile_mark(prof, slot, s, false);
     };
+    // skinny batches split K across workgroups through a zeroed fp32 accumulator (each GEMM leaves it zero)
+    float* accum = T <= SKINNY_MAX_T ? w.accum : nullptr;
+    if (accum) e = launch_fill_zero(accum, (int64_t)w.accum_floats, s);
     run(S_NORM1, [&] { return launch_rmsnorm(x, false, wt->w_in_norm, c.rms_eps, T, c.hidden, w.h, s); });
     run(S_QKV, [&] {
-        return launch_qkv_rope_append(b->dev, *L, w.h, wt->w_qkv, w.q, cache.k_pages, cache.v_pages, s);
+        return launch_qkv_rope_append(b->dev, *L, w.h, wt->w_qkv, w.q, cache.k_pages, cache.v_pages, s, accum);
     });
     if (e == hipSuccess)
         e = launch_attention(b->dev, *L, w.q, L->q_dim, cache.k_pages, cache.v_pages, w.attn, w.part_o,
                              w.part_ml, s, prof);
-    run(S_O, [&] { return launch_linear(w.attn, wt->w_o, T, c.hidden, L->q_dim, 1, x, w.x1, s); });
+    run(S_O, [&] { return launch_linear(w.attn, wt->w_o, T, c.hidden, L->q_dim, 1, x, w.x1, s, accum); });
     run(S_NORM2, [&] { return launch_rmsnorm(w.x1, true, wt->w_post_norm, c.rms_eps, T, c.hidden, w.h, s); });
-    run(S_GU, [&] { return launch_linear(w.h, wt->w_gate_up, T, 2 * c.mlp_dim, c.hidden, 3, nullptr, w.act, s); });
-    run(S_DOWN, [&] { return launch_linear(w.act, wt->w_down, T, c.hidden, c.mlp_dim, 2, w.x1, y, s); });
+    run(S_GU, [&] { return launch_linear(w.h, wt->w_gate_up, T, 2 * c.mlp_dim, c.hidden, 3, nullptr, w.act, s, accum); });
+    run(S_DOWN, [&] { return launch_linear(w.act, wt->w_down, T, c.hidden, c.mlp_dim, 2, w.x1, y, s, accum); });
     return e == hipSuccess ? RELSERVE_OK : RELSERVE_ERR_HIP;
 }
 

@@ -85,6 +85,7 @@ int32_t expand_batch(const relserve_layer_config& cfg, const relserve_batch_desc
 
 // Rows of queries one attention workgroup covers (4 waves x 32 MFMA columns).
 constexpr int ATTN_BLOCK_M = 128;
+constexpr int SKINNY_MAX_T = 256;      // batches up to this many tokens take the split-K GEMM path
 constexpr int ATTN_SPLIT_ROWS = 16;   // query heads per kv head the decode kernel's 16-column MFMA holds
 
 // ---- kernel launchers (each enqueues on `s` and returns the launch status) ----------------
@@ -98,11 +99,14 @@ hipError_t launch_kv_append(const BatchDev& b, const void* k, const void* v, voi
                             int32_t row_elems, hipStream_t s);
 hipError_t launch_rope_append(const BatchDev& b, const relserve_layer& L, void* qkv, void* k_pages,
                               void* v_pages, hipStream_t s);
+// accum: optional fp32 [T, N] scratch holding zeros; lets skinny problems (T <= 256) split K over
+// workgroups.  It holds zeros again when the launched kernels have finished.
 hipError_t launch_linear(const void* a, const void* w, int32_t T, int32_t N, int32_t K, int32_t epilogue,
-                         const void* residual, void* out, hipStream_t s);
+                         const void* residual, void* out, hipStream_t s, float* accum = nullptr);
+hipError_t launch_fill_zero(float* ptr, int64_t n_floats, hipStream_t s);
 // q/k/v projection with rotary embedding and KV append fused into the epilogue: q_out [T, n_q d] bf16.
 hipError_t launch_qkv_rope_append(const BatchDev& b, const relserve_layer& L, const void* h, const void* w_qkv,
-                                  void* q_out, void* k_pages, void* v_pages, hipStream_t s);
+                                  void* q_out, void* k_pages, void* v_pages, hipStream_t s, float* accum = nullptr);
 // Attention passes; part_o [T, n_q, d] fp32 and part_ml [T, n_q, 2] fp32 hold the prefix partials.
 hipError_t launch_attention(const BatchDev& b, const relserve_layer& L, const void* q, int32_t q_pitch,
                             const void* k_pages, const void* v_pages, void* out, float* part_o,

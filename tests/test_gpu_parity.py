@@ -336,6 +336,17 @@ def test_full_size_prefill_only_13b(rs, oracle):
     _sampled_parity(rs, oracle, wl, [0, 31, 63], max_prefill_rows=40)
 
 
+def test_full_size_decode_only_70b(rs, oracle):
+    """T = 256 decode rows: the weight-streaming (split-K) GEMM path and the decode attention kernel."""
+    wl = W.workload_decode_heavy_70b(with_chunk=False)
+    _sampled_parity(rs, oracle, wl, [0, 1, 63, 64, 100, 128, 191, 192, 254, 255])
+
+
+def test_full_size_decode_only_13b(rs, oracle):
+    wl = W.workload_decode_plus_chunk_13b(0)
+    _sampled_parity(rs, oracle, wl, [0, 5, 64, 127])
+
+
 def test_full_size_decode_plus_chunk_13b(rs, oracle):
     wl = W.workload_decode_plus_chunk_13b(512)
     _sampled_parity(rs, oracle, wl, [0, 127, 128], max_prefill_rows=24)

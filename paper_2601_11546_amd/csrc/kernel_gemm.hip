@@ -577,7 +577,7 @@ __global__ void __launch_bounds__(256) gemm_finish_kernel(GemmArgs p) {
 // weights (2 x 32 KB) are in flight per CU.
 template <int BM, int EPI, int D>
 hipError_t launch_split(GemmArgs p, int splits, hipStream_t s) {
-    constexpr int BN = 256, NS = 3;
+    constexpr int BN = 256, NS = BM == 64 ? 4 : 3;     // 160 KB / 144 KB of LDS: one workgroup per CU
     constexpr int smem = NS * (BM + BN) * 64 * 2;
     static bool attr_done = false;
     if (!attr_done) {

@@ -347,6 +347,22 @@ def test_full_size_decode_only_13b(rs, oracle):
     _sampled_parity(rs, oracle, wl, [0, 5, 64, 127])
 
 
+def test_skinny_batches_of_every_token_tile_count(rs, oracle):
+    """1, 20, 33, 64, 65 and 128 decode tokens: every token-tile count of the weight-streaming GEMM,
+    on a layer wide enough for several feature tiles and k splits."""
+    shape = W.LayerShape(1024, 8, 2, 128, 2048)
+    weights = W.make_weights(shape, 7)
+    for n in (1, 20, 33, 64, 65, 128):
+        rng = np.random.default_rng(n)
+        b = W.build_batch(shape, np.ones(n, np.int64), rng.integers(1, 200, n), seed=n)
+        x = W.make_activations(b.T, shape.hidden, n)
+        kp, vp = W.make_cache(shape, b.num_pages, n)
+        gl = GpuLayer(rs, shape, weights, kp, vp, b.T)
+        y = host_f32(gl.step(b, x))
+        res = oracle.layer_step(shape, b, weights, x, kp, vp)
+        assert_close(y, res.y_f32, f"{n} decode tokens")
+
+
 def test_full_size_decode_plus_chunk_13b(rs, oracle):
     wl = W.workload_decode_plus_chunk_13b(512)
     _sampled_parity(rs, oracle, wl, [0, 127, 128], max_prefill_rows=24)
@@ -381,7 +397,10 @@ def _model_case(rs, oracle, shape, batch, n_layers, vocab, seed, scaled, what):
     # ~1e5 logits is bounded at six times the RMS deviation that bound allows
     scale = float(np.sqrt(np.mean(want.astype(np.float64) ** 2)))
     err, rel = assert_close(got, want, what, max_abs=6e-2 * scale, rel_l2=1e-2)
-    assert (got.argmax(1) == want.argmax(1)).mean() >= 0.9       # next-token choice survives bf16 noise (ties aside)
+    # the next-token choice must agree wherever the oracle's lead over the runner-up exceeds the deviation
+    top2 = np.sort(want, axis=1)[:, -2:]
+    clear = (top2[:, 1] - top2[:, 0]) > 2 * err
+    assert (got.argmax(1)[clear] == want.argmax(1)[clear]).all()
     print(f"[parity] {what}: logits max-abs {err:.3e} (scale {scale:.2f}) rel-L2 {rel:.3e}", flush=True)
     # every layer's cache received the appended rows where the oracle put them
     slots = rs.relserve_batch_slots(shape, batch)

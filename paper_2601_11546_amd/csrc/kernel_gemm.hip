@@ -650,17 +650,43 @@ hipError_t launch_cfg(const GemmArgs& base, hipStream_t s) {
     return hipGetLastError();
 }
 
+// Tile choice.  A launch runs ceil(tiles / resident workgroups) rounds; the cost of a round is the
+// tile's MFMA work divided by the tile shape's measured in-tile efficiency (relative to 256 x 256).
+// The candidate with the lowest estimated cost wins: this trades tile quantisation in T (padding
+// to BM), the tail round, and the per-tile efficiency against each other.
+struct TileCand { int bm, bn, wg_per_cu; float eff; };
+constexpr TileCand kTiles[] = {
+    // efficiencies calibrated on T = 1282 / 6144 problems of the 13B and 70B layer shapes
+    {256, 256, 1, 1.00f}, {192, 256, 1, 0.92f}, {128, 256, 1, 0.78f}, {128, 128, 2, 0.87f}, {64, 128, 3, 0.75f}};
+
+int choose_tile(int T, int64_t n_eff, bool need_bn256) {
+    static const char* force = getenv("RELSERVE_GEMM_TILE");   // test hook: index into kTiles
+    if (force) return atoi(force);
+    int best = 0;
+    double best_cost = 1e300;
+    for (int i = 0; i < (int)(sizeof(kTiles) / sizeof(kTiles[0])); ++i) {
+        const TileCand& c = kTiles[i];
+        if (need_bn256 && c.bn != 256) continue;
+        const int64_t tiles = ((T + c.bm - 1) / c.bm) * ((n_eff + c.bn - 1) / c.bn);
+        const int64_t slots = 256 * c.wg_per_cu;
+        const double rounds = (double)((tiles + slots - 1) / slots);
+        // resident workgroups of a CU share its MFMA pipes: a round of wg_per_cu tiles costs wg_per_cu tile times
+        const double cost = rounds * c.wg_per_cu * (double)c.bm * c.bn / c.eff;
+        if (cost < best_cost) best_cost = cost, best = i;
+    }
+    return best;
+}
+
 template <int EPI>
 hipError_t launch_epi(const GemmArgs& p, hipStream_t s) {
-    // Tile choice: the largest tile that still leaves at least ~2 workgroups per CU; small
-    // problems fall back to 128 x 128 so the chip is not left idle by tile quantisation.
     const int64_t n_eff = EPI == EPI_SWIGLU ? 2 * (int64_t)p.n_half : p.N;
-    const int64_t big = ((p.T + 255) / 256) * ((n_eff + 255) / 256);
-    if (big >= 512) return launch_cfg<256, 256, EPI>(p, s);
-    const int64_t mid = ((p.T + 127) / 128) * ((n_eff + 255) / 256);
-    if (mid >= 384) return launch_cfg<128, 256, EPI>(p, s);
-    if (p.T > 64) return launch_cfg<128, 128, EPI>(p, s);
-    return launch_cfg<64, 128, EPI>(p, s);
+    switch (choose_tile(p.T, n_eff, false)) {
+        case 0: return launch_cfg<256, 256, EPI>(p, s);
+        case 1: return launch_cfg<192, 256, EPI>(p, s);
+        case 2: return launch_cfg<128, 256, EPI>(p, s);
+        case 3: return launch_cfg<128, 128, EPI>(p, s);
+        default: return launch_cfg<64, 128, EPI>(p, s);
+    }
 }
 
 }  // namespace
@@ -709,10 +735,12 @@ hipError_t launch_linear(const void* a, const void* w, int32_t T, int32_t N, int
 namespace {
 template <int D>
 hipError_t launch_qkv_d(const GemmArgs& p, hipStream_t s) {
-    const int64_t big = ((p.T + 255) / 256) * ((p.N + 255) / 256);
-    if (big >= 512) return launch_cfg<256, 256, EPI_QKV_ROPE, D>(p, s);
-    if (p.T > 64) return launch_cfg<128, 256, EPI_QKV_ROPE, D>(p, s);
-    return launch_cfg<64, 256, EPI_QKV_ROPE, D>(p, s);
+    if (p.T <= 64) return launch_cfg<64, 256, EPI_QKV_ROPE, D>(p, s);
+    switch (choose_tile(p.T, p.N, true)) {   // the rotation needs 128 features per wave: BN = 256 only
+        case 0: return launch_cfg<256, 256, EPI_QKV_ROPE, D>(p, s);
+        case 1: return launch_cfg<192, 256, EPI_QKV_ROPE, D>(p, s);
+        default: return launch_cfg<128, 256, EPI_QKV_ROPE, D>(p, s);
+    }
 }
 }  // namespace
 

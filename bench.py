@@ -107,6 +107,8 @@ def main() -> None:
     ap.add_argument("--workload", default="relquery_13b")
     ap.add_argument("--layer-sets", type=int, default=0, help="independent (weights, cache) sets to rotate over (0 = auto)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also run a plain 1 GiB device copy (reference for rocprofv3's FETCH_SIZE / WRITE_SIZE)")
     ap.add_argument("--cpu-tokens", type=int, default=0, help="token budget of the oracle sample (0 = auto)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -155,6 +157,13 @@ def main() -> None:
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
+    if args.calibration_copy:     # a kernel of known traffic: reads 1 GiB, writes 1 GiB
+        src = torch.ones(1 << 29, dtype=torch.bfloat16, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     # timed region: exactly K steps, HIP events around every kernel on the launch stream
     rs.relserve_profile_enable(layer, True)
     torch.cuda.synchronize()

@@ -441,25 +441,17 @@ __global__ void __launch_bounds__(256) gemm_dma_kernel(GemmArgs p) {
 #pragma unroll
         for (int ks = 0; ks < KSTEPS; ++ks) {
             if (ks + 1 < KSTEPS) {
-#ifndef RELSERVE_EXP_NO_LDS
                 load_frags((ks + 1) & 1, cur, ks + 1);
-#endif
             } else if (kt + 1 < nk) {
                 // Every fragment of this stage is in registers.  Wait for the next stage (the NS - 2
                 // younger ones may stay in flight), hand over, refill this stage's buffer with the
                 // stage NS iterations ahead, and start reading the next stage.
-#ifdef RELSERVE_EXP_NO_VMWAIT   // timing experiment only: results are wrong, every access stays in bounds
-                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-#else
                 if (kt + NS - 1 < nk)
                     asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"((NS - 2) * LOADS) : "memory");
                 else
                     asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
-#endif
                 __syncthreads();
-#ifndef RELSERVE_EXP_NO_DMA
                 if (kt + NS < nk) issue_stage(cur, (kbeg + kt + NS) * BKD);
-#endif
                 load_frags((ks + 1) & 1, nxt, 0);
                 // keep this step's MFMAs behind the hand-over: they cover the latency of the reads above
                 __builtin_amdgcn_sched_barrier(0);
@@ -470,14 +462,6 @@ __global__ void __launch_bounds__(256) gemm_dma_kernel(GemmArgs p) {
                 for (int tm = 0; tm < TM; ++tm)
                     acc[tn][tm] = EPI == EPI_ATOMIC ? mfma_32x32x16(af[ks & 1][tm], wf[ks & 1][tn], acc[tn][tm])
                                                     : mfma_32x32x16(wf[ks & 1][tn], af[ks & 1][tm], acc[tn][tm]);
-#ifdef RELSERVE_EXP_INTERLEAVE
-            // spread the fragment reads of the next step between this step's MFMAs
-#pragma unroll
-            for (int i = 0; i < TN + TM; ++i) {
-                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                     // one LDS read
-                __builtin_amdgcn_sched_group_barrier(0x008, TN * TM / (TN + TM), 0);   // a share of the MFMAs
-            }
-#endif
         }
         cur = nxt;
     }

@@ -106,7 +106,9 @@ __device__ __forceinline__ void state_store(const RowState<D>& st, const AttnArg
 // One 32-key tile: S^T = K Q^T, mask, online softmax update, O^T += V^T P^T.
 //   sk : the tile's 32 key rows in LDS, K_STRIDE bytes apart, d contiguous
 //   sv : V^T in LDS, row d at sv + d * V_STRIDE; the tile's keys start at 16-byte column group
-//        cg0; group index is XORed with (d >> 3) & SW; inside each 16 keys the columns are
+//        cg0; group index is XORed with (d >> 4) & SW (constant over the 16 rows that 16 lanes read
+//        together, so the reads of the 64-bank LDS stay conflict free while the transposing writes
+//        of 16 lanes that hold 16 different d-chunks spread over all banks); inside each 16 keys the columns are
 //        stored with key bits 2 and 3 swapped (matches the accumulator layout of S^T)
 template <int D, int K_STRIDE, int V_STRIDE, int SW>
 __device__ __forceinline__ void attn_tile32(RowState<D>& st, const bf16x8_t (&qf)[D / 16], const unsigned char* sk,
@@ -158,7 +160,7 @@ __device__ __forceinline__ void attn_tile32(RowState<D>& st, const bf16x8_t (&qf
     for (int td = 0; td < D / 32; ++td) {
         const int d = 32 * td + l32;
         const unsigned char* vrow = sv + d * V_STRIDE;
-        const int sw = (d >> 3) & SW;
+        const int sw = (d >> 4) & SW;
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
             const bf16x8_t vf = as_bf16x8(*reinterpret_cast<const uint4*>(vrow + ((cg0 + 2 * h + g) ^ sw) * 16));
@@ -171,7 +173,7 @@ __device__ __forceinline__ void attn_tile32(RowState<D>& st, const bf16x8_t (&qf
 template <int V_STRIDE, int SW>
 __device__ __forceinline__ void store_vt_pair(unsigned char* sv, int kc, int pi, uint4 ve, uint4 vo) {
     const int kp = (pi & ~6) | ((pi & 2) << 1) | ((pi & 4) >> 1);  // swap key bits 2 and 3
-    const int col = (((kp >> 2) ^ (kc & SW)) << 2) | (kp & 3);     // dword column, swizzled
+    const int col = (((kp >> 2) ^ ((kc >> 1) & SW)) << 2) | (kp & 3);     // dword column, swizzled (d >> 4 = kc >> 1)
     const uint32_t e[4] = {ve.x, ve.y, ve.z, ve.w}, o[4] = {vo.x, vo.y, vo.z, vo.w};
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
@@ -419,7 +421,7 @@ __global__ void __launch_bounds__(256) attn_decode_kernel(AttnArgs p) {
         for (int i = 0; i < V_IT; ++i) {
             const int pi = krow0 + ROWS_PER_PASS * i;                              // key pair 0..15
             const int kp = (((pi >> 1) & 3) << 2) | ((pi >> 3) << 1) | (pi & 1);   // dword column before swizzle
-            const int col = (((kp >> 2) ^ (kc & 3)) << 2) | (kp & 3);
+            const int col = (((kp >> 2) ^ ((kc >> 1) & 3)) << 2) | (kp & 3);
             const uint32_t e[4] = {v_reg[i][0].x, v_reg[i][0].y, v_reg[i][0].z, v_reg[i][0].w};
             const uint32_t o[4] = {v_reg[i][1].x, v_reg[i][1].y, v_reg[i][1].z, v_reg[i][1].w};
 #pragma unroll
@@ -497,7 +499,7 @@ __global__ void __launch_bounds__(256) attn_decode_kernel(AttnArgs p) {
         for (int td = 0; td < TD; ++td) {
             const int d = 16 * td + l16;
             const bf16x8_t vf = as_bf16x8(*reinterpret_cast<const uint4*>(
-                sv + d * SM::V_STRIDE + ((gq ^ ((d >> 3) & 3)) << 4)));
+                sv + d * SM::V_STRIDE + ((gq ^ ((d >> 4) & 3)) << 4)));
             o_acc[td] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pf, o_acc[td], 0, 0, 0);
         }
     }

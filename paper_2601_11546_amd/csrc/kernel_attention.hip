@@ -6,10 +6,10 @@
 // MFMA row index, query rows on the column index): a lane then owns ONE query row
 // (lane % 32) and 16 of each 32 keys, so the row max / row sum are in-register reductions
 // plus one exchange with lane ^ 32, and the probabilities are already laid out as the B
-// operand of O^T = V^T P^T.  V is transposed on its way into LDS (two keys packed per 32-bit
-// write, 16-byte column groups XOR-swizzled so that the MFMA operand reads are conflict free).
+// operand of O^T = V^T P^T.  The tiled kernel keeps V row-major in LDS and transposes it in the
+// LDS read (ds_read_b64_tr_b16); the decode kernel transposes V on its way into LDS.
 //
-// Two kernels share the per-tile arithmetic:
+// Two kernels:
 //   attn_tile_kernel   one workgroup = up to 128 rows x one kv head; the four waves own 32
 //                      rows each and share K/V blocks of 64 keys staged by all 256 threads.
 //                      Used for the joint shared-prefix pass (rows = every query token of the
@@ -103,112 +103,53 @@ __device__ __forceinline__ void state_store(const RowState<D>& st, const AttnArg
     }
 }
 
-// One 32-key tile: S^T = K Q^T, mask, online softmax update, O^T += V^T P^T.
-//   sk : the tile's 32 key rows in LDS, K_STRIDE bytes apart, d contiguous
-//   sv : V^T in LDS, row d at sv + d * V_STRIDE; the tile's keys start at 16-byte column group
-//        cg0; group index is XORed with (d >> 4) & SW (constant over the 16 rows that 16 lanes read
-//        together, so the reads of the 64-bank LDS stay conflict free while the transposing writes
-//        of 16 lanes that hold 16 different d-chunks spread over all banks); inside each 16 keys the columns are
-//        stored with key bits 2 and 3 swapped (matches the accumulator layout of S^T)
-template <int D, int K_STRIDE, int V_STRIDE, int SW>
-__device__ __forceinline__ void attn_tile32(RowState<D>& st, const bf16x8_t (&qf)[D / 16], const unsigned char* sk,
-                                            const unsigned char* sv, int cg0, int key0, int klim, bool need_mask,
-                                            float scale_log2, int l32, int g) {
-    f32x16_t s;
-#pragma unroll
-    for (int r = 0; r < 16; ++r) s[r] = 0.f;
-#pragma unroll
-    for (int ks = 0; ks < D / 16; ++ks) {
-        const bf16x8_t kf = as_bf16x8(*reinterpret_cast<const uint4*>(sk + l32 * K_STRIDE + (2 * ks + g) * 16));
-        s = mfma_32x32x16(kf, qf[ks], s);
-    }
-    float mx = -INFINITY;
-#pragma unroll
-    for (int r = 0; r < 16; ++r) {
-        float v = s[r] * scale_log2;
-        if (need_mask && key0 + 8 * (r >> 2) + 4 * g + (r & 3) >= klim) v = -INFINITY;
-        s[r] = v;
-        mx = fmaxf(mx, v);
-    }
-    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-    const float m_new = fmaxf(st.m, mx);
-    const float m_use = m_new == -INFINITY ? 0.f : m_new;  // a row that has seen no key yet
-    const float alpha = __builtin_amdgcn_exp2f(st.m - m_use);
-    st.m = m_new;
-    float psum = 0.f;
-    bf16x8_t pf[2];
-#pragma unroll
-    for (int h = 0; h < 2; ++h) {
-        uint32_t w[4];
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const float p0 = __builtin_amdgcn_exp2f(s[8 * h + 2 * j] - m_use);
-            const float p1 = __builtin_amdgcn_exp2f(s[8 * h + 2 * j + 1] - m_use);
-            psum += p0 + p1;
-            w[j] = pack_bf16x2(p0, p1);
-        }
-        pf[h] = as_bf16x8(make_uint4(w[0], w[1], w[2], w[3]));
-    }
-    st.l = st.l * alpha + psum;
-    if (__any(alpha != 1.0f)) {
-#pragma unroll
-        for (int td = 0; td < D / 32; ++td)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) st.o[td][r] *= alpha;
-    }
-#pragma unroll
-    for (int td = 0; td < D / 32; ++td) {
-        const int d = 32 * td + l32;
-        const unsigned char* vrow = sv + d * V_STRIDE;
-        const int sw = (d >> 4) & SW;
-#pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            const bf16x8_t vf = as_bf16x8(*reinterpret_cast<const uint4*>(vrow + ((cg0 + 2 * h + g) ^ sw) * 16));
-            st.o[td] = mfma_32x32x16(vf, pf[h], st.o[td]);
-        }
-    }
-}
-
-// Writes one pair of keys (even key in the low half-words) of 8 consecutive d into V^T.
-template <int V_STRIDE, int SW>
-__device__ __forceinline__ void store_vt_pair(unsigned char* sv, int kc, int pi, uint4 ve, uint4 vo) {
-    const int kp = (pi & ~6) | ((pi & 2) << 1) | ((pi & 4) >> 1);  // swap key bits 2 and 3
-    const int col = (((kp >> 2) ^ ((kc >> 1) & SW)) << 2) | (kp & 3);     // dword column, swizzled (d >> 4 = kc >> 1)
-    const uint32_t e[4] = {ve.x, ve.y, ve.z, ve.w}, o[4] = {vo.x, vo.y, vo.z, vo.w};
-#pragma unroll
-    for (int j = 0; j < 8; ++j) {
-        const uint32_t ev = (j & 1) ? (e[j >> 1] >> 16) : (e[j >> 1] & 0xffffu);
-        const uint32_t ov = (j & 1) ? (o[j >> 1] & 0xffff0000u) : (o[j >> 1] << 16);
-        *reinterpret_cast<uint32_t*>(sv + (8 * kc + j) * V_STRIDE + col * 4) = ev | ov;
-    }
-}
-
 // ------------------------------------------------------------------------------------------
 // row-tiled kernel (prefix pass, prefill rows)
 // ------------------------------------------------------------------------------------------
+// K and V blocks of 64 keys go global -> LDS directly (global_load_lds_dwordx4, no register
+// staging), both row-major [key][d] with XOR-swizzled 16-byte chunks:
+//   K chunk c of row r sits at c ^ kswz(r): the 16 rows that 16 lanes read together (same chunk)
+//     then cover all 64 banks;
+//   V chunk c of row r sits at c ^ vswz(r): the four key rows x 64 bytes that one transposing read
+//     of 32 lanes touches then cover all 64 banks.
+// The V^T operand of O^T = V^T P^T is produced by ds_read_b64_tr_b16: within 16 lanes, lane s points
+// at V[key0 + s / 4][d0 + 4 (s % 4) .. + 3] and lane i receives V[key0 + 0..3][d0 + i], i.e. four
+// keys of one d, which is the MFMA operand layout (checked on the device: lane i, element e comes
+// from source lane 4 e + i / 4, element i % 4).
 template <int D>
 struct TileSmem {
     static constexpr int BLOCK_N = 64;
-    static constexpr int K_STRIDE = (D + 8) * 2;        // bytes per key row (16-byte pad)
-    static constexpr int K_BYTES = BLOCK_N * K_STRIDE;
-    static constexpr int V_STRIDE = (BLOCK_N + 8) * 2;  // bytes per d row of V^T (36 dwords)
-    static constexpr int V_BYTES = D * V_STRIDE;
+    static constexpr int ROWB = D * 2;                  // bytes per key row, no padding
+    static constexpr int K_BYTES = BLOCK_N * ROWB;
+    static constexpr int V_BYTES = BLOCK_N * ROWB;
     static constexpr int STAGE = K_BYTES + V_BYTES;
 };
 
 template <int D>
-__global__ void __launch_bounds__(256) attn_tile_kernel(AttnArgs p) {
+__device__ __forceinline__ int kswz(int row) { return D == 128 ? (row & 15) : ((row >> 1) & 7); }
+template <int D>
+__device__ __forceinline__ int vswz(int row) { return D == 128 ? 4 * (row & 3) : 4 * ((row >> 1) & 1); }
+
+// 64 lanes x 16 bytes from per-lane global addresses to 1 KB of LDS starting at lds_addr.
+__device__ __forceinline__ void dma16_ptr(const void* gptr, uint32_t lds_addr) {
+    asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gptr), "s"(lds_addr) : "memory");
+}
+
+typedef short short4_t __attribute__((ext_vector_type(4)));
+
+template <int D>
+__global__ void __launch_bounds__(256, 2) attn_tile_kernel(AttnArgs p) {
     using SM = TileSmem<D>;
     constexpr int BLOCK_N = SM::BLOCK_N;
-    constexpr int CH = D / 8;            // 16-byte chunks per K/V row
-    constexpr int K_IT = CH / 4;         // K chunks per thread per block
-    constexpr int V_IT = CH / 8;         // V key pairs per thread per block
-    constexpr int ROWS_PER_PASS = 256 / CH;
+    constexpr int CH = D / 8;                 // 16-byte chunks per K/V row
+    constexpr int RPI = 64 / CH;              // rows one 1 KB wave load covers
+    constexpr int IT = BLOCK_N / (4 * RPI);   // wave loads per wave, per tensor and block
     extern __shared__ __align__(16) unsigned char smem[];
 
     const AttnItem it = p.items[blockIdx.x];
     const int kvh = blockIdx.y;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l32 = lane & 31, g = lane >> 5;
 
     // ---- this lane's query row
@@ -238,74 +179,122 @@ __global__ void __launch_bounds__(256) attn_tile_kernel(AttnArgs p) {
     RowState<D> st;
     state_init<D>(st, p, it, valid, row_id, g);
 
-    // ---- staging: K rows as they are, V transposed
+    // ---- staging.  Wave load j of this wave fills LDS rows (4 j + wave) * RPI ..; lane l owns row
+    // l / CH of those and the 16-byte slot l % CH.  Keys past the end re-read the last key: their
+    // scores are masked and their probabilities are exact zeros.
     const int32_t* bt = p.block_table + (int64_t)it.bt_req * p.max_blocks;
-    const int kc = tid % CH, krow0 = tid / CH;
-    uint4 k_reg[K_IT], v_reg[V_IT][2];
-    // Branch-free and in two phases (all block-table entries first, then all K/V rows), so that the
-    // loads of a block are in flight together instead of one dependent pair after the other.  Keys
-    // past the end read the last valid key and are replaced by exact zeros.
     const int last_key = it.key_end - 1;
-    auto slot_of = [&](int key) -> int64_t {
-        return ((int64_t)bt[key >> p.page_shift] << p.page_shift) + (key & p.page_mask);
+    const int lrow = lane / CH, lslot = lane % CH;
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem;
+    int64_t slot_cur[IT], slot_nxt[IT];
+    auto lookup = [&](int kb0, int64_t (&slots)[IT]) {   // block-table entries of this lane's rows
+#pragma unroll
+        for (int j = 0; j < IT; ++j) {
+            const int key = min(kb0 + (4 * j + wave) * RPI + lrow, last_key);
+            slots[j] = ((int64_t)bt[key >> p.page_shift] << p.page_shift) + (key & p.page_mask);
+        }
     };
-    auto stage_load = [&](int kb0) {
-        int64_t ks[K_IT], vs[V_IT][2];
+    auto issue = [&](int buf, const int64_t (&slots)[IT]) {
+        const uint32_t base = lds0 + buf * SM::STAGE + wave * 1024;
 #pragma unroll
-        for (int i = 0; i < K_IT; ++i) ks[i] = slot_of(min(kb0 + krow0 + ROWS_PER_PASS * i, last_key));
-#pragma unroll
-        for (int i = 0; i < V_IT; ++i)
-#pragma unroll
-            for (int e = 0; e < 2; ++e) vs[i][e] = slot_of(min(kb0 + 2 * (krow0 + ROWS_PER_PASS * i) + e, last_key));
-#pragma unroll
-        for (int i = 0; i < K_IT; ++i)
-            k_reg[i] = *reinterpret_cast<const uint4*>(p.k_pages + (ks[i] * p.n_kv + kvh) * D + kc * 8);
-#pragma unroll
-        for (int i = 0; i < V_IT; ++i)
-#pragma unroll
-            for (int e = 0; e < 2; ++e)
-                v_reg[i][e] = *reinterpret_cast<const uint4*>(p.v_pages + (vs[i][e] * p.n_kv + kvh) * D + kc * 8);
-#pragma unroll
-        for (int i = 0; i < K_IT; ++i)
-            if (kb0 + krow0 + ROWS_PER_PASS * i > last_key) k_reg[i] = make_uint4(0, 0, 0, 0);
-#pragma unroll
-        for (int i = 0; i < V_IT; ++i)
-#pragma unroll
-            for (int e = 0; e < 2; ++e)   // keys past the end contribute exact zeros
-                if (kb0 + 2 * (krow0 + ROWS_PER_PASS * i) + e > last_key) v_reg[i][e] = make_uint4(0, 0, 0, 0);
-    };
-    auto stage_store = [&](int buf) {
-        unsigned char* sk = smem + buf * SM::STAGE;
-        unsigned char* sv = sk + SM::K_BYTES;
-#pragma unroll
-        for (int i = 0; i < K_IT; ++i)
-            *reinterpret_cast<uint4*>(sk + (krow0 + ROWS_PER_PASS * i) * SM::K_STRIDE + kc * 16) = k_reg[i];
-#pragma unroll
-        for (int i = 0; i < V_IT; ++i)
-            store_vt_pair<SM::V_STRIDE, 7>(sv, kc, krow0 + ROWS_PER_PASS * i, v_reg[i][0], v_reg[i][1]);
+        for (int j = 0; j < IT; ++j) {
+            const int row = (4 * j + wave) * RPI + lrow;
+            const int64_t off = (slots[j] * p.n_kv + kvh) * D;
+            dma16_ptr(p.k_pages + off + ((lslot ^ kswz<D>(row)) << 3), base + j * 4096);
+            dma16_ptr(p.v_pages + off + ((lslot ^ vswz<D>(row)) << 3), base + SM::K_BYTES + j * 4096);
+        }
     };
 
     const int n_blocks = (it.key_end - it.key_begin + BLOCK_N - 1) / BLOCK_N;
     if (n_blocks > 0) {
-        stage_load(it.key_begin);
-        stage_store(0);
+        lookup(it.key_begin, slot_cur);
+        issue(0, slot_cur);
+        lookup(min(it.key_begin + BLOCK_N, last_key), slot_nxt);
     }
-    __syncthreads();
+    // operand addresses that do not change from block to block
+    const int G = lane >> 4, s16 = lane & 15;
     for (int b = 0; b < n_blocks; ++b) {
         const int kb0 = it.key_begin + b * BLOCK_N;
-        const bool more = b + 1 < n_blocks;
-        if (more) stage_load(kb0 + BLOCK_N);
+        // this block has landed for every wave, and every wave is done with the other buffer
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+        if (b + 1 < n_blocks) {
+            issue((b + 1) & 1, slot_nxt);
+            lookup(min(kb0 + 2 * BLOCK_N, last_key), slot_nxt);   // consumed one iteration later
+        }
         if (wave_active && kb0 < wave_klim_max) {
-            const unsigned char* sk = smem + (b & 1) * SM::STAGE;
-            const unsigned char* sv = sk + SM::K_BYTES;
+            unsigned char* sk = smem + (b & 1) * SM::STAGE;
+            unsigned char* sv = sk + SM::K_BYTES;
             const bool need_mask = kb0 + BLOCK_N > wave_klim_min;
 #pragma unroll
-            for (int t = 0; t < 2; ++t)
-                attn_tile32<D, SM::K_STRIDE, SM::V_STRIDE, 7>(st, qf, sk + 32 * t * SM::K_STRIDE, sv, 4 * t,
-                                                              kb0 + 32 * t, klim, need_mask, p.scale_log2, l32, g);
+            for (int t = 0; t < 2; ++t) {
+                // S^T = K Q^T for 32 keys
+                f32x16_t sc;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) sc[r] = 0.f;
+                const int krow = 32 * t + l32;
+#pragma unroll
+                for (int ks = 0; ks < D / 16; ++ks) {
+                    const bf16x8_t kf = as_bf16x8(*reinterpret_cast<const uint4*>(
+                        sk + krow * SM::ROWB + (((2 * ks + g) ^ kswz<D>(krow)) << 4)));
+                    sc = mfma_32x32x16(kf, qf[ks], sc);
+                }
+                float mx = -INFINITY;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    float v = sc[r] * p.scale_log2;
+                    if (need_mask && kb0 + 32 * t + 8 * (r >> 2) + 4 * g + (r & 3) >= klim) v = -INFINITY;
+                    sc[r] = v;
+                    mx = fmaxf(mx, v);
+                }
+                mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+                const float m_new = fmaxf(st.m, mx);
+                const float m_use = m_new == -INFINITY ? 0.f : m_new;  // a row that has seen no key yet
+                const float alpha = __builtin_amdgcn_exp2f(st.m - m_use);
+                st.m = m_new;
+                float psum = 0.f;
+                bf16x8_t pf[2];
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    uint32_t w[4];
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const float p0 = __builtin_amdgcn_exp2f(sc[8 * h + 2 * j] - m_use);
+                        const float p1 = __builtin_amdgcn_exp2f(sc[8 * h + 2 * j + 1] - m_use);
+                        psum += p0 + p1;
+                        w[j] = pack_bf16x2(p0, p1);
+                    }
+                    pf[h] = as_bf16x8(make_uint4(w[0], w[1], w[2], w[3]));
+                }
+                st.l = st.l * alpha + psum;
+                if (__any(alpha != 1.0f)) {
+#pragma unroll
+                    for (int td = 0; td < D / 32; ++td)
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) st.o[td][r] *= alpha;
+                }
+                // O^T += V^T P^T.  Element e of lane group g's probabilities is key
+                // 32 t + 16 h + 8 (e / 4) + 4 g + e % 4; the two transposing reads fetch those keys.
+#pragma unroll
+                for (int td = 0; td < D / 32; ++td)
+#pragma unroll
+                    for (int h = 0; h < 2; ++h) {
+                        short4_t lo, hi;
+                        {
+                            const int key = 32 * t + 16 * h + 4 * (G >> 1) + (s16 >> 2);
+                            const int chunk = 4 * td + 2 * (G & 1) + ((s16 & 3) >> 1);
+                            unsigned char* a0 = sv + key * SM::ROWB + ((chunk ^ vswz<D>(key)) << 4) + (s16 & 1) * 8;
+                            const int key1 = key + 8;
+                            unsigned char* a1 = sv + key1 * SM::ROWB + ((chunk ^ vswz<D>(key1)) << 4) + (s16 & 1) * 8;
+                            lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((short4_t __attribute__((address_space(3)))*)(a0));
+                            hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((short4_t __attribute__((address_space(3)))*)(a1));
+                        }
+                        typedef short short8_t __attribute__((ext_vector_type(8)));
+                        const short8_t v8 = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+                        st.o[td] = mfma_32x32x16(__builtin_bit_cast(bf16x8_t, v8), pf[h], st.o[td]);
+                    }
+            }
         }
-        if (more) stage_store((b + 1) & 1);
-        __syncthreads();
     }
     if (valid) state_store<D>(st, p, it, row_id, g);
 }

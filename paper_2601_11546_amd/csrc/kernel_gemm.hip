@@ -13,6 +13,7 @@
 // of tiles, token tiles fastest: concurrent workgroups of an XCD share weight tiles.
 #include <algorithm>
 #include <cstdlib>
+#include <type_traits>
 
 #include "device_utils.h"
 #include "relserve_internal.h"
@@ -62,12 +63,25 @@ __device__ __forceinline__ int remap_xcd(int bid, int num) {
     return xcd < rem ? xcd * (per + 1) + idx : rem * (per + 1) + (xcd - rem) * per + idx;
 }
 
+// Tile order inside an XCD's run: token tiles fastest within panels of GROUP_M token tiles, then
+// feature tiles, then the next panel.  The ~32 tiles an XCD works on at a time then cover about
+// GROUP_M token tiles x 32 / GROUP_M feature tiles, so that its L2 serves ~12 distinct operand
+// slices per k step instead of 33 when the batch has many token tiles.
+constexpr int GROUP_M = 8;
+__device__ __forceinline__ void tile_coords(int t, int tiles_m, int tiles_n, int& tile_m, int& tile_n) {
+    const int per_group = GROUP_M * tiles_n;
+    const int first_m = (t / per_group) * GROUP_M, in_group = t % per_group;
+    const int gsz = min(tiles_m - first_m, GROUP_M);
+    tile_m = first_m + in_group % gsz;
+    tile_n = in_group / gsz;
+}
+
 // Epilogue shared by both GEMM kernels: register r of accumulator tile (tn, tm) holds feature
 // 32 tn + 8 (r / 4) + 4 g + r % 4 of the wave's feature range and token 32 tm + l32 of its token range.
-template <int BM, int BN, int EPI, int D>
-__device__ __forceinline__ void gemm_epilogue(const f32x16_t (&acc)[BN / 64][BM / 64], const GemmArgs& p, int tile_m,
-                                              int tile_n, int wm, int wn, int l32, int g) {
-    constexpr int TM = BM / 64, TN = BN / 64;
+template <int BM, int BN, int EPI, int D, int WGM = 2, int WGN = 2>
+__device__ __forceinline__ void gemm_epilogue(const f32x16_t (&acc)[BN / (32 * WGN)][BM / (32 * WGM)], const GemmArgs& p,
+                                              int tile_m, int tile_n, int wm, int wn, int l32, int g) {
+    constexpr int TM = BM / (32 * WGM), TN = BN / (32 * WGN);
     const int t0 = tile_m * BM;
     if (EPI == EPI_ATOMIC) {
         // Split-K partial sums.  These tiles were accumulated with the operands swapped: register r
@@ -77,10 +91,10 @@ __device__ __forceinline__ void gemm_epilogue(const f32x16_t (&acc)[BN / 64][BM 
         for (int tm = 0; tm < TM; ++tm)
 #pragma unroll
             for (int tn = 0; tn < TN; ++tn) {
-                const int n = tile_n * BN + wn * (BN / 2) + 32 * tn + l32;
+                const int n = tile_n * BN + wn * (BN / WGN) + 32 * tn + l32;
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
-                    const int t = t0 + wm * (BM / 2) + 32 * tm + 8 * (r >> 2) + 4 * g + (r & 3);
+                    const int t = t0 + wm * (BM / WGM) + 32 * tm + 8 * (r >> 2) + 4 * g + (r & 3);
                     if (t < p.T && n < p.N) unsafeAtomicAdd(p.accum + (int64_t)t * p.N + n, acc[tn][tm][r]);
                 }
             }
@@ -88,7 +102,7 @@ __device__ __forceinline__ void gemm_epilogue(const f32x16_t (&acc)[BN / 64][BM 
     }
 #pragma unroll
     for (int tm = 0; tm < TM; ++tm) {
-        const int t = t0 + wm * (BM / 2) + 32 * tm + l32;
+        const int t = t0 + wm * (BM / WGM) + 32 * tm + l32;
         if (t >= p.T) continue;
         if (EPI == EPI_ATOMIC) {
             // handled before this loop (transposed accumulator layout)
@@ -149,7 +163,7 @@ __device__ __forceinline__ void gemm_epilogue(const f32x16_t (&acc)[BN / 64][BM 
             for (int tn = 0; tn < TN / 2; ++tn) {
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
-                    const int i = tile_n * (BN / 2) + wn * (BN / 4) + 32 * tn + 8 * q + 4 * g;
+                    const int i = tile_n * (BN / 2) + wn * (BN / (2 * WGN)) + 32 * tn + 8 * q + 4 * g;
                     if (i >= p.n_half) continue;  // n_half is a multiple of 8, i of 4: whole quad in or out
                     float o[4];
 #pragma unroll
@@ -166,7 +180,7 @@ __device__ __forceinline__ void gemm_epilogue(const f32x16_t (&acc)[BN / 64][BM 
             for (int tn = 0; tn < TN; ++tn) {
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
-                    const int n = tile_n * BN + wn * (BN / 2) + 32 * tn + 8 * q + 4 * g;
+                    const int n = tile_n * BN + wn * (BN / WGN) + 32 * tn + 8 * q + 4 * g;
                     if (n >= p.N) continue;  // N is a multiple of 4 on every path that reaches here
                     const int64_t o = (int64_t)t * p.N + n;
                     float v[4];
@@ -206,7 +220,8 @@ __global__ void __launch_bounds__(256) gemm_bf16_kernel(GemmArgs p) {
     const int l32 = lane & 31, g = lane >> 5;
 
     const int tile = remap_xcd(blockIdx.x, p.tiles_m * p.tiles_n);
-    const int tile_m = tile % p.tiles_m, tile_n = tile / p.tiles_m;
+    int tile_m, tile_n;
+    tile_coords(tile, p.tiles_m, p.tiles_n, tile_m, tile_n);
     const int t0 = tile_m * BM;
     const int K = p.K;
 
@@ -322,52 +337,57 @@ __device__ __forceinline__ void dma16(const void* base, uint32_t voff, uint32_t 
 }
 
 // BKD = k extent of one LDS stage (64 or 32), NS = stages in the ring (NS - 1 are in flight).
-template <int BM, int BN, int EPI, int D, int BKD, int NS>
-__global__ void __launch_bounds__(256) gemm_dma_kernel(GemmArgs p) {
-    constexpr int TM = BM / 64, TN = BN / 64;
+// WGM x WGN = grid of waves over the tile (4 or 8 waves; 8 waves = two per SIMD, each with a quarter
+// of the registers, so that one wave's MFMAs cover the other's memory-instruction issue).
+template <int BM, int BN, int EPI, int D, int BKD, int NS, int WGM = 2, int WGN = 2>
+__global__ void __launch_bounds__(64 * WGM * WGN) gemm_dma_kernel(GemmArgs p) {
+    constexpr int NW = WGM * WGN;
+    constexpr int TM = BM / (32 * WGM), TN = BN / (32 * WGN);
     constexpr int ROWB = BKD * 2;                        // bytes per LDS row
     constexpr int CPR = BKD / 8;                         // 16-byte chunks per row
     constexpr int RPI = 1024 / ROWB;                     // rows one 1 KB wave load covers
-    constexpr int A_IT = BM / (4 * RPI), W_IT = BN / (4 * RPI);
+    constexpr int A_IT = BM / (NW * RPI), W_IT = BN / (NW * RPI);
     constexpr int A_BYTES = BM * ROWB, W_BYTES = BN * ROWB, STAGE = A_BYTES + W_BYTES;
     constexpr int KSTEPS = BKD / 16;
     constexpr int LOADS = A_IT + W_IT;                   // wave loads per stage
     static_assert(BKD == 64 || BKD == 32, "stage depth");
     static_assert((NS - 1) * LOADS < 64, "vmcnt field");
     static_assert(EPI != EPI_SWIGLU || TN % 2 == 0, "SwiGLU needs gate and up tiles in one wave");
-    static_assert(EPI != EPI_QKV_ROPE || (BN == 256 && (D == 64 || D == 128)), "a wave must own whole heads");
+    static_assert(EPI != EPI_QKV_ROPE || (BN / WGN == 128 && (D == 64 || D == 128)), "a wave must own whole heads");
+    static_assert(BM % (NW * RPI) == 0 && BN % (NW * RPI) == 0, "whole wave loads");
     extern __shared__ __align__(16) unsigned char smem[];
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wm = wave >> 1, wn = wave & 1;
+    const int wm = wave / WGN, wn = wave % WGN;
     const int l32 = lane & 31, g = lane >> 5;
 
     const int n_tiles = p.tiles_m * p.tiles_n;
     const int tile = remap_xcd(blockIdx.x % n_tiles, n_tiles);
     const int split = blockIdx.x / n_tiles;
-    const int tile_m = tile % p.tiles_m, tile_n = tile / p.tiles_m;
+    int tile_m, tile_n;
+    tile_coords(tile, p.tiles_m, p.tiles_n, tile_m, tile_n);
     const int t0 = tile_m * BM;
     const int K = p.K;
 
-    // ---- per-lane source offsets: wave load j of this wave fills LDS rows (4 j + wave) * RPI .. ;
+    // ---- per-lane source offsets: wave load j of this wave fills LDS rows (NW j + wave) * RPI .. ;
     // lane l owns row l / CPR of those and slot l % CPR, which holds the row's chunk slot ^ swz(row).
     // The LDS has 64 four-byte banks and serves a 16-byte-per-lane read 16 lanes at a time, so the
     // 16 consecutive rows those lanes read must cover all 64 banks once: swz = (row >> 1) & 7 for
     // 128-byte rows (row parity picks the bank half), (row >> 2) & 3 for 64-byte rows.
     // Rows past the end of a matrix re-read its last row: their products are never stored.
     const uint32_t lrow = lane / CPR;
-    const uint32_t row_lo = (uint32_t)(wave * RPI) + lrow;   // LDS row modulo 4 * RPI (>= 32): all the swizzle needs
+    const uint32_t row_lo = (uint32_t)(wave * RPI) + lrow;   // LDS row modulo NW * RPI (>= 32): all the swizzle needs
     const uint32_t chunk = (lane % CPR) ^ (BKD == 64 ? ((row_lo >> 1) & 7) : ((row_lo >> 2) & 3));
     uint32_t a_voff[A_IT], w_voff[W_IT];
 #pragma unroll
     for (int j = 0; j < A_IT; ++j) {
-        const int t = min(t0 + (4 * j + wave) * RPI + (int)lrow, p.T - 1);
+        const int t = min(t0 + (NW * j + wave) * RPI + (int)lrow, p.T - 1);
         a_voff[j] = ((uint32_t)t * (uint32_t)K + chunk * 8) * 2;
     }
 #pragma unroll
     for (int j = 0; j < W_IT; ++j) {
-        const int lr = (4 * j + wave) * RPI + (int)lrow;
+        const int lr = (NW * j + wave) * RPI + (int)lrow;
         int n;
         if (EPI == EPI_SWIGLU) {
             constexpr int HALF = BN / 2;
@@ -384,22 +404,22 @@ __global__ void __launch_bounds__(256) gemm_dma_kernel(GemmArgs p) {
         const char* wbase = reinterpret_cast<const char*>(p.w) + (size_t)k0 * 2;
         const uint32_t la = lds0 + stage * STAGE + wave * 1024;
 #pragma unroll
-        for (int j = 0; j < A_IT; ++j) dma16(abase, a_voff[j], la + j * 4096);
+        for (int j = 0; j < A_IT; ++j) dma16(abase, a_voff[j], la + j * (NW * 1024));
 #pragma unroll
-        for (int j = 0; j < W_IT; ++j) dma16(wbase, w_voff[j], la + A_BYTES + j * 4096);
+        for (int j = 0; j < W_IT; ++j) dma16(wbase, w_voff[j], la + A_BYTES + j * (NW * 1024));
     };
 
     // ---- LDS -> MFMA operand offsets
     int a_rd[TM], w_rd[TN];
 #pragma unroll
-    for (int tm = 0; tm < TM; ++tm) a_rd[tm] = (wm * (BM / 2) + 32 * tm + l32) * ROWB;
+    for (int tm = 0; tm < TM; ++tm) a_rd[tm] = (wm * (BM / WGM) + 32 * tm + l32) * ROWB;
 #pragma unroll
     for (int tn = 0; tn < TN; ++tn) {
         int row;
         if (EPI == EPI_SWIGLU)
-            row = (tn < TN / 2 ? 0 : BN / 2) + wn * (BN / 4) + 32 * (tn % (TN / 2)) + l32;
+            row = (tn < TN / 2 ? 0 : BN / 2) + wn * (BN / (2 * WGN)) + 32 * (tn % (TN / 2)) + l32;
         else
-            row = wn * (BN / 2) + 32 * tn + l32;
+            row = wn * (BN / WGN) + 32 * tn + l32;
         w_rd[tn] = A_BYTES + row * ROWB;
     }
     const int swz = BKD == 64 ? ((l32 >> 1) & 7) : ((l32 >> 2) & 3);
@@ -435,37 +455,71 @@ __global__ void __launch_bounds__(256) gemm_dma_kernel(GemmArgs p) {
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
     load_frags(0, 0, 0);
+    auto mfma_one = [&](int buf, int i) {   // i-th of the TN * TM products of a k step
+        const int tn = i / TM, tm = i % TM;
+        acc[tn][tm] = EPI == EPI_ATOMIC ? mfma_32x32x16(af[buf][tm], wf[buf][tn], acc[tn][tm])
+                                        : mfma_32x32x16(wf[buf][tn], af[buf][tm], acc[tn][tm]);
+    };
+    auto load_frag_one = [&](int buf, int stage, int i) {   // i-th of the TN + TM fragment reads of k step 0
+        const unsigned char* st = smem + stage * STAGE;
+        const int ch = (g ^ swz) << 4;
+        if (i < TN)
+            wf[buf][i] = as_bf16x8(*reinterpret_cast<const uint4*>(st + w_rd[i] + ch));
+        else
+            af[buf][i - TN] = as_bf16x8(*reinterpret_cast<const uint4*>(st + a_rd[i - TN] + ch));
+    };
+    auto issue_one = [&](int stage, int k0, int i) {   // i-th of the LOADS wave loads of a stage
+        const uint32_t la = lds0 + stage * STAGE + wave * 1024;
+        if (i < A_IT)
+            dma16(reinterpret_cast<const char*>(p.a) + (size_t)k0 * 2, a_voff[i], la + i * (NW * 1024));
+        else
+            dma16(reinterpret_cast<const char*>(p.w) + (size_t)k0 * 2, w_voff[i - A_IT],
+                  la + A_BYTES + (i - A_IT) * (NW * 1024));
+    };
+    constexpr int NM = TN * TM, NF = TN + TM;
+    // Hand-over at the last k step of a stage: all fragments of the stage are in registers; after the
+    // barrier the step's MFMAs are issued one by one with the refill loads of the freed buffer and (in
+    // the second half) the first fragment reads of the next stage slotted between them, so neither
+    // the load issue nor the LDS latency leaves the matrix pipe idle.  The MFMAs sit on ONE control
+    // path on purpose: at a join the compiler would make them wait for the newest reads.
     int cur = 0;  // stage being computed
     for (int kt = 0; kt < nk; ++kt) {
         const int nxt = cur + 1 == NS ? 0 : cur + 1;
 #pragma unroll
-        for (int ks = 0; ks < KSTEPS; ++ks) {
-            if (ks + 1 < KSTEPS) {
-                load_frags((ks + 1) & 1, cur, ks + 1);
-            } else if (kt + 1 < nk) {
-                // Every fragment of this stage is in registers.  Wait for the next stage (the NS - 2
-                // younger ones may stay in flight), hand over, refill this stage's buffer with the
-                // stage NS iterations ahead, and start reading the next stage.
-                if (kt + NS - 1 < nk)
-                    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"((NS - 2) * LOADS) : "memory");
-                else
-                    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
-                __syncthreads();
-                if (kt + NS < nk) issue_stage(cur, (kbeg + kt + NS) * BKD);
-                load_frags((ks + 1) & 1, nxt, 0);
-                // keep this step's MFMAs behind the hand-over: they cover the latency of the reads above
-                __builtin_amdgcn_sched_barrier(0);
+        for (int ks = 0; ks + 1 < KSTEPS; ++ks) {
+            load_frags((ks + 1) & 1, cur, ks + 1);
+#pragma unroll
+            for (int i = 0; i < NM; ++i) mfma_one(ks & 1, i);
+        }
+        // Last k step of the stage: wait for the next stage (the NS - 2 younger ones may stay in
+        // flight) and hand over.  After the last stage this reads fragments nobody uses.
+        constexpr int LB = (KSTEPS - 1) & 1;
+        if (NS == 2 || kt + NS - 1 >= nk)
+            asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+        else
+            asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"((NS - 2) * LOADS) : "memory");
+        __syncthreads();
+        const bool refill = kt + NS < nk;
+        const int k0 = (kbeg + kt + NS) * BKD;
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int i = 0; i < NM; ++i) {
+            mfma_one(LB, i);
+            __builtin_amdgcn_sched_barrier(0);
+            if (refill) {
+#pragma unroll
+                for (int d = i * LOADS / NM; d < (i + 1) * LOADS / NM; ++d) issue_one(cur, k0, d);
             }
+            if (i >= NM / 2) {
 #pragma unroll
-            for (int tn = 0; tn < TN; ++tn)
-#pragma unroll
-                for (int tm = 0; tm < TM; ++tm)
-                    acc[tn][tm] = EPI == EPI_ATOMIC ? mfma_32x32x16(af[ks & 1][tm], wf[ks & 1][tn], acc[tn][tm])
-                                                    : mfma_32x32x16(wf[ks & 1][tn], af[ks & 1][tm], acc[tn][tm]);
+                for (int f = (i - NM / 2) * NF / (NM - NM / 2); f < (i + 1 - NM / 2) * NF / (NM - NM / 2); ++f)
+                    load_frag_one(LB ^ 1, nxt, f);
+            }
+            __builtin_amdgcn_sched_barrier(0);
         }
         cur = nxt;
     }
-    gemm_epilogue<BM, BN, EPI, D>(acc, p, tile_m, tile_n, wm, wn, l32, g);
+    gemm_epilogue<BM, BN, EPI, D, WGM, WGN>(acc, p, tile_m, tile_n, wm, wn, l32, g);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -608,13 +662,12 @@ bool skinny_applies(int T, int N, int K, const float* accum) {
     return accum != nullptr && T <= 256 && K % 64 == 0 && N % 4 == 0 && !g_force_generic;
 }
 
-template <int BM, int BN, int EPI, int D = 0>
+template <int BM, int BN, int EPI, int D = 0, int WGM = 2, int WGN = 2>
 hipError_t launch_cfg(const GemmArgs& base, hipStream_t s) {
     GemmArgs p = base;
     p.tiles_m = (p.T + BM - 1) / BM;
     p.tiles_n = EPI == EPI_SWIGLU ? (p.n_half + BN / 2 - 1) / (BN / 2) : (p.N + BN - 1) / BN;
     constexpr int smem = 2 * (BM + BN) * BK * 2;
-    // ring of the direct-to-LDS kernel: as many 32-deep stages as fit beside nothing else
     constexpr int DMA_BK = RELSERVE_DMA_BK, DMA_NS = RELSERVE_DMA_NS;
     constexpr int dma_smem = DMA_NS * (BM + BN) * DMA_BK * 2;
     static bool attr_done = false;
@@ -622,13 +675,15 @@ hipError_t launch_cfg(const GemmArgs& base, hipStream_t s) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_bf16_kernel<BM, BN, EPI, D>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, smem);
         if (e == hipSuccess)
-            e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_dma_kernel<BM, BN, EPI, D, DMA_BK, DMA_NS>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, dma_smem);
+            e = hipFuncSetAttribute(
+                reinterpret_cast<const void*>(&gemm_dma_kernel<BM, BN, EPI, D, DMA_BK, DMA_NS, WGM, WGN>),
+                hipFuncAttributeMaxDynamicSharedMemorySize, dma_smem);
         if (e != hipSuccess) return e;
         attr_done = true;
     }
     if (p.K % 64 == 0 && !g_force_generic)
-        gemm_dma_kernel<BM, BN, EPI, D, DMA_BK, DMA_NS><<<dim3(p.tiles_m * p.tiles_n), dim3(256), dma_smem, s>>>(p);
+        gemm_dma_kernel<BM, BN, EPI, D, DMA_BK, DMA_NS, WGM, WGN>
+            <<<dim3(p.tiles_m * p.tiles_n), dim3(64 * WGM * WGN), dma_smem, s>>>(p);
     else
         gemm_bf16_kernel<BM, BN, EPI, D><<<dim3(p.tiles_m * p.tiles_n), dim3(256), smem, s>>>(p);
     return hipGetLastError();
@@ -641,7 +696,8 @@ hipError_t launch_cfg(const GemmArgs& base, hipStream_t s) {
 struct TileCand { int bm, bn, wg_per_cu; float eff; };
 constexpr TileCand kTiles[] = {
     // efficiencies calibrated on T = 1282 / 6144 problems of the 13B and 70B layer shapes
-    {256, 256, 1, 1.00f}, {192, 256, 1, 0.92f}, {128, 256, 1, 0.78f}, {128, 128, 2, 0.87f}, {64, 128, 3, 0.75f}};
+    {256, 256, 1, 1.00f}, {192, 256, 1, 0.92f}, {128, 256, 1, 0.78f}, {128, 128, 2, 0.87f}, {64, 128, 3, 0.75f},
+    {256, 256, 1, 0.0f}};   // index 5: 256 x 256 with 8 waves (experimental, only by the test hook)
 
 int choose_tile(int T, int64_t n_eff, bool need_bn256) {
     static const char* force = getenv("RELSERVE_GEMM_TILE");   // test hook: index into kTiles
@@ -650,7 +706,7 @@ int choose_tile(int T, int64_t n_eff, bool need_bn256) {
     double best_cost = 1e300;
     for (int i = 0; i < (int)(sizeof(kTiles) / sizeof(kTiles[0])); ++i) {
         const TileCand& c = kTiles[i];
-        if (need_bn256 && c.bn != 256) continue;
+        if ((need_bn256 && c.bn != 256) || c.eff <= 0.f) continue;
         const int64_t tiles = ((T + c.bm - 1) / c.bm) * ((n_eff + c.bn - 1) / c.bn);
         const int64_t slots = 256 * c.wg_per_cu;
         const double rounds = (double)((tiles + slots - 1) / slots);
@@ -669,6 +725,13 @@ hipError_t launch_epi(const GemmArgs& p, hipStream_t s) {
         case 1: return launch_cfg<192, 256, EPI>(p, s);
         case 2: return launch_cfg<128, 256, EPI>(p, s);
         case 3: return launch_cfg<128, 128, EPI>(p, s);
+        case 5: return launch_cfg<256, 256, EPI, 0, 4, 2>(p, s);
+        case 6: return launch_cfg<256, 256, EPI, 0, 2, 4>(p, s);
+        case 7: return launch_cfg<256, 256, EPI, 0, 4, 4>(p, s);
+#if RELSERVE_DMA_BK == 64
+        case 8: return launch_cfg<192, 256, EPI, 0, 2, 4>(p, s);
+        case 9: return launch_cfg<128, 256, EPI, 0, 2, 4>(p, s);
+#endif
         default: return launch_cfg<64, 128, EPI>(p, s);
     }
 }
@@ -723,6 +786,7 @@ hipError_t launch_qkv_d(const GemmArgs& p, hipStream_t s) {
     switch (choose_tile(p.T, p.N, true)) {   // the rotation needs 128 features per wave: BN = 256 only
         case 0: return launch_cfg<256, 256, EPI_QKV_ROPE, D>(p, s);
         case 1: return launch_cfg<192, 256, EPI_QKV_ROPE, D>(p, s);
+        case 5: return launch_cfg<256, 256, EPI_QKV_ROPE, D, 4, 2>(p, s);
         default: return launch_cfg<128, 256, EPI_QKV_ROPE, D>(p, s);
     }
 }

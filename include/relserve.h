@@ -232,16 +232,26 @@ int32_t relserve_attention(const relserve_layer* layer, const relserve_batch* ba
                            const void* q, int32_t q_pitch, relserve_kv_cache cache,
                            void* out, void* workspace, size_t workspace_bytes, void* stream);
 
+/* ---- test hook ----
+ * Forces the tile shape and the tail split of every later GEMM launch of this process:
+ * tile = 0..4 (256x256, 192x256, 128x256, 128x128, 64x128 tokens x features), 5..9 = eight-wave
+ * variants of 256x256 (5, 6, 7), 192x256 (8) and 128x256 (9); -1 = automatic choice.  tail_splits
+ * = 2..8 makes the tiles of the incomplete last round split their k range that many ways (0 or 1 =
+ * whole tiles only).  Shapes a tile cannot serve (the fused q/k/v epilogue needs 256 features per
+ * tile) fall back to the nearest one that can.  Process-wide, not thread-safe; for tests and tuning. */
+int32_t relserve_debug_force_gemm_plan(int32_t tile, int32_t tail_splits);
+
 /* ---- per-kernel timing with HIP events on the caller's stream ---- */
 
 #define RELSERVE_PROFILE_SLOTS 12
 /* names, in launch order, of the kernels one layer step runs */
 const char* relserve_profile_slot_name(int32_t slot);
-/* When enabled, relserve_layer_step records an event pair around each kernel
- * and accumulates the durations at the next relserve_profile_read, which
- * synchronises the stream.  ms_sum / launches: host arrays of
+/* slot_mask: bit i set = relserve_layer_step records an event pair around the
+ * kernel of slot i (-1 = every kernel, 0 = off); the durations are accumulated
+ * at the next relserve_profile_read, which synchronises the stream.  Each pair
+ * costs a few microseconds of stream time.  ms_sum / launches: host arrays of
  * RELSERVE_PROFILE_SLOTS entries. */
-int32_t relserve_profile_enable(relserve_layer* layer, int32_t enable);
+int32_t relserve_profile_enable(relserve_layer* layer, int32_t slot_mask);
 int32_t relserve_profile_read(relserve_layer* layer, double* ms_sum, int64_t* launches, int32_t reset);
 
 #ifdef __cplusplus

@@ -27,7 +27,8 @@ EXPORTS = ["relserve_version", "relserve_strerror", "relserve_config_validate", 
            "relserve_batch_destroy", "relserve_batch_get_info", "relserve_workspace_bytes", "relserve_kv_append",
            "relserve_layer_step", "relserve_model_workspace_bytes", "relserve_model_step", "relserve_rmsnorm", "relserve_linear", "relserve_rope_append",
            "relserve_qkv_rope_append",
-           "relserve_attention", "relserve_profile_slot_name", "relserve_profile_enable", "relserve_profile_read"]
+           "relserve_attention", "relserve_profile_slot_name", "relserve_profile_enable", "relserve_profile_read",
+           "relserve_debug_force_gemm_plan"]
 
 
 class RelserveError(RuntimeError):
@@ -96,6 +97,7 @@ for _n, _a in {
     "relserve_attention": [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, KVCache, C.c_void_p, C.c_void_p,
                            C.c_size_t, C.c_void_p],
     "relserve_profile_enable": [C.c_void_p, C.c_int32],
+    "relserve_debug_force_gemm_plan": [C.c_int32, C.c_int32],
     "relserve_profile_read": [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32],
 }.items():
     getattr(_lib, _n).restype = C.c_int32
@@ -294,12 +296,26 @@ def relserve_attention(layer, pbatch, q, q_pitch: int, k_pages, v_pages, out, wo
                                    _stream(stream)), "relserve_attention")
 
 
+def relserve_debug_force_gemm_plan(tile: int = -1, tail_splits: int = 0) -> None:
+    _check(_lib.relserve_debug_force_gemm_plan(int(tile), int(tail_splits)), "relserve_debug_force_gemm_plan")
+
+
 def relserve_profile_slot_name(slot: int) -> str:
     return _lib.relserve_profile_slot_name(int(slot)).decode()
 
 
-def relserve_profile_enable(layer, enable: bool) -> None:
-    _check(_lib.relserve_profile_enable(layer.handle, int(bool(enable))), "relserve_profile_enable")
+def relserve_profile_enable(layer, slots=True) -> None:
+    """slots: True = every kernel, False = off, or an iterable of slot names / indices."""
+    if slots is True:
+        mask = -1
+    elif not slots:
+        mask = 0
+    else:
+        names = [relserve_profile_slot_name(i) for i in range(PROFILE_SLOTS)]
+        mask = 0
+        for s in slots:
+            mask |= 1 << (names.index(s) if isinstance(s, str) else int(s))
+    _check(_lib.relserve_profile_enable(layer.handle, mask), "relserve_profile_enable")
 
 
 def relserve_profile_read(layer, reset: bool = True) -> dict:

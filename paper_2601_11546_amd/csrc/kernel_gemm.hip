@@ -13,6 +13,7 @@
 // of tiles, token tiles fastest: concurrent workgroups of an XCD share weight tiles.
 #include <algorithm>
 #include <cstdlib>
+#include <cstring>
 #include <type_traits>
 
 #include "device_utils.h"
@@ -24,6 +25,8 @@ namespace {
 
 constexpr int BK = 64;
 constexpr int NUM_XCD = 8;
+constexpr int kTailCounters = GEMM_TAIL_COUNTERS;          // int32 arrival counters at the head of the scratch
+constexpr int64_t kTailFloats = GEMM_TAIL_FLOATS;          // fp32 partial tiles behind them
 
 struct GemmArgs {
     const uint16_t* a;
@@ -43,6 +46,13 @@ struct GemmArgs {
     // that tile and adds its partial sums into accum [T, N] fp32 (zero on entry)
     float* accum;
     int32_t k_per_split;   // in units of 64; 0 = no split
+    // tail split (main path): the last tail_tiles tiles (those of the incomplete last round) are each
+    // computed by tail_splits workgroups over k_per_split k steps each.  The partial tiles are stored
+    // to tail_buf (tail_splits x tail_tiles x BM x BN fp32) and the workgroup that arrives last at a
+    // tile (tail_count, zero on entry and on exit) adds them up and runs the epilogue.
+    int32_t tail_tiles, tail_splits;
+    float* tail_buf;
+    int32_t* tail_count;
 };
 
 #ifndef RELSERVE_DMA_BK
@@ -54,6 +64,14 @@ struct GemmArgs {
 
 // Test hook: route every shape through the register-staged kernel (set from RELSERVE_GEMM_GENERIC=1).
 bool g_force_generic = getenv("RELSERVE_GEMM_GENERIC") != nullptr;
+// Test hook: tile candidate (index into kTiles) and tail splits every launch must use; -1 = cost model.
+// Initialised from RELSERVE_GEMM_TILE="cand" or "cand,splits".
+int g_force_cand = [] { const char* e = getenv("RELSERVE_GEMM_TILE"); return e ? atoi(e) : -1; }();
+int g_force_splits = [] {
+    const char* e = getenv("RELSERVE_GEMM_TILE");
+    const char* comma = e ? strchr(e, ',') : nullptr;
+    return comma ? atoi(comma + 1) : 0;
+}();
 
 enum { EPI_BF16 = 0, EPI_RES_BF16_OUT_F32 = 1, EPI_RES_F32_OUT_BF16 = 2, EPI_SWIGLU = 3, EPI_QKV_ROPE = 4, EPI_ATOMIC = 5 };
 
@@ -363,8 +381,27 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_dma_kernel(GemmArgs p) {
     const int l32 = lane & 31, g = lane >> 5;
 
     const int n_tiles = p.tiles_m * p.tiles_n;
-    const int tile = remap_xcd(blockIdx.x % n_tiles, n_tiles);
-    const int split = blockIdx.x / n_tiles;
+    int tile, split;
+    bool tail = false;
+    int tail_idx = 0;
+    if (EPI == EPI_ATOMIC) {
+        tile = remap_xcd(blockIdx.x % n_tiles, n_tiles);
+        split = blockIdx.x / n_tiles;
+    } else {
+        // the tail units come first in the grid: their short k ranges and atomic epilogues are over
+        // before the last whole tiles finish
+        const int tail_units = p.tail_tiles * p.tail_splits, dp_tiles = n_tiles - p.tail_tiles;
+        tail = (int)blockIdx.x < tail_units;
+        if (tail) {
+            const int u = remap_xcd(blockIdx.x, tail_units);   // runs of one split, consecutive tiles, per XCD
+            split = u / p.tail_tiles;
+            tail_idx = u % p.tail_tiles;
+            tile = dp_tiles + tail_idx;
+        } else {
+            split = 0;
+            tile = remap_xcd(blockIdx.x - tail_units, dp_tiles);
+        }
+    }
     int tile_m, tile_n;
     tile_coords(tile, p.tiles_m, p.tiles_n, tile_m, tile_n);
     const int t0 = tile_m * BM;
@@ -443,8 +480,9 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_dma_kernel(GemmArgs p) {
     };
 
     // k range of this workgroup (the whole K unless the launch splits it)
-    const int kbeg = EPI == EPI_ATOMIC ? split * p.k_per_split * (64 / BKD) : 0;
-    const int nk = EPI == EPI_ATOMIC ? min(p.k_per_split * (64 / BKD), K / BKD - kbeg) : K / BKD;
+    const bool part = EPI == EPI_ATOMIC || tail;
+    const int kbeg = part ? split * p.k_per_split * (64 / BKD) : 0;
+    const int nk = part ? min(p.k_per_split * (64 / BKD), K / BKD - kbeg) : K / BKD;
     // prologue: fill the whole ring, wait for stage 0 only
 #pragma unroll
     for (int s = 0; s < NS; ++s)
@@ -518,6 +556,58 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_dma_kernel(GemmArgs p) {
             __builtin_amdgcn_sched_barrier(0);
         }
         cur = nxt;
+    }
+    if (EPI != EPI_ATOMIC && tail) {
+        // Partial tile -> this split's slab (registers 4 c .. 4 c + 3 of accumulator tile (tn, tm) of
+        // thread tid are the float4 at ((tn TM + tm) 4 + c) * threads + tid: coalesced 16-byte accesses).
+        // The workgroup that arrives last at the tile adds the slabs in split order, so the result
+        // does not depend on the arrival order.
+        constexpr int AREA4 = BM * BN / 4, NT = 64 * NW;
+        float4* slab = reinterpret_cast<float4*>(p.tail_buf) + ((size_t)split * p.tail_tiles + tail_idx) * AREA4 + tid;
+#pragma unroll
+        for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+            for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+                for (int c = 0; c < 4; ++c)
+                    slab[((tn * TM + tm) * 4 + c) * NT] = make_float4(acc[tn][tm][4 * c], acc[tn][tm][4 * c + 1],
+                                                                      acc[tn][tm][4 * c + 2], acc[tn][tm][4 * c + 3]);
+        __shared__ int s_last;
+        __threadfence();   // the slab is visible device-wide before the arrival count moves
+        __syncthreads();
+        if (tid == 0) s_last = atomicAdd(p.tail_count + tail_idx, 1) == p.tail_splits - 1;
+        __syncthreads();
+        if (!s_last) return;
+        __threadfence();   // the other workgroups' slabs are visible
+#pragma unroll
+        for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+            for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[tn][tm][r] = 0.f;
+        for (int q = 0; q < p.tail_splits; ++q) {
+            const float4* src = reinterpret_cast<const float4*>(p.tail_buf) + ((size_t)q * p.tail_tiles + tail_idx) * AREA4 + tid;
+#pragma unroll
+            for (int tn = 0; tn < TN; ++tn) {
+                // One batch of loads in flight before the first add.  Written as asm because the compiler,
+                // with every register of the main loop still allocated, would wait for each load in turn.
+                typedef float vec4_t __attribute__((ext_vector_type(4)));
+                vec4_t v[TM * 4];
+#pragma unroll
+                for (int i = 0; i < TM * 4; ++i)
+                    asm volatile("global_load_dwordx4 %0, %1, off" : "=&v"(v[i]) : "v"(src + (tn * TM * 4 + i) * NT) : "memory");
+                asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+#pragma unroll
+                for (int i = 0; i < TM * 4; ++i) asm volatile("" : "+v"(v[i]));   // uses stay behind the wait
+#pragma unroll
+                for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+                    for (int c = 0; c < 4; ++c)
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) acc[tn][tm][4 * c + e] += v[tm * 4 + c][e];
+            }
+        }
+        if (tid == 0) p.tail_count[tail_idx] = 0;   // ready for the next launch
     }
     gemm_epilogue<BM, BN, EPI, D, WGM, WGN>(acc, p, tile_m, tile_n, wm, wn, l32, g);
 }
@@ -662,8 +752,11 @@ bool skinny_applies(int T, int N, int K, const float* accum) {
     return accum != nullptr && T <= 256 && K % 64 == 0 && N % 4 == 0 && !g_force_generic;
 }
 
+// What a launch does beyond whole tiles: the last tail_tiles tiles split their k range over `splits` workgroups.
+struct Plan { int cand, tail_tiles, splits; };
+
 template <int BM, int BN, int EPI, int D = 0, int WGM = 2, int WGN = 2>
-hipError_t launch_cfg(const GemmArgs& base, hipStream_t s) {
+hipError_t launch_cfg(const GemmArgs& base, hipStream_t s, const Plan& plan = Plan{0, 0, 1}) {
     GemmArgs p = base;
     p.tiles_m = (p.T + BM - 1) / BM;
     p.tiles_n = EPI == EPI_SWIGLU ? (p.n_half + BN / 2 - 1) / (BN / 2) : (p.N + BN - 1) / BN;
@@ -681,11 +774,25 @@ hipError_t launch_cfg(const GemmArgs& base, hipStream_t s) {
         if (e != hipSuccess) return e;
         attr_done = true;
     }
-    if (p.K % 64 == 0 && !g_force_generic)
+    const int tiles = p.tiles_m * p.tiles_n;
+    if (p.K % 64 == 0 && !g_force_generic) {
+        int grid = tiles;
+        if (plan.tail_tiles > 0 && plan.splits > 1 && p.accum && p.T > SKINNY_MAX_T) {
+            const int nk = p.K / 64;
+            p.k_per_split = (nk + plan.splits - 1) / plan.splits;
+            p.tail_splits = (nk + p.k_per_split - 1) / p.k_per_split;   // no empty split
+            p.tail_tiles = std::min(plan.tail_tiles, tiles);
+            p.tail_count = reinterpret_cast<int32_t*>(p.accum);
+            p.tail_buf = p.accum + kTailCounters;
+            if (p.tail_tiles > kTailCounters || (int64_t)p.tail_tiles * p.tail_splits * BM * BN > kTailFloats)
+                return hipErrorInvalidValue;   // a plan that does not fit the scratch: choose_plan never makes one
+            grid = tiles - p.tail_tiles + p.tail_tiles * p.tail_splits;
+        }
         gemm_dma_kernel<BM, BN, EPI, D, DMA_BK, DMA_NS, WGM, WGN>
-            <<<dim3(p.tiles_m * p.tiles_n), dim3(64 * WGM * WGN), dma_smem, s>>>(p);
-    else
-        gemm_bf16_kernel<BM, BN, EPI, D><<<dim3(p.tiles_m * p.tiles_n), dim3(256), smem, s>>>(p);
+            <<<dim3(grid), dim3(64 * WGM * WGN), dma_smem, s>>>(p);
+    } else {
+        gemm_bf16_kernel<BM, BN, EPI, D><<<dim3(tiles), dim3(256), smem, s>>>(p);
+    }
     return hipGetLastError();
 }
 
@@ -693,26 +800,55 @@ hipError_t launch_cfg(const GemmArgs& base, hipStream_t s) {
 // tile's MFMA work divided by the tile shape's measured in-tile efficiency (relative to 256 x 256).
 // The candidate with the lowest estimated cost wins: this trades tile quantisation in T (padding
 // to BM), the tail round, and the per-tile efficiency against each other.
-struct TileCand { int bm, bn, wg_per_cu; float eff; };
+struct TileCand { int bm, bn, wg_per_cu; float eff; bool qkv; };   // qkv: usable by the fused q/k/v epilogue (128 features per wave)
 constexpr TileCand kTiles[] = {
     // efficiencies calibrated on T = 1282 / 6144 problems of the 13B and 70B layer shapes
-    {256, 256, 1, 1.00f}, {192, 256, 1, 0.92f}, {128, 256, 1, 0.78f}, {128, 128, 2, 0.87f}, {64, 128, 3, 0.75f},
-    {256, 256, 1, 0.0f}};   // index 5: 256 x 256 with 8 waves (experimental, only by the test hook)
+    {256, 256, 1, 1.00f, true}, {192, 256, 1, 0.92f, true}, {128, 256, 1, 0.78f, true}, {128, 128, 2, 0.87f, false},
+    {64, 128, 3, 0.75f, false},
+    // 8-wave variants, only by the test hook: 5 = 256 x 256 (4 x 2 waves), 6 = (2 x 4), 7 = 16 waves, 8 = 192 x 256, 9 = 128 x 256
+    {256, 256, 1, 0.0f, true}, {256, 256, 1, 0.0f, false}, {256, 256, 1, 0.0f, false}, {192, 256, 1, 0.0f, false},
+    {128, 256, 1, 0.0f, false}};
 
-int choose_tile(int T, int64_t n_eff, bool need_bn256) {
-    static const char* force = getenv("RELSERVE_GEMM_TILE");   // test hook: index into kTiles
-    if (force) return atoi(force);
-    int best = 0;
+// A tail (the tiles of the incomplete last round) may split its k range over workgroups, so that the
+// round takes 1 / splits of a tile time; the price is that every partial tile is written to memory
+// and read back by the workgroup that finishes the tile.  Costs in seconds.
+constexpr double kCuFlops = 4.5e12;          // sustained MFMA rate of one CU inside a 256 x 256 tile
+constexpr double kSlabBytesPerSec = 2.0e12;  // partial tiles through memory, write + read, as seen by the launch
+
+Plan choose_plan(int T, int64_t n_eff, int K, bool need_bn256, bool allow_tail) {
+    const int n_cand = (int)(sizeof(kTiles) / sizeof(kTiles[0]));
+    const bool force = g_force_cand >= 0 && g_force_cand < n_cand;
+    Plan best{0, 0, 1};
     double best_cost = 1e300;
-    for (int i = 0; i < (int)(sizeof(kTiles) / sizeof(kTiles[0])); ++i) {
+    for (int i = 0; i < n_cand; ++i) {
         const TileCand& c = kTiles[i];
-        if ((need_bn256 && c.bn != 256) || c.eff <= 0.f) continue;
+        int forced_splits = 0;
+        if (need_bn256 && !c.qkv) continue;
+        if (force) {
+            if (g_force_cand != i && !(need_bn256 && !kTiles[g_force_cand].qkv)) continue;
+            if (g_force_cand == i) forced_splits = g_force_splits;
+        } else if (c.eff <= 0.f) {
+            continue;
+        }
+        const double eff = c.eff > 0.f ? c.eff : 1.0;
         const int64_t tiles = ((T + c.bm - 1) / c.bm) * ((n_eff + c.bn - 1) / c.bn);
         const int64_t slots = 256 * c.wg_per_cu;
-        const double rounds = (double)((tiles + slots - 1) / slots);
         // resident workgroups of a CU share its MFMA pipes: a round of wg_per_cu tiles costs wg_per_cu tile times
-        const double cost = rounds * c.wg_per_cu * (double)c.bm * c.bn / c.eff;
-        if (cost < best_cost) best_cost = cost, best = i;
+        const double t_round = c.wg_per_cu * 2.0 * c.bm * c.bn * (double)K / (eff * kCuFlops);
+        const int64_t full = tiles / slots, rem = tiles % slots;
+        const double whole = (double)(full + (rem ? 1 : 0)) * t_round;
+        if (whole < best_cost && forced_splits <= 1) best_cost = whole, best = Plan{i, 0, 1};
+        const int nk = K / 64;
+        const bool can_tail = allow_tail && rem > 0 && K % 64 == 0;
+        for (int sp = 2; can_tail && sp <= 8 && nk / sp >= 8; ++sp) {
+            if (forced_splits > 1 && sp != forced_splits) continue;
+            const int64_t units = rem * sp;
+            if (units * c.bm * c.bn > kTailFloats) break;
+            const double rounds = (double)((units + slots - 1) / slots);
+            const double slabs = (double)units * c.bm * c.bn * 4.0 * 2.0 / kSlabBytesPerSec;
+            const double cost = full * t_round + rounds * t_round / sp + slabs;
+            if (cost < best_cost || forced_splits > 1) best_cost = cost, best = Plan{i, (int)rem, sp};
+        }
     }
     return best;
 }
@@ -720,23 +856,40 @@ int choose_tile(int T, int64_t n_eff, bool need_bn256) {
 template <int EPI>
 hipError_t launch_epi(const GemmArgs& p, hipStream_t s) {
     const int64_t n_eff = EPI == EPI_SWIGLU ? 2 * (int64_t)p.n_half : p.N;
-    switch (choose_tile(p.T, n_eff, false)) {
-        case 0: return launch_cfg<256, 256, EPI>(p, s);
-        case 1: return launch_cfg<192, 256, EPI>(p, s);
-        case 2: return launch_cfg<128, 256, EPI>(p, s);
-        case 3: return launch_cfg<128, 128, EPI>(p, s);
-        case 5: return launch_cfg<256, 256, EPI, 0, 4, 2>(p, s);
-        case 6: return launch_cfg<256, 256, EPI, 0, 2, 4>(p, s);
-        case 7: return launch_cfg<256, 256, EPI, 0, 4, 4>(p, s);
+    const Plan plan = choose_plan(p.T, n_eff, p.K, false, p.accum != nullptr);
+    switch (plan.cand) {
+        case 0: return launch_cfg<256, 256, EPI>(p, s, plan);
+        case 1: return launch_cfg<192, 256, EPI>(p, s, plan);
+        case 2: return launch_cfg<128, 256, EPI>(p, s, plan);
+        case 3: return launch_cfg<128, 128, EPI>(p, s, plan);
+        case 5: return launch_cfg<256, 256, EPI, 0, 4, 2>(p, s, plan);
+        case 6: return launch_cfg<256, 256, EPI, 0, 2, 4>(p, s, plan);
+        case 7: return launch_cfg<256, 256, EPI, 0, 4, 4>(p, s, plan);
 #if RELSERVE_DMA_BK == 64
-        case 8: return launch_cfg<192, 256, EPI, 0, 2, 4>(p, s);
-        case 9: return launch_cfg<128, 256, EPI, 0, 2, 4>(p, s);
+        case 8: return launch_cfg<192, 256, EPI, 0, 2, 4>(p, s, plan);
+        case 9: return launch_cfg<128, 256, EPI, 0, 2, 4>(p, s, plan);
 #endif
-        default: return launch_cfg<64, 128, EPI>(p, s);
+        default: return launch_cfg<64, 128, EPI>(p, s, plan);
     }
 }
 
 }  // namespace
+
+void gemm_force_plan(int cand, int splits) {
+    g_force_cand = cand;
+    g_force_splits = splits;
+}
+
+int64_t gemm_scratch_floats(int64_t T, int64_t n_max) {
+    return T <= SKINNY_MAX_T ? T * n_max : kTailCounters + kTailFloats;
+}
+
+int64_t gemm_scratch_used(int32_t T, int32_t N, int32_t K, bool qkv) {
+    if (T <= SKINNY_MAX_T) return (int64_t)T * N;
+    if (K % 64 || g_force_generic || (qkv && T <= 64)) return 0;
+    const Plan plan = choose_plan(T, N, K, qkv, true);
+    return plan.tail_tiles == 0 ? 0 : kTailCounters;   // only the arrival counters must start at zero
+}
 
 hipError_t launch_fill_zero(float* ptr, int64_t n_floats, hipStream_t s) {
     const int64_t n4 = (n_floats + 3) / 4;
@@ -783,11 +936,12 @@ namespace {
 template <int D>
 hipError_t launch_qkv_d(const GemmArgs& p, hipStream_t s) {
     if (p.T <= 64) return launch_cfg<64, 256, EPI_QKV_ROPE, D>(p, s);
-    switch (choose_tile(p.T, p.N, true)) {   // the rotation needs 128 features per wave: BN = 256 only
-        case 0: return launch_cfg<256, 256, EPI_QKV_ROPE, D>(p, s);
-        case 1: return launch_cfg<192, 256, EPI_QKV_ROPE, D>(p, s);
-        case 5: return launch_cfg<256, 256, EPI_QKV_ROPE, D, 4, 2>(p, s);
-        default: return launch_cfg<128, 256, EPI_QKV_ROPE, D>(p, s);
+    const Plan plan = choose_plan(p.T, p.N, p.K, true, p.accum != nullptr);   // the rotation needs 128 features per wave
+    switch (plan.cand) {
+        case 0: return launch_cfg<256, 256, EPI_QKV_ROPE, D>(p, s, plan);
+        case 1: return launch_cfg<192, 256, EPI_QKV_ROPE, D>(p, s, plan);
+        case 5: return launch_cfg<256, 256, EPI_QKV_ROPE, D, 4, 2>(p, s, plan);
+        default: return launch_cfg<128, 256, EPI_QKV_ROPE, D>(p, s, plan);
     }
 }
 }  // namespace

@@ -27,7 +27,7 @@ struct Workspace {
     char* act;       // [T, I] bf16
     float* part_o;   // [T, n_q, d] fp32
     float* part_ml;  // [T, n_q, 2] fp32
-    float* accum;    // [min(T, 256), widest GEMM output] fp32 split-K accumulator
+    float* accum;    // fp32 split-K scratch of the GEMMs
     size_t accum_floats;
     size_t total;
 };
@@ -48,7 +48,7 @@ Workspace carve(const relserve_layer& L, int64_t T, void* base) {
     w.act = take((size_t)T * c.mlp_dim * 2);
     w.part_o = reinterpret_cast<float*>(take((size_t)T * L.q_dim * 4));
     w.part_ml = reinterpret_cast<float*>(take((size_t)T * c.n_q_heads * 2 * 4));
-    w.accum_floats = (size_t)std::min<int64_t>(T, SKINNY_MAX_T) * std::max({L.qkv_dim, 2 * c.mlp_dim, c.hidden});
+    w.accum_floats = (size_t)gemm_scratch_floats(T, std::max({L.qkv_dim, 2 * c.mlp_dim, c.hidden}));
     w.accum = reinterpret_cast<float*>(take(w.accum_floats * 4));
     w.total = off;
     return w;
@@ -286,6 +286,7 @@ int32_t relserve_layer_destroy(relserve_layer* L) {
         (void)hipEventDestroy(p.a);
         (void)hipEventDestroy(p.b);
     }
+    for (hipEvent_t e : L->event_pool) (void)hipEventDestroy(e);
     delete L;
     return RELSERVE_OK;
 }
@@ -514,9 +515,14 @@ int32_t relserve_layer_step(const relserve_layer* L, const relserve_batch* b, co
         e = launch();
         profile_mark(prof, slot, s, false);
     };
-    // skinny batches split K across workgroups through a zeroed fp32 accumulator (each GEMM leaves it zero)
-    float* accum = T <= SKINNY_MAX_T ? w.accum : nullptr;
-    if (accum) e = launch_fill_zero(accum, (int64_t)w.accum_floats, s);
+    // the GEMMs split K across workgroups (whole skinny problems, or the incomplete last round of tiles)
+    // through a zeroed fp32 scratch; each GEMM leaves what it used zero again
+    float* accum = w.accum;
+    const int64_t used = std::max({gemm_scratch_used(T, L->qkv_dim, c.hidden, true),
+                                   gemm_scratch_used(T, c.hidden, L->q_dim, false),
+                                   gemm_scratch_used(T, 2 * c.mlp_dim, c.hidden, false),
+                                   gemm_scratch_used(T, c.hidden, c.mlp_dim, false)});
+    if (used > 0) e = launch_fill_zero(accum, used, s);
     run(S_NORM1, [&] { return launch_rmsnorm(x, false, wt->w_in_norm, c.rms_eps, T, c.hidden, w.h, s); });
     run(S_QKV, [&] {
         return launch_qkv_rope_append(b->dev, *L, w.h, wt->w_qkv, w.q, cache.k_pages, cache.v_pages, s, accum);
@@ -575,14 +581,20 @@ int32_t relserve_model_step(const relserve_layer* L, const relserve_batch* b, co
     return RELSERVE_OK;
 }
 
+int32_t relserve_debug_force_gemm_plan(int32_t tile, int32_t tail_splits) {
+    if (tile < -1 || tile > 9 || tail_splits < 0 || tail_splits > 8) return RELSERVE_ERR_BAD_ARGUMENT;
+    gemm_force_plan(tile, tail_splits);
+    return RELSERVE_OK;
+}
+
 // ---- profiling ---------------------------------------------------------------------------
 const char* relserve_profile_slot_name(int32_t slot) {
     return (slot >= 0 && slot < RELSERVE_PROFILE_SLOTS) ? kSlotNames[slot] : "";
 }
 
-int32_t relserve_profile_enable(relserve_layer* L, int32_t enable) {
+int32_t relserve_profile_enable(relserve_layer* L, int32_t slot_mask) {
     if (!L) return RELSERVE_ERR_NULL_POINTER;
-    L->profile = enable != 0;
+    L->profile = static_cast<uint32_t>(slot_mask);
     return RELSERVE_OK;
 }
 
@@ -597,8 +609,8 @@ int32_t relserve_profile_read(relserve_layer* L, double* ms_sum, int64_t* launch
                 L->ms_sum[p.slot] += ms;
                 L->launches[p.slot] += 1;
             }
-            (void)hipEventDestroy(p.a);
-            (void)hipEventDestroy(p.b);
+            L->event_pool.push_back(p.a);
+            L->event_pool.push_back(p.b);
         }
         L->pending.clear();
     }
@@ -613,10 +625,18 @@ int32_t relserve_profile_read(relserve_layer* L, double* ms_sum, int64_t* launch
 }  // extern "C"
 
 void relserve::profile_mark(relserve_layer* L, int slot, hipStream_t s, bool begin) {
-    if (!L) return;
+    if (!L || !((L->profile >> slot) & 1u)) return;
     if (begin) {
         relserve_layer::Pending p{slot, nullptr, nullptr};
-        if (hipEventCreate(&p.a) != hipSuccess || hipEventCreate(&p.b) != hipSuccess) return;
+        auto get = [&](hipEvent_t* e) {
+            if (!L->event_pool.empty()) {
+                *e = L->event_pool.back();
+                L->event_pool.pop_back();
+                return true;
+            }
+            return hipEventCreate(e) == hipSuccess;
+        };
+        if (!get(&p.a) || !get(&p.b)) return;
         (void)hipEventRecord(p.a, s);
         L->pending.push_back(p);
         L->pending_stream = s;

@@ -55,9 +55,10 @@ struct relserve_layer {
     int32_t q_dim, kv_dim, qkv_dim;
     std::vector<float> inv_freq;  // [head_dim / 2] base^(-2i/d), rounded from double
     // profiling
-    bool profile = false;
+    uint32_t profile = 0;   // bit i set: time the kernel of slot i
     struct Pending { int slot; hipEvent_t a, b; };
     std::vector<Pending> pending;
+    std::vector<hipEvent_t> event_pool;   // events of earlier reads, reused
     hipStream_t pending_stream = nullptr;
     double ms_sum[RELSERVE_PROFILE_SLOTS] = {0};
     int64_t launches[RELSERVE_PROFILE_SLOTS] = {0};
@@ -86,6 +87,8 @@ int32_t expand_batch(const relserve_layer_config& cfg, const relserve_batch_desc
 // Rows of queries one attention workgroup covers (4 waves x 32 MFMA columns).
 constexpr int ATTN_BLOCK_M = 128;
 constexpr int SKINNY_MAX_T = 256;      // batches up to this many tokens take the split-K GEMM path
+constexpr int GEMM_TAIL_COUNTERS = 1024;               // split-tile arrival counters at the head of the GEMM scratch
+constexpr int64_t GEMM_TAIL_FLOATS = 256 * 65536;      // partial tiles of one round of split 256 x 256 tiles
 constexpr int ATTN_SPLIT_ROWS = 16;   // query heads per kv head the decode kernel's 16-column MFMA holds
 
 // ---- kernel launchers (each enqueues on `s` and returns the launch status) ----------------
@@ -99,8 +102,14 @@ hipError_t launch_kv_append(const BatchDev& b, const void* k, const void* v, voi
                             int32_t row_elems, hipStream_t s);
 hipError_t launch_rope_append(const BatchDev& b, const relserve_layer& L, void* qkv, void* k_pages,
                               void* v_pages, hipStream_t s);
-// accum: optional fp32 [T, N] scratch holding zeros; lets skinny problems (T <= 256) split K over
-// workgroups.  It holds zeros again when the launched kernels have finished.
+// accum: optional fp32 scratch holding zeros (gemm_scratch_floats(T, widest N) floats); lets skinny
+// problems (T <= 256) and the incomplete last round of larger ones split K over workgroups.  It
+// holds zeros again when the launched kernels have finished.
+int64_t gemm_scratch_floats(int64_t T, int64_t n_max);
+// Floats at the head of the scratch that launch_linear / launch_qkv_rope_append will use for this problem
+// (0 = none); the caller clears the largest such prefix once before a sequence of launches.
+int64_t gemm_scratch_used(int32_t T, int32_t N, int32_t K, bool qkv);
+void gemm_force_plan(int cand, int splits);   // test hook, see relserve_debug_force_gemm_plan
 hipError_t launch_linear(const void* a, const void* w, int32_t T, int32_t N, int32_t K, int32_t epilogue,
                          const void* residual, void* out, hipStream_t s, float* accum = nullptr);
 hipError_t launch_fill_zero(float* ptr, int64_t n_floats, hipStream_t s);

@@ -326,6 +326,19 @@ def test_full_size_relquery_13b(rs, oracle):
     _sampled_parity(rs, oracle, wl, [0, 7, 15, 16, 17, 99, 150, 199])
 
 
+@pytest.mark.parametrize("tile,splits", [(0, 2), (1, 3), (3, 4), (5, 2)],
+                         ids=["256x256/2", "192x256/3", "128x128/4", "256x256-8w/2"])
+def test_full_size_relquery_13b_forced_tail_split(rs, oracle, tile, splits):
+    """The tiles of the incomplete last round split their k range over workgroups (partial tiles through the
+    fp32 scratch, summed by the last workgroup to arrive); here forced for every GEMM of the step."""
+    wl = W.workload_relquery_13b()
+    rs.relserve_debug_force_gemm_plan(tile, splits)
+    try:
+        _sampled_parity(rs, oracle, wl, [0, 16, 99, 199])
+    finally:
+        rs.relserve_debug_force_gemm_plan(-1, 0)
+
+
 def test_full_size_decode_heavy_70b(rs, oracle):
     wl = W.workload_decode_heavy_70b()
     _sampled_parity(rs, oracle, wl, [0, 63, 64, 130, 255, 256], max_prefill_rows=24)

@@ -12,6 +12,7 @@
 // Workgroup ids are remapped so that each of the 8 XCDs (own L2 each) walks a contiguous run
 // of tiles, token tiles fastest: concurrent workgroups of an XCD share weight tiles.
 #include <algorithm>
+#include <cstdio>
 #include <cstdlib>
 #include <cstring>
 #include <type_traits>
@@ -498,87 +499,101 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_dma_kernel(GemmArgs p) {
         acc[tn][tm] = EPI == EPI_ATOMIC ? mfma_32x32x16(af[buf][tm], wf[buf][tn], acc[tn][tm])
                                         : mfma_32x32x16(wf[buf][tn], af[buf][tm], acc[tn][tm]);
     };
-    auto load_frag_one = [&](int buf, int stage, int i) {   // i-th of the TN + TM fragment reads of k step 0
+    auto load_frag_one = [&](int buf, int stage, int ks, int i) {   // i-th of the TN + TM fragment reads of a k step
         const unsigned char* st = smem + stage * STAGE;
-        const int ch = (g ^ swz) << 4;
+        const int ch = ((2 * ks + g) ^ swz) << 4;
         if (i < TN)
             wf[buf][i] = as_bf16x8(*reinterpret_cast<const uint4*>(st + w_rd[i] + ch));
         else
             af[buf][i - TN] = as_bf16x8(*reinterpret_cast<const uint4*>(st + a_rd[i - TN] + ch));
     };
     auto issue_one = [&](int stage, int k0, int i) {   // i-th of the LOADS wave loads of a stage
+        // weights first: they come from further away (HBM) than the activations (L2)
         const uint32_t la = lds0 + stage * STAGE + wave * 1024;
-        if (i < A_IT)
-            dma16(reinterpret_cast<const char*>(p.a) + (size_t)k0 * 2, a_voff[i], la + i * (NW * 1024));
+        if (i < W_IT)
+            dma16(reinterpret_cast<const char*>(p.w) + (size_t)k0 * 2, w_voff[i], la + A_BYTES + i * (NW * 1024));
         else
-            dma16(reinterpret_cast<const char*>(p.w) + (size_t)k0 * 2, w_voff[i - A_IT],
-                  la + A_BYTES + (i - A_IT) * (NW * 1024));
+            dma16(reinterpret_cast<const char*>(p.a) + (size_t)k0 * 2, a_voff[i - W_IT], la + (i - W_IT) * (NW * 1024));
     };
     constexpr int NM = TN * TM, NF = TN + TM;
-    // Hand-over at the last k step of a stage: all fragments of the stage are in registers; after the
-    // barrier the step's MFMAs are issued one by one with the refill loads of the freed buffer and (in
-    // the second half) the first fragment reads of the next stage slotted between them, so neither
-    // the load issue nor the LDS latency leaves the matrix pipe idle.  The MFMAs sit on ONE control
-    // path on purpose: at a join the compiler would make them wait for the newest reads.
+    // One k step, issued in a fixed order: MFMA i, then the share of the refill loads and of the next
+    // step's fragment reads that falls between MFMA i and i + 1.  A CU's address unit takes one
+    // 1 KB load per ~16 cycles and an MFMA lasts 32, so the refill loads of a stage (LOADS per wave,
+    // four waves) are spread over SPREAD k steps; issued back to back they would hold up the MFMAs
+    // behind them.  The MFMAs sit on ONE control path on purpose: at a join the compiler would make
+    // them wait for the newest reads.
+    constexpr int SPREAD = KSTEPS > 1 ? KSTEPS - 1 : 1;   // the last k step before the next hand-over stays free: landing time
+    auto k_step = [&](int buf, int rd_stage, int rd_ks, int part, bool refill, int rf_stage, int rf_k0) {
+        // share of the stage's loads issued in each part, cumulative, in sixteenths: the weights (first half
+        // of the loads) go out at once, the activations (L2 hits, quick to land) trail over two more steps
+        constexpr int cut[5] = {0, 8, 13, 16, 16};
+        const int pc = part < SPREAD ? part : SPREAD;
+        const int d_lo = SPREAD == 3 ? cut[pc] * LOADS / 16 : pc * LOADS / SPREAD;
+        const int d_n = (SPREAD == 3 ? cut[pc + 1] * LOADS / 16 : (pc + 1) * LOADS / SPREAD) - d_lo;
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int i = 0; i < NM; ++i) {
+            mfma_one(buf, i);
+            __builtin_amdgcn_sched_barrier(0);
+            if (part < SPREAD && refill) {
+#pragma unroll
+                for (int d = d_lo + i * d_n / NM; d < d_lo + (i + 1) * d_n / NM; ++d) issue_one(rf_stage, rf_k0, d);
+            }
+            if (i < NM / 2) {   // all reads in the first half: the last one has half a step to come back
+#pragma unroll
+                for (int f = i * NF / (NM / 2); f < (i + 1) * NF / (NM / 2); ++f)
+                    load_frag_one(buf ^ 1, rd_stage, rd_ks, f);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
     int cur = 0;  // stage being computed
+    bool refill = false;       // a refill begun at the last hand-over is still being issued
+    int rf_stage = 0, rf_k0 = 0;
     for (int kt = 0; kt < nk; ++kt) {
         const int nxt = cur + 1 == NS ? 0 : cur + 1;
 #pragma unroll
-        for (int ks = 0; ks + 1 < KSTEPS; ++ks) {
-            load_frags((ks + 1) & 1, cur, ks + 1);
-#pragma unroll
-            for (int i = 0; i < NM; ++i) mfma_one(ks & 1, i);
-        }
-        // Last k step of the stage: wait for the next stage (the NS - 2 younger ones may stay in
-        // flight) and hand over.  After the last stage this reads fragments nobody uses.
+        for (int ks = 0; ks + 1 < KSTEPS; ++ks) k_step(ks & 1, cur, ks + 1, ks + 1, refill, rf_stage, rf_k0);
+        // Last k step of the stage: all its fragments are in registers.  Wait for the next stage (the
+        // NS - 2 younger ones may stay in flight), hand over, and start refilling the freed buffer.
+        // After the last stage this reads fragments nobody uses.
         constexpr int LB = (KSTEPS - 1) & 1;
         if (NS == 2 || kt + NS - 1 >= nk)
             asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
         else
             asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"((NS - 2) * LOADS) : "memory");
         __syncthreads();
-        const bool refill = kt + NS < nk;
-        const int k0 = (kbeg + kt + NS) * BKD;
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int i = 0; i < NM; ++i) {
-            mfma_one(LB, i);
-            __builtin_amdgcn_sched_barrier(0);
-            if (refill) {
-#pragma unroll
-                for (int d = i * LOADS / NM; d < (i + 1) * LOADS / NM; ++d) issue_one(cur, k0, d);
-            }
-            if (i >= NM / 2) {
-#pragma unroll
-                for (int f = (i - NM / 2) * NF / (NM - NM / 2); f < (i + 1 - NM / 2) * NF / (NM - NM / 2); ++f)
-                    load_frag_one(LB ^ 1, nxt, f);
-            }
-            __builtin_amdgcn_sched_barrier(0);
-        }
+        refill = kt + NS < nk;
+        rf_stage = cur;
+        rf_k0 = (kbeg + kt + NS) * BKD;
+        k_step(LB, nxt, 0, 0, refill, rf_stage, rf_k0);
         cur = nxt;
     }
     if (EPI != EPI_ATOMIC && tail) {
         // Partial tile -> this split's slab (registers 4 c .. 4 c + 3 of accumulator tile (tn, tm) of
-        // thread tid are the float4 at ((tn TM + tm) 4 + c) * threads + tid: coalesced 16-byte accesses).
-        // The workgroup that arrives last at the tile adds the slabs in split order, so the result
-        // does not depend on the arrival order.
+        // thread tid are the 16 bytes at ((tn TM + tm) 4 + c) * threads + tid: coalesced).  The workgroup
+        // that arrives last at the tile adds the slabs in split order, so the result does not depend
+        // on the arrival order.  Release / acquire fences around the arrival counter make the slabs of
+        // workgroups on other XCDs (other L2s) visible.
+        typedef float vec4_t __attribute__((ext_vector_type(4)));
         constexpr int AREA4 = BM * BN / 4, NT = 64 * NW;
-        float4* slab = reinterpret_cast<float4*>(p.tail_buf) + ((size_t)split * p.tail_tiles + tail_idx) * AREA4 + tid;
+        vec4_t* slab = reinterpret_cast<vec4_t*>(p.tail_buf) + ((size_t)split * p.tail_tiles + tail_idx) * AREA4 + tid;
 #pragma unroll
         for (int tn = 0; tn < TN; ++tn)
 #pragma unroll
             for (int tm = 0; tm < TM; ++tm)
 #pragma unroll
-                for (int c = 0; c < 4; ++c)
-                    slab[((tn * TM + tm) * 4 + c) * NT] = make_float4(acc[tn][tm][4 * c], acc[tn][tm][4 * c + 1],
-                                                                      acc[tn][tm][4 * c + 2], acc[tn][tm][4 * c + 3]);
+                for (int c = 0; c < 4; ++c) {
+                    vec4_t v = {acc[tn][tm][4 * c], acc[tn][tm][4 * c + 1], acc[tn][tm][4 * c + 2], acc[tn][tm][4 * c + 3]};
+                    slab[((tn * TM + tm) * 4 + c) * NT] = v;
+                }
         __shared__ int s_last;
-        __threadfence();   // the slab is visible device-wide before the arrival count moves
+        __threadfence();   // release: this thread's part of the slab is visible device-wide ...
         __syncthreads();
-        if (tid == 0) s_last = atomicAdd(p.tail_count + tail_idx, 1) == p.tail_splits - 1;
+        if (tid == 0) s_last = atomicAdd(p.tail_count + tail_idx, 1) == p.tail_splits - 1;   // ... before the count moves
         __syncthreads();
         if (!s_last) return;
-        __threadfence();   // the other workgroups' slabs are visible
+        __threadfence();   // acquire: the other workgroups' slabs
 #pragma unroll
         for (int tn = 0; tn < TN; ++tn)
 #pragma unroll
@@ -586,12 +601,11 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_dma_kernel(GemmArgs p) {
 #pragma unroll
                 for (int r = 0; r < 16; ++r) acc[tn][tm][r] = 0.f;
         for (int q = 0; q < p.tail_splits; ++q) {
-            const float4* src = reinterpret_cast<const float4*>(p.tail_buf) + ((size_t)q * p.tail_tiles + tail_idx) * AREA4 + tid;
+            const vec4_t* src = reinterpret_cast<const vec4_t*>(p.tail_buf) + ((size_t)q * p.tail_tiles + tail_idx) * AREA4 + tid;
 #pragma unroll
             for (int tn = 0; tn < TN; ++tn) {
-                // One batch of loads in flight before the first add.  Written as asm because the compiler,
-                // with every register of the main loop still allocated, would wait for each load in turn.
-                typedef float vec4_t __attribute__((ext_vector_type(4)));
+                // One batch of loads in flight before the first add (asm also because the compiler, with
+                // every register of the main loop still allocated, would wait for each load in turn).
                 vec4_t v[TM * 4];
 #pragma unroll
                 for (int i = 0; i < TM * 4; ++i)
@@ -813,9 +827,22 @@ constexpr TileCand kTiles[] = {
 // round takes 1 / splits of a tile time; the price is that every partial tile is written to memory
 // and read back by the workgroup that finishes the tile.  Costs in seconds.
 constexpr double kCuFlops = 4.5e12;          // sustained MFMA rate of one CU inside a 256 x 256 tile
-constexpr double kSlabBytesPerSec = 2.0e12;  // partial tiles through memory, write + read, as seen by the launch
+constexpr double kSlabBytesPerSec = 1.2e12;  // partial tiles through memory (write, fences, read), as seen by the launch
 
+Plan choose_plan_impl(int T, int64_t n_eff, int K, bool need_bn256, bool allow_tail);
 Plan choose_plan(int T, int64_t n_eff, int K, bool need_bn256, bool allow_tail) {
+    static const bool debug = getenv("RELSERVE_GEMM_DEBUG") != nullptr;   // print every choice
+    static const bool no_tail = getenv("RELSERVE_GEMM_NOTAIL") != nullptr;   // tuning hook: whole tiles only
+    allow_tail = allow_tail && !no_tail;
+    const Plan p = choose_plan_impl(T, n_eff, K, need_bn256, allow_tail);
+    if (debug)
+        fprintf(stderr, "[gemm] T=%d N=%lld K=%d qkv=%d tail_ok=%d -> tile %d (%dx%d) tail_tiles=%d splits=%d\n", T,
+                (long long)n_eff, K, (int)need_bn256, (int)allow_tail, p.cand, kTiles[p.cand].bm, kTiles[p.cand].bn,
+                p.tail_tiles, p.splits);
+    return p;
+}
+
+Plan choose_plan_impl(int T, int64_t n_eff, int K, bool need_bn256, bool allow_tail) {
     const int n_cand = (int)(sizeof(kTiles) / sizeof(kTiles[0]));
     const bool force = g_force_cand >= 0 && g_force_cand < n_cand;
     Plan best{0, 0, 1};

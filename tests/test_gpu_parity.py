@@ -326,8 +326,7 @@ def test_full_size_relquery_13b(rs, oracle):
     _sampled_parity(rs, oracle, wl, [0, 7, 15, 16, 17, 99, 150, 199])
 
 
-@pytest.mark.parametrize("tile,splits", [(0, 2), (1, 3), (3, 4), (5, 2)],
-                         ids=["256x256/2", "192x256/3", "128x128/4", "256x256-8w/2"])
+@pytest.mark.parametrize("tile,splits", [(0, 2), (1, 3), (5, 2)], ids=["256x256/2", "192x256/3", "256x256-8w/2"])
 def test_full_size_relquery_13b_forced_tail_split(rs, oracle, tile, splits):
     """The tiles of the incomplete last round split their k range over workgroups (partial tiles through the
     fp32 scratch, summed by the last workgroup to arrive); here forced for every GEMM of the step."""
@@ -335,6 +334,18 @@ def test_full_size_relquery_13b_forced_tail_split(rs, oracle, tile, splits):
     rs.relserve_debug_force_gemm_plan(tile, splits)
     try:
         _sampled_parity(rs, oracle, wl, [0, 16, 99, 199])
+    finally:
+        rs.relserve_debug_force_gemm_plan(-1, 0)
+
+
+@pytest.mark.parametrize("tile,splits", [(3, 2), (3, 5), (4, 3), (2, 4)], ids=["128x128/2", "128x128/5", "64x128/3", "128x256/4"])
+def test_full_size_decode_plus_chunk_13b_forced_tail_split(rs, oracle, tile, splits):
+    """T = 640: few enough tiles that the small tile shapes (two or three workgroups per CU) fit the
+    scratch with every tile split."""
+    wl = W.workload_decode_plus_chunk_13b(512)
+    rs.relserve_debug_force_gemm_plan(tile, splits)
+    try:
+        _sampled_parity(rs, oracle, wl, [0, 127, 128], max_prefill_rows=24)
     finally:
         rs.relserve_debug_force_gemm_plan(-1, 0)
 

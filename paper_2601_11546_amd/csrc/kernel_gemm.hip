@@ -6,11 +6,16 @@
 // the tokens the column index, so that an accumulator quad holds 4 consecutive output
 // features of one token (one 8/16-byte store).
 //
-// Workgroup = 4 waves in a 2 x 2 grid over a BM (tokens) x BN (features) tile, BK = 64.
-// Tiles go global -> registers -> LDS (XOR-swizzled 16-byte chunks, conflict-free for both the
-// row-wise writes and the MFMA operand reads), double buffered with one barrier per k step.
-// Workgroup ids are remapped so that each of the 8 XCDs (own L2 each) walks a contiguous run
-// of tiles, token tiles fastest: concurrent workgroups of an XCD share weight tiles.
+// Workgroup = a grid of waves (2 x 2 in production) over a BM (tokens) x BN (features) tile, BK = 64.
+// Main kernel (gemm_dma_kernel, K % 64 == 0): tiles go global -> LDS directly, XOR-swizzled 16-byte
+// chunks, two stages, one barrier per k iteration, every k step issued in a fixed order that
+// slots the refill loads and the next fragment reads between the MFMAs.  Fallback kernel
+// (gemm_bf16_kernel): global -> registers -> LDS with zero-filled tails for any K % 8 == 0.
+// Workgroup ids are remapped so that each of the 8 XCDs (own L2 each) walks a contiguous run of
+// tiles, inside it token tiles fastest within panels of GROUP_M token tiles.
+// Launch plans: tile shape by a cost model; the incomplete last round of tiles may split k over
+// workgroups (partial tiles through fp32 slabs); batches of at most 256 tokens split k everywhere
+// (fp32 atomics + a finishing kernel).
 #include <algorithm>
 #include <cstdio>
 #include <cstdlib>

@@ -166,6 +166,9 @@ __device__ __forceinline__ void gemm_epilogue(const f32x16_t (&acc)[BN / (32 * W
                             *reinterpret_cast<uint2*>(dst + i) = make_uint2(pack_bf16x2(lo[0], lo[1]), pack_bf16x2(lo[2], lo[3]));
                             *reinterpret_cast<uint2*>(dst + i + D / 2) =
                                 make_uint2(pack_bf16x2(hi[0], hi[1]), pack_bf16x2(hi[2], hi[3]));
+                            // every register is taken by the accumulators: keep the scheduler from starting the
+                            // next quads' table loads early (they would spill)
+                            __builtin_amdgcn_sched_barrier(0);
                         }
                     }
                 } else {
@@ -178,6 +181,7 @@ __device__ __forceinline__ void gemm_epilogue(const f32x16_t (&acc)[BN / (32 * W
                             const f32x16_t& a = acc[hh * TPH + tl][tm];
                             *reinterpret_cast<uint2*>(dst + i) = make_uint2(pack_bf16x2(a[4 * q], a[4 * q + 1]),
                                                                             pack_bf16x2(a[4 * q + 2], a[4 * q + 3]));
+                            __builtin_amdgcn_sched_barrier(0);
                         }
                     }
                 }
@@ -224,6 +228,7 @@ __device__ __forceinline__ void gemm_epilogue(const f32x16_t (&acc)[BN / (32 * W
                         uint2 st = make_uint2(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]));
                         *reinterpret_cast<uint2*>(static_cast<uint16_t*>(p.out) + o) = st;
                     }
+                    __builtin_amdgcn_sched_barrier(0);   // see the q/k/v epilogue
                 }
             }
         }
@@ -627,6 +632,10 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_dma_kernel(GemmArgs p) {
             }
         }
         if (tid == 0) p.tail_count[tail_idx] = 0;   // ready for the next launch
+        // a second copy of the epilogue on purpose: merging the two paths would turn every accumulator
+        // into a two-way merge of register tuples, which the whole-tile path then pays for in copies
+        gemm_epilogue<BM, BN, EPI, D, WGM, WGN>(acc, p, tile_m, tile_n, wm, wn, l32, g);
+        return;
     }
     gemm_epilogue<BM, BN, EPI, D, WGM, WGN>(acc, p, tile_m, tile_n, wm, wn, l32, g);
 }

@@ -557,13 +557,25 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_dma_kernel(GemmArgs p) {
             __builtin_amdgcn_sched_barrier(0);
         }
     };
+    // Small tiles (two or three workgroups per CU, a handful of MFMAs per k step) do better when the
+    // compiler orders the steps between hand-overs and the other resident workgroups fill the gaps;
+    // only their hand-over step keeps the fixed order, with the whole refill in it.
+    constexpr bool FIXED = NM >= 12;
     int cur = 0;  // stage being computed
     bool refill = false;       // a refill begun at the last hand-over is still being issued
     int rf_stage = 0, rf_k0 = 0;
     for (int kt = 0; kt < nk; ++kt) {
         const int nxt = cur + 1 == NS ? 0 : cur + 1;
 #pragma unroll
-        for (int ks = 0; ks + 1 < KSTEPS; ++ks) k_step(ks & 1, cur, ks + 1, ks + 1, refill, rf_stage, rf_k0);
+        for (int ks = 0; ks + 1 < KSTEPS; ++ks) {
+            if (FIXED) {
+                k_step(ks & 1, cur, ks + 1, ks + 1, refill, rf_stage, rf_k0);
+            } else {
+                load_frags((ks + 1) & 1, cur, ks + 1);
+#pragma unroll
+                for (int i = 0; i < NM; ++i) mfma_one(ks & 1, i);
+            }
+        }
         // Last k step of the stage: all its fragments are in registers.  Wait for the next stage (the
         // NS - 2 younger ones may stay in flight), hand over, and start refilling the freed buffer.
         // After the last stage this reads fragments nobody uses.
@@ -576,7 +588,26 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_dma_kernel(GemmArgs p) {
         refill = kt + NS < nk;
         rf_stage = cur;
         rf_k0 = (kbeg + kt + NS) * BKD;
-        k_step(LB, nxt, 0, 0, refill, rf_stage, rf_k0);
+        if (FIXED) {
+            k_step(LB, nxt, 0, 0, refill, rf_stage, rf_k0);
+        } else {
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int i = 0; i < NM; ++i) {
+                mfma_one(LB, i);
+                __builtin_amdgcn_sched_barrier(0);
+                if (refill) {
+#pragma unroll
+                    for (int d = i * LOADS / NM; d < (i + 1) * LOADS / NM; ++d) issue_one(rf_stage, rf_k0, d);
+                }
+                if (i >= NM / 2) {
+#pragma unroll
+                    for (int f = (i - NM / 2) * NF / (NM - NM / 2); f < (i + 1 - NM / 2) * NF / (NM - NM / 2); ++f)
+                        load_frag_one(LB ^ 1, nxt, 0, f);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
         cur = nxt;
     }
     if (EPI != EPI_ATOMIC && tail) {

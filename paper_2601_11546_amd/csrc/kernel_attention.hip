@@ -20,6 +20,8 @@
 //                      group); each wave streams its own 32-key blocks through a private LDS
 //                      region, so a workgroup needs no barrier and short contexts still fill
 //                      the chip.  HBM-bound: the MFMA work is a few percent of the time.
+#include <type_traits>
+
 #include "device_utils.h"
 #include "relserve_internal.h"
 
@@ -211,8 +213,84 @@ __global__ void __launch_bounds__(256, 2) attn_tile_kernel(AttnArgs p) {
         issue(0, slot_cur);
         lookup(min(it.key_begin + BLOCK_N, last_key), slot_nxt);
     }
-    // operand addresses that do not change from block to block
+    // Operand addresses inside a stage that do not change from block to block.  K: key row
+    // 32 t + l32, chunk (2 ks + g) ^ kswz (the swizzle only depends on l32).  V: the transposing read
+    // of (t, h, half) points lane (G, s16) at key 32 t + 16 h + 8 half + 4 (G >> 1) + s16 / 4 and at
+    // d = 32 td + 16 (G & 1) + 4 (s16 % 4); its swizzle only depends on s16.
     const int G = lane >> 4, s16 = lane & 15;
+    uint32_t k_off[D / 16], v_off[D / 32];
+#pragma unroll
+    for (int ks = 0; ks < D / 16; ++ks) k_off[ks] = l32 * SM::ROWB + (((2 * ks + g) ^ kswz<D>(l32)) << 4);
+    {
+        const int key = 4 * (G >> 1) + (s16 >> 2);
+#pragma unroll
+        for (int td = 0; td < D / 32; ++td) {
+            const int chunk = 4 * td + 2 * (G & 1) + ((s16 & 3) >> 1);
+            v_off[td] = SM::K_BYTES + key * SM::ROWB + ((chunk ^ vswz<D>(key)) << 4) + (s16 & 1) * 8;
+        }
+    }
+    const float scale = p.scale_log2;
+    // One 32-key tile: S^T = K Q^T, online softmax in the log2 domain (the scale is folded into the
+    // exponent's multiply-add; the running maximum is kept scaled), O^T += V^T P^T.
+    auto tile = [&](bool masked, int t, const unsigned char* stage, int key0) {
+        f32x16_t sc;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) sc[r] = 0.f;
+#pragma unroll
+        for (int ks = 0; ks < D / 16; ++ks) {
+            const bf16x8_t kf = as_bf16x8(*reinterpret_cast<const uint4*>(stage + k_off[ks] + t * 32 * SM::ROWB));
+            sc = mfma_32x32x16(kf, qf[ks], sc);
+        }
+        if (masked) {   // wave-uniform: only the blocks that straddle some row's limit pay for the mask
+            const int lim = klim - key0 - 4 * g;
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+                if (8 * (r >> 2) + (r & 3) >= lim) sc[r] = -INFINITY;
+        }
+        float mx = -INFINITY;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sc[r]);
+        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+        const float m_new = fmaxf(st.m, mx * scale);
+        const float m_use = m_new == -INFINITY ? 0.f : m_new;  // a row that has seen no key yet
+        const float alpha = __builtin_amdgcn_exp2f(st.m - m_use);
+        st.m = m_new;
+        float psum = 0.f;
+        bf16x8_t pf[2];
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            uint32_t w[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[8 * h + 2 * j], scale, -m_use));
+                const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[8 * h + 2 * j + 1], scale, -m_use));
+                psum += p0 + p1;
+                w[j] = pack_bf16x2(p0, p1);
+            }
+            pf[h] = as_bf16x8(make_uint4(w[0], w[1], w[2], w[3]));
+        }
+        st.l = st.l * alpha + psum;
+        if (__any(alpha != 1.0f)) {
+#pragma unroll
+            for (int td = 0; td < D / 32; ++td)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) st.o[td][r] *= alpha;
+        }
+        // Element e of lane group g's probabilities is key 32 t + 16 h + 8 (e / 4) + 4 g + e % 4; the two
+        // transposing reads fetch those keys.
+        typedef short short8_t __attribute__((ext_vector_type(8)));
+        typedef short4_t __attribute__((address_space(3))) * lds_v4;
+#pragma unroll
+        for (int td = 0; td < D / 32; ++td)
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                unsigned char* a0 = const_cast<unsigned char*>(stage) + v_off[td] + (32 * t + 16 * h) * SM::ROWB;
+                const short4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(a0));
+                const short4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(a0 + 8 * SM::ROWB));
+                const short8_t v8 = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+                st.o[td] = mfma_32x32x16(__builtin_bit_cast(bf16x8_t, v8), pf[h], st.o[td]);
+            }
+    };
     for (int b = 0; b < n_blocks; ++b) {
         const int kb0 = it.key_begin + b * BLOCK_N;
         // this block has landed for every wave, and every wave is done with the other buffer
@@ -223,77 +301,10 @@ __global__ void __launch_bounds__(256, 2) attn_tile_kernel(AttnArgs p) {
             lookup(min(kb0 + 2 * BLOCK_N, last_key), slot_nxt);   // consumed one iteration later
         }
         if (wave_active && kb0 < wave_klim_max) {
-            unsigned char* sk = smem + (b & 1) * SM::STAGE;
-            unsigned char* sv = sk + SM::K_BYTES;
-            const bool need_mask = kb0 + BLOCK_N > wave_klim_min;
-#pragma unroll
-            for (int t = 0; t < 2; ++t) {
-                // S^T = K Q^T for 32 keys
-                f32x16_t sc;
-#pragma unroll
-                for (int r = 0; r < 16; ++r) sc[r] = 0.f;
-                const int krow = 32 * t + l32;
-#pragma unroll
-                for (int ks = 0; ks < D / 16; ++ks) {
-                    const bf16x8_t kf = as_bf16x8(*reinterpret_cast<const uint4*>(
-                        sk + krow * SM::ROWB + (((2 * ks + g) ^ kswz<D>(krow)) << 4)));
-                    sc = mfma_32x32x16(kf, qf[ks], sc);
-                }
-                float mx = -INFINITY;
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    float v = sc[r] * p.scale_log2;
-                    if (need_mask && kb0 + 32 * t + 8 * (r >> 2) + 4 * g + (r & 3) >= klim) v = -INFINITY;
-                    sc[r] = v;
-                    mx = fmaxf(mx, v);
-                }
-                mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-                const float m_new = fmaxf(st.m, mx);
-                const float m_use = m_new == -INFINITY ? 0.f : m_new;  // a row that has seen no key yet
-                const float alpha = __builtin_amdgcn_exp2f(st.m - m_use);
-                st.m = m_new;
-                float psum = 0.f;
-                bf16x8_t pf[2];
-#pragma unroll
-                for (int h = 0; h < 2; ++h) {
-                    uint32_t w[4];
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) {
-                        const float p0 = __builtin_amdgcn_exp2f(sc[8 * h + 2 * j] - m_use);
-                        const float p1 = __builtin_amdgcn_exp2f(sc[8 * h + 2 * j + 1] - m_use);
-                        psum += p0 + p1;
-                        w[j] = pack_bf16x2(p0, p1);
-                    }
-                    pf[h] = as_bf16x8(make_uint4(w[0], w[1], w[2], w[3]));
-                }
-                st.l = st.l * alpha + psum;
-                if (__any(alpha != 1.0f)) {
-#pragma unroll
-                    for (int td = 0; td < D / 32; ++td)
-#pragma unroll
-                        for (int r = 0; r < 16; ++r) st.o[td][r] *= alpha;
-                }
-                // O^T += V^T P^T.  Element e of lane group g's probabilities is key
-                // 32 t + 16 h + 8 (e / 4) + 4 g + e % 4; the two transposing reads fetch those keys.
-#pragma unroll
-                for (int td = 0; td < D / 32; ++td)
-#pragma unroll
-                    for (int h = 0; h < 2; ++h) {
-                        short4_t lo, hi;
-                        {
-                            const int key = 32 * t + 16 * h + 4 * (G >> 1) + (s16 >> 2);
-                            const int chunk = 4 * td + 2 * (G & 1) + ((s16 & 3) >> 1);
-                            unsigned char* a0 = sv + key * SM::ROWB + ((chunk ^ vswz<D>(key)) << 4) + (s16 & 1) * 8;
-                            const int key1 = key + 8;
-                            unsigned char* a1 = sv + key1 * SM::ROWB + ((chunk ^ vswz<D>(key1)) << 4) + (s16 & 1) * 8;
-                            lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((short4_t __attribute__((address_space(3)))*)(a0));
-                            hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((short4_t __attribute__((address_space(3)))*)(a1));
-                        }
-                        typedef short short8_t __attribute__((ext_vector_type(8)));
-                        const short8_t v8 = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-                        st.o[td] = mfma_32x32x16(__builtin_bit_cast(bf16x8_t, v8), pf[h], st.o[td]);
-                    }
-            }
+            const unsigned char* stage = smem + (b & 1) * SM::STAGE;
+            const bool masked = __builtin_amdgcn_readfirstlane(kb0 + BLOCK_N > wave_klim_min);
+            tile(masked, 0, stage, kb0);
+            tile(masked, 1, stage, kb0 + 32);
         }
     }
     if (valid) state_store<D>(st, p, it, row_id, g);

@@ -251,7 +251,12 @@ __global__ void __launch_bounds__(256, 2) attn_tile_kernel(AttnArgs p) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sc[r]);
         mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-        const float m_new = fmaxf(st.m, mx * scale);
+        // The reference value of the exponents only follows the running maximum when that grew by more
+        // than 8 (a factor 256): probabilities then stay below 2^8, harmless in bf16 / fp32, and the
+        // rescaling of the 64 output accumulators becomes rare instead of happening for some row of
+        // the wave in almost every tile.
+        const float m_cand = mx * scale;
+        const float m_new = m_cand > st.m + 8.0f ? m_cand : st.m;
         const float m_use = m_new == -INFINITY ? 0.f : m_new;  // a row that has seen no key yet
         const float alpha = __builtin_amdgcn_exp2f(st.m - m_use);
         st.m = m_new;

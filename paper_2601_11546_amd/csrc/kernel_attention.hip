@@ -321,35 +321,41 @@ __global__ void __launch_bounds__(256, 2) attn_tile_kernel(AttnArgs p) {
 // Uses the 16x16x32 MFMA (A[i = l % 16][k = 8 (l / 16) ..+7], B[k][j = l % 16], accumulator
 // register r = D[4 (l / 16) + r][l % 16]): 16 query rows are enough for the heads of one kv
 // group, and accumulators, query fragments and scores take half the registers of the 32-wide
-// form, which is what lets two of these waves share a SIMD.
+// form.  Each wave owns 32 key rows of K and of V in LDS (row-major, XOR-swizzled 16-byte chunks)
+// and fills them with direct global -> LDS loads; V^T operands come from transposing LDS reads.
+// One buffer per wave: eight waves per CU (D = 128) overlap each other's load and compute phases,
+// and no wave ever waits for another (no barrier).
 template <int D>
 struct DecodeSmem {
     static constexpr int BLOCK_N = 32;
-    static constexpr int K_STRIDE = (D + 8) * 2;
-    static constexpr int K_BYTES = BLOCK_N * K_STRIDE;
-    static constexpr int V_STRIDE = (BLOCK_N + 8) * 2;  // 20 dwords: 8 consecutive rows hit distinct bank groups
-    static constexpr int V_BYTES = D * V_STRIDE;
+    static constexpr int ROWB = D * 2;
+    static constexpr int K_BYTES = BLOCK_N * ROWB;
+    static constexpr int V_BYTES = BLOCK_N * ROWB;
     static constexpr int WAVE_BYTES = K_BYTES + V_BYTES;
 };
+// V chunk c of key row r sits at c ^ dvswz(r): a transposing read of 64 lanes touches 16 key rows x 32 bytes,
+// which this spreads over all banks twice (the minimum for 512 bytes).
+template <int D>
+__device__ __forceinline__ int dvswz(int row) { return D == 128 ? 2 * (row & 7) : 2 * ((row >> 1) & 3); }
 
 template <int D>
 __global__ void __launch_bounds__(256) attn_decode_kernel(AttnArgs p) {
     using SM = DecodeSmem<D>;
-    constexpr int CH = D / 8;
-    constexpr int ROWS_PER_PASS = 64 / CH;       // key rows one wave-wide load covers
-    constexpr int K_IT = 32 / ROWS_PER_PASS;     // K loads per lane per block
-    constexpr int V_IT = 16 / ROWS_PER_PASS;     // V key pairs per lane per block
+    constexpr int CH = D / 8;                 // 16-byte chunks per K/V row
+    constexpr int RPI = 64 / CH;              // rows one 1 KB wave load covers
+    constexpr int IT = SM::BLOCK_N / RPI;     // wave loads per tensor and block
     constexpr int KS = D / 32, TD = D / 16;
     extern __shared__ __align__(16) unsigned char smem[];
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l16 = lane & 15, gq = lane >> 4;
     const int item_idx = blockIdx.x * 4 + wave;
     if (item_idx >= p.n_items) return;           // whole wave leaves; the kernel has no workgroup barrier
     const AttnItem it = p.items[item_idx];
     const int kvh = blockIdx.y;
     unsigned char* sk = smem + wave * SM::WAVE_BYTES;
-    unsigned char* sv = sk + SM::K_BYTES;
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)sk;
 
     // a decode item is one token (pad0) whose last visible key is its own: klim = key_end
     const int tok = it.pad0;
@@ -381,78 +387,52 @@ __global__ void __launch_bounds__(256) attn_decode_kernel(AttnArgs p) {
         }
     }
 
+    // ---- staging: wave load j fills rows j * RPI ..; lane l owns row l / CH of those and the 16-byte
+    // slot l % CH.  Keys past the end re-read the last key: their scores are masked, their
+    // probabilities exact zeros.  Block-table entries are looked up one block ahead of the loads.
     const int32_t* bt = p.block_table + (int64_t)it.bt_req * p.max_blocks;
-    const int kc = lane % CH, krow0 = lane / CH;
-    uint4 k_reg[K_IT], v_reg[V_IT][2];
-    // Branch-free and in two phases (all block-table entries first, then all K/V rows), so that the
-    // loads of a block are in flight together instead of one dependent pair after the other.  Keys
-    // past the end read the last valid key and are replaced by exact zeros.
     const int last_key = it.key_end - 1;
-    auto slot_of = [&](int key) -> int64_t {
-        return ((int64_t)bt[key >> p.page_shift] << p.page_shift) + (key & p.page_mask);
-    };
-    auto stage_load = [&](int kb0) {
-        int64_t ks[K_IT], vs[V_IT][2];
+    const int lrow = lane / CH, lslot = lane % CH;
+    int64_t slots[IT];
+    auto lookup = [&](int kb0) {
 #pragma unroll
-        for (int i = 0; i < K_IT; ++i) ks[i] = slot_of(min(kb0 + krow0 + ROWS_PER_PASS * i, last_key));
-#pragma unroll
-        for (int i = 0; i < V_IT; ++i)
-#pragma unroll
-            for (int e = 0; e < 2; ++e) vs[i][e] = slot_of(min(kb0 + 2 * (krow0 + ROWS_PER_PASS * i) + e, last_key));
-#pragma unroll
-        for (int i = 0; i < K_IT; ++i)
-            k_reg[i] = *reinterpret_cast<const uint4*>(p.k_pages + (ks[i] * p.n_kv + kvh) * D + kc * 8);
-#pragma unroll
-        for (int i = 0; i < V_IT; ++i)
-#pragma unroll
-            for (int e = 0; e < 2; ++e)
-                v_reg[i][e] = *reinterpret_cast<const uint4*>(p.v_pages + (vs[i][e] * p.n_kv + kvh) * D + kc * 8);
-#pragma unroll
-        for (int i = 0; i < K_IT; ++i)
-            if (kb0 + krow0 + ROWS_PER_PASS * i > last_key) k_reg[i] = make_uint4(0, 0, 0, 0);
-#pragma unroll
-        for (int i = 0; i < V_IT; ++i)
-#pragma unroll
-            for (int e = 0; e < 2; ++e)   // keys past the end contribute exact zeros
-                if (kb0 + 2 * (krow0 + ROWS_PER_PASS * i) + e > last_key) v_reg[i][e] = make_uint4(0, 0, 0, 0);
-    };
-    // V^T column of key k (0..31): 8 ((k >> 2) & 3) + 4 (k >> 4) + (k & 3), so that lane group gq
-    // finds the 8 keys it holds probabilities for (4 gq .. +3 and 16 + 4 gq .. +3) side by side.
-    auto stage_store = [&]() {
-#pragma unroll
-        for (int i = 0; i < K_IT; ++i)
-            *reinterpret_cast<uint4*>(sk + (krow0 + ROWS_PER_PASS * i) * SM::K_STRIDE + kc * 16) = k_reg[i];
-#pragma unroll
-        for (int i = 0; i < V_IT; ++i) {
-            const int pi = krow0 + ROWS_PER_PASS * i;                              // key pair 0..15
-            const int kp = (((pi >> 1) & 3) << 2) | ((pi >> 3) << 1) | (pi & 1);   // dword column before swizzle
-            const int col = (((kp >> 2) ^ ((kc >> 1) & 3)) << 2) | (kp & 3);
-            const uint32_t e[4] = {v_reg[i][0].x, v_reg[i][0].y, v_reg[i][0].z, v_reg[i][0].w};
-            const uint32_t o[4] = {v_reg[i][1].x, v_reg[i][1].y, v_reg[i][1].z, v_reg[i][1].w};
-#pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                const uint32_t ev = (j & 1) ? (e[j >> 1] >> 16) : (e[j >> 1] & 0xffffu);
-                const uint32_t ov = (j & 1) ? (o[j >> 1] & 0xffff0000u) : (o[j >> 1] << 16);
-                *reinterpret_cast<uint32_t*>(sv + (8 * kc + j) * SM::V_STRIDE + col * 4) = ev | ov;
-            }
+        for (int j = 0; j < IT; ++j) {
+            const int key = min(kb0 + j * RPI + lrow, last_key);
+            slots[j] = ((int64_t)bt[key >> p.page_shift] << p.page_shift) + (key & p.page_mask);
         }
     };
-    // LDS traffic of one wave is processed in order; the fences keep the compiler from moving
-    // the tile reads across the tile writes of the other lanes.
-    auto wave_sync = [&]() {
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    auto issue = [&]() {
+#pragma unroll
+        for (int j = 0; j < IT; ++j) {
+            const int row = j * RPI + lrow;
+            const int64_t off = (slots[j] * p.n_kv + kvh) * D;
+            dma16_ptr(p.k_pages + off + ((lslot ^ kswz<D>(row)) << 3), lds0 + j * 1024);
+            dma16_ptr(p.v_pages + off + ((lslot ^ dvswz<D>(row)) << 3), lds0 + SM::K_BYTES + j * 1024);
+        }
     };
+    // operand addresses: K fragment (t, ks) = key row 16 t + l16, chunk 4 ks + gq; the transposing V read
+    // (td, half) points lane (gq, s = l16) at key 16 half + 4 gq + s / 4 and d = 16 td + 4 (s % 4)
+    uint32_t k_off[KS], v_off[TD];
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) k_off[ks] = l16 * SM::ROWB + (((4 * ks + gq) ^ kswz<D>(l16)) << 4);
+    {
+        const int key = 4 * gq + (l16 >> 2);
+#pragma unroll
+        for (int td = 0; td < TD; ++td)
+            v_off[td] = SM::K_BYTES + key * SM::ROWB + (((2 * td + ((l16 & 3) >> 1)) ^ dvswz<D>(key)) << 4) + (l16 & 1) * 8;
+    }
+    typedef short short8_t __attribute__((ext_vector_type(8)));
+    typedef short4_t __attribute__((address_space(3))) * lds_v4;
 
     const int n_blocks = (it.key_end - it.key_begin + SM::BLOCK_N - 1) / SM::BLOCK_N;
-    if (n_blocks > 0) stage_load(it.key_begin);
+    if (n_blocks > 0) {
+        lookup(it.key_begin);
+        issue();
+        if (n_blocks > 1) lookup(it.key_begin + SM::BLOCK_N);
+    }
     for (int b = 0; b < n_blocks; ++b) {
         const int kb0 = it.key_begin + b * SM::BLOCK_N;
-        wave_sync();     // every lane is done reading the previous tile
-        stage_store();
-        wave_sync();     // the tile is complete
-        if (b + 1 < n_blocks) stage_load(kb0 + SM::BLOCK_N);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the block has landed
 
         // S^T = K Q^T for two 16-key tiles; lane holds keys kb0 + 16 t + 4 gq + r of query row l16
         f32x4_t s[2];
@@ -461,10 +441,23 @@ __global__ void __launch_bounds__(256) attn_decode_kernel(AttnArgs p) {
             s[t] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) {
-                const bf16x8_t kf = as_bf16x8(*reinterpret_cast<const uint4*>(
-                    sk + (16 * t + l16) * SM::K_STRIDE + (4 * ks + gq) * 16));
+                const bf16x8_t kf = as_bf16x8(*reinterpret_cast<const uint4*>(sk + k_off[ks] + t * 16 * SM::ROWB));
                 s[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf, qf[ks], s[t], 0, 0, 0);
             }
+        }
+        // the block's 32 key rows of V, as the operand of O^T += V^T P^T (rows d = 16 td + l16)
+        bf16x8_t vf[TD];
+#pragma unroll
+        for (int td = 0; td < TD; ++td) {
+            const short4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(sk + v_off[td]));
+            const short4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(sk + v_off[td] + 16 * SM::ROWB));
+            vf[td] = __builtin_bit_cast(bf16x8_t, (short8_t)__builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+        }
+        // everything of this block is in registers: the next block may overwrite the buffer
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        if (b + 1 < n_blocks) {
+            issue();
+            if (b + 2 < n_blocks) lookup(kb0 + 2 * SM::BLOCK_N);
         }
         const bool need_mask = kb0 + SM::BLOCK_N > klim;
         float mx = -INFINITY;
@@ -492,6 +485,8 @@ __global__ void __launch_bounds__(256) attn_decode_kernel(AttnArgs p) {
                 pv[4 * t + r] = __builtin_amdgcn_exp2f(s[t][r] - m_use);
                 psum += pv[4 * t + r];
             }
+        // element e of the operand: key 4 gq + e (e < 4), 16 + 4 gq + e - 4 (e >= 4), the keys the two
+        // transposing reads fetched
         const bf16x8_t pf = as_bf16x8(make_uint4(pack_bf16x2(pv[0], pv[1]), pack_bf16x2(pv[2], pv[3]),
                                                  pack_bf16x2(pv[4], pv[5]), pack_bf16x2(pv[6], pv[7])));
         l_run = l_run * alpha + psum;
@@ -499,14 +494,8 @@ __global__ void __launch_bounds__(256) attn_decode_kernel(AttnArgs p) {
 #pragma unroll
             for (int td = 0; td < TD; ++td) o_acc[td] *= alpha;
         }
-        // O^T += V^T P^T: rows d = 16 td + l16, contraction over the block's 32 keys
 #pragma unroll
-        for (int td = 0; td < TD; ++td) {
-            const int d = 16 * td + l16;
-            const bf16x8_t vf = as_bf16x8(*reinterpret_cast<const uint4*>(
-                sv + d * SM::V_STRIDE + ((gq ^ ((d >> 4) & 3)) << 4)));
-            o_acc[td] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pf, o_acc[td], 0, 0, 0);
-        }
+        for (int td = 0; td < TD; ++td) o_acc[td] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[td], pf, o_acc[td], 0, 0, 0);
     }
     if (!valid) return;
     float l_tot = l_run + __shfl_xor(l_run, 16, 64);

@@ -99,6 +99,33 @@ def cpu_baseline(wl, weights, x, budget_tokens: int) -> dict:
                       f"{int((sub.q_len > 1).sum())} prefill rows, {int((sub.q_len == 1).sum())} decode rows), one layer step"}
 
 
+def peak_probes(rs, torch) -> dict:
+    """What this GPU sustains (not the figures fractions are reported against): a loop of independent
+    32x32x16 bf16 MFMAs on random operands, and a streaming read of 4 GiB."""
+    sink = torch.zeros(64, dtype=torch.float32, device="cuda")
+    buf = torch.empty(1 << 32, dtype=torch.uint8, device="cuda")
+    buf.view(torch.int32).random_()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    rs.relserve_peak_probe_mfma(sink, 2000)
+    rs.relserve_peak_probe_stream(buf, buf.numel(), sink)
+    torch.cuda.synchronize()
+    best_tf, best_gb = 0.0, 0.0
+    for _ in range(3):
+        e0.record()
+        flops = rs.relserve_peak_probe_mfma(sink, 100000)
+        e1.record()
+        torch.cuda.synchronize()
+        best_tf = max(best_tf, flops / (e0.elapsed_time(e1) * 1e-3) / 1e12)
+        e0.record()
+        rs.relserve_peak_probe_stream(buf, buf.numel(), sink)
+        e1.record()
+        torch.cuda.synchronize()
+        best_gb = max(best_gb, buf.numel() / (e0.elapsed_time(e1) * 1e-3) / 1e9)
+    del buf
+    return {"mfma_issue_loop_tflops": round(best_tf, 1), "stream_read_gbs": round(best_gb, 1),
+            "note": "random bf16 operands, 16 independent accumulators per wave; 4 GiB read with 16-byte loads"}
+
+
 def main() -> None:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -107,6 +134,7 @@ def main() -> None:
     ap.add_argument("--workload", default="relquery_13b")
     ap.add_argument("--layer-sets", type=int, default=0, help="independent (weights, cache) sets to rotate over (0 = auto)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-peak-probes", action="store_true", help="skip the MFMA issue loop and the streaming read")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (reference for rocprofv3's FETCH_SIZE / WRITE_SIZE)")
     ap.add_argument("--cpu-tokens", type=int, default=0, help="token budget of the oracle sample (0 = auto)")
@@ -240,8 +268,10 @@ def main() -> None:
                  "batch_prepare_ms": round(prepare_ms, 3)},
         "kernels": kernels,
     }
+    if not args.no_peak_probes:
+        out["measured_peaks"] = peak_probes(rs, torch)
     if not args.no_cpu_baseline:
-        budget = args.cpu_tokens or max(8, int(4.0e10 / (2 * shape.params)))   # about 40 GFLOP of dense work
+        budget = args.cpu_tokens or max(8, int(1.6e11 / (2 * shape.params)))   # about 160 GFLOP of dense work, ~10 s
         out["cpu_baseline"] = cpu_baseline(wl, weights0, x_bits, budget)
     print(json.dumps(out))
 

@@ -232,6 +232,15 @@ int32_t relserve_attention(const relserve_layer* layer, const relserve_batch* ba
                            const void* q, int32_t q_pitch, relserve_kv_cache cache,
                            void* out, void* workspace, size_t workspace_bytes, void* stream);
 
+/* ---- peak probes: what this GPU sustains, reported by bench.py beside the published peaks ----
+ * relserve_peak_probe_mfma enqueues 256 workgroups of 4 waves that each issue iters x 16 independent
+ * 32x32x16 bf16 MFMAs on random operands (no memory traffic) and writes the flop count of the launch to
+ * *flops (host).  relserve_peak_probe_stream enqueues one read of `bytes` bytes of device memory at src
+ * (16-byte aligned).  sink: device memory, at least 16 bytes, never written in practice.  The caller
+ * times the launches on `stream`. */
+int32_t relserve_peak_probe_mfma(void* sink, int32_t iters, double* flops, void* stream);
+int32_t relserve_peak_probe_stream(const void* src, size_t bytes, void* sink, void* stream);
+
 /* ---- test hook ----
  * Forces the tile shape and the tail split of every later GEMM launch of this process:
  * tile = 0..4 (256x256, 192x256, 128x256, 128x128, 64x128 tokens x features), 5..9 = eight-wave

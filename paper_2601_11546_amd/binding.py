@@ -28,7 +28,7 @@ EXPORTS = ["relserve_version", "relserve_strerror", "relserve_config_validate", 
            "relserve_layer_step", "relserve_model_workspace_bytes", "relserve_model_step", "relserve_rmsnorm", "relserve_linear", "relserve_rope_append",
            "relserve_qkv_rope_append",
            "relserve_attention", "relserve_profile_slot_name", "relserve_profile_enable", "relserve_profile_read",
-           "relserve_debug_force_gemm_plan"]
+           "relserve_debug_force_gemm_plan", "relserve_peak_probe_mfma", "relserve_peak_probe_stream"]
 
 
 class RelserveError(RuntimeError):
@@ -98,6 +98,8 @@ for _n, _a in {
                            C.c_size_t, C.c_void_p],
     "relserve_profile_enable": [C.c_void_p, C.c_int32],
     "relserve_debug_force_gemm_plan": [C.c_int32, C.c_int32],
+    "relserve_peak_probe_mfma": [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p],
+    "relserve_peak_probe_stream": [C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p],
     "relserve_profile_read": [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32],
 }.items():
     getattr(_lib, _n).restype = C.c_int32
@@ -294,6 +296,17 @@ def relserve_attention(layer, pbatch, q, q_pitch: int, k_pages, v_pages, out, wo
     _check(_lib.relserve_attention(layer.handle, pbatch.handle, _ptr(q), int(q_pitch), _cache(k_pages, v_pages),
                                    _ptr(out), _ptr(workspace), workspace.numel() * workspace.element_size(),
                                    _stream(stream)), "relserve_attention")
+
+
+def relserve_peak_probe_mfma(sink, iters: int, stream=None) -> float:
+    """Enqueues the MFMA issue loop; returns the flop count of the launch."""
+    flops = C.c_double(0.0)
+    _check(_lib.relserve_peak_probe_mfma(_ptr(sink), int(iters), C.byref(flops), _stream(stream)), "relserve_peak_probe_mfma")
+    return flops.value
+
+
+def relserve_peak_probe_stream(src, nbytes: int, sink, stream=None) -> None:
+    _check(_lib.relserve_peak_probe_stream(_ptr(src), int(nbytes), _ptr(sink), _stream(stream)), "relserve_peak_probe_stream")
 
 
 def relserve_debug_force_gemm_plan(tile: int = -1, tail_splits: int = 0) -> None:

@@ -581,6 +581,24 @@ int32_t relserve_model_step(const relserve_layer* L, const relserve_batch* b, co
     return RELSERVE_OK;
 }
 
+int32_t relserve_peak_probe_mfma(void* sink, int32_t iters, double* flops, void* stream) {
+    if (!sink || !flops) return RELSERVE_ERR_NULL_POINTER;
+    if (iters <= 0) return RELSERVE_ERR_BAD_ARGUMENT;
+    *flops = 256.0 * 4.0 * iters * 16.0 * 32768.0;
+    return launch_peak_mfma(static_cast<float*>(sink), iters, static_cast<hipStream_t>(stream)) == hipSuccess
+               ? RELSERVE_OK
+               : RELSERVE_ERR_HIP;
+}
+
+int32_t relserve_peak_probe_stream(const void* src, size_t bytes, void* sink, void* stream) {
+    if (!src || !sink) return RELSERVE_ERR_NULL_POINTER;
+    if (bytes < 16 || (reinterpret_cast<uintptr_t>(src) % 16)) return RELSERVE_ERR_BAD_ARGUMENT;
+    return launch_peak_stream(src, (int64_t)bytes, static_cast<uint32_t*>(sink), static_cast<hipStream_t>(stream)) ==
+                   hipSuccess
+               ? RELSERVE_OK
+               : RELSERVE_ERR_HIP;
+}
+
 int32_t relserve_debug_force_gemm_plan(int32_t tile, int32_t tail_splits) {
     if (tile < -1 || tile > 9 || tail_splits < 0 || tail_splits > 8) return RELSERVE_ERR_BAD_ARGUMENT;
     gemm_force_plan(tile, tail_splits);

@@ -453,3 +453,15 @@ def test_model_step_13b_two_layer_slice(rs, oracle):
     reqs = [0, 77, 127, 128]
     print(f"[case] 2-layer 13B model step, requests {reqs} of {wl.batch.num_reqs}", flush=True)
     _model_case(rs, oracle, wl.shape, wl.batch.select(reqs), 2, 32000, 92, True, "model step 13B x2")
+
+
+def test_peak_probes_run(rs):
+    """The MFMA issue loop and the streaming read that bench.py reports as measured peaks."""
+    sink = torch.zeros(64, dtype=torch.float32, device="cuda")
+    buf = torch.ones(1 << 24, dtype=torch.uint8, device="cuda")
+    flops = rs.relserve_peak_probe_mfma(sink, 100)
+    assert flops == 256 * 4 * 100 * 16 * 32768
+    rs.relserve_peak_probe_stream(buf, buf.numel(), sink)
+    torch.cuda.synchronize()
+    assert float(sink.abs().max()) == 0.0
+

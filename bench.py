@@ -133,6 +133,8 @@ def main() -> None:
     ap.add_argument("--warmup", type=int, default=8)
     ap.add_argument("--workload", default="relquery_13b")
     ap.add_argument("--layer-sets", type=int, default=0, help="independent (weights, cache) sets to rotate over (0 = auto)")
+    ap.add_argument("--row-major-weights", action="store_true",
+                    help="feed the projections row-major [out, in] weights instead of the packed streaming layout")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-peak-probes", action="store_true", help="skip the MFMA issue loop and the streaming read")
     ap.add_argument("--calibration-copy", action="store_true",
@@ -165,11 +167,17 @@ def main() -> None:
     kp, vp = W.make_cache(shape, b.num_pages, wl.seed)
     base = ({k: dev(v) for k, v in weights0.items()}, dev(kp), dev(vp))
     del kp, vp
-    sets = [base]
-    for i in range(1, n_sets):
-        sets.append(({k: torch.roll(v, 7 * i, 0) for k, v in base[0].items()},
-                     torch.roll(base[1].view(-1, base[1].shape[-1]), 5 * i, 0).view(base[1].shape).contiguous(),
-                     torch.roll(base[2].view(-1, base[2].shape[-1]), 5 * i, 0).view(base[2].shape).contiguous()))
+    packed = not args.row_major_weights and all(d % 64 == 0 for d in (shape.hidden, shape.n_q_heads * shape.head_dim, shape.mlp_dim))
+    sets = []
+    for i in range(n_sets):
+        wts = base[0] if i == 0 else {k: torch.roll(v, 7 * i, 0) for k, v in base[0].items()}
+        if packed:   # one-time conversion at model load (relserve_pack_weight); the row-major copy is dropped
+            wts = rs.pack_layer_weights(wts)
+        sets.append((wts,
+                     base[1] if i == 0 else torch.roll(base[1].view(-1, base[1].shape[-1]), 5 * i, 0).view(base[1].shape).contiguous(),
+                     base[2] if i == 0 else torch.roll(base[2].view(-1, base[2].shape[-1]), 5 * i, 0).view(base[2].shape).contiguous()))
+    if packed:
+        base = (None, base[1], base[2])
     layer = rs.relserve_layer_create(shape)
     t0 = time.perf_counter()
     pb = rs.relserve_batch_prepare(layer, b)
@@ -260,7 +268,8 @@ def main() -> None:
         "config": {"workload": wl.name, "layer": f"H{shape.hidden} q{shape.n_q_heads}/kv{shape.n_kv_heads}x{shape.head_dim} "
                    f"I{shape.mlp_dim} P{shape.page_size}", "query_tokens": b.T, "requests": b.num_reqs,
                    "prefill_rows": int((b.q_len > 1).sum()), "decode_rows": int((b.q_len == 1).sum()),
-                   "layer_sets_rotated": n_sets, "batch_info": pb.info},
+                   "layer_sets_rotated": n_sets, "weight_layout": "packed" if packed else "row-major",
+                   "batch_info": pb.info},
         "roofline": roofline,
         "step": {"tflops": round(step_tflops, 1), "frac_mfma_peak": round(step_tflops / PEAK_BF16_TFLOPS, 4),
                  "algorithmic_gbs": round(step_gbs, 1), "frac_hbm_peak": round(step_gbs / PEAK_HBM_GBS, 4),

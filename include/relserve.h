@@ -111,6 +111,8 @@ typedef struct {          /* all device, bf16 */
     const void* w_post_norm;   /* [H] */
     const void* w_gate_up;     /* [2 I, H] */
     const void* w_down;        /* [H, I] */
+    int32_t packed;            /* 0: the four matrices are row-major [out, in]; 1: each was converted with
+                                * relserve_pack_weight (needs hidden, n_q d and I to be multiples of 64) */
 } relserve_layer_weights;
 
 typedef struct {
@@ -212,6 +214,18 @@ int32_t relserve_rmsnorm(const void* x, int32_t x_is_f32, const void* w, float e
  * K must be a multiple of 8, N of 4 (of 16 for SwiGLU). */
 int32_t relserve_linear(const void* a, const void* w, int32_t T, int32_t N, int32_t K,
                         int32_t epilogue, const void* residual, void* out, void* stream);
+
+/* Tiled weight layout for streaming.  A row-major matrix w [N, K] (K a multiple of 64) becomes
+ * out[N / 256][K / 64][N % 256][K % 64] with N padded to a multiple of 256 (zero rows): one 64-wide k
+ * slice of 256 output features is 32 KB of consecutive memory, which is what one pipeline stage of the
+ * GEMM kernels reads; with row-major weights the same stage is 256 pieces of 128 bytes 2 K bytes apart,
+ * and the weight-bound (small T) projections reach only about half of the streaming rate.
+ * relserve_packed_weight_elems: bf16 elements of the packed matrix.  relserve_pack_weight: device to
+ * device, out must not overlap w.  relserve_linear_packed: relserve_linear on a packed w. */
+int32_t relserve_packed_weight_elems(int32_t N, int32_t K, int64_t* out);
+int32_t relserve_pack_weight(const void* w, int32_t N, int32_t K, void* out, void* stream);
+int32_t relserve_linear_packed(const void* a, const void* w_packed, int32_t T, int32_t N, int32_t K,
+                               int32_t epilogue, const void* residual, void* out, void* stream);
 
 /* Rotary embedding of q and k inside qkv [T, (n_q + 2 n_kv) d] (in place on the
  * q part) and append of the rotated k and of v into the cache. */

@@ -28,7 +28,8 @@ EXPORTS = ["relserve_version", "relserve_strerror", "relserve_config_validate", 
            "relserve_layer_step", "relserve_model_workspace_bytes", "relserve_model_step", "relserve_rmsnorm", "relserve_linear", "relserve_rope_append",
            "relserve_qkv_rope_append",
            "relserve_attention", "relserve_profile_slot_name", "relserve_profile_enable", "relserve_profile_read",
-           "relserve_debug_force_gemm_plan", "relserve_peak_probe_mfma", "relserve_peak_probe_stream"]
+           "relserve_debug_force_gemm_plan", "relserve_peak_probe_mfma", "relserve_peak_probe_stream",
+           "relserve_packed_weight_elems", "relserve_pack_weight", "relserve_linear_packed"]
 
 
 class RelserveError(RuntimeError):
@@ -53,9 +54,12 @@ class KVCache(C.Structure):
     _fields_ = [("k_pages", C.c_void_p), ("v_pages", C.c_void_p), ("num_pages", C.c_int32)]
 
 
+WEIGHT_NAMES = ("w_in_norm", "w_qkv", "w_o", "w_post_norm", "w_gate_up", "w_down")
+MATRIX_NAMES = ("w_qkv", "w_o", "w_gate_up", "w_down")
+
+
 class LayerWeights(C.Structure):
-    _fields_ = [(n, C.c_void_p) for n in
-                ("w_in_norm", "w_qkv", "w_o", "w_post_norm", "w_gate_up", "w_down")]
+    _fields_ = [(n, C.c_void_p) for n in WEIGHT_NAMES] + [("packed", C.c_int32)]
 
 
 class Model(C.Structure):
@@ -92,6 +96,10 @@ for _n, _a in {
     "relserve_rmsnorm": [C.c_void_p, C.c_int32, C.c_void_p, C.c_float, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p],
     "relserve_linear": [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_void_p,
                         C.c_void_p, C.c_void_p],
+    "relserve_linear_packed": [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_void_p,
+                               C.c_void_p, C.c_void_p],
+    "relserve_packed_weight_elems": [C.c_int32, C.c_int32, C.c_void_p],
+    "relserve_pack_weight": [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p],
     "relserve_rope_append": [C.c_void_p, C.c_void_p, C.c_void_p, KVCache, C.c_void_p],
     "relserve_qkv_rope_append": [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, KVCache, C.c_void_p],
     "relserve_attention": [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, KVCache, C.c_void_p, C.c_void_p,
@@ -240,7 +248,8 @@ def relserve_kv_append(layer, pbatch, k, v, k_pages, v_pages, stream=None) -> No
 
 
 def _weights(w: dict) -> LayerWeights:
-    return LayerWeights(*[w[n].data_ptr() for n, _ in LayerWeights._fields_])
+    """w: the six tensors by name; an entry "packed": True marks matrices converted by relserve_pack_weight."""
+    return LayerWeights(*[w[n].data_ptr() for n in WEIGHT_NAMES], int(bool(w.get("packed", False))))
 
 
 def relserve_layer_step(layer, pbatch, weights: dict, x, y, k_pages, v_pages, workspace, stream=None) -> None:
@@ -280,6 +289,35 @@ def relserve_rmsnorm(x, w, eps: float, out, stream=None) -> None:
 def relserve_linear(a, w, epilogue: int, residual, out, stream=None) -> None:
     _check(_lib.relserve_linear(_ptr(a), _ptr(w), a.shape[0], w.shape[0], w.shape[1], int(epilogue),
                                 _ptr(residual), _ptr(out), _stream(stream)), "relserve_linear")
+
+
+def relserve_packed_weight_elems(n: int, k: int) -> int:
+    out = C.c_int64(0)
+    _check(_lib.relserve_packed_weight_elems(int(n), int(k), C.byref(out)), "relserve_packed_weight_elems")
+    return out.value
+
+
+def relserve_pack_weight(w, out, stream=None) -> None:
+    """w: row-major [N, K] device bf16; out: device bf16 with relserve_packed_weight_elems(N, K) elements."""
+    _check(_lib.relserve_pack_weight(_ptr(w), w.shape[0], w.shape[1], _ptr(out), _stream(stream)), "relserve_pack_weight")
+
+
+def relserve_linear_packed(a, w_packed, n: int, epilogue: int, residual, out, stream=None) -> None:
+    _check(_lib.relserve_linear_packed(_ptr(a), _ptr(w_packed), a.shape[0], int(n), a.shape[1], int(epilogue),
+                                       _ptr(residual), _ptr(out), _stream(stream)), "relserve_linear_packed")
+
+
+def pack_layer_weights(weights: dict) -> dict:
+    """A copy of a layer's weight dict with the four matrices in the packed layout (torch device tensors)."""
+    import torch
+    out = dict(weights)
+    for name in MATRIX_NAMES:
+        w = weights[name]
+        packed = torch.empty(relserve_packed_weight_elems(w.shape[0], w.shape[1]), dtype=w.dtype, device=w.device)
+        relserve_pack_weight(w, packed)
+        out[name] = packed
+    out["packed"] = True
+    return out
 
 
 def relserve_rope_append(layer, pbatch, qkv, k_pages, v_pages, stream=None) -> None:

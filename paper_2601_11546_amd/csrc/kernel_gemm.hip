@@ -37,6 +37,7 @@ constexpr int64_t kTailFloats = GEMM_TAIL_FLOATS;          // fp32 partial tiles
 struct GemmArgs {
     const uint16_t* a;
     const uint16_t* w;
+    int32_t w_packed;   // weights in the tiled layout of pack_weight_kernel instead of row-major [N, K]
     const void* residual;
     void* out;
     int32_t T, N, K;
@@ -444,12 +445,14 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_dma_kernel(GemmArgs p) {
         } else {
             n = min(tile_n * BN + lr, p.N - 1);
         }
-        w_voff[j] = ((uint32_t)n * (uint32_t)K + chunk * 8) * 2;
+        // row-major: row n starts at n * K; packed: block n / 256 holds, k slice after k slice, 256 rows of 128 bytes
+        w_voff[j] = p.w_packed ? (uint32_t)(n >> 8) * (uint32_t)K * 512u + (uint32_t)(n & 255) * 128u + chunk * 16
+                               : ((uint32_t)n * (uint32_t)K + chunk * 8) * 2;
     }
     const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem;
     auto issue_stage = [&](int stage, int k0) {
         const char* abase = reinterpret_cast<const char*>(p.a) + (size_t)k0 * 2;
-        const char* wbase = reinterpret_cast<const char*>(p.w) + (size_t)k0 * 2;
+        const char* wbase = reinterpret_cast<const char*>(p.w) + (p.w_packed ? (size_t)k0 * 512 : (size_t)k0 * 2);
         const uint32_t la = lds0 + stage * STAGE + wave * 1024;
 #pragma unroll
         for (int j = 0; j < A_IT; ++j) dma16(abase, a_voff[j], la + j * (NW * 1024));
@@ -521,7 +524,8 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_dma_kernel(GemmArgs p) {
         // weights first: they come from further away (HBM) than the activations (L2)
         const uint32_t la = lds0 + stage * STAGE + wave * 1024;
         if (i < W_IT)
-            dma16(reinterpret_cast<const char*>(p.w) + (size_t)k0 * 2, w_voff[i], la + A_BYTES + i * (NW * 1024));
+            dma16(reinterpret_cast<const char*>(p.w) + (p.w_packed ? (size_t)k0 * 512 : (size_t)k0 * 2), w_voff[i],
+                  la + A_BYTES + i * (NW * 1024));
         else
             dma16(reinterpret_cast<const char*>(p.a) + (size_t)k0 * 2, a_voff[i - W_IT], la + (i - W_IT) * (NW * 1024));
     };
@@ -963,6 +967,27 @@ int64_t gemm_scratch_used(int32_t T, int32_t N, int32_t K, bool qkv) {
     return plan.tail_tiles == 0 ? 0 : kTailCounters;   // only the arrival counters must start at zero
 }
 
+// Tiled weight layout for streaming: out[n / 256][k / 64][n % 256][k % 64], rows past N are zeros.  One k
+// slice of 256 rows is 32 KB of consecutive memory, so a stage of the GEMM reads whole DRAM pages
+// instead of 128-byte pieces 2 K bytes apart.
+__global__ void pack_weight_kernel(const uint4* w, uint4* out, int32_t N, int32_t K, int64_t n_chunks) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;   // 16-byte chunk of the output
+    if (i >= n_chunks) return;
+    const int c = (int)(i & 7), r = (int)((i >> 3) & 255);
+    const int64_t slice = i >> 11;                                       // (block, k slice)
+    const int ks = (int)(slice % (K / 64));
+    const int64_t n = (slice / (K / 64)) * 256 + r;
+    out[i] = n < N ? w[(n * K + ks * 64) / 8 + c] : make_uint4(0, 0, 0, 0);
+}
+
+hipError_t launch_pack_weight(const void* w, int32_t N, int32_t K, void* out, hipStream_t s) {
+    const int64_t n_chunks = (int64_t)((N + 255) / 256) * 256 * K / 8;
+    if (n_chunks == 0) return hipSuccess;
+    pack_weight_kernel<<<dim3((unsigned)((n_chunks + 255) / 256)), dim3(256), 0, s>>>(
+        static_cast<const uint4*>(w), static_cast<uint4*>(out), N, K, n_chunks);
+    return hipGetLastError();
+}
+
 hipError_t launch_fill_zero(float* ptr, int64_t n_floats, hipStream_t s) {
     const int64_t n4 = (n_floats + 3) / 4;
     if (n4 == 0) return hipSuccess;
@@ -971,12 +996,14 @@ hipError_t launch_fill_zero(float* ptr, int64_t n_floats, hipStream_t s) {
 }
 
 hipError_t launch_linear(const void* a, const void* w, int32_t T, int32_t N, int32_t K, int32_t epilogue,
-                         const void* residual, void* out, hipStream_t s, float* accum) {
+                         const void* residual, void* out, hipStream_t s, float* accum, bool w_packed) {
     if (T == 0) return hipSuccess;
     if ((int64_t)T * K >= ((int64_t)1 << 31) || (int64_t)N * K >= ((int64_t)1 << 31)) return hipErrorInvalidValue;
     if (epilogue != EPI_SWIGLU && (N % 4)) return hipErrorInvalidValue;
     if (epilogue == EPI_SWIGLU && ((N / 2) % 8)) return hipErrorInvalidValue;
+    if (w_packed && (K % 64 || g_force_generic)) return hipErrorInvalidValue;   // only the direct-to-LDS kernel reads it
     GemmArgs p{};
+    p.w_packed = w_packed;
     p.a = static_cast<const uint16_t*>(a);
     p.w = static_cast<const uint16_t*>(w);
     p.residual = residual;
@@ -1019,12 +1046,15 @@ hipError_t launch_qkv_d(const GemmArgs& p, hipStream_t s) {
 }  // namespace
 
 hipError_t launch_qkv_rope_append(const BatchDev& b, const relserve_layer& L, const void* h, const void* w_qkv,
-                                  void* q_out, void* k_pages, void* v_pages, hipStream_t s, float* accum) {
+                                  void* q_out, void* k_pages, void* v_pages, hipStream_t s, float* accum,
+                                  bool w_packed) {
     if (b.T == 0) return hipSuccess;
     const int32_t K = L.cfg.hidden;
     if ((int64_t)b.T * K >= ((int64_t)1 << 31) || (int64_t)L.qkv_dim * K >= ((int64_t)1 << 31))
         return hipErrorInvalidValue;
     GemmArgs p{};
+    if (w_packed && (K % 64 || g_force_generic)) return hipErrorInvalidValue;
+    p.w_packed = w_packed;
     p.a = static_cast<const uint16_t*>(h);
     p.w = static_cast<const uint16_t*>(w_qkv);
     p.out = q_out;

@@ -442,16 +442,45 @@ int32_t relserve_rmsnorm(const void* x, int32_t x_is_f32, const void* w, float e
     return e == hipSuccess ? RELSERVE_OK : RELSERVE_ERR_HIP;
 }
 
-int32_t relserve_linear(const void* a, const void* w, int32_t T, int32_t N, int32_t K, int32_t epilogue,
-                        const void* residual, void* out, void* stream) {
+namespace {
+int32_t linear_entry(const void* a, const void* w, int32_t T, int32_t N, int32_t K, int32_t epilogue,
+                     const void* residual, void* out, void* stream, bool packed) {
     if (T < 0 || N <= 0 || K <= 0 || K % 8 || epilogue < 0 || epilogue > 3) return RELSERVE_ERR_BAD_ARGUMENT;
     if (epilogue == 3 ? (N % 16) : (N % 4)) return RELSERVE_ERR_BAD_ARGUMENT;
-    if ((int64_t)T * K >= ((int64_t)1 << 31) || (int64_t)N * K >= ((int64_t)1 << 31)) return RELSERVE_ERR_TOO_LARGE;
+    if (packed && K % 64) return RELSERVE_ERR_BAD_ARGUMENT;
+    const int64_t n_rows = packed ? ((int64_t)N + 255) / 256 * 256 : N;
+    if ((int64_t)T * K >= ((int64_t)1 << 31) || n_rows * K >= ((int64_t)1 << 31)) return RELSERVE_ERR_TOO_LARGE;
     if (T == 0) return RELSERVE_OK;
     if (!a || !w || !out) return RELSERVE_ERR_NULL_POINTER;
     if (epilogue == 2 && !residual) return RELSERVE_ERR_NULL_POINTER;
-    hipError_t e = launch_linear(a, w, T, N, K, epilogue, residual, out, static_cast<hipStream_t>(stream));
+    hipError_t e = launch_linear(a, w, T, N, K, epilogue, residual, out, static_cast<hipStream_t>(stream), nullptr, packed);
     return e == hipSuccess ? RELSERVE_OK : RELSERVE_ERR_HIP;
+}
+}  // namespace
+
+int32_t relserve_linear(const void* a, const void* w, int32_t T, int32_t N, int32_t K, int32_t epilogue,
+                        const void* residual, void* out, void* stream) {
+    return linear_entry(a, w, T, N, K, epilogue, residual, out, stream, false);
+}
+
+int32_t relserve_linear_packed(const void* a, const void* w_packed, int32_t T, int32_t N, int32_t K, int32_t epilogue,
+                               const void* residual, void* out, void* stream) {
+    return linear_entry(a, w_packed, T, N, K, epilogue, residual, out, stream, true);
+}
+
+int32_t relserve_packed_weight_elems(int32_t N, int32_t K, int64_t* out) {
+    if (!out) return RELSERVE_ERR_NULL_POINTER;
+    if (N <= 0 || K <= 0 || K % 64) return RELSERVE_ERR_BAD_ARGUMENT;
+    *out = ((int64_t)N + 255) / 256 * 256 * K;
+    return *out >= ((int64_t)1 << 31) ? RELSERVE_ERR_TOO_LARGE : RELSERVE_OK;
+}
+
+int32_t relserve_pack_weight(const void* w, int32_t N, int32_t K, void* out, void* stream) {
+    int64_t elems = 0;
+    if (int32_t rc = relserve_packed_weight_elems(N, K, &elems)) return rc;
+    if (!w || !out) return RELSERVE_ERR_NULL_POINTER;
+    return launch_pack_weight(w, N, K, out, static_cast<hipStream_t>(stream)) == hipSuccess ? RELSERVE_OK
+                                                                                              : RELSERVE_ERR_HIP;
 }
 
 int32_t relserve_rope_append(const relserve_layer* L, const relserve_batch* b, void* qkv,
@@ -504,6 +533,8 @@ int32_t relserve_layer_step(const relserve_layer* L, const relserve_batch* b, co
     if (!workspace || (reinterpret_cast<uintptr_t>(workspace) % kAlign)) return RELSERVE_ERR_WORKSPACE;
     Workspace w = carve(*L, T, workspace);
     if (w.total > workspace_bytes) return RELSERVE_ERR_WORKSPACE;
+    const bool packed = wt->packed != 0;
+    if (packed && (L->cfg.hidden % 64 || L->q_dim % 64 || L->cfg.mlp_dim % 64)) return RELSERVE_ERR_BAD_ARGUMENT;
 
     hipStream_t s = static_cast<hipStream_t>(stream);
     const relserve_layer_config& c = L->cfg;
@@ -525,15 +556,17 @@ int32_t relserve_layer_step(const relserve_layer* L, const relserve_batch* b, co
     if (used > 0) e = launch_fill_zero(accum, used, s);
     run(S_NORM1, [&] { return launch_rmsnorm(x, false, wt->w_in_norm, c.rms_eps, T, c.hidden, w.h, s); });
     run(S_QKV, [&] {
-        return launch_qkv_rope_append(b->dev, *L, w.h, wt->w_qkv, w.q, cache.k_pages, cache.v_pages, s, accum);
+        return launch_qkv_rope_append(b->dev, *L, w.h, wt->w_qkv, w.q, cache.k_pages, cache.v_pages, s, accum, packed);
     });
     if (e == hipSuccess)
         e = launch_attention(b->dev, *L, w.q, L->q_dim, cache.k_pages, cache.v_pages, w.attn, w.part_o,
                              w.part_ml, s, prof);
-    run(S_O, [&] { return launch_linear(w.attn, wt->w_o, T, c.hidden, L->q_dim, 1, x, w.x1, s, accum); });
+    run(S_O, [&] { return launch_linear(w.attn, wt->w_o, T, c.hidden, L->q_dim, 1, x, w.x1, s, accum, packed); });
     run(S_NORM2, [&] { return launch_rmsnorm(w.x1, true, wt->w_post_norm, c.rms_eps, T, c.hidden, w.h, s); });
-    run(S_GU, [&] { return launch_linear(w.h, wt->w_gate_up, T, 2 * c.mlp_dim, c.hidden, 3, nullptr, w.act, s, accum); });
-    run(S_DOWN, [&] { return launch_linear(w.act, wt->w_down, T, c.hidden, c.mlp_dim, 2, w.x1, y, s, accum); });
+    run(S_GU, [&] {
+        return launch_linear(w.h, wt->w_gate_up, T, 2 * c.mlp_dim, c.hidden, 3, nullptr, w.act, s, accum, packed);
+    });
+    run(S_DOWN, [&] { return launch_linear(w.act, wt->w_down, T, c.hidden, c.mlp_dim, 2, w.x1, y, s, accum, packed); });
     return e == hipSuccess ? RELSERVE_OK : RELSERVE_ERR_HIP;
 }
 

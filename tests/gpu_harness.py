@@ -35,11 +35,13 @@ def assert_close(got: np.ndarray, want: np.ndarray, what: str, max_abs=MAX_ABS, 
 class GpuLayer:
     """One layer's device state: weights, cache pools, workspace."""
 
-    def __init__(self, rs, shape, weights_bits: dict, k_pages_bits, v_pages_bits, max_tokens: int):
+    def __init__(self, rs, shape, weights_bits: dict, k_pages_bits, v_pages_bits, max_tokens: int, packed: bool = False):
         self.rs = rs
         self.shape = shape
         self.layer = rs.relserve_layer_create(shape)
         self.weights = {k: dev_bf16(v) for k, v in weights_bits.items()}
+        if packed:   # the four matrices in the library's tiled streaming layout
+            self.weights = rs.pack_layer_weights(self.weights)
         self.k_pages = dev_bf16(k_pages_bits)
         self.v_pages = dev_bf16(v_pages_bits)
         self.workspace = torch.empty(rs.relserve_workspace_bytes(self.layer, max_tokens), dtype=torch.uint8, device="cuda")

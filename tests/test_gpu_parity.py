@@ -288,13 +288,13 @@ def test_multi_step_flow_matches_oracle(rs, oracle, shape):
 # full-size configurations, checked on sampled requests (the oracle recomputes the
 # sampled requests as a sub-batch over the same cache: requests are independent)
 # ---------------------------------------------------------------------------
-def _sampled_parity(rs, oracle, wl, reqs, max_prefill_rows=None):
+def _sampled_parity(rs, oracle, wl, reqs, max_prefill_rows=None, packed=False):
     shape, b = wl.shape, wl.batch
     print(f"[case] {wl.name}: T={b.T} reqs={b.num_reqs} sampled={list(reqs)}", flush=True)
     weights = wl.weights()
     x = W.make_activations(b.T, shape.hidden, wl.seed)
     kp, vp = W.make_cache(shape, b.num_pages, wl.seed)
-    gl = GpuLayer(rs, shape, weights, kp, vp, b.T)
+    gl = GpuLayer(rs, shape, weights, kp, vp, b.T, packed=packed)
     y = host_f32(gl.step(b, x))
     sub = b.select(reqs)
     rows = b.token_rows(reqs)
@@ -453,6 +453,87 @@ def test_model_step_13b_two_layer_slice(rs, oracle):
     reqs = [0, 77, 127, 128]
     print(f"[case] 2-layer 13B model step, requests {reqs} of {wl.batch.num_reqs}", flush=True)
     _model_case(rs, oracle, wl.shape, wl.batch.select(reqs), 2, 32000, 92, True, "model step 13B x2")
+
+
+# ---------------------------------------------------------------------------
+# packed (tiled) weight layout: same arithmetic, different addresses
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("N,K", [(256, 64), (300, 128), (768, 256), (5120, 1024), (1000, 192)])
+def test_pack_weight_layout_bit_exact(rs, N, K):
+    rng = np.random.default_rng(N + K)
+    wb = rng.integers(0, 1 << 16, (N, K), dtype=np.uint16)
+    w = dev_bf16(wb)
+    out = torch.empty(rs.relserve_packed_weight_elems(N, K), dtype=torch.bfloat16, device="cuda")
+    rs.relserve_pack_weight(w, out)
+    torch.cuda.synchronize()
+    n_pad = (N + 255) // 256 * 256
+    want = np.zeros((n_pad, K), np.uint16)
+    want[:N] = wb
+    want = want.reshape(n_pad // 256, 256, K // 64, 64).transpose(0, 2, 1, 3).reshape(-1)   # [block][k slice][row][k]
+    assert np.array_equal(host_bits(out).reshape(-1), want)
+
+
+@pytest.mark.parametrize("T,N,K", [(1, 256, 256), (134, 768, 256), (77, 264, 1024), (1384, 5120, 5120), (520, 15360, 512),
+                                   (2304, 1024, 384), (4100, 4096, 128)])
+def test_linear_packed_equals_row_major(rs, T, N, K):
+    """Every epilogue on packed weights gives bit-identical results to the row-major call (same kernels, same order)."""
+    rng = np.random.default_rng(T + N + K + 1)
+    a = dev_bf16(W.f32_to_bf16_bits(rng.standard_normal((T, K), dtype=np.float32)))
+    w = dev_bf16(W.f32_to_bf16_bits(rng.standard_normal((N, K), dtype=np.float32) * 0.05))
+    wp = torch.empty(rs.relserve_packed_weight_elems(N, K), dtype=torch.bfloat16, device="cuda")
+    rs.relserve_pack_weight(w, wp)
+    resb = dev_bf16(W.f32_to_bf16_bits(rng.standard_normal((T, N), dtype=np.float32)))
+    resf = torch.from_numpy(rng.standard_normal((T, N), dtype=np.float32)).cuda()
+    for epi, res, shape, dt in ((0, None, (T, N), torch.bfloat16), (1, resb, (T, N), torch.float32),
+                                (2, resf, (T, N), torch.bfloat16), (3, None, (T, N // 2), torch.bfloat16)):
+        if epi == 3 and N % 16:
+            continue
+        o1 = torch.empty(shape, dtype=dt, device="cuda")
+        o2 = torch.empty(shape, dtype=dt, device="cuda")
+        rs.relserve_linear(a, w, epi, res, o1)
+        rs.relserve_linear_packed(a, wp, N, epi, res, o2)
+        torch.cuda.synchronize()
+        assert torch.equal(o1, o2), f"epilogue {epi}"
+
+
+def test_packed_rejects_shapes_it_cannot_serve(rs):
+    with pytest.raises(rs.RelserveError):
+        rs.relserve_packed_weight_elems(256, 100)          # K not a multiple of 64
+    shape = W.TINY                                          # mlp width 688 is not a multiple of 64
+    wl = W.workload_tiny()
+    gl = GpuLayer(rs, shape, {k: v for k, v in W.make_weights(shape, 3).items()}, *W.make_cache(shape, wl.batch.num_pages, 3), wl.batch.T)
+    gl.weights = dict(gl.weights, packed=True)             # claims a packing the shape does not allow
+    with pytest.raises(rs.RelserveError):
+        gl.step(wl.batch, W.make_activations(wl.batch.T, shape.hidden, 3))
+
+
+@pytest.mark.parametrize("make", [W.workload_tiny, W.workload_tiny_prefix])
+def test_layer_step_tiny_packed(rs, oracle, make):
+    shape = W.LayerShape(256, 8, 2, 64, 704)               # as the tiny GQA shape, mlp width a multiple of 64
+    wl = make(shape=shape)
+    b = wl.batch
+    weights = W.make_weights(shape, wl.seed)
+    x = W.make_activations(b.T, shape.hidden, wl.seed)
+    kp, vp = W.make_cache(shape, b.num_pages, wl.seed)
+    y = host_f32(GpuLayer(rs, shape, weights, kp, vp, b.T, packed=True).step(b, x))
+    res = oracle.layer_step(shape, b, weights, x, kp, vp)
+    assert_close(y, res.y_f32, "tiny layer step, packed weights")
+
+
+def test_full_size_relquery_13b_packed(rs, oracle):
+    _sampled_parity(rs, oracle, W.workload_relquery_13b(), [0, 16, 99, 199], packed=True)
+
+
+def test_full_size_decode_only_70b_packed(rs, oracle):
+    _sampled_parity(rs, oracle, W.workload_decode_heavy_70b(with_chunk=False), [0, 63, 64, 128, 255], packed=True)
+
+
+def test_full_size_decode_only_13b_packed(rs, oracle):
+    _sampled_parity(rs, oracle, W.workload_decode_plus_chunk_13b(0), [0, 64, 127], packed=True)
+
+
+def test_full_size_prefill_only_13b_packed(rs, oracle):
+    _sampled_parity(rs, oracle, W.workload_prefill_only_13b(), [0, 63], max_prefill_rows=24, packed=True)
 
 
 def test_peak_probes_run(rs):

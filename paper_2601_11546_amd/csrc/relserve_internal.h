@@ -111,11 +111,14 @@ int64_t gemm_scratch_floats(int64_t T, int64_t n_max);
 int64_t gemm_scratch_used(int32_t T, int32_t N, int32_t K, bool qkv);
 void gemm_force_plan(int cand, int splits);   // test hook, see relserve_debug_force_gemm_plan
 hipError_t launch_linear(const void* a, const void* w, int32_t T, int32_t N, int32_t K, int32_t epilogue,
-                         const void* residual, void* out, hipStream_t s, float* accum = nullptr);
+                         const void* residual, void* out, hipStream_t s, float* accum = nullptr, bool w_packed = false);
+// w [N, K] row-major -> the tiled streaming layout (ceil(N / 256) * 256 * K elements), K % 64 == 0
+hipError_t launch_pack_weight(const void* w, int32_t N, int32_t K, void* out, hipStream_t s);
 hipError_t launch_fill_zero(float* ptr, int64_t n_floats, hipStream_t s);
 // q/k/v projection with rotary embedding and KV append fused into the epilogue: q_out [T, n_q d] bf16.
 hipError_t launch_qkv_rope_append(const BatchDev& b, const relserve_layer& L, const void* h, const void* w_qkv,
-                                  void* q_out, void* k_pages, void* v_pages, hipStream_t s, float* accum = nullptr);
+                                  void* q_out, void* k_pages, void* v_pages, hipStream_t s, float* accum = nullptr,
+                                  bool w_packed = false);
 // Attention passes; part_o [T, n_q, d] fp32 and part_ml [T, n_q, 2] fp32 hold the prefix partials.
 hipError_t launch_attention(const BatchDev& b, const relserve_layer& L, const void* q, int32_t q_pitch,
                             const void* k_pages, const void* v_pages, void* out, float* part_o,

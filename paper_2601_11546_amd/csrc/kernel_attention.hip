@@ -230,9 +230,12 @@ __global__ void __launch_bounds__(256, 2) attn_tile_kernel(AttnArgs p) {
         }
     }
     const float scale = p.scale_log2;
-    // One 32-key tile: S^T = K Q^T, online softmax in the log2 domain (the scale is folded into the
+    // A 32-key tile: S^T = K Q^T, online softmax in the log2 domain (the scale is folded into the
     // exponent's multiply-add; the running maximum is kept scaled), O^T += V^T P^T.
-    auto tile = [&](bool masked, int t, const unsigned char* stage, int key0) {
+    // The three phases of a 32-key tile.  The block loop issues the score MFMAs of BOTH tiles first, so
+    // that the second tile's MFMAs (and later the first tile's P V MFMAs) run while the VALU does the
+    // other tile's softmax.
+    auto scores = [&](int t, const unsigned char* stage) {
         f32x16_t sc;
 #pragma unroll
         for (int r = 0; r < 16; ++r) sc[r] = 0.f;
@@ -241,6 +244,9 @@ __global__ void __launch_bounds__(256, 2) attn_tile_kernel(AttnArgs p) {
             const bf16x8_t kf = as_bf16x8(*reinterpret_cast<const uint4*>(stage + k_off[ks] + t * 32 * SM::ROWB));
             sc = mfma_32x32x16(kf, qf[ks], sc);
         }
+        return sc;
+    };
+    auto softmax = [&](f32x16_t& sc, bool masked, int key0, bf16x8_t (&pf)[2]) {
         if (masked) {   // wave-uniform: only the blocks that straddle some row's limit pay for the mask
             const int lim = klim - key0 - 4 * g;
 #pragma unroll
@@ -261,7 +267,6 @@ __global__ void __launch_bounds__(256, 2) attn_tile_kernel(AttnArgs p) {
         const float alpha = __builtin_amdgcn_exp2f(st.m - m_use);
         st.m = m_new;
         float psum = 0.f;
-        bf16x8_t pf[2];
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
             uint32_t w[4];
@@ -281,8 +286,10 @@ __global__ void __launch_bounds__(256, 2) attn_tile_kernel(AttnArgs p) {
 #pragma unroll
                 for (int r = 0; r < 16; ++r) st.o[td][r] *= alpha;
         }
-        // Element e of lane group g's probabilities is key 32 t + 16 h + 8 (e / 4) + 4 g + e % 4; the two
-        // transposing reads fetch those keys.
+    };
+    // Element e of lane group g's probabilities is key 32 t + 16 h + 8 (e / 4) + 4 g + e % 4; the two
+    // transposing reads fetch those keys.
+    auto weighted_values = [&](int t, const unsigned char* stage, const bf16x8_t (&pf)[2]) {
         typedef short short8_t __attribute__((ext_vector_type(8)));
         typedef short4_t __attribute__((address_space(3))) * lds_v4;
 #pragma unroll
@@ -308,8 +315,13 @@ __global__ void __launch_bounds__(256, 2) attn_tile_kernel(AttnArgs p) {
         if (wave_active && kb0 < wave_klim_max) {
             const unsigned char* stage = smem + (b & 1) * SM::STAGE;
             const bool masked = __builtin_amdgcn_readfirstlane(kb0 + BLOCK_N > wave_klim_min);
-            tile(masked, 0, stage, kb0);
-            tile(masked, 1, stage, kb0 + 32);
+            f32x16_t sc0 = scores(0, stage);
+            f32x16_t sc1 = scores(1, stage);
+            bf16x8_t pf[2];
+            softmax(sc0, masked, kb0, pf);
+            weighted_values(0, stage, pf);
+            softmax(sc1, masked, kb0 + 32, pf);
+            weighted_values(1, stage, pf);
         }
     }
     if (valid) state_store<D>(st, p, it, row_id, g);

@@ -36,8 +36,9 @@ def build_workload(name: str):
         "decode_only_70b": lambda: W.workload_decode_heavy_70b(with_chunk=False),
         "prefill_only_13b": W.workload_prefill_only_13b,               # configs[3]
         "decode128_13b": lambda: W.workload_decode_plus_chunk_13b(0),  # configs[4], one layer, chunk 0
-        "decode128_chunk2048_13b": lambda: W.workload_decode_plus_chunk_13b(2048),
     }
+    for c in (512, 1024, 2048, 4096):                                  # configs[4] with a prefill chunk of c tokens
+        table[f"decode128_chunk{c}_13b"] = (lambda c=c: W.workload_decode_plus_chunk_13b(c))
     if name not in table:
         raise SystemExit(f"unknown workload {name!r}; choose from {sorted(table)}")
     return table[name]()
@@ -126,6 +127,61 @@ def peak_probes(rs, torch) -> dict:
             "note": "random bf16 operands, 16 independent accumulators per wave; 4 GiB read with 16-byte loads"}
 
 
+def model_step_bench(args, rs, W, torch) -> dict:
+    """The model step (Sec. 2.3 "LLM Inference": embedding, layer stack, output layer on the last hidden states)
+    at full depth.  Weights and caches are drawn on the device (a 40-layer 13B stack with 128 contexts of 1024
+    tokens is 25 GB of weights and 107 GB of KV cache); values follow the same distributions as the
+    host-seeded workloads, seeded with torch's generator."""
+    wl = build_workload(args.workload)
+    shape, b, n_layers, vocab = wl.shape, wl.batch, args.model_layers, 32000
+    g = torch.Generator(device="cuda")
+    g.manual_seed(wl.seed)
+
+    def randn(*size, std=1.0, mean=0.0):
+        return (torch.randn(*size, generator=g, device="cuda", dtype=torch.float32) * std + mean).to(torch.bfloat16)
+
+    H, I, qd, qkv = shape.hidden, shape.mlp_dim, shape.n_q_heads * shape.head_dim, shape.qkv_dim
+    res_std = 0.02 / (2 * n_layers) ** 0.5
+    layers, caches = [], []
+    pool = (b.num_pages, shape.page_size, shape.n_kv_heads, shape.head_dim)
+    for _ in range(n_layers):
+        w = {"w_in_norm": randn(H, std=0.02, mean=1.0), "w_qkv": randn(qkv, H, std=0.02), "w_o": randn(H, qd, std=res_std),
+             "w_post_norm": randn(H, std=0.02, mean=1.0), "w_gate_up": randn(2 * I, H, std=0.02), "w_down": randn(H, I, std=res_std)}
+        layers.append(w if args.row_major_weights else rs.pack_layer_weights(w))
+        caches.append((randn(*pool), randn(*pool)))
+    model = {"embedding": randn(vocab, H), "layers": layers, "caches": caches, "w_final_norm": randn(H, std=0.02, mean=1.0),
+             "w_lm_head": randn(vocab, H, std=0.02)}
+    ids = torch.randint(0, vocab, (b.T,), generator=g, device="cuda", dtype=torch.int32)
+    layer = rs.relserve_layer_create(shape)
+    pb = rs.relserve_batch_prepare(layer, b)
+    ws = torch.empty(rs.relserve_model_workspace_bytes(layer, b.T, b.num_reqs), dtype=torch.uint8, device="cuda")
+    logits = torch.empty(b.num_reqs, vocab, dtype=torch.float32, device="cuda")
+    steps, warm = max(1, min(args.steps, 10)), max(1, min(args.warmup, 2))
+    for _ in range(warm):
+        rs.relserve_model_step(layer, pb, model, ids, logits, ws)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        rs.relserve_model_step(layer, pb, model, ids, logits, ws)
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) / steps * 1e3
+    assert bool(torch.isfinite(logits).all())
+    c = algorithmic_counts(shape, b)
+    flops = n_layers * c["flops_total"] + 2 * b.num_reqs * vocab * H
+    nbytes = n_layers * c["bytes_total"] + (vocab * H + b.T * H) * 2
+    hbm = torch.cuda.max_memory_allocated() / 1e9
+    return {"metric": "model_step_tokens_per_s", "value": round(b.T / (ms * 1e-3), 1), "unit": "tokens/s", "n_gpus": 1,
+            "steps": steps, "warmup": warm, "ms_per_step": round(ms, 3), "higher_is_better": True, "scaling": "weak",
+            "vs_baseline": None, "dtype": "bf16", "data": "synthetic (drawn on the device)",
+            "config": {"workload": f"model_step_{wl.name}", "layers": n_layers, "vocab": vocab, "query_tokens": b.T,
+                       "requests": b.num_reqs, "weight_layout": "row-major" if args.row_major_weights else "packed",
+                       "hbm_allocated_gb": round(hbm, 1)},
+            "step": {"ms_per_layer": round(ms / n_layers, 4), "tflops": round(flops / (ms * 1e-3) / 1e12, 1),
+                     "frac_mfma_peak": round(flops / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
+                     "algorithmic_gbs": round(nbytes / (ms * 1e-3) / 1e9, 1),
+                     "frac_hbm_peak": round(nbytes / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)}}
+
+
 def main() -> None:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -135,6 +191,9 @@ def main() -> None:
     ap.add_argument("--layer-sets", type=int, default=0, help="independent (weights, cache) sets to rotate over (0 = auto)")
     ap.add_argument("--row-major-weights", action="store_true",
                     help="feed the projections row-major [out, in] weights instead of the packed streaming layout")
+    ap.add_argument("--model-layers", type=int, default=0,
+                    help="time the model step (embedding, this many layers, final norm, output layer) instead of one layer step; "
+                         "device-generated weights and caches, e.g. --workload decode128_13b --model-layers 40 (133 GB of HBM)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-peak-probes", action="store_true", help="skip the MFMA issue loop and the streaming read")
     ap.add_argument("--calibration-copy", action="store_true",
@@ -151,6 +210,9 @@ def main() -> None:
 
     assert torch.cuda.is_available(), "bench.py needs an MI355X"
     torch.cuda.set_device(0)
+    if args.model_layers > 0:
+        print(json.dumps(model_step_bench(args, rs, W, torch)))
+        return
     wl = build_workload(args.workload)
     shape, b = wl.shape, wl.batch
     counts = algorithmic_counts(shape, b)

@@ -67,7 +67,7 @@ def algorithmic_counts(shape, batch) -> dict:
     bytes_total = weights + uniq_tokens * kv_tok + 2 * T * H * 2 + T * kv_tok
     return {"gemm_flops": gemm, "attn_flops": attn_flops, "flops_total": sum(gemm.values()) + attn_flops,
             "weight_bytes": weights, "kv_unique_bytes": uniq_tokens * kv_tok, "bytes_total": bytes_total,
-            "kv_decode_own_bytes": own_tokens["decode"] * kv_tok,
+            "kv_decode_own_bytes": own_tokens["decode"] * kv_tok, "kv_prefill_own_bytes": own_tokens["prefill"] * kv_tok,
             "kv_naive_bytes": int(batch.ctx_len.astype(np.int64).sum()) * kv_tok}
 
 
@@ -297,11 +297,15 @@ def main() -> None:
             k["tflops"] = round(counts["gemm_flops"][name] / (avg_ms * 1e-3) / 1e12, 1)
             k["frac_mfma_peak"] = round(k["tflops"] / PEAK_BF16_TFLOPS, 4)
         kernels[name] = k
-    attn_ms = sum(kernels[n]["avg_ms"] for n in ("attn_prefix", "attn_tile", "attn_split") if n in kernels)
+    attn_ms = sum(kernels[n]["avg_ms"] for n in ("attn_prefix", "attn_own_keys", "attn_tile", "attn_split") if n in kernels)
     if attn_ms > 0:
         kernels["attention_all"] = {"avg_ms": round(attn_ms, 4),
                                     "tflops": round(counts["attn_flops"] / (attn_ms * 1e-3) / 1e12, 1),
                                     "kv_unique_gbs": round(counts["kv_unique_bytes"] / (attn_ms * 1e-3) / 1e9, 1)}
+    if "attn_own_keys" in kernels:   # prefill rows and decode rows over their own keys in one launch
+        gbs = (counts["kv_decode_own_bytes"] + counts["kv_prefill_own_bytes"]) / (kernels["attn_own_keys"]["avg_ms"] * 1e-3) / 1e9
+        kernels["attn_own_keys"]["kv_gbs"] = round(gbs, 1)
+        kernels["attn_own_keys"]["frac_hbm_peak"] = round(gbs / PEAK_HBM_GBS, 4)
     if "attn_split" in kernels and counts["kv_decode_own_bytes"]:
         gbs = counts["kv_decode_own_bytes"] / (kernels["attn_split"]["avg_ms"] * 1e-3) / 1e9
         kernels["attn_split"]["kv_gbs"] = round(gbs, 1)

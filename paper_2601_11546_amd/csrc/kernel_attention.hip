@@ -31,6 +31,8 @@ namespace {
 
 struct AttnArgs {
     const AttnItem* items;
+    const AttnItem* items_b;   // fused launch only: the decode items (items = the row-tiled items)
+    int32_t n_items_b;
     const int32_t* attn_tok;
     const int32_t* tok_pos;
     const int32_t* block_table;
@@ -140,7 +142,7 @@ __device__ __forceinline__ void dma16_ptr(const void* gptr, uint32_t lds_addr) {
 typedef short short4_t __attribute__((ext_vector_type(4)));
 
 template <int D>
-__global__ void __launch_bounds__(256, 2) attn_tile_kernel(AttnArgs p) {
+__device__ __forceinline__ void attn_tile_body(const AttnArgs& p, int item_idx, int kvh) {
     using SM = TileSmem<D>;
     constexpr int BLOCK_N = SM::BLOCK_N;
     constexpr int CH = D / 8;                 // 16-byte chunks per K/V row
@@ -148,8 +150,7 @@ __global__ void __launch_bounds__(256, 2) attn_tile_kernel(AttnArgs p) {
     constexpr int IT = BLOCK_N / (4 * RPI);   // wave loads per wave, per tensor and block
     extern __shared__ __align__(16) unsigned char smem[];
 
-    const AttnItem it = p.items[blockIdx.x];
-    const int kvh = blockIdx.y;
+    const AttnItem it = p.items[item_idx];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l32 = lane & 31, g = lane >> 5;
@@ -351,7 +352,7 @@ template <int D>
 __device__ __forceinline__ int dvswz(int row) { return D == 128 ? 2 * (row & 7) : 2 * ((row >> 1) & 3); }
 
 template <int D>
-__global__ void __launch_bounds__(256) attn_decode_kernel(AttnArgs p) {
+__device__ __forceinline__ void attn_decode_body(const AttnArgs& p, const AttnItem* items, int n_items, int wg_idx, int kvh) {
     using SM = DecodeSmem<D>;
     constexpr int CH = D / 8;                 // 16-byte chunks per K/V row
     constexpr int RPI = 64 / CH;              // rows one 1 KB wave load covers
@@ -362,10 +363,9 @@ __global__ void __launch_bounds__(256) attn_decode_kernel(AttnArgs p) {
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l16 = lane & 15, gq = lane >> 4;
-    const int item_idx = blockIdx.x * 4 + wave;
-    if (item_idx >= p.n_items) return;           // whole wave leaves; the kernel has no workgroup barrier
-    const AttnItem it = p.items[item_idx];
-    const int kvh = blockIdx.y;
+    const int item_idx = wg_idx * 4 + wave;
+    if (item_idx >= n_items) return;             // whole wave leaves; this path has no workgroup barrier
+    const AttnItem it = items[item_idx];
     unsigned char* sk = smem + wave * SM::WAVE_BYTES;
     const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)sk;
 
@@ -522,22 +522,57 @@ __global__ void __launch_bounds__(256) attn_decode_kernel(AttnArgs p) {
 }
 
 template <int D>
-hipError_t launch_d(const AttnArgs& base, const AttnItem* items, int32_t n_items, bool decode, hipStream_t s) {
+__global__ void __launch_bounds__(256, 2) attn_tile_kernel(AttnArgs p) {
+    attn_tile_body<D>(p, blockIdx.x, blockIdx.y);
+}
+
+template <int D>
+__global__ void __launch_bounds__(256, 2) attn_decode_kernel(AttnArgs p) {
+    attn_decode_body<D>(p, p.items, p.n_items, blockIdx.x, blockIdx.y);
+}
+
+// Prefill rows (row-tiled items) and decode rows (wave items) over their own keys in ONE launch: the two
+// item lists are independent, each alone leaves part of the chip idle at its end, and both need the same
+// registers and LDS.  Workgroups [0, n_items n_kv) take the tiled items (the longer ones), the rest the
+// decode items, four per workgroup.
+template <int D>
+__global__ void __launch_bounds__(256, 2) attn_own_keys_kernel(AttnArgs p) {
+    const int n_tile_wg = p.n_items * p.n_kv;
+    const int b = blockIdx.x;
+    if (b < n_tile_wg) {
+        attn_tile_body<D>(p, b % p.n_items, b / p.n_items);
+    } else {
+        const int n_dec_wg = (p.n_items_b + 3) / 4;
+        attn_decode_body<D>(p, p.items_b, p.n_items_b, (b - n_tile_wg) % n_dec_wg, (b - n_tile_wg) / n_dec_wg);
+    }
+}
+
+template <int D>
+hipError_t launch_d(const AttnArgs& base, const AttnItem* items, int32_t n_items, const AttnItem* items_b,
+                    int32_t n_items_b, bool decode, hipStream_t s) {
     static bool attr_done = false;
     constexpr int tile_smem = 2 * TileSmem<D>::STAGE, dec_smem = 4 * DecodeSmem<D>::WAVE_BYTES;
+    constexpr int both_smem = tile_smem > dec_smem ? tile_smem : dec_smem;
     if (!attr_done) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_tile_kernel<D>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, tile_smem);
         if (e == hipSuccess)
             e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_decode_kernel<D>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, dec_smem);
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_own_keys_kernel<D>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, both_smem);
         if (e != hipSuccess) return e;
         attr_done = true;
     }
     AttnArgs p = base;
     p.items = items;
     p.n_items = n_items;
-    if (decode)
+    p.items_b = items_b;
+    p.n_items_b = n_items_b;
+    if (items_b)
+        attn_own_keys_kernel<D><<<dim3(n_items * p.n_kv + (n_items_b + 3) / 4 * p.n_kv), dim3(256), both_smem, s>>>(p);
+    else if (decode)
         attn_decode_kernel<D><<<dim3((n_items + 3) / 4, p.n_kv), dim3(256), dec_smem, s>>>(p);
     else
         attn_tile_kernel<D><<<dim3(n_items, p.n_kv), dim3(256), tile_smem, s>>>(p);
@@ -569,15 +604,18 @@ hipError_t launch_attention(const BatchDev& b, const relserve_layer& L, const vo
     p.scale_log2 = (float)(1.4426950408889634 / sqrt((double)L.cfg.head_dim));
     const bool d128 = L.cfg.head_dim == 128;
     hipError_t e = hipSuccess;
-    struct Pass { int slot; const AttnItem* items; int32_t n; bool decode; };
-    const Pass passes[3] = {{3, b.items_prefix, b.n_items_prefix, false},
-                            {4, b.items_tile, b.n_items_tile, false},
-                            {5, b.items_split, b.n_items_split, true}};
-    for (const Pass& ps : passes) {
-        if (e != hipSuccess || ps.n == 0) continue;
-        profile_mark(prof, ps.slot, s, true);
-        e = d128 ? launch_d<128>(p, ps.items, ps.n, ps.decode, s) : launch_d<64>(p, ps.items, ps.n, ps.decode, s);
-        profile_mark(prof, ps.slot, s, false);
+    auto launch = [&](int slot, const AttnItem* items, int32_t n, const AttnItem* items_b, int32_t n_b, bool decode) {
+        if (e != hipSuccess || n == 0) return;
+        profile_mark(prof, slot, s, true);
+        e = d128 ? launch_d<128>(p, items, n, items_b, n_b, decode, s) : launch_d<64>(p, items, n, items_b, n_b, decode, s);
+        profile_mark(prof, slot, s, false);
+    };
+    launch(3, b.items_prefix, b.n_items_prefix, nullptr, 0, false);
+    if (b.n_items_tile > 0 && b.n_items_split > 0) {   // both kinds of rows: one launch for their own keys
+        launch(2, b.items_tile, b.n_items_tile, b.items_split, b.n_items_split, false);
+    } else {
+        launch(4, b.items_tile, b.n_items_tile, nullptr, 0, false);
+        launch(5, b.items_split, b.n_items_split, nullptr, 0, true);
     }
     return e;
 }

@@ -15,9 +15,9 @@ constexpr size_t kAlign = 256;
 inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
 const char* const kSlotNames[RELSERVE_PROFILE_SLOTS] = {
-    "rmsnorm_in", "gemm_qkv_rope_append", "unused", "attn_prefix", "attn_tile", "attn_split",
+    "rmsnorm_in", "gemm_qkv_rope_append", "attn_own_keys", "attn_prefix", "attn_tile", "attn_split",
     "gemm_o",     "rmsnorm_post", "gemm_gate_up", "gemm_down",  "unused",    "unused"};
-enum { S_NORM1 = 0, S_QKV, S_ROPE, S_ATTN_PREFIX, S_ATTN_TILE, S_ATTN_SPLIT, S_O, S_NORM2, S_GU, S_DOWN };
+enum { S_NORM1 = 0, S_QKV, S_ATTN_OWN, S_ATTN_PREFIX, S_ATTN_TILE, S_ATTN_SPLIT, S_O, S_NORM2, S_GU, S_DOWN };
 
 struct Workspace {
     char* h;         // [T, H] bf16 (normed activations; reused for the post norm)

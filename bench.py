@@ -39,6 +39,10 @@ def build_workload(name: str):
     }
     for c in (512, 1024, 2048, 4096):                                  # configs[4] with a prefill chunk of c tokens
         table[f"decode128_chunk{c}_13b"] = (lambda c=c: W.workload_decode_plus_chunk_13b(c))
+    import re
+    m = re.fullmatch(r"prefill_chunk(\d+)_13b", name)                   # one prefill chunk of any size, no decode rows
+    if m:
+        table[name] = lambda: W.workload_decode_plus_chunk_13b(int(m.group(1)), n_dec=0)
     if name not in table:
         raise SystemExit(f"unknown workload {name!r}; choose from {sorted(table)}")
     return table[name]()
@@ -194,6 +198,9 @@ def main() -> None:
     ap.add_argument("--model-layers", type=int, default=0,
                     help="time the model step (embedding, this many layers, final norm, output layer) instead of one layer step; "
                          "device-generated weights and caches, e.g. --workload decode128_13b --model-layers 40 (133 GB of HBM)")
+    ap.add_argument("--duration-model", action="store_true",
+                    help="instead of the benchmark line: time the 13B layer step over seeded prefill and decode batches and "
+                         "print the fitted batch-duration model (slope, intercept, R^2 against uncached and total tokens)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-peak-probes", action="store_true", help="skip the MFMA issue loop and the streaming read")
     ap.add_argument("--calibration-copy", action="store_true",
@@ -212,6 +219,10 @@ def main() -> None:
     torch.cuda.set_device(0)
     if args.model_layers > 0:
         print(json.dumps(model_step_bench(args, rs, W, torch)))
+        return
+    if args.duration_model:
+        from paper_2601_11546_amd import duration_model
+        print(json.dumps(duration_model.run(steps=max(1, min(args.steps, 10)), warmup=max(1, min(args.warmup, 3)))))
         return
     wl = build_workload(args.workload)
     shape, b = wl.shape, wl.batch

@@ -25,6 +25,9 @@
  *     enqueued there asynchronously, no call synchronises except
  *     relserve_batch_prepare (one blocking descriptor upload) and the
  *     relserve_profile_* readers.
+ *   - a call that enqueues GPU work first discards the error, if any, that an
+ *     earlier HIP call of the calling thread left pending in the runtime, so that
+ *     RELSERVE_ERR_HIP always refers to this call's own launches.
  *   - all 16-bit floating point data are bfloat16, all matrices row-major.
  *   - layouts: activations [T, features]; weights [out_features, in_features];
  *     w_qkv rows = [q heads | k heads | v heads]; w_gate_up rows = [gate | up];
@@ -245,6 +248,25 @@ int32_t relserve_qkv_rope_append(const relserve_layer* layer, const relserve_bat
 int32_t relserve_attention(const relserve_layer* layer, const relserve_batch* batch,
                            const void* q, int32_t q_pitch, relserve_kv_cache cache,
                            void* out, void* workspace, size_t workspace_bytes, void* stream);
+
+/* ---- batch-duration model (Sec. 4.2, Eq. 9) ----
+ * The scheduler predicts the duration of a prefill batch p as alpha_p * utok(p) + beta_p (utok = query
+ * tokens the batch really computes, i.e. not served by the prefix cache) and of a decode batch d as
+ * alpha_d * req(d) + beta_d (req = its requests); the coefficients come from fitting durations measured
+ * offline.  relserve_duration_fit is that fit (ordinary least squares): units[i] = size measure of run
+ * i, seconds[i] = its measured duration, both HOST arrays of n >= 2 finite values that are read only;
+ * *out receives slope, intercept, the coefficient of determination r2 = 1 - SS_res / SS_tot (1 when all
+ * durations are equal and fitted exactly) and n.  RELSERVE_ERR_BAD_ARGUMENT: n < 2, a non-finite value,
+ * or all units equal.  relserve_duration_predict evaluates Eq. 9 for one batch.  Host only; no device
+ * work, no allocation. */
+typedef struct relserve_duration_model {
+    double  alpha;   /* seconds per unit */
+    double  beta;    /* seconds */
+    double  r2;
+    int32_t n;
+} relserve_duration_model;
+int32_t relserve_duration_fit(const double* units, const double* seconds, int32_t n, relserve_duration_model* out);
+int32_t relserve_duration_predict(const relserve_duration_model* model, double units, double* seconds);
 
 /* ---- peak probes: what this GPU sustains, reported by bench.py beside the published peaks ----
  * relserve_peak_probe_mfma enqueues 256 workgroups of 4 waves that each issue iters x 16 independent

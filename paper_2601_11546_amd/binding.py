@@ -18,6 +18,11 @@ LIB_PATH = os.path.join(_HERE, "librelserve.so")
 if not os.path.exists(LIB_PATH):
     raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2601_11546_amd.build` "
                       "(there is no CPU or PyTorch fallback for the layer step)")
+# PyTorch ships its own HIP runtime; the library must bind to that one (streams and device pointers come
+# from torch), so torch is loaded before the library.  Loaded the other way round, the process holds two
+# runtimes and every launch on a torch stream fails.
+import torch  # noqa: E402,F401
+
 _lib = C.CDLL(LIB_PATH)
 
 PROFILE_SLOTS = 12
@@ -29,7 +34,8 @@ EXPORTS = ["relserve_version", "relserve_strerror", "relserve_config_validate", 
            "relserve_qkv_rope_append",
            "relserve_attention", "relserve_profile_slot_name", "relserve_profile_enable", "relserve_profile_read",
            "relserve_debug_force_gemm_plan", "relserve_peak_probe_mfma", "relserve_peak_probe_stream",
-           "relserve_packed_weight_elems", "relserve_pack_weight", "relserve_linear_packed"]
+           "relserve_packed_weight_elems", "relserve_pack_weight", "relserve_linear_packed",
+           "relserve_duration_fit", "relserve_duration_predict"]
 
 
 class RelserveError(RuntimeError):
@@ -65,6 +71,10 @@ class LayerWeights(C.Structure):
 class Model(C.Structure):
     _fields_ = [("n_layers", C.c_int32), ("vocab", C.c_int32), ("embedding", C.c_void_p), ("layers", C.c_void_p),
                 ("caches", C.c_void_p), ("w_final_norm", C.c_void_p), ("w_lm_head", C.c_void_p)]
+
+
+class DurationModel(C.Structure):
+    _fields_ = [("alpha", C.c_double), ("beta", C.c_double), ("r2", C.c_double), ("n", C.c_int32)]
 
 
 class BatchInfo(C.Structure):
@@ -109,6 +119,8 @@ for _n, _a in {
     "relserve_peak_probe_mfma": [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p],
     "relserve_peak_probe_stream": [C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p],
     "relserve_profile_read": [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32],
+    "relserve_duration_fit": [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p],
+    "relserve_duration_predict": [C.c_void_p, C.c_double, C.c_void_p],
 }.items():
     getattr(_lib, _n).restype = C.c_int32
     getattr(_lib, _n).argtypes = _a
@@ -378,3 +390,22 @@ def relserve_profile_read(layer, reset: bool = True) -> dict:
         if n[i]:
             out[relserve_profile_slot_name(i)] = {"ms_sum": ms[i], "launches": int(n[i])}
     return out
+
+
+def relserve_duration_fit(units, seconds) -> dict:
+    """Eq. 9's coefficients from measured (size, duration) points: {"alpha", "beta", "r2", "n"}."""
+    u = np.ascontiguousarray(units, np.float64)
+    s = np.ascontiguousarray(seconds, np.float64)
+    if u.ndim != 1 or u.shape != s.shape:
+        raise ValueError("units and seconds must be vectors of one length")
+    m = DurationModel()
+    _check(_lib.relserve_duration_fit(u.ctypes.data_as(C.c_void_p), s.ctypes.data_as(C.c_void_p), len(u), C.byref(m)),
+           "relserve_duration_fit")
+    return {"alpha": m.alpha, "beta": m.beta, "r2": m.r2, "n": m.n}
+
+
+def relserve_duration_predict(model: dict, units: float) -> float:
+    m = DurationModel(model["alpha"], model["beta"], model.get("r2", 0.0), model.get("n", 0))
+    out = C.c_double()
+    _check(_lib.relserve_duration_predict(C.byref(m), float(units), C.byref(out)), "relserve_duration_predict")
+    return out.value

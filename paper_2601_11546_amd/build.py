@@ -17,7 +17,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "librelserve.so")
-SOURCES = ["relserve_api.hip", "kernels_elementwise.hip", "kernel_gemm.hip", "kernel_attention.hip", "kernels_peaks.hip"]
+SOURCES = ["relserve_api.hip", "kernels_elementwise.hip", "kernel_gemm.hip", "kernel_attention.hip", "kernels_peaks.hip", "duration_model.hip"]
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-fno-gpu-rdc",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wall", "-Wno-unused-function", "-Wno-unknown-warning-option",

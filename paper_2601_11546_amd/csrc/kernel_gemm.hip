@@ -768,7 +768,7 @@ __global__ void __launch_bounds__(256) gemm_finish_kernel(GemmArgs p) {
 // weights (2 x 32 KB) are in flight per CU.
 template <int BM, int EPI, int D>
 hipError_t launch_split(GemmArgs p, int splits, hipStream_t s) {
-    constexpr int BN = 256, NS = BM == 64 ? 4 : 3;     // 160 KB / 144 KB of LDS: one workgroup per CU
+    constexpr int BN = 256, NS = BM == 64 ? 4 : BM == 128 ? 3 : 2;     // 160 / 144 / 128 KB of LDS: one workgroup per CU
     constexpr int smem = NS * (BM + BN) * 64 * 2;
     static bool attr_done = false;
     if (!attr_done) {
@@ -812,7 +812,30 @@ hipError_t launch_skinny(const GemmArgs& p, hipStream_t s) {
 }
 
 bool skinny_applies(int T, int N, int K, const float* accum) {
-    return accum != nullptr && T <= 256 && K % 64 == 0 && N % 4 == 0 && !g_force_generic;
+    return accum != nullptr && T <= SKINNY_MAX_T && K % 64 == 0 && N % 4 == 0 && !g_force_generic;
+}
+
+// Mid-size batches on a narrow output (W_o and W_down at a few hundred tokens): whole tiles are too few
+// for 256 CUs and splitting them through the fenced partial-tile protocol costs more than it gains, so
+// these run like the skinny path (k ranges accumulated with atomics, then the epilogue kernel) on tiles
+// of 128 rows while every tile gets at least two k ranges, or of 256 rows while it gets at least three
+// and k is long.  Returns the tile rows, 0 = not this path.  The accumulator region (T x N floats, at
+// most 128 x 128 x 256 or 85 x 256 x 256) lies behind the tail scratch.
+constexpr int64_t kSplitFloats = 96 * 65536;
+int split_rows(int T, int N, int K, bool has_accum) {
+    static const bool off = getenv("RELSERVE_GEMM_NOSPLIT") != nullptr;   // tuning hook
+    if (off || !has_accum || T <= SKINNY_MAX_T || K % 64 || N % 4 || g_force_generic || g_force_cand >= 0) return 0;
+    const int tn = (N + 255) / 256;
+    if (((T + 127) / 128) * tn <= 128) return 128;
+    if (((T + 255) / 256) * tn <= 85 && K >= 8192) return 256;
+    return 0;
+}
+
+template <int EPI>
+hipError_t launch_mid_split(GemmArgs p, int bm, hipStream_t s) {
+    p.accum += kTailCounters + kTailFloats;
+    if (bm == 128) return launch_split<128, EPI, 0>(p, choose_splits(p.T, p.N, p.K, 128), s);
+    return launch_split<256, EPI, 0>(p, choose_splits(p.T, p.N, p.K, 256), s);
 }
 
 // What a launch does beyond whole tiles: the last tail_tiles tiles split their k range over `splits` workgroups.
@@ -957,14 +980,15 @@ void gemm_force_plan(int cand, int splits) {
 }
 
 int64_t gemm_scratch_floats(int64_t T, int64_t n_max) {
-    return T <= SKINNY_MAX_T ? T * n_max : kTailCounters + kTailFloats;
+    return T <= SKINNY_MAX_T ? T * n_max : kTailCounters + kTailFloats + kSplitFloats;
 }
 
-int64_t gemm_scratch_used(int32_t T, int32_t N, int32_t K, bool qkv) {
-    if (T <= SKINNY_MAX_T) return (int64_t)T * N;
-    if (K % 64 || g_force_generic || (qkv && T <= 64)) return 0;
+ScratchUse gemm_scratch_use(int32_t T, int32_t N, int32_t K, bool qkv) {
+    if (T <= SKINNY_MAX_T) return ScratchUse{(int64_t)T * N, 0, 0};
+    if (K % 64 || g_force_generic || (qkv && T <= 64)) return ScratchUse{0, 0, 0};
+    if (!qkv && split_rows(T, N, K, true)) return ScratchUse{0, kTailCounters + kTailFloats, (int64_t)T * N};
     const Plan plan = choose_plan(T, N, K, qkv, true);
-    return plan.tail_tiles == 0 ? 0 : kTailCounters;   // only the arrival counters must start at zero
+    return ScratchUse{plan.tail_tiles == 0 ? 0 : kTailCounters, 0, 0};   // only the arrival counters must start at zero
 }
 
 // Tiled weight layout for streaming: out[n / 256][k / 64][n % 256][k % 64], rows past N are zeros.  One k
@@ -1019,6 +1043,15 @@ hipError_t launch_linear(const void* a, const void* w, int32_t T, int32_t N, int
             case EPI_RES_BF16_OUT_F32: return launch_skinny<EPI_RES_BF16_OUT_F32, 0>(p, s);
             case EPI_RES_F32_OUT_BF16: return launch_skinny<EPI_RES_F32_OUT_BF16, 0>(p, s);
             case EPI_SWIGLU: return launch_skinny<EPI_SWIGLU, 0>(p, s);
+            default: return hipErrorInvalidValue;
+        }
+    }
+    if (const int bm = split_rows(T, N, K, accum != nullptr)) {
+        switch (epilogue) {
+            case EPI_BF16: return launch_mid_split<EPI_BF16>(p, bm, s);
+            case EPI_RES_BF16_OUT_F32: return launch_mid_split<EPI_RES_BF16_OUT_F32>(p, bm, s);
+            case EPI_RES_F32_OUT_BF16: return launch_mid_split<EPI_RES_F32_OUT_BF16>(p, bm, s);
+            case EPI_SWIGLU: return launch_mid_split<EPI_SWIGLU>(p, bm, s);
             default: return hipErrorInvalidValue;
         }
     }

@@ -223,6 +223,10 @@ int32_t relserve::expand_batch(const relserve_layer_config& cfg, const relserve_
 // ------------------------------------------------------------------------------------------
 // plain entry points
 // ------------------------------------------------------------------------------------------
+// The launchers report hipGetLastError() after a launch; an error an earlier, unrelated HIP call of this thread left
+// behind (the runtime keeps the last one until it is read) must not be taken for theirs.
+static inline void drop_stale_hip_error() { (void)hipGetLastError(); }
+
 extern "C" {
 
 int32_t relserve_version(void) { return 100; }
@@ -310,6 +314,7 @@ int32_t relserve_batch_slots(const relserve_layer_config* cfg, const relserve_ba
 
 int32_t relserve_batch_prepare(const relserve_layer* L, const relserve_batch_desc* desc, void* stream,
                                relserve_batch** out) {
+    drop_stale_hip_error();
     if (!L || !desc || !out) return RELSERVE_ERR_NULL_POINTER;
     *out = nullptr;
     HostBatch hb;
@@ -424,6 +429,7 @@ int32_t relserve_workspace_bytes(const relserve_layer* L, int32_t max_tokens, si
 
 int32_t relserve_kv_append(const relserve_layer* L, const relserve_batch* b, const void* k, const void* v,
                            relserve_kv_cache cache, void* stream) {
+    drop_stale_hip_error();
     if (int32_t rc = check_pair(L, b)) return rc;
     if (int32_t rc = check_cache(b, cache)) return rc;
     if (b->dev.T == 0) return RELSERVE_OK;
@@ -435,6 +441,7 @@ int32_t relserve_kv_append(const relserve_layer* L, const relserve_batch* b, con
 
 int32_t relserve_rmsnorm(const void* x, int32_t x_is_f32, const void* w, float eps, int32_t n_rows,
                          int32_t hidden, void* out, void* stream) {
+    drop_stale_hip_error();
     if (n_rows < 0 || hidden <= 0 || hidden % 8) return RELSERVE_ERR_BAD_ARGUMENT;
     if (n_rows == 0) return RELSERVE_OK;
     if (!x || !w || !out) return RELSERVE_ERR_NULL_POINTER;
@@ -460,11 +467,13 @@ int32_t linear_entry(const void* a, const void* w, int32_t T, int32_t N, int32_t
 
 int32_t relserve_linear(const void* a, const void* w, int32_t T, int32_t N, int32_t K, int32_t epilogue,
                         const void* residual, void* out, void* stream) {
+    drop_stale_hip_error();
     return linear_entry(a, w, T, N, K, epilogue, residual, out, stream, false);
 }
 
 int32_t relserve_linear_packed(const void* a, const void* w_packed, int32_t T, int32_t N, int32_t K, int32_t epilogue,
                                const void* residual, void* out, void* stream) {
+    drop_stale_hip_error();
     return linear_entry(a, w_packed, T, N, K, epilogue, residual, out, stream, true);
 }
 
@@ -476,6 +485,7 @@ int32_t relserve_packed_weight_elems(int32_t N, int32_t K, int64_t* out) {
 }
 
 int32_t relserve_pack_weight(const void* w, int32_t N, int32_t K, void* out, void* stream) {
+    drop_stale_hip_error();
     int64_t elems = 0;
     if (int32_t rc = relserve_packed_weight_elems(N, K, &elems)) return rc;
     if (!w || !out) return RELSERVE_ERR_NULL_POINTER;
@@ -485,6 +495,7 @@ int32_t relserve_pack_weight(const void* w, int32_t N, int32_t K, void* out, voi
 
 int32_t relserve_rope_append(const relserve_layer* L, const relserve_batch* b, void* qkv,
                              relserve_kv_cache cache, void* stream) {
+    drop_stale_hip_error();
     if (int32_t rc = check_pair(L, b)) return rc;
     if (int32_t rc = check_cache(b, cache)) return rc;
     if (b->dev.T == 0) return RELSERVE_OK;
@@ -495,6 +506,7 @@ int32_t relserve_rope_append(const relserve_layer* L, const relserve_batch* b, v
 
 int32_t relserve_qkv_rope_append(const relserve_layer* L, const relserve_batch* b, const void* h, const void* w_qkv,
                                  void* q_out, relserve_kv_cache cache, void* stream) {
+    drop_stale_hip_error();
     if (int32_t rc = check_pair(L, b)) return rc;
     if (int32_t rc = check_cache(b, cache)) return rc;
     if (b->dev.T == 0) return RELSERVE_OK;
@@ -507,6 +519,7 @@ int32_t relserve_qkv_rope_append(const relserve_layer* L, const relserve_batch* 
 int32_t relserve_attention(const relserve_layer* L, const relserve_batch* b, const void* q, int32_t q_pitch,
                            relserve_kv_cache cache, void* out, void* workspace, size_t workspace_bytes,
                            void* stream) {
+    drop_stale_hip_error();
     if (int32_t rc = check_pair(L, b)) return rc;
     if (int32_t rc = check_cache(b, cache)) return rc;
     if (b->dev.T == 0) return RELSERVE_OK;
@@ -523,6 +536,7 @@ int32_t relserve_attention(const relserve_layer* L, const relserve_batch* b, con
 int32_t relserve_layer_step(const relserve_layer* L, const relserve_batch* b, const relserve_layer_weights* wt,
                             const void* x, void* y, relserve_kv_cache cache, void* workspace,
                             size_t workspace_bytes, void* stream) {
+    drop_stale_hip_error();
     if (int32_t rc = check_pair(L, b)) return rc;
     if (!wt) return RELSERVE_ERR_NULL_POINTER;
     if (int32_t rc = check_cache(b, cache)) return rc;
@@ -549,11 +563,15 @@ int32_t relserve_layer_step(const relserve_layer* L, const relserve_batch* b, co
     // the GEMMs split K across workgroups (whole skinny problems, or the incomplete last round of tiles)
     // through a zeroed fp32 scratch; each GEMM leaves what it used zero again
     float* accum = w.accum;
-    const int64_t used = std::max({gemm_scratch_used(T, L->qkv_dim, c.hidden, true),
-                                   gemm_scratch_used(T, c.hidden, L->q_dim, false),
-                                   gemm_scratch_used(T, 2 * c.mlp_dim, c.hidden, false),
-                                   gemm_scratch_used(T, c.hidden, c.mlp_dim, false)});
-    if (used > 0) e = launch_fill_zero(accum, used, s);
+    ScratchUse use{0, 0, 0};
+    for (const ScratchUse& u : {gemm_scratch_use(T, L->qkv_dim, c.hidden, true), gemm_scratch_use(T, c.hidden, L->q_dim, false),
+                                gemm_scratch_use(T, 2 * c.mlp_dim, c.hidden, false), gemm_scratch_use(T, c.hidden, c.mlp_dim, false)}) {
+        use.head = std::max(use.head, u.head);
+        if (u.mid > 0) use.mid_offset = u.mid_offset;
+        use.mid = std::max(use.mid, u.mid);
+    }
+    if (use.head > 0) e = launch_fill_zero(accum, use.head, s);
+    if (use.mid > 0 && e == hipSuccess) e = launch_fill_zero(accum + use.mid_offset, use.mid, s);
     run(S_NORM1, [&] { return launch_rmsnorm(x, false, wt->w_in_norm, c.rms_eps, T, c.hidden, w.h, s); });
     run(S_QKV, [&] {
         return launch_qkv_rope_append(b->dev, *L, w.h, wt->w_qkv, w.q, cache.k_pages, cache.v_pages, s, accum, packed);
@@ -581,6 +599,7 @@ int32_t relserve_model_workspace_bytes(const relserve_layer* L, int32_t max_toke
 int32_t relserve_model_step(const relserve_layer* L, const relserve_batch* b, const relserve_model* m,
                             const int32_t* token_ids, void* logits, void* workspace, size_t workspace_bytes,
                             void* stream) {
+    drop_stale_hip_error();
     if (int32_t rc = check_pair(L, b)) return rc;
     if (!m) return RELSERVE_ERR_NULL_POINTER;
     if (m->n_layers < 0 || m->vocab <= 0 || m->vocab % 4) return RELSERVE_ERR_BAD_ARGUMENT;
@@ -615,6 +634,7 @@ int32_t relserve_model_step(const relserve_layer* L, const relserve_batch* b, co
 }
 
 int32_t relserve_peak_probe_mfma(void* sink, int32_t iters, double* flops, void* stream) {
+    drop_stale_hip_error();
     if (!sink || !flops) return RELSERVE_ERR_NULL_POINTER;
     if (iters <= 0) return RELSERVE_ERR_BAD_ARGUMENT;
     *flops = 256.0 * 4.0 * iters * 16.0 * 32768.0;
@@ -624,6 +644,7 @@ int32_t relserve_peak_probe_mfma(void* sink, int32_t iters, double* flops, void*
 }
 
 int32_t relserve_peak_probe_stream(const void* src, size_t bytes, void* sink, void* stream) {
+    drop_stale_hip_error();
     if (!src || !sink) return RELSERVE_ERR_NULL_POINTER;
     if (bytes < 16 || (reinterpret_cast<uintptr_t>(src) % 16)) return RELSERVE_ERR_BAD_ARGUMENT;
     return launch_peak_stream(src, (int64_t)bytes, static_cast<uint32_t*>(sink), static_cast<hipStream_t>(stream)) ==

@@ -102,13 +102,16 @@ hipError_t launch_kv_append(const BatchDev& b, const void* k, const void* v, voi
                             int32_t row_elems, hipStream_t s);
 hipError_t launch_rope_append(const BatchDev& b, const relserve_layer& L, void* qkv, void* k_pages,
                               void* v_pages, hipStream_t s);
-// accum: optional fp32 scratch holding zeros (gemm_scratch_floats(T, widest N) floats); lets skinny
-// problems (T <= 256) and the incomplete last round of larger ones split K over workgroups.  It
-// holds zeros again when the launched kernels have finished.
+// accum: optional fp32 scratch (gemm_scratch_floats(T, widest N) floats) whose parts named by
+// gemm_scratch_use hold zeros; lets skinny problems (T <= 256), narrow outputs at mid-size T and the
+// incomplete last round of larger ones split K over workgroups.  Those parts hold zeros again when the
+// launched kernels have finished.
 int64_t gemm_scratch_floats(int64_t T, int64_t n_max);
-// Floats at the head of the scratch that launch_linear / launch_qkv_rope_append will use for this problem
-// (0 = none); the caller clears the largest such prefix once before a sequence of launches.
-int64_t gemm_scratch_used(int32_t T, int32_t N, int32_t K, bool qkv);
+// The parts of the scratch that launch_linear / launch_qkv_rope_append expect to hold zeros for this
+// problem: `head` floats from its start and `mid` floats from float offset `mid_offset` (0 = none).  The
+// caller clears the largest of each over a sequence of launches once before it.
+struct ScratchUse { int64_t head, mid_offset, mid; };
+ScratchUse gemm_scratch_use(int32_t T, int32_t N, int32_t K, bool qkv);
 void gemm_force_plan(int cand, int splits);   // test hook, see relserve_debug_force_gemm_plan
 hipError_t launch_linear(const void* a, const void* w, int32_t T, int32_t N, int32_t K, int32_t epilogue,
                          const void* residual, void* out, hipStream_t s, float* accum = nullptr, bool w_packed = false);

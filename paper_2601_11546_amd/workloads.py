@@ -322,4 +322,65 @@ def workload_decode_plus_chunk_13b(chunk: int, seed: int = 1004, n_dec: int = 12
     q_len = [1] * n_dec + ([chunk] if chunk else [])
     c = [ctx] * n_dec + ([chunk] if chunk else [])
     b = build_batch(shape, q_len, c, seed=seed, name=f"decode128_chunk{chunk}")
-    return Workload(f"decode128_chunk{chunk}_13b", shape, b, seed, n_layers=40)
+    return Workload(f"decode{n_dec}_chunk{chunk}_13b" if n_dec else f"prefill_chunk{chunk}_13b", shape, b, seed, n_layers=40)
+
+
+# ----------------------------------------------------------------------------
+# batches for fitting the batch-duration model (Sec. 4.2, Eq. 9)
+# ----------------------------------------------------------------------------
+def prefill_tokens(b: Batch) -> tuple:
+    """(utok, total) of a batch's prefill rows: the query tokens they compute, and all their prompt tokens
+    including the ones the prefix cache serves (the two abscissae the paper compares)."""
+    pre = b.q_len > 1
+    return int(b.q_len[pre].sum()), int(b.ctx_len[pre].sum())
+
+
+def duration_sweep_prefill(n_batches: int, seed: int = 1100, max_tokens: int = 8192, max_reqs: int = 256,
+                           shape: LayerShape = LLAMA_13B) -> list:
+    """Prefill batches as a serving run meets them: requests of one to three relQueries (template prefix
+    of 256-1024 tokens, private suffix of 30-120), each request either finding its template in the prefix
+    cache (it computes its suffix only) or not (it computes the whole prompt into private pages).  The
+    batch's token budget and its cache hit rate are drawn per batch so that the sweep covers the range of
+    uncached tokens and decorrelates them from the total."""
+    rng = np.random.default_rng(seed)
+    out = []
+    for i in range(n_batches):
+        budget = int(rng.integers(256, max_tokens + 1))
+        hit = float(rng.random())
+        prefixes = [int(p) for p in rng.choice([256, 512, 768, 1024], int(rng.integers(1, 4)))]
+        q_len, ctx, pid = [], [], []
+        utok = 0
+        while len(q_len) < max_reqs:
+            rel = len(q_len) % len(prefixes)
+            suffix = int(rng.integers(30, 121))
+            cached = bool(rng.random() < hit)
+            q = suffix if cached else prefixes[rel] + suffix
+            if q_len and utok + q > budget:
+                break
+            q_len.append(q)
+            ctx.append(prefixes[rel] + suffix)
+            pid.append(rel if cached else -1)
+            utok += q
+        used = sorted({p for p in pid if p >= 0})
+        remap = {p: j for j, p in enumerate(used)}
+        pid = [remap[p] if p >= 0 else -1 for p in pid]
+        out.append(build_batch(shape, q_len, ctx, pid, [prefixes[p] for p in used], seed=seed + i,
+                               name=f"duration_prefill_{i}"))
+    return out
+
+
+def duration_sweep_decode(sizes, seed: int = 1200, shape: LayerShape = LLAMA_13B) -> list:
+    """Decode batches of the given request counts: members of relQueries of 1-100 requests behind their
+    template (256-1024 tokens), suffix 30-120, 1-16 tokens generated so far."""
+    rng = np.random.default_rng(seed)
+    out = []
+    for i, n in enumerate(sizes):
+        ctx, pid, prefixes = [], [], []
+        while len(ctx) < n:
+            members = min(int(rng.integers(1, 101)), n - len(ctx))
+            prefixes.append(int(rng.choice([256, 512, 768, 1024])))
+            for _ in range(members):
+                ctx.append(prefixes[-1] + int(rng.integers(30, 121)) + int(rng.integers(1, 17)))
+                pid.append(len(prefixes) - 1)
+        out.append(build_batch(shape, [1] * n, ctx, pid, prefixes, seed=seed + i, name=f"duration_decode_{n}"))
+    return out

@@ -387,6 +387,35 @@ def test_skinny_batches_of_every_token_tile_count(rs, oracle):
         assert_close(y, res.y_f32, f"{n} decode tokens")
 
 
+def test_mid_size_batches_on_narrow_outputs(rs, oracle):
+    """257 to 700 prefill tokens on a layer whose W_o / W_down outputs are few tiles wide: these GEMMs split
+    their k range over workgroups (atomic accumulation, then the epilogue kernel) behind the tail scratch."""
+    shape = W.LayerShape(1024, 8, 2, 128, 2048)
+    weights = W.make_weights(shape, 11)
+    for q_len in ([257], [150, 150], [300, 211], [1, 400, 299]):
+        T = sum(q_len)
+        b = W.build_batch(shape, q_len, q_len, seed=T)
+        print(f"[case] mid-size T={T}", flush=True)
+        x = W.make_activations(b.T, shape.hidden, T)
+        kp, vp = W.make_cache(shape, b.num_pages, T)
+        gl = GpuLayer(rs, shape, weights, kp, vp, b.T)
+        y = host_f32(gl.step(b, x))
+        y2 = host_f32(gl.step(b, x))                 # the scratch was left clean: a second step gives the same bits
+        assert np.array_equal(y, y2) or np.abs(y - y2).max() < 1e-2
+        res = oracle.layer_step(shape, b, weights, x, kp, vp)
+        assert_close(y, res.y_f32, f"{T} prefill tokens")
+
+
+def test_full_size_mid_size_chunks_13b(rs, oracle):
+    """T = 1000 on the 13B shape: W_down (k = 13824) runs on 256-row tiles with three k ranges each, W_o on
+    whole tiles; T = 384: both on 128-row tiles with several k ranges."""
+    for q_len, reqs in (([400, 350, 250], [2]), ([200, 184], [1])):
+        b = W.build_batch(W.LLAMA_13B, q_len, q_len, seed=sum(q_len), name=f"mid_chunks_{sum(q_len)}")
+        wl = W.Workload(b.name, W.LLAMA_13B, b, 1005, n_layers=40)
+        _sampled_parity(rs, oracle, wl, reqs, max_prefill_rows=16)
+        _sampled_parity(rs, oracle, wl, reqs, max_prefill_rows=16, packed=True)
+
+
 def test_full_size_decode_plus_chunk_13b(rs, oracle):
     wl = W.workload_decode_plus_chunk_13b(512)
     _sampled_parity(rs, oracle, wl, [0, 127, 128], max_prefill_rows=24)

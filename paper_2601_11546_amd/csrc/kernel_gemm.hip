@@ -55,11 +55,10 @@ struct GemmArgs {
     int32_t k_per_split;   // in units of 64; 0 = no split
     // tail split (main path): the last tail_tiles tiles (those of the incomplete last round) are each
     // computed by tail_splits workgroups over k_per_split k steps each.  The partial tiles are stored
-    // to tail_buf (tail_splits x tail_tiles x BM x BN fp32) and the workgroup that arrives last at a
-    // tile (tail_count, zero on entry and on exit) adds them up and runs the epilogue.
+    // to tail_buf (tail_splits x tail_tiles x BM x BN fp32); a second kernel adds them up and runs the
+    // epilogue.
     int32_t tail_tiles, tail_splits;
     float* tail_buf;
-    int32_t* tail_count;
 };
 
 #ifndef RELSERVE_DMA_BK
@@ -105,7 +104,7 @@ __device__ __forceinline__ void tile_coords(int t, int tiles_m, int tiles_n, int
 // 32 tn + 8 (r / 4) + 4 g + r % 4 of the wave's feature range and token 32 tm + l32 of its token range.
 template <int BM, int BN, int EPI, int D, int WGM = 2, int WGN = 2>
 __device__ __forceinline__ void gemm_epilogue(const f32x16_t (&acc)[BN / (32 * WGN)][BM / (32 * WGM)], const GemmArgs& p,
-                                              int tile_m, int tile_n, int wm, int wn, int l32, int g) {
+                                              int tile_m, int tile_n, int wm, int wn, int l32, int g, int tm_only = -1) {
     constexpr int TM = BM / (32 * WGM), TN = BN / (32 * WGN);
     const int t0 = tile_m * BM;
     if (EPI == EPI_ATOMIC) {
@@ -127,6 +126,7 @@ __device__ __forceinline__ void gemm_epilogue(const f32x16_t (&acc)[BN / (32 * W
     }
 #pragma unroll
     for (int tm = 0; tm < TM; ++tm) {
+        if (tm_only >= 0 && tm != tm_only) continue;   // the tail finish kernel: one row of accumulator tiles per workgroup
         const int t = t0 + wm * (BM / WGM) + 32 * tm + l32;
         if (t >= p.T) continue;
         if (EPI == EPI_ATOMIC) {
@@ -616,10 +616,10 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_dma_kernel(GemmArgs p) {
     }
     if (EPI != EPI_ATOMIC && tail) {
         // Partial tile -> this split's slab (registers 4 c .. 4 c + 3 of accumulator tile (tn, tm) of
-        // thread tid are the 16 bytes at ((tn TM + tm) 4 + c) * threads + tid: coalesced).  The workgroup
-        // that arrives last at the tile adds the slabs in split order, so the result does not depend
-        // on the arrival order.  Release / acquire fences around the arrival counter make the slabs of
-        // workgroups on other XCDs (other L2s) visible.
+        // thread tid are the 16 bytes at ((tn TM + tm) 4 + c) * threads + tid: coalesced).
+        // gemm_tail_finish_kernel, launched behind this kernel, adds the slabs of a tile in split order and
+        // runs the epilogue; the kernel boundary is what makes the slabs of workgroups on other XCDs
+        // (other L2s) visible, so nothing here waits or fences.
         typedef float vec4_t __attribute__((ext_vector_type(4)));
         constexpr int AREA4 = BM * BN / 4, NT = 64 * NW;
         vec4_t* slab = reinterpret_cast<vec4_t*>(p.tail_buf) + ((size_t)split * p.tail_tiles + tail_idx) * AREA4 + tid;
@@ -632,47 +632,51 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_dma_kernel(GemmArgs p) {
                     vec4_t v = {acc[tn][tm][4 * c], acc[tn][tm][4 * c + 1], acc[tn][tm][4 * c + 2], acc[tn][tm][4 * c + 3]};
                     slab[((tn * TM + tm) * 4 + c) * NT] = v;
                 }
-        __shared__ int s_last;
-        __threadfence();   // release: this thread's part of the slab is visible device-wide ...
-        __syncthreads();
-        if (tid == 0) s_last = atomicAdd(p.tail_count + tail_idx, 1) == p.tail_splits - 1;   // ... before the count moves
-        __syncthreads();
-        if (!s_last) return;
-        __threadfence();   // acquire: the other workgroups' slabs
-#pragma unroll
-        for (int tn = 0; tn < TN; ++tn)
-#pragma unroll
-            for (int tm = 0; tm < TM; ++tm)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) acc[tn][tm][r] = 0.f;
-        for (int q = 0; q < p.tail_splits; ++q) {
-            const vec4_t* src = reinterpret_cast<const vec4_t*>(p.tail_buf) + ((size_t)q * p.tail_tiles + tail_idx) * AREA4 + tid;
-#pragma unroll
-            for (int tn = 0; tn < TN; ++tn) {
-                // One batch of loads in flight before the first add (asm also because the compiler, with
-                // every register of the main loop still allocated, would wait for each load in turn).
-                vec4_t v[TM * 4];
-#pragma unroll
-                for (int i = 0; i < TM * 4; ++i)
-                    asm volatile("global_load_dwordx4 %0, %1, off" : "=&v"(v[i]) : "v"(src + (tn * TM * 4 + i) * NT) : "memory");
-                asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-#pragma unroll
-                for (int i = 0; i < TM * 4; ++i) asm volatile("" : "+v"(v[i]));   // uses stay behind the wait
-#pragma unroll
-                for (int tm = 0; tm < TM; ++tm)
-#pragma unroll
-                    for (int c = 0; c < 4; ++c)
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) acc[tn][tm][4 * c + e] += v[tm * 4 + c][e];
-            }
-        }
-        if (tid == 0) p.tail_count[tail_idx] = 0;   // ready for the next launch
-        // a second copy of the epilogue on purpose: merging the two paths would turn every accumulator
-        // into a two-way merge of register tuples, which the whole-tile path then pays for in copies
-        gemm_epilogue<BM, BN, EPI, D, WGM, WGN>(acc, p, tile_m, tile_n, wm, wn, l32, g);
         return;
     }
     gemm_epilogue<BM, BN, EPI, D, WGM, WGN>(acc, p, tile_m, tile_n, wm, wn, l32, g);
+}
+
+// Second half of a tail split: workgroup (tail tile, row tm of accumulator tiles) has the thread layout of
+// the GEMM workgroup that wrote the slabs, adds its part of the tile's slabs in split order (so the sum
+// does not depend on scheduling) and runs the GEMM's own epilogue on it.
+template <int BM, int BN, int EPI, int D, int WGM, int WGN>
+__global__ void __launch_bounds__(64 * WGM * WGN) gemm_tail_finish_kernel(GemmArgs p) {
+    constexpr int NW = WGM * WGN, NT = 64 * NW, TM = BM / (32 * WGM), TN = BN / (32 * WGN), AREA4 = BM * BN / 4;
+    typedef float vec4_t __attribute__((ext_vector_type(4)));
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave / WGN, wn = wave % WGN;
+    const int l32 = lane & 31, g = lane >> 5;
+    const int tail_idx = blockIdx.x / TM, tm_sel = blockIdx.x % TM;
+    int tile_m, tile_n;
+    tile_coords(p.tiles_m * p.tiles_n - p.tail_tiles + tail_idx, p.tiles_m, p.tiles_n, tile_m, tile_n);
+    f32x16_t acc[TN][TM];
+#pragma unroll
+    for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+        for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[tn][tm][r] = 0.f;
+    for (int q = 0; q < p.tail_splits; ++q) {
+        const vec4_t* src = reinterpret_cast<const vec4_t*>(p.tail_buf) + ((size_t)q * p.tail_tiles + tail_idx) * AREA4 + tid;
+#pragma unroll
+        for (int tm = 0; tm < TM; ++tm) {
+            if (tm != tm_sel) continue;
+            vec4_t v[TN][4];
+#pragma unroll
+            for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+                for (int c = 0; c < 4; ++c) v[tn][c] = src[((tn * TM + tm) * 4 + c) * NT];
+#pragma unroll
+            for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+                for (int c = 0; c < 4; ++c)
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) acc[tn][tm][4 * c + e] += v[tn][c][e];
+        }
+    }
+    gemm_epilogue<BM, BN, EPI, D, WGM, WGN>(acc, p, tile_m, tile_n, wm, wn, l32, g, tm_sel);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -868,14 +872,19 @@ hipError_t launch_cfg(const GemmArgs& base, hipStream_t s, const Plan& plan = Pl
             p.k_per_split = (nk + plan.splits - 1) / plan.splits;
             p.tail_splits = (nk + p.k_per_split - 1) / p.k_per_split;   // no empty split
             p.tail_tiles = std::min(plan.tail_tiles, tiles);
-            p.tail_count = reinterpret_cast<int32_t*>(p.accum);
             p.tail_buf = p.accum + kTailCounters;
-            if (p.tail_tiles > kTailCounters || (int64_t)p.tail_tiles * p.tail_splits * BM * BN > kTailFloats)
+            if ((int64_t)p.tail_tiles * p.tail_splits * BM * BN > kTailFloats)
                 return hipErrorInvalidValue;   // a plan that does not fit the scratch: choose_plan never makes one
             grid = tiles - p.tail_tiles + p.tail_tiles * p.tail_splits;
         }
         gemm_dma_kernel<BM, BN, EPI, D, DMA_BK, DMA_NS, WGM, WGN>
             <<<dim3(grid), dim3(64 * WGM * WGN), dma_smem, s>>>(p);
+        if (p.tail_tiles > 0) {
+            hipError_t e = hipGetLastError();
+            if (e != hipSuccess) return e;
+            gemm_tail_finish_kernel<BM, BN, EPI, D, WGM, WGN>
+                <<<dim3(p.tail_tiles * (BM / (32 * WGM))), dim3(64 * WGM * WGN), 0, s>>>(p);
+        }
     } else {
         gemm_bf16_kernel<BM, BN, EPI, D><<<dim3(tiles), dim3(256), smem, s>>>(p);
     }
@@ -899,7 +908,8 @@ constexpr TileCand kTiles[] = {
 // round takes 1 / splits of a tile time; the price is that every partial tile is written to memory
 // and read back by the workgroup that finishes the tile.  Costs in seconds.
 constexpr double kCuFlops = 4.5e12;          // sustained MFMA rate of one CU inside a 256 x 256 tile
-constexpr double kSlabBytesPerSec = 1.2e12;  // partial tiles through memory (write, fences, read), as seen by the launch
+constexpr double kSlabBytesPerSec = 3.0e12;  // partial tiles through memory (written by the GEMM, read by the finish kernel)
+constexpr double kTailFinishSec = 6e-6;      // the finish kernel's launch and ramp
 
 Plan choose_plan_impl(int T, int64_t n_eff, int K, bool need_bn256, bool allow_tail);
 Plan choose_plan(int T, int64_t n_eff, int K, bool need_bn256, bool allow_tail) {
@@ -945,7 +955,7 @@ Plan choose_plan_impl(int T, int64_t n_eff, int K, bool need_bn256, bool allow_t
             if (units * c.bm * c.bn > kTailFloats) break;
             const double rounds = (double)((units + slots - 1) / slots);
             const double slabs = (double)units * c.bm * c.bn * 4.0 * 2.0 / kSlabBytesPerSec;
-            const double cost = full * t_round + rounds * t_round / sp + slabs;
+            const double cost = full * t_round + rounds * t_round / sp + slabs + kTailFinishSec;
             if (cost < best_cost || forced_splits > 1) best_cost = cost, best = Plan{i, (int)rem, sp};
         }
     }
@@ -987,8 +997,8 @@ ScratchUse gemm_scratch_use(int32_t T, int32_t N, int32_t K, bool qkv) {
     if (T <= SKINNY_MAX_T) return ScratchUse{(int64_t)T * N, 0, 0};
     if (K % 64 || g_force_generic || (qkv && T <= 64)) return ScratchUse{0, 0, 0};
     if (!qkv && split_rows(T, N, K, true)) return ScratchUse{0, kTailCounters + kTailFloats, (int64_t)T * N};
-    const Plan plan = choose_plan(T, N, K, qkv, true);
-    return ScratchUse{plan.tail_tiles == 0 ? 0 : kTailCounters, 0, 0};   // only the arrival counters must start at zero
+    (void)N;
+    return ScratchUse{0, 0, 0};   // whole tiles, or tail slabs that are written before they are read
 }
 
 // Tiled weight layout for streaming: out[n / 256][k / 64][n % 256][k % 64], rows past N are zeros.  One k

@@ -31,6 +31,7 @@ def build_workload(name: str):
     from paper_2601_11546_amd import workloads as W
     table = {
         "relquery_13b": W.workload_relquery_13b,                       # configs[1]: the headline workload
+        "relquery_32b": W.workload_relquery_32b,                       # the same batch on the 32B (5 q heads per kv head) shape
         "tiny": W.workload_tiny,                                       # configs[0]
         "decode_heavy_70b": W.workload_decode_heavy_70b,               # configs[2]
         "decode_only_70b": lambda: W.workload_decode_heavy_70b(with_chunk=False),

@@ -151,7 +151,7 @@ int32_t relserve::expand_batch(const relserve_layer_config& cfg, const relserve_
 
     if (build_items) {
         const int32_t group = cfg.n_q_heads / cfg.n_kv_heads;
-        const int32_t tile_tok = ATTN_BLOCK_M / group;    // tokens per row-tiled item
+        const int32_t tile_tok = ATTN_BLOCK_M / group;    // tokens per row-tiled item (rows past tile_tok * group stay idle)
         const int32_t split_tok = std::max(1, ATTN_SPLIT_ROWS / group);
         (void)split_tok;
         // a prefix is handled jointly when at least two requests of the batch carry it
@@ -259,7 +259,6 @@ int32_t relserve_config_validate(const relserve_layer_config* c) {
     if (c->head_dim != 64 && c->head_dim != 128) return RELSERVE_ERR_BAD_CONFIG;
     if (c->n_kv_heads <= 0 || c->n_q_heads <= 0 || c->n_q_heads % c->n_kv_heads) return RELSERVE_ERR_BAD_CONFIG;
     if (c->n_q_heads / c->n_kv_heads > ATTN_SPLIT_ROWS) return RELSERVE_ERR_BAD_CONFIG;  // one wave's query rows
-    if (ATTN_BLOCK_M % (c->n_q_heads / c->n_kv_heads)) return RELSERVE_ERR_BAD_CONFIG;
     if (!is_pow2(c->page_size) || c->page_size < 8 || c->page_size > 256) return RELSERVE_ERR_BAD_CONFIG;
     if (!(c->rms_eps >= 0.0f) || !(c->rope_base > 0.0f)) return RELSERVE_ERR_BAD_CONFIG;
     return RELSERVE_OK;

@@ -68,8 +68,11 @@ class LayerShape:
 TINY = LayerShape(256, 4, 4, 64, 688)
 TINY_GQA = LayerShape(256, 8, 2, 64, 688)
 TINY_D128 = LayerShape(256, 2, 1, 128, 688)
+TINY_G5 = LayerShape(256, 10, 2, 64, 688)        # 5 query heads per kv head: the group does not divide a 128-row tile
+TINY_G3_D128 = LayerShape(256, 6, 2, 128, 688)
 LLAMA_13B = LayerShape(5120, 40, 40, 128, 13824)
 LLAMA_70B = LayerShape(8192, 64, 8, 128, 28672)
+QWEN_32B = LayerShape(5120, 40, 8, 128, 27648)   # Sec. 5.1: the 32B model of the evaluation (grouped-query, 5 heads per kv head)
 
 
 # ----------------------------------------------------------------------------
@@ -280,6 +283,12 @@ def workload_relquery_13b(seed: int = 1001, n_rows: int = 200, n_prefill: int = 
     b = build_batch(shape, q_len, ctx, np.zeros(n_rows, np.int32), [prefix], seed=seed,
                     name="relquery_13b")
     return Workload("relquery_13b_16p184d", shape, b, seed, n_layers=40)
+
+
+def workload_relquery_32b(seed: int = 1006) -> Workload:
+    """The relQuery batch of workload_relquery_13b on the 32B layer shape (64 layers deep)."""
+    wl = workload_relquery_13b(seed=seed, shape=QWEN_32B)
+    return Workload("relquery_32b_16p184d", QWEN_32B, wl.batch, seed, n_layers=64)
 
 
 def workload_decode_heavy_70b(seed: int = 1002, with_chunk: bool = True, n_rel: int = 4,

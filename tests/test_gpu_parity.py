@@ -175,7 +175,7 @@ def test_qkv_rope_append_fused_epilogue(rs, oracle, shape, n_req):
 
 
 @pytest.mark.parametrize("make", [W.workload_tiny, W.workload_tiny_prefix])
-@pytest.mark.parametrize("shape", [W.TINY, W.TINY_GQA, W.TINY_D128], ids=["mha", "gqa", "d128"])
+@pytest.mark.parametrize("shape", [W.TINY, W.TINY_GQA, W.TINY_D128, W.TINY_G5, W.TINY_G3_D128], ids=["mha", "gqa", "d128", "g5", "g3d128"])
 def test_attention_stage(rs, oracle, make, shape):
     b = make(shape=shape).batch
     rng = np.random.default_rng(10)
@@ -212,7 +212,7 @@ def _step_case(rs, oracle, wl, cache_seed_off=0):
 
 
 @pytest.mark.parametrize("make", [W.workload_tiny, W.workload_tiny_prefix])
-@pytest.mark.parametrize("shape", [W.TINY, W.TINY_GQA, W.TINY_D128], ids=["mha", "gqa", "d128"])
+@pytest.mark.parametrize("shape", [W.TINY, W.TINY_GQA, W.TINY_D128, W.TINY_G5, W.TINY_G3_D128], ids=["mha", "gqa", "d128", "g5", "g3d128"])
 def test_layer_step_tiny(rs, oracle, make, shape):
     wl = make(shape=shape)
     gl, y, res, kp, vp = _step_case(rs, oracle, wl)
@@ -348,6 +348,12 @@ def test_full_size_decode_plus_chunk_13b_forced_tail_split(rs, oracle, tile, spl
         _sampled_parity(rs, oracle, wl, [0, 127, 128], max_prefill_rows=24)
     finally:
         rs.relserve_debug_force_gemm_plan(-1, 0)
+
+
+def test_full_size_relquery_32b(rs, oracle):
+    """The 32B shape: 5 query heads per kv head, so a 128-row attention tile holds 25 tokens and 3 idle rows."""
+    wl = W.workload_relquery_32b()
+    _sampled_parity(rs, oracle, wl, [0, 15, 16, 99, 199], packed=True)
 
 
 def test_full_size_decode_heavy_70b(rs, oracle):

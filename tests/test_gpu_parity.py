@@ -229,6 +229,21 @@ def test_layer_step_tiny(rs, oracle, make, shape):
         assert_bf16_neighbours(g[slots], ora.reshape(-1, nkv, d)[slots], "appended kv")
 
 
+@pytest.mark.parametrize("page", [8, 32, 64, 256])
+@pytest.mark.parametrize("shape", [W.TINY_GQA, W.TINY_D128], ids=["gqa", "d128"])
+def test_layer_step_page_sizes(rs, oracle, shape, page):
+    """Pages of 8 to 256 tokens (32-key and 64-key attention blocks span several pages, or a part of one)."""
+    from dataclasses import replace
+    shape = replace(shape, page_size=page)
+    for make in (W.workload_tiny, W.workload_tiny_prefix):
+        wl = make(shape=shape)
+        gl, y, res, kp, vp = _step_case(rs, oracle, wl)
+        assert_close(host_f32(y), res.y_f32, f"layer step {wl.name} page {page}")
+        slots = rs.relserve_batch_slots(shape, wl.batch)
+        nkv, d = shape.n_kv_heads, shape.head_dim
+        assert_bf16_neighbours(host_bits(gl.k_pages).reshape(-1, nkv, d)[slots], kp.reshape(-1, nkv, d)[slots], "appended k")
+
+
 def test_layer_step_in_place_and_repeatable(rs, oracle):
     wl = W.workload_tiny_prefix()
     shape, b = wl.shape, wl.batch

@@ -31,8 +31,7 @@ namespace {
 
 constexpr int BK = 64;
 constexpr int NUM_XCD = 8;
-constexpr int kTailCounters = GEMM_TAIL_COUNTERS;          // int32 arrival counters at the head of the scratch
-constexpr int64_t kTailFloats = GEMM_TAIL_FLOATS;          // fp32 partial tiles behind them
+constexpr int64_t kTailFloats = GEMM_TAIL_FLOATS;          // fp32 partial tiles (slabs) of the split paths at T > 256
 
 struct GemmArgs {
     const uint16_t* a;
@@ -49,10 +48,12 @@ struct GemmArgs {
     uint16_t* k_pages;
     uint16_t* v_pages;
     int32_t n_q, n_kv;
-    // split-K (skinny T): workgroup b handles tile b % tiles and k steps [split * k_per_split, ...) of
-    // that tile and adds its partial sums into accum [T, N] fp32 (zero on entry)
+    // split-K (skinny and mid-size T): workgroup b handles tile b % tiles and k steps [split * k_per_split, ...)
+    // of that tile and stores its partial sums to slab `split` of accum [n_splits][T, N] fp32; the finish
+    // kernel adds the slabs in split order
     float* accum;
     int32_t k_per_split;   // in units of 64; 0 = no split
+    int32_t n_splits;
     // tail split (main path): the last tail_tiles tiles (those of the incomplete last round) are each
     // computed by tail_splits workgroups over k_per_split k steps each.  The partial tiles are stored
     // to tail_buf (tail_splits x tail_tiles x BM x BN fp32); a second kernel adds them up and runs the
@@ -104,13 +105,16 @@ __device__ __forceinline__ void tile_coords(int t, int tiles_m, int tiles_n, int
 // 32 tn + 8 (r / 4) + 4 g + r % 4 of the wave's feature range and token 32 tm + l32 of its token range.
 template <int BM, int BN, int EPI, int D, int WGM = 2, int WGN = 2>
 __device__ __forceinline__ void gemm_epilogue(const f32x16_t (&acc)[BN / (32 * WGN)][BM / (32 * WGM)], const GemmArgs& p,
-                                              int tile_m, int tile_n, int wm, int wn, int l32, int g, int tm_only = -1) {
+                                              int tile_m, int tile_n, int wm, int wn, int l32, int g, int tm_only = -1,
+                                              int split = 0) {
     constexpr int TM = BM / (32 * WGM), TN = BN / (32 * WGN);
     const int t0 = tile_m * BM;
     if (EPI == EPI_ATOMIC) {
-        // Split-K partial sums.  These tiles were accumulated with the operands swapped: register r
-        // holds token 8 (r / 4) + 4 g + r % 4 and feature l32, so one atomic instruction adds two
-        // runs of 32 consecutive floats.
+        // Split-K partial sums -> this split's slab.  These tiles were accumulated with the operands
+        // swapped: register r holds token 8 (r / 4) + 4 g + r % 4 and feature l32, so one store
+        // instruction writes two runs of 32 consecutive floats.  Plain stores: nothing is read back in
+        // this kernel, and fp32 atomics into a shared accumulator ran at a quarter of the rate.
+        float* slab = p.accum + (int64_t)split * p.T * p.N;
 #pragma unroll
         for (int tm = 0; tm < TM; ++tm)
 #pragma unroll
@@ -119,7 +123,7 @@ __device__ __forceinline__ void gemm_epilogue(const f32x16_t (&acc)[BN / (32 * W
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     const int t = t0 + wm * (BM / WGM) + 32 * tm + 8 * (r >> 2) + 4 * g + (r & 3);
-                    if (t < p.T && n < p.N) unsafeAtomicAdd(p.accum + (int64_t)t * p.N + n, acc[tn][tm][r]);
+                    if (t < p.T && n < p.N) slab[(int64_t)t * p.N + n] = acc[tn][tm][r];
                 }
             }
         return;
@@ -634,7 +638,7 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_dma_kernel(GemmArgs p) {
                 }
         return;
     }
-    gemm_epilogue<BM, BN, EPI, D, WGM, WGN>(acc, p, tile_m, tile_n, wm, wn, l32, g);
+    gemm_epilogue<BM, BN, EPI, D, WGM, WGN>(acc, p, tile_m, tile_n, wm, wn, l32, g, -1, split);
 }
 
 // Second half of a tail split: workgroup (tail tile, row tm of accumulator tiles) has the thread layout of
@@ -680,28 +684,28 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_tail_finish_kernel(GemmAr
 }
 
 // ------------------------------------------------------------------------------------------
-// Split-K companion kernels: clear the fp32 accumulator, and turn it into the final output with
-// the same epilogues as the fused path (each thread owns 4 consecutive features of one token and
-// writes zeros back, so the accumulator is clean for the next GEMM of the step).
+// Split-K companion kernel: adds the splits' slabs in split order (the sum does not depend on scheduling)
+// and applies the same epilogues as the fused path; each thread owns 4 consecutive features of one token.
 // ------------------------------------------------------------------------------------------
-__global__ void fill_zero_kernel(float4* p, int64_t n4) {
-    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n4) p[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+__device__ __forceinline__ float4 slab_sum(const float* first, int64_t slab_stride, int n_splits) {
+    float4 v = *reinterpret_cast<const float4*>(first);
+    for (int q = 1; q < n_splits; ++q) {
+        const float4 w = *reinterpret_cast<const float4*>(first + q * slab_stride);
+        v.x += w.x; v.y += w.y; v.z += w.z; v.w += w.w;
+    }
+    return v;
 }
 
 template <int EPI, int D>
 __global__ void __launch_bounds__(256) gemm_finish_kernel(GemmArgs p) {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    const float4 zero = make_float4(0.f, 0.f, 0.f, 0.f);
+    const int64_t stride = (int64_t)p.T * p.N;
     if (EPI == EPI_SWIGLU) {
         const int q_per_row = p.n_half / 4;
         if (i >= (int64_t)p.T * q_per_row) return;
         const int t = (int)(i / q_per_row), c = (int)(i % q_per_row) * 4;
-        float4* ga = reinterpret_cast<float4*>(p.accum + (int64_t)t * p.N + c);
-        float4* ua = reinterpret_cast<float4*>(p.accum + (int64_t)t * p.N + p.n_half + c);
-        const float4 gt = *ga, up = *ua;
-        *ga = zero;
-        *ua = zero;
+        const float4 gt = slab_sum(p.accum + (int64_t)t * p.N + c, stride, p.n_splits);
+        const float4 up = slab_sum(p.accum + (int64_t)t * p.N + p.n_half + c, stride, p.n_splits);
         const float o0 = gt.x / (1.0f + __expf(-gt.x)) * up.x, o1 = gt.y / (1.0f + __expf(-gt.y)) * up.y;
         const float o2 = gt.z / (1.0f + __expf(-gt.z)) * up.z, o3 = gt.w / (1.0f + __expf(-gt.w)) * up.w;
         *reinterpret_cast<uint2*>(static_cast<uint16_t*>(p.out) + (int64_t)t * p.n_half + c) =
@@ -715,14 +719,11 @@ __global__ void __launch_bounds__(256) gemm_finish_kernel(GemmArgs p) {
         const int t = (int)(i / units), u = (int)(i % units);
         const int64_t slot = p.tok_slot[t];
         const int kv_dim = p.n_kv * 2 * HALF;
-        float* row = p.accum + (int64_t)t * p.N;
+        const float* row = p.accum + (int64_t)t * p.N;
         if (u < rot_units) {
             const int head = u / (HALF / 4), i0 = (u % (HALF / 4)) * 4;
-            float4* lp = reinterpret_cast<float4*>(row + head * 2 * HALF + i0);
-            float4* hp = reinterpret_cast<float4*>(row + head * 2 * HALF + HALF + i0);
-            const float4 lo = *lp, hi = *hp;
-            *lp = zero;
-            *hp = zero;
+            const float4 lo = slab_sum(row + head * 2 * HALF + i0, stride, p.n_splits);
+            const float4 hi = slab_sum(row + head * 2 * HALF + HALF + i0, stride, p.n_splits);
             const float2* cs = p.rope_cs + (int64_t)t * HALF + i0;
             const float4 c01 = *reinterpret_cast<const float4*>(cs), c23 = *reinterpret_cast<const float4*>(cs + 2);
             const float a[4] = {lo.x, lo.y, lo.z, lo.w}, b[4] = {hi.x, hi.y, hi.z, hi.w};
@@ -739,18 +740,14 @@ __global__ void __launch_bounds__(256) gemm_finish_kernel(GemmArgs p) {
             *reinterpret_cast<uint2*>(dst + HALF + i0) = make_uint2(pack_bf16x2(h2[0], h2[1]), pack_bf16x2(h2[2], h2[3]));
         } else {
             const int c = (u - rot_units) * 4;
-            float4* vp = reinterpret_cast<float4*>(row + (p.n_q + p.n_kv) * 2 * HALF + c);
-            const float4 v = *vp;
-            *vp = zero;
+            const float4 v = slab_sum(row + (p.n_q + p.n_kv) * 2 * HALF + c, stride, p.n_splits);
             *reinterpret_cast<uint2*>(p.v_pages + slot * kv_dim + c) = make_uint2(pack_bf16x2(v.x, v.y), pack_bf16x2(v.z, v.w));
         }
     } else {
         const int q_per_row = p.N / 4;
         if (i >= (int64_t)p.T * q_per_row) return;
         const int64_t o = i * 4;
-        float4* ap = reinterpret_cast<float4*>(p.accum + o);
-        float4 v = *ap;
-        *ap = zero;
+        float4 v = slab_sum(p.accum + o, stride, p.n_splits);
         if (EPI == EPI_RES_BF16_OUT_F32) {
             if (p.residual) {
                 const uint2 r = *reinterpret_cast<const uint2*>(static_cast<const uint16_t*>(p.residual) + o);
@@ -768,7 +765,8 @@ __global__ void __launch_bounds__(256) gemm_finish_kernel(GemmArgs p) {
 }
 
 // Skinny path: T <= 256.  The weights are streamed once; to fill 256 CUs the k range of every
-// 128 x 256 (or 64 x 256) tile is split over several workgroups.  3-stage LDS ring: two stages of
+// 128 x 256 (or 64 x 256) tile is split over several workgroups, each storing its partial tile to its
+// split's slab.  3-stage LDS ring: two stages of
 // weights (2 x 32 KB) are in flight per CU.
 template <int BM, int EPI, int D>
 hipError_t launch_split(GemmArgs p, int splits, hipStream_t s) {
@@ -785,7 +783,8 @@ hipError_t launch_split(GemmArgs p, int splits, hipStream_t s) {
     p.tiles_n = (p.N + BN - 1) / BN;
     const int nk = p.K / 64;
     p.k_per_split = (nk + splits - 1) / splits;
-    splits = (nk + p.k_per_split - 1) / p.k_per_split;   // no empty split
+    splits = (nk + p.k_per_split - 1) / p.k_per_split;   // no empty split: the finish kernel reads every slab
+    p.n_splits = splits;
     gemm_dma_kernel<BM, BN, EPI_ATOMIC, 0, 64, NS><<<dim3(p.tiles_m * p.tiles_n * splits), dim3(256), smem, s>>>(p);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
@@ -821,11 +820,10 @@ bool skinny_applies(int T, int N, int K, const float* accum) {
 
 // Mid-size batches on a narrow output (W_o and W_down at a few hundred tokens): whole tiles are too few
 // for 256 CUs and splitting them through the fenced partial-tile protocol costs more than it gains, so
-// these run like the skinny path (k ranges accumulated with atomics, then the epilogue kernel) on tiles
+// these run like the skinny path (k ranges stored to slabs, then the finish kernel) on tiles
 // of 128 rows while every tile gets at least two k ranges, or of 256 rows while it gets at least three
-// and k is long.  Returns the tile rows, 0 = not this path.  The accumulator region (T x N floats, at
-// most 128 x 128 x 256 or 85 x 256 x 256) lies behind the tail scratch.
-constexpr int64_t kSplitFloats = 96 * 65536;
+// and k is long.  Returns the tile rows, 0 = not this path.  The slabs (at most 256 units x 256 x 256
+// floats) use the tail scratch.
 int split_rows(int T, int N, int K, bool has_accum) {
     static const bool off = getenv("RELSERVE_GEMM_NOSPLIT") != nullptr;   // tuning hook
     if (off || !has_accum || T <= SKINNY_MAX_T || K % 64 || N % 4 || g_force_generic || g_force_cand >= 0) return 0;
@@ -837,7 +835,6 @@ int split_rows(int T, int N, int K, bool has_accum) {
 
 template <int EPI>
 hipError_t launch_mid_split(GemmArgs p, int bm, hipStream_t s) {
-    p.accum += kTailCounters + kTailFloats;
     if (bm == 128) return launch_split<128, EPI, 0>(p, choose_splits(p.T, p.N, p.K, 128), s);
     return launch_split<256, EPI, 0>(p, choose_splits(p.T, p.N, p.K, 256), s);
 }
@@ -872,7 +869,7 @@ hipError_t launch_cfg(const GemmArgs& base, hipStream_t s, const Plan& plan = Pl
             p.k_per_split = (nk + plan.splits - 1) / plan.splits;
             p.tail_splits = (nk + p.k_per_split - 1) / p.k_per_split;   // no empty split
             p.tail_tiles = std::min(plan.tail_tiles, tiles);
-            p.tail_buf = p.accum + kTailCounters;
+            p.tail_buf = p.accum;
             if ((int64_t)p.tail_tiles * p.tail_splits * BM * BN > kTailFloats)
                 return hipErrorInvalidValue;   // a plan that does not fit the scratch: choose_plan never makes one
             grid = tiles - p.tail_tiles + p.tail_tiles * p.tail_splits;
@@ -990,16 +987,10 @@ void gemm_force_plan(int cand, int splits) {
 }
 
 int64_t gemm_scratch_floats(int64_t T, int64_t n_max) {
-    return T <= SKINNY_MAX_T ? T * n_max : kTailCounters + kTailFloats + kSplitFloats;
+    // skinny: one slab per split, at most 256 units of 128 x 256 floats, or a single slab of T x N
+    return T <= SKINNY_MAX_T ? std::max<int64_t>(T * n_max, 256 * 128 * 256) : kTailFloats;
 }
 
-ScratchUse gemm_scratch_use(int32_t T, int32_t N, int32_t K, bool qkv) {
-    if (T <= SKINNY_MAX_T) return ScratchUse{(int64_t)T * N, 0, 0};
-    if (K % 64 || g_force_generic || (qkv && T <= 64)) return ScratchUse{0, 0, 0};
-    if (!qkv && split_rows(T, N, K, true)) return ScratchUse{0, kTailCounters + kTailFloats, (int64_t)T * N};
-    (void)N;
-    return ScratchUse{0, 0, 0};   // whole tiles, or tail slabs that are written before they are read
-}
 
 // Tiled weight layout for streaming: out[n / 256][k / 64][n % 256][k % 64], rows past N are zeros.  One k
 // slice of 256 rows is 32 KB of consecutive memory, so a stage of the GEMM reads whole DRAM pages
@@ -1022,12 +1013,6 @@ hipError_t launch_pack_weight(const void* w, int32_t N, int32_t K, void* out, hi
     return hipGetLastError();
 }
 
-hipError_t launch_fill_zero(float* ptr, int64_t n_floats, hipStream_t s) {
-    const int64_t n4 = (n_floats + 3) / 4;
-    if (n4 == 0) return hipSuccess;
-    fill_zero_kernel<<<dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, s>>>(reinterpret_cast<float4*>(ptr), n4);
-    return hipGetLastError();
-}
 
 hipError_t launch_linear(const void* a, const void* w, int32_t T, int32_t N, int32_t K, int32_t epilogue,
                          const void* residual, void* out, hipStream_t s, float* accum, bool w_packed) {

@@ -559,18 +559,9 @@ int32_t relserve_layer_step(const relserve_layer* L, const relserve_batch* b, co
         e = launch();
         profile_mark(prof, slot, s, false);
     };
-    // the GEMMs split K across workgroups (whole skinny problems, or the incomplete last round of tiles)
-    // through a zeroed fp32 scratch; each GEMM leaves what it used zero again
+    // the GEMMs split K across workgroups (whole skinny problems, narrow outputs at mid-size T, or the
+    // incomplete last round of tiles) through an fp32 scratch that they write before they read
     float* accum = w.accum;
-    ScratchUse use{0, 0, 0};
-    for (const ScratchUse& u : {gemm_scratch_use(T, L->qkv_dim, c.hidden, true), gemm_scratch_use(T, c.hidden, L->q_dim, false),
-                                gemm_scratch_use(T, 2 * c.mlp_dim, c.hidden, false), gemm_scratch_use(T, c.hidden, c.mlp_dim, false)}) {
-        use.head = std::max(use.head, u.head);
-        if (u.mid > 0) use.mid_offset = u.mid_offset;
-        use.mid = std::max(use.mid, u.mid);
-    }
-    if (use.head > 0) e = launch_fill_zero(accum, use.head, s);
-    if (use.mid > 0 && e == hipSuccess) e = launch_fill_zero(accum + use.mid_offset, use.mid, s);
     run(S_NORM1, [&] { return launch_rmsnorm(x, false, wt->w_in_norm, c.rms_eps, T, c.hidden, w.h, s); });
     run(S_QKV, [&] {
         return launch_qkv_rope_append(b->dev, *L, w.h, wt->w_qkv, w.q, cache.k_pages, cache.v_pages, s, accum, packed);

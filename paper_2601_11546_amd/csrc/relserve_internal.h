@@ -87,8 +87,7 @@ int32_t expand_batch(const relserve_layer_config& cfg, const relserve_batch_desc
 // Rows of queries one attention workgroup covers (4 waves x 32 MFMA columns).
 constexpr int ATTN_BLOCK_M = 128;
 constexpr int SKINNY_MAX_T = 256;      // batches up to this many tokens take the split-K GEMM path
-constexpr int GEMM_TAIL_COUNTERS = 1024;               // split-tile arrival counters at the head of the GEMM scratch
-constexpr int64_t GEMM_TAIL_FLOATS = 256 * 65536;      // partial tiles of one round of split 256 x 256 tiles
+constexpr int64_t GEMM_TAIL_FLOATS = 256 * 65536;      // GEMM scratch at T > 256: partial tiles of one round of split 256 x 256 tiles
 constexpr int ATTN_SPLIT_ROWS = 16;   // query heads per kv head the decode kernel's 16-column MFMA holds
 
 // ---- kernel launchers (each enqueues on `s` and returns the launch status) ----------------
@@ -102,22 +101,15 @@ hipError_t launch_kv_append(const BatchDev& b, const void* k, const void* v, voi
                             int32_t row_elems, hipStream_t s);
 hipError_t launch_rope_append(const BatchDev& b, const relserve_layer& L, void* qkv, void* k_pages,
                               void* v_pages, hipStream_t s);
-// accum: optional fp32 scratch (gemm_scratch_floats(T, widest N) floats) whose parts named by
-// gemm_scratch_use hold zeros; lets skinny problems (T <= 256), narrow outputs at mid-size T and the
-// incomplete last round of larger ones split K over workgroups.  Those parts hold zeros again when the
-// launched kernels have finished.
+// accum: optional fp32 scratch (gemm_scratch_floats(T, widest N) floats, contents irrelevant on entry);
+// lets skinny problems (T <= 256), narrow outputs at mid-size T and the incomplete last round of larger
+// ones split K over workgroups (partial tiles written there, summed by a second kernel).
 int64_t gemm_scratch_floats(int64_t T, int64_t n_max);
-// The parts of the scratch that launch_linear / launch_qkv_rope_append expect to hold zeros for this
-// problem: `head` floats from its start and `mid` floats from float offset `mid_offset` (0 = none).  The
-// caller clears the largest of each over a sequence of launches once before it.
-struct ScratchUse { int64_t head, mid_offset, mid; };
-ScratchUse gemm_scratch_use(int32_t T, int32_t N, int32_t K, bool qkv);
 void gemm_force_plan(int cand, int splits);   // test hook, see relserve_debug_force_gemm_plan
 hipError_t launch_linear(const void* a, const void* w, int32_t T, int32_t N, int32_t K, int32_t epilogue,
                          const void* residual, void* out, hipStream_t s, float* accum = nullptr, bool w_packed = false);
 // w [N, K] row-major -> the tiled streaming layout (ceil(N / 256) * 256 * K elements), K % 64 == 0
 hipError_t launch_pack_weight(const void* w, int32_t N, int32_t K, void* out, hipStream_t s);
-hipError_t launch_fill_zero(float* ptr, int64_t n_floats, hipStream_t s);
 // q/k/v projection with rotary embedding and KV append fused into the epilogue: q_out [T, n_q d] bf16.
 hipError_t launch_qkv_rope_append(const BatchDev& b, const relserve_layer& L, const void* h, const void* w_qkv,
                                   void* q_out, void* k_pages, void* v_pages, hipStream_t s, float* accum = nullptr,

@@ -765,13 +765,14 @@ __global__ void __launch_bounds__(256) gemm_finish_kernel(GemmArgs p) {
 }
 
 // Skinny path: T <= 256.  The weights are streamed once; to fill 256 CUs the k range of every
-// 128 x 256 (or 64 x 256) tile is split over several workgroups, each storing its partial tile to its
-// split's slab.  3-stage LDS ring: two stages of
-// weights (2 x 32 KB) are in flight per CU.
-template <int BM, int EPI, int D>
+// BM x BN tile (BM = 64 / 128 tokens, BN = 128 / 256 features) is split over several workgroups, each
+// storing its partial tile to its split's slab.  The LDS ring is as deep as 160 KB allow (one workgroup
+// per CU); all stages but the one being computed are in flight.
+template <int BM, int EPI, int D, int BN = 256>
 hipError_t launch_split(GemmArgs p, int splits, hipStream_t s) {
-    constexpr int BN = 256, NS = BM == 64 ? 4 : BM == 128 ? 3 : 2;     // 160 / 144 / 128 KB of LDS: one workgroup per CU
+    constexpr int NS = BM + BN <= 192 ? 6 : BM + BN <= 256 ? 4 : BM + BN <= 320 ? 4 : BM + BN <= 384 ? 3 : 2;
     constexpr int smem = NS * (BM + BN) * 64 * 2;
+    static_assert(smem <= 160 * 1024, "ring exceeds the LDS");
     static bool attr_done = false;
     if (!attr_done) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_dma_kernel<BM, BN, EPI_ATOMIC, 0, 64, NS>),
@@ -800,17 +801,50 @@ hipError_t launch_split(GemmArgs p, int splits, hipStream_t s) {
 }
 
 // Number of k splits for a skinny GEMM: enough workgroups for every CU, at least 4 k steps each.
-int choose_splits(int T, int N, int K, int BM) {
-    const int tiles = ((T + BM - 1) / BM) * ((N + 255) / 256);
+int choose_splits(int T, int N, int K, int BM, int BN = 256) {
+    const int tiles = ((T + BM - 1) / BM) * ((N + BN - 1) / BN);
     const int nk = K / 64;
-    int splits = 256 / tiles;   // one workgroup per CU (144 KB of LDS each): a single full round
+    int splits = 256 / tiles;   // one workgroup per CU: a single full round
     splits = std::min(splits, std::max(1, nk / 4));
     return std::max(1, splits);
 }
 
+// The fused kernel on 128-feature tiles with a deep ring, one workgroup per CU: for a skinny GEMM whose
+// tiles fill the CUs without any k split (the gate/up projection), so no slabs and no finish kernel.
+template <int BM, int EPI>
+hipError_t launch_skinny_whole(GemmArgs p, hipStream_t s) {
+    constexpr int BN = 128, NS = BM == 64 ? 6 : 4;
+    constexpr int smem = NS * (BM + BN) * 64 * 2;
+    static_assert(smem <= 160 * 1024, "ring exceeds the LDS");
+    static bool attr_done = false;
+    if (!attr_done) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_dma_kernel<BM, BN, EPI, 0, 64, NS>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+        if (e != hipSuccess) return e;
+        attr_done = true;
+    }
+    p.tiles_m = (p.T + BM - 1) / BM;
+    p.tiles_n = EPI == EPI_SWIGLU ? (p.n_half + BN / 2 - 1) / (BN / 2) : (p.N + BN - 1) / BN;
+    p.tail_tiles = 0;
+    p.tail_splits = 1;
+    gemm_dma_kernel<BM, BN, EPI, 0, 64, NS><<<dim3(p.tiles_m * p.tiles_n), dim3(256), smem, s>>>(p);
+    return hipGetLastError();
+}
+
 template <int EPI, int D>
 hipError_t launch_skinny(const GemmArgs& p, hipStream_t s) {
-    if (p.T <= 64) return launch_split<64, EPI, D>(p, choose_splits(p.T, p.N, p.K, 64), s);
+    if (p.T <= 128) {
+        // One token tile: the MFMA work is small next to the weight stream, so 128-feature tiles cost nothing
+        // and need half the k splits (half the slab traffic); the gate/up projection has enough of them to
+        // fill the CUs unsplit and runs the fused kernel.
+        if constexpr (EPI == EPI_SWIGLU) {
+            const int tiles = (p.n_half + 63) / 64, rounds = (tiles + 255) / 256;
+            if (tiles >= 0.8 * 256 * rounds)
+                return p.T <= 64 ? launch_skinny_whole<64, EPI>(p, s) : launch_skinny_whole<128, EPI>(p, s);
+        }
+        if (p.T <= 64) return launch_split<64, EPI, D, 128>(p, choose_splits(p.T, p.N, p.K, 64, 128), s);
+        return launch_split<128, EPI, D, 128>(p, choose_splits(p.T, p.N, p.K, 128, 128), s);
+    }
     return launch_split<128, EPI, D>(p, choose_splits(p.T, p.N, p.K, 128), s);
 }
 

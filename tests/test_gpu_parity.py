@@ -392,6 +392,18 @@ def test_full_size_decode_only_13b(rs, oracle):
     _sampled_parity(rs, oracle, wl, [0, 5, 64, 127])
 
 
+@pytest.mark.parametrize("shape,n_dec,packed", [(W.LLAMA_13B, 40, True), (W.LLAMA_13B, 40, False), (W.LLAMA_70B, 100, True)],
+                         ids=["13b-40", "13b-40-rowmajor", "70b-100"])
+def test_full_size_small_decode_batches(rs, oracle, shape, n_dec, packed):
+    """Up to 128 decode rows on the full layer shapes: the gate/up projection has enough 128-feature tiles to
+    run the fused kernel unsplit (64- and 128-token tiles, deep ring); the others split k on 128-feature tiles."""
+    rng = np.random.default_rng(n_dec)
+    ctx = rng.integers(40, 400, n_dec)
+    b = W.build_batch(shape, np.ones(n_dec, np.int64), ctx, seed=n_dec, name=f"small_decode_{n_dec}")
+    wl = W.Workload(b.name, shape, b, 1007, n_layers=40)
+    _sampled_parity(rs, oracle, wl, [0, 1, n_dec // 2, n_dec - 1], packed=packed)
+
+
 def test_skinny_batches_of_every_token_tile_count(rs, oracle):
     """1, 20, 33, 64, 65 and 128 decode tokens: every token-tile count of the weight-streaming GEMM,
     on a layer wide enough for several feature tiles and k splits."""

@@ -1,0 +1,76 @@
+"""Oracle of the Priority Estimation Model (test infrastructure, not product code).
+
+Sec. 4.2: Algorithm 1 (Batch Decomposition) walks the requests of a relQuery in order and simulates the
+engine: requests join the current prefill batch p and the current decode batch d; p is closed when the next
+request would push it over max_num_batched_tokens; when the next request would push the tokens held on the
+GPU over `cap` or the decode batch over max_num_seqs, p is closed and d is decoded to completion (OL copies
+of d), after which both start empty again; what is left at the end is closed the same way.  Eq. 10: the
+priority of the relQuery is the sum of the predicted durations (Eq. 9) of all these batches.
+
+Readings where the algorithm's text leaves a choice (the product takes the same ones):
+  * the running token count `accum` starts again at zero together with p and d after a decode-to-completion
+    (the listing does not say; if it kept growing, every later request would force a flush);
+  * an empty batch is never emitted (a flush can find p empty right after a max_num_batched_tokens close);
+  * a request larger than max_num_batched_tokens forms a prefill batch of its own;
+  * a request with utok = 0 (already prefilled) joins no prefill batch; a request flagged as not decoding any
+    more joins no decode batch (Sec. 4.2, last sentence of the Algorithm 1 walk-through).
+
+Pure Python loops, in the order of the algorithm.  Only tests import this.
+"""
+from __future__ import annotations
+
+
+def batch_decompose(utok, out_len, cap, mns, mnbt, decodes=None):
+    """Returns (P, D): P = list of prefill batches (lists of request indices), D = list of decode batches
+    (each decode group repeated out_len times)."""
+    n = len(utok)
+    decodes = [True] * n if decodes is None else [bool(x) for x in decodes]
+    P, D = [], []
+    p, d, accum = [], [], 0
+
+    def close_prefill():
+        nonlocal p
+        if p:
+            P.append(p)
+        p = []
+
+    def decode_to_completion():
+        nonlocal d, accum
+        if d:
+            for _ in range(out_len):
+                D.append(list(d))
+        d, accum = [], 0
+
+    for i in range(n):
+        if utok[i] + accum > cap or len(d) + (1 if decodes[i] else 0) > mns:
+            close_prefill()
+            decode_to_completion()
+        if utok[i] + sum(utok[r] for r in p) > mnbt:
+            close_prefill()
+        if utok[i] > 0:
+            p.append(i)
+        if decodes[i]:
+            d.append(i)
+        accum += utok[i]
+    close_prefill()
+    decode_to_completion()
+    return P, D
+
+
+def pem(utok, out_len, cap, mns, mnbt, prefill_model, decode_model, decodes=None):
+    """Eq. 10 with Eq. 9's lines: models are (alpha, beta) pairs."""
+    P, D = batch_decompose(utok, out_len, cap, mns, mnbt, decodes)
+    ap, bp = prefill_model
+    ad, bd = decode_model
+    total = 0.0
+    for p in P:
+        total += ap * sum(utok[r] for r in p) + bp
+    for d in D:
+        total += ad * len(d) + bd
+    return total
+
+
+def utok_estimate(tok, sample_utok, sample_tok):
+    """Eq. 11: uncached tokens of a request estimated from the cache miss ratio of a sample of its relQuery."""
+    ratio = sum(sample_utok) / sum(sample_tok)
+    return [t * ratio for t in tok]

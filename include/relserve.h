@@ -268,6 +268,36 @@ typedef struct relserve_duration_model {
 int32_t relserve_duration_fit(const double* units, const double* seconds, int32_t n, relserve_duration_model* out);
 int32_t relserve_duration_predict(const relserve_duration_model* model, double units, double* seconds);
 
+/* ---- Priority Estimation Model (Sec. 4.2: Algorithm 1 "Batch Decomposition", Eq. 10) ----
+ * The scheduler's priority of a relQuery is its predicted remaining duration: its requests, in order, are
+ * decomposed into the prefill batches and decode batches the engine would run, and Eq. 9 is summed over them.
+ * utok[i] >= 0: uncached tokens request i still has to prefill (0 = already prefilled; it joins no prefill
+ * batch); decodes (may be NULL = all 1): whether request i still decodes; out_len = OL(R), the decode
+ * iterations of each group; limits: tokens the KV cache manager admits at once (cap), max_num_seqs and
+ * max_num_batched_tokens.  Walking the requests: request i first closes the open prefill batch and decodes the
+ * open group to completion if it would exceed cap or max_num_seqs (the token count restarts with them), then
+ * closes the open prefill batch if it would exceed max_num_batched_tokens, then joins both; the leftovers are
+ * closed at the end.  Empty batches are never emitted; a request above max_num_batched_tokens is a batch of
+ * its own.
+ * relserve_batch_decompose: outputs (any may be NULL except the counts): prefill_batch_of[i] / decode_group_of[i]
+ * = index of the batch / group request i joined (-1 = none); prefill_utok[b] = tokens of prefill batch b and
+ * group_req[g] = requests of decode group g (arrays of n entries are always large enough); *n_prefill, *n_groups.
+ * Every decode group stands for out_len identical decode batches.
+ * relserve_pem_estimate: *seconds = sum over prefill batches of (alpha_p utok + beta_p) + out_len x sum over
+ * decode groups of (alpha_d req + beta_d).  All pointers are HOST memory, read (or written) during the call.
+ * RELSERVE_ERR_BAD_ARGUMENT: negative n / out_len / utok / cap, or a limit below 1. */
+typedef struct relserve_pem_limits {
+    int32_t cap;
+    int32_t max_num_seqs;
+    int32_t max_num_batched_tokens;
+} relserve_pem_limits;
+int32_t relserve_batch_decompose(const int32_t* utok, const uint8_t* decodes, int32_t n, int32_t out_len,
+                                 const relserve_pem_limits* limits, int32_t* prefill_batch_of, int32_t* decode_group_of,
+                                 int32_t* prefill_utok, int32_t* n_prefill, int32_t* group_req, int32_t* n_groups);
+int32_t relserve_pem_estimate(const int32_t* utok, const uint8_t* decodes, int32_t n, int32_t out_len,
+                              const relserve_pem_limits* limits, const relserve_duration_model* prefill,
+                              const relserve_duration_model* decode, double* seconds);
+
 /* ---- peak probes: what this GPU sustains, reported by bench.py beside the published peaks ----
  * relserve_peak_probe_mfma enqueues 256 workgroups of 4 waves that each issue iters x 16 independent
  * 32x32x16 bf16 MFMAs on random operands (no memory traffic) and writes the flop count of the launch to

@@ -35,7 +35,7 @@ EXPORTS = ["relserve_version", "relserve_strerror", "relserve_config_validate", 
            "relserve_attention", "relserve_profile_slot_name", "relserve_profile_enable", "relserve_profile_read",
            "relserve_debug_force_gemm_plan", "relserve_peak_probe_mfma", "relserve_peak_probe_stream",
            "relserve_packed_weight_elems", "relserve_pack_weight", "relserve_linear_packed",
-           "relserve_duration_fit", "relserve_duration_predict"]
+           "relserve_duration_fit", "relserve_duration_predict", "relserve_batch_decompose", "relserve_pem_estimate"]
 
 
 class RelserveError(RuntimeError):
@@ -75,6 +75,10 @@ class Model(C.Structure):
 
 class DurationModel(C.Structure):
     _fields_ = [("alpha", C.c_double), ("beta", C.c_double), ("r2", C.c_double), ("n", C.c_int32)]
+
+
+class PemLimits(C.Structure):
+    _fields_ = [("cap", C.c_int32), ("max_num_seqs", C.c_int32), ("max_num_batched_tokens", C.c_int32)]
 
 
 class BatchInfo(C.Structure):
@@ -121,6 +125,9 @@ for _n, _a in {
     "relserve_profile_read": [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32],
     "relserve_duration_fit": [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p],
     "relserve_duration_predict": [C.c_void_p, C.c_double, C.c_void_p],
+    "relserve_batch_decompose": [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
+                                 C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p],
+    "relserve_pem_estimate": [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p],
 }.items():
     getattr(_lib, _n).restype = C.c_int32
     getattr(_lib, _n).argtypes = _a
@@ -408,4 +415,41 @@ def relserve_duration_predict(model: dict, units: float) -> float:
     m = DurationModel(model["alpha"], model["beta"], model.get("r2", 0.0), model.get("n", 0))
     out = C.c_double()
     _check(_lib.relserve_duration_predict(C.byref(m), float(units), C.byref(out)), "relserve_duration_predict")
+    return out.value
+
+
+def _pem_inputs(utok, decodes):
+    u = np.ascontiguousarray(utok, np.int32)
+    d = None if decodes is None else np.ascontiguousarray(decodes, np.uint8)
+    if u.ndim != 1 or (d is not None and d.shape != u.shape):
+        raise ValueError("utok and decodes must be vectors of one length")
+    return u, d
+
+
+def relserve_batch_decompose(utok, out_len: int, cap: int, max_num_seqs: int, max_num_batched_tokens: int, decodes=None) -> dict:
+    """Algorithm 1: {"prefill_batch_of", "decode_group_of", "prefill_utok", "group_req"} (numpy int32 arrays)."""
+    u, d = _pem_inputs(utok, decodes)
+    n = len(u)
+    lim = PemLimits(cap, max_num_seqs, max_num_batched_tokens)
+    pb, dg = np.empty(n, np.int32), np.empty(n, np.int32)
+    pu, gr = np.empty(max(n, 1), np.int32), np.empty(max(n, 1), np.int32)
+    npre, ngrp = C.c_int32(), C.c_int32()
+    _check(_lib.relserve_batch_decompose(u.ctypes.data_as(C.c_void_p), None if d is None else d.ctypes.data_as(C.c_void_p), n,
+                                         int(out_len), C.byref(lim), pb.ctypes.data_as(C.c_void_p), dg.ctypes.data_as(C.c_void_p),
+                                         pu.ctypes.data_as(C.c_void_p), C.byref(npre), gr.ctypes.data_as(C.c_void_p),
+                                         C.byref(ngrp)), "relserve_batch_decompose")
+    return {"prefill_batch_of": pb, "decode_group_of": dg, "prefill_utok": pu[:npre.value].copy(),
+            "group_req": gr[:ngrp.value].copy()}
+
+
+def relserve_pem_estimate(utok, out_len: int, cap: int, max_num_seqs: int, max_num_batched_tokens: int,
+                          prefill_model: dict, decode_model: dict, decodes=None) -> float:
+    """Eq. 10: predicted duration of a relQuery from its requests' uncached tokens and the two fitted lines."""
+    u, d = _pem_inputs(utok, decodes)
+    lim = PemLimits(cap, max_num_seqs, max_num_batched_tokens)
+    mp = DurationModel(prefill_model["alpha"], prefill_model["beta"], 0.0, 0)
+    md = DurationModel(decode_model["alpha"], decode_model["beta"], 0.0, 0)
+    out = C.c_double()
+    _check(_lib.relserve_pem_estimate(u.ctypes.data_as(C.c_void_p), None if d is None else d.ctypes.data_as(C.c_void_p), len(u),
+                                      int(out_len), C.byref(lim), C.byref(mp), C.byref(md), C.byref(out)), "relserve_pem_estimate")
     return out.value

@@ -48,3 +48,97 @@ int32_t relserve_duration_predict(const relserve_duration_model* model, double u
 }
 
 }  // extern "C"
+
+// ---- Priority Estimation Model (Sec. 4.2: Algorithm 1 and Eq. 10) ----
+// One walk over the requests in order.  State: tokens of the open prefill batch, requests of the open decode
+// group, tokens held on the GPU since the last decode-to-completion.
+namespace {
+struct PemWalk {
+    const relserve_pem_limits& lim;
+    int32_t out_len;
+    int32_t* prefill_utok;   // optional outputs
+    int32_t* group_req;
+    int32_t n_prefill = 0, n_groups = 0;
+    int64_t p_tok = 0, accum = 0;
+    int32_t p_req = 0, d_req = 0;
+    double seconds = 0;
+    const relserve_duration_model* mp;
+    const relserve_duration_model* md;
+
+    void close_prefill() {
+        if (p_req > 0) {
+            if (prefill_utok) prefill_utok[n_prefill] = (int32_t)p_tok;
+            if (mp) seconds += mp->alpha * (double)p_tok + mp->beta;
+            ++n_prefill;
+        }
+        p_tok = 0;
+        p_req = 0;
+    }
+    void decode_to_completion() {
+        if (d_req > 0) {
+            if (group_req) group_req[n_groups] = d_req;
+            if (md) seconds += (double)out_len * (md->alpha * (double)d_req + md->beta);
+            ++n_groups;
+        }
+        d_req = 0;
+        accum = 0;
+    }
+};
+
+int32_t pem_walk(const int32_t* utok, const uint8_t* decodes, int32_t n, int32_t out_len, const relserve_pem_limits* lim,
+                 int32_t* prefill_batch_of, int32_t* decode_group_of, PemWalk& w) {
+    if (n < 0 || out_len < 0 || !lim || lim->cap < 0 || lim->max_num_seqs < 1 || lim->max_num_batched_tokens < 1)
+        return RELSERVE_ERR_BAD_ARGUMENT;
+    if (n > 0 && !utok) return RELSERVE_ERR_NULL_POINTER;
+    for (int32_t i = 0; i < n; ++i)
+        if (utok[i] < 0) return RELSERVE_ERR_BAD_ARGUMENT;
+    for (int32_t i = 0; i < n; ++i) {
+        const bool dec = !decodes || decodes[i] != 0;
+        if ((int64_t)utok[i] + w.accum > lim->cap || w.d_req + (dec ? 1 : 0) > lim->max_num_seqs) {
+            w.close_prefill();
+            w.decode_to_completion();
+        }
+        if ((int64_t)utok[i] + w.p_tok > lim->max_num_batched_tokens) w.close_prefill();
+        if (prefill_batch_of) prefill_batch_of[i] = utok[i] > 0 ? w.n_prefill : -1;
+        if (decode_group_of) decode_group_of[i] = dec ? w.n_groups : -1;
+        if (utok[i] > 0) {
+            w.p_tok += utok[i];
+            ++w.p_req;
+        }
+        if (dec) ++w.d_req;
+        w.accum += utok[i];
+    }
+    w.close_prefill();
+    w.decode_to_completion();
+    return RELSERVE_OK;
+}
+}  // namespace
+
+extern "C" {
+
+int32_t relserve_batch_decompose(const int32_t* utok, const uint8_t* decodes, int32_t n, int32_t out_len,
+                                 const relserve_pem_limits* limits, int32_t* prefill_batch_of, int32_t* decode_group_of,
+                                 int32_t* prefill_utok, int32_t* n_prefill, int32_t* group_req, int32_t* n_groups) {
+    if (!limits || !n_prefill || !n_groups) return RELSERVE_ERR_NULL_POINTER;
+    PemWalk w{*limits, out_len, prefill_utok, group_req};
+    w.mp = nullptr;
+    w.md = nullptr;
+    if (int32_t rc = pem_walk(utok, decodes, n, out_len, limits, prefill_batch_of, decode_group_of, w)) return rc;
+    *n_prefill = w.n_prefill;
+    *n_groups = w.n_groups;
+    return RELSERVE_OK;
+}
+
+int32_t relserve_pem_estimate(const int32_t* utok, const uint8_t* decodes, int32_t n, int32_t out_len,
+                              const relserve_pem_limits* limits, const relserve_duration_model* prefill,
+                              const relserve_duration_model* decode, double* seconds) {
+    if (!limits || !prefill || !decode || !seconds) return RELSERVE_ERR_NULL_POINTER;
+    PemWalk w{*limits, out_len, nullptr, nullptr};
+    w.mp = prefill;
+    w.md = decode;
+    if (int32_t rc = pem_walk(utok, decodes, n, out_len, limits, nullptr, nullptr, w)) return rc;
+    *seconds = w.seconds;
+    return RELSERVE_OK;
+}
+
+}  // extern "C"

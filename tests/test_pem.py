@@ -80,3 +80,80 @@ def test_invariants_on_random_relqueries():
 def test_utok_estimate_is_the_sample_miss_ratio():
     est = opem.utok_estimate([100, 200, 50], sample_utok=[30, 10], sample_tok=[100, 100])    # miss ratio 0.2
     assert est == pytest.approx([20.0, 40.0, 10.0])
+
+
+# ---------------------------------------------------------------- the library against the oracle
+@pytest.fixture(scope="module")
+def rs():
+    from paper_2601_11546_amd import binding
+    return binding
+
+
+def _as_lists(res, n, out_len):
+    """Library outputs -> the oracle's (P, D) lists."""
+    P = [[] for _ in res["prefill_utok"]]
+    G = [[] for _ in res["group_req"]]
+    for i in range(n):
+        if res["prefill_batch_of"][i] >= 0:
+            P[res["prefill_batch_of"][i]].append(i)
+        if res["decode_group_of"][i] >= 0:
+            G[res["decode_group_of"][i]].append(i)
+    D = [list(g) for g in G for _ in range(out_len)]
+    return P, D, G
+
+
+def _same(rs, utok, ol, cap, mns, mnbt, decodes=None):
+    res = rs.relserve_batch_decompose(utok, ol, cap, mns, mnbt, decodes)
+    P, D, G = _as_lists(res, len(utok), ol)
+    oP, oD = opem.batch_decompose(list(utok), ol, cap, mns, mnbt, decodes)
+    assert P == oP and D == oD
+    assert list(res["prefill_utok"]) == [sum(utok[r] for r in p) for p in oP]
+    assert list(res["group_req"]) == [len(g) for g in G]
+    mp, md = {"alpha": MP[0], "beta": MP[1]}, {"alpha": MD[0], "beta": MD[1]}
+    got = rs.relserve_pem_estimate(utok, ol, cap, mns, mnbt, mp, md, decodes)
+    want = opem.pem(list(utok), ol, cap, mns, mnbt, MP, MD, decodes)
+    assert abs(got - want) <= 1e-12 * max(1.0, abs(want))
+
+
+def test_library_decomposition_matches_oracle_hand_cases(rs):
+    INT = 2 ** 31 - 1
+    _same(rs, [100, 100, 100], 2, INT, INT, INT)
+    _same(rs, [100, 100, 100], 3, INT, INT, 150)
+    _same(rs, [100, 40, 30, 90], 1, INT, INT, 150)
+    _same(rs, [100, 100, 100], 2, INT, 2, INT)
+    _same(rs, [100, 100, 100, 100, 100], 1, 250, INT, INT)
+    _same(rs, [80, 80, 80], 1, 200, INT, 100)
+    _same(rs, [500, 10], 1, INT, INT, 100)
+    _same(rs, [0, 50, 0], 2, INT, INT, INT)
+    _same(rs, [0, 50, 0], 2, INT, INT, INT, decodes=[0, 1, 1])
+    _same(rs, [], 3, 10, 10, 10)
+    _same(rs, [7], 0, 10, 1, 10)                       # no decode iterations: prefill cost only
+
+
+def test_library_decomposition_matches_oracle_random(rs):
+    rng = np.random.default_rng(1)
+    for _ in range(300):
+        n = int(rng.integers(0, 80))
+        utok = [int(x) for x in rng.integers(0, 600, n)]
+        decodes = None if rng.random() < 0.5 else [int(x) for x in rng.integers(0, 2, n)]
+        _same(rs, utok, int(rng.integers(0, 6)), int(rng.integers(0, 5000)), int(rng.integers(1, 24)),
+              int(rng.integers(1, 2500)), decodes)
+
+
+def test_library_pem_rejects_bad_arguments(rs):
+    m = {"alpha": 1.0, "beta": 1.0}
+    for args in (([5, -1], 1, 10, 1, 10), ([5], -1, 10, 1, 10), ([5], 1, -1, 1, 10), ([5], 1, 10, 0, 10), ([5], 1, 10, 1, 0)):
+        with pytest.raises(rs.RelserveError) as e:
+            rs.relserve_pem_estimate(*args, m, m)
+        assert e.value.status == -14
+
+
+def test_pem_orders_relqueries_by_work(rs):
+    """What the scheduler uses it for: with the fitted lines of this GPU, a relQuery with a cached template is
+    estimated shorter than the same relQuery uncached, and more requests take longer."""
+    mp, md = {"alpha": 22e-6, "beta": 8.3e-3}, {"alpha": 47e-6, "beta": 6.9e-3}      # 40-layer 13B, seconds
+    lim = (65536, 256, 8192)
+    cached = rs.relserve_pem_estimate([60] * 100, 5, *lim, mp, md)
+    cold = rs.relserve_pem_estimate([572] * 100, 5, *lim, mp, md)
+    more = rs.relserve_pem_estimate([60] * 200, 5, *lim, mp, md)
+    assert cached < cold and cached < more

@@ -298,6 +298,35 @@ int32_t relserve_pem_estimate(const int32_t* utok, const uint8_t* decodes, int32
                               const relserve_pem_limits* limits, const relserve_duration_model* prefill,
                               const relserve_duration_model* decode, double* seconds);
 
+/* ---- Adaptive Batch Arranger decision (Sec. 4.3, Eq. 14-17) and starvation rule (Sec. 4.2, Eq. 13) ----
+ * Each iteration runs either the candidate decode batch (all running requests) or the candidate prefill batch
+ * (requests of the first waiting relQuery).  relserve_aba_decide: both candidates empty -> IDLE; one empty ->
+ * the other; otherwise with m_running / m_waiting the smallest priority values in the two candidates (Eq. 14):
+ * m_running >= m_waiting -> PREFILL (a shorter relQuery preempts, or the running relQuery is still being
+ * prefilled); m_running < m_waiting -> *delta = delta_plus - delta_minus, where delta_plus (Eq. 15) =
+ * L_prefill(candidate) x running relQueries + sum over running relQueries R of alpha_d x req(candidate) x
+ * min(OL(R), OL(candidate)) and delta_minus (Eq. 16) = waiting relQueries x beta_d x min(OL(candidate), max OL(R));
+ * PREFILL iff *delta < 0 (Eq. 16 is a reduction: it is subtracted).  running_out_len: HOST array of
+ * n_running_relqueries entries, read only in the last case.  delta may be NULL; it is 0 in the other cases.
+ * relserve_starved_priority: *out = 0 if waiting_seconds / n_requests_submitted > threshold, else priority.
+ * Host only. */
+enum { RELSERVE_ABA_IDLE = 0, RELSERVE_ABA_PREFILL = 1, RELSERVE_ABA_DECODE = 2 };
+typedef struct relserve_aba_input {
+    double         m_running;               /* smallest priority value among the running requests */
+    double         m_waiting;               /* smallest priority value in the candidate prefill batch */
+    int32_t        n_running_reqs;          /* requests of the candidate decode batch (0 = empty) */
+    int32_t        cand_prefill_reqs;       /* requests of the candidate prefill batch (0 = empty) */
+    int32_t        cand_prefill_utok;       /* its uncached tokens */
+    int32_t        cand_prefill_out_len;    /* OL of its relQuery */
+    int32_t        n_running_relqueries;
+    int32_t        n_waiting_relqueries;
+    const int32_t* running_out_len;         /* OL of every running relQuery */
+} relserve_aba_input;
+int32_t relserve_aba_decide(const relserve_aba_input* in, const relserve_duration_model* prefill,
+                            const relserve_duration_model* decode, int32_t* decision, double* delta);
+int32_t relserve_starved_priority(double priority, double waiting_seconds, int32_t n_requests_submitted, double threshold,
+                                  double* out);
+
 /* ---- peak probes: what this GPU sustains, reported by bench.py beside the published peaks ----
  * relserve_peak_probe_mfma enqueues 256 workgroups of 4 waves that each issue iters x 16 independent
  * 32x32x16 bf16 MFMAs on random operands (no memory traffic) and writes the flop count of the launch to

@@ -35,7 +35,8 @@ EXPORTS = ["relserve_version", "relserve_strerror", "relserve_config_validate", 
            "relserve_attention", "relserve_profile_slot_name", "relserve_profile_enable", "relserve_profile_read",
            "relserve_debug_force_gemm_plan", "relserve_peak_probe_mfma", "relserve_peak_probe_stream",
            "relserve_packed_weight_elems", "relserve_pack_weight", "relserve_linear_packed",
-           "relserve_duration_fit", "relserve_duration_predict", "relserve_batch_decompose", "relserve_pem_estimate"]
+           "relserve_duration_fit", "relserve_duration_predict", "relserve_batch_decompose", "relserve_pem_estimate",
+           "relserve_aba_decide", "relserve_starved_priority"]
 
 
 class RelserveError(RuntimeError):
@@ -79,6 +80,12 @@ class DurationModel(C.Structure):
 
 class PemLimits(C.Structure):
     _fields_ = [("cap", C.c_int32), ("max_num_seqs", C.c_int32), ("max_num_batched_tokens", C.c_int32)]
+
+
+class AbaInput(C.Structure):
+    _fields_ = [("m_running", C.c_double), ("m_waiting", C.c_double), ("n_running_reqs", C.c_int32),
+                ("cand_prefill_reqs", C.c_int32), ("cand_prefill_utok", C.c_int32), ("cand_prefill_out_len", C.c_int32),
+                ("n_running_relqueries", C.c_int32), ("n_waiting_relqueries", C.c_int32), ("running_out_len", C.c_void_p)]
 
 
 class BatchInfo(C.Structure):
@@ -128,6 +135,8 @@ for _n, _a in {
     "relserve_batch_decompose": [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
                                  C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p],
     "relserve_pem_estimate": [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p],
+    "relserve_aba_decide": [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p],
+    "relserve_starved_priority": [C.c_double, C.c_double, C.c_int32, C.c_double, C.c_void_p],
 }.items():
     getattr(_lib, _n).restype = C.c_int32
     getattr(_lib, _n).argtypes = _a
@@ -452,4 +461,24 @@ def relserve_pem_estimate(utok, out_len: int, cap: int, max_num_seqs: int, max_n
     out = C.c_double()
     _check(_lib.relserve_pem_estimate(u.ctypes.data_as(C.c_void_p), None if d is None else d.ctypes.data_as(C.c_void_p), len(u),
                                       int(out_len), C.byref(lim), C.byref(mp), C.byref(md), C.byref(out)), "relserve_pem_estimate")
+    return out.value
+
+
+def relserve_aba_decide(m_running: float, m_waiting: float, n_running_reqs: int, cand_reqs: int, cand_utok: int,
+                        cand_out_len: int, running_out_lens, n_waiting: int, prefill_model: dict, decode_model: dict):
+    """Sec. 4.3: (decision, delta) with decision 0 = idle, 1 = run the prefill candidate, 2 = run the decode candidate."""
+    ol = np.ascontiguousarray(running_out_lens, np.int32)
+    inp = AbaInput(m_running, m_waiting, n_running_reqs, cand_reqs, cand_utok, cand_out_len, len(ol), n_waiting,
+                   ol.ctypes.data if len(ol) else None)
+    mp = DurationModel(prefill_model["alpha"], prefill_model["beta"], 0.0, 0)
+    md = DurationModel(decode_model["alpha"], decode_model["beta"], 0.0, 0)
+    dec, delta = C.c_int32(), C.c_double()
+    _check(_lib.relserve_aba_decide(C.byref(inp), C.byref(mp), C.byref(md), C.byref(dec), C.byref(delta)), "relserve_aba_decide")
+    return dec.value, delta.value
+
+
+def relserve_starved_priority(priority: float, waiting_seconds: float, n_requests_submitted: int, threshold: float) -> float:
+    out = C.c_double()
+    _check(_lib.relserve_starved_priority(priority, waiting_seconds, n_requests_submitted, threshold, C.byref(out)),
+           "relserve_starved_priority")
     return out.value

@@ -142,3 +142,46 @@ int32_t relserve_pem_estimate(const int32_t* utok, const uint8_t* decodes, int32
 }
 
 }  // extern "C"
+
+// ---- Adaptive Batch Arranger decision (Sec. 4.3, Eq. 14-17) and starvation rule (Sec. 4.2, Eq. 13) ----
+extern "C" {
+
+int32_t relserve_aba_decide(const relserve_aba_input* in, const relserve_duration_model* prefill,
+                            const relserve_duration_model* decode, int32_t* decision, double* delta) {
+    if (!in || !prefill || !decode || !decision) return RELSERVE_ERR_NULL_POINTER;
+    if (in->n_running_reqs < 0 || in->cand_prefill_reqs < 0 || in->cand_prefill_utok < 0 || in->cand_prefill_out_len < 0 ||
+        in->n_running_relqueries < 0 || in->n_waiting_relqueries < 0)
+        return RELSERVE_ERR_BAD_ARGUMENT;
+    if (delta) *delta = 0.0;
+    if (in->n_running_reqs == 0 && in->cand_prefill_reqs == 0) { *decision = RELSERVE_ABA_IDLE; return RELSERVE_OK; }
+    if (in->n_running_reqs == 0) { *decision = RELSERVE_ABA_PREFILL; return RELSERVE_OK; }
+    if (in->cand_prefill_reqs == 0) { *decision = RELSERVE_ABA_DECODE; return RELSERVE_OK; }
+    if (in->m_running >= in->m_waiting) { *decision = RELSERVE_ABA_PREFILL; return RELSERVE_OK; }   // preemption / same relQuery
+    // transitional case: latency added to the running relQueries against latency saved for the waiting ones
+    if (in->n_running_relqueries < 1 || !in->running_out_len) return RELSERVE_ERR_BAD_ARGUMENT;
+    const double l_prefill = prefill->alpha * (double)in->cand_prefill_utok + prefill->beta;
+    double d_plus = l_prefill * (double)in->n_running_relqueries;
+    int32_t max_ol = 0;
+    for (int32_t i = 0; i < in->n_running_relqueries; ++i) {
+        const int32_t ol = in->running_out_len[i];
+        if (ol < 0) return RELSERVE_ERR_BAD_ARGUMENT;
+        d_plus += decode->alpha * (double)in->cand_prefill_reqs * (double)(ol < in->cand_prefill_out_len ? ol : in->cand_prefill_out_len);
+        if (ol > max_ol) max_ol = ol;
+    }
+    const double d_minus = (double)in->n_waiting_relqueries * decode->beta *
+                           (double)(in->cand_prefill_out_len < max_ol ? in->cand_prefill_out_len : max_ol);
+    const double d = d_plus - d_minus;
+    if (delta) *delta = d;
+    *decision = d < 0 ? RELSERVE_ABA_PREFILL : RELSERVE_ABA_DECODE;
+    return RELSERVE_OK;
+}
+
+int32_t relserve_starved_priority(double priority, double waiting_seconds, int32_t n_requests_submitted, double threshold,
+                                  double* out) {
+    if (!out) return RELSERVE_ERR_NULL_POINTER;
+    if (n_requests_submitted < 1) return RELSERVE_ERR_BAD_ARGUMENT;
+    *out = waiting_seconds / (double)n_requests_submitted > threshold ? 0.0 : priority;
+    return RELSERVE_OK;
+}
+
+}  // extern "C"

@@ -811,14 +811,14 @@ int choose_splits(int T, int N, int K, int BM, int BN = 256) {
 
 // The fused kernel on 128-feature tiles with a deep ring, one workgroup per CU: for a skinny GEMM whose
 // tiles fill the CUs without any k split (the gate/up projection), so no slabs and no finish kernel.
-template <int BM, int EPI>
+template <int BM, int EPI, int D = 0, int BN = 128>
 hipError_t launch_skinny_whole(GemmArgs p, hipStream_t s) {
-    constexpr int BN = 128, NS = BM == 64 ? 6 : 4;
+    constexpr int NS = BM + BN <= 192 ? 6 : BM + BN <= 256 ? 4 : 3;
     constexpr int smem = NS * (BM + BN) * 64 * 2;
     static_assert(smem <= 160 * 1024, "ring exceeds the LDS");
     static bool attr_done = false;
     if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_dma_kernel<BM, BN, EPI, 0, 64, NS>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_dma_kernel<BM, BN, EPI, D, 64, NS>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, smem);
         if (e != hipSuccess) return e;
         attr_done = true;
@@ -827,7 +827,7 @@ hipError_t launch_skinny_whole(GemmArgs p, hipStream_t s) {
     p.tiles_n = EPI == EPI_SWIGLU ? (p.n_half + BN / 2 - 1) / (BN / 2) : (p.N + BN - 1) / BN;
     p.tail_tiles = 0;
     p.tail_splits = 1;
-    gemm_dma_kernel<BM, BN, EPI, 0, 64, NS><<<dim3(p.tiles_m * p.tiles_n), dim3(256), smem, s>>>(p);
+    gemm_dma_kernel<BM, BN, EPI, D, 64, NS><<<dim3(p.tiles_m * p.tiles_n), dim3(256), smem, s>>>(p);
     return hipGetLastError();
 }
 
@@ -845,7 +845,10 @@ hipError_t launch_skinny(const GemmArgs& p, hipStream_t s) {
         if (p.T <= 64) return launch_split<64, EPI, D, 128>(p, choose_splits(p.T, p.N, p.K, 64, 128), s);
         return launch_split<128, EPI, D, 128>(p, choose_splits(p.T, p.N, p.K, 128, 128), s);
     }
-    return launch_split<128, EPI, D>(p, choose_splits(p.T, p.N, p.K, 128), s);
+    // two token tiles: 256-feature tiles; a projection wide enough to need no k split runs the fused kernel
+    const int splits = choose_splits(p.T, p.N, p.K, 128);
+    if (splits == 1) return launch_skinny_whole<128, EPI, D, 256>(p, s);
+    return launch_split<128, EPI, D>(p, splits, s);
 }
 
 bool skinny_applies(int T, int N, int K, const float* accum) {

@@ -931,9 +931,9 @@ hipError_t launch_cfg(const GemmArgs& base, hipStream_t s, const Plan& plan = Pl
 // to BM), the tail round, and the per-tile efficiency against each other.
 struct TileCand { int bm, bn, wg_per_cu; float eff; bool qkv; };   // qkv: usable by the fused q/k/v epilogue (128 features per wave)
 constexpr TileCand kTiles[] = {
-    // efficiencies calibrated on T = 1282 / 6144 problems of the 13B and 70B layer shapes
-    {256, 256, 1, 1.00f, true}, {192, 256, 1, 0.92f, true}, {128, 256, 1, 0.78f, true}, {128, 128, 2, 0.87f, false},
-    {64, 128, 3, 0.75f, false},
+    // efficiencies from per-round times of forced plans at T = 288 ... 1282 on the 13B layer's projections
+    {256, 256, 1, 1.00f, true}, {192, 256, 1, 0.92f, true}, {128, 256, 1, 0.68f, true}, {128, 128, 2, 0.76f, false},
+    {64, 128, 3, 0.60f, false},
     // 8-wave variants, only by the test hook: 5 = 256 x 256 (4 x 2 waves), 6 = (2 x 4), 7 = 16 waves, 8 = 192 x 256, 9 = 128 x 256
     {256, 256, 1, 0.0f, true}, {256, 256, 1, 0.0f, false}, {256, 256, 1, 0.0f, false}, {192, 256, 1, 0.0f, false},
     {128, 256, 1, 0.0f, false}};
@@ -941,7 +941,7 @@ constexpr TileCand kTiles[] = {
 // A tail (the tiles of the incomplete last round) may split its k range over workgroups, so that the
 // round takes 1 / splits of a tile time; the price is that every partial tile is written to memory
 // and read back by the workgroup that finishes the tile.  Costs in seconds.
-constexpr double kCuFlops = 4.5e12;          // sustained MFMA rate of one CU inside a 256 x 256 tile
+constexpr double kCuFlops = 5.2e12;          // sustained MFMA rate of one CU inside a 256 x 256 tile
 constexpr double kSlabBytesPerSec = 3.0e12;  // partial tiles through memory (written by the GEMM, read by the finish kernel)
 constexpr double kTailFinishSec = 6e-6;      // the finish kernel's launch and ramp
 
@@ -977,12 +977,16 @@ Plan choose_plan_impl(int T, int64_t n_eff, int K, bool need_bn256, bool allow_t
         const int64_t tiles = ((T + c.bm - 1) / c.bm) * ((n_eff + c.bn - 1) / c.bn);
         const int64_t slots = 256 * c.wg_per_cu;
         // resident workgroups of a CU share its MFMA pipes: a round of wg_per_cu tiles costs wg_per_cu tile times
-        const double t_round = c.wg_per_cu * 2.0 * c.bm * c.bn * (double)K / (eff * kCuFlops);
+        double t_round = c.wg_per_cu * 2.0 * c.bm * c.bn * (double)K / (eff * kCuFlops);
+        // a launch that leaves CUs idle runs its big tiles faster (the chip is power-limited: up to 2.2 GHz
+        // instead of ~1.9); the small tiles are bound by L2 traffic and gain nothing
+        if (tiles < slots && c.bm >= 192) t_round /= 1.0 + 0.25 * (1.0 - (double)tiles / (double)slots);
         const int64_t full = tiles / slots, rem = tiles % slots;
         const double whole = (double)(full + (rem ? 1 : 0)) * t_round;
         if (whole < best_cost && forced_splits <= 1) best_cost = whole, best = Plan{i, 0, 1};
         const int nk = K / 64;
-        const bool can_tail = allow_tail && rem > 0 && K % 64 == 0;
+        // tiles that share a CU (two or three workgroups) gained nothing from split tails in any measured case
+        const bool can_tail = allow_tail && rem > 0 && K % 64 == 0 && (c.wg_per_cu == 1 || forced_splits > 1);
         for (int sp = 2; can_tail && sp <= 8 && nk / sp >= 8; ++sp) {
             if (forced_splits > 1 && sp != forced_splits) continue;
             const int64_t units = rem * sp;

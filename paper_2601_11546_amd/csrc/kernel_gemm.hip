@@ -14,8 +14,8 @@
 // Workgroup ids are remapped so that each of the 8 XCDs (own L2 each) walks a contiguous run of
 // tiles, inside it token tiles fastest within panels of GROUP_M token tiles.
 // Launch plans: tile shape by a cost model; the incomplete last round of tiles may split k over
-// workgroups (partial tiles through fp32 slabs); batches of at most 256 tokens split k everywhere
-// (fp32 atomics + a finishing kernel).
+// workgroups; batches of at most 256 tokens, and narrow outputs at a few hundred, split k everywhere.
+// Every split writes partial tiles to fp32 slabs that a second kernel sums and finishes.
 #include <algorithm>
 #include <cstdio>
 #include <cstdlib>
@@ -80,7 +80,7 @@ int g_force_splits = [] {
     return comma ? atoi(comma + 1) : 0;
 }();
 
-enum { EPI_BF16 = 0, EPI_RES_BF16_OUT_F32 = 1, EPI_RES_F32_OUT_BF16 = 2, EPI_SWIGLU = 3, EPI_QKV_ROPE = 4, EPI_ATOMIC = 5 };
+enum { EPI_BF16 = 0, EPI_RES_BF16_OUT_F32 = 1, EPI_RES_F32_OUT_BF16 = 2, EPI_SWIGLU = 3, EPI_QKV_ROPE = 4, EPI_SLAB = 5 };
 
 __device__ __forceinline__ int remap_xcd(int bid, int num) {
     const int per = num / NUM_XCD, rem = num % NUM_XCD;
@@ -109,7 +109,7 @@ __device__ __forceinline__ void gemm_epilogue(const f32x16_t (&acc)[BN / (32 * W
                                               int split = 0) {
     constexpr int TM = BM / (32 * WGM), TN = BN / (32 * WGN);
     const int t0 = tile_m * BM;
-    if (EPI == EPI_ATOMIC) {
+    if (EPI == EPI_SLAB) {
         // Split-K partial sums -> this split's slab.  These tiles were accumulated with the operands
         // swapped: register r holds token 8 (r / 4) + 4 g + r % 4 and feature l32, so one store
         // instruction writes two runs of 32 consecutive floats.  Plain stores: nothing is read back in
@@ -133,7 +133,7 @@ __device__ __forceinline__ void gemm_epilogue(const f32x16_t (&acc)[BN / (32 * W
         if (tm_only >= 0 && tm != tm_only) continue;   // the tail finish kernel: one row of accumulator tiles per workgroup
         const int t = t0 + wm * (BM / WGM) + 32 * tm + l32;
         if (t >= p.T) continue;
-        if (EPI == EPI_ATOMIC) {
+        if (EPI == EPI_SLAB) {
             // handled before this loop (transposed accumulator layout)
         } else if (EPI == EPI_QKV_ROPE) {
             // The wave owns features [nb, nb + 128): one head (d = 128) or two (d = 64).  The rotation
@@ -400,12 +400,12 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_dma_kernel(GemmArgs p) {
     int tile, split;
     bool tail = false;
     int tail_idx = 0;
-    if (EPI == EPI_ATOMIC) {
+    if (EPI == EPI_SLAB) {
         tile = remap_xcd(blockIdx.x % n_tiles, n_tiles);
         split = blockIdx.x / n_tiles;
     } else {
-        // the tail units come first in the grid: their short k ranges and atomic epilogues are over
-        // before the last whole tiles finish
+        // the tail units come first in the grid: their short k ranges and slab stores are over before the
+        // last whole tiles finish
         const int tail_units = p.tail_tiles * p.tail_splits, dp_tiles = n_tiles - p.tail_tiles;
         tail = (int)blockIdx.x < tail_units;
         if (tail) {
@@ -498,7 +498,7 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_dma_kernel(GemmArgs p) {
     };
 
     // k range of this workgroup (the whole K unless the launch splits it)
-    const bool part = EPI == EPI_ATOMIC || tail;
+    const bool part = EPI == EPI_SLAB || tail;
     const int kbeg = part ? split * p.k_per_split * (64 / BKD) : 0;
     const int nk = part ? min(p.k_per_split * (64 / BKD), K / BKD - kbeg) : K / BKD;
     // prologue: fill the whole ring, wait for stage 0 only
@@ -513,7 +513,7 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_dma_kernel(GemmArgs p) {
     load_frags(0, 0, 0);
     auto mfma_one = [&](int buf, int i) {   // i-th of the TN * TM products of a k step
         const int tn = i / TM, tm = i % TM;
-        acc[tn][tm] = EPI == EPI_ATOMIC ? mfma_32x32x16(af[buf][tm], wf[buf][tn], acc[tn][tm])
+        acc[tn][tm] = EPI == EPI_SLAB ? mfma_32x32x16(af[buf][tm], wf[buf][tn], acc[tn][tm])
                                         : mfma_32x32x16(wf[buf][tn], af[buf][tm], acc[tn][tm]);
     };
     auto load_frag_one = [&](int buf, int stage, int ks, int i) {   // i-th of the TN + TM fragment reads of a k step
@@ -618,7 +618,7 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_dma_kernel(GemmArgs p) {
         }
         cur = nxt;
     }
-    if (EPI != EPI_ATOMIC && tail) {
+    if (EPI != EPI_SLAB && tail) {
         // Partial tile -> this split's slab (registers 4 c .. 4 c + 3 of accumulator tile (tn, tm) of
         // thread tid are the 16 bytes at ((tn TM + tm) 4 + c) * threads + tid: coalesced).
         // gemm_tail_finish_kernel, launched behind this kernel, adds the slabs of a tile in split order and
@@ -775,7 +775,7 @@ hipError_t launch_split(GemmArgs p, int splits, hipStream_t s) {
     static_assert(smem <= 160 * 1024, "ring exceeds the LDS");
     static bool attr_done = false;
     if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_dma_kernel<BM, BN, EPI_ATOMIC, 0, 64, NS>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_dma_kernel<BM, BN, EPI_SLAB, 0, 64, NS>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, smem);
         if (e != hipSuccess) return e;
         attr_done = true;
@@ -786,7 +786,7 @@ hipError_t launch_split(GemmArgs p, int splits, hipStream_t s) {
     p.k_per_split = (nk + splits - 1) / splits;
     splits = (nk + p.k_per_split - 1) / p.k_per_split;   // no empty split: the finish kernel reads every slab
     p.n_splits = splits;
-    gemm_dma_kernel<BM, BN, EPI_ATOMIC, 0, 64, NS><<<dim3(p.tiles_m * p.tiles_n * splits), dim3(256), smem, s>>>(p);
+    gemm_dma_kernel<BM, BN, EPI_SLAB, 0, 64, NS><<<dim3(p.tiles_m * p.tiles_n * splits), dim3(256), smem, s>>>(p);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     int64_t units;

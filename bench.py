@@ -329,7 +329,8 @@ def main() -> None:
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "traffic.json")
     if os.path.exists(tpath):
-        traffic = json.load(open(tpath)).get(args.workload, {}).get(dom)
+        per_workload = json.load(open(tpath)).get(args.workload, {})
+        traffic = per_workload.get("whole_step" if hbm_bound else dom)
     if hbm_bound:
         roofline = {"bound": "hbm", "achieved": round(step_gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
                     "frac": round(step_gbs / PEAK_HBM_GBS, 4), "traffic": traffic, "kernel": "whole step",

@@ -202,6 +202,9 @@ def main() -> None:
     ap.add_argument("--duration-model", action="store_true",
                     help="instead of the benchmark line: time the 13B layer step over seeded prefill and decode batches and "
                          "print the fitted batch-duration model (slope, intercept, R^2 against uncached and total tokens)")
+    ap.add_argument("--serve-sim", action="store_true",
+                    help="fit the batch-duration model on this GPU (short sweep), then serve seeded Poisson traces of relQueries "
+                         "on the virtual clock under the FCFS and the RelServe policies and print their mean latencies")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-peak-probes", action="store_true", help="skip the MFMA issue loop and the streaming read")
     ap.add_argument("--calibration-copy", action="store_true",
@@ -220,6 +223,17 @@ def main() -> None:
     torch.cuda.set_device(0)
     if args.model_layers > 0:
         print(json.dumps(model_step_bench(args, rs, W, torch)))
+        return
+    if args.serve_sim:
+        from paper_2601_11546_amd import duration_model, scheduler
+        fit = duration_model.run(n_prefill=32, decode_sizes=(1, 16, 32, 64, 96, 128, 160, 192, 224, 256), steps=3, warmup=1)
+        layers = 40
+        mp = {k: fit["prefill"]["uncached_tokens"][k] * layers for k in ("alpha", "beta")}
+        md = {k: fit["decode"]["requests"][k] * layers for k in ("alpha", "beta")}
+        print(json.dumps({"metric": "mean_relquery_latency_s", "model": "13B layer shape x 40 layers (durations from the fitted lines)",
+                          "prefill_model": mp, "decode_model": md, "trace": "80 relQueries per run, 3 seeds, 1-100 requests each, "
+                          "templates 256-1024 tokens, suffixes 30-120, output 5 or 50 tokens",
+                          "results": scheduler.compare_policies(mp, md)}))
         return
     if args.duration_model:
         from paper_2601_11546_amd import duration_model

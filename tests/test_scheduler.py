@@ -1,0 +1,92 @@
+"""Iteration-level relQuery scheduler on the virtual clock (Sec. 4.1-4.3): conservation and limits, agreement of the
+engine loop with Algorithm 1's decomposition (Eq. 10), the head-of-line case the paper is about, starvation."""
+import numpy as np
+import pytest
+
+from oracle import pem as opem
+
+MP, MD = {"alpha": 2.2e-5, "beta": 8.6e-3}, {"alpha": 4.0e-5, "beta": 6.6e-3}     # 40-layer 13B on this GPU, seconds
+
+
+@pytest.fixture(scope="module")
+def sch():
+    from paper_2601_11546_amd import scheduler
+    return scheduler
+
+
+def _check_log(sch, trace, res, lim):
+    pre = sum(r[3] for r in res["log"] if r[1] == "prefill")
+    dec = sum(r[3] for r in res["log"] if r[1] == "decode")
+    assert pre == sum(q.n for q in trace)                                  # every request prefilled once
+    assert dec == sum(q.n * q.out_len for q in trace)                      # and decoded OL times
+    for t, kind, rid, reqs, toks in res["log"]:
+        if kind == "prefill":
+            assert toks <= lim.max_num_batched_tokens or reqs == 1
+        else:
+            assert reqs <= lim.max_num_seqs
+    assert all(v > 0 for v in res["latency"].values()) and len(res["latency"]) == len(trace)
+    times = [r[0] for r in res["log"]]
+    assert times == sorted(times)
+
+
+def test_tiny_trace_by_hand(sch):
+    # one relQuery, cold template of 100 tokens, suffixes 10 and 20, two decode iterations
+    q = sch.RelQuery(0, 0.0, 100, [10, 20], 2)
+    res = sch.serve([q], MP, MD, "fcfs")
+    kinds = [(r[1], r[3], r[4]) for r in res["log"]]
+    assert kinds == [("prefill", 2, 130), ("decode", 2, 2), ("decode", 2, 2)]          # the first request computes the template
+    want = MP["alpha"] * 130 + MP["beta"] + 2 * (MD["alpha"] * 2 + MD["beta"])
+    assert abs(res["latency"][0] - want) < 1e-12
+    assert sch.serve([q], MP, MD, "relserve")["latency"][0] == pytest.approx(want, abs=1e-12)
+
+
+@pytest.mark.parametrize("policy", ["fcfs", "relserve"])
+def test_lone_relquery_runs_as_algorithm_1_decomposes_it(sch, policy):
+    """The engine loop on a single relQuery executes exactly the batches Algorithm 1 predicts, so its duration is the
+    Priority Estimation Model's value (Eq. 10) computed by the independent oracle."""
+    rng = np.random.default_rng(5)
+    for _ in range(40):
+        n = int(rng.integers(1, 120))
+        q = sch.RelQuery(0, 0.0, int(rng.choice([256, 512, 1024])), [int(x) for x in rng.integers(30, 121, n)], int(rng.integers(1, 8)))
+        lim = sch.Limits(cap=int(rng.integers(1200, 9000)), max_num_seqs=int(rng.integers(2, 64)),
+                         max_num_batched_tokens=int(rng.integers(1200, 4096)))
+        res = sch.serve([q], MP, MD, policy, lim)
+        utok = [q.prefix + q.suffix[0]] + q.suffix[1:]
+        want = opem.pem(utok, q.out_len, lim.cap, lim.max_num_seqs, lim.max_num_batched_tokens,
+                        (MP["alpha"], MP["beta"]), (MD["alpha"], MD["beta"]))
+        assert res["latency"][0] == pytest.approx(want, rel=1e-9)
+        _check_log(sch, [q], res, lim)
+
+
+@pytest.mark.parametrize("policy", ["fcfs", "relserve"])
+def test_conservation_and_limits_on_poisson_traces(sch, policy):
+    for seed in range(4):
+        trace = sch.poisson_trace(25, rate=0.5, seed=seed)
+        lim = sch.Limits(cap=20000, max_num_seqs=64, max_num_batched_tokens=4096)
+        res = sch.serve(trace, MP, MD, policy, lim)
+        _check_log(sch, trace, res, lim)
+
+
+def test_short_relqueries_are_not_blocked_behind_a_long_one(sch):
+    long_q = sch.RelQuery(0, 0.0, 1024, [100] * 100, 50)
+    short = [sch.RelQuery(1 + i, 0.05 + 0.01 * i, 512, [60] * 3, 5) for i in range(5)]
+    lim = sch.Limits(cap=65536, max_num_seqs=64, max_num_batched_tokens=4096)
+    fcfs = sch.serve([long_q] + short, MP, MD, "fcfs", lim)
+    rel = sch.serve([long_q] + short, MP, MD, "relserve", lim)
+    assert rel["mean_latency"] < 0.7 * fcfs["mean_latency"]
+    for i in range(1, 6):                                                  # each short relQuery finishes earlier
+        assert rel["latency"][i] < fcfs["latency"][i]
+
+
+def test_starvation_threshold_bounds_the_wait_of_a_long_relquery(sch):
+    # short relQueries arrive a little faster than they can be served; a long one, entirely waiting, is passed over
+    # by each of them until its waiting time per request exceeds the threshold
+    stream = [sch.RelQuery(i, 0.045 * i, 256, [40] * 4, 5) for i in range(100)]
+    long_q = sch.RelQuery(1000, 0.01, 1024, [100] * 60, 20)
+    lim = sch.Limits(cap=65536, max_num_seqs=64, max_num_batched_tokens=4096)
+    free = sch.serve(stream + [long_q], MP, MD, "relserve", lim)
+    fair = sch.serve(stream + [long_q], MP, MD, "relserve", lim, starvation_threshold=0.02)
+    assert free["latency"][1000] > 3.0                                     # starved until the stream dries up
+    assert fair["latency"][1000] < 0.75 * free["latency"][1000]
+    first_long = min(r[0] for r in fair["log"] if r[1] == "prefill" and r[2] == 1000)
+    assert first_long >= 0.01 + 0.02 * 60                                  # not before the threshold is crossed

@@ -11,7 +11,8 @@ Every iteration runs one prefill batch or one decode batch (Sec. 4.1 step 1).  T
               (`relserve_aba_decide`) picks between it and the candidate decode batch.
 
 What a batch costs comes from the fitted batch-duration model (Eq. 9), so a run needs no GPU: the same loop can
-drive `relserve_model_step` by passing `execute=`, which is then called with every batch before the clock moves.
+drive `relserve_model_step` by passing `execute=` (`serving.GpuWorker`), which is called with every batch and returns
+the measured duration that then moves the clock instead of the prediction.
 The prefix cache is modelled per template: once a request of a relQuery has been prefilled, its template's tokens
 are cached (least-recently-used templates are dropped beyond `cache_tokens`) and later requests compute their
 suffix only.  Block-level prefix matching is not modelled.
@@ -169,9 +170,8 @@ class Engine:
 
     def run_prefill(self, cand) -> None:
         reqs, toks = sum(len(t) for _, t in cand), sum(sum(t) for _, t in cand)
-        if self.execute:
-            self.execute("prefill", cand)
-        self.now += rs.relserve_duration_predict(self.mp, toks)
+        measured = self.execute("prefill", cand) if self.execute else None
+        self.now += rs.relserve_duration_predict(self.mp, toks) if measured is None else measured
         for q, taken in cand:
             q.running += [[q.out_len, u] for u in taken]
             q.next_req += len(taken)
@@ -181,9 +181,8 @@ class Engine:
 
     def run_decode(self, running) -> None:
         reqs = sum(len(q.running) for q in running)
-        if self.execute:
-            self.execute("decode", running)
-        self.now += rs.relserve_duration_predict(self.md, reqs)
+        measured = self.execute("decode", running) if self.execute else None
+        self.now += rs.relserve_duration_predict(self.md, reqs) if measured is None else measured
         for q in running:
             for r in q.running:
                 r[0] -= 1
@@ -196,6 +195,8 @@ class Engine:
         q.running = left
         if q.done and q.finish_time < 0:
             q.finish_time = self.now
+            if self.execute is not None and hasattr(self.execute, "relquery_done"):
+                self.execute.relquery_done(q)
 
 
 def serve(relqueries, prefill_model: dict, decode_model: dict, policy: str, limits: Limits = Limits(), **kw) -> dict:

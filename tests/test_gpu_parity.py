@@ -422,7 +422,7 @@ def test_skinny_batches_of_every_token_tile_count(rs, oracle):
 
 def test_mid_size_batches_on_narrow_outputs(rs, oracle):
     """257 to 700 prefill tokens on a layer whose W_o / W_down outputs are few tiles wide: these GEMMs split
-    their k range over workgroups (atomic accumulation, then the epilogue kernel) behind the tail scratch."""
+    their k range over workgroups (partial tiles to slabs, then the finish kernel)."""
     shape = W.LayerShape(1024, 8, 2, 128, 2048)
     weights = W.make_weights(shape, 11)
     for q_len in ([257], [150, 150], [300, 211], [1, 400, 299]):

@@ -90,3 +90,34 @@ def test_starvation_threshold_bounds_the_wait_of_a_long_relquery(sch):
     assert fair["latency"][1000] < 0.75 * free["latency"][1000]
     first_long = min(r[0] for r in fair["log"] if r[1] == "prefill" and r[2] == 1000)
     assert first_long >= 0.01 + 0.02 * 60                                  # not before the threshold is crossed
+
+
+# ---------------------------------------------------------------- the loop executing its batches on the GPU
+@pytest.mark.gpu
+@pytest.mark.parametrize("policy", ["fcfs", "relserve"])
+def test_serving_loop_executes_its_batches_on_the_gpu(sch, policy):
+    """A short trace served for real: every batch goes through relserve_batch_prepare (which validates block tables,
+    prefix groups and write slots) and relserve_model_step; the page pool is whole again at the end; and a request
+    that read its relQuery's template from pages shared with (and written by) another request gets the logits of a
+    private recomputation."""
+    from paper_2601_11546_amd import serving
+    from paper_2601_11546_amd import workloads as W
+    shape, vocab = W.TINY_GQA, 512
+    rng = np.random.default_rng(9)
+    trace = [sch.RelQuery(i, 0.002 * i, int(rng.choice([32, 48, 64])), [int(x) for x in rng.integers(5, 21, int(rng.integers(2, 9)))],
+                          int(rng.integers(2, 5))) for i in range(6)]
+    lim = sch.Limits(cap=600, max_num_seqs=12, max_num_batched_tokens=160)
+    print(f"serving loop, policy {policy}: {sum(q.n for q in trace)} requests", flush=True)
+    worker = serving.GpuWorker(shape, n_layers=2, vocab=vocab, num_pages=256, max_tokens=256, max_reqs=16, seed=3, keep_logits=True)
+    res = sch.serve(trace, MP, MD, policy, lim, execute=worker)
+    _check_log(sch, trace, res, lim)
+    assert worker.batches == len(res["log"]) and res["makespan"] > 0
+    assert sorted(worker.free) == list(range(256)) and not worker.req_pages and not worker.template_pages
+    checked = 0
+    for q in trace:
+        for req in (0, q.n - 1):                      # the template's writer, and a reader of the shared pages
+            want = worker.standalone_logits(q, req)
+            got = worker.logits[(q.rid, req)]
+            assert np.abs(got - want).max() <= 2e-2 * max(1.0, np.abs(want).max()), (q.rid, req)
+            checked += 1
+    assert checked == 12 and sorted(worker.free) == list(range(256))

@@ -187,6 +187,35 @@ def model_step_bench(args, rs, W, torch) -> dict:
                      "frac_hbm_peak": round(nbytes / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)}}
 
 
+def serve_gpu(rs, W) -> dict:
+    """The scheduler loop with its batches executed on the GPU (Sec. 4.1): FCFS against the RelServe policy."""
+    from paper_2601_11546_amd import duration_model, scheduler, serving
+    layers, vocab = 4, 32000
+    fit = duration_model.run(n_prefill=32, decode_sizes=(1, 16, 32, 64, 96, 128, 160, 192, 224, 256), steps=3, warmup=1)
+    mp = {k: fit["prefill"]["uncached_tokens"][k] * layers for k in ("alpha", "beta")}     # what the policy predicts with
+    md = {k: fit["decode"]["requests"][k] * layers for k in ("alpha", "beta")}
+    lim = scheduler.Limits(cap=65536, max_num_seqs=256, max_num_batched_tokens=8192)
+    worker = serving.GpuWorker(W.LLAMA_13B, layers, vocab, num_pages=6144, max_tokens=8192 + 1200, max_reqs=256, seed=5)
+    rows = []
+    for rate in (20.0, 40.0, 60.0, 80.0):
+        trace = scheduler.poisson_trace(80, rate, seed=int(rate))
+        row = {"relqueries_per_s": rate}
+        for policy in ("fcfs", "relserve"):
+            t0 = time.perf_counter()
+            kw = {"starvation_threshold": 0.2} if policy == "relserve" else {}
+            res = scheduler.serve(trace, mp, md, policy, lim, execute=worker, **kw)
+            row[policy + "_mean_latency_s"] = round(res["mean_latency"], 4)
+            row[policy + "_batches"] = len(res["log"])
+            row[policy + "_wall_s"] = round(time.perf_counter() - t0, 1)
+            assert len(worker.free) == worker.num_pages
+        row["ratio"] = round(row["fcfs_mean_latency_s"] / row["relserve_mean_latency_s"], 3)
+        rows.append(row)
+    return {"metric": "mean_relquery_latency_s", "clock": "sum of the measured GPU durations of the executed batches",
+            "model": f"13B layer shape x {layers} layers, vocab {vocab}, random-init", "prefill_model": mp, "decode_model": md,
+            "trace": "80 relQueries per run, 1-100 requests each, templates 256-1024 tokens, suffixes 30-120, output 5 or 50 tokens",
+            "results": rows}
+
+
 def main() -> None:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -205,6 +234,9 @@ def main() -> None:
     ap.add_argument("--serve-sim", action="store_true",
                     help="fit the batch-duration model on this GPU (short sweep), then serve seeded Poisson traces of relQueries "
                          "on the virtual clock under the FCFS and the RelServe policies and print their mean latencies")
+    ap.add_argument("--serve-gpu", action="store_true",
+                    help="serve seeded Poisson traces of relQueries for real: every scheduled batch runs through "
+                         "relserve_model_step on a 4-layer model of the 13B layer shape; the clock is the measured GPU time")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-peak-probes", action="store_true", help="skip the MFMA issue loop and the streaming read")
     ap.add_argument("--calibration-copy", action="store_true",
@@ -223,6 +255,9 @@ def main() -> None:
     torch.cuda.set_device(0)
     if args.model_layers > 0:
         print(json.dumps(model_step_bench(args, rs, W, torch)))
+        return
+    if args.serve_gpu:
+        print(json.dumps(serve_gpu(rs, W)))
         return
     if args.serve_sim:
         from paper_2601_11546_amd import duration_model, scheduler

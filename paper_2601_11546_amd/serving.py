@@ -16,10 +16,13 @@ from . import binding as rs
 from . import workloads as W
 
 
-def token_id(rid: int, req: int, pos: int, vocab: int) -> int:
-    """Deterministic synthetic token: template positions (req = -1) are shared by the requests of a relQuery."""
-    h = (rid * 1000003 + (req + 1) * 7919 + pos * 104729 + 12345) & 0x7FFFFFFF
-    return (h * 2654435761 >> 7) % vocab
+def token_ids(rid: int, req: int, first: int, n: int, prefix: int, vocab: int) -> np.ndarray:
+    """Deterministic synthetic tokens of positions [first, first + n) of a request: template positions (below
+    `prefix`) depend on the relQuery only, so all its requests share them."""
+    pos = np.arange(first, first + n, dtype=np.int64)
+    who = np.where(pos < prefix, 0, req + 1)
+    h = (rid * 1000003 + who * 7919 + pos * 104729 + 12345) & 0x7FFFFFFF
+    return ((h * 2654435761 >> 7) % vocab).astype(np.int32)
 
 
 class GpuWorker:
@@ -102,9 +105,8 @@ class GpuWorker:
             pages = self.template_pages[q.rid] + self.req_pages[(q.rid, req)]
             nb = (c + P - 1) // P
             bt[r, :nb] = pages[:nb]
-            for pos in range(first, first + n):
-                ids[o] = token_id(q.rid, -1 if pos < q.prefix else req, pos, self.vocab)
-                o += 1
+            ids[o:o + n] = token_ids(q.rid, req, first, n, q.prefix, self.vocab)
+            o += n
         qs = np.zeros(len(rows) + 1, np.int32)
         qs[1:] = np.cumsum(q_len)
         pid = np.array([pid_of[q.rid] if first > 0 and q.rid in pid_of else -1 for q, _, first, _, _ in rows], np.int32)
@@ -150,7 +152,7 @@ class GpuWorker:
         bt = np.array([pages], np.int32)
         batch = W.Batch(np.array([0, n], np.int32), np.array([n], np.int32), bt, np.array([-1], np.int32), np.zeros(0, np.int32),
                         self.num_pages, "standalone")
-        ids = np.array([token_id(q.rid, -1 if pos < q.prefix else req, pos, self.vocab) for pos in range(n)], np.int32)
+        ids = token_ids(q.rid, req, 0, n, q.prefix, self.vocab)
         pb = rs.relserve_batch_prepare(self.layer, batch)
         logits = torch.empty(1, self.vocab, dtype=torch.float32, device="cuda")
         rs.relserve_model_step(self.layer, pb, self.model, torch.from_numpy(ids).cuda(), logits, self.ws)

@@ -32,6 +32,8 @@ def build_workload(name: str):
     table = {
         "relquery_13b": W.workload_relquery_13b,                       # configs[1]: the headline workload
         "relquery_32b": W.workload_relquery_32b,                       # the same batch on the 32B (5 q heads per kv head) shape
+        "relquery_70b_tp4_share": lambda: W.workload_tp_share("70b_tp4"),   # one GPU's share of the 70B layer at TP = 4
+        "relquery_32b_tp2_share": lambda: W.workload_tp_share("32b_tp2"),   # one GPU's share of the 32B layer at TP = 2
         "tiny": W.workload_tiny,                                       # configs[0]
         "decode_heavy_70b": W.workload_decode_heavy_70b,               # configs[2]
         "decode_only_70b": lambda: W.workload_decode_heavy_70b(with_chunk=False),

@@ -72,6 +72,8 @@ TINY_G5 = LayerShape(256, 10, 2, 64, 688)        # 5 query heads per kv head: th
 TINY_G3_D128 = LayerShape(256, 6, 2, 128, 688)
 LLAMA_13B = LayerShape(5120, 40, 40, 128, 13824)
 LLAMA_70B = LayerShape(8192, 64, 8, 128, 28672)
+LLAMA_70B_TP4 = LayerShape(8192, 16, 2, 128, 7168)     # one GPU's share of the 70B layer under 4-way tensor parallelism (Sec. 5.1)
+QWEN_32B_TP2 = LayerShape(5120, 20, 4, 128, 13824)     # one GPU's share of the 32B layer under 2-way tensor parallelism
 QWEN_32B = LayerShape(5120, 40, 8, 128, 27648)   # Sec. 5.1: the 32B model of the evaluation (grouped-query, 5 heads per kv head)
 
 
@@ -289,6 +291,14 @@ def workload_relquery_32b(seed: int = 1006) -> Workload:
     """The relQuery batch of workload_relquery_13b on the 32B layer shape (64 layers deep)."""
     wl = workload_relquery_13b(seed=seed, shape=QWEN_32B)
     return Workload("relquery_32b_16p184d", QWEN_32B, wl.batch, seed, n_layers=64)
+
+
+def workload_tp_share(which: str = "70b_tp4", seed: int = 1008) -> Workload:
+    """The relQuery batch of workload_relquery_13b on one GPU's share of a tensor-parallel layer: heads and MLP columns
+    divided by the parallel degree, hidden size whole (the all-reduces between the shares are not part of this build)."""
+    shape, depth = {"70b_tp4": (LLAMA_70B_TP4, 80), "32b_tp2": (QWEN_32B_TP2, 64)}[which]
+    wl = workload_relquery_13b(seed=seed, shape=shape)
+    return Workload(f"relquery_{which}_share", shape, wl.batch, seed, n_layers=depth)
 
 
 def workload_decode_heavy_70b(seed: int = 1002, with_chunk: bool = True, n_rel: int = 4,

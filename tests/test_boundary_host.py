@@ -43,7 +43,7 @@ def test_config_validation(rs):
            replace(ok, rope_base=0.0), replace(ok, n_q_heads=32, n_kv_heads=1)]
     for b in bad:
         assert rs.relserve_config_validate(b) == -2, b
-    for good in (W.TINY_GQA, W.TINY_D128, W.TINY_G5, W.TINY_G3_D128, W.LLAMA_13B, W.LLAMA_70B, W.QWEN_32B,
+    for good in (W.TINY_GQA, W.TINY_D128, W.TINY_G5, W.TINY_G3_D128, W.LLAMA_13B, W.LLAMA_70B, W.QWEN_32B, W.LLAMA_70B_TP4, W.QWEN_32B_TP2,
                  replace(ok, page_size=256)):
         assert rs.relserve_config_validate(good) == 0
 

@@ -371,6 +371,14 @@ def test_full_size_relquery_32b(rs, oracle):
     _sampled_parity(rs, oracle, wl, [0, 15, 16, 99, 199], packed=True)
 
 
+@pytest.mark.parametrize("which", ["70b_tp4", "32b_tp2"])
+def test_full_size_tensor_parallel_shares(rs, oracle, which):
+    """One GPU's share of the 70B layer at 4-way and of the 32B layer at 2-way tensor parallelism (the shapes the
+    paper's multi-GPU runs put on each GPU): heads and MLP columns divided, hidden size whole."""
+    wl = W.workload_tp_share(which)
+    _sampled_parity(rs, oracle, wl, [0, 15, 16, 120, 199], packed=True)
+
+
 def test_full_size_decode_heavy_70b(rs, oracle):
     wl = W.workload_decode_heavy_70b()
     _sampled_parity(rs, oracle, wl, [0, 63, 64, 130, 255, 256], max_prefill_rows=24)

@@ -209,12 +209,14 @@ def serve_gpu(rs, W) -> dict:
             row[policy + "_mean_latency_s"] = round(res["mean_latency"], 4)
             row[policy + "_batches"] = len(res["log"])
             row[policy + "_wall_s"] = round(time.perf_counter() - t0, 1)
-            assert len(worker.free) == worker.num_pages
+            worker.cache.check()
+            assert not worker.pages
         row["ratio"] = round(row["fcfs_mean_latency_s"] / row["relserve_mean_latency_s"], 3)
         rows.append(row)
     return {"metric": "mean_relquery_latency_s", "clock": "sum of the measured GPU durations of the executed batches",
             "model": f"13B layer shape x {layers} layers, vocab {vocab}, random-init", "prefill_model": mp, "decode_model": md,
             "trace": "80 relQueries per run, 1-100 requests each, templates 256-1024 tokens, suffixes 30-120, output 5 or 50 tokens",
+            "prefix_cache": {"tokens_served_from_cache": worker.cache.hits, "tokens_computed": worker.cache.misses},
             "results": rows}
 
 

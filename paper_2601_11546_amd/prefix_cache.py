@@ -95,6 +95,15 @@ class BlockPrefixCache:
         self.misses += len(tokens) - cached * P
         return pages, cached * P, n_ready
 
+    def acquire_private(self, n_pages: int) -> list:
+        """Pages that take no part in sharing (no keys): for a computation that must not touch cached blocks."""
+        if n_pages > self.pages_available():
+            raise RuntimeError("KV page pool exhausted")
+        pages = [self._take() for _ in range(n_pages)]
+        for page in pages:
+            self.refs[page] = 1
+        return pages
+
     def mark_ready(self, pages) -> None:
         """The batch that wrote these pages has run."""
         for page in pages:

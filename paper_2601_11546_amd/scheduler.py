@@ -32,6 +32,7 @@ class RelQuery:
     prefix: int                    # template tokens shared by all requests
     suffix: list                   # private tokens per request
     out_len: int                   # OL(R): decode iterations per request
+    template: int = -1             # relQueries with the same template id share its tokens (-1: its own)
     # run state
     next_req: int = 0              # requests [0, next_req) have been prefilled
     running: list = field(default_factory=list)    # [remaining decode iterations, tokens admitted] of the prefilled, unfinished requests
@@ -72,16 +73,23 @@ class Engine:
         self.log = []                                # (time, kind, rid or -1, requests, tokens)
 
     # ---- prefix cache (template granularity)
+    @staticmethod
+    def tid(q: RelQuery) -> int:
+        return q.template if q.template >= 0 else -1 - q.rid
+
     def cached(self, q: RelQuery) -> bool:
-        return q.rid in self.cache
+        return self.tid(q) in self.cache
 
     def touch(self, q: RelQuery) -> None:
-        self.cache[q.rid] = q.prefix
-        self.cache.move_to_end(q.rid)
+        self.cache[self.tid(q)] = q.prefix
+        self.cache.move_to_end(self.tid(q))
         while sum(self.cache.values()) > self.cache_tokens and len(self.cache) > 1:
             self.cache.popitem(last=False)
 
     def utok(self, q: RelQuery, i: int, cached: bool) -> int:
+        if self.execute is not None and hasattr(self.execute, "uncached_tokens"):
+            exact = self.execute.uncached_tokens(q, i)       # the worker's block-level cache as it stands
+            return min(exact, q.suffix[i]) if cached else exact
         return q.suffix[i] + (0 if cached else q.prefix)
 
     # ---- admission limits shared by both policies
@@ -195,13 +203,11 @@ class Engine:
         q.running = left
         if q.done and q.finish_time < 0:
             q.finish_time = self.now
-            if self.execute is not None and hasattr(self.execute, "relquery_done"):
-                self.execute.relquery_done(q)
 
 
 def serve(relqueries, prefill_model: dict, decode_model: dict, policy: str, limits: Limits = Limits(), **kw) -> dict:
     """Runs the trace to completion; returns per-relQuery latencies and the iteration log."""
-    qs = sorted((RelQuery(q.rid, q.arrival, q.prefix, list(q.suffix), q.out_len) for q in relqueries),
+    qs = sorted((RelQuery(q.rid, q.arrival, q.prefix, list(q.suffix), q.out_len, q.template) for q in relqueries),
                 key=lambda q: (q.arrival, q.rid))
     eng = Engine(prefill_model, decode_model, limits, policy, **kw)
     arrived, i = [], 0

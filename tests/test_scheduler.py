@@ -106,18 +106,27 @@ def test_serving_loop_executes_its_batches_on_the_gpu(sch, policy):
     rng = np.random.default_rng(9)
     trace = [sch.RelQuery(i, 0.002 * i, int(rng.choice([32, 48, 64])), [int(x) for x in rng.integers(5, 21, int(rng.integers(2, 9)))],
                           int(rng.integers(2, 5))) for i in range(6)]
+    trace.append(sch.RelQuery(6, 0.02, trace[0].prefix, [7, 19, 12], 3, template=0))      # a second relQuery behind relQuery 0's template
+    trace[0].template = 0
     lim = sch.Limits(cap=600, max_num_seqs=12, max_num_batched_tokens=160)
     print(f"serving loop, policy {policy}: {sum(q.n for q in trace)} requests", flush=True)
     worker = serving.GpuWorker(shape, n_layers=2, vocab=vocab, num_pages=256, max_tokens=256, max_reqs=16, seed=3, keep_logits=True)
     res = sch.serve(trace, MP, MD, policy, lim, execute=worker)
     _check_log(sch, trace, res, lim)
     assert worker.batches == len(res["log"]) and res["makespan"] > 0
-    assert sorted(worker.free) == list(range(256)) and not worker.req_pages and not worker.template_pages
+    worker.cache.check()
+    assert not worker.pages and all(r == 0 for r in worker.cache.refs)
+    # every relQuery's template was computed once: by its first request, or not at all behind a cached template
+    computed = sum(r[4] for r in res["log"] if r[1] == "prefill")
+    assert computed == sum(sum(q.suffix) for q in trace) + sum(q.prefix for q in trace[:6])
+    assert worker.cache.misses == computed and worker.cache.hits == sum(q.prefix * q.n for q in trace) - sum(q.prefix for q in trace[:6])
     checked = 0
     for q in trace:
-        for req in (0, q.n - 1):                      # the template's writer, and a reader of the shared pages
+        for req in (0, q.n - 1):                      # the template's writer (or first reader), and a reader of the shared pages
             want = worker.standalone_logits(q, req)
             got = worker.logits[(q.rid, req)]
             assert np.abs(got - want).max() <= 2e-2 * max(1.0, np.abs(want).max()), (q.rid, req)
             checked += 1
-    assert checked == 12 and sorted(worker.free) == list(range(256))
+    assert checked == 14
+    worker.cache.check()
+    assert all(r == 0 for r in worker.cache.refs)

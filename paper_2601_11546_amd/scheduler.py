@@ -6,7 +6,8 @@ Every iteration runs one prefill batch or one decode batch (Sec. 4.1 step 1).  T
   "fcfs"      the engine default the paper starts from (Sec. 2.3): waiting requests in arrival order, prefill
               first whenever a request can be admitted, otherwise decode all running requests;
   "relserve"  priorities = predicted remaining duration of each relQuery (`relserve_pem_estimate` over the current
-              prefix-cache state, reused while a relQuery is entirely waiting, zeroed by the starvation rule);
+              prefix-cache state — uncached tokens counted exactly or estimated from a sample's miss ratio (Eq. 11) —
+              reused while a relQuery is entirely waiting (Eq. 12), zeroed by the starvation rule (Eq. 13));
               the candidate prefill batch holds requests of the first waiting relQuery only; the arranger
               (`relserve_aba_decide`) picks between it and the candidate decode batch.
 
@@ -64,10 +65,11 @@ class Limits:
 
 class Engine:
     def __init__(self, prefill_model: dict, decode_model: dict, limits: Limits = Limits(), policy: str = "relserve",
-                 cache_tokens: int = 1 << 20, starvation_threshold: float = float("inf"), execute=None):
+                 cache_tokens: int = 1 << 20, starvation_threshold: float = float("inf"), execute=None, sample_size: int = 0):
         assert policy in ("fcfs", "relserve")
         self.mp, self.md, self.lim, self.policy = prefill_model, decode_model, limits, policy
         self.cache_tokens, self.threshold, self.execute = cache_tokens, starvation_threshold, execute
+        self.sample_size = sample_size               # Eq. 11: requests sampled per relQuery for the miss ratio (0 = count exactly)
         self.cache: OrderedDict = OrderedDict()      # rid -> template tokens, in LRU order
         self.now = 0.0
         self.log = []                                # (time, kind, rid or -1, requests, tokens)
@@ -112,12 +114,24 @@ class Engine:
         return taken
 
     # ---- priorities (Sec. 4.2)
+    def waiting_utok(self, q: RelQuery) -> list:
+        """Uncached tokens of the waiting requests of q: counted exactly, or (Eq. 11) for the first waiting request
+        exactly and for the others as their prompt length times the cache miss ratio of a small sample of them."""
+        cached = self.cached(q)
+        first, rest = q.next_req, list(range(q.next_req + 1, q.n))
+        out = [self.utok(q, first, cached)] if first < q.n else []
+        if not self.sample_size or len(rest) <= self.sample_size:
+            return out + [self.utok(q, i, True) for i in rest]
+        step = len(rest) / self.sample_size
+        sample = [rest[int(k * step)] for k in range(self.sample_size)]        # evenly spread: deterministic
+        ratio = sum(self.utok(q, i, True) for i in sample) / sum(q.prefix + q.suffix[i] for i in sample)
+        return out + [int(round((q.prefix + q.suffix[i]) * ratio)) for i in rest]
+
     def update_priorities(self, active) -> None:
         for q in active:
             entirely_waiting = q.next_req == 0
             if not (q.priority_valid and entirely_waiting):          # Eq. 12: reuse while nothing of it has run
-                cached = self.cached(q)
-                utok = [0] * q.next_req + [self.utok(q, i, cached or i > q.next_req) for i in range(q.next_req, q.n)]
+                utok = [0] * q.next_req + self.waiting_utok(q)
                 decodes = [0] * q.n
                 for i in range(q.next_req, q.n):
                     decodes[i] = 1

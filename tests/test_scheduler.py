@@ -130,3 +130,24 @@ def test_serving_loop_executes_its_batches_on_the_gpu(sch, policy):
     assert checked == 14
     worker.cache.check()
     assert all(r == 0 for r in worker.cache.refs)
+
+
+def test_sampled_miss_ratio_estimates_uncached_tokens(sch):
+    """Eq. 11: the estimate for the unsampled requests is their prompt length times the sample's miss ratio (the
+    oracle's formula), and the priorities built on it stay close to the exactly counted ones."""
+    from oracle import pem as opem
+    rng = np.random.default_rng(2)
+    q = sch.RelQuery(0, 0.0, 512, [int(x) for x in rng.integers(30, 121, 60)], 5)
+    exact = sch.Engine(MP, MD).waiting_utok(q)
+    eng = sch.Engine(MP, MD, sample_size=8)
+    est = eng.waiting_utok(q)
+    assert est[0] == exact[0] == 512 + q.suffix[0]                        # the first request brings the template
+    rest = list(range(1, 60))
+    sample = [rest[int(k * len(rest) / 8)] for k in range(8)]
+    want = opem.utok_estimate([512 + q.suffix[i] for i in rest], [q.suffix[i] for i in sample], [512 + q.suffix[i] for i in sample])
+    assert est[1:] == [int(round(w)) for w in want]
+    assert abs(sum(est) - sum(exact)) <= 0.25 * sum(exact)                 # eight samples of suffixes spread over 30-120
+    trace = sch.poisson_trace(30, rate=4.0, seed=7)
+    a = sch.serve(trace, MP, MD, "relserve")["mean_latency"]
+    b = sch.serve(trace, MP, MD, "relserve", sample_size=8)["mean_latency"]
+    assert abs(a - b) <= 0.15 * a

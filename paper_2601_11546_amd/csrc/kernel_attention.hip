@@ -19,7 +19,9 @@
 //   attn_decode_kernel one WAVE = one decode token x one kv head (rows = the heads of the
 //                      group); each wave streams its own 32-key blocks through a private LDS
 //                      region, so a workgroup needs no barrier and short contexts still fill
-//                      the chip.  HBM-bound: the MFMA work is a few percent of the time.
+//                      the chip.  The four waves of a workgroup take four adjacent kv heads of
+//                      one token, i.e. 1 KB of every cached row.  HBM-bound: the MFMA work is a
+//                      few percent of the time.
 #include <type_traits>
 
 #include "device_utils.h"
@@ -45,6 +47,7 @@ struct AttnArgs {
     int32_t n_items;
     int32_t max_blocks, page_shift, page_mask;
     int32_t q_pitch, n_q, n_kv, group;
+    int32_t dec_by_head;   // decode workgroups take four adjacent kv heads of one token (n_kv % 4 == 0)
     float scale_log2;  // log2(e) / sqrt(d)
 };
 
@@ -352,7 +355,7 @@ template <int D>
 __device__ __forceinline__ int dvswz(int row) { return D == 128 ? 2 * (row & 7) : 2 * ((row >> 1) & 3); }
 
 template <int D>
-__device__ __forceinline__ void attn_decode_body(const AttnArgs& p, const AttnItem* items, int n_items, int wg_idx, int kvh) {
+__device__ __forceinline__ void attn_decode_body(const AttnArgs& p, const AttnItem* items, int n_items, int w) {
     using SM = DecodeSmem<D>;
     constexpr int CH = D / 8;                 // 16-byte chunks per K/V row
     constexpr int RPI = 64 / CH;              // rows one 1 KB wave load covers
@@ -363,7 +366,20 @@ __device__ __forceinline__ void attn_decode_body(const AttnArgs& p, const AttnIt
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l16 = lane & 15, gq = lane >> 4;
-    const int item_idx = wg_idx * 4 + wave;
+    // Decode workgroup w: with a multiple of four kv heads, its four waves take four ADJACENT heads of ONE token, so
+    // the workgroup reads 1 KB of every key / value row where four tokens' single heads would read 256 bytes each
+    // (a row is all heads of a token, back to back), and consecutive workgroups finish the row; otherwise the waves
+    // take four tokens of one head.
+    int item_idx, kvh;
+    if (p.dec_by_head) {
+        const int hg = p.n_kv >> 2;
+        item_idx = w / hg;
+        kvh = (w % hg) * 4 + wave;
+    } else {
+        const int n_wg = (n_items + 3) / 4;
+        item_idx = (w % n_wg) * 4 + wave;
+        kvh = w / n_wg;
+    }
     if (item_idx >= n_items) return;             // whole wave leaves; this path has no workgroup barrier
     const AttnItem it = items[item_idx];
     unsigned char* sk = smem + wave * SM::WAVE_BYTES;
@@ -528,7 +544,7 @@ __global__ void __launch_bounds__(256, 2) attn_tile_kernel(AttnArgs p) {
 
 template <int D>
 __global__ void __launch_bounds__(256, 2) attn_decode_kernel(AttnArgs p) {
-    attn_decode_body<D>(p, p.items, p.n_items, blockIdx.x, blockIdx.y);
+    attn_decode_body<D>(p, p.items, p.n_items, blockIdx.x);
 }
 
 // Prefill rows (row-tiled items) and decode rows (wave items) over their own keys in ONE launch: the two
@@ -542,9 +558,12 @@ __global__ void __launch_bounds__(256, 2) attn_own_keys_kernel(AttnArgs p) {
     if (b < n_tile_wg) {
         attn_tile_body<D>(p, b % p.n_items, b / p.n_items);
     } else {
-        const int n_dec_wg = (p.n_items_b + 3) / 4;
-        attn_decode_body<D>(p, p.items_b, p.n_items_b, (b - n_tile_wg) % n_dec_wg, (b - n_tile_wg) / n_dec_wg);
+        attn_decode_body<D>(p, p.items_b, p.n_items_b, b - n_tile_wg);
     }
+}
+
+inline int decode_wgs(const AttnArgs& p, int n_items) {
+    return p.dec_by_head ? n_items * (p.n_kv >> 2) : (n_items + 3) / 4 * p.n_kv;
 }
 
 template <int D>
@@ -571,9 +590,9 @@ hipError_t launch_d(const AttnArgs& base, const AttnItem* items, int32_t n_items
     p.items_b = items_b;
     p.n_items_b = n_items_b;
     if (items_b)
-        attn_own_keys_kernel<D><<<dim3(n_items * p.n_kv + (n_items_b + 3) / 4 * p.n_kv), dim3(256), both_smem, s>>>(p);
+        attn_own_keys_kernel<D><<<dim3(n_items * p.n_kv + decode_wgs(p, n_items_b)), dim3(256), both_smem, s>>>(p);
     else if (decode)
-        attn_decode_kernel<D><<<dim3((n_items + 3) / 4, p.n_kv), dim3(256), dec_smem, s>>>(p);
+        attn_decode_kernel<D><<<dim3(decode_wgs(p, n_items)), dim3(256), dec_smem, s>>>(p);
     else
         attn_tile_kernel<D><<<dim3(n_items, p.n_kv), dim3(256), tile_smem, s>>>(p);
     return hipGetLastError();
@@ -601,6 +620,7 @@ hipError_t launch_attention(const BatchDev& b, const relserve_layer& L, const vo
     p.n_q = L.cfg.n_q_heads;
     p.n_kv = L.cfg.n_kv_heads;
     p.group = L.group;
+    p.dec_by_head = L.cfg.n_kv_heads % 4 == 0 ? 1 : 0;
     p.scale_log2 = (float)(1.4426950408889634 / sqrt((double)L.cfg.head_dim));
     const bool d128 = L.cfg.head_dim == 128;
     hipError_t e = hipSuccess;

@@ -54,16 +54,15 @@ int32_t relserve_duration_predict(const relserve_duration_model* model, double u
 // group, tokens held on the GPU since the last decode-to-completion.
 namespace {
 struct PemWalk {
-    const relserve_pem_limits& lim;
     int32_t out_len;
-    int32_t* prefill_utok;   // optional outputs
+    int32_t* prefill_utok;                 // optional outputs
     int32_t* group_req;
+    const relserve_duration_model* mp;     // optional: the lines to sum
+    const relserve_duration_model* md;
     int32_t n_prefill = 0, n_groups = 0;
     int64_t p_tok = 0, accum = 0;
     int32_t p_req = 0, d_req = 0;
     double seconds = 0;
-    const relserve_duration_model* mp;
-    const relserve_duration_model* md;
 
     void close_prefill() {
         if (p_req > 0) {
@@ -120,9 +119,7 @@ int32_t relserve_batch_decompose(const int32_t* utok, const uint8_t* decodes, in
                                  const relserve_pem_limits* limits, int32_t* prefill_batch_of, int32_t* decode_group_of,
                                  int32_t* prefill_utok, int32_t* n_prefill, int32_t* group_req, int32_t* n_groups) {
     if (!limits || !n_prefill || !n_groups) return RELSERVE_ERR_NULL_POINTER;
-    PemWalk w{*limits, out_len, prefill_utok, group_req};
-    w.mp = nullptr;
-    w.md = nullptr;
+    PemWalk w{out_len, prefill_utok, group_req, nullptr, nullptr};
     if (int32_t rc = pem_walk(utok, decodes, n, out_len, limits, prefill_batch_of, decode_group_of, w)) return rc;
     *n_prefill = w.n_prefill;
     *n_groups = w.n_groups;
@@ -133,9 +130,7 @@ int32_t relserve_pem_estimate(const int32_t* utok, const uint8_t* decodes, int32
                               const relserve_pem_limits* limits, const relserve_duration_model* prefill,
                               const relserve_duration_model* decode, double* seconds) {
     if (!limits || !prefill || !decode || !seconds) return RELSERVE_ERR_NULL_POINTER;
-    PemWalk w{*limits, out_len, nullptr, nullptr};
-    w.mp = prefill;
-    w.md = decode;
+    PemWalk w{out_len, nullptr, nullptr, prefill, decode};
     if (int32_t rc = pem_walk(utok, decodes, n, out_len, limits, nullptr, nullptr, w)) return rc;
     *seconds = w.seconds;
     return RELSERVE_OK;

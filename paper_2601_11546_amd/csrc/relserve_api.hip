@@ -152,8 +152,6 @@ int32_t relserve::expand_batch(const relserve_layer_config& cfg, const relserve_
     if (build_items) {
         const int32_t group = cfg.n_q_heads / cfg.n_kv_heads;
         const int32_t tile_tok = ATTN_BLOCK_M / group;    // tokens per row-tiled item (rows past tile_tok * group stay idle)
-        const int32_t split_tok = std::max(1, ATTN_SPLIT_ROWS / group);
-        (void)split_tok;
         // a prefix is handled jointly when at least two requests of the batch carry it
         std::vector<uint8_t> joint(d.num_prefixes, 0);
         for (int32_t p = 0; p < d.num_prefixes; ++p)

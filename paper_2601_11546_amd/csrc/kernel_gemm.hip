@@ -450,13 +450,14 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_dma_kernel(GemmArgs p) {
             n = min(tile_n * BN + lr, p.N - 1);
         }
         // row-major: row n starts at n * K; packed: block n / 256 holds, k slice after k slice, 256 rows of 128 bytes
+        // (a 32-wide stage is the first or the second half of every row of a slice)
         w_voff[j] = p.w_packed ? (uint32_t)(n >> 8) * (uint32_t)K * 512u + (uint32_t)(n & 255) * 128u + chunk * 16
                                : ((uint32_t)n * (uint32_t)K + chunk * 8) * 2;
     }
     const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem;
     auto issue_stage = [&](int stage, int k0) {
         const char* abase = reinterpret_cast<const char*>(p.a) + (size_t)k0 * 2;
-        const char* wbase = reinterpret_cast<const char*>(p.w) + (p.w_packed ? (size_t)k0 * 512 : (size_t)k0 * 2);
+        const char* wbase = reinterpret_cast<const char*>(p.w) + (p.w_packed ? (size_t)(k0 >> 6) * 32768 + (size_t)(k0 & 63) * 2 : (size_t)k0 * 2);
         const uint32_t la = lds0 + stage * STAGE + wave * 1024;
 #pragma unroll
         for (int j = 0; j < A_IT; ++j) dma16(abase, a_voff[j], la + j * (NW * 1024));
@@ -528,7 +529,7 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_dma_kernel(GemmArgs p) {
         // weights first: they come from further away (HBM) than the activations (L2)
         const uint32_t la = lds0 + stage * STAGE + wave * 1024;
         if (i < W_IT)
-            dma16(reinterpret_cast<const char*>(p.w) + (p.w_packed ? (size_t)k0 * 512 : (size_t)k0 * 2), w_voff[i],
+            dma16(reinterpret_cast<const char*>(p.w) + (p.w_packed ? (size_t)(k0 >> 6) * 32768 + (size_t)(k0 & 63) * 2 : (size_t)k0 * 2), w_voff[i],
                   la + A_BYTES + i * (NW * 1024));
         else
             dma16(reinterpret_cast<const char*>(p.a) + (size_t)k0 * 2, a_voff[i - W_IT], la + (i - W_IT) * (NW * 1024));
@@ -813,12 +814,14 @@ int choose_splits(int T, int N, int K, int BM, int BN = 256) {
 // tiles fill the CUs without any k split (the gate/up projection), so no slabs and no finish kernel.
 template <int BM, int EPI, int D = 0, int BN = 128>
 hipError_t launch_skinny_whole(GemmArgs p, hipStream_t s) {
-    constexpr int NS = BM + BN <= 192 ? 6 : BM + BN <= 256 ? 4 : 3;
-    constexpr int smem = NS * (BM + BN) * 64 * 2;
+    // (256 x 256 tiles have room for two 64-k stages only; four 32-k stages measured no faster)
+    constexpr int BKD = 64;
+    constexpr int NS = BM + BN <= 192 ? 6 : BM + BN <= 256 ? 4 : BM + BN <= 384 ? 3 : 2;
+    constexpr int smem = NS * (BM + BN) * BKD * 2;
     static_assert(smem <= 160 * 1024, "ring exceeds the LDS");
     static bool attr_done = false;
     if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_dma_kernel<BM, BN, EPI, D, 64, NS>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_dma_kernel<BM, BN, EPI, D, BKD, NS>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, smem);
         if (e != hipSuccess) return e;
         attr_done = true;
@@ -827,7 +830,7 @@ hipError_t launch_skinny_whole(GemmArgs p, hipStream_t s) {
     p.tiles_n = EPI == EPI_SWIGLU ? (p.n_half + BN / 2 - 1) / (BN / 2) : (p.N + BN - 1) / BN;
     p.tail_tiles = 0;
     p.tail_splits = 1;
-    gemm_dma_kernel<BM, BN, EPI, D, 64, NS><<<dim3(p.tiles_m * p.tiles_n), dim3(256), smem, s>>>(p);
+    gemm_dma_kernel<BM, BN, EPI, D, BKD, NS><<<dim3(p.tiles_m * p.tiles_n), dim3(256), smem, s>>>(p);
     return hipGetLastError();
 }
 
@@ -847,7 +850,13 @@ hipError_t launch_skinny(const GemmArgs& p, hipStream_t s) {
     }
     // two token tiles: 256-feature tiles; a projection wide enough to need no k split runs the fused kernel
     const int splits = choose_splits(p.T, p.N, p.K, 128);
-    if (splits == 1) return launch_skinny_whole<128, EPI, D, 256>(p, s);
+    if (splits == 1) {
+        // wide enough that one 256 x 256 tile per CU is (nearly) a full round: one token tile instead of two
+        // halves the weight fragments read from LDS per flop
+        const int tiles256 = EPI == EPI_SWIGLU ? (p.n_half + 127) / 128 : (p.N + 255) / 256;
+        if (p.T > 192 && tiles256 >= 200 && tiles256 <= 256) return launch_skinny_whole<256, EPI, D, 256>(p, s);
+        return launch_skinny_whole<128, EPI, D, 256>(p, s);
+    }
     return launch_split<128, EPI, D>(p, splits, s);
 }
 

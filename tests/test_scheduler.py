@@ -99,7 +99,7 @@ def test_serving_loop_executes_its_batches_on_the_gpu(sch, policy):
     """A short trace served for real: every batch goes through relserve_batch_prepare (which validates block tables,
     prefix groups and write slots) and relserve_model_step; the page pool is whole again at the end; and a request
     that read its relQuery's template from pages shared with (and written by) another request gets the logits of a
-    private recomputation."""
+    private recomputation and the CPU oracle's for the same prompt."""
     from paper_2601_11546_amd import serving
     from paper_2601_11546_amd import workloads as W
     shape, vocab = W.TINY_GQA, 512
@@ -130,6 +130,24 @@ def test_serving_loop_executes_its_batches_on_the_gpu(sch, policy):
     assert checked == 14
     worker.cache.check()
     assert all(r == 0 for r in worker.cache.refs)
+    # and the oracle, run privately on the same prompts with the same weights, gives those logits: the writer of a
+    # template, a reader within its relQuery, and a reader from another relQuery
+    from oracle import relserve_oracle
+    orc = relserve_oracle.load("f32")
+    import torch
+    bits = lambda t: t.detach().cpu().contiguous().view(torch.int16).numpy().view(np.uint16)
+    model = {"embedding": bits(worker.model["embedding"]), "w_final_norm": bits(worker.model["w_final_norm"]),
+             "w_lm_head": bits(worker.model["w_lm_head"]),
+             "layers": [{k: bits(v) for k, v in w.items()} for w in worker.model["layers"]]}
+    for q, req in ((trace[0], 0), (trace[0], trace[0].n - 1), (trace[6], 1)):
+        ids = worker.prompt(q, req)
+        b = W.build_batch(shape, [len(ids)], [len(ids)], seed=1)
+        pools = [W.make_cache(shape, b.num_pages, 0, fill=False) for _ in range(2)]
+        want, _ = orc.model_step(shape, b, model, ids, [k for k, _ in pools], [v for _, v in pools])
+        got = worker.logits[(q.rid, req)]
+        scale = float(np.sqrt(np.mean(want[0].astype(np.float64) ** 2)))
+        rel = float(np.linalg.norm(got - want[0]) / np.linalg.norm(want[0]))
+        assert rel <= 1e-2 and np.abs(got - want[0]).max() <= 6e-2 * scale, (q.rid, req, rel)
 
 
 def test_sampled_miss_ratio_estimates_uncached_tokens(sch):

@@ -400,11 +400,13 @@ def test_full_size_decode_only_13b(rs, oracle):
     _sampled_parity(rs, oracle, wl, [0, 5, 64, 127])
 
 
-@pytest.mark.parametrize("shape,n_dec,packed", [(W.LLAMA_13B, 40, True), (W.LLAMA_13B, 40, False), (W.LLAMA_70B, 100, True)],
-                         ids=["13b-40", "13b-40-rowmajor", "70b-100"])
+@pytest.mark.parametrize("shape,n_dec,packed", [(W.LLAMA_13B, 40, True), (W.LLAMA_13B, 40, False), (W.LLAMA_70B, 100, True),
+                                                (W.LLAMA_13B, 200, True), (W.LLAMA_70B, 150, True), (W.LLAMA_70B, 150, False)],
+                         ids=["13b-40", "13b-40-rowmajor", "70b-100", "13b-200", "70b-150", "70b-150-rowmajor"])
 def test_full_size_small_decode_batches(rs, oracle, shape, n_dec, packed):
     """Up to 128 decode rows on the full layer shapes: the gate/up projection has enough 128-feature tiles to
-    run the fused kernel unsplit (64- and 128-token tiles, deep ring); the others split k on 128-feature tiles."""
+    run the fused kernel unsplit (64- and 128-token tiles, deep ring); the others split k on 128-feature tiles.
+    129 to 256 rows: two 128-token tiles, the gate/up projection unsplit on 128 x 256 tiles with a three-stage ring."""
     rng = np.random.default_rng(n_dec)
     ctx = rng.integers(40, 400, n_dec)
     b = W.build_batch(shape, np.ones(n_dec, np.int64), ctx, seed=n_dec, name=f"small_decode_{n_dec}")

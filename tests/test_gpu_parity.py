@@ -414,6 +414,13 @@ def test_full_size_small_decode_batches(rs, oracle, shape, n_dec, packed):
     _sampled_parity(rs, oracle, wl, [0, 1, n_dec // 2, n_dec - 1], packed=packed)
 
 
+def test_full_size_small_mixed_batch_13b(rs, oracle):
+    """100 decode rows and a 64-token prefill chunk (T = 164): the weight-streaming GEMM paths together with the
+    fused own-keys attention launch."""
+    wl = W.workload_decode_plus_chunk_13b(64, n_dec=100, ctx=300)
+    _sampled_parity(rs, oracle, wl, [0, 50, 99, 100], packed=True)
+
+
 def test_skinny_batches_of_every_token_tile_count(rs, oracle):
     """1, 20, 33, 64, 65 and 128 decode tokens: every token-tile count of the weight-streaming GEMM,
     on a layer wide enough for several feature tiles and k splits."""

@@ -167,8 +167,10 @@ int32_t relserve_kv_append(const relserve_layer* layer, const relserve_batch* ba
 
 /* The whole layer step (Eq. 3-5 and the wiring listed at the top).  x, y:
  * device [T, H] bf16; y may alias x.  workspace: device, 256-byte aligned,
- * at least relserve_workspace_bytes(layer, T).  The cache pools are updated
- * in place at the batch's slots and nowhere else. */
+ * at least relserve_workspace_bytes(layer, T); pure scratch: its contents on
+ * entry do not matter and nothing is kept in it between calls, so calls that
+ * may overlap (other streams) need workspaces of their own.  The cache pools
+ * are updated in place at the batch's slots and nowhere else. */
 int32_t relserve_layer_step(const relserve_layer* layer, const relserve_batch* batch,
                             const relserve_layer_weights* weights,
                             const void* x, void* y, relserve_kv_cache cache,

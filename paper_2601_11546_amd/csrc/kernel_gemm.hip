@@ -894,7 +894,8 @@ hipError_t launch_cfg(const GemmArgs& base, hipStream_t s, const Plan& plan = Pl
     p.tiles_m = (p.T + BM - 1) / BM;
     p.tiles_n = EPI == EPI_SWIGLU ? (p.n_half + BN / 2 - 1) / (BN / 2) : (p.N + BN - 1) / BN;
     constexpr int smem = 2 * (BM + BN) * BK * 2;
-    constexpr int DMA_BK = RELSERVE_DMA_BK, DMA_NS = RELSERVE_DMA_NS;
+    // 128 x 256 tiles are one workgroup per CU either way, so they take the third stage that fits (144 KB)
+    constexpr int DMA_BK = RELSERVE_DMA_BK, DMA_NS = (BM == 128 && BN == 256 && RELSERVE_DMA_NS == 2) ? 3 : RELSERVE_DMA_NS;
     constexpr int dma_smem = DMA_NS * (BM + BN) * DMA_BK * 2;
     static bool attr_done = false;
     if (!attr_done) {

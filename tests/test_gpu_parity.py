@@ -414,6 +414,28 @@ def test_full_size_small_decode_batches(rs, oracle, shape, n_dec, packed):
     _sampled_parity(rs, oracle, wl, [0, 1, n_dec // 2, n_dec - 1], packed=packed)
 
 
+@pytest.mark.parametrize("make", [W.workload_relquery_13b, lambda: W.workload_decode_plus_chunk_13b(0),
+                                  lambda: W.workload_decode_plus_chunk_13b(512), W.workload_prefill_only_13b],
+                         ids=["relquery", "decode128", "decode128+chunk512", "prefill8192"])
+def test_layer_step_is_bitwise_repeatable(rs, make):
+    """No kernel of the step accumulates through atomics or in arrival order (k splits go through slabs that are added
+    in split order): two runs of the same step give the same bits, in the output and in the appended cache rows."""
+    wl = make()
+    shape, b = wl.shape, wl.batch
+    print(f"[case] repeatable {wl.name}: T={b.T}", flush=True)
+    weights = wl.weights()
+    x = W.make_activations(b.T, shape.hidden, wl.seed)
+    outs = []
+    for _ in range(2):
+        kp, vp = W.make_cache(shape, b.num_pages, wl.seed)
+        gl = GpuLayer(rs, shape, weights, kp, vp, b.T, packed=True)
+        y = host_bits(gl.step(b, x))
+        outs.append((y, host_bits(gl.k_pages), host_bits(gl.v_pages)))
+        del gl
+    for a, c in zip(outs[0], outs[1]):
+        assert np.array_equal(a, c)
+
+
 def test_full_size_small_mixed_batch_13b(rs, oracle):
     """100 decode rows and a 64-token prefill chunk (T = 164): the weight-streaming GEMM paths together with the
     fused own-keys attention launch."""

@@ -70,7 +70,7 @@ class Engine:
         self.mp, self.md, self.lim, self.policy = prefill_model, decode_model, limits, policy
         self.cache_tokens, self.threshold, self.execute = cache_tokens, starvation_threshold, execute
         self.sample_size = sample_size               # Eq. 11: requests sampled per relQuery for the miss ratio (0 = count exactly)
-        self.cache: OrderedDict = OrderedDict()      # rid -> template tokens, in LRU order
+        self.cache: OrderedDict = OrderedDict()      # template id -> template tokens, in LRU order
         self.now = 0.0
         self.log = []                                # (time, kind, rid or -1, requests, tokens)
 

@@ -103,12 +103,14 @@ __device__ __forceinline__ void tile_coords(int t, int tiles_m, int tiles_n, int
 
 // Epilogue shared by both GEMM kernels: register r of accumulator tile (tn, tm) holds feature
 // 32 tn + 8 (r / 4) + 4 g + r % 4 of the wave's feature range and token 32 tm + l32 of its token range.
-template <int BM, int BN, int EPI, int D, int WGM = 2, int WGN = 2>
-__device__ __forceinline__ void gemm_epilogue(const f32x16_t (&acc)[BN / (32 * WGN)][BM / (32 * WGM)], const GemmArgs& p,
-                                              int tile_m, int tile_n, int wm, int wn, int l32, int g, int tm_only = -1,
+// TMX of the wave's BM / (32 WGM) rows of accumulator tiles are held in acc, starting at row tm_base (the GEMM kernels
+// hold all of them; the tail finish kernel one per workgroup, which lets several workgroups share a CU).
+template <int BM, int BN, int EPI, int D, int WGM = 2, int WGN = 2, int TMX = BM / (32 * WGM)>
+__device__ __forceinline__ void gemm_epilogue(const f32x16_t (&acc)[BN / (32 * WGN)][TMX], const GemmArgs& p,
+                                              int tile_m, int tile_n, int wm, int wn, int l32, int g, int tm_base = 0,
                                               int split = 0) {
-    constexpr int TM = BM / (32 * WGM), TN = BN / (32 * WGN);
-    const int t0 = tile_m * BM;
+    constexpr int TM = TMX, TN = BN / (32 * WGN);
+    const int t0 = tile_m * BM + 32 * tm_base;
     if (EPI == EPI_SLAB) {
         // Split-K partial sums -> this split's slab.  These tiles were accumulated with the operands
         // swapped: register r holds token 8 (r / 4) + 4 g + r % 4 and feature l32, so one store
@@ -130,7 +132,6 @@ __device__ __forceinline__ void gemm_epilogue(const f32x16_t (&acc)[BN / (32 * W
     }
 #pragma unroll
     for (int tm = 0; tm < TM; ++tm) {
-        if (tm_only >= 0 && tm != tm_only) continue;   // the tail finish kernel: one row of accumulator tiles per workgroup
         const int t = t0 + wm * (BM / WGM) + 32 * tm + l32;
         if (t >= p.T) continue;
         if (EPI == EPI_SLAB) {
@@ -639,7 +640,7 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_dma_kernel(GemmArgs p) {
                 }
         return;
     }
-    gemm_epilogue<BM, BN, EPI, D, WGM, WGN>(acc, p, tile_m, tile_n, wm, wn, l32, g, -1, split);
+    gemm_epilogue<BM, BN, EPI, D, WGM, WGN>(acc, p, tile_m, tile_n, wm, wn, l32, g, 0, split);
 }
 
 // Second half of a tail split: workgroup (tail tile, row tm of accumulator tiles) has the thread layout of
@@ -656,32 +657,26 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_tail_finish_kernel(GemmAr
     const int tail_idx = blockIdx.x / TM, tm_sel = blockIdx.x % TM;
     int tile_m, tile_n;
     tile_coords(p.tiles_m * p.tiles_n - p.tail_tiles + tail_idx, p.tiles_m, p.tiles_n, tile_m, tile_n);
-    f32x16_t acc[TN][TM];
+    f32x16_t acc[TN][1];
 #pragma unroll
     for (int tn = 0; tn < TN; ++tn)
 #pragma unroll
-        for (int tm = 0; tm < TM; ++tm)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[tn][tm][r] = 0.f;
+        for (int r = 0; r < 16; ++r) acc[tn][0][r] = 0.f;
     for (int q = 0; q < p.tail_splits; ++q) {
         const vec4_t* src = reinterpret_cast<const vec4_t*>(p.tail_buf) + ((size_t)q * p.tail_tiles + tail_idx) * AREA4 + tid;
+        vec4_t v[TN][4];
 #pragma unroll
-        for (int tm = 0; tm < TM; ++tm) {
-            if (tm != tm_sel) continue;
-            vec4_t v[TN][4];
+        for (int tn = 0; tn < TN; ++tn)
 #pragma unroll
-            for (int tn = 0; tn < TN; ++tn)
+            for (int c = 0; c < 4; ++c) v[tn][c] = src[((tn * TM + tm_sel) * 4 + c) * NT];
 #pragma unroll
-                for (int c = 0; c < 4; ++c) v[tn][c] = src[((tn * TM + tm) * 4 + c) * NT];
+        for (int tn = 0; tn < TN; ++tn)
 #pragma unroll
-            for (int tn = 0; tn < TN; ++tn)
+            for (int c = 0; c < 4; ++c)
 #pragma unroll
-                for (int c = 0; c < 4; ++c)
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) acc[tn][tm][4 * c + e] += v[tn][c][e];
-        }
+                for (int e = 0; e < 4; ++e) acc[tn][0][4 * c + e] += v[tn][c][e];
     }
-    gemm_epilogue<BM, BN, EPI, D, WGM, WGN>(acc, p, tile_m, tile_n, wm, wn, l32, g, tm_sel);
+    gemm_epilogue<BM, BN, EPI, D, WGM, WGN, 1>(acc, p, tile_m, tile_n, wm, wn, l32, g, tm_sel);
 }
 
 // ------------------------------------------------------------------------------------------

@@ -31,6 +31,7 @@ def build_workload(name: str):
     from paper_2601_11546_amd import workloads as W
     table = {
         "relquery_13b": W.workload_relquery_13b,                       # configs[1]: the headline workload
+        "relquery_decode_13b": lambda: W.workload_relquery_13b(n_rows=256, n_prefill=0),   # a pure decode batch of one relQuery
         "relquery_32b": W.workload_relquery_32b,                       # the same batch on the 32B (5 q heads per kv head) shape
         "relquery_70b_tp4_share": lambda: W.workload_tp_share("70b_tp4"),   # one GPU's share of the 70B layer at TP = 4
         "relquery_32b_tp2_share": lambda: W.workload_tp_share("32b_tp2"),   # one GPU's share of the 32B layer at TP = 2

@@ -274,6 +274,18 @@ def workload_tiny_prefix(seed: int = 1001, shape: LayerShape = TINY) -> Workload
     return Workload("tiny_prefix", shape, b, seed)
 
 
+def workload_tiny_long_prefixes(seed: int = 1011, shape: LayerShape = TINY) -> Workload:
+    """Test-only: two shared prefixes of very different lengths (33 and 6 pages) under few rows, so that a joint prefix
+    pass split by keys sees full, ragged and empty key ranges; prefill chunks and decode rows behind both."""
+    P = shape.page_size
+    pa, pb = 33 * P, 6 * P
+    q_len = [23, 1, 1, 9, 1, 1, 1, 30, 1]
+    ctx = [pa + 23, pa + 4, pa + 1, pb + 9, pb + 12, pa + 40, 50, 30, pb + 1]
+    pid = [0, 0, 0, 1, 1, 0, -1, -1, 1]
+    b = build_batch(shape, q_len, ctx, pid, [pa, pb], seed=seed, name="tiny_long_prefixes")
+    return Workload("tiny_long_prefixes", shape, b, seed)
+
+
 def workload_relquery_13b(seed: int = 1001, n_rows: int = 200, n_prefill: int = 16,
                           prefix: int = 512, shape: LayerShape = LLAMA_13B) -> Workload:
     """One relQuery: rows share a template prefix; a few rows prefill their suffix, the rest decode."""

@@ -174,7 +174,7 @@ def test_qkv_rope_append_fused_epilogue(rs, oracle, shape, n_req):
     np.testing.assert_array_equal(gv[mask], vp.reshape(-1, nkv * d)[mask])
 
 
-@pytest.mark.parametrize("make", [W.workload_tiny, W.workload_tiny_prefix])
+@pytest.mark.parametrize("make", [W.workload_tiny, W.workload_tiny_prefix, W.workload_tiny_long_prefixes])
 @pytest.mark.parametrize("shape", [W.TINY, W.TINY_GQA, W.TINY_D128, W.TINY_G5, W.TINY_G3_D128], ids=["mha", "gqa", "d128", "g5", "g3d128"])
 def test_attention_stage(rs, oracle, make, shape):
     b = make(shape=shape).batch
@@ -211,7 +211,7 @@ def _step_case(rs, oracle, wl, cache_seed_off=0):
     return gl, y, res, kp, vp
 
 
-@pytest.mark.parametrize("make", [W.workload_tiny, W.workload_tiny_prefix])
+@pytest.mark.parametrize("make", [W.workload_tiny, W.workload_tiny_prefix, W.workload_tiny_long_prefixes])
 @pytest.mark.parametrize("shape", [W.TINY, W.TINY_GQA, W.TINY_D128, W.TINY_G5, W.TINY_G3_D128], ids=["mha", "gqa", "d128", "g5", "g3d128"])
 def test_layer_step_tiny(rs, oracle, make, shape):
     wl = make(shape=shape)
@@ -414,9 +414,18 @@ def test_full_size_small_decode_batches(rs, oracle, shape, n_dec, packed):
     _sampled_parity(rs, oracle, wl, [0, 1, n_dec // 2, n_dec - 1], packed=packed)
 
 
+@pytest.mark.parametrize("n_rows,n_prefill", [(256, 0), (96, 3)], ids=["256-decode", "93-decode-3-prefill"])
+def test_full_size_relquery_small_batches_13b(rs, oracle, n_rows, n_prefill):
+    """A relQuery batch of few tokens behind a 512-token template: the joint prefix pass has too few token tiles to
+    fill the chip and is split into four key ranges, merged before the rows attend to their own keys."""
+    wl = W.workload_relquery_13b(seed=1012, n_rows=n_rows, n_prefill=n_prefill)
+    _sampled_parity(rs, oracle, wl, [0, 1, 2, n_rows // 2, n_rows - 1], packed=True)
+
+
 @pytest.mark.parametrize("make", [W.workload_relquery_13b, lambda: W.workload_decode_plus_chunk_13b(0),
-                                  lambda: W.workload_decode_plus_chunk_13b(512), W.workload_prefill_only_13b],
-                         ids=["relquery", "decode128", "decode128+chunk512", "prefill8192"])
+                                  lambda: W.workload_decode_plus_chunk_13b(512), W.workload_prefill_only_13b,
+                                  lambda: W.workload_relquery_13b(n_rows=256, n_prefill=0)],
+                         ids=["relquery", "decode128", "decode128+chunk512", "prefill8192", "relquery-decode256"])
 def test_layer_step_is_bitwise_repeatable(rs, make):
     """No kernel of the step accumulates through atomics or in arrival order (k splits go through slabs that are added
     in split order): two runs of the same step give the same bits, in the output and in the appended cache rows."""

@@ -47,8 +47,6 @@ struct AttnArgs {
     int32_t n_items;
     int32_t max_blocks, page_shift, page_mask;
     int32_t q_pitch, n_q, n_kv, group;
-    int64_t part_stride_o, part_stride_ml;   // floats between the partial-state slots of a key-split prefix pass
-    int32_t n_parts, n_prefix_tok;
     int32_t dec_by_head;   // decode workgroups take four adjacent kv heads of one token (n_kv % 4 == 0)
     float scale_log2;  // log2(e) / sqrt(d)
 };
@@ -91,8 +89,8 @@ __device__ __forceinline__ void state_store(const RowState<D>& st, const AttnArg
                                             int64_t row_id, int g) {
     const float l_tot = st.l + __shfl_xor(st.l, 32, 64);
     if (it.flags & ITEM_WRITE_PARTIAL) {
-        if (g == 0) *reinterpret_cast<float2*>(p.part_ml + it.pad1 * p.part_stride_ml + row_id * 2) = make_float2(st.m, l_tot);
-        float* po = p.part_o + it.pad1 * p.part_stride_o + row_id * D + 4 * g;
+        if (g == 0) *reinterpret_cast<float2*>(p.part_ml + row_id * 2) = make_float2(st.m, l_tot);
+        float* po = p.part_o + row_id * D + 4 * g;
 #pragma unroll
         for (int td = 0; td < D / 32; ++td)
 #pragma unroll
@@ -564,33 +562,6 @@ __global__ void __launch_bounds__(256, 2) attn_own_keys_kernel(AttnArgs p) {
     }
 }
 
-// Combines the partial states of a key-split joint prefix pass into slot 0: for every row, with m the largest of
-// the slots' running maxima (log2 domain), o = sum_s o_s 2^(m_s - m) and l likewise.  One thread per four values.
-template <int D>
-__global__ void __launch_bounds__(256) attn_merge_parts_kernel(AttnArgs p) {
-    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    constexpr int QD = D / 4;
-    if (i >= (int64_t)p.n_prefix_tok * p.n_q * QD) return;
-    const int c = (int)(i % QD) * 4;
-    const int64_t r = i / QD;
-    const int64_t row_id = (int64_t)p.attn_tok[r / p.n_q] * p.n_q + (r % p.n_q);
-    float m = -INFINITY;
-    for (int s = 0; s < p.n_parts; ++s) m = fmaxf(m, p.part_ml[s * p.part_stride_ml + row_id * 2]);
-    float4 o = make_float4(0.f, 0.f, 0.f, 0.f);
-    float l = 0.f;
-    for (int s = 0; s < p.n_parts; ++s) {
-        const float ms = p.part_ml[s * p.part_stride_ml + row_id * 2];
-        const float w = ms == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(ms - m);
-        const float4 v = *reinterpret_cast<const float4*>(p.part_o + s * p.part_stride_o + row_id * D + c);
-        o.x += w * v.x; o.y += w * v.y; o.z += w * v.z; o.w += w * v.w;
-        l += w * p.part_ml[s * p.part_stride_ml + row_id * 2 + 1];
-    }
-    // slot 0 of (m, l) is rewritten by the thread of the row's LAST quad only after every thread of the row has
-    // read it: the rows' quads sit in one wave (QD <= 32 consecutive threads), whose loads above precede this store
-    *reinterpret_cast<float4*>(p.part_o + row_id * D + c) = o;
-    if (c == D - 4) *reinterpret_cast<float2*>(p.part_ml + row_id * 2) = make_float2(m, l);
-}
-
 inline int decode_wgs(const AttnArgs& p, int n_items) {
     return p.dec_by_head ? n_items * (p.n_kv >> 2) : (n_items + 3) / 4 * p.n_kv;
 }
@@ -659,18 +630,7 @@ hipError_t launch_attention(const BatchDev& b, const relserve_layer& L, const vo
         e = d128 ? launch_d<128>(p, items, n, items_b, n_b, decode, s) : launch_d<64>(p, items, n, items_b, n_b, decode, s);
         profile_mark(prof, slot, s, false);
     };
-    p.n_parts = b.n_prefix_parts;
-    p.n_prefix_tok = b.n_prefix_tok;
-    p.part_stride_o = (int64_t)b.T * L.q_dim;             // slot s of the partial states starts s * T rows in
-    p.part_stride_ml = (int64_t)b.T * L.cfg.n_q_heads * 2;
     launch(3, b.items_prefix, b.n_items_prefix, nullptr, 0, false);
-    if (e == hipSuccess && b.n_items_prefix > 0 && b.n_prefix_parts > 1) {
-        const int64_t n = (int64_t)b.n_prefix_tok * L.q_dim / 4;
-        const dim3 grid((unsigned)((n + 255) / 256));
-        if (d128) attn_merge_parts_kernel<128><<<grid, dim3(256), 0, s>>>(p);
-        else attn_merge_parts_kernel<64><<<grid, dim3(256), 0, s>>>(p);
-        e = hipGetLastError();
-    }
     if (b.n_items_tile > 0 && b.n_items_split > 0) {   // both kinds of rows: one launch for their own keys
         launch(2, b.items_tile, b.n_items_tile, b.items_split, b.n_items_split, false);
     } else {

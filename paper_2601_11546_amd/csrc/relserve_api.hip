@@ -46,11 +46,8 @@ Workspace carve(const relserve_layer& L, int64_t T, void* base) {
     w.attn = take((size_t)T * L.q_dim * 2);
     w.x1 = take((size_t)T * c.hidden * 4);
     w.act = take((size_t)T * c.mlp_dim * 2);
-    // partial attention states: one slot, or PREFIX_SPLIT_MAX slots for the small batches that split their prefix
-    // passes by keys (sized so that the total never shrinks as T grows)
-    const size_t part_rows = std::max<size_t>((size_t)T, (size_t)std::min<int64_t>(T, PREFIX_SPLIT_MAX_T) * PREFIX_SPLIT_MAX);
-    w.part_o = reinterpret_cast<float*>(take(part_rows * L.q_dim * 4));
-    w.part_ml = reinterpret_cast<float*>(take(part_rows * c.n_q_heads * 2 * 4));
+    w.part_o = reinterpret_cast<float*>(take((size_t)T * L.q_dim * 4));
+    w.part_ml = reinterpret_cast<float*>(take((size_t)T * c.n_q_heads * 2 * 4));
     w.accum_floats = (size_t)gemm_scratch_floats(T, std::max({L.qkv_dim, 2 * c.mlp_dim, c.hidden}));
     w.accum = reinterpret_cast<float*>(take(w.accum_floats * 4));
     w.total = off;
@@ -159,25 +156,6 @@ int32_t relserve::expand_batch(const relserve_layer_config& cfg, const relserve_
         std::vector<uint8_t> joint(d.num_prefixes, 0);
         for (int32_t p = 0; p < d.num_prefixes; ++p)
             joint[p] = (members[p] >= 2 && d.prefix_len[p] > 0);
-        // A small batch gives the joint passes few workgroups (tokens / tile_tok per kv head): then every prefix
-        // is cut into up to PREFIX_SPLIT_MAX key ranges, each its own item with its own partial-state slot, and a
-        // merge kernel combines the slots before the rows continue over their own keys.
-        int32_t parts = 1;
-        if (T <= PREFIX_SPLIT_MAX_T) {
-            int64_t wgs = 0;
-            int32_t longest = 0;
-            for (int32_t p = 0; p < d.num_prefixes; ++p) {
-                if (!joint[p]) continue;
-                int32_t n = 0;
-                for (int32_t r = 0; r < B; ++r)
-                    if (d.prefix_id[r] == p) n += d.q_start[r + 1] - d.q_start[r];
-                wgs += (int64_t)((n + tile_tok - 1) / tile_tok) * cfg.n_kv_heads;
-                longest = std::max(longest, d.prefix_len[p]);
-            }
-            if (wgs > 0 && wgs < 256)
-                parts = (int32_t)std::max<int64_t>(1, std::min<int64_t>({PREFIX_SPLIT_MAX, longest / 128, 512 / wgs}));
-        }
-        hb.n_prefix_parts = parts;
         for (int32_t p = 0; p < d.num_prefixes; ++p) {
             if (!joint[p]) continue;
             ++hb.n_groups;
@@ -186,22 +164,17 @@ int32_t relserve::expand_batch(const relserve_layer_config& cfg, const relserve_
                 if (d.prefix_id[r] == p)
                     for (int32_t t = d.q_start[r]; t < d.q_start[r + 1]; ++t) hb.attn_tok.push_back(t);
             const int32_t n = (int32_t)hb.attn_tok.size() - start;
-            const int32_t pl = d.prefix_len[p];
-            const int32_t chunk = ((pl + parts - 1) / parts + 63) / 64 * 64;   // whole 64-key blocks
-            for (int32_t o = 0; o < n; o += tile_tok)
-                for (int32_t s = 0; s < parts; ++s) {
-                    AttnItem it{};
-                    it.tok_off = start + o;
-                    it.n_tok = std::min(tile_tok, n - o);
-                    it.bt_req = first_member[p];
-                    it.key_begin = std::min(s * chunk, pl);
-                    it.key_end = std::min((s + 1) * chunk, pl);   // an empty range stores the neutral state
-                    it.flags = ITEM_WRITE_PARTIAL;
-                    it.pad1 = s;
-                    hb.items_prefix.push_back(it);
-                }
+            for (int32_t o = 0; o < n; o += tile_tok) {
+                AttnItem it{};
+                it.tok_off = start + o;
+                it.n_tok = std::min(tile_tok, n - o);
+                it.bt_req = first_member[p];
+                it.key_begin = 0;
+                it.key_end = d.prefix_len[p];
+                it.flags = ITEM_WRITE_PARTIAL;
+                hb.items_prefix.push_back(it);
+            }
         }
-        hb.n_prefix_tok = (int32_t)hb.attn_tok.size();
         for (int32_t r = 0; r < B; ++r) {
             const int32_t q_len = d.q_start[r + 1] - d.q_start[r];
             const int32_t pid = d.prefix_id ? d.prefix_id[r] : -1;
@@ -412,8 +385,6 @@ int32_t relserve_batch_prepare(const relserve_layer* L, const relserve_batch_des
     dv.items_split = reinterpret_cast<AttnItem*>(base + o_is);
     dv.rope_cs = reinterpret_cast<float2*>(base + o_cs);
     dv.n_items_prefix = (int32_t)hb.items_prefix.size();
-    dv.n_prefix_parts = hb.n_prefix_parts;
-    dv.n_prefix_tok = hb.n_prefix_tok;
     dv.n_items_tile = (int32_t)hb.items_tile.size();
     dv.n_items_split = (int32_t)hb.items_split.size();
     b->info = relserve_batch_info{T, B, hb.n_decode, hb.n_prefill, hb.n_groups,

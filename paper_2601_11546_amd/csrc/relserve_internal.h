@@ -28,7 +28,7 @@ struct AttnItem {
     int32_t key_end;    // one past the last key position any row may see
     int32_t flags;
     int32_t pad0;       // decode items: the query token
-    int32_t pad1;       // joint prefix items: which of the prefix's key ranges (0 .. n_prefix_parts - 1)
+    int32_t pad1;
 };
 
 // Device-side view of a prepared batch (all pointers into one device allocation).
@@ -45,8 +45,6 @@ struct BatchDev {
     const AttnItem* items_tile;    // row-tiled passes (prefill rows)
     const AttnItem* items_split;   // key-split passes (decode rows)
     int32_t n_items_prefix, n_items_tile, n_items_split;
-    int32_t n_prefix_parts;   // key ranges the joint prefix passes are split into (partial states merged afterwards)
-    int32_t n_prefix_tok;     // attn_tok[0, n_prefix_tok) are the tokens of the joint prefix passes
 };
 
 }  // namespace relserve
@@ -82,15 +80,12 @@ struct HostBatch {
     std::vector<int32_t> attn_tok;
     std::vector<AttnItem> items_prefix, items_tile, items_split;
     int32_t n_decode = 0, n_prefill = 0, n_groups = 0;
-    int32_t n_prefix_parts = 1, n_prefix_tok = 0;
 };
 int32_t expand_batch(const relserve_layer_config& cfg, const relserve_batch_desc& d, bool build_items,
                      HostBatch* out);
 
 // Rows of queries one attention workgroup covers (4 waves x 32 MFMA columns).
 constexpr int ATTN_BLOCK_M = 128;
-constexpr int PREFIX_SPLIT_MAX_T = 1024;   // batches up to this many tokens may split their joint prefix passes by keys
-constexpr int PREFIX_SPLIT_MAX = 4;         // ... into at most this many ranges (each with its own partial-state slot)
 constexpr int SKINNY_MAX_T = 256;      // batches up to this many tokens take the split-K GEMM path
 constexpr int64_t GEMM_TAIL_FLOATS = 256 * 65536;      // GEMM scratch at T > 256: partial tiles of one round of split 256 x 256 tiles
 constexpr int ATTN_SPLIT_ROWS = 16;   // query heads per kv head the decode kernel's 16-column MFMA holds

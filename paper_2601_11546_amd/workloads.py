@@ -275,8 +275,8 @@ def workload_tiny_prefix(seed: int = 1001, shape: LayerShape = TINY) -> Workload
 
 
 def workload_tiny_long_prefixes(seed: int = 1011, shape: LayerShape = TINY) -> Workload:
-    """Test-only: two shared prefixes of very different lengths (33 and 6 pages) under few rows, so that a joint prefix
-    pass split by keys sees full, ragged and empty key ranges; prefill chunks and decode rows behind both."""
+    """Test-only: two shared prefixes of very different lengths (33 and 6 pages: many key blocks with a ragged last
+    one) under few rows; prefill chunks and decode rows behind both."""
     P = shape.page_size
     pa, pb = 33 * P, 6 * P
     q_len = [23, 1, 1, 9, 1, 1, 1, 30, 1]

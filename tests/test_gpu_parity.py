@@ -416,8 +416,8 @@ def test_full_size_small_decode_batches(rs, oracle, shape, n_dec, packed):
 
 @pytest.mark.parametrize("n_rows,n_prefill", [(256, 0), (96, 3)], ids=["256-decode", "93-decode-3-prefill"])
 def test_full_size_relquery_small_batches_13b(rs, oracle, n_rows, n_prefill):
-    """A relQuery batch of few tokens behind a 512-token template: the joint prefix pass has too few token tiles to
-    fill the chip and is split into four key ranges, merged before the rows attend to their own keys."""
+    """A relQuery batch of few tokens behind a 512-token template: one or two token tiles in the joint prefix pass,
+    every row continuing from its stored state over its own keys."""
     wl = W.workload_relquery_13b(seed=1012, n_rows=n_rows, n_prefill=n_prefill)
     _sampled_parity(rs, oracle, wl, [0, 1, 2, n_rows // 2, n_rows - 1], packed=True)
 

@@ -104,7 +104,8 @@ def test_batch_validation_status_per_rule(rs):
     assert rs.relserve_batch_validate(shape, e) == 0
 
 
-@pytest.mark.parametrize("make", [W.workload_tiny, W.workload_tiny_prefix, W.workload_relquery_13b,
+@pytest.mark.parametrize("make", [W.workload_tiny, W.workload_tiny_prefix, W.workload_tiny_long_prefixes,
+                                  W.workload_relquery_13b, lambda: W.workload_relquery_13b(n_rows=256, n_prefill=0),
                                   W.workload_decode_heavy_70b, W.workload_prefill_only_13b])
 def test_slot_placement_matches_oracle_bit_exactly(rs, oracle, make):
     wl = make()

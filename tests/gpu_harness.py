@@ -57,16 +57,19 @@ class GpuLayer:
         return y
 
 
-def assert_bf16_neighbours(got_bits: np.ndarray, want_bits: np.ndarray, what: str, min_exact=0.25, ulps=1.0):
+def assert_bf16_neighbours(got_bits: np.ndarray, want_bits: np.ndarray, what: str, min_exact=0.45, ulps=1.0):
     """Two bf16 tensors rounded from nearly equal fp32 values (the GPU feeds bf16-rounded normed
-    activations to the projection, the oracle fp32 ones): many entries are
+    activations to the projection, the oracle fp32 ones): about half of the entries are
     bit-equal, the rest differ by one unit in the last place (or by cancellation noise near 0)."""
     g = W.bf16_bits_to_f32(got_bits).astype(np.float64)
     w = W.bf16_bits_to_f32(want_bits).astype(np.float64)
     assert np.isfinite(g).all(), what
-    ulp = 2.0 ** -7 * np.maximum(np.abs(w), 1e-30)
-    # before rounding the two sides differ by the bf16 rounding of the projection's input:
-    # about 1e-3 of the tensor's RMS per entry (allow 1e-2), then each side rounds once
+    # spacing of bf16 values at the larger of the two magnitudes
+    ulp = 2.0 ** (np.floor(np.log2(np.maximum(np.maximum(np.abs(w), np.abs(g)), 2.0 ** -120))) - 7)
+    # Before rounding the two sides differ by the bf16 rounding of the projection's input: half a unit in the
+    # last place of each input entry, a relative error of RMS 2^-8 / sqrt(3) / 1.4 = 1.6e-3, hence a deviation
+    # of 1.6e-3 of the tensor's RMS in every output entry.  Six standard deviations of it (1e-2 RMS: the largest
+    # of ~1e5..1e6 entries) are allowed on top of the one unit the two final roundings can be apart.
     bad = np.abs(g - w) > 1.001 * ulps * ulp + 1e-2 * np.sqrt(np.mean(w * w))
     assert not bad.any(), f"{what}: {int(bad.sum())} entries off by more than one bf16 ulp, worst {np.abs(g - w).max():.3e}"
     exact = float(np.mean(got_bits == want_bits))

@@ -303,7 +303,10 @@ def test_multi_step_flow_matches_oracle(rs, oracle, shape):
 # full-size configurations, checked on sampled requests (the oracle recomputes the
 # sampled requests as a sub-batch over the same cache: requests are independent)
 # ---------------------------------------------------------------------------
-def _sampled_parity(rs, oracle, wl, reqs, max_prefill_rows=None, packed=False):
+def _sampled_parity(rs, oracle, wl, reqs, max_prefill_rows=None, packed=False, plain_init=False):
+    if plain_init:      # N(0, 0.02) for every projection instead of the depth-scaled residual writers
+        from dataclasses import replace
+        wl = replace(wl, name=wl.name + "_plain_init", n_layers=0)
     shape, b = wl.shape, wl.batch
     print(f"[case] {wl.name}: T={b.T} reqs={b.num_reqs} sampled={list(reqs)}", flush=True)
     weights = wl.weights()
@@ -323,17 +326,57 @@ def _sampled_parity(rs, oracle, wl, reqs, max_prefill_rows=None, packed=False):
         sel = np.array(sorted(keep), np.int32)
     res = oracle.layer_step(shape, sub, weights, x[rows], kp, vp, rows=sel)
     got = y[rows] if sel is None else y[rows][sel]
+    xin = W.bf16_bits_to_f32(x[rows] if sel is None else x[rows][sel])
+    if plain_init:
+        _plain_init_criterion(got, res.y_f32, xin, wl.name)
+        return
     err, rel = assert_close(got, res.y_f32, wl.name)
     # the layer's own contribution (residual input removed), so that the copied stream cannot mask an error
-    xin = W.bf16_bits_to_f32(x[rows] if sel is None else x[rows][sel])
-    derr, drel = assert_close(got - xin, res.y_f32 - xin, wl.name + " (y - x)", max_abs=2e-2, rel_l2=5e-2)
+    derr, drel = assert_close(got - xin, res.y_f32 - xin, wl.name + " (y - x)", max_abs=2e-2, rel_l2=1e-2)
     print(f"[parity] {wl.name}: max-abs {err:.3e} rel-L2 {rel:.3e}; y-x rel-L2 {drel:.3e} on {got.shape[0]} rows", flush=True)
     # appended slots of the sampled requests hold what the oracle wrote (to bf16 rounding)
     slots = rs.relserve_batch_slots(shape, sub)
     nkv, d = shape.n_kv_heads, shape.head_dim
-    ek = assert_bf16_neighbours(host_bits(gl.k_pages).reshape(-1, nkv, d)[slots], kp.reshape(-1, nkv, d)[slots], "appended k")
-    ev = assert_bf16_neighbours(host_bits(gl.v_pages).reshape(-1, nkv, d)[slots], vp.reshape(-1, nkv, d)[slots], "appended v")
+    ek = assert_bf16_neighbours(host_bits(gl.k_pages).reshape(-1, nkv, d)[slots], kp.reshape(-1, nkv, d)[slots], "appended k", min_exact=0.5)
+    ev = assert_bf16_neighbours(host_bits(gl.v_pages).reshape(-1, nkv, d)[slots], vp.reshape(-1, nkv, d)[slots], "appended v", min_exact=0.5)
     print(f"[parity] {wl.name}: appended k / v bit-equal fractions {ek:.4f} / {ev:.4f}", flush=True)
+
+
+def _plain_init_criterion(got, want, xin, what):
+    """With N(0, 0.02) on every projection a layer this wide multiplies the stream: the layer's own
+    contribution c = y - x has an RMS s of about 3 and |y| reaches 8-16, where neighbouring bf16 values are
+    0.0625 apart.  The relative bounds are scale-free and apply unchanged (1e-2 on y and on c).  The absolute
+    bound (2e-2) was stated for unit-scale outputs and is below what bf16 operands allow here: rounding the
+    GEMM inputs to bf16 (relative 1.6e-3 each) alone puts a deviation of RMS ~4e-3 s = 1.2e-2 on every entry.
+    Per entry the bound becomes: half a bf16 unit of |y| (the output rounding) plus the largest of N entries of a
+    deviation whose RMS meets the relative bound, sqrt(2 ln N) * 1e-2 * s; and no entry may stand out of the
+    observed deviation (an isolated wrong value would): at most 7 times its RMS."""
+    got, want, xin = (np.asarray(a, np.float64) for a in (got, want, xin))
+    assert np.isfinite(got).all(), what
+    c_got, c_want = got - xin, want - xin
+    rel = np.linalg.norm(got - want) / np.linalg.norm(want)
+    crel = np.linalg.norm(c_got - c_want) / np.linalg.norm(c_want)
+    s = float(np.sqrt(np.mean(c_want * c_want)))
+    half_ulp = 2.0 ** (np.floor(np.log2(np.maximum(np.abs(want), 2.0 ** -120))) - 8)
+    err = np.abs(got - want)
+    excess = float((err - half_ulp).max())
+    rms_err = float(np.sqrt(np.mean(err * err)))
+    limit = max(2e-2, float(np.sqrt(2.0 * np.log(want.size))) * 1e-2 * s)
+    print(f"[parity] {what}: |y| max {np.abs(want).max():.2f}, contribution RMS {s:.3f}; rel-L2 {rel:.3e}, (y - x) rel-L2 {crel:.3e}; "
+          f"max-abs {err.max():.3e}, beyond the output rounding {excess:.3e} (limit {limit:.3e}); "
+          f"error RMS {rms_err:.3e}", flush=True)
+    assert rel <= 1e-2 and crel <= 1e-2, (what, rel, crel)
+    assert excess <= limit and err.max() <= 7.0 * rms_err, (what, excess, limit, float(err.max()), rms_err)
+
+
+def test_full_size_relquery_13b_plain_init(rs, oracle):
+    """The headline batch with the plain N(0, 0.02) init on all four projections."""
+    _sampled_parity(rs, oracle, W.workload_relquery_13b(), [0, 15, 16, 99, 199], packed=True, plain_init=True)
+
+
+def test_full_size_decode_heavy_70b_plain_init(rs, oracle):
+    _sampled_parity(rs, oracle, W.workload_decode_heavy_70b(), [0, 64, 130, 255, 256], max_prefill_rows=16, packed=True,
+                    plain_init=True)
 
 
 def test_full_size_relquery_13b(rs, oracle):
@@ -344,7 +387,7 @@ def test_full_size_relquery_13b(rs, oracle):
 @pytest.mark.parametrize("tile,splits", [(0, 2), (1, 3), (5, 2)], ids=["256x256/2", "192x256/3", "256x256-8w/2"])
 def test_full_size_relquery_13b_forced_tail_split(rs, oracle, tile, splits):
     """The tiles of the incomplete last round split their k range over workgroups (partial tiles through the
-    fp32 scratch, summed by the last workgroup to arrive); here forced for every GEMM of the step."""
+    fp32 scratch, summed in split order by the finish kernel); here forced for every GEMM of the step."""
     wl = W.workload_relquery_13b()
     rs.relserve_debug_force_gemm_plan(tile, splits)
     try:
@@ -481,8 +524,8 @@ def test_mid_size_batches_on_narrow_outputs(rs, oracle):
         kp, vp = W.make_cache(shape, b.num_pages, T)
         gl = GpuLayer(rs, shape, weights, kp, vp, b.T)
         y = host_f32(gl.step(b, x))
-        y2 = host_f32(gl.step(b, x))                 # the scratch was left clean: a second step gives the same bits
-        assert np.array_equal(y, y2) or np.abs(y - y2).max() < 1e-2
+        y2 = host_f32(gl.step(b, x))                 # slabs are summed in split order: a second step gives the same bits
+        assert np.array_equal(y, y2)
         res = oracle.layer_step(shape, b, weights, x, kp, vp)
         assert_close(y, res.y_f32, f"{T} prefill tokens")
 
@@ -526,16 +569,7 @@ def _model_case(rs, oracle, shape, batch, n_layers, vocab, seed, scaled, what):
     ks, vs = [k for k, _ in caches], [v for _, v in caches]
     want, _ = oracle.model_step(shape, batch, model, ids, ks, vs)
     got = logits.cpu().numpy()
-    # logits are fp32 sums over H products of a stream that went through n_layers bf16 roundings on
-    # both sides: the criterion is the relative-L2 bound (1e-2); the largest single deviation among
-    # ~1e5 logits is bounded at six times the RMS deviation that bound allows
-    scale = float(np.sqrt(np.mean(want.astype(np.float64) ** 2)))
-    err, rel = assert_close(got, want, what, max_abs=6e-2 * scale, rel_l2=1e-2)
-    # the next-token choice must agree wherever the oracle's lead over the runner-up exceeds the deviation
-    top2 = np.sort(want, axis=1)[:, -2:]
-    clear = (top2[:, 1] - top2[:, 0]) > 2 * err
-    assert (got.argmax(1)[clear] == want.argmax(1)[clear]).all()
-    print(f"[parity] {what}: logits max-abs {err:.3e} (scale {scale:.2f}) rel-L2 {rel:.3e}", flush=True)
+    _logits_criterion(got, want, what)
     # every layer's cache received the appended rows where the oracle put them
     slots = rs.relserve_batch_slots(shape, batch)
     nkv, d = shape.n_kv_heads, shape.head_dim
@@ -543,7 +577,7 @@ def _model_case(rs, oracle, shape, batch, n_layers, vocab, seed, scaled, what):
         gk = host_bits(gm["caches"][l][0]).reshape(-1, nkv, d)[slots]
         wk = ks[l].reshape(-1, nkv, d)[slots]
         if l == 0:      # same bf16 inputs on both sides: one rounding apart
-            assert_bf16_neighbours(gk, wk, "layer 0 appended k", min_exact=0.15)
+            assert_bf16_neighbours(gk, wk, "layer 0 appended k")
         else:           # the incoming stream already differs by bf16 roundings of earlier layers
             wf = W.bf16_bits_to_f32(wk)
             assert_close(W.bf16_bits_to_f32(gk), wf, f"layer {l} appended k",
@@ -563,6 +597,95 @@ def test_model_step_13b_two_layer_slice(rs, oracle):
     reqs = [0, 77, 127, 128]
     print(f"[case] 2-layer 13B model step, requests {reqs} of {wl.batch.num_reqs}", flush=True)
     _model_case(rs, oracle, wl.shape, wl.batch.select(reqs), 2, 32000, 92, True, "model step 13B x2")
+
+
+# The full batch of the composition sweep (128 decode rows of context 1024 plus one prefill chunk of 0 / 512 / 1024 /
+# 2048 / 4096 tokens) through relserve_model_step on a 2-layer slice of the 13B stack with the 32000-entry
+# vocabulary.  The GPU runs the WHOLE batch (T = 128 ... 4224, logits for all 128 or 129 requests); the oracle
+# recomputes sampled requests as a sub-batch over the same caches (requests are independent).
+_SWEEP_VOCAB, _SWEEP_LAYERS, _SWEEP_SEED = 32000, 2, 93
+
+
+@pytest.fixture(scope="module")
+def sweep_model():
+    shape = W.LLAMA_13B
+    model = W.make_model(shape, _SWEEP_LAYERS, _SWEEP_VOCAB, _SWEEP_SEED, scaled=True)
+    pages = max(W.workload_decode_plus_chunk_13b(c).batch.num_pages for c in (0, 512, 1024, 2048, 4096))
+    caches = [W.make_cache(shape, pages, _SWEEP_SEED + 7 * l) for l in range(_SWEEP_LAYERS)]   # pristine; every case works on copies
+    return shape, model, caches
+
+
+def _logits_criterion(got, want, what):
+    """Logits are fp32 dot products over H entries of a stream that crossed n_layers bf16 roundings on both
+    sides.  Relative-L2 <= 1e-2 as for a layer output.  The absolute bound of a layer output (2e-2 at unit
+    scale) has no direct meaning for them: a deviation whose RMS meets the relative bound, sigma = 1e-2 *
+    RMS(logits), has over N values a largest entry of about sqrt(2 ln N) sigma, which is the bound used; an
+    isolated wrong logit (an indexing mistake) is far outside it."""
+    got, want = np.asarray(got, np.float64), np.asarray(want, np.float64)
+    rms = float(np.sqrt(np.mean(want * want)))
+    bound = float(np.sqrt(2.0 * np.log(want.size))) * 1e-2 * rms
+    err, rel = assert_close(got, want, what, max_abs=bound, rel_l2=1e-2)
+    top2 = np.sort(want, axis=1)[:, -2:]
+    clear = (top2[:, 1] - top2[:, 0]) > 2 * err          # next-token choice wherever the lead exceeds the deviation
+    assert (got.argmax(1)[clear] == want.argmax(1)[clear]).all()
+    print(f"[parity] {what}: logits max-abs {err:.3e} (bound {bound:.3e}, RMS {rms:.2f}) rel-L2 {rel:.3e}, "
+          f"{int(clear.sum())} of {len(clear)} next tokens decided", flush=True)
+
+
+@pytest.mark.parametrize("chunk", [0, 512, 1024, 2048, 4096])
+def test_model_step_composition_sweep_full_batch(rs, oracle, sweep_model, chunk):
+    shape, model, caches0 = sweep_model
+    wl = W.workload_decode_plus_chunk_13b(chunk)
+    b = wl.batch
+    print(f"[case] 2-layer 13B model step, full batch: chunk {chunk}, T={b.T}, requests {b.num_reqs}", flush=True)
+    ids = W.make_token_ids(b.T, _SWEEP_VOCAB, _SWEEP_SEED + chunk)
+    gm = _gpu_model(rs, shape, model, caches0)
+    gm["layers"] = [rs.pack_layer_weights(w) for w in gm["layers"]]
+    layer = rs.relserve_layer_create(shape)
+    pb = rs.relserve_batch_prepare(layer, b)
+    ws = torch.empty(rs.relserve_model_workspace_bytes(layer, b.T, b.num_reqs), dtype=torch.uint8, device="cuda")
+    logits = torch.full((b.num_reqs, _SWEEP_VOCAB), float("nan"), dtype=torch.float32, device="cuda")
+    rs.relserve_model_step(layer, pb, gm, torch.from_numpy(ids).cuda(), logits, ws)
+    torch.cuda.synchronize()
+    got = logits.cpu().numpy()
+    assert np.isfinite(got).all()                       # every one of the 128 / 129 rows was written
+    # sampled requests: decode rows at every composition; the chunk itself where the oracle finishes in about a minute
+    reqs = [0, 77, 127] + ([128] if chunk == 512 else [])
+    sub = b.select(reqs)
+    rows = b.token_rows(reqs)
+    ks = [k.copy() for k, _ in caches0]
+    vs = [v.copy() for _, v in caches0]
+    want, _ = oracle.model_step(shape, sub, model, ids[rows], ks, vs)
+    _logits_criterion(got[reqs], want, f"model step 13B x2, chunk {chunk}, requests {reqs}")
+    # every layer's cache holds the sampled requests' appended rows where the oracle put them
+    slots = rs.relserve_batch_slots(shape, sub)
+    nkv, d = shape.n_kv_heads, shape.head_dim
+    for l in range(_SWEEP_LAYERS):
+        gk = host_bits(gm["caches"][l][0]).reshape(-1, nkv, d)[slots]
+        wk = ks[l].reshape(-1, nkv, d)[slots]
+        if l == 0:
+            assert_bf16_neighbours(gk, wk, "layer 0 appended k")
+        else:
+            wf = W.bf16_bits_to_f32(wk)
+            assert_close(W.bf16_bits_to_f32(gk), wf, f"layer {l} appended k",
+                         max_abs=6e-2 * float(np.sqrt(np.mean(wf.astype(np.float64) ** 2))), rel_l2=1e-2)
+    if chunk >= 1024:
+        # The chunk's own logits, beyond the oracle's reach at this size, through a property that holds at any size
+        # (Sec. 2.3 "KV Cache": cached keys are a memo, so a prompt processed in pieces gives the result of one pass):
+        # the same prompt as consecutive 512-token model steps -- the size checked against the oracle above.
+        caches = [(dev_bf16(k), dev_bf16(v)) for k, v in caches0]
+        gm2 = dict(gm, caches=caches)
+        bt = np.ascontiguousarray(b.block_table[128:129])
+        piece_logits = None
+        for done in range(0, chunk, 512):
+            pbatch = W.Batch(np.array([0, 512], np.int32), np.array([done + 512], np.int32), bt, np.array([-1], np.int32),
+                             np.zeros(0, np.int32), b.num_pages)
+            ppb = rs.relserve_batch_prepare(layer, pbatch)
+            piece_logits = torch.empty(1, _SWEEP_VOCAB, dtype=torch.float32, device="cuda")
+            rs.relserve_model_step(layer, ppb, gm2, torch.from_numpy(ids[128 + done:128 + done + 512]).cuda(), piece_logits, ws)
+            torch.cuda.synchronize()
+            ppb.close()
+        _logits_criterion(got[128:129], piece_logits.cpu().numpy(), f"chunk {chunk} in one pass against 512-token pieces")
 
 
 # ---------------------------------------------------------------------------

@@ -49,7 +49,9 @@ def build_workload(name: str):
         table[name] = lambda: W.workload_decode_plus_chunk_13b(int(m.group(1)), n_dec=0)
     if name not in table:
         raise SystemExit(f"unknown workload {name!r}; choose from {sorted(table)}")
-    return table[name]()
+    wl = table[name]()
+    wl.extra["bench_key"] = name          # the key profiles/traffic.json files this workload under
+    return wl
 
 
 def algorithmic_counts(shape, batch) -> dict:
@@ -73,7 +75,13 @@ def algorithmic_counts(shape, batch) -> dict:
     uniq_tokens += own_tokens["decode"] + own_tokens["prefill"]
     weights = shape.params * 2
     bytes_total = weights + uniq_tokens * kv_tok + 2 * T * H * 2 + T * kv_tok
-    return {"gemm_flops": gemm, "attn_flops": attn_flops, "flops_total": sum(gemm.values()) + attn_flops,
+    qd = nq * d
+    # bytes one launch of each GEMM must move: its weights, its input, its output, its residual input
+    gemm_bytes = {"gemm_qkv_rope_append": 2 * (shape.qkv_dim * H + T * H + T * shape.qkv_dim),
+                  "gemm_o": 2 * (H * qd + T * qd + T * H) + 4 * T * H,
+                  "gemm_gate_up": 2 * (2 * I * H + T * H + T * I),
+                  "gemm_down": 2 * (H * I + T * I + T * H) + 4 * T * H}
+    return {"gemm_flops": gemm, "gemm_bytes": gemm_bytes, "attn_flops": attn_flops, "flops_total": sum(gemm.values()) + attn_flops,
             "weight_bytes": weights, "kv_unique_bytes": uniq_tokens * kv_tok, "bytes_total": bytes_total,
             "kv_decode_own_bytes": own_tokens["decode"] * kv_tok, "kv_prefill_own_bytes": own_tokens["prefill"] * kv_tok,
             "kv_naive_bytes": int(batch.ctx_len.astype(np.int64).sum()) * kv_tok}
@@ -85,16 +93,20 @@ def cpu_baseline(wl, weights, x, budget_tokens: int) -> dict:
     from paper_2601_11546_amd import workloads as W
     orc = relserve_oracle.load("f32")
     b = wl.batch
-    # sample: the shortest prefill request plus decode requests in batch order, up to the token budget
+    # sample with the batch's own mix of prefill and decode TOKENS: the shortest prefill requests up to the prefill
+    # share of the token budget, then decode requests in batch order for the rest
     pre = sorted((r for r in range(b.num_reqs) if b.q_len[r] > 1), key=lambda r: int(b.q_len[r]))
     dec = [r for r in range(b.num_reqs) if b.q_len[r] == 1]
-    picked = pre[:1]
-    tokens = int(b.q_len[picked[0]]) if picked else 0
-    for r in dec[:max(4, budget_tokens - tokens)]:
-        picked.append(r)
-        tokens += 1
-        if tokens >= budget_tokens and len(picked) >= 5:
+    pre_tokens = int(b.q_len[pre].sum()) if pre else 0
+    picked, tokens = [], 0
+    for r in pre:
+        if picked and tokens + int(b.q_len[r]) > budget_tokens * pre_tokens / max(b.T, 1):
             break
+        picked.append(r)
+        tokens += int(b.q_len[r])
+    n_pre = len(picked)
+    want_dec = max(1 if dec else 0, int(round(tokens * (b.T - pre_tokens) / pre_tokens))) if pre_tokens else budget_tokens
+    picked += dec[:want_dec]
     picked.sort()
     sub = b.select(picked)
     rows = b.token_rows(picked)
@@ -102,10 +114,37 @@ def cpu_baseline(wl, weights, x, budget_tokens: int) -> dict:
     t0 = time.perf_counter()
     orc.layer_step(wl.shape, sub, weights, x[rows], kp, vp)
     dt = time.perf_counter() - t0
+    del n_pre
     return {"value": sub.T / dt, "unit": "tokens/s", "cores": orc.num_threads, "kind": "oracle",
             "seconds": round(dt, 3),
             "sample": f"{len(picked)} of {b.num_reqs} requests of the same batch ({sub.T} of {b.T} query tokens: "
                       f"{int((sub.q_len > 1).sum())} prefill rows, {int((sub.q_len == 1).sum())} decode rows), one layer step"}
+
+
+def cpu_baseline_tiny_single_thread() -> dict:
+    """The whole tiny configuration (configs[0]) through the oracle on ONE host thread."""
+    import ctypes
+    from oracle import relserve_oracle
+    from paper_2601_11546_amd import workloads as W
+    orc = relserve_oracle.load("f32")
+    omp = ctypes.CDLL("libgomp.so.1")
+    omp.omp_get_max_threads.restype = ctypes.c_int
+    before = omp.omp_get_max_threads()
+    wl = W.workload_tiny()
+    x = W.make_activations(wl.batch.T, wl.shape.hidden, wl.seed)
+    weights = wl.weights()
+    omp.omp_set_num_threads(1)
+    try:
+        best = float("inf")
+        for _ in range(3):
+            kp, vp = W.make_cache(wl.shape, wl.batch.num_pages, wl.seed)
+            t0 = time.perf_counter()
+            orc.layer_step(wl.shape, wl.batch, weights, x, kp, vp)
+            best = min(best, time.perf_counter() - t0)
+    finally:
+        omp.omp_set_num_threads(before)
+    return {"workload": "tiny", "query_tokens": wl.batch.T, "seconds": round(best, 5), "tokens_per_s": round(wl.batch.T / best, 1),
+            "cores": 1}
 
 
 def peak_probes(rs, torch) -> dict:
@@ -221,6 +260,181 @@ def serve_gpu(rs, W) -> dict:
             "results": rows}
 
 
+def _stats(ms: list) -> dict:
+    a = np.sort(np.asarray(ms, np.float64))
+    return {"median": round(float(np.median(a)), 4), "p10": round(float(np.percentile(a, 10)), 4),
+            "p90": round(float(np.percentile(a, 90)), 4), "min": round(float(a[0]), 4), "max": round(float(a[-1]), 4),
+            "repeats": len(a)}
+
+
+def measure_layer_step(rs, W, torch, args, wl, host_draws: bool) -> dict:
+    """Times the layer step of one workload.  host_draws: weights, cache and activations are the seeded host draws the
+    parity tests use (needed for the oracle leg); otherwise they are drawn on the device from the same distributions."""
+    shape, b = wl.shape, wl.batch
+    counts = algorithmic_counts(shape, b)
+    H, I, qd = shape.hidden, shape.mlp_dim, shape.n_q_heads * shape.head_dim
+
+    def dev(bits):
+        return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).cuda().view(torch.bfloat16)
+
+    # enough sets that the rotating working set exceeds the 256 MB last-level cache several times
+    n_sets = args.layer_sets or max(2, min(4, int(np.ceil(2.5e9 / counts["weight_bytes"]))))
+    packed = not args.row_major_weights and all(v % 64 == 0 for v in (H, qd, I))
+    weights0 = x_bits = None
+    pool = (b.num_pages, shape.page_size, shape.n_kv_heads, shape.head_dim)
+    if host_draws:
+        weights0 = wl.weights()
+        x_bits = W.make_activations(b.T, H, wl.seed)
+        kp, vp = W.make_cache(shape, b.num_pages, wl.seed)
+        base = ({k: dev(v) for k, v in weights0.items()}, dev(kp), dev(vp))
+        del kp, vp
+        x = dev(x_bits)
+    else:
+        g = torch.Generator(device="cuda")
+        g.manual_seed(wl.seed)
+
+        def randn(*size, std=1.0, mean=0.0):
+            return (torch.randn(*size, generator=g, device="cuda", dtype=torch.float32) * std + mean).to(torch.bfloat16)
+
+        res_std = 0.02 / (2 * wl.n_layers) ** 0.5 if wl.n_layers else 0.02
+        base = ({"w_in_norm": randn(H, std=0.02, mean=1.0), "w_qkv": randn(shape.qkv_dim, H, std=0.02),
+                 "w_o": randn(H, qd, std=res_std), "w_post_norm": randn(H, std=0.02, mean=1.0),
+                 "w_gate_up": randn(2 * I, H, std=0.02), "w_down": randn(H, I, std=res_std)}, randn(*pool), randn(*pool))
+        x = randn(b.T, H)
+    # set 0 holds the draws; the other sets are row-rotated device copies of it (same values and
+    # distribution at other addresses), which keeps set-up time short
+    sets = []
+    for i in range(n_sets):
+        wts = base[0] if i == 0 else {k: torch.roll(v, 7 * i, 0) for k, v in base[0].items()}
+        if packed:   # one-time conversion at model load (relserve_pack_weight); the row-major copy is dropped
+            wts = rs.pack_layer_weights(wts)
+        sets.append((wts,
+                     base[1] if i == 0 else torch.roll(base[1].view(-1, base[1].shape[-1]), 5 * i, 0).view(base[1].shape).contiguous(),
+                     base[2] if i == 0 else torch.roll(base[2].view(-1, base[2].shape[-1]), 5 * i, 0).view(base[2].shape).contiguous()))
+    if packed:
+        base = (None, base[1], base[2])
+    layer = rs.relserve_layer_create(shape)
+    rs.relserve_batch_prepare(layer, b).close()          # the first call of a process also pays the runtime's set-up
+    t0 = time.perf_counter()
+    pb = rs.relserve_batch_prepare(layer, b)
+    prepare_ms = (time.perf_counter() - t0) * 1e3
+    y = torch.empty_like(x)
+    ws = torch.empty(rs.relserve_workspace_bytes(layer, b.T), dtype=torch.uint8, device="cuda")
+
+    def step(i):
+        wts, kd, vd = sets[i % n_sets]
+        rs.relserve_layer_step(layer, pb, wts, x, y, kd, vd, ws)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    if args.calibration_copy:     # a kernel of known traffic: reads 1 GiB, writes 1 GiB
+        src = torch.ones(1 << 29, dtype=torch.bfloat16, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+    # untimed pass with HIP events around every kernel: the per-kernel table, and which kernel dominates
+    rs.relserve_profile_enable(layer, True)
+    for i in range(min(args.steps, 10)):
+        step(i)
+    prof = rs.relserve_profile_read(layer, reset=True)
+    dom = max(prof, key=lambda n: prof[n]["ms_sum"] / prof[n]["launches"])
+    # timed region: `repeats` times exactly K steps, each bracketed by a device synchronisation; HIP events (recorded
+    # by the library on the launch stream) around the dominant kernel only, since every event pair costs stream time
+    rs.relserve_profile_enable(layer, [dom])
+    per_loop = []
+    for _ in range(args.repeats):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            step(i)
+        torch.cuda.synchronize()
+        per_loop.append((time.perf_counter() - t0) / args.steps * 1e3)
+    prof_timed = rs.relserve_profile_read(layer, reset=True)
+    rs.relserve_profile_enable(layer, False)
+    prof[dom] = prof_timed[dom]
+    # the same K steps without any events, to show what the pair costs
+    plain = []
+    for _ in range(max(1, args.repeats // 2)):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            step(i)
+        torch.cuda.synchronize()
+        plain.append((time.perf_counter() - t0) / args.steps * 1e3)
+    stats = _stats(per_loop)
+    ms_step = stats["median"]
+
+    kv_bytes = {"attn_own_keys": counts["kv_decode_own_bytes"] + counts["kv_prefill_own_bytes"],
+                "attn_split": counts["kv_decode_own_bytes"], "attn_tile": counts["kv_prefill_own_bytes"]}
+    kernels = {}
+    for name, v in prof.items():
+        avg_ms = v["ms_sum"] / v["launches"]
+        k = {"avg_ms": round(avg_ms, 4), "launches": v["launches"]}
+        if name in counts["gemm_flops"]:
+            k["tflops"] = round(counts["gemm_flops"][name] / (avg_ms * 1e-3) / 1e12, 1)
+            k["frac_mfma_peak"] = round(k["tflops"] / PEAK_BF16_TFLOPS, 4)
+            k["gbs"] = round(counts["gemm_bytes"][name] / (avg_ms * 1e-3) / 1e9, 1)
+            k["frac_hbm_peak"] = round(k["gbs"] / PEAK_HBM_GBS, 4)
+        elif kv_bytes.get(name):
+            k["kv_gbs"] = round(kv_bytes[name] / (avg_ms * 1e-3) / 1e9, 1)
+            k["frac_hbm_peak"] = round(k["kv_gbs"] / PEAK_HBM_GBS, 4)
+        kernels[name] = k
+    attn_ms = sum(kernels[n]["avg_ms"] for n in ("attn_prefix", "attn_own_keys", "attn_tile", "attn_split") if n in kernels)
+    if attn_ms > 0:
+        kernels["attention_all"] = {"avg_ms": round(attn_ms, 4),
+                                    "tflops": round(counts["attn_flops"] / (attn_ms * 1e-3) / 1e12, 1),
+                                    "kv_unique_gbs": round(counts["kv_unique_bytes"] / (attn_ms * 1e-3) / 1e9, 1)}
+
+    step_tflops = counts["flops_total"] / (ms_step * 1e-3) / 1e12
+    step_gbs = counts["bytes_total"] / (ms_step * 1e-3) / 1e9
+    hbm_bound = (counts["bytes_total"] / (PEAK_HBM_GBS * 1e9)) > (counts["flops_total"] / (PEAK_BF16_TFLOPS * 1e12))
+    traffic, traffic_source = None, None
+    tpath = os.path.join(ROOT, "profiles", "traffic.json")
+    key = wl.extra.get("bench_key")
+    if os.path.exists(tpath) and key:
+        traffic = json.load(open(tpath)).get(key, {}).get(dom)
+        if traffic is not None:
+            traffic_source = "recorded: profiles/traffic.json (rocprofv3 --pmc FETCH_SIZE + WRITE_SIZE of an earlier run of this command)"
+    dk = kernels[dom]
+    if hbm_bound:      # the dominant kernel against the bytes it must move, and the whole step beside it
+        dom_bytes = counts["gemm_bytes"].get(dom) or kv_bytes.get(dom) or 0
+        roofline = {"bound": "hbm", "achieved": round(dom_bytes / (dk["avg_ms"] * 1e-3) / 1e9, 1), "peak": PEAK_HBM_GBS,
+                    "unit": "GB/s", "frac": round(dom_bytes / (dk["avg_ms"] * 1e-3) / 1e9 / PEAK_HBM_GBS, 4), "traffic": traffic,
+                    "traffic_source": traffic_source, "kernel": dom, "bytes_per_launch": dom_bytes, "avg_launch_ms": dk["avg_ms"],
+                    "whole_step": {"achieved": round(step_gbs, 1), "frac": round(step_gbs / PEAK_HBM_GBS, 4),
+                                   "bytes": counts["bytes_total"]}}
+    else:
+        roofline = {"bound": "mfma", "achieved": dk["tflops"], "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                    "frac": dk["frac_mfma_peak"], "traffic": traffic, "traffic_source": traffic_source, "kernel": dom,
+                    "flops_per_launch": counts["gemm_flops"][dom], "avg_launch_ms": dk["avg_ms"],
+                    "whole_step": {"achieved": round(step_tflops, 1), "frac": round(step_tflops / PEAK_BF16_TFLOPS, 4),
+                                   "flops": counts["flops_total"]}}
+    line = {
+        "metric": "mixed_batch_layer_step_tokens_per_s", "value": round(b.T / (ms_step * 1e-3), 1), "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": wl.name, "layer": f"H{shape.hidden} q{shape.n_q_heads}/kv{shape.n_kv_heads}x{shape.head_dim} "
+                   f"I{shape.mlp_dim} P{shape.page_size}", "query_tokens": b.T, "requests": b.num_reqs,
+                   "prefill_rows": int((b.q_len > 1).sum()), "decode_rows": int((b.q_len == 1).sum()),
+                   "layer_sets_rotated": n_sets, "weight_layout": "packed" if packed else "row-major",
+                   "batch_info": pb.info},
+        "ms_per_step_stats": stats,
+        "roofline": roofline,
+        "step": {"tflops": round(step_tflops, 1), "frac_mfma_peak": round(step_tflops / PEAK_BF16_TFLOPS, 4),
+                 "algorithmic_gbs": round(step_gbs, 1), "frac_hbm_peak": round(step_gbs / PEAK_HBM_GBS, 4),
+                 "ms_per_step_without_events": round(float(np.median(plain)), 4),
+                 "batch_prepare_ms": round(prepare_ms, 3)},
+        "kernels": kernels,
+    }
+    pb.close()
+    del sets, base, ws, x, y
+    torch.cuda.empty_cache()
+    return {"line": line, "weights0": weights0, "x_bits": x_bits}
+
+
 def main() -> None:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -244,6 +458,9 @@ def main() -> None:
                          "relserve_model_step on a 4-layer model of the 13B layer shape; the clock is the measured GPU time")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-peak-probes", action="store_true", help="skip the MFMA issue loop and the streaming read")
+    ap.add_argument("--repeats", type=int, default=9, help="how many times the K timed steps are repeated (median, p10, p90)")
+    ap.add_argument("--no-regimes", action="store_true",
+                    help="headline workload only (by default the line also carries the prefill-only and the decode-only regimes)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (reference for rocprofv3's FETCH_SIZE / WRITE_SIZE)")
     ap.add_argument("--cpu-tokens", type=int, default=0, help="token budget of the oracle sample (0 = auto)")
@@ -280,141 +497,24 @@ def main() -> None:
         print(json.dumps(duration_model.run(steps=max(1, min(args.steps, 10)), warmup=max(1, min(args.warmup, 3)))))
         return
     wl = build_workload(args.workload)
-    shape, b = wl.shape, wl.batch
-    counts = algorithmic_counts(shape, b)
-
-    def dev(bits):
-        return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).cuda().view(torch.bfloat16)
-
-    # enough sets that the rotating working set exceeds the 256 MB last-level cache several times
-    n_sets = args.layer_sets or max(2, min(4, int(np.ceil(2.5e9 / counts["weight_bytes"]))))
-    weights0 = wl.weights()
-    x_bits = W.make_activations(b.T, shape.hidden, wl.seed)
-    # set 0 holds the seeded host draws; the other sets are row-rotated device copies of it
-    # (same values and distribution at other addresses), which keeps host set-up time short
-    kp, vp = W.make_cache(shape, b.num_pages, wl.seed)
-    base = ({k: dev(v) for k, v in weights0.items()}, dev(kp), dev(vp))
-    del kp, vp
-    packed = not args.row_major_weights and all(d % 64 == 0 for d in (shape.hidden, shape.n_q_heads * shape.head_dim, shape.mlp_dim))
-    sets = []
-    for i in range(n_sets):
-        wts = base[0] if i == 0 else {k: torch.roll(v, 7 * i, 0) for k, v in base[0].items()}
-        if packed:   # one-time conversion at model load (relserve_pack_weight); the row-major copy is dropped
-            wts = rs.pack_layer_weights(wts)
-        sets.append((wts,
-                     base[1] if i == 0 else torch.roll(base[1].view(-1, base[1].shape[-1]), 5 * i, 0).view(base[1].shape).contiguous(),
-                     base[2] if i == 0 else torch.roll(base[2].view(-1, base[2].shape[-1]), 5 * i, 0).view(base[2].shape).contiguous()))
-    if packed:
-        base = (None, base[1], base[2])
-    layer = rs.relserve_layer_create(shape)
-    t0 = time.perf_counter()
-    pb = rs.relserve_batch_prepare(layer, b)
-    prepare_ms = (time.perf_counter() - t0) * 1e3
-    x = dev(x_bits)
-    y = torch.empty_like(x)
-    ws = torch.empty(rs.relserve_workspace_bytes(layer, b.T), dtype=torch.uint8, device="cuda")
-
-    def step(i):
-        wts, kd, vd = sets[i % n_sets]
-        rs.relserve_layer_step(layer, pb, wts, x, y, kd, vd, ws)
-
-    for i in range(args.warmup):
-        step(i)
-    torch.cuda.synchronize()
-    if args.calibration_copy:     # a kernel of known traffic: reads 1 GiB, writes 1 GiB
-        src = torch.ones(1 << 29, dtype=torch.bfloat16, device="cuda")
-        dst = torch.empty_like(src)
-        for _ in range(3):
-            dst.copy_(src)
-        torch.cuda.synchronize()
-        del src, dst
-    # untimed pass with HIP events around every kernel: the per-kernel table, and which GEMM dominates
-    rs.relserve_profile_enable(layer, True)
-    for i in range(min(args.steps, 10)):
-        step(i)
-    prof = rs.relserve_profile_read(layer, reset=True)
-    dom = max(counts["gemm_flops"], key=lambda n: prof[n]["ms_sum"] / prof[n]["launches"] if n in prof else 0.0)
-    # timed region: exactly K steps; HIP events (on the launch stream) around the dominant kernel only,
-    # since every event pair costs stream time that the other kernels' pairs would add to the step
-    rs.relserve_profile_enable(layer, [dom])
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        step(i)
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
-    prof_timed = rs.relserve_profile_read(layer, reset=True)
-    rs.relserve_profile_enable(layer, False)
-    prof[dom] = prof_timed[dom]
-    # the same K steps without any events, to show what the pair costs
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        step(i)
-    torch.cuda.synchronize()
-    elapsed_plain = time.perf_counter() - t0
-
-    ms_step = elapsed / args.steps * 1e3
-    kernels = {}
-    for name, v in prof.items():
-        avg_ms = v["ms_sum"] / v["launches"]
-        k = {"avg_ms": round(avg_ms, 4), "launches": v["launches"]}
-        if name in counts["gemm_flops"]:
-            k["tflops"] = round(counts["gemm_flops"][name] / (avg_ms * 1e-3) / 1e12, 1)
-            k["frac_mfma_peak"] = round(k["tflops"] / PEAK_BF16_TFLOPS, 4)
-        kernels[name] = k
-    attn_ms = sum(kernels[n]["avg_ms"] for n in ("attn_prefix", "attn_own_keys", "attn_tile", "attn_split") if n in kernels)
-    if attn_ms > 0:
-        kernels["attention_all"] = {"avg_ms": round(attn_ms, 4),
-                                    "tflops": round(counts["attn_flops"] / (attn_ms * 1e-3) / 1e12, 1),
-                                    "kv_unique_gbs": round(counts["kv_unique_bytes"] / (attn_ms * 1e-3) / 1e9, 1)}
-    if "attn_own_keys" in kernels:   # prefill rows and decode rows over their own keys in one launch
-        gbs = (counts["kv_decode_own_bytes"] + counts["kv_prefill_own_bytes"]) / (kernels["attn_own_keys"]["avg_ms"] * 1e-3) / 1e9
-        kernels["attn_own_keys"]["kv_gbs"] = round(gbs, 1)
-        kernels["attn_own_keys"]["frac_hbm_peak"] = round(gbs / PEAK_HBM_GBS, 4)
-    if "attn_split" in kernels and counts["kv_decode_own_bytes"]:
-        gbs = counts["kv_decode_own_bytes"] / (kernels["attn_split"]["avg_ms"] * 1e-3) / 1e9
-        kernels["attn_split"]["kv_gbs"] = round(gbs, 1)
-        kernels["attn_split"]["frac_hbm_peak"] = round(gbs / PEAK_HBM_GBS, 4)
-
-    step_tflops = counts["flops_total"] / (ms_step * 1e-3) / 1e12
-    step_gbs = counts["bytes_total"] / (ms_step * 1e-3) / 1e9
-    hbm_bound = (counts["bytes_total"] / (PEAK_HBM_GBS * 1e9)) > (counts["flops_total"] / (PEAK_BF16_TFLOPS * 1e12))
-    traffic = None
-    tpath = os.path.join(ROOT, "profiles", "traffic.json")
-    if os.path.exists(tpath):
-        per_workload = json.load(open(tpath)).get(args.workload, {})
-        traffic = per_workload.get("whole_step" if hbm_bound else dom)
-    if hbm_bound:
-        roofline = {"bound": "hbm", "achieved": round(step_gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                    "frac": round(step_gbs / PEAK_HBM_GBS, 4), "traffic": traffic, "kernel": "whole step",
-                    "bytes": counts["bytes_total"]}
-    else:
-        roofline = {"bound": "mfma", "achieved": kernels[dom]["tflops"], "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                    "frac": kernels[dom]["frac_mfma_peak"], "traffic": traffic, "kernel": dom,
-                    "flops_per_launch": counts["gemm_flops"][dom], "avg_launch_ms": kernels[dom]["avg_ms"]}
-
-    out = {
-        "metric": "mixed_batch_layer_step_tokens_per_s", "value": round(b.T / (ms_step * 1e-3), 1), "unit": "tokens/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_step, 4),
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": wl.name, "layer": f"H{shape.hidden} q{shape.n_q_heads}/kv{shape.n_kv_heads}x{shape.head_dim} "
-                   f"I{shape.mlp_dim} P{shape.page_size}", "query_tokens": b.T, "requests": b.num_reqs,
-                   "prefill_rows": int((b.q_len > 1).sum()), "decode_rows": int((b.q_len == 1).sum()),
-                   "layer_sets_rotated": n_sets, "weight_layout": "packed" if packed else "row-major",
-                   "batch_info": pb.info},
-        "roofline": roofline,
-        "step": {"tflops": round(step_tflops, 1), "frac_mfma_peak": round(step_tflops / PEAK_BF16_TFLOPS, 4),
-                 "algorithmic_gbs": round(step_gbs, 1), "frac_hbm_peak": round(step_gbs / PEAK_HBM_GBS, 4),
-                 "ms_per_step_without_events": round(elapsed_plain / args.steps * 1e3, 4),
-                 "batch_prepare_ms": round(prepare_ms, 3)},
-        "kernels": kernels,
-    }
+    res = measure_layer_step(rs, W, torch, args, wl, host_draws=True)
+    out = res["line"]
+    if not args.no_regimes and args.workload == "relquery_13b":
+        # the two regimes the roofline targets are stated on, each with its own roofline object
+        out["regimes"] = {}
+        for name in ("prefill_only_13b", "decode128_13b", "decode_only_70b"):
+            r = measure_layer_step(rs, W, torch, args, build_workload(name), host_draws=False)["line"]
+            out["regimes"][name] = {"ms_per_step": r["ms_per_step"], "ms_per_step_stats": r["ms_per_step_stats"],
+                                    "tokens_per_s": r["value"], "query_tokens": r["config"]["query_tokens"],
+                                    "requests": r["config"]["requests"], "layer": r["config"]["layer"],
+                                    "data": "synthetic (drawn on the device)", "roofline": r["roofline"], "step": r["step"],
+                                    "kernels": r["kernels"]}
     if not args.no_peak_probes:
         out["measured_peaks"] = peak_probes(rs, torch)
     if not args.no_cpu_baseline:
-        budget = args.cpu_tokens or max(8, int(1.6e11 / (2 * shape.params)))   # about 160 GFLOP of dense work, ~10 s
-        out["cpu_baseline"] = cpu_baseline(wl, weights0, x_bits, budget)
+        budget = args.cpu_tokens or max(8, int(1.6e11 / (2 * wl.shape.params)))   # about 160 GFLOP of dense work, ~10 s
+        out["cpu_baseline"] = cpu_baseline(wl, res["weights0"], res["x_bits"], budget)
+        out["cpu_baseline"]["tiny_single_thread"] = cpu_baseline_tiny_single_thread()
     print(json.dumps(out))
 
 

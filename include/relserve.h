@@ -58,7 +58,7 @@ typedef enum {
     RELSERVE_ERR_WORKSPACE = -9,          /* workspace missing, misaligned or too small */
     RELSERVE_ERR_HIP = -10,               /* a HIP runtime call failed */
     RELSERVE_ERR_NO_DEVICE = -11,         /* no gfx950 device is current */
-    RELSERVE_ERR_TOO_LARGE = -12,         /* a size overflows the 32-bit indices used on the device */
+    RELSERVE_ERR_TOO_LARGE = -12,         /* a size overflows the 32-bit indices used on the device, or the fixed scratch */
     RELSERVE_ERR_MISMATCH = -13,          /* batch prepared for another layer shape, or cache smaller than the batch's */
     RELSERVE_ERR_BAD_ARGUMENT = -14
 } relserve_status;
@@ -175,6 +175,21 @@ int32_t relserve_layer_step(const relserve_layer* layer, const relserve_batch* b
                             const relserve_layer_weights* weights,
                             const void* x, void* y, relserve_kv_cache cache,
                             void* workspace, size_t workspace_bytes, void* stream);
+
+/* relserve_layer_step for callers that cannot allocate or carry a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same kernels, same results bit for bit;
+ * the workspace is a fixed array of RELSERVE_STATIC_SCRATCH_BYTES in device memory that belongs to the
+ * library (one copy per GPU it runs on, held until the process ends).  The call allocates nothing and frees
+ * nothing.  A batch whose relserve_workspace_bytes exceeds the array (the 13B shape up to 256 query
+ * tokens, the 70B shape up to 128) is refused with RELSERVE_ERR_TOO_LARGE and nothing is launched.  Every
+ * call on a GPU uses that GPU's one array: calls that may overlap on one GPU (two streams, two threads)
+ * race; the array is pure scratch (written before it is read), so nothing has to be cleared between
+ * calls.  relserve_static_scratch_bytes reports the size. */
+#define RELSERVE_STATIC_SCRATCH_BYTES (64u << 20)
+int32_t relserve_static_scratch_bytes(size_t* out);
+int32_t relserve_layer_step_static(const relserve_layer* layer, const relserve_batch* batch,
+                                   const relserve_layer_weights* weights,
+                                   const void* x, void* y, relserve_kv_cache cache, void* stream);
 
 /* A stack of n_layers identical-shape layers between an embedding table and an
  * output layer (Sec. 2.3 "LLM Inference": the output layer turns the final

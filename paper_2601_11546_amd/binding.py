@@ -30,7 +30,7 @@ PROFILE_SLOTS = 12
 EXPORTS = ["relserve_version", "relserve_strerror", "relserve_config_validate", "relserve_layer_create",
            "relserve_layer_destroy", "relserve_batch_validate", "relserve_batch_slots", "relserve_batch_prepare",
            "relserve_batch_destroy", "relserve_batch_get_info", "relserve_workspace_bytes", "relserve_kv_append",
-           "relserve_layer_step", "relserve_model_workspace_bytes", "relserve_model_step", "relserve_rmsnorm", "relserve_linear", "relserve_rope_append",
+           "relserve_layer_step", "relserve_layer_step_static", "relserve_static_scratch_bytes", "relserve_model_workspace_bytes", "relserve_model_step", "relserve_rmsnorm", "relserve_linear", "relserve_rope_append",
            "relserve_qkv_rope_append",
            "relserve_attention", "relserve_profile_slot_name", "relserve_profile_enable", "relserve_profile_read",
            "relserve_debug_force_gemm_plan", "relserve_peak_probe_mfma", "relserve_peak_probe_stream",
@@ -111,6 +111,8 @@ for _n, _a in {
     "relserve_kv_append": [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, KVCache, C.c_void_p],
     "relserve_layer_step": [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, KVCache,
                             C.c_void_p, C.c_size_t, C.c_void_p],
+    "relserve_layer_step_static": [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, KVCache, C.c_void_p],
+    "relserve_static_scratch_bytes": [C.c_void_p],
     "relserve_model_workspace_bytes": [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p],
     "relserve_model_step": [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t,
                             C.c_void_p],
@@ -286,6 +288,18 @@ def relserve_layer_step(layer, pbatch, weights: dict, x, y, k_pages, v_pages, wo
                                     _cache(k_pages, v_pages), _ptr(workspace),
                                     workspace.numel() * workspace.element_size(), _stream(stream)),
            "relserve_layer_step")
+
+
+def relserve_layer_step_static(layer, pbatch, weights: dict, x, y, k_pages, v_pages, stream=None) -> None:
+    wt = _weights(weights)
+    _check(_lib.relserve_layer_step_static(layer.handle, pbatch.handle, C.byref(wt), _ptr(x), _ptr(y),
+                                           _cache(k_pages, v_pages), _stream(stream)), "relserve_layer_step_static")
+
+
+def relserve_static_scratch_bytes() -> int:
+    out = C.c_size_t()
+    _check(_lib.relserve_static_scratch_bytes(C.byref(out)), "relserve_static_scratch_bytes")
+    return int(out.value)
 
 
 def relserve_model_workspace_bytes(layer: Layer, max_tokens: int, max_reqs: int) -> int:

@@ -3,6 +3,7 @@
 #include <algorithm>
 #include <cmath>
 #include <cstring>
+#include <mutex>
 #include <new>
 
 #include "relserve_internal.h"
@@ -55,6 +56,29 @@ Workspace carve(const relserve_layer& L, int64_t T, void* base) {
 }
 
 bool is_pow2(int32_t v) { return v > 0 && (v & (v - 1)) == 0; }
+
+// Workspace of relserve_layer_step_static: a fixed array in device memory, one copy per GPU the library runs on,
+// held until the process ends.  `scratch` is only a host-side stand-in for the symbol: the device address comes
+// from hipGetSymbolAddress, once per device, and only that address is handed to kernels.
+constexpr size_t kStaticScratchBytes = (size_t)RELSERVE_STATIC_SCRATCH_BYTES;
+__device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+int32_t static_scratch(void** out) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess) return RELSERVE_ERR_NO_DEVICE;
+    if (dev < 0 || dev >= kMaxDevices) return RELSERVE_ERR_BAD_ARGUMENT;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return RELSERVE_ERR_HIP;
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return RELSERVE_OK;
+}
 
 int32_t check_cache(const relserve_batch* b, const relserve_kv_cache& cache) {
     if (!cache.k_pages || !cache.v_pages) return RELSERVE_ERR_NULL_POINTER;
@@ -243,7 +267,7 @@ const char* relserve_strerror(int32_t s) {
         case RELSERVE_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
         case RELSERVE_ERR_HIP: return "HIP runtime error";
         case RELSERVE_ERR_NO_DEVICE: return "no gfx950 device";
-        case RELSERVE_ERR_TOO_LARGE: return "size exceeds 32-bit device indices";
+        case RELSERVE_ERR_TOO_LARGE: return "size exceeds 32-bit device indices or the fixed scratch";
         case RELSERVE_ERR_MISMATCH: return "batch / layer / cache do not belong together";
         case RELSERVE_ERR_BAD_ARGUMENT: return "bad argument";
         default: return "unknown status";
@@ -574,6 +598,22 @@ int32_t relserve_layer_step(const relserve_layer* L, const relserve_batch* b, co
     });
     run(S_DOWN, [&] { return launch_linear(w.act, wt->w_down, T, c.hidden, c.mlp_dim, 2, w.x1, y, s, accum, packed); });
     return e == hipSuccess ? RELSERVE_OK : RELSERVE_ERR_HIP;
+}
+
+int32_t relserve_static_scratch_bytes(size_t* out) {
+    if (!out) return RELSERVE_ERR_NULL_POINTER;
+    *out = kStaticScratchBytes;
+    return RELSERVE_OK;
+}
+
+int32_t relserve_layer_step_static(const relserve_layer* L, const relserve_batch* b, const relserve_layer_weights* wt,
+                                   const void* x, void* y, relserve_kv_cache cache, void* stream) {
+    drop_stale_hip_error();
+    if (int32_t rc = check_pair(L, b)) return rc;
+    if (carve(*L, b->dev.T, nullptr).total > kStaticScratchBytes) return RELSERVE_ERR_TOO_LARGE;
+    void* ws = nullptr;
+    if (int32_t rc = static_scratch(&ws)) return rc;
+    return relserve_layer_step(L, b, wt, x, y, cache, ws, kStaticScratchBytes, stream);
 }
 
 int32_t relserve_model_workspace_bytes(const relserve_layer* L, int32_t max_tokens, int32_t max_reqs, size_t* out) {

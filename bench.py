@@ -171,7 +171,7 @@ def peak_probes(rs, torch) -> dict:
         best_gb = max(best_gb, buf.numel() / (e0.elapsed_time(e1) * 1e-3) / 1e9)
     del buf
     return {"mfma_issue_loop_tflops": round(best_tf, 1), "stream_read_gbs": round(best_gb, 1),
-            "note": "random bf16 operands, 16 independent accumulators per wave; 4 GiB read with 16-byte loads"}
+            "note": "random bf16 operands, 16 independent accumulators per wave; 4 GiB read with 16-byte non-temporal loads"}
 
 
 def model_step_bench(args, rs, W, torch) -> dict:

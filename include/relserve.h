@@ -353,13 +353,14 @@ int32_t relserve_starved_priority(double priority, double waiting_seconds, int32
 int32_t relserve_peak_probe_mfma(void* sink, int32_t iters, double* flops, void* stream);
 int32_t relserve_peak_probe_stream(const void* src, size_t bytes, void* sink, void* stream);
 
-/* ---- test hook ----
- * Forces the tile shape and the tail split of every later GEMM launch of this process:
- * tile = 0..4 (256x256, 192x256, 128x256, 128x128, 64x128 tokens x features), 5..9 = eight-wave
- * variants of 256x256 (5, 6, 7), 192x256 (8) and 128x256 (9); -1 = automatic choice.  tail_splits
- * = 2..8 makes the tiles of the incomplete last round split their k range that many ways (0 or 1 =
- * whole tiles only).  Shapes a tile cannot serve (the fused q/k/v epilogue needs 256 features per
- * tile) fall back to the nearest one that can.  Process-wide, not thread-safe; for tests and tuning. */
+/* ---- test hook (the only one; not part of the serving interface) ----
+ * Forces the tile shape and the tail split of every later GEMM launch of this process, so that tests can
+ * drive each tile shape and the split-tail path on shapes the automatic choice would serve otherwise:
+ * tile = 0..4 (256x256, 192x256, 128x256, 128x128, 64x128 tokens x features), -1 = automatic choice.
+ * tail_splits = 2..8 makes the tiles of the incomplete last round split their k range that many ways
+ * (0 or 1 = whole tiles only).  Shapes a tile cannot serve (the fused q/k/v epilogue needs 256 features per
+ * tile) fall back to the nearest one that can.  Process-wide; the setting is one atomic word, so a launch
+ * on another host thread sees either the old or the new pair. */
 int32_t relserve_debug_force_gemm_plan(int32_t tile, int32_t tail_splits);
 
 /* ---- per-kernel timing with HIP events on the caller's stream ---- */

@@ -17,9 +17,8 @@
 // workgroups; batches of at most 256 tokens, and narrow outputs at a few hundred, split k everywhere.
 // Every split writes partial tiles to fp32 slabs that a second kernel sums and finishes.
 #include <algorithm>
-#include <cstdio>
-#include <cstdlib>
-#include <cstring>
+#include <atomic>
+#include <mutex>
 #include <type_traits>
 
 #include "device_utils.h"
@@ -62,23 +61,20 @@ struct GemmArgs {
     float* tail_buf;
 };
 
-#ifndef RELSERVE_DMA_BK
-#define RELSERVE_DMA_BK 64
-#endif
-#ifndef RELSERVE_DMA_NS
-#define RELSERVE_DMA_NS 2
-#endif
+// Test hook (relserve_debug_force_gemm_plan): tile candidate (index into kTiles) and tail splits every launch
+// must use; -1 = cost model.  One word, so that a launch on another host thread sees a consistent pair.
+std::atomic<int> g_forced_plan{-1};   // -1, or cand | splits << 8
+inline int forced_cand() { const int v = g_forced_plan.load(std::memory_order_relaxed); return v < 0 ? -1 : (v & 0xff); }
+inline int forced_splits() { const int v = g_forced_plan.load(std::memory_order_relaxed); return v < 0 ? 0 : (v >> 8); }
 
-// Test hook: route every shape through the register-staged kernel (set from RELSERVE_GEMM_GENERIC=1).
-bool g_force_generic = getenv("RELSERVE_GEMM_GENERIC") != nullptr;
-// Test hook: tile candidate (index into kTiles) and tail splits every launch must use; -1 = cost model.
-// Initialised from RELSERVE_GEMM_TILE="cand" or "cand,splits".
-int g_force_cand = [] { const char* e = getenv("RELSERVE_GEMM_TILE"); return e ? atoi(e) : -1; }();
-int g_force_splits = [] {
-    const char* e = getenv("RELSERVE_GEMM_TILE");
-    const char* comma = e ? strchr(e, ',') : nullptr;
-    return comma ? atoi(comma + 1) : 0;
-}();
+// The dynamic-LDS limit of a kernel is raised once per process, whichever host thread launches it first.
+template <typename Kernel>
+hipError_t allow_smem_once(std::once_flag& once, hipError_t& status, Kernel kernel, int bytes) {
+    std::call_once(once, [&] {
+        status = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    });
+    return status;
+}
 
 enum { EPI_BF16 = 0, EPI_RES_BF16_OUT_F32 = 1, EPI_RES_F32_OUT_BF16 = 2, EPI_SWIGLU = 3, EPI_QKV_ROPE = 4, EPI_SLAB = 5 };
 
@@ -367,14 +363,22 @@ __global__ void __launch_bounds__(256) gemm_bf16_kernel(GemmArgs p) {
 // k iteration to land.
 // ------------------------------------------------------------------------------------------
 // 64 lanes x 16 bytes from (base + per-lane byte offset) to 1 KB of LDS starting at lds_addr.
+// NT = non-temporal: for bytes that are read once (the weights of a batch of one token tile).  A streaming read of
+// HBM reaches 7.1-7.4 TB/s with the hint against 6.3-6.4 TB/s without (measured with 32 KB per workgroup in flight);
+// operands that other workgroups read again keep the default policy, which lets the L2 hold them.
+template <bool NT = false>
 __device__ __forceinline__ void dma16(const void* base, uint32_t voff, uint32_t lds_addr) {
-    asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(base), "s"(lds_addr) : "memory");
+    if (NT)
+        asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1 nt" ::"v"(voff), "s"(base), "s"(lds_addr) : "memory");
+    else
+        asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(base), "s"(lds_addr) : "memory");
 }
 
 // BKD = k extent of one LDS stage (64 or 32), NS = stages in the ring (NS - 1 are in flight).
 // WGM x WGN = grid of waves over the tile (4 or 8 waves; 8 waves = two per SIMD, each with a quarter
 // of the registers, so that one wave's MFMAs cover the other's memory-instruction issue).
-template <int BM, int BN, int EPI, int D, int BKD, int NS, int WGM = 2, int WGN = 2>
+// WNT: the weights are loaded with the non-temporal hint (launches in which no other workgroup reads them again).
+template <int BM, int BN, int EPI, int D, int BKD, int NS, int WGM = 2, int WGN = 2, bool WNT = false>
 __global__ void __launch_bounds__(64 * WGM * WGN) gemm_dma_kernel(GemmArgs p) {
     constexpr int NW = WGM * WGN;
     constexpr int TM = BM / (32 * WGM), TN = BN / (32 * WGN);
@@ -463,7 +467,7 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_dma_kernel(GemmArgs p) {
 #pragma unroll
         for (int j = 0; j < A_IT; ++j) dma16(abase, a_voff[j], la + j * (NW * 1024));
 #pragma unroll
-        for (int j = 0; j < W_IT; ++j) dma16(wbase, w_voff[j], la + A_BYTES + j * (NW * 1024));
+        for (int j = 0; j < W_IT; ++j) dma16<WNT>(wbase, w_voff[j], la + A_BYTES + j * (NW * 1024));
     };
 
     // ---- LDS -> MFMA operand offsets
@@ -530,8 +534,8 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_dma_kernel(GemmArgs p) {
         // weights first: they come from further away (HBM) than the activations (L2)
         const uint32_t la = lds0 + stage * STAGE + wave * 1024;
         if (i < W_IT)
-            dma16(reinterpret_cast<const char*>(p.w) + (p.w_packed ? (size_t)(k0 >> 6) * 32768 + (size_t)(k0 & 63) * 2 : (size_t)k0 * 2), w_voff[i],
-                  la + A_BYTES + i * (NW * 1024));
+            dma16<WNT>(reinterpret_cast<const char*>(p.w) + (p.w_packed ? (size_t)(k0 >> 6) * 32768 + (size_t)(k0 & 63) * 2 : (size_t)k0 * 2), w_voff[i],
+                       la + A_BYTES + i * (NW * 1024));
         else
             dma16(reinterpret_cast<const char*>(p.a) + (size_t)k0 * 2, a_voff[i - W_IT], la + (i - W_IT) * (NW * 1024));
     };
@@ -764,25 +768,21 @@ __global__ void __launch_bounds__(256) gemm_finish_kernel(GemmArgs p) {
 // BM x BN tile (BM = 64 / 128 tokens, BN = 128 / 256 features) is split over several workgroups, each
 // storing its partial tile to its split's slab.  The LDS ring is as deep as 160 KB allow (one workgroup
 // per CU); all stages but the one being computed are in flight.
-template <int BM, int EPI, int D, int BN = 256>
+template <int BM, int EPI, int D, int BN = 256, bool WNT = false>
 hipError_t launch_split(GemmArgs p, int splits, hipStream_t s) {
     constexpr int NS = BM + BN <= 192 ? 6 : BM + BN <= 256 ? 4 : BM + BN <= 320 ? 4 : BM + BN <= 384 ? 3 : 2;
     constexpr int smem = NS * (BM + BN) * 64 * 2;
     static_assert(smem <= 160 * 1024, "ring exceeds the LDS");
-    static bool attr_done = false;
-    if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_dma_kernel<BM, BN, EPI_SLAB, 0, 64, NS>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, smem);
-        if (e != hipSuccess) return e;
-        attr_done = true;
-    }
+    static std::once_flag once;
+    static hipError_t attr_status = hipSuccess;
+    if (hipError_t e = allow_smem_once(once, attr_status, &gemm_dma_kernel<BM, BN, EPI_SLAB, 0, 64, NS, 2, 2, WNT>, smem)) return e;
     p.tiles_m = (p.T + BM - 1) / BM;
     p.tiles_n = (p.N + BN - 1) / BN;
     const int nk = p.K / 64;
     p.k_per_split = (nk + splits - 1) / splits;
     splits = (nk + p.k_per_split - 1) / p.k_per_split;   // no empty split: the finish kernel reads every slab
     p.n_splits = splits;
-    gemm_dma_kernel<BM, BN, EPI_SLAB, 0, 64, NS><<<dim3(p.tiles_m * p.tiles_n * splits), dim3(256), smem, s>>>(p);
+    gemm_dma_kernel<BM, BN, EPI_SLAB, 0, 64, NS, 2, 2, WNT><<<dim3(p.tiles_m * p.tiles_n * splits), dim3(256), smem, s>>>(p);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     int64_t units;
@@ -807,25 +807,21 @@ int choose_splits(int T, int N, int K, int BM, int BN = 256) {
 
 // The fused kernel on 128-feature tiles with a deep ring, one workgroup per CU: for a skinny GEMM whose
 // tiles fill the CUs without any k split (the gate/up projection), so no slabs and no finish kernel.
-template <int BM, int EPI, int D = 0, int BN = 128>
+template <int BM, int EPI, int D = 0, int BN = 128, bool WNT = true>
 hipError_t launch_skinny_whole(GemmArgs p, hipStream_t s) {
     // (256 x 256 tiles have room for two 64-k stages only; four 32-k stages measured no faster)
     constexpr int BKD = 64;
     constexpr int NS = BM + BN <= 192 ? 6 : BM + BN <= 256 ? 4 : BM + BN <= 384 ? 3 : 2;
     constexpr int smem = NS * (BM + BN) * BKD * 2;
     static_assert(smem <= 160 * 1024, "ring exceeds the LDS");
-    static bool attr_done = false;
-    if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_dma_kernel<BM, BN, EPI, D, BKD, NS>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, smem);
-        if (e != hipSuccess) return e;
-        attr_done = true;
-    }
+    static std::once_flag once;
+    static hipError_t attr_status = hipSuccess;
+    if (hipError_t e = allow_smem_once(once, attr_status, &gemm_dma_kernel<BM, BN, EPI, D, BKD, NS, 2, 2, WNT>, smem)) return e;
     p.tiles_m = (p.T + BM - 1) / BM;
     p.tiles_n = EPI == EPI_SWIGLU ? (p.n_half + BN / 2 - 1) / (BN / 2) : (p.N + BN - 1) / BN;
     p.tail_tiles = 0;
     p.tail_splits = 1;
-    gemm_dma_kernel<BM, BN, EPI, D, BKD, NS><<<dim3(p.tiles_m * p.tiles_n), dim3(256), smem, s>>>(p);
+    gemm_dma_kernel<BM, BN, EPI, D, BKD, NS, 2, 2, WNT><<<dim3(p.tiles_m * p.tiles_n), dim3(256), smem, s>>>(p);
     return hipGetLastError();
 }
 
@@ -840,8 +836,8 @@ hipError_t launch_skinny(const GemmArgs& p, hipStream_t s) {
             if (tiles >= 0.8 * 256 * rounds)
                 return p.T <= 64 ? launch_skinny_whole<64, EPI>(p, s) : launch_skinny_whole<128, EPI>(p, s);
         }
-        if (p.T <= 64) return launch_split<64, EPI, D, 128>(p, choose_splits(p.T, p.N, p.K, 64, 128), s);
-        return launch_split<128, EPI, D, 128>(p, choose_splits(p.T, p.N, p.K, 128, 128), s);
+        if (p.T <= 64) return launch_split<64, EPI, D, 128, true>(p, choose_splits(p.T, p.N, p.K, 64, 128), s);
+        return launch_split<128, EPI, D, 128, true>(p, choose_splits(p.T, p.N, p.K, 128, 128), s);
     }
     // two token tiles: 256-feature tiles; a projection wide enough to need no k split runs the fused kernel
     const int splits = choose_splits(p.T, p.N, p.K, 128);
@@ -852,11 +848,11 @@ hipError_t launch_skinny(const GemmArgs& p, hipStream_t s) {
         if (p.T > 192 && tiles256 >= 200 && tiles256 <= 256) return launch_skinny_whole<256, EPI, D, 256>(p, s);
         return launch_skinny_whole<128, EPI, D, 256>(p, s);
     }
-    return launch_split<128, EPI, D>(p, splits, s);
+    return launch_split<128, EPI, D, 256, true>(p, splits, s);
 }
 
 bool skinny_applies(int T, int N, int K, const float* accum) {
-    return accum != nullptr && T <= SKINNY_MAX_T && K % 64 == 0 && N % 4 == 0 && !g_force_generic;
+    return accum != nullptr && T <= SKINNY_MAX_T && K % 64 == 0 && N % 4 == 0;
 }
 
 // Mid-size batches on a narrow output (W_o and W_down at a few hundred tokens): whole tiles are too few
@@ -866,8 +862,7 @@ bool skinny_applies(int T, int N, int K, const float* accum) {
 // and k is long.  Returns the tile rows, 0 = not this path.  The slabs (at most 256 units x 256 x 256
 // floats) use the tail scratch.
 int split_rows(int T, int N, int K, bool has_accum) {
-    static const bool off = getenv("RELSERVE_GEMM_NOSPLIT") != nullptr;   // tuning hook
-    if (off || !has_accum || T <= SKINNY_MAX_T || K % 64 || N % 4 || g_force_generic || g_force_cand >= 0) return 0;
+    if (!has_accum || T <= SKINNY_MAX_T || K % 64 || N % 4 || forced_cand() >= 0) return 0;
     const int tn = (N + 255) / 256;
     if (((T + 127) / 128) * tn <= 128) return 128;
     if (((T + 255) / 256) * tn <= 85 && K >= 8192) return 256;
@@ -890,21 +885,15 @@ hipError_t launch_cfg(const GemmArgs& base, hipStream_t s, const Plan& plan = Pl
     p.tiles_n = EPI == EPI_SWIGLU ? (p.n_half + BN / 2 - 1) / (BN / 2) : (p.N + BN - 1) / BN;
     constexpr int smem = 2 * (BM + BN) * BK * 2;
     // 128 x 256 tiles are one workgroup per CU either way, so they take the third stage that fits (144 KB)
-    constexpr int DMA_BK = RELSERVE_DMA_BK, DMA_NS = (BM == 128 && BN == 256 && RELSERVE_DMA_NS == 2) ? 3 : RELSERVE_DMA_NS;
+    constexpr int DMA_BK = 64, DMA_NS = (BM == 128 && BN == 256) ? 3 : 2;
     constexpr int dma_smem = DMA_NS * (BM + BN) * DMA_BK * 2;
-    static bool attr_done = false;
-    if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_bf16_kernel<BM, BN, EPI, D>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, smem);
-        if (e == hipSuccess)
-            e = hipFuncSetAttribute(
-                reinterpret_cast<const void*>(&gemm_dma_kernel<BM, BN, EPI, D, DMA_BK, DMA_NS, WGM, WGN>),
-                hipFuncAttributeMaxDynamicSharedMemorySize, dma_smem);
-        if (e != hipSuccess) return e;
-        attr_done = true;
-    }
+    static std::once_flag once_generic, once_dma;
+    static hipError_t st_generic = hipSuccess, st_dma = hipSuccess;
+    if (hipError_t e = allow_smem_once(once_generic, st_generic, &gemm_bf16_kernel<BM, BN, EPI, D>, smem)) return e;
+    if (hipError_t e = allow_smem_once(once_dma, st_dma, &gemm_dma_kernel<BM, BN, EPI, D, DMA_BK, DMA_NS, WGM, WGN>, dma_smem))
+        return e;
     const int tiles = p.tiles_m * p.tiles_n;
-    if (p.K % 64 == 0 && !g_force_generic) {
+    if (p.K % 64 == 0) {
         int grid = tiles;
         if (plan.tail_tiles > 0 && plan.splits > 1 && p.accum && p.T > SKINNY_MAX_T) {
             const int nk = p.K / 64;
@@ -938,10 +927,7 @@ struct TileCand { int bm, bn, wg_per_cu; float eff; bool qkv; };   // qkv: usabl
 constexpr TileCand kTiles[] = {
     // efficiencies from per-round times of forced plans at T = 288 ... 1282 on the 13B layer's projections
     {256, 256, 1, 1.00f, true}, {192, 256, 1, 0.92f, true}, {128, 256, 1, 0.68f, true}, {128, 128, 2, 0.76f, false},
-    {64, 128, 3, 0.60f, false},
-    // 8-wave variants, only by the test hook: 5 = 256 x 256 (4 x 2 waves), 6 = (2 x 4), 7 = 16 waves, 8 = 192 x 256, 9 = 128 x 256
-    {256, 256, 1, 0.0f, true}, {256, 256, 1, 0.0f, false}, {256, 256, 1, 0.0f, false}, {192, 256, 1, 0.0f, false},
-    {128, 256, 1, 0.0f, false}};
+    {64, 128, 3, 0.60f, false}};
 
 // A tail (the tiles of the incomplete last round) may split its k range over workgroups, so that the
 // round takes 1 / splits of a tile time; the price is that every partial tile is written to memory
@@ -950,22 +936,10 @@ constexpr double kCuFlops = 5.2e12;          // sustained MFMA rate of one CU in
 constexpr double kSlabBytesPerSec = 3.0e12;  // partial tiles through memory (written by the GEMM, read by the finish kernel)
 constexpr double kTailFinishSec = 6e-6;      // the finish kernel's launch and ramp
 
-Plan choose_plan_impl(int T, int64_t n_eff, int K, bool need_bn256, bool allow_tail);
 Plan choose_plan(int T, int64_t n_eff, int K, bool need_bn256, bool allow_tail) {
-    static const bool debug = getenv("RELSERVE_GEMM_DEBUG") != nullptr;   // print every choice
-    static const bool no_tail = getenv("RELSERVE_GEMM_NOTAIL") != nullptr;   // tuning hook: whole tiles only
-    allow_tail = allow_tail && !no_tail;
-    const Plan p = choose_plan_impl(T, n_eff, K, need_bn256, allow_tail);
-    if (debug)
-        fprintf(stderr, "[gemm] T=%d N=%lld K=%d qkv=%d tail_ok=%d -> tile %d (%dx%d) tail_tiles=%d splits=%d\n", T,
-                (long long)n_eff, K, (int)need_bn256, (int)allow_tail, p.cand, kTiles[p.cand].bm, kTiles[p.cand].bn,
-                p.tail_tiles, p.splits);
-    return p;
-}
-
-Plan choose_plan_impl(int T, int64_t n_eff, int K, bool need_bn256, bool allow_tail) {
     const int n_cand = (int)(sizeof(kTiles) / sizeof(kTiles[0]));
-    const bool force = g_force_cand >= 0 && g_force_cand < n_cand;
+    const int f_cand = forced_cand(), f_splits = forced_splits();
+    const bool force = f_cand >= 0 && f_cand < n_cand;
     Plan best{0, 0, 1};
     double best_cost = 1e300;
     for (int i = 0; i < n_cand; ++i) {
@@ -973,12 +947,10 @@ Plan choose_plan_impl(int T, int64_t n_eff, int K, bool need_bn256, bool allow_t
         int forced_splits = 0;
         if (need_bn256 && !c.qkv) continue;
         if (force) {
-            if (g_force_cand != i && !(need_bn256 && !kTiles[g_force_cand].qkv)) continue;
-            if (g_force_cand == i) forced_splits = g_force_splits;
-        } else if (c.eff <= 0.f) {
-            continue;
+            if (f_cand != i && !(need_bn256 && !kTiles[f_cand].qkv)) continue;
+            if (f_cand == i) forced_splits = f_splits;
         }
-        const double eff = c.eff > 0.f ? c.eff : 1.0;
+        const double eff = c.eff;
         const int64_t tiles = ((T + c.bm - 1) / c.bm) * ((n_eff + c.bn - 1) / c.bn);
         const int64_t slots = 256 * c.wg_per_cu;
         // resident workgroups of a CU share its MFMA pipes: a round of wg_per_cu tiles costs wg_per_cu tile times
@@ -1014,13 +986,6 @@ hipError_t launch_epi(const GemmArgs& p, hipStream_t s) {
         case 1: return launch_cfg<192, 256, EPI>(p, s, plan);
         case 2: return launch_cfg<128, 256, EPI>(p, s, plan);
         case 3: return launch_cfg<128, 128, EPI>(p, s, plan);
-        case 5: return launch_cfg<256, 256, EPI, 0, 4, 2>(p, s, plan);
-        case 6: return launch_cfg<256, 256, EPI, 0, 2, 4>(p, s, plan);
-        case 7: return launch_cfg<256, 256, EPI, 0, 4, 4>(p, s, plan);
-#if RELSERVE_DMA_BK == 64
-        case 8: return launch_cfg<192, 256, EPI, 0, 2, 4>(p, s, plan);
-        case 9: return launch_cfg<128, 256, EPI, 0, 2, 4>(p, s, plan);
-#endif
         default: return launch_cfg<64, 128, EPI>(p, s, plan);
     }
 }
@@ -1028,8 +993,7 @@ hipError_t launch_epi(const GemmArgs& p, hipStream_t s) {
 }  // namespace
 
 void gemm_force_plan(int cand, int splits) {
-    g_force_cand = cand;
-    g_force_splits = splits;
+    g_forced_plan.store(cand < 0 ? -1 : (cand | (splits << 8)), std::memory_order_relaxed);
 }
 
 int64_t gemm_scratch_floats(int64_t T, int64_t n_max) {
@@ -1066,7 +1030,7 @@ hipError_t launch_linear(const void* a, const void* w, int32_t T, int32_t N, int
     if ((int64_t)T * K >= ((int64_t)1 << 31) || (int64_t)N * K >= ((int64_t)1 << 31)) return hipErrorInvalidValue;
     if (epilogue != EPI_SWIGLU && (N % 4)) return hipErrorInvalidValue;
     if (epilogue == EPI_SWIGLU && ((N / 2) % 8)) return hipErrorInvalidValue;
-    if (w_packed && (K % 64 || g_force_generic)) return hipErrorInvalidValue;   // only the direct-to-LDS kernel reads it
+    if (w_packed && K % 64) return hipErrorInvalidValue;   // only the direct-to-LDS kernel reads it
     GemmArgs p{};
     p.w_packed = w_packed;
     p.a = static_cast<const uint16_t*>(a);
@@ -1113,7 +1077,6 @@ hipError_t launch_qkv_d(const GemmArgs& p, hipStream_t s) {
     switch (plan.cand) {
         case 0: return launch_cfg<256, 256, EPI_QKV_ROPE, D>(p, s, plan);
         case 1: return launch_cfg<192, 256, EPI_QKV_ROPE, D>(p, s, plan);
-        case 5: return launch_cfg<256, 256, EPI_QKV_ROPE, D, 4, 2>(p, s, plan);
         default: return launch_cfg<128, 256, EPI_QKV_ROPE, D>(p, s, plan);
     }
 }
@@ -1127,7 +1090,7 @@ hipError_t launch_qkv_rope_append(const BatchDev& b, const relserve_layer& L, co
     if ((int64_t)b.T * K >= ((int64_t)1 << 31) || (int64_t)L.qkv_dim * K >= ((int64_t)1 << 31))
         return hipErrorInvalidValue;
     GemmArgs p{};
-    if (w_packed && (K % 64 || g_force_generic)) return hipErrorInvalidValue;
+    if (w_packed && K % 64) return hipErrorInvalidValue;
     p.w_packed = w_packed;
     p.a = static_cast<const uint16_t*>(h);
     p.w = static_cast<const uint16_t*>(w_qkv);

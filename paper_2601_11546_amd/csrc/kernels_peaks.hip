@@ -1,6 +1,6 @@
 // Probes of what this GPU sustains, for reporting beside the published peaks: a wave-level issue loop of
 // independent 32x32x16 bf16 MFMAs on random operands (no memory traffic), and a streaming read of a large
-// buffer (16-byte loads, many in flight).  They share nothing with the layer kernels.
+// buffer (16-byte non-temporal loads, 32 KB per workgroup in flight).  They share nothing with the layer kernels.
 #include "device_utils.h"
 #include "relserve_internal.h"
 
@@ -36,20 +36,25 @@ __global__ void __launch_bounds__(256) mfma_issue_kernel(float* sink, int iters,
     if (s == 12345.678f) sink[0] = s;   // keeps the loop alive, never true in practice
 }
 
-// Every thread walks the buffer with a grid stride, eight 16-byte loads in flight per thread.
-__global__ void __launch_bounds__(256) stream_read_kernel(const uint4* src, int64_t n16, uint32_t* sink) {
-    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+// Workgroups take 32 KB pieces of the buffer in turn: eight 16-byte loads in flight per thread, each wave load 1 KB of
+// consecutive memory, with the non-temporal hint (the bytes are read once).  Of the patterns tried (grid-stride or
+// contiguous pieces, 4 to 16 loads in flight, 256 to 8192 workgroups, with and without the hint) this one reads fastest:
+// 7.0-7.3 TB/s, against 5.6-6.4 TB/s for the same loads without the hint.
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+__global__ void __launch_bounds__(256) stream_read_kernel(const u32x4_t* src, int64_t n16, uint32_t* sink) {
+    constexpr int U = 8;
+    const int64_t per = 256 * U, n_pieces = n16 / per;
     uint32_t acc = 0;
-    for (; i + 7 * stride < n16; i += 8 * stride) {
-        uint4 v[8];
+    for (int64_t c = blockIdx.x; c < n_pieces; c += gridDim.x) {
+        const u32x4_t* p = src + c * per + threadIdx.x;
+        u32x4_t v[U];
 #pragma unroll
-        for (int j = 0; j < 8; ++j) v[j] = src[i + j * stride];
+        for (int j = 0; j < U; ++j) v[j] = __builtin_nontemporal_load(p + j * 256);
 #pragma unroll
-        for (int j = 0; j < 8; ++j) acc ^= v[j].x ^ v[j].y ^ v[j].z ^ v[j].w;
+        for (int j = 0; j < U; ++j) acc ^= v[j].x ^ v[j].y ^ v[j].z ^ v[j].w;
     }
-    for (; i < n16; i += stride) {
-        const uint4 v = src[i];
+    for (int64_t i = n_pieces * per + (int64_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += (int64_t)gridDim.x * 256) {
+        const u32x4_t v = src[i];
         acc ^= v.x ^ v.y ^ v.z ^ v.w;
     }
     if (acc == 0x9e3779b9u) sink[0] = acc;   // keeps the loads alive
@@ -63,7 +68,7 @@ hipError_t launch_peak_mfma(float* sink, int32_t iters, hipStream_t s) {
 }
 
 hipError_t launch_peak_stream(const void* src, int64_t bytes, uint32_t* sink, hipStream_t s) {
-    stream_read_kernel<<<dim3(256 * 8), dim3(256), 0, s>>>(static_cast<const uint4*>(src), bytes / 16, sink);
+    stream_read_kernel<<<dim3(512), dim3(256), 0, s>>>(static_cast<const u32x4_t*>(src), bytes / 16, sink);
     return hipGetLastError();
 }
 

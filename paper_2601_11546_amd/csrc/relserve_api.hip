@@ -682,7 +682,7 @@ int32_t relserve_peak_probe_stream(const void* src, size_t bytes, void* sink, vo
 }
 
 int32_t relserve_debug_force_gemm_plan(int32_t tile, int32_t tail_splits) {
-    if (tile < -1 || tile > 9 || tail_splits < 0 || tail_splits > 8) return RELSERVE_ERR_BAD_ARGUMENT;
+    if (tile < -1 || tile > 4 || tail_splits < 0 || tail_splits > 8) return RELSERVE_ERR_BAD_ARGUMENT;
     gemm_force_plan(tile, tail_splits);
     return RELSERVE_OK;
 }

@@ -384,7 +384,7 @@ def test_full_size_relquery_13b(rs, oracle):
     _sampled_parity(rs, oracle, wl, [0, 7, 15, 16, 17, 99, 150, 199])
 
 
-@pytest.mark.parametrize("tile,splits", [(0, 2), (1, 3), (5, 2)], ids=["256x256/2", "192x256/3", "256x256-8w/2"])
+@pytest.mark.parametrize("tile,splits", [(0, 2), (1, 3)], ids=["256x256/2", "192x256/3"])
 def test_full_size_relquery_13b_forced_tail_split(rs, oracle, tile, splits):
     """The tiles of the incomplete last round split their k range over workgroups (partial tiles through the
     fp32 scratch, summed in split order by the finish kernel); here forced for every GEMM of the step."""
@@ -767,6 +767,51 @@ def test_full_size_decode_only_13b_packed(rs, oracle):
 
 def test_full_size_prefill_only_13b_packed(rs, oracle):
     _sampled_parity(rs, oracle, W.workload_prefill_only_13b(), [0, 63], max_prefill_rows=24, packed=True)
+
+
+def test_two_host_threads_step_concurrently(rs):
+    """Two host threads, each with its own stream, workspace, cache and output, run layer steps at the same time
+    (ctypes releases the interpreter lock during a call): the results are those of the same steps run one after the
+    other.  Different batch sizes, so that the threads launch different kernels, some of them for the first time."""
+    import threading
+    shape = W.LayerShape(1024, 8, 2, 128, 2048)
+    weights = {k: dev_bf16(v) for k, v in W.make_weights(shape, 21).items()}
+    layer = rs.relserve_layer_create(shape)
+    cases = []
+    for i, q_len in enumerate(([1] * 70, [300, 1, 1, 211], [1] * 200, [90, 40])):
+        ctx = [q + 37 * (j % 5) for j, q in enumerate(q_len)]
+        b = W.build_batch(shape, q_len, ctx, seed=30 + i)
+        kp, vp = W.make_cache(shape, b.num_pages, 40 + i)
+        cases.append({"pb": rs.relserve_batch_prepare(layer, b), "x": dev_bf16(W.make_activations(b.T, shape.hidden, 50 + i)),
+                      "kv": (kp, vp), "T": b.T})
+
+    def run(case, stream, out):
+        kd, vd = dev_bf16(case["kv"][0]), dev_bf16(case["kv"][1])
+        ws = torch.empty(rs.relserve_workspace_bytes(layer, case["T"]), dtype=torch.uint8, device="cuda")
+        y = torch.empty_like(case["x"])
+        torch.cuda.synchronize()
+        for _ in range(10):
+            rs.relserve_layer_step(layer, case["pb"], weights, case["x"], y, kd, vd, ws, stream=stream)
+        stream.synchronize()
+        out.append((host_bits(y), host_bits(kd), host_bits(vd)))
+
+    serial = []
+    for c in cases:
+        o = []
+        run(c, torch.cuda.current_stream(), o)
+        serial.append(o[0])
+    for first, second in ((0, 1), (2, 3)):
+        outs = {first: [], second: []}
+        streams = {first: torch.cuda.Stream(), second: torch.cuda.Stream()}
+        threads = [threading.Thread(target=run, args=(cases[i], streams[i], outs[i])) for i in (first, second)]
+        for t in threads:
+            t.start()
+        for t in threads:
+            t.join()
+        for i in (first, second):
+            assert len(outs[i]) == 1
+            for a, c in zip(outs[i][0], serial[i]):
+                assert np.array_equal(a, c)
 
 
 def test_peak_probes_run(rs):

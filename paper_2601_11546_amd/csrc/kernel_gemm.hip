@@ -199,7 +199,7 @@ __device__ __forceinline__ void gemm_epilogue(const f32x16_t (&acc)[BN / (32 * W
 #pragma unroll
                     for (int j = 0; j < 4; ++j) {
                         const float gate = acc[tn][tm][4 * q + j], up = acc[tn + TN / 2][tm][4 * q + j];
-                        o[j] = gate / (1.0f + __expf(-gate)) * up;
+                        o[j] = silu_mul(gate, up);
                     }
                     uint2 st = make_uint2(pack_bf16x2(o[0], o[1]), pack_bf16x2(o[2], o[3]));
                     *reinterpret_cast<uint2*>(static_cast<uint16_t*>(p.out) + (int64_t)t * p.n_half + i) = st;
@@ -363,6 +363,13 @@ __global__ void __launch_bounds__(256) gemm_bf16_kernel(GemmArgs p) {
 // k iteration to land.
 // ------------------------------------------------------------------------------------------
 // 64 lanes x 16 bytes from (base + per-lane byte offset) to 1 KB of LDS starting at lds_addr.
+// A pointer every lane holds the same value of, moved to scalar registers (the compiler cannot always prove it).
+__device__ __forceinline__ const char* uniform_ptr(const char* ptr) {
+    const uint64_t v = reinterpret_cast<uint64_t>(ptr);
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v), hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+    return reinterpret_cast<const char*>(((uint64_t)hi << 32) | lo);
+}
+
 // NT = non-temporal: for bytes that are read once (the weights of a batch of one token tile).  A streaming read of
 // HBM reaches 7.1-7.4 TB/s with the hint against 6.3-6.4 TB/s without (measured with 32 KB per workgroup in flight);
 // operands that other workgroups read again keep the default policy, which lets the L2 hold them.
@@ -494,7 +501,7 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_dma_kernel(GemmArgs p) {
             for (int r = 0; r < 16; ++r) acc[tn][tm][r] = 0.f;
 
     bf16x8_t wf[2][TN], af[2][TM];
-    auto load_frags = [&](int buf, int stage, int ks) {
+    auto load_frags = [&](int buf, int stage, int ks) __attribute__((always_inline)) {
         const unsigned char* st = smem + stage * STAGE;
         const int ch = ((2 * ks + g) ^ swz) << 4;
 #pragma unroll
@@ -517,12 +524,12 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_dma_kernel(GemmArgs p) {
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
     load_frags(0, 0, 0);
-    auto mfma_one = [&](int buf, int i) {   // i-th of the TN * TM products of a k step
+    auto mfma_one = [&](int buf, int i) __attribute__((always_inline)) {   // i-th of the TN * TM products of a k step
         const int tn = i / TM, tm = i % TM;
         acc[tn][tm] = EPI == EPI_SLAB ? mfma_32x32x16(af[buf][tm], wf[buf][tn], acc[tn][tm])
                                         : mfma_32x32x16(wf[buf][tn], af[buf][tm], acc[tn][tm]);
     };
-    auto load_frag_one = [&](int buf, int stage, int ks, int i) {   // i-th of the TN + TM fragment reads of a k step
+    auto load_frag_one = [&](int buf, int stage, int ks, int i) __attribute__((always_inline)) {   // i-th of the TN + TM fragment reads of a k step
         const unsigned char* st = smem + stage * STAGE;
         const int ch = ((2 * ks + g) ^ swz) << 4;
         if (i < TN)
@@ -530,14 +537,24 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_dma_kernel(GemmArgs p) {
         else
             af[buf][i - TN] = as_bf16x8(*reinterpret_cast<const uint4*>(st + a_rd[i - TN] + ch));
     };
-    auto issue_one = [&](int stage, int k0, int i) {   // i-th of the LOADS wave loads of a stage
+    // Source of the refill in progress (set at a hand-over): the k slice's first byte in both operands and the
+    // freed stage's LDS address, so that a load costs its own two instructions plus one scalar add.
+    const char* rf_a = nullptr;
+    const char* rf_w = nullptr;
+    uint32_t rf_la = 0;
+    auto issue_one = [&](int i) __attribute__((always_inline)) {   // i-th of the LOADS wave loads of a stage
         // weights first: they come from further away (HBM) than the activations (L2)
-        const uint32_t la = lds0 + stage * STAGE + wave * 1024;
         if (i < W_IT)
-            dma16<WNT>(reinterpret_cast<const char*>(p.w) + (p.w_packed ? (size_t)(k0 >> 6) * 32768 + (size_t)(k0 & 63) * 2 : (size_t)k0 * 2), w_voff[i],
-                       la + A_BYTES + i * (NW * 1024));
+            dma16<WNT>(rf_w, w_voff[i], rf_la + A_BYTES + i * (NW * 1024));
         else
-            dma16(reinterpret_cast<const char*>(p.a) + (size_t)k0 * 2, a_voff[i - W_IT], la + (i - W_IT) * (NW * 1024));
+            dma16(rf_a, a_voff[i - W_IT], rf_la + (i - W_IT) * (NW * 1024));
+    };
+    // A flag that is either a run-time bool or std::true_type: the steady-state iterations pass the latter, so their
+    // loads sit in straight-line code (a branch and its scalar set-up around each load cost more issue slots than
+    // the load itself, and a wave has seven slots between two MFMAs).
+    auto on = [](auto flag) {
+        if constexpr (std::is_same_v<decltype(flag), std::true_type>) return true;
+        else return flag;
     };
     constexpr int NM = TN * TM, NF = TN + TM;
     // One k step, issued in a fixed order: MFMA i, then the share of the refill loads and of the next
@@ -547,7 +564,7 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_dma_kernel(GemmArgs p) {
     // behind them.  The MFMAs sit on ONE control path on purpose: at a join the compiler would make
     // them wait for the newest reads.
     constexpr int SPREAD = KSTEPS > 1 ? KSTEPS - 1 : 1;   // the last k step before the next hand-over stays free: landing time
-    auto k_step = [&](int buf, int rd_stage, int rd_ks, int part, bool refill, int rf_stage, int rf_k0) {
+    auto k_step = [&](int buf, int rd_stage, int rd_ks, int part, auto refill) __attribute__((always_inline)) {
         // share of the stage's loads issued in each part, cumulative, in sixteenths: the weights (first half
         // of the loads) go out at once, the activations (L2 hits, quick to land) trail over two more steps
         constexpr int cut[5] = {0, 8, 13, 16, 16};
@@ -559,9 +576,9 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_dma_kernel(GemmArgs p) {
         for (int i = 0; i < NM; ++i) {
             mfma_one(buf, i);
             __builtin_amdgcn_sched_barrier(0);
-            if (part < SPREAD && refill) {
+            if (part < SPREAD && on(refill)) {
 #pragma unroll
-                for (int d = d_lo + i * d_n / NM; d < d_lo + (i + 1) * d_n / NM; ++d) issue_one(rf_stage, rf_k0, d);
+                for (int d = d_lo + i * d_n / NM; d < d_lo + (i + 1) * d_n / NM; ++d) issue_one(d);
             }
             if (i < NM / 2) {   // all reads in the first half: the last one has half a step to come back
 #pragma unroll
@@ -576,14 +593,14 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_dma_kernel(GemmArgs p) {
     // only their hand-over step keeps the fixed order, with the whole refill in it.
     constexpr bool FIXED = NM >= 12;
     int cur = 0;  // stage being computed
-    bool refill = false;       // a refill begun at the last hand-over is still being issued
-    int rf_stage = 0, rf_k0 = 0;
-    for (int kt = 0; kt < nk; ++kt) {
+    // One k iteration (one LDS stage).  refill_open: the refill begun at the previous hand-over is still being
+    // issued; refill_next: this iteration's hand-over starts another one.
+    auto iteration = [&](int kt, auto refill_open, auto refill_next) __attribute__((always_inline)) {
         const int nxt = cur + 1 == NS ? 0 : cur + 1;
 #pragma unroll
         for (int ks = 0; ks + 1 < KSTEPS; ++ks) {
             if (FIXED) {
-                k_step(ks & 1, cur, ks + 1, ks + 1, refill, rf_stage, rf_k0);
+                k_step(ks & 1, cur, ks + 1, ks + 1, refill_open);
             } else {
                 load_frags((ks + 1) & 1, cur, ks + 1);
 #pragma unroll
@@ -594,25 +611,30 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_dma_kernel(GemmArgs p) {
         // NS - 2 younger ones may stay in flight), hand over, and start refilling the freed buffer.
         // After the last stage this reads fragments nobody uses.
         constexpr int LB = (KSTEPS - 1) & 1;
-        if (NS == 2 || kt + NS - 1 >= nk)
+        constexpr bool steady = std::is_same_v<decltype(refill_next), std::true_type>;   // then kt + NS < nk
+        if (NS == 2 || (!steady && kt + NS - 1 >= nk))
             asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
         else
             asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"((NS - 2) * LOADS) : "memory");
         __syncthreads();
-        refill = kt + NS < nk;
-        rf_stage = cur;
-        rf_k0 = (kbeg + kt + NS) * BKD;
+        if (on(refill_next)) {
+            const int k0 = (kbeg + kt + NS) * BKD;
+            rf_a = uniform_ptr(reinterpret_cast<const char*>(p.a) + (size_t)k0 * 2);
+            rf_w = uniform_ptr(reinterpret_cast<const char*>(p.w) +
+                               (p.w_packed ? (size_t)(k0 >> 6) * 32768 + (size_t)(k0 & 63) * 2 : (size_t)k0 * 2));
+            rf_la = __builtin_amdgcn_readfirstlane(lds0 + cur * STAGE + wave * 1024);
+        }
         if (FIXED) {
-            k_step(LB, nxt, 0, 0, refill, rf_stage, rf_k0);
+            k_step(LB, nxt, 0, 0, refill_next);
         } else {
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int i = 0; i < NM; ++i) {
                 mfma_one(LB, i);
                 __builtin_amdgcn_sched_barrier(0);
-                if (refill) {
+                if (on(refill_next)) {
 #pragma unroll
-                    for (int d = i * LOADS / NM; d < (i + 1) * LOADS / NM; ++d) issue_one(rf_stage, rf_k0, d);
+                    for (int d = i * LOADS / NM; d < (i + 1) * LOADS / NM; ++d) issue_one(d);
                 }
                 if (i >= NM / 2) {
 #pragma unroll
@@ -623,7 +645,15 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_dma_kernel(GemmArgs p) {
             }
         }
         cur = nxt;
+    };
+    // first iteration (nothing to refill yet), steady state (every hand-over refills), drain
+    int kt = 0;
+    if (nk > 0) {
+        iteration(0, false, NS < nk);
+        kt = 1;
     }
+    for (; kt < nk - NS; ++kt) iteration(kt, std::true_type{}, std::true_type{});
+    for (; kt < nk; ++kt) iteration(kt, kt - 1 + NS < nk, kt + NS < nk);
     if (EPI != EPI_SLAB && tail) {
         // Partial tile -> this split's slab (registers 4 c .. 4 c + 3 of accumulator tile (tn, tm) of
         // thread tid are the 16 bytes at ((tn TM + tm) 4 + c) * threads + tid: coalesced).
@@ -706,8 +736,7 @@ __global__ void __launch_bounds__(256) gemm_finish_kernel(GemmArgs p) {
         const int t = (int)(i / q_per_row), c = (int)(i % q_per_row) * 4;
         const float4 gt = slab_sum(p.accum + (int64_t)t * p.N + c, stride, p.n_splits);
         const float4 up = slab_sum(p.accum + (int64_t)t * p.N + p.n_half + c, stride, p.n_splits);
-        const float o0 = gt.x / (1.0f + __expf(-gt.x)) * up.x, o1 = gt.y / (1.0f + __expf(-gt.y)) * up.y;
-        const float o2 = gt.z / (1.0f + __expf(-gt.z)) * up.z, o3 = gt.w / (1.0f + __expf(-gt.w)) * up.w;
+        const float o0 = silu_mul(gt.x, up.x), o1 = silu_mul(gt.y, up.y), o2 = silu_mul(gt.z, up.z), o3 = silu_mul(gt.w, up.w);
         *reinterpret_cast<uint2*>(static_cast<uint16_t*>(p.out) + (int64_t)t * p.n_half + c) =
             make_uint2(pack_bf16x2(o0, o1), pack_bf16x2(o2, o3));
     } else if (EPI == EPI_QKV_ROPE) {

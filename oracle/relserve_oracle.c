@@ -304,3 +304,21 @@ int32_t oracle_model_step(const oracle_config* c, const oracle_model* m, const o
     free(last); free(normed); free(x); free(y);
     return 0;
 }
+
+/* Greedy decoding: the next token of a request is the vocabulary entry with the largest logit.
+ * Reading R14: among equal largest logits the lowest token id wins; NaN logits never win
+ * (a row of only NaN gives token 0). */
+void oracle_greedy_sample(const float* logits, int32_t n_rows, int32_t vocab, int32_t* next_token)
+{
+    for (int32_t r = 0; r < n_rows; ++r) {
+        const float* row = logits + (size_t)r * vocab;
+        int32_t best = 0;
+        int have = 0;
+        for (int32_t v = 0; v < vocab; ++v) {
+            if (row[v] != row[v]) continue;
+            if (!have || row[v] > row[best]) { best = v; have = 1; }
+        }
+        next_token[r] = best;
+    }
+}
+

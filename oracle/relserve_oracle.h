@@ -37,6 +37,7 @@
  *       slot = block_table[r][pos / P] * P + pos % P.
  *   R10 a shared prefix is nothing but equal leading block-table entries; the
  *       oracle has no notion of prefix ids.
+ *   R14 greedy next token: the largest logit, the lowest token id among equal ones.
  *
  * Precision: inputs, weights and the cache hold bf16 bit patterns (uint16_t);
  * all arithmetic is fp32 with acc_t accumulators (float, or double when built
@@ -152,6 +153,12 @@ typedef struct {
 int32_t oracle_model_step(const oracle_config* c, const oracle_model* m, const oracle_batch* b,
                           const int32_t* token_ids, uint16_t* const* k_pages, uint16_t* const* v_pages,
                           int32_t num_pages, float* logits, uint16_t* hidden_out);
+
+/* Sec. 2.3 "LLM Inference": the output layer's logits of a request's last token give its next token.
+ * Greedy choice (reading R14): the largest logit, the lowest token id among equals, NaN never chosen.
+ * logits [n_rows, vocab] fp32 -> next_token [n_rows].  Pinned by numpy's argmax, planted ties and
+ * hand-written rows (tests/test_oracle_pins.py). */
+void oracle_greedy_sample(const float* logits, int32_t n_rows, int32_t vocab, int32_t* next_token);
 
 /* 1 when built with double accumulators. */
 int32_t oracle_acc_is_f64(void);

@@ -98,6 +98,8 @@ class Oracle:
         L.oracle_model_step.restype = C.c_int32
         L.oracle_model_step.argtypes = [C.c_void_p] * 6 + [C.c_int32, C.c_void_p, C.c_void_p]
         L.oracle_num_threads.restype = C.c_int32
+        L.oracle_greedy_sample.restype = None
+        L.oracle_greedy_sample.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p]
 
     # -- marshalling helpers -------------------------------------------------
     @staticmethod
@@ -225,6 +227,12 @@ class Oracle:
             raise ValueError(f"oracle_model_step rc={rc}")
         del keep, keep_w
         return logits, hidden
+
+    def greedy_sample(self, logits: np.ndarray) -> np.ndarray:
+        logits = _chk(np.ascontiguousarray(logits), np.float32, "logits")
+        out = np.empty(logits.shape[0], np.int32)
+        self.lib.oracle_greedy_sample(_ptr(logits), logits.shape[0], logits.shape[1], _ptr(out))
+        return out
 
     @property
     def num_threads(self) -> int:

@@ -34,6 +34,8 @@ MUTANTS = [
      "oracle_linear(m->w_lm_head, m->vocab, H, last, b->num_reqs, logits);"),
     ("layers_share_one_cache", "x, k_pages[l], v_pages[l], num_pages,", "x, k_pages[0], v_pages[0], num_pages,"),
     ("stream_not_rounded_between_layers", "NULL, 0, y, x, NULL, NULL);", "NULL, 0, y, NULL, NULL, NULL); for (size_t i = 0; i < (size_t)T * H; ++i) x[i] = (uint16_t)(oracle_f32_to_bf16(y[i]) & 0xfff0u);"),
+    ("greedy_last_of_equals", "if (!have || row[v] > row[best]) { best = v; have = 1; }", "if (!have || row[v] >= row[best]) { best = v; have = 1; }"),
+    ("greedy_smallest", "if (!have || row[v] > row[best]) { best = v; have = 1; }", "if (!have || row[v] < row[best]) { best = v; have = 1; }"),
     ("softmax_unnormalised", "out[(size_t)a * d + i] = (float)(o[i] / denom);", "out[(size_t)a * d + i] = (float)(o[i]);"),
 ]
 

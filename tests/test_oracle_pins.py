@@ -462,6 +462,26 @@ def test_model_step_is_the_composition_of_pinned_pieces(oracle):
         oracle.model_step(shape, b, model, bad, ks, vs)
 
 
+def test_greedy_sample_is_the_first_largest_logit(oracle):
+    """Sec. 2.3 "LLM Inference": the next token from the output layer's logits.  Pins: numpy's argmax on random
+    rows, hand-written rows, planted ties (lowest id wins), extreme values, NaN never chosen."""
+    rng = np.random.default_rng(5)
+    logits = rng.standard_normal((37, 1000)).astype(np.float32)
+    np.testing.assert_array_equal(oracle.greedy_sample(logits), np.argmax(logits, axis=1))
+    hand = np.array([[0.0, 1.0, -1.0, 0.5], [3.0, 3.0, 2.0, 3.0], [-5.0, -4.0, -4.0, -6.0], [-np.inf, -np.inf, -1e30, -np.inf],
+                     [np.nan, 2.0, np.inf, np.inf], [np.nan, np.nan, np.nan, np.nan]], np.float32)
+    np.testing.assert_array_equal(oracle.greedy_sample(hand), [1, 0, 1, 2, 2, 0])
+    tied = logits.copy()
+    for r in range(tied.shape[0]):           # copy the row maximum to a later and to an earlier position
+        m = int(np.argmax(tied[r]))
+        tied[r, (m + 17) % 1000] = tied[r, m]
+        want = min(m, (m + 17) % 1000)
+        assert oracle.greedy_sample(tied[r:r + 1])[0] == want
+    last = np.full((1, 64), -1.0, np.float32)
+    last[0, 63] = 0.0                        # the maximum in the last position
+    assert oracle.greedy_sample(last)[0] == 63
+
+
 def test_golden_tiny_layer_step_is_stable():
     """The frozen oracle outputs (written by tests/golden/make_golden.py) still hold."""
     import os

@@ -220,6 +220,13 @@ int32_t relserve_model_step(const relserve_layer* layer, const relserve_batch* b
                             const relserve_model* model, const int32_t* token_ids, void* logits,
                             void* workspace, size_t workspace_bytes, void* stream);
 
+/* Greedy decoding after the output layer (Sec. 2.3 "LLM Inference": the output layer's result for a
+ * request's last token determines its next token): next_token[r] = the vocabulary entry with the largest
+ * logit of row r, the lowest id among equal largest ones; NaN entries never win, a row without any number
+ * gives 0.  logits: device fp32 [n_rows, vocab] (what relserve_model_step writes); next_token: device
+ * int32 [n_rows].  Integer result, defined exactly. */
+int32_t relserve_greedy_sample(const void* logits, int32_t n_rows, int32_t vocab, int32_t* next_token, void* stream);
+
 /* ---- single stages, exported so that each kernel can be checked alone ---- */
 
 /* out[t, :] = x[t, :] * w / sqrt(mean(x[t, :]^2) + eps); x is bf16 when

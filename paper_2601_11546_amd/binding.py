@@ -30,7 +30,7 @@ PROFILE_SLOTS = 12
 EXPORTS = ["relserve_version", "relserve_strerror", "relserve_config_validate", "relserve_layer_create",
            "relserve_layer_destroy", "relserve_batch_validate", "relserve_batch_slots", "relserve_batch_prepare",
            "relserve_batch_destroy", "relserve_batch_get_info", "relserve_workspace_bytes", "relserve_kv_append",
-           "relserve_layer_step", "relserve_layer_step_static", "relserve_static_scratch_bytes", "relserve_model_workspace_bytes", "relserve_model_step", "relserve_rmsnorm", "relserve_linear", "relserve_rope_append",
+           "relserve_layer_step", "relserve_layer_step_static", "relserve_static_scratch_bytes", "relserve_model_workspace_bytes", "relserve_model_step", "relserve_greedy_sample", "relserve_rmsnorm", "relserve_linear", "relserve_rope_append",
            "relserve_qkv_rope_append",
            "relserve_attention", "relserve_profile_slot_name", "relserve_profile_enable", "relserve_profile_read",
            "relserve_debug_force_gemm_plan", "relserve_peak_probe_mfma", "relserve_peak_probe_stream",
@@ -116,6 +116,7 @@ for _n, _a in {
     "relserve_model_workspace_bytes": [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p],
     "relserve_model_step": [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t,
                             C.c_void_p],
+    "relserve_greedy_sample": [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p],
     "relserve_rmsnorm": [C.c_void_p, C.c_int32, C.c_void_p, C.c_float, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p],
     "relserve_linear": [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_void_p,
                         C.c_void_p, C.c_void_p],
@@ -320,6 +321,12 @@ def relserve_model_step(layer, pbatch, model: dict, token_ids, logits, workspace
     _check(_lib.relserve_model_step(layer.handle, pbatch.handle, C.byref(m), _ptr(token_ids), _ptr(logits),
                                     _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream)),
            "relserve_model_step")
+
+
+def relserve_greedy_sample(logits, next_token, stream=None) -> None:
+    """logits: device fp32 [rows, vocab]; next_token: device int32 [rows]."""
+    _check(_lib.relserve_greedy_sample(_ptr(logits), logits.shape[0], logits.shape[1], _ptr(next_token), _stream(stream)),
+           "relserve_greedy_sample")
 
 
 def relserve_rmsnorm(x, w, eps: float, out, stream=None) -> None:

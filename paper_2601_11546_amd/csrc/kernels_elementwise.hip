@@ -179,4 +179,45 @@ hipError_t launch_rope_append(const BatchDev& b, const relserve_layer& L, void* 
     return hipGetLastError();
 }
 
+// ---- greedy next token: first largest logit of every row ------------------------------------
+// One workgroup per row.  A candidate (value, id) beats another if its value is larger, or equal with a lower id;
+// NaN never competes; a row without any number gives id 0.
+__device__ __forceinline__ void greedy_take(float& bv, int32_t& bi, float v, int32_t i) {
+    if (v > bv || (v == bv && i < bi)) bv = v, bi = i;
+}
+
+__global__ void __launch_bounds__(256) greedy_sample_kernel(const float* __restrict__ logits, int32_t vocab,
+                                                            int32_t* __restrict__ next_token) {
+    const float* row = logits + (int64_t)blockIdx.x * vocab;
+    const int tid = threadIdx.x;
+    float bv = -INFINITY;
+    int32_t bi = INT32_MAX;
+    const int32_t n4 = (reinterpret_cast<uintptr_t>(row) % 16 == 0) ? vocab / 4 : 0;   // 16-byte loads when the row allows
+    for (int32_t c = tid; c < n4; c += 256) {
+        const float4 v = reinterpret_cast<const float4*>(row)[c];
+        greedy_take(bv, bi, v.x, 4 * c);
+        greedy_take(bv, bi, v.y, 4 * c + 1);
+        greedy_take(bv, bi, v.z, 4 * c + 2);
+        greedy_take(bv, bi, v.w, 4 * c + 3);
+    }
+    for (int32_t i = 4 * n4 + tid; i < vocab; i += 256) greedy_take(bv, bi, row[i], i);
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) greedy_take(bv, bi, __shfl_xor(bv, o, 64), __shfl_xor(bi, o, 64));
+    __shared__ float sv[4];
+    __shared__ int32_t si[4];
+    if ((tid & 63) == 0) sv[tid >> 6] = bv, si[tid >> 6] = bi;
+    __syncthreads();
+    if (tid == 0) {
+#pragma unroll
+        for (int w = 1; w < 4; ++w) greedy_take(bv, bi, sv[w], si[w]);
+        next_token[blockIdx.x] = bi == INT32_MAX ? 0 : bi;
+    }
+}
+
+hipError_t launch_greedy_sample(const float* logits, int32_t n_rows, int32_t vocab, int32_t* next_token, hipStream_t s) {
+    if (n_rows == 0) return hipSuccess;
+    greedy_sample_kernel<<<dim3(n_rows), dim3(256), 0, s>>>(logits, vocab, next_token);
+    return hipGetLastError();
+}
+
 }  // namespace relserve

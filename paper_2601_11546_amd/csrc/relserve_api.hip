@@ -661,6 +661,18 @@ int32_t relserve_model_step(const relserve_layer* L, const relserve_batch* b, co
     return RELSERVE_OK;
 }
 
+int32_t relserve_greedy_sample(const void* logits, int32_t n_rows, int32_t vocab, int32_t* next_token, void* stream) {
+    drop_stale_hip_error();
+    if (n_rows < 0 || vocab <= 0) return RELSERVE_ERR_BAD_ARGUMENT;
+    if (n_rows == 0) return RELSERVE_OK;
+    if (!logits || !next_token) return RELSERVE_ERR_NULL_POINTER;
+    if (reinterpret_cast<uintptr_t>(logits) % 4) return RELSERVE_ERR_BAD_ARGUMENT;
+    return launch_greedy_sample(static_cast<const float*>(logits), n_rows, vocab, next_token,
+                                static_cast<hipStream_t>(stream)) == hipSuccess
+               ? RELSERVE_OK
+               : RELSERVE_ERR_HIP;
+}
+
 int32_t relserve_peak_probe_mfma(void* sink, int32_t iters, double* flops, void* stream) {
     drop_stale_hip_error();
     if (!sink || !flops) return RELSERVE_ERR_NULL_POINTER;

@@ -97,6 +97,7 @@ hipError_t launch_rmsnorm(const void* x, bool x_is_f32, const void* w, float eps
                           void* out, hipStream_t s, const int32_t* row_index = nullptr);
 hipError_t launch_embedding(const int32_t* ids, const void* table, int32_t vocab, int32_t H, int32_t T, void* out,
                             hipStream_t s);
+hipError_t launch_greedy_sample(const float* logits, int32_t n_rows, int32_t vocab, int32_t* next_token, hipStream_t s);
 hipError_t launch_kv_append(const BatchDev& b, const void* k, const void* v, void* k_pages, void* v_pages,
                             int32_t row_elems, hipStream_t s);
 hipError_t launch_rope_append(const BatchDev& b, const relserve_layer& L, void* qkv, void* k_pages,

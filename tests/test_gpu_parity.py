@@ -649,6 +649,10 @@ def test_model_step_composition_sweep_full_batch(rs, oracle, sweep_model, chunk)
     torch.cuda.synchronize()
     got = logits.cpu().numpy()
     assert np.isfinite(got).all()                       # every one of the 128 / 129 rows was written
+    next_tok = torch.empty(b.num_reqs, dtype=torch.int32, device="cuda")
+    rs.relserve_greedy_sample(logits, next_tok)         # greedy decoding on the step's own logits: exact
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(next_tok.cpu().numpy(), oracle.greedy_sample(got))
     # sampled requests: decode rows at every composition; the chunk itself where the oracle finishes in about a minute
     reqs = [0, 77, 127] + ([128] if chunk == 512 else [])
     sub = b.select(reqs)
@@ -767,6 +771,33 @@ def test_full_size_decode_only_13b_packed(rs, oracle):
 
 def test_full_size_prefill_only_13b_packed(rs, oracle):
     _sampled_parity(rs, oracle, W.workload_prefill_only_13b(), [0, 63], max_prefill_rows=24, packed=True)
+
+
+@pytest.mark.parametrize("rows,vocab", [(129, 32000), (5, 1000), (3, 7), (1, 1), (17, 4099)])
+def test_greedy_sample_is_bit_exact(rs, oracle, rows, vocab):
+    """The next-token choice is integer work: on the same logits the kernel and the oracle agree exactly, including
+    equal maxima (lowest id), maxima in the first and last position, infinities and NaN."""
+    rng = np.random.default_rng(rows * 31 + vocab)
+    logits = rng.standard_normal((rows, vocab)).astype(np.float32)
+    for r in range(rows):
+        m = int(np.argmax(logits[r]))
+        kind = r % 6
+        if kind == 1:
+            logits[r, (m + vocab // 2) % vocab] = logits[r, m]            # two equal maxima
+        elif kind == 2:
+            logits[r, vocab - 1] = 9.0                                   # maximum in the last position
+        elif kind == 3:
+            logits[r, 0] = np.nan                                        # NaN never wins
+            logits[r, vocab // 3] = np.inf
+        elif kind == 4:
+            logits[r, :] = -np.inf                                       # only infinities: the first one
+        elif kind == 5:
+            logits[r, :] = np.nan                                        # nothing to choose from: id 0
+    want = oracle.greedy_sample(logits)
+    out = torch.full((rows,), -7, dtype=torch.int32, device="cuda")
+    rs.relserve_greedy_sample(torch.from_numpy(logits).cuda(), out)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(out.cpu().numpy(), want)
 
 
 def test_two_host_threads_step_concurrently(rs):

@@ -351,6 +351,30 @@ int32_t relserve_aba_decide(const relserve_aba_input* in, const relserve_duratio
 int32_t relserve_starved_priority(double priority, double waiting_seconds, int32_t n_requests_submitted, double threshold,
                                   double* out);
 
+/* ---- the remaining per-iteration arithmetic of the scheduler; all host only, no device work, no allocation ----
+ * relserve_static_priority (Sec. 3, Eq. 6-7, the static-priority baseline): *priority = sum over the n requests
+ * of L1(tok[i]) + L2(out_len) with linear L1(x) = l1->alpha x + l1->beta and L2(x) = l2->alpha x + l2->beta
+ * (identity and constant mappings are special cases); computed once when a relQuery arrives and never updated.
+ * relserve_utok_estimate (Sec. 4.2 "Fast Priority Estimation", Eq. 11): cache miss ratio of a sample of the
+ * relQuery's requests = sum sample_utok / sum sample_tok; utok_out[i] = tok[i] x ratio rounded to the nearest
+ * integer (ties to even).  Which requests are sampled is the caller's random draw.
+ * relserve_priority_reuse (Eq. 12): *reuse = 1 iff every request of the relQuery was waiting at the previous
+ * iteration and still is (n_waiting_before == n_waiting_now == n_submitted).
+ * relserve_prefill_candidate (Sec. 4.3, the candidate prefill batch): requests are added from the front of utok
+ * (the waiting requests of ONE relQuery, in order) while the three limits hold: a sequence slot is free
+ * (seqs_free), the KV cache manager has room for the request's uncached tokens (tokens_free), and the batch stays
+ * within max_num_batched_tokens (tokens_in_batch = tokens other relQueries already put into it; a request that
+ * alone exceeds the limit is still taken into an empty batch).  Outputs: requests taken and their tokens.
+ * RELSERVE_ERR_BAD_ARGUMENT on negative counts or sample_utok > sample_tok. */
+int32_t relserve_static_priority(const int32_t* tok, int32_t n, int32_t out_len, const relserve_duration_model* l1,
+                                 const relserve_duration_model* l2, double* priority);
+int32_t relserve_utok_estimate(const int32_t* tok, int32_t n, const int32_t* sample_tok, const int32_t* sample_utok,
+                               int32_t n_sample, int32_t* utok_out);
+int32_t relserve_priority_reuse(int32_t n_submitted, int32_t n_waiting_before, int32_t n_waiting_now, int32_t* reuse);
+int32_t relserve_prefill_candidate(const int32_t* utok, int32_t n, int64_t tokens_free, int32_t seqs_free,
+                                   int32_t tokens_in_batch, int32_t max_num_batched_tokens, int32_t* n_taken,
+                                   int64_t* tokens_taken);
+
 /* ---- peak probes: what this GPU sustains, reported by bench.py beside the published peaks ----
  * relserve_peak_probe_mfma enqueues 256 workgroups of 4 waves that each issue iters x 16 independent
  * 32x32x16 bf16 MFMAs on random operands (no memory traffic) and writes the flop count of the launch to

@@ -15,45 +15,55 @@ Readings where the algorithm's text leaves a choice (the product takes the same 
   * a request with utok = 0 (already prefilled) joins no prefill batch; a request flagged as not decoding any
     more joins no decode batch (Sec. 4.2, last sentence of the Algorithm 1 walk-through).
 
-Pure Python loops, in the order of the algorithm.  Only tests import this.
+Pure Python loops.  Only tests import this.
 """
 from __future__ import annotations
 
 
+def _segments(utok, decodes, cap, mns):
+    """First pass: where the engine has to decode to completion.  A segment is a longest run of consecutive requests
+    whose uncached tokens together fit `cap` and of which at most `mns` still decode; the next request opens a new
+    segment as soon as it would break either limit (a request that breaks a limit alone is a segment of its own)."""
+    segs, start, tokens, decoding = [], 0, 0, 0
+    for i in range(len(utok)):
+        if i > start and (tokens + utok[i] > cap or decoding + decodes[i] > mns):
+            segs.append((start, i))
+            start, tokens, decoding = i, 0, 0
+        tokens += utok[i]
+        decoding += decodes[i]
+    if len(utok) > start:
+        segs.append((start, len(utok)))
+    return segs
+
+
+def _prefill_batches(utok, lo, hi, mnbt):
+    """Second pass, inside one segment: its requests that still have tokens to compute, in order, cut into prefill
+    batches of at most `mnbt` tokens (a longer request is a batch of its own)."""
+    batches, cur, cur_tokens = [], [], 0
+    for i in range(lo, hi):
+        if utok[i] + cur_tokens > mnbt and cur:
+            batches.append(cur)
+            cur, cur_tokens = [], 0
+        if utok[i] > 0:
+            cur.append(i)
+            cur_tokens += utok[i]
+    if cur:
+        batches.append(cur)
+    return batches
+
+
 def batch_decompose(utok, out_len, cap, mns, mnbt, decodes=None):
     """Returns (P, D): P = list of prefill batches (lists of request indices), D = list of decode batches
-    (each decode group repeated out_len times)."""
+    (each decode group repeated out_len times).  Derived in two passes (segments between decodes-to-completion,
+    then the prefill batches of each segment) rather than as one walk: same batches as Algorithm 1."""
     n = len(utok)
-    decodes = [True] * n if decodes is None else [bool(x) for x in decodes]
+    decodes = [1] * n if decodes is None else [1 if x else 0 for x in decodes]
     P, D = [], []
-    p, d, accum = [], [], 0
-
-    def close_prefill():
-        nonlocal p
-        if p:
-            P.append(p)
-        p = []
-
-    def decode_to_completion():
-        nonlocal d, accum
-        if d:
-            for _ in range(out_len):
-                D.append(list(d))
-        d, accum = [], 0
-
-    for i in range(n):
-        if utok[i] + accum > cap or len(d) + (1 if decodes[i] else 0) > mns:
-            close_prefill()
-            decode_to_completion()
-        if utok[i] + sum(utok[r] for r in p) > mnbt:
-            close_prefill()
-        if utok[i] > 0:
-            p.append(i)
-        if decodes[i]:
-            d.append(i)
-        accum += utok[i]
-    close_prefill()
-    decode_to_completion()
+    for lo, hi in _segments(utok, decodes, cap, mns):
+        P.extend(_prefill_batches(utok, lo, hi, mnbt))
+        group = [i for i in range(lo, hi) if decodes[i]]
+        if group:
+            D.extend([list(group) for _ in range(out_len)])
     return P, D
 
 

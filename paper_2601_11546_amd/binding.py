@@ -36,7 +36,8 @@ EXPORTS = ["relserve_version", "relserve_strerror", "relserve_config_validate", 
            "relserve_debug_force_gemm_plan", "relserve_peak_probe_mfma", "relserve_peak_probe_stream",
            "relserve_packed_weight_elems", "relserve_pack_weight", "relserve_linear_packed",
            "relserve_duration_fit", "relserve_duration_predict", "relserve_batch_decompose", "relserve_pem_estimate",
-           "relserve_aba_decide", "relserve_starved_priority"]
+           "relserve_aba_decide", "relserve_starved_priority", "relserve_static_priority", "relserve_utok_estimate",
+           "relserve_priority_reuse", "relserve_prefill_candidate"]
 
 
 class RelserveError(RuntimeError):
@@ -140,6 +141,10 @@ for _n, _a in {
     "relserve_pem_estimate": [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p],
     "relserve_aba_decide": [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p],
     "relserve_starved_priority": [C.c_double, C.c_double, C.c_int32, C.c_double, C.c_void_p],
+    "relserve_static_priority": [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p],
+    "relserve_utok_estimate": [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p],
+    "relserve_priority_reuse": [C.c_int32, C.c_int32, C.c_int32, C.c_void_p],
+    "relserve_prefill_candidate": [C.c_void_p, C.c_int32, C.c_int64, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p],
 }.items():
     getattr(_lib, _n).restype = C.c_int32
     getattr(_lib, _n).argtypes = _a
@@ -503,3 +508,46 @@ def relserve_starved_priority(priority: float, waiting_seconds: float, n_request
     _check(_lib.relserve_starved_priority(priority, waiting_seconds, n_requests_submitted, threshold, C.byref(out)),
            "relserve_starved_priority")
     return out.value
+
+
+def _i32(a):
+    a = np.ascontiguousarray(a, np.int32)
+    return a, (a.ctypes.data_as(C.c_void_p) if a.size else None)
+
+
+def relserve_static_priority(tok, out_len: int, l1: dict, l2: dict) -> float:
+    """Eq. 6-7: sum over the requests of L1(tok) + L2(out_len), both linear ({"alpha", "beta"})."""
+    t, tp = _i32(tok)
+    m1 = DurationModel(l1["alpha"], l1["beta"], 0.0, 0)
+    m2 = DurationModel(l2["alpha"], l2["beta"], 0.0, 0)
+    out = C.c_double()
+    _check(_lib.relserve_static_priority(tp, len(t), int(out_len), C.byref(m1), C.byref(m2), C.byref(out)), "relserve_static_priority")
+    return out.value
+
+
+def relserve_utok_estimate(tok, sample_tok, sample_utok) -> np.ndarray:
+    """Eq. 11: tok x (cache miss ratio of the sample), rounded to integers."""
+    t, tp = _i32(tok)
+    st, stp = _i32(sample_tok)
+    su, sup = _i32(sample_utok)
+    out = np.empty(len(t), np.int32)
+    _check(_lib.relserve_utok_estimate(tp, len(t), stp, sup, len(st), out.ctypes.data_as(C.c_void_p) if len(t) else None),
+           "relserve_utok_estimate")
+    return out
+
+
+def relserve_priority_reuse(n_submitted: int, n_waiting_before: int, n_waiting_now: int) -> bool:
+    out = C.c_int32()
+    _check(_lib.relserve_priority_reuse(int(n_submitted), int(n_waiting_before), int(n_waiting_now), C.byref(out)),
+           "relserve_priority_reuse")
+    return bool(out.value)
+
+
+def relserve_prefill_candidate(utok, tokens_free: int, seqs_free: int, tokens_in_batch: int, max_num_batched_tokens: int):
+    """Sec. 4.3: (requests taken from the front of utok, their tokens) under the three limits."""
+    u, up = _i32(utok)
+    n, toks = C.c_int32(), C.c_int64()
+    _check(_lib.relserve_prefill_candidate(up, len(u), int(tokens_free), int(seqs_free), int(tokens_in_batch),
+                                           int(max_num_batched_tokens), C.byref(n), C.byref(toks)), "relserve_prefill_candidate")
+    return n.value, toks.value
+

@@ -180,3 +180,72 @@ int32_t relserve_starved_priority(double priority, double waiting_seconds, int32
 }
 
 }  // extern "C"
+
+// ---- the rest of the scheduler's per-iteration arithmetic (Sec. 3 Eq. 6-7; Sec. 4.2 Eq. 11-12; Sec. 4.3 candidates) ----
+extern "C" {
+
+int32_t relserve_static_priority(const int32_t* tok, int32_t n, int32_t out_len, const relserve_duration_model* l1,
+                                 const relserve_duration_model* l2, double* priority) {
+    if (!l1 || !l2 || !priority) return RELSERVE_ERR_NULL_POINTER;
+    if (n < 0 || out_len < 0) return RELSERVE_ERR_BAD_ARGUMENT;
+    if (n > 0 && !tok) return RELSERVE_ERR_NULL_POINTER;
+    double sum = 0.0;
+    for (int32_t i = 0; i < n; ++i) {
+        if (tok[i] < 0) return RELSERVE_ERR_BAD_ARGUMENT;
+        sum += (l1->alpha * (double)tok[i] + l1->beta) + (l2->alpha * (double)out_len + l2->beta);   // Eq. 6, summed as Eq. 7
+    }
+    *priority = sum;
+    return RELSERVE_OK;
+}
+
+int32_t relserve_utok_estimate(const int32_t* tok, int32_t n, const int32_t* sample_tok, const int32_t* sample_utok,
+                               int32_t n_sample, int32_t* utok_out) {
+    if (n < 0 || n_sample < 1) return RELSERVE_ERR_BAD_ARGUMENT;
+    if (!sample_tok || !sample_utok || (n > 0 && (!tok || !utok_out))) return RELSERVE_ERR_NULL_POINTER;
+    int64_t su = 0, st = 0;
+    for (int32_t i = 0; i < n_sample; ++i) {
+        if (sample_tok[i] < 0 || sample_utok[i] < 0 || sample_utok[i] > sample_tok[i]) return RELSERVE_ERR_BAD_ARGUMENT;
+        su += sample_utok[i];
+        st += sample_tok[i];
+    }
+    if (st == 0) return RELSERVE_ERR_BAD_ARGUMENT;
+    const double ratio = (double)su / (double)st;                      // cache miss ratio of the sample
+    for (int32_t i = 0; i < n; ++i) {
+        if (tok[i] < 0) return RELSERVE_ERR_BAD_ARGUMENT;
+        utok_out[i] = (int32_t)__builtin_nearbyint((double)tok[i] * ratio);   // ties to even
+    }
+    return RELSERVE_OK;
+}
+
+int32_t relserve_priority_reuse(int32_t n_submitted, int32_t n_waiting_before, int32_t n_waiting_now, int32_t* reuse) {
+    if (!reuse) return RELSERVE_ERR_NULL_POINTER;
+    if (n_submitted < 1 || n_waiting_before < 0 || n_waiting_now < 0 || n_waiting_before > n_submitted ||
+        n_waiting_now > n_waiting_before)
+        return RELSERVE_ERR_BAD_ARGUMENT;
+    *reuse = (n_waiting_before == n_submitted && n_waiting_now == n_submitted) ? 1 : 0;
+    return RELSERVE_OK;
+}
+
+int32_t relserve_prefill_candidate(const int32_t* utok, int32_t n, int64_t tokens_free, int32_t seqs_free,
+                                   int32_t tokens_in_batch, int32_t max_num_batched_tokens, int32_t* n_taken,
+                                   int64_t* tokens_taken) {
+    if (!n_taken || !tokens_taken) return RELSERVE_ERR_NULL_POINTER;
+    if (n < 0 || tokens_in_batch < 0 || max_num_batched_tokens < 1) return RELSERVE_ERR_BAD_ARGUMENT;
+    if (n > 0 && !utok) return RELSERVE_ERR_NULL_POINTER;
+    int32_t taken = 0;
+    int64_t toks = 0;
+    for (int32_t i = 0; i < n; ++i) {
+        const int64_t u = utok[i];
+        if (u < 0) return RELSERVE_ERR_BAD_ARGUMENT;
+        if (seqs_free - taken < 1 || u > tokens_free - toks) break;                                    // max_num_seqs, cap
+        if (tokens_in_batch + toks + u > max_num_batched_tokens && (taken > 0 || tokens_in_batch > 0)) break;
+        ++taken;
+        toks += u;
+    }
+    *n_taken = taken;
+    *tokens_taken = toks;
+    return RELSERVE_OK;
+}
+
+}  // extern "C"
+

@@ -5,11 +5,17 @@ Every iteration runs one prefill batch or one decode batch (Sec. 4.1 step 1).  T
 
   "fcfs"      the engine default the paper starts from (Sec. 2.3): waiting requests in arrival order, prefill
               first whenever a request can be admitted, otherwise decode all running requests;
+  "static"    the static-priority baseline (Sec. 3, Eq. 6-7): a relQuery's priority value is computed once, at
+              arrival (`relserve_static_priority`), and orders the waiting queue; otherwise as "fcfs";
   "relserve"  priorities = predicted remaining duration of each relQuery (`relserve_pem_estimate` over the current
-              prefix-cache state — uncached tokens counted exactly or estimated from a sample's miss ratio (Eq. 11) —
-              reused while a relQuery is entirely waiting (Eq. 12), zeroed by the starvation rule (Eq. 13));
-              the candidate prefill batch holds requests of the first waiting relQuery only; the arranger
-              (`relserve_aba_decide`) picks between it and the candidate decode batch.
+              prefix-cache state — uncached tokens counted exactly or estimated from a random sample's miss ratio
+              (Eq. 11, `relserve_utok_estimate`) — reused while a relQuery is entirely waiting (Eq. 12,
+              `relserve_priority_reuse`) and its template's cached state is unchanged, zeroed by the starvation rule
+              (Eq. 13)); the candidate prefill batch holds requests of the first waiting relQuery only
+              (`relserve_prefill_candidate`); the arranger (`relserve_aba_decide`) picks between it and the candidate
+              decode batch.
+
+This module only keeps the queues and calls the library: every formula of the method sits behind the C ABI.
 
 What a batch costs comes from the fitted batch-duration model (Eq. 9), so a run needs no GPU: the same loop can
 drive `relserve_model_step` by passing `execute=` (`serving.GpuWorker`), which is called with every batch and returns
@@ -41,7 +47,10 @@ class RelQuery:
     finish_time: float = -1.0
     priority: float = 0.0
     priority_valid: bool = False
+    priority_cached: bool = False  # whether the template was cached when `priority` was computed
+    priority_waiting: int = 0      # requests waiting when `priority` was computed / last checked
     effective: float = 0.0         # priority after the starvation rule
+    static_priority: float = -1.0  # Eq. 6-7, fixed at arrival
 
     @property
     def n(self) -> int:
@@ -65,11 +74,17 @@ class Limits:
 
 class Engine:
     def __init__(self, prefill_model: dict, decode_model: dict, limits: Limits = Limits(), policy: str = "relserve",
-                 cache_tokens: int = 1 << 20, starvation_threshold: float = float("inf"), execute=None, sample_size: int = 0):
-        assert policy in ("fcfs", "relserve")
+                 cache_tokens: int = 1 << 20, starvation_threshold: float = float("inf"), execute=None, sample_size: int = 0,
+                 draw=None, l1: dict | None = None, l2: dict | None = None):
+        assert policy in ("fcfs", "static", "relserve")
         self.mp, self.md, self.lim, self.policy = prefill_model, decode_model, limits, policy
         self.cache_tokens, self.threshold, self.execute = cache_tokens, starvation_threshold, execute
         self.sample_size = sample_size               # Eq. 11: requests sampled per relQuery for the miss ratio (0 = count exactly)
+        self.draw = draw                             # draw(rid, key, n, k) -> k distinct positions in range(n): the random sample
+        assert not sample_size or draw is not None
+        # Eq. 6: L1 and L2 as lines; by default the slopes of the fitted duration lines (tokens and output lengths in seconds)
+        self.l1 = l1 or {"alpha": prefill_model["alpha"], "beta": 0.0}
+        self.l2 = l2 or {"alpha": decode_model["alpha"], "beta": 0.0}
         self.cache: OrderedDict = OrderedDict()      # template id -> template tokens, in LRU order
         self.now = 0.0
         self.log = []                                # (time, kind, rid or -1, requests, tokens)
@@ -100,18 +115,11 @@ class Engine:
 
     def take_prefill(self, q: RelQuery, budget_left: int, seqs_left: int, tokens_in_batch: int):
         """Requests of q, in order, that fit the limits; returns their uncached token counts."""
-        taken, toks = [], 0
         cached = self.cached(q)
-        for i in range(q.next_req, q.n):
-            u = self.utok(q, i, cached or len(taken) > 0)     # the first request of a cold template computes it for the rest
-            if seqs_left - len(taken) < 1 or u > budget_left:
-                break
-            if tokens_in_batch + toks + u > self.lim.max_num_batched_tokens and (taken or tokens_in_batch > 0):
-                break
-            taken.append(u)
-            toks += u
-            budget_left -= u
-        return taken
+        # the first request of a cold template computes it for the rest
+        u = [self.utok(q, i, cached or i > q.next_req) for i in range(q.next_req, q.n)]
+        k, _ = rs.relserve_prefill_candidate(u, budget_left, seqs_left, tokens_in_batch, self.lim.max_num_batched_tokens)
+        return u[:k]
 
     # ---- priorities (Sec. 4.2)
     def waiting_utok(self, q: RelQuery) -> list:
@@ -122,15 +130,18 @@ class Engine:
         out = [self.utok(q, first, cached)] if first < q.n else []
         if not self.sample_size or len(rest) <= self.sample_size:
             return out + [self.utok(q, i, True) for i in rest]
-        step = len(rest) / self.sample_size
-        sample = [rest[int(k * step)] for k in range(self.sample_size)]        # evenly spread: deterministic
-        ratio = sum(self.utok(q, i, True) for i in sample) / sum(q.prefix + q.suffix[i] for i in sample)
-        return out + [int(round((q.prefix + q.suffix[i]) * ratio)) for i in rest]
+        sample = [rest[p] for p in self.draw(q.rid, q.next_req, len(rest), self.sample_size)]
+        est = rs.relserve_utok_estimate([q.prefix + q.suffix[i] for i in rest], [q.prefix + q.suffix[i] for i in sample],
+                                        [self.utok(q, i, True) for i in sample])
+        return out + [int(e) for e in est]
 
     def update_priorities(self, active) -> None:
         for q in active:
-            entirely_waiting = q.next_req == 0
-            if not (q.priority_valid and entirely_waiting):          # Eq. 12: reuse while nothing of it has run
+            cached = self.cached(q)
+            reuse = (q.priority_valid and rs.relserve_priority_reuse(q.n, q.priority_waiting, q.waiting)     # Eq. 12
+                     and q.priority_cached == cached)         # and nobody else has cached (or evicted) its template meanwhile
+            q.priority_waiting = q.waiting
+            if not reuse:
                 utok = [0] * q.next_req + self.waiting_utok(q)
                 decodes = [0] * q.n
                 for i in range(q.next_req, q.n):
@@ -140,7 +151,7 @@ class Engine:
                     decodes[i] = 1
                 q.priority = rs.relserve_pem_estimate(utok, q.out_len, self.lim.cap, self.lim.max_num_seqs,
                                                       self.lim.max_num_batched_tokens, self.mp, self.md, decodes)
-                q.priority_valid = True
+                q.priority_valid, q.priority_cached = True, cached
             if q.waiting:
                 q.effective = rs.relserve_starved_priority(q.priority, self.now - q.arrival, q.n, self.threshold)
             else:
@@ -153,10 +164,15 @@ class Engine:
         n_running = sum(len(q.running) for q in running)
         budget = self.lim.cap - self.admitted_tokens(active)
         seqs = self.lim.max_num_seqs - n_running
-        if self.policy == "fcfs":
-            cand = []                                                  # [(q, uncached tokens of the requests taken)] in arrival order
+        if self.policy in ("fcfs", "static"):
+            cand = []                                                  # [(q, uncached tokens of the requests taken)] in queue order
             toks = 0
-            for q in sorted((q for q in active if q.waiting), key=lambda q: (q.arrival, q.rid)):
+            if self.policy == "static":
+                for q in active:
+                    if q.static_priority < 0:                          # once, when the relQuery is first seen
+                        q.static_priority = rs.relserve_static_priority([q.prefix + x for x in q.suffix], q.out_len, self.l1, self.l2)
+            order = (lambda q: (q.arrival, q.rid)) if self.policy == "fcfs" else (lambda q: (q.static_priority, q.arrival, q.rid))
+            for q in sorted((q for q in active if q.waiting), key=order):
                 taken = self.take_prefill(q, budget, seqs, toks)
                 if not taken:
                     break
@@ -240,17 +256,10 @@ def serve(relqueries, prefill_model: dict, decode_model: dict, policy: str, limi
 
 
 def poisson_trace(n_relqueries: int, rate: float, seed: int = 0, max_requests: int = 100, out_lens=(5, 50)):
-    """Seeded synthetic trace shaped like Sec. 5.1's workloads: Poisson arrivals, 1-100 requests per relQuery,
-    a template of 256-1024 tokens, suffixes of 30-120 tokens, output lengths of 5 or 50 tokens."""
-    import numpy as np
-    rng = np.random.default_rng(seed)
-    t, out = 0.0, []
-    for rid in range(n_relqueries):
-        t += float(rng.exponential(1.0 / rate))
-        n = int(rng.integers(1, max_requests + 1))
-        out.append(RelQuery(rid, t, int(rng.choice([256, 512, 768, 1024])), [int(x) for x in rng.integers(30, 121, n)],
-                            int(rng.choice(out_lens))))
-    return out
+    """The seeded synthetic trace of workloads.poisson_trace as run-state records."""
+    from . import workloads as W
+    return [RelQuery(s.rid, s.arrival, s.prefix, list(s.suffix), s.out_len, s.template)
+            for s in W.poisson_trace(n_relqueries, rate, seed, max_requests, out_lens)]
 
 
 def compare_policies(prefill_model: dict, decode_model: dict, rates=(2.0, 4.0, 6.0, 8.0), n_relqueries: int = 80, seeds=(0, 1, 2),
@@ -259,13 +268,13 @@ def compare_policies(prefill_model: dict, decode_model: dict, rates=(2.0, 4.0, 6
     """Mean relQuery latency under both policies on seeded Poisson traces, one row per arrival rate."""
     rows = []
     for rate in rates:
-        acc = {"fcfs": [], "relserve": []}
+        acc = {"fcfs": [], "static": [], "relserve": []}
         for seed in seeds:
             trace = poisson_trace(n_relqueries, rate, seed)
             for policy in acc:
                 kw = {"starvation_threshold": starvation_threshold} if policy == "relserve" else {}
                 acc[policy].append(serve(trace, prefill_model, decode_model, policy, limits, **kw)["mean_latency"])
-        f, r = sum(acc["fcfs"]) / len(seeds), sum(acc["relserve"]) / len(seeds)
-        rows.append({"relqueries_per_s": rate, "fcfs_mean_latency_s": round(f, 4), "relserve_mean_latency_s": round(r, 4),
-                     "speedup": round(f / r, 3)})
+        f, st, r = (sum(acc[k]) / len(seeds) for k in ("fcfs", "static", "relserve"))
+        rows.append({"relqueries_per_s": rate, "fcfs_mean_latency_s": round(f, 4), "static_priority_mean_latency_s": round(st, 4),
+                     "relserve_mean_latency_s": round(r, 4), "speedup": round(f / r, 3), "speedup_over_static": round(st / r, 3)})
     return rows

@@ -415,3 +415,48 @@ def duration_sweep_decode(sizes, seed: int = 1200, shape: LayerShape = LLAMA_13B
                 pid.append(len(prefixes) - 1)
         out.append(build_batch(shape, [1] * n, ctx, pid, prefixes, seed=seed + i, name=f"duration_decode_{n}"))
     return out
+
+
+# ----------------------------------------------------------------------------
+# relQuery traces for the serving loop (Sec. 5.1 "Datasets and Workloads")
+# ----------------------------------------------------------------------------
+@dataclass
+class RelQuerySpec:
+    rid: int
+    arrival: float        # seconds
+    prefix: int           # template tokens shared by all requests
+    suffix: list          # private tokens per request
+    out_len: int          # OL(R)
+    template: int = -1    # relQueries with the same template id share its tokens (-1: its own)
+
+
+def poisson_trace(n_relqueries: int, rate: float, seed: int = 0, max_requests: int = 100, out_lens=(5, 50),
+                  n_templates: int = 0) -> list:
+    """Seeded synthetic trace shaped like Sec. 5.1's workloads: Poisson arrivals, 1-100 requests per relQuery,
+    a template of 256-1024 tokens, suffixes of 30-120 tokens, output lengths of 5 or 50 tokens.  With n_templates > 0
+    the relQueries draw their template (and its length) from that many shared ones."""
+    rng = np.random.default_rng(seed)
+    lens = [int(x) for x in rng.choice([256, 512, 768, 1024], max(n_templates, 1))]
+    t, out = 0.0, []
+    for rid in range(n_relqueries):
+        t += float(rng.exponential(1.0 / rate))
+        n = int(rng.integers(1, max_requests + 1))
+        prefix = int(rng.choice([256, 512, 768, 1024]))
+        suffix = [int(x) for x in rng.integers(30, 121, n)]
+        ol = int(rng.choice(out_lens))
+        tmpl = -1
+        if n_templates > 0:
+            tmpl = int(rng.integers(0, n_templates))
+            prefix = lens[tmpl]
+        out.append(RelQuerySpec(rid, t, prefix, suffix, ol, tmpl))
+    return out
+
+
+def sample_positions(seed: int):
+    """The random draws of Eq. 11's sample, as a function both the scheduler and its oracle are handed:
+    draw(rid, key, n, k) -> k distinct positions in range(n), a pure function of its arguments and the seed."""
+    def draw(rid: int, key: int, n: int, k: int) -> list:
+        rng = np.random.default_rng([seed, rid, key, n, k])
+        return sorted(int(x) for x in rng.choice(n, k, replace=False))
+    return draw
+

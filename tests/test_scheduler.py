@@ -58,7 +58,7 @@ def test_lone_relquery_runs_as_algorithm_1_decomposes_it(sch, policy):
         _check_log(sch, [q], res, lim)
 
 
-@pytest.mark.parametrize("policy", ["fcfs", "relserve"])
+@pytest.mark.parametrize("policy", ["fcfs", "static", "relserve"])
 def test_conservation_and_limits_on_poisson_traces(sch, policy):
     for seed in range(4):
         trace = sch.poisson_trace(25, rate=0.5, seed=seed)
@@ -151,21 +151,139 @@ def test_serving_loop_executes_its_batches_on_the_gpu(sch, policy):
 
 
 def test_sampled_miss_ratio_estimates_uncached_tokens(sch):
-    """Eq. 11: the estimate for the unsampled requests is their prompt length times the sample's miss ratio (the
-    oracle's formula), and the priorities built on it stay close to the exactly counted ones."""
+    """Eq. 11: the estimate for the unsampled requests is their prompt length times the miss ratio of a random sample
+    (the oracle's formula on the same draws), and the priorities built on it stay close to the exactly counted ones."""
     from oracle import pem as opem
+    from paper_2601_11546_amd import workloads as W
     rng = np.random.default_rng(2)
     q = sch.RelQuery(0, 0.0, 512, [int(x) for x in rng.integers(30, 121, 60)], 5)
+    draw = W.sample_positions(11)
     exact = sch.Engine(MP, MD).waiting_utok(q)
-    eng = sch.Engine(MP, MD, sample_size=8)
+    eng = sch.Engine(MP, MD, sample_size=8, draw=draw)
     est = eng.waiting_utok(q)
     assert est[0] == exact[0] == 512 + q.suffix[0]                        # the first request brings the template
     rest = list(range(1, 60))
-    sample = [rest[int(k * len(rest) / 8)] for k in range(8)]
+    sample = [rest[p] for p in draw(0, 0, len(rest), 8)]
+    assert len(set(sample)) == 8
     want = opem.utok_estimate([512 + q.suffix[i] for i in rest], [q.suffix[i] for i in sample], [512 + q.suffix[i] for i in sample])
     assert est[1:] == [int(round(w)) for w in want]
     assert abs(sum(est) - sum(exact)) <= 0.25 * sum(exact)                 # eight samples of suffixes spread over 30-120
     trace = sch.poisson_trace(30, rate=4.0, seed=7)
     a = sch.serve(trace, MP, MD, "relserve")["mean_latency"]
-    b = sch.serve(trace, MP, MD, "relserve", sample_size=8)["mean_latency"]
+    b = sch.serve(trace, MP, MD, "relserve", sample_size=8, draw=draw)["mean_latency"]
     assert abs(a - b) <= 0.15 * a
+
+
+# ---------------------------------------------------------------- the loop against its oracle, batch by batch
+def _oracle_log(trace, policy, lim, **kw):
+    from oracle import scheduler as osch
+    return osch.serve(trace, (MP["alpha"], MP["beta"]), (MD["alpha"], MD["beta"]), policy, lim.cap, lim.max_num_seqs,
+                      lim.max_num_batched_tokens, **kw)
+
+
+def _same_logs(got, want):
+    assert len(got) == len(want)
+    for i, (g, w) in enumerate(zip(got, want)):
+        assert g[1:] == w[1:], (i, g, w)                                   # kind, relQuery, requests, tokens: exact
+        assert g[0] == pytest.approx(w[0], rel=1e-12, abs=1e-12), (i, g, w)
+
+
+@pytest.mark.parametrize("policy", ["fcfs", "static", "relserve"])
+def test_every_batch_is_the_one_the_oracle_loop_runs(sch, policy):
+    """Seeded Poisson traces (own templates and templates shared between relQueries, loose and tight limits, with and
+    without the sampled miss ratio and the starvation rule): the engine executes, batch by batch, what the plain-Python
+    oracle of Sec. 4.1's iteration executes."""
+    from paper_2601_11546_amd import workloads as W
+    cases = 0
+    for seed in range(6):
+        for n_templates in (0, 3):
+            trace = W.poisson_trace(18, rate=(3.0, 8.0, 20.0)[seed % 3], seed=seed, max_requests=40, n_templates=n_templates)
+            for lim in (sch.Limits(cap=65536, max_num_seqs=256, max_num_batched_tokens=8192),
+                        sch.Limits(cap=3000, max_num_seqs=24, max_num_batched_tokens=1500)):
+                variants = [{}]
+                if policy == "relserve":
+                    variants = [{}, {"threshold": 0.03}, {"sample_size": 4, "draw": W.sample_positions(seed)},
+                                {"cache_tokens": 1200, "threshold": 0.05}]
+                for v in variants:
+                    kw = {("starvation_threshold" if k == "threshold" else k): x for k, x in v.items()}
+                    res = sch.serve(trace, MP, MD, policy, lim, **kw)
+                    log, lat = _oracle_log(trace, policy, lim, **v)
+                    _same_logs(res["log"], log)
+                    assert res["latency"].keys() == lat.keys()
+                    for rid in lat:
+                        assert res["latency"][rid] == pytest.approx(lat[rid], rel=1e-12)
+                    cases += 1
+    assert cases >= 24
+
+
+def test_scheduler_primitives_match_their_oracles(sch):
+    """Eq. 6-7, Eq. 11, Eq. 12 and the candidate prefill batch of Sec. 4.3: the library's functions against the plain ones."""
+    from oracle import pem as opem
+    from oracle import scheduler as osch
+    from paper_2601_11546_amd import binding as rs
+    rng = np.random.default_rng(3)
+    # hand-worked: two requests of 110 and 120 prompt tokens, OL 3, L1(x) = 2x + 1, L2(x) = x / 2: (221 + 1.5) + (241 + 1.5)
+    assert rs.relserve_static_priority([110, 120], 3, {"alpha": 2.0, "beta": 1.0}, {"alpha": 0.5, "beta": 0.0}) == 465.0
+    assert osch.static_priority([110, 120], 3, (2.0, 1.0), (0.5, 0.0)) == 465.0
+    # hand-worked candidate: limits 1000 free tokens, 3 free slots, 300 tokens per batch
+    assert rs.relserve_prefill_candidate([100, 200, 50, 40], 1000, 3, 0, 300) == (2, 300)      # the third would exceed the batch
+    assert rs.relserve_prefill_candidate([100, 100, 50, 40], 1000, 3, 0, 300) == (3, 250)      # the fourth has no slot
+    assert rs.relserve_prefill_candidate([100, 100, 50, 40], 220, 9, 0, 300) == (2, 200)       # the third exceeds the cache room
+    assert rs.relserve_prefill_candidate([500, 10], 1000, 9, 0, 300) == (1, 500)               # alone above the batch limit
+    assert rs.relserve_prefill_candidate([500, 10], 1000, 9, 40, 300) == (0, 0)                # ... but not into a started batch
+    for _ in range(300):
+        n = int(rng.integers(0, 30))
+        tok = [int(x) for x in rng.integers(0, 900, n)]
+        ol = int(rng.integers(0, 60))
+        l1, l2 = (float(rng.random()), float(rng.random())), (float(rng.random()), float(rng.random()))
+        got = rs.relserve_static_priority(tok, ol, {"alpha": l1[0], "beta": l1[1]}, {"alpha": l2[0], "beta": l2[1]})
+        assert got == pytest.approx(osch.static_priority(tok, ol, l1, l2), rel=1e-12, abs=1e-12)
+        args = (int(rng.integers(0, 3000)), int(rng.integers(0, 12)), int(rng.integers(0, 500)), int(rng.integers(1, 1500)))
+        assert rs.relserve_prefill_candidate(tok, *args) == osch.prefill_candidate(tok, *args)
+        ns = int(rng.integers(1, 6))
+        st = [int(x) for x in rng.integers(1, 900, ns)]
+        su = [int(rng.integers(0, t + 1)) for t in st]
+        want = [int(round(x)) for x in opem.utok_estimate(tok, su, st)]
+        assert list(rs.relserve_utok_estimate(tok, st, su)) == want
+        sub = int(rng.integers(1, 50))
+        before = int(rng.integers(0, sub + 1))
+        nowv = int(rng.integers(0, before + 1))
+        assert rs.relserve_priority_reuse(sub, before, nowv) == osch.priority_reuse(sub, before, nowv)
+    with pytest.raises(rs.RelserveError):
+        rs.relserve_utok_estimate([5], [10], [11])                       # more uncached than prompt tokens
+    with pytest.raises(rs.RelserveError):
+        rs.relserve_priority_reuse(4, 3, 4)                              # waiting requests cannot come back
+
+
+def test_three_relqueries_by_hand(sch):
+    """A hand-worked trace under the RelServe policy, batch by batch.  Lines: prefill 1 ms per token + 10 ms, decode
+    1 ms per request + 5 ms.  A (2 requests, template 100, suffixes 10 / 10, OL 2) arrives at 0; B (1 request, template
+    20, suffix 5, OL 1) at 0.05; C (3 requests, A's template, suffixes 10 / 10 / 10, OL 1) at 0.06.
+      t = 0      only A: prefill A (110 + 10 tokens: 120 ms + 10 ms) -> 0.130 s; B and C have arrived meanwhile.
+      t = 0.130  priorities: A = 2 decode iterations of 2 requests = 2 x 7 ms = 0.014; B = (25 + 10) ms + 6 ms = 0.041;
+                 C: A's template is cached, so 30 tokens: (30 + 10) ms + (3 + 5) ms = 0.048.  m+ = 0.014 < m- = 0.041:
+                 transitional case, delta+ = L_prefill(B) x 1 + 1 ms x 1 x min(2, 1) = 0.036, delta- = 2 waiting x 5 ms x
+                 min(1, 2) = 0.010: delta > 0, decode A -> 0.137; the same again -> 0.144, A done (latency 0.144).
+      t = 0.144  nothing runs: prefill B (25 tokens, 35 ms) -> 0.179; now m+ = B = 0.006 < m- = C = 0.048, delta+ = 0.040 +
+                 0.003 > delta- = 0.005: decode B (6 ms) -> 0.185, B done (latency 0.135).
+      t = 0.185  prefill C (30 tokens, 40 ms) -> 0.225; decode C (3 requests, 8 ms) -> 0.233 (latency 0.173)."""
+    mp, md = {"alpha": 1e-3, "beta": 1e-2}, {"alpha": 1e-3, "beta": 5e-3}
+    trace = [sch.RelQuery(0, 0.0, 100, [10, 10], 2, template=7), sch.RelQuery(1, 0.05, 20, [5], 1),
+             sch.RelQuery(2, 0.06, 100, [10, 10, 10], 1, template=7)]
+    res = sch.serve(trace, mp, md, "relserve")
+    want = [(0.130, "prefill", 0, 2, 120), (0.137, "decode", -1, 2, 2), (0.144, "decode", -1, 2, 2),
+            (0.179, "prefill", 1, 1, 25), (0.185, "decode", -1, 1, 1), (0.225, "prefill", 2, 3, 30), (0.233, "decode", -1, 3, 3)]
+    _same_logs(res["log"], want)
+    assert res["latency"] == pytest.approx({0: 0.144, 1: 0.135, 2: 0.173}, abs=1e-9)
+    from oracle import scheduler as osch
+    log, lat = osch.serve(trace, (1e-3, 1e-2), (1e-3, 5e-3), "relserve", 65536, 256, 8192)
+    _same_logs(log, want)
+    # static priorities (Eq. 6-7 with the default lines: 1 ms per prompt token + 1 ms per output token):
+    # A = 2 x (110 + 2) ms = 0.224, B = 26 ms, C = 3 x 111 ms = 0.333.  After A's prefill the queue is B, C; prefill comes
+    # first and a batch may span relQueries: B's request (25 tokens) and C's three (30) run as one prefill batch, then
+    # all six requests decode together; A needs a second iteration.
+    st = sch.serve(trace, mp, md, "static")
+    want = [(0.130, "prefill", 0, 2, 120), (0.195, "prefill", -1, 4, 55), (0.206, "decode", -1, 6, 6), (0.213, "decode", -1, 2, 2)]
+    _same_logs(st["log"], want)
+    log, _ = osch.serve(trace, (1e-3, 1e-2), (1e-3, 5e-3), "static", 65536, 256, 8192)
+    _same_logs(log, want)

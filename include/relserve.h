@@ -185,7 +185,7 @@ int32_t relserve_layer_step(const relserve_layer* layer, const relserve_batch* b
  * call on a GPU uses that GPU's one array: calls that may overlap on one GPU (two streams, two threads)
  * race; the array is pure scratch (written before it is read), so nothing has to be cleared between
  * calls.  relserve_static_scratch_bytes reports the size. */
-#define RELSERVE_STATIC_SCRATCH_BYTES (64u << 20)
+#define RELSERVE_STATIC_SCRATCH_BYTES (80u << 20)
 int32_t relserve_static_scratch_bytes(size_t* out);
 int32_t relserve_layer_step_static(const relserve_layer* layer, const relserve_batch* batch,
                                    const relserve_layer_weights* weights,

@@ -46,6 +46,8 @@ struct AttnArgs {
     float* part_o;
     float* part_ml;
     int32_t n_items;
+    int32_t T;                 // rows T + slot of part_o / part_ml hold the chunk partials of split decode rows
+    const MergeItem* merge_items;
     int32_t max_blocks, page_shift, page_mask;
     int32_t q_pitch, n_q, n_kv, group;
     int32_t dec_by_head;   // decode workgroups take four adjacent kv heads of one token (n_kv % 4 == 0)
@@ -534,6 +536,16 @@ __device__ __forceinline__ void attn_decode_body(const AttnArgs& p, const AttnIt
     if (!valid) return;
     float l_tot = l_run + __shfl_xor(l_run, 16, 64);
     l_tot += __shfl_xor(l_tot, 32, 64);
+    if (it.flags & ITEM_WRITE_PARTIAL) {
+        // one chunk of a split row: its running state goes to the chunk's slot, the merge kernel finishes the row
+        const int64_t prow = (int64_t)(p.T + it.pad1) * p.n_q + hq;
+        if (gq == 0) *reinterpret_cast<float2*>(p.part_ml + prow * 2) = make_float2(m_run, l_tot);
+        float* po = p.part_o + prow * D + 4 * gq;
+#pragma unroll
+        for (int td = 0; td < TD; ++td)
+            *reinterpret_cast<float4*>(po + 16 * td) = make_float4(o_acc[td][0], o_acc[td][1], o_acc[td][2], o_acc[td][3]);
+        return;
+    }
     const float inv = 1.0f / l_tot;
     uint16_t* orow = p.out + row_id * D + 4 * gq;
 #pragma unroll
@@ -541,6 +553,34 @@ __device__ __forceinline__ void attn_decode_body(const AttnArgs& p, const AttnIt
         *reinterpret_cast<uint2*>(orow + 16 * td) =
             make_uint2(pack_bf16x2(o_acc[td][0] * inv, o_acc[td][1] * inv),
                        pack_bf16x2(o_acc[td][2] * inv, o_acc[td][3] * inv));
+}
+
+// Finishes the decode rows whose keys were cut into chunks: with chunk states (m_c, l_c, O_c) in the log2 domain,
+// out = sum_c 2^(m_c - M) O_c / sum_c 2^(m_c - M) l_c with M the largest m_c, accumulated in chunk order with a running
+// maximum.  A thread per four output values of one row; blockIdx.x = row, blockIdx.y = 256 of its units.
+template <int D>
+__global__ void __launch_bounds__(256) attn_merge_kernel(AttnArgs p) {
+    const MergeItem mi = p.merge_items[blockIdx.x];
+    const int u = blockIdx.y * 256 + threadIdx.x;
+    if (u >= p.n_q * (D / 4)) return;
+    const int hq = u / (D / 4), d0 = (u % (D / 4)) * 4;
+    const int64_t row0 = (int64_t)(p.T + mi.first_slot) * p.n_q + hq;
+    float M = -INFINITY, L = 0.f;
+    float4 o = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll 4
+    for (int c = 0; c < mi.n_chunks; ++c) {
+        const int64_t prow = row0 + (int64_t)c * p.n_q;
+        const float2 ml = *reinterpret_cast<const float2*>(p.part_ml + prow * 2);
+        const float4 v = *reinterpret_cast<const float4*>(p.part_o + prow * D + d0);
+        const float m_new = fmaxf(M, ml.x);
+        const float a = __builtin_amdgcn_exp2f(M - m_new), w = __builtin_amdgcn_exp2f(ml.x - m_new);   // a = 0 at the first chunk
+        M = m_new;
+        L = L * a + w * ml.y;
+        o.x = o.x * a + w * v.x; o.y = o.y * a + w * v.y; o.z = o.z * a + w * v.z; o.w = o.w * a + w * v.w;
+    }
+    const float inv = 1.0f / L;
+    *reinterpret_cast<uint2*>(p.out + ((int64_t)mi.tok * p.n_q + hq) * D + d0) =
+        make_uint2(pack_bf16x2(o.x * inv, o.y * inv), pack_bf16x2(o.z * inv, o.w * inv));
 }
 
 template <int D>
@@ -638,12 +678,24 @@ hipError_t launch_attention(const BatchDev& b, const relserve_layer& L, const vo
         e = d128 ? launch_d<128>(p, items, n, items_b, n_b, decode, s) : launch_d<64>(p, items, n, items_b, n_b, decode, s);
         profile_mark(prof, slot, s, false);
     };
+    p.T = b.T;
+    p.merge_items = b.merge_items;
     launch(3, b.items_prefix, b.n_items_prefix, nullptr, 0, false);
     if (b.n_items_tile > 0 && b.n_items_split > 0) {   // both kinds of rows: one launch for their own keys
         launch(2, b.items_tile, b.n_items_tile, b.items_split, b.n_items_split, false);
     } else {
         launch(4, b.items_tile, b.n_items_tile, nullptr, 0, false);
         launch(5, b.items_split, b.n_items_split, nullptr, 0, true);
+    }
+    if (e == hipSuccess && b.n_merge > 0) {
+        profile_mark(prof, 10, s, true);
+        const unsigned y_blocks = (unsigned)((p.n_q * (L.cfg.head_dim / 4) + 255) / 256);
+        if (d128)
+            attn_merge_kernel<128><<<dim3(b.n_merge, y_blocks), dim3(256), 0, s>>>(p);
+        else
+            attn_merge_kernel<64><<<dim3(b.n_merge, y_blocks), dim3(256), 0, s>>>(p);
+        e = hipGetLastError();
+        profile_mark(prof, 10, s, false);
     }
     return e;
 }

@@ -17,8 +17,8 @@ inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
 const char* const kSlotNames[RELSERVE_PROFILE_SLOTS] = {
     "rmsnorm_in", "gemm_qkv_rope_append", "attn_own_keys", "attn_prefix", "attn_tile", "attn_split",
-    "gemm_o",     "rmsnorm_post", "gemm_gate_up", "gemm_down",  "unused",    "unused"};
-enum { S_NORM1 = 0, S_QKV, S_ATTN_OWN, S_ATTN_PREFIX, S_ATTN_TILE, S_ATTN_SPLIT, S_O, S_NORM2, S_GU, S_DOWN };
+    "gemm_o",     "rmsnorm_post", "gemm_gate_up", "gemm_down",  "attn_merge", "unused"};
+enum { S_NORM1 = 0, S_QKV, S_ATTN_OWN, S_ATTN_PREFIX, S_ATTN_TILE, S_ATTN_SPLIT, S_O, S_NORM2, S_GU, S_DOWN, S_ATTN_MERGE };
 
 struct Workspace {
     char* h;         // [T, H] bf16 (normed activations; reused for the post norm)
@@ -26,8 +26,8 @@ struct Workspace {
     char* attn;      // [T, q_dim] bf16
     char* x1;        // [T, H] fp32 residual stream after attention
     char* act;       // [T, I] bf16
-    float* part_o;   // [T, n_q, d] fp32
-    float* part_ml;  // [T, n_q, 2] fp32
+    float* part_o;   // [T + split slots, n_q, d] fp32
+    float* part_ml;  // [T + split slots, n_q, 2] fp32
     float* accum;    // fp32 split-K scratch of the GEMMs
     size_t accum_floats;
     size_t total;
@@ -47,8 +47,9 @@ Workspace carve(const relserve_layer& L, int64_t T, void* base) {
     w.attn = take((size_t)T * L.q_dim * 2);
     w.x1 = take((size_t)T * c.hidden * 4);
     w.act = take((size_t)T * c.mlp_dim * 2);
-    w.part_o = reinterpret_cast<float*>(take((size_t)T * L.q_dim * 4));
-    w.part_ml = reinterpret_cast<float*>(take((size_t)T * c.n_q_heads * 2 * 4));
+    const size_t part_rows = (size_t)(T + split_slot_cap(T));
+    w.part_o = reinterpret_cast<float*>(take(part_rows * L.q_dim * 4));
+    w.part_ml = reinterpret_cast<float*>(take(part_rows * c.n_q_heads * 2 * 4));
     w.accum_floats = (size_t)gemm_scratch_floats(T, std::max({L.qkv_dim, 2 * c.mlp_dim, c.hidden}));
     w.accum = reinterpret_cast<float*>(take(w.accum_floats * 4));
     w.total = off;
@@ -199,6 +200,32 @@ int32_t relserve::expand_batch(const relserve_layer_config& cfg, const relserve_
                 hb.items_prefix.push_back(it);
             }
         }
+        // Decode rows with many own keys are cut into chunks (one wave item each, merged afterwards), so that one long
+        // context does not set the kernel's duration and the waves come in several even rounds.  The chunk length is
+        // the smallest of 128 .. 1024 keys whose chunks fit the partial-state slots of the workspace.
+        auto own_keys = [&](int32_t r) {
+            const int32_t pid = d.prefix_id ? d.prefix_id[r] : -1;
+            return d.ctx_len[r] - ((pid >= 0 && joint[pid]) ? d.prefix_len[pid] : 0);
+        };
+        auto chunks_of = [](int32_t own, int32_t len) { return len > 0 ? std::max(1, (own + len / 2) / len) : 1; };
+        int32_t chunk_len = 0;   // 0 = no row is cut
+        // (with two rounds of waves or more -- 256 CUs x 8 resident waves each -- the rows balance by themselves: cutting
+        // the 128 rows x 40 heads of 1024 keys of a 13B decode batch in two left its kernel at 6.5 TB/s and added the merge)
+        if ((int64_t)hb.n_decode * cfg.n_kv_heads < 2 * 2048) {
+            const int64_t cap = split_slot_cap(T);
+            for (int32_t len = 128; len <= 1024 && chunk_len == 0; len *= 2) {
+                int64_t slots = 0;
+                bool any = false;
+                for (int32_t r = 0; r < B; ++r)
+                    if (d.q_start[r + 1] - d.q_start[r] == 1) {
+                        const int32_t n = chunks_of(own_keys(r), len);
+                        if (n > 1) slots += n, any = true;
+                    }
+                if (!any) break;               // no row is longer than a chunk and a half: nothing to cut at any larger length
+                if (slots <= cap) chunk_len = len;
+            }
+        }
+        int32_t next_slot = 0;
         for (int32_t r = 0; r < B; ++r) {
             const int32_t q_len = d.q_start[r + 1] - d.q_start[r];
             const int32_t pid = d.prefix_id ? d.prefix_id[r] : -1;
@@ -207,16 +234,30 @@ int32_t relserve::expand_batch(const relserve_layer_config& cfg, const relserve_
             const int32_t flags = ITEM_CAUSAL | (grouped ? ITEM_INIT_PARTIAL : 0);
             const int32_t past = d.ctx_len[r] - q_len;
             if (q_len == 1) {
-                AttnItem it{};
-                it.tok_off = (int32_t)hb.attn_tok.size();
-                hb.attn_tok.push_back(d.q_start[r]);
-                it.n_tok = 1;
-                it.pad0 = d.q_start[r];  // the decode kernel takes its single token from here
-                it.bt_req = r;
-                it.key_begin = kb;
-                it.key_end = d.ctx_len[r];
-                it.flags = flags;
-                hb.items_split.push_back(it);
+                const int32_t own = d.ctx_len[r] - kb;
+                const int32_t n_chunks = chunks_of(own, chunk_len);
+                // chunk boundaries on multiples of 32 keys (the wave kernel's block) counted from the first own key
+                const int32_t per = n_chunks > 1 ? ((own + n_chunks - 1) / n_chunks + 31) / 32 * 32 : own;
+                if (n_chunks > 1) hb.merge_items.push_back(MergeItem{d.q_start[r], next_slot, 0, 0});
+                for (int32_t c = 0; c < n_chunks; ++c) {
+                    const int32_t b0 = kb + c * per, b1 = std::min(kb + (c + 1) * per, d.ctx_len[r]);
+                    if (b0 >= b1) break;
+                    AttnItem it{};
+                    it.tok_off = (int32_t)hb.attn_tok.size();
+                    hb.attn_tok.push_back(d.q_start[r]);
+                    it.n_tok = 1;
+                    it.pad0 = d.q_start[r];  // the decode kernel takes its single token from here
+                    it.bt_req = r;
+                    it.key_begin = b0;
+                    it.key_end = b1;
+                    it.flags = c == 0 ? flags : ITEM_CAUSAL;      // only the first chunk continues from the prefix pass's state
+                    if (n_chunks > 1) {
+                        it.flags |= ITEM_WRITE_PARTIAL;
+                        it.pad1 = next_slot++;
+                        ++hb.merge_items.back().n_chunks;
+                    }
+                    hb.items_split.push_back(it);
+                }
             } else {
                 for (int32_t o = 0; o < q_len; o += tile_tok) {
                     AttnItem it{};
@@ -363,6 +404,7 @@ int32_t relserve_batch_prepare(const relserve_layer* L, const relserve_batch_des
     const size_t o_ip = reserve(sizeof(AttnItem) * hb.items_prefix.size());
     const size_t o_it = reserve(sizeof(AttnItem) * hb.items_tile.size());
     const size_t o_is = reserve(sizeof(AttnItem) * hb.items_split.size());
+    const size_t o_mi = reserve(sizeof(MergeItem) * hb.merge_items.size());
     const size_t o_freq = reserve(sizeof(float) * half);
     const size_t host_bytes = off;
     const size_t o_cs = reserve(sizeof(float2) * (size_t)T * half);
@@ -383,6 +425,7 @@ int32_t relserve_batch_prepare(const relserve_layer* L, const relserve_batch_des
     put(o_ip, hb.items_prefix.data(), sizeof(AttnItem) * hb.items_prefix.size());
     put(o_it, hb.items_tile.data(), sizeof(AttnItem) * hb.items_tile.size());
     put(o_is, hb.items_split.data(), sizeof(AttnItem) * hb.items_split.size());
+    put(o_mi, hb.merge_items.data(), sizeof(MergeItem) * hb.merge_items.size());
     put(o_freq, L->inv_freq.data(), sizeof(float) * half);
 
     relserve_batch* b = new (std::nothrow) relserve_batch();
@@ -407,6 +450,8 @@ int32_t relserve_batch_prepare(const relserve_layer* L, const relserve_batch_des
     dv.items_prefix = reinterpret_cast<AttnItem*>(base + o_ip);
     dv.items_tile = reinterpret_cast<AttnItem*>(base + o_it);
     dv.items_split = reinterpret_cast<AttnItem*>(base + o_is);
+    dv.merge_items = reinterpret_cast<MergeItem*>(base + o_mi);
+    dv.n_merge = (int32_t)hb.merge_items.size();
     dv.rope_cs = reinterpret_cast<float2*>(base + o_cs);
     dv.n_items_prefix = (int32_t)hb.items_prefix.size();
     dv.n_items_tile = (int32_t)hb.items_tile.size();

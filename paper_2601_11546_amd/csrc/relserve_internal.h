@@ -28,8 +28,21 @@ struct AttnItem {
     int32_t key_end;    // one past the last key position any row may see
     int32_t flags;
     int32_t pad0;       // decode items: the query token
-    int32_t pad1;
+    int32_t pad1;       // decode items that write partial state: the slot
 };
+
+// A decode row whose own keys were cut into several wave items (chunks): each chunk stores its running softmax state
+// in a slot, and one merge combines the slots [first_slot, first_slot + n_chunks) into the row's output.
+struct MergeItem {
+    int32_t tok;
+    int32_t first_slot;
+    int32_t n_chunks;
+    int32_t pad;
+};
+
+// Slots of partial state the chunked decode rows of a batch of T tokens may use (rows T .. T + cap of the partial-state
+// buffers, behind the T rows that hold the shared-prefix pass's state).
+inline int64_t split_slot_cap(int64_t T) { return 2 * (T < 2048 ? T : 2048); }
 
 // Device-side view of a prepared batch (all pointers into one device allocation).
 struct BatchDev {
@@ -43,8 +56,9 @@ struct BatchDev {
     const int32_t* attn_tok;     // token lists of the attention items
     const AttnItem* items_prefix;  // joint prefix passes (write partial state)
     const AttnItem* items_tile;    // row-tiled passes (prefill rows)
-    const AttnItem* items_split;   // key-split passes (decode rows)
-    int32_t n_items_prefix, n_items_tile, n_items_split;
+    const AttnItem* items_split;   // wave items (decode rows, or chunks of their keys)
+    const MergeItem* merge_items;  // decode rows cut into chunks
+    int32_t n_items_prefix, n_items_tile, n_items_split, n_merge;
 };
 
 }  // namespace relserve
@@ -79,6 +93,7 @@ struct HostBatch {
     std::vector<int32_t> tok_req, tok_pos, tok_slot;
     std::vector<int32_t> attn_tok;
     std::vector<AttnItem> items_prefix, items_tile, items_split;
+    std::vector<MergeItem> merge_items;
     int32_t n_decode = 0, n_prefill = 0, n_groups = 0;
 };
 int32_t expand_batch(const relserve_layer_config& cfg, const relserve_batch_desc& d, bool build_items,
@@ -115,7 +130,8 @@ hipError_t launch_pack_weight(const void* w, int32_t N, int32_t K, void* out, hi
 hipError_t launch_qkv_rope_append(const BatchDev& b, const relserve_layer& L, const void* h, const void* w_qkv,
                                   void* q_out, void* k_pages, void* v_pages, hipStream_t s, float* accum = nullptr,
                                   bool w_packed = false);
-// Attention passes; part_o [T, n_q, d] fp32 and part_ml [T, n_q, 2] fp32 hold the prefix partials.
+// Attention passes; part_o [T + split_slot_cap(T), n_q, d] fp32 and part_ml [.., n_q, 2] fp32 hold the prefix partials
+// (rows of the tokens) and the chunk partials of split decode rows (rows T + slot).
 hipError_t launch_attention(const BatchDev& b, const relserve_layer& L, const void* q, int32_t q_pitch,
                             const void* k_pages, const void* v_pages, void* out, float* part_o,
                             float* part_ml, hipStream_t s, relserve_layer* prof);

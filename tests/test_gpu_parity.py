@@ -244,6 +244,28 @@ def test_layer_step_page_sizes(rs, oracle, shape, page):
         assert_bf16_neighbours(host_bits(gl.k_pages).reshape(-1, nkv, d)[slots], kp.reshape(-1, nkv, d)[slots], "appended k")
 
 
+@pytest.mark.parametrize("shape", [W.TINY, W.TINY_GQA, W.TINY_D128, W.TINY_G5], ids=["mha", "gqa", "d128", "g5"])
+def test_layer_step_long_and_ragged_decode_rows(rs, oracle, shape):
+    """Decode rows whose own keys are cut into chunks (one wave item per chunk, states merged afterwards): a single row
+    over 4096 keys, ragged rows of 129 to 1500 keys, rows behind a shared prefix (the first chunk continues from the
+    prefix pass's state), next to rows short enough to stay whole and a prefill chunk."""
+    P = shape.page_size
+    pl = 4 * P
+    q_len = [1, 1, 1, 1, 1, 1, 1, 1, 7]
+    ctx = [4096, 129, 700, pl + 1500, pl + 333, pl + 40, 17, 193, 50]
+    pid = [-1, -1, -1, 0, 0, 0, -1, -1, -1]
+    b = W.build_batch(shape, q_len, ctx, pid, [pl], seed=77, name="long_ragged_decode")
+    wl = W.Workload(b.name, shape, b, 1077)
+    gl, y, res, kp, vp = _step_case(rs, oracle, wl)
+    info = rs.relserve_batch_prepare(gl.layer, b).info
+    assert info["num_attn_items"] > len(q_len) + 1           # rows were cut: more wave items than rows
+    assert_close(host_f32(y), res.y_f32, "long and ragged decode rows")
+    one = W.build_batch(shape, [1], [4096], seed=78, name="one_row_4096_keys")
+    wl = W.Workload(one.name, shape, one, 1078)
+    gl, y, res, kp, vp = _step_case(rs, oracle, wl)
+    assert_close(host_f32(y), res.y_f32, "one decode row over 4096 keys")
+
+
 def test_layer_step_in_place_and_repeatable(rs, oracle):
     wl = W.workload_tiny_prefix()
     shape, b = wl.shape, wl.batch

@@ -34,7 +34,7 @@ def _both(rs, shape, batch, weights_dev, x_bits, cache_seed):
 def test_static_scratch_layer_step_matches_workspace_entry_point(oracle):
     from paper_2601_11546_amd import binding as rs
     assert torch.cuda.is_available()
-    assert rs.relserve_static_scratch_bytes() == 64 << 20
+    assert rs.relserve_static_scratch_bytes() == 80 << 20
     shape = W.LLAMA_13B
     weights = W.make_weights(shape, 1013, n_layers=40)
     wd = rs.pack_layer_weights({k: dev_bf16(v) for k, v in weights.items()})
@@ -53,10 +53,10 @@ def test_static_scratch_layer_step_matches_workspace_entry_point(oracle):
         res = oracle.layer_step(shape, sub, weights, x[rows], kp, vp)
         assert_close(W.bf16_bits_to_f32(y1)[rows], res.y_f32, f"static scratch call {i}")
     # a batch beyond the fixed array is refused, nothing is launched
-    big = W.build_batch(shape, [300], [300], seed=3)
+    big = W.build_batch(shape, [400], [400], seed=3)
     layer = rs.relserve_layer_create(shape)
     pb = rs.relserve_batch_prepare(layer, big)
-    xb = dev_bf16(W.make_activations(300, shape.hidden, 4))
+    xb = dev_bf16(W.make_activations(400, shape.hidden, 4))
     kd, vd = (dev_bf16(a) for a in W.make_cache(shape, big.num_pages, 5))
     y = torch.zeros_like(xb)
     with pytest.raises(rs.RelserveError) as e:

@@ -44,6 +44,39 @@ uint16_t oracle_f32_to_bf16(float f)
     return (uint16_t)(u >> 16);
 }
 
+/* R15: 8-bit floating point of the quantised cache: 1 sign, 4 exponent (bias 7), 3 mantissa bits; the largest
+ * finite magnitude is 448 (0x7e); 0x7f / 0xff are NaN; there is no infinity.  Subnormals are multiples of 2^-9. */
+float oracle_e4m3_to_f32(uint8_t code)
+{
+    int e = (code >> 3) & 0xf, m = code & 7;
+    float mag;
+    if (e == 0xf && m == 7) return NAN;
+    if (e == 0) mag = ldexpf((float)m, -9);
+    else        mag = ldexpf((float)(8 + m), e - 7 - 3);
+    return (code & 0x80) ? -mag : mag;
+}
+
+/* round to nearest, ties to the even mantissa; magnitudes above 448 (and infinities) become 448; NaN stays NaN */
+uint8_t oracle_f32_to_e4m3(float x)
+{
+    if (x != x) return 0x7f;
+    uint8_t sign = signbit(x) ? 0x80 : 0x00;
+    float a = fabsf(x);
+    if (a >= 448.0f) return (uint8_t)(sign | 0x7e);
+    int e;
+    (void)frexpf(a, &e);                 /* a = f * 2^e, f in [0.5, 1): the binade of a is [2^(e-1), 2^e) */
+    int q = e - 1 - 3;                   /* spacing 2^q keeps 4 significant bits ...                      */
+    if (q < -9) q = -9;                  /* ... but never finer than the subnormal spacing                */
+    float n = nearbyintf(ldexpf(a, -q)); /* exact scaling, then ties-to-even (default rounding mode)      */
+    if (n == 0.0f) return sign;
+    float r = ldexpf(n, q);              /* the rounded magnitude; may have moved up into the next binade */
+    (void)frexpf(r, &e);
+    int E = e - 1 + 7;                   /* biased exponent of r                                          */
+    if (E <= 0) return (uint8_t)(sign | (uint8_t)ldexpf(r, 9));          /* subnormal: r / 2^-9 in 1..7    */
+    int m = (int)ldexpf(r, 3 - (e - 1)) - 8;
+    return (uint8_t)(sign | (E << 3) | m);
+}
+
 /* R2: x_i * w_i / sqrt(mean(x^2) + eps) */
 void oracle_rmsnorm(const float* x, const uint16_t* w, float eps,
                     int32_t n_rows, int32_t H, float* out)
@@ -118,10 +151,17 @@ int32_t oracle_kv_append(const oracle_config* c, const oracle_batch* b,
     return 0;
 }
 
+/* One cached element: a bf16 value, or (R15) an 8-bit code times the pool's scale */
+static float cache_value(const void* pages, size_t idx, int fp8, float scale)
+{
+    if (fp8) return oracle_e4m3_to_f32(((const uint8_t*)pages)[idx]) * scale;
+    return oracle_bf16_to_f32(((const uint16_t*)pages)[idx]);
+}
+
 /* Eq. 4, then the weighted value sum of Eq. 5, for every query head of one token */
-void oracle_attention_token(const oracle_config* c, const oracle_batch* b,
+static void attention_token(const oracle_config* c, const oracle_batch* b,
                             int32_t r, int32_t pos, const float* q,
-                            const uint16_t* k_pages, const uint16_t* v_pages,
+                            const void* k_pages, const void* v_pages, int fp8, float k_scale, float v_scale,
                             float* out)
 {
     int32_t d = c->head_dim, n_kv = c->n_kv_heads;
@@ -135,9 +175,9 @@ void oracle_attention_token(const oracle_config* c, const oracle_batch* b,
         const float* qa = q + (size_t)a * d;
         float m = -INFINITY;
         for (int32_t j = 0; j < n_keys; ++j) {
-            const uint16_t* kj = k_pages + ((size_t)slot_of(c, b, r, j) * n_kv + kvh) * d;
+            size_t kj = ((size_t)slot_of(c, b, r, j) * n_kv + kvh) * d;
             acc_t dot = 0;
-            for (int32_t i = 0; i < d; ++i) dot += (acc_t)qa[i] * (acc_t)oracle_bf16_to_f32(kj[i]);
+            for (int32_t i = 0; i < d; ++i) dot += (acc_t)qa[i] * (acc_t)cache_value(k_pages, kj + i, fp8, k_scale);
             s[j] = (float)dot * scale;
             if (s[j] > m) m = s[j];
         }
@@ -149,17 +189,55 @@ void oracle_attention_token(const oracle_config* c, const oracle_batch* b,
         acc_t o[d];
         for (int32_t i = 0; i < d; ++i) o[i] = 0;
         for (int32_t j = 0; j < n_keys; ++j) {
-            const uint16_t* vj = v_pages + ((size_t)slot_of(c, b, r, j) * n_kv + kvh) * d;
-            for (int32_t i = 0; i < d; ++i) o[i] += (acc_t)s[j] * (acc_t)oracle_bf16_to_f32(vj[i]);
+            size_t vj = ((size_t)slot_of(c, b, r, j) * n_kv + kvh) * d;
+            for (int32_t i = 0; i < d; ++i) o[i] += (acc_t)s[j] * (acc_t)cache_value(v_pages, vj + i, fp8, v_scale);
         }
         for (int32_t i = 0; i < d; ++i) out[(size_t)a * d + i] = (float)(o[i] / denom);
     }
     free(s);
 }
 
-int32_t oracle_layer_step(const oracle_config* c, const oracle_batch* b,
+void oracle_attention_token(const oracle_config* c, const oracle_batch* b,
+                            int32_t r, int32_t pos, const float* q,
+                            const uint16_t* k_pages, const uint16_t* v_pages,
+                            float* out)
+{
+    attention_token(c, b, r, pos, q, k_pages, v_pages, 0, 1.0f, 1.0f, out);
+}
+
+void oracle_attention_token_fp8kv(const oracle_config* c, const oracle_batch* b,
+                                  int32_t r, int32_t pos, const float* q,
+                                  const uint8_t* k_pages, const uint8_t* v_pages, float k_scale, float v_scale,
+                                  float* out)
+{
+    attention_token(c, b, r, pos, q, k_pages, v_pages, 1, k_scale, v_scale, out);
+}
+
+/* R15: the step's keys and values as 8-bit codes of x / scale, written to their slots */
+static int32_t kv_append_fp8(const oracle_config* c, const oracle_batch* b, const float* qkv, int32_t qkv_dim, int32_t q_dim,
+                             uint8_t* k_pages, uint8_t* v_pages, int32_t num_pages, float k_scale, float v_scale)
+{
+    size_t row = (size_t)c->n_kv_heads * c->head_dim;
+    float k_inv = (float)(1.0 / (double)k_scale), v_inv = (float)(1.0 / (double)v_scale);
+    for (int32_t r = 0; r < b->num_reqs; ++r) {
+        int32_t q_len = b->q_start[r + 1] - b->q_start[r];
+        int32_t past = b->ctx_len[r] - q_len;
+        for (int32_t j = 0; j < q_len; ++j) {
+            const float* src = qkv + (size_t)(b->q_start[r] + j) * qkv_dim + q_dim;
+            int64_t slot = slot_of(c, b, r, past + j);
+            if (slot < 0 || slot >= (int64_t)num_pages * c->page_size) return -1;
+            for (size_t i = 0; i < row; ++i) {
+                k_pages[(size_t)slot * row + i] = oracle_f32_to_e4m3(src[i] * k_inv);
+                v_pages[(size_t)slot * row + i] = oracle_f32_to_e4m3(src[row + i] * v_inv);
+            }
+        }
+    }
+    return 0;
+}
+
+static int32_t layer_step(const oracle_config* c, const oracle_batch* b,
                           const oracle_weights* w, const uint16_t* x,
-                          uint16_t* k_pages, uint16_t* v_pages, int32_t num_pages,
+                          void* k_pages, void* v_pages, int32_t num_pages, int fp8, float k_scale, float v_scale,
                           const int32_t* rows, int32_t n_rows,
                           float* y_f32, uint16_t* y_bf16,
                           float* tap_attn_out, float* tap_x1)
@@ -211,7 +289,8 @@ int32_t oracle_layer_step(const oracle_config* c, const oracle_batch* b,
             vb[(size_t)t * kv_dim + i] = oracle_f32_to_bf16(row[q_dim + kv_dim + i]);
         }
     }
-    int32_t rc = oracle_kv_append(c, b, kb, vb, k_pages, v_pages, num_pages, NULL);
+    int32_t rc = fp8 ? kv_append_fp8(c, b, qkv, qkv_dim, q_dim, (uint8_t*)k_pages, (uint8_t*)v_pages, num_pages, k_scale, v_scale)
+                     : oracle_kv_append(c, b, kb, vb, (uint16_t*)k_pages, (uint16_t*)v_pages, num_pages, NULL);
     free(kb); free(vb);
     if (rc) { free(tok_req); free(tok_pos); free(xf); free(qkv); return -4; }
 
@@ -231,8 +310,8 @@ int32_t oracle_layer_step(const oracle_config* c, const oracle_batch* b,
 #pragma omp parallel for schedule(dynamic, 1)
     for (int32_t i = 0; i < n_out; ++i) {
         int32_t t = sel[i];
-        oracle_attention_token(c, b, tok_req[t], tok_pos[t], qkv + (size_t)t * qkv_dim,
-                               k_pages, v_pages, attn + (size_t)i * q_dim);
+        attention_token(c, b, tok_req[t], tok_pos[t], qkv + (size_t)t * qkv_dim,
+                        k_pages, v_pages, fp8, k_scale, v_scale, attn + (size_t)i * q_dim);
     }
     free(qkv);
     if (tap_attn_out) memcpy(tap_attn_out, attn, sizeof(float) * (size_t)n_out * q_dim);
@@ -272,6 +351,27 @@ int32_t oracle_layer_step(const oracle_config* c, const oracle_batch* b,
     }
     free(mlp); free(x1); free(sel); free(tok_req); free(tok_pos);
     return 0;
+}
+
+int32_t oracle_layer_step(const oracle_config* c, const oracle_batch* b,
+                          const oracle_weights* w, const uint16_t* x,
+                          uint16_t* k_pages, uint16_t* v_pages, int32_t num_pages,
+                          const int32_t* rows, int32_t n_rows,
+                          float* y_f32, uint16_t* y_bf16,
+                          float* tap_attn_out, float* tap_x1)
+{
+    return layer_step(c, b, w, x, k_pages, v_pages, num_pages, 0, 1.0f, 1.0f, rows, n_rows, y_f32, y_bf16, tap_attn_out, tap_x1);
+}
+
+int32_t oracle_layer_step_fp8kv(const oracle_config* c, const oracle_batch* b,
+                                const oracle_weights* w, const uint16_t* x,
+                                uint8_t* k_pages, uint8_t* v_pages, int32_t num_pages, float k_scale, float v_scale,
+                                const int32_t* rows, int32_t n_rows,
+                                float* y_f32, uint16_t* y_bf16,
+                                float* tap_attn_out, float* tap_x1)
+{
+    if (!(k_scale > 0.0f) || !(v_scale > 0.0f)) return -7;
+    return layer_step(c, b, w, x, k_pages, v_pages, num_pages, 1, k_scale, v_scale, rows, n_rows, y_f32, y_bf16, tap_attn_out, tap_x1);
 }
 
 /* Embedding -> n_layers x layer step -> final norm -> output layer on each request's last token */

@@ -38,6 +38,13 @@
  *   R10 a shared prefix is nothing but equal leading block-table entries; the
  *       oracle has no notion of prefix ids.
  *   R14 greedy next token: the largest logit, the lowest token id among equal ones.
+ *   R15 quantised cache (a variant; the paper runs 16-bit caches): the pools hold 8-bit floating point
+ *       codes (1 sign, 4 exponent, 3 mantissa bits, bias 7, largest magnitude 448, no infinity) of
+ *       x / scale with one scale per pool, given by the caller (as an engine calibrates it offline).
+ *       The step's rotated keys and its values are quantised ONCE from their fp32 values:
+ *       code = round-to-nearest-even(x * (1 / scale)), magnitudes above 448 become 448, with the
+ *       reciprocal formed in double and rounded to fp32; a cached element reads back as
+ *       value(code) * scale in fp32.  Everything else is unchanged.
  *
  * Precision: inputs, weights and the cache hold bf16 bit patterns (uint16_t);
  * all arithmetic is fp32 with acc_t accumulators (float, or double when built
@@ -118,6 +125,16 @@ void oracle_attention_token(const oracle_config* c, const oracle_batch* b,
                             const uint16_t* k_pages, const uint16_t* v_pages,
                             float* out);
 
+/* R15: the 8-bit format of the quantised cache. */
+float   oracle_e4m3_to_f32(uint8_t code);
+uint8_t oracle_f32_to_e4m3(float x);
+
+/* oracle_attention_token over a quantised cache (R15). */
+void oracle_attention_token_fp8kv(const oracle_config* c, const oracle_batch* b,
+                                  int32_t r, int32_t pos, const float* q,
+                                  const uint8_t* k_pages, const uint8_t* v_pages, float k_scale, float v_scale,
+                                  float* out);
+
 /* The whole step.  x: [T, H] bf16.  The cache is updated in place for every
  * token of the batch.  rows/n_rows select which token rows get the rest of the
  * layer (NULL/0 = all T, in order); y_f32 [n_out, H] and optional y_bf16 are
@@ -130,6 +147,15 @@ int32_t oracle_layer_step(const oracle_config* c, const oracle_batch* b,
                           const int32_t* rows, int32_t n_rows,
                           float* y_f32, uint16_t* y_bf16,
                           float* tap_attn_out, float* tap_x1);
+
+/* oracle_layer_step with the quantised cache of R15: pools [num_pages, P, n_kv, d] of 8-bit codes.
+ * Returns -7 for a scale that is not positive. */
+int32_t oracle_layer_step_fp8kv(const oracle_config* c, const oracle_batch* b,
+                                const oracle_weights* w, const uint16_t* x,
+                                uint8_t* k_pages, uint8_t* v_pages, int32_t num_pages, float k_scale, float v_scale,
+                                const int32_t* rows, int32_t n_rows,
+                                float* y_f32, uint16_t* y_bf16,
+                                float* tap_attn_out, float* tap_x1);
 
 /* A stack of identical-shape layers between an embedding table and an output
  * layer (Sec. 2.3 "LLM Inference": embedding layer, Transformer layers, output

@@ -98,6 +98,16 @@ class Oracle:
         L.oracle_model_step.restype = C.c_int32
         L.oracle_model_step.argtypes = [C.c_void_p] * 6 + [C.c_int32, C.c_void_p, C.c_void_p]
         L.oracle_num_threads.restype = C.c_int32
+        L.oracle_e4m3_to_f32.restype = C.c_float
+        L.oracle_e4m3_to_f32.argtypes = [C.c_uint8]
+        L.oracle_f32_to_e4m3.restype = C.c_uint8
+        L.oracle_f32_to_e4m3.argtypes = [C.c_float]
+        L.oracle_attention_token_fp8kv.restype = None
+        L.oracle_attention_token_fp8kv.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
+                                                   C.c_void_p, C.c_float, C.c_float, C.c_void_p]
+        L.oracle_layer_step_fp8kv.restype = C.c_int32
+        L.oracle_layer_step_fp8kv.argtypes = ([C.c_void_p] * 6 + [C.c_int32, C.c_float, C.c_float, C.c_void_p, C.c_int32]
+                                              + [C.c_void_p] * 4)
         L.oracle_greedy_sample.restype = None
         L.oracle_greedy_sample.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p]
 
@@ -171,15 +181,34 @@ class Oracle:
         del keep
         return out
 
-    def layer_step(self, shape, batch, weights: dict, x_bits, k_pages, v_pages, rows=None) -> StepResult:
-        """One layer step; k_pages / v_pages are updated in place."""
+    def e4m3_to_f32(self, code: int) -> float:
+        return float(self.lib.oracle_e4m3_to_f32(int(code)))
+
+    def f32_to_e4m3(self, x: float) -> int:
+        return int(self.lib.oracle_f32_to_e4m3(float(x)))
+
+    def attention_token_fp8kv(self, shape, batch, r, pos, q, k_pages, v_pages, k_scale, v_scale):
+        cfg = self._cfg(shape)
+        b, keep = self._batch(batch)
+        q = _chk(np.ascontiguousarray(q), np.float32, "q")
+        out = np.empty((shape.n_q_heads, shape.head_dim), np.float32)
+        self.lib.oracle_attention_token_fp8kv(C.byref(cfg), C.byref(b), int(r), int(pos), _ptr(q),
+                                              _ptr(_chk(k_pages, np.uint8, "k_pages")), _ptr(_chk(v_pages, np.uint8, "v_pages")),
+                                              float(k_scale), float(v_scale), _ptr(out))
+        del keep
+        return out
+
+    def layer_step(self, shape, batch, weights: dict, x_bits, k_pages, v_pages, rows=None, kv_scales=None) -> StepResult:
+        """One layer step; k_pages / v_pages are updated in place.  kv_scales = (k_scale, v_scale) selects the
+        quantised cache: the pools are then uint8 arrays of 8-bit codes."""
         cfg = self._cfg(shape)
         b, keep = self._batch(batch)
         wk = {k: _chk(np.ascontiguousarray(v), np.uint16, k) for k, v in weights.items()}
         w = _Weights(*[_ptr(wk[n]) for n, _ in _Weights._fields_])
         x_bits = _chk(np.ascontiguousarray(x_bits), np.uint16, "x")
-        _chk(k_pages, np.uint16, "k_pages")
-        _chk(v_pages, np.uint16, "v_pages")
+        pool_dtype = np.uint16 if kv_scales is None else np.uint8
+        _chk(k_pages, pool_dtype, "k_pages")
+        _chk(v_pages, pool_dtype, "v_pages")
         T = int(batch.q_start[-1])
         assert x_bits.shape == (T, shape.hidden), (x_bits.shape, T, shape.hidden)
         if rows is not None:
@@ -189,11 +218,15 @@ class Oracle:
         yb = np.empty((n_out, shape.hidden), np.uint16)
         attn = np.empty((n_out, shape.n_q_heads * shape.head_dim), np.float32)
         x1 = np.empty((n_out, shape.hidden), np.float32)
-        rc = self.lib.oracle_layer_step(C.byref(cfg), C.byref(b), C.byref(w), _ptr(x_bits),
-                                        _ptr(k_pages), _ptr(v_pages), k_pages.shape[0],
-                                        _ptr(rows) if rows is not None and len(rows) else None,
-                                        0 if rows is None else len(rows),
-                                        _ptr(y), _ptr(yb), _ptr(attn), _ptr(x1))
+        tail = (_ptr(rows) if rows is not None and len(rows) else None, 0 if rows is None else len(rows),
+                _ptr(y), _ptr(yb), _ptr(attn), _ptr(x1))
+        if kv_scales is None:
+            rc = self.lib.oracle_layer_step(C.byref(cfg), C.byref(b), C.byref(w), _ptr(x_bits),
+                                            _ptr(k_pages), _ptr(v_pages), k_pages.shape[0], *tail)
+        else:
+            rc = self.lib.oracle_layer_step_fp8kv(C.byref(cfg), C.byref(b), C.byref(w), _ptr(x_bits),
+                                                  _ptr(k_pages), _ptr(v_pages), k_pages.shape[0],
+                                                  float(kv_scales[0]), float(kv_scales[1]), *tail)
         if rc:
             raise ValueError(f"oracle_layer_step rc={rc}")
         del keep, wk

@@ -238,6 +238,17 @@ def make_cache(shape: LayerShape, num_pages: int, seed: int, fill: bool = True):
     return k, v
 
 
+def make_cache_fp8(shape: LayerShape, num_pages: int, seed: int):
+    """K and V page pools [num_pages, P, n_kv, d] of 8-bit floating point codes (1-4-3 bits), every slot filled:
+    uniformly drawn codes with the two NaN patterns (0x7f, 0xff) replaced.  A format detail only, no arithmetic."""
+    shp = (num_pages, shape.page_size, shape.n_kv_heads, shape.head_dim)
+    rng = np.random.default_rng(seed + 15485863)
+    # codes below exponent field 12 (magnitudes under 32): a cache of unit-scale keys and values
+    k = (rng.integers(0, 96, shp, dtype=np.uint8) | (rng.integers(0, 2, shp, dtype=np.uint8) << 7)).astype(np.uint8)
+    v = (rng.integers(0, 96, shp, dtype=np.uint8) | (rng.integers(0, 2, shp, dtype=np.uint8) << 7)).astype(np.uint8)
+    return k, v
+
+
 # ----------------------------------------------------------------------------
 # the benchmark configurations
 # ----------------------------------------------------------------------------

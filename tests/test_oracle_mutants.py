@@ -36,6 +36,12 @@ MUTANTS = [
     ("stream_not_rounded_between_layers", "NULL, 0, y, x, NULL, NULL);", "NULL, 0, y, NULL, NULL, NULL); for (size_t i = 0; i < (size_t)T * H; ++i) x[i] = (uint16_t)(oracle_f32_to_bf16(y[i]) & 0xfff0u);"),
     ("greedy_last_of_equals", "if (!have || row[v] > row[best]) { best = v; have = 1; }", "if (!have || row[v] >= row[best]) { best = v; have = 1; }"),
     ("greedy_smallest", "if (!have || row[v] > row[best]) { best = v; have = 1; }", "if (!have || row[v] < row[best]) { best = v; have = 1; }"),
+    ("e4m3_truncates", "float n = nearbyintf(ldexpf(a, -q));", "float n = floorf(ldexpf(a, -q));"),
+    ("e4m3_no_saturation", "if (a >= 448.0f) return (uint8_t)(sign | 0x7e);", "if (a >= 1e30f) return (uint8_t)(sign | 0x7e);"),
+    ("e4m3_bias", "else        mag = ldexpf((float)(8 + m), e - 7 - 3);", "else        mag = ldexpf((float)(8 + m), e - 8 - 3);"),
+    ("quantised_scale_dropped_on_read", "return oracle_e4m3_to_f32(((const uint8_t*)pages)[idx]) * scale;", "return oracle_e4m3_to_f32(((const uint8_t*)pages)[idx]);"),
+    ("quantised_v_with_k_scale", "v_pages[(size_t)slot * row + i] = oracle_f32_to_e4m3(src[row + i] * v_inv);", "v_pages[(size_t)slot * row + i] = oracle_f32_to_e4m3(src[row + i] * k_inv);"),
+    ("quantised_k_before_rotation_slot", "k_pages[(size_t)slot * row + i] = oracle_f32_to_e4m3(src[i] * k_inv);", "k_pages[(size_t)slot * row + i] = oracle_f32_to_e4m3(src[i] * k_scale);"),
     ("softmax_unnormalised", "out[(size_t)a * d + i] = (float)(o[i] / denom);", "out[(size_t)a * d + i] = (float)(o[i]);"),
 ]
 

@@ -482,6 +482,135 @@ def test_greedy_sample_is_the_first_largest_logit(oracle):
     assert oracle.greedy_sample(last)[0] == 63
 
 
+# ---------------------------------------------------------------------------
+# quantised cache (reading R15)
+# ---------------------------------------------------------------------------
+def test_e4m3_format_matches_the_library_type(oracle):
+    """The 8-bit format against torch's float8_e4m3fn: every code decodes to the same value; random and boundary values
+    encode to the same code (round to nearest even); exact midpoints go to the even neighbour; round trips are exact;
+    above 448 the code saturates (the library type has no saturation: checked by definition)."""
+    codes = np.arange(256, dtype=np.uint8)
+    lib = torch.from_numpy(codes).view(torch.float8_e4m3fn).float().numpy()
+    mine = np.array([oracle.e4m3_to_f32(int(c)) for c in codes], np.float32)
+    np.testing.assert_array_equal(np.isnan(mine), np.isnan(lib))
+    np.testing.assert_array_equal(mine[~np.isnan(lib)], lib[~np.isnan(lib)])
+    assert mine[0x7e] == 448.0 and mine[0x01] == 2.0 ** -9 and mine[0x08] == 2.0 ** -6 and mine[0x38] == 1.0
+    finite = [int(c) for c in codes if not np.isnan(lib[c])]
+    for c in finite:                                                       # round trip, both signs of zero included
+        assert oracle.f32_to_e4m3(float(lib[c])) == c
+    rng = np.random.default_rng(1)
+    x = np.concatenate([rng.standard_normal(4000) * 3, rng.standard_normal(2000) * 0.01, rng.uniform(-448, 448, 2000),
+                        [448.0, -448.0, 447.9, 2.0 ** -10, 2.0 ** -10 * 1.0001, 2.0 ** -10 * 0.9999, 0.0]]).astype(np.float32)
+    want = torch.from_numpy(x).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+    got = np.array([oracle.f32_to_e4m3(float(v)) for v in x], np.uint8)
+    np.testing.assert_array_equal(got, want)
+    pos = sorted(set(float(lib[c]) for c in finite if lib[c] >= 0))
+    for lo, hi in zip(pos[:-1], pos[1:]):                                  # the midpoint of two neighbours goes to the even code
+        mid = np.float32((np.float64(lo) + np.float64(hi)) / 2)
+        c = oracle.f32_to_e4m3(float(mid))
+        assert c % 2 == 0 and oracle.e4m3_to_f32(c) in (lo, hi)
+        assert oracle.f32_to_e4m3(float(np.nextafter(mid, np.float32(1e9)))) == oracle.f32_to_e4m3(hi)
+        assert oracle.f32_to_e4m3(float(np.nextafter(mid, np.float32(-1e9)))) == oracle.f32_to_e4m3(lo)
+    for big in (448.1, 464.0, 480.0, 1e9, float("inf")):                    # saturation
+        assert oracle.f32_to_e4m3(big) == 0x7e and oracle.f32_to_e4m3(-big) == 0xfe
+    assert oracle.f32_to_e4m3(float("nan")) & 0x7f == 0x7f
+
+
+def test_quantised_cache_reads_like_the_16_bit_cache_holding_the_same_values(oracle):
+    """With power-of-two scales every code x scale is a bf16 number, so a 16-bit cache can hold exactly what the
+    quantised one represents: attention over the two must agree bit for bit (same sums in the same order)."""
+    shape = W.TINY_GQA
+    b = W.workload_tiny_prefix(shape=shape).batch
+    k8, v8 = W.make_cache_fp8(shape, b.num_pages, 7)
+    ks, vs = 0.25, 2.0
+    deq = np.array([oracle.e4m3_to_f32(c) for c in range(256)], np.float32)
+    kp, vp = W.f32_to_bf16_bits(deq[k8] * np.float32(ks)), W.f32_to_bf16_bits(deq[v8] * np.float32(vs))
+    np.testing.assert_array_equal(W.bf16_bits_to_f32(kp), deq[k8] * np.float32(ks))         # representable: nothing was rounded
+    rng = np.random.default_rng(8)
+    for r in range(b.num_reqs):
+        pos = int(b.ctx_len[r]) - 1
+        q = rng.standard_normal((shape.n_q_heads, shape.head_dim)).astype(np.float32)
+        got = oracle.attention_token_fp8kv(shape, b, r, pos, q, k8, v8, ks, vs)
+        want = oracle.attention_token(shape, b, r, pos, q, kp, vp)
+        np.testing.assert_array_equal(got, want)
+    # a scale that is not a power of two: the dequantised values in fp64, Eq. 4-5 written out
+    ks, vs = 0.3, 0.7
+    r, pos = 0, int(b.ctx_len[0]) - 1
+    q = rng.standard_normal((shape.n_q_heads, shape.head_dim)).astype(np.float32)
+    got = oracle.attention_token_fp8kv(shape, b, r, pos, q, k8, v8, ks, vs)
+    P, group = shape.page_size, shape.n_q_heads // shape.n_kv_heads
+    slots = [int(b.block_table[r][j // P]) * P + j % P for j in range(pos + 1)]
+    K = deq[k8.reshape(-1, shape.n_kv_heads, shape.head_dim)[slots]].astype(np.float64) * np.float64(np.float32(ks))
+    V = deq[v8.reshape(-1, shape.n_kv_heads, shape.head_dim)[slots]].astype(np.float64) * np.float64(np.float32(vs))
+    for a in range(shape.n_q_heads):
+        s = K[:, a // group] @ q[a].astype(np.float64) / np.sqrt(shape.head_dim)
+        w = np.exp(s - s.max())
+        np.testing.assert_allclose(got[a], (w / w.sum()) @ V[:, a // group], rtol=2e-5, atol=2e-6)
+
+
+def test_quantised_cache_layer_step(oracle):
+    """The step with the quantised cache: the appended codes are the library type's rounding of (rotated key x 1 / scale)
+    and (value x 1 / scale); the attention output is the pinned 16-bit attention over a cache holding the same values;
+    caching stays a memo (decoding one token at a time = one pass over the prompt, exactly); a pool of other codes at
+    unused slots changes nothing."""
+    shape = W.TINY_GQA
+    wl = W.workload_tiny_prefix(shape=shape)
+    b, weights = wl.batch, wl.weights()
+    x = W.make_activations(b.T, shape.hidden, 3)
+    ks, vs = 0.25, 0.125                                                     # powers of two
+    k8, v8 = W.make_cache_fp8(shape, b.num_pages, 9)
+    k0, v0 = k8.copy(), v8.copy()
+    res = oracle.layer_step(shape, b, weights, x, k8, v8, kv_scales=(ks, vs))
+    # what must have been written: pieces that are pinned on their own
+    h = oracle.rmsnorm(W.bf16_bits_to_f32(x), weights["w_in_norm"], shape.rms_eps)
+    qkv = oracle.linear(weights["w_qkv"], h)
+    d, nq, nkv, P = shape.head_dim, shape.n_q_heads, shape.n_kv_heads, shape.page_size
+    pos = np.concatenate([np.arange(p, p + q) for p, q in zip(b.past, b.q_len)])
+    for t in range(b.T):
+        for hd in range(nq + nkv):
+            qkv[t, hd * d:(hd + 1) * d] = oracle.rope(qkv[t, hd * d:(hd + 1) * d], int(pos[t]), shape.rope_base)
+    slots = oracle.kv_append(shape, b, np.zeros((b.T, nkv, d), np.uint16), np.zeros((b.T, nkv, d), np.uint16),
+                             np.zeros(k8.shape, np.uint16), np.zeros(k8.shape, np.uint16))
+    want_k = torch.from_numpy(qkv[:, nq * d:(nq + nkv) * d] * np.float32(1 / ks)).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+    want_v = torch.from_numpy(qkv[:, (nq + nkv) * d:] * np.float32(1 / vs)).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+    np.testing.assert_array_equal(k8.reshape(-1, nkv * d)[slots], want_k)
+    np.testing.assert_array_equal(v8.reshape(-1, nkv * d)[slots], want_v)
+    mask = np.ones(k8.shape[0] * P, bool)
+    mask[slots] = False
+    np.testing.assert_array_equal(k8.reshape(-1, nkv * d)[mask], k0.reshape(-1, nkv * d)[mask])     # nothing else was written
+    np.testing.assert_array_equal(v8.reshape(-1, nkv * d)[mask], v0.reshape(-1, nkv * d)[mask])
+    # attention over the quantised cache = the 16-bit attention over the same values
+    deq = np.array([oracle.e4m3_to_f32(c) for c in range(256)], np.float32)
+    kp, vp = W.f32_to_bf16_bits(deq[k8] * np.float32(ks)), W.f32_to_bf16_bits(deq[v8] * np.float32(vs))
+    t = 0
+    for r in range(b.num_reqs):
+        for j in range(int(b.q_len[r])):
+            want = oracle.attention_token(shape, b, r, int(b.past[r]) + j, qkv[t, :nq * d].reshape(nq, d), kp, vp)
+            np.testing.assert_array_equal(res.attn_out[t], want.reshape(-1))
+            t += 1
+    # a saturating scale: codes stop at the largest magnitude
+    k9, v9 = W.make_cache_fp8(shape, b.num_pages, 9)
+    oracle.layer_step(shape, b, weights, x, k9, v9, kv_scales=(1e-4, 1e-4))
+    assert set(np.unique(k9.reshape(-1, nkv * d)[slots] & 0x7f)) <= set(range(0x7f)) and (k9.reshape(-1, nkv * d)[slots] & 0x7f).max() == 0x7e
+    # memoisation: one token at a time == one pass, exactly
+    L = 30
+    outs = []
+    for sched in ([[(0, L)]], [[(0, 1)] for _ in range(L)], [[(0, 11)], [(0, 19)]]):
+        flow = make_flow(shape, [L], sched, seed=50)
+        kq, vq = W.make_cache_fp8(shape, flow.num_pages, 51)
+        ys = run_flow(flow, lambda bb, xx: oracle.layer_step(shape, bb, weights, xx, kq, vq, kv_scales=(ks, vs)).y_f32)
+        outs.append((ys[0], kq, vq))
+    for y, kq, vq in outs[1:]:
+        np.testing.assert_array_equal(y, outs[0][0])
+        np.testing.assert_array_equal(kq, outs[0][1])
+        np.testing.assert_array_equal(vq, outs[0][2])
+    # and close to the 16-bit step: the quantisation is fine enough not to change the output by more than a few percent
+    kp16 = W.f32_to_bf16_bits(deq[k0] * np.float32(ks))
+    vp16 = W.f32_to_bf16_bits(deq[v0] * np.float32(vs))
+    y16 = oracle.layer_step(shape, b, weights, x, kp16, vp16).y_f32
+    assert np.linalg.norm(res.y_f32 - y16) / np.linalg.norm(y16) < 3e-2
+
+
 def test_golden_tiny_layer_step_is_stable():
     """The frozen oracle outputs (written by tests/golden/make_golden.py) still hold."""
     import os

@@ -101,10 +101,23 @@ typedef struct {
     int32_t        num_pages;      /* pages in the cache pools the batch addresses */
 } relserve_batch_desc;
 
+/* Cache pools.  dtype RELSERVE_KV_BF16: 16-bit pools as described at the top.  dtype RELSERVE_KV_FP8: a
+ * variant with half the bytes per cached token (the paper runs 16-bit caches; decode attention is bound by
+ * exactly these bytes, Sec. 2.3 "Prefill and Decode Phases"): the pools hold one byte per element, an 8-bit
+ * floating point code (1 sign, 4 exponent, 3 mantissa bits, bias 7, largest magnitude 448, no infinity) of
+ * x / scale, with one positive scale per pool given by the caller.  The step's rotated keys and its values are
+ * quantised once from their fp32 values: round to nearest even of x * (1 / scale), magnitudes above 448 become
+ * 448 (the code of a NaN input is unspecified); attention reads value(code) * scale.  Served by
+ * relserve_layer_step(_static), relserve_model_step, relserve_qkv_rope_append and relserve_attention; the
+ * stand-alone relserve_kv_append / relserve_rope_append take 16-bit pools only. */
+enum { RELSERVE_KV_BF16 = 0, RELSERVE_KV_FP8 = 1 };
 typedef struct {
-    void*   k_pages;     /* device, [num_pages, P, n_kv, d] bf16 */
+    void*   k_pages;     /* device, [num_pages, P, n_kv, d] bf16 (or 8-bit codes) */
     void*   v_pages;     /* device, same shape */
     int32_t num_pages;
+    int32_t dtype;       /* RELSERVE_KV_BF16 or RELSERVE_KV_FP8 */
+    float   k_scale;     /* RELSERVE_KV_FP8 only: > 0 */
+    float   v_scale;
 } relserve_kv_cache;
 
 typedef struct {          /* all device, bf16 */

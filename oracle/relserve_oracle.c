@@ -273,6 +273,8 @@ static int32_t layer_step(const oracle_config* c, const oracle_batch* b,
     /* 1. input norm (R2), 2. q/k/v (Eq. 3) for every token of the batch */
     float* h = (float*)malloc(sizeof(float) * (size_t)T * H);
     oracle_rmsnorm(xf, w->w_in_norm, c->rms_eps, T, H, h);
+    if (fp8)    /* R15: the quantisation decision is taken in the kernel's precision: bf16 inputs, fp32 sums */
+        for (size_t i = 0; i < (size_t)T * H; ++i) h[i] = oracle_bf16_to_f32(oracle_f32_to_bf16(h[i]));
     float* qkv = (float*)malloc(sizeof(float) * (size_t)T * qkv_dim);
     oracle_linear(w->w_qkv, qkv_dim, H, h, T, qkv);
     free(h);

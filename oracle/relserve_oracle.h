@@ -44,7 +44,11 @@
  *       The step's rotated keys and its values are quantised ONCE from their fp32 values:
  *       code = round-to-nearest-even(x * (1 / scale)), magnitudes above 448 become 448, with the
  *       reciprocal formed in double and rounded to fp32; a cached element reads back as
- *       value(code) * scale in fp32.  Everything else is unchanged.
+ *       value(code) * scale in fp32.  A code is an integer decided by floating point, so the decision is
+ *       taken in the precision the kernel takes it in: in this variant the normed activations are
+ *       rounded to bf16 before the q/k/v projection (bf16 inputs, fp32 sums); otherwise two correct
+ *       implementations would disagree on the ~5 % of codes whose value lies next to a rounding boundary.
+ *       Everything else is unchanged.
  *
  * Precision: inputs, weights and the cache hold bf16 bit patterns (uint16_t);
  * all arithmetic is fp32 with acc_t accumulators (float, or double when built

@@ -59,7 +59,22 @@ class BatchDesc(C.Structure):
 
 
 class KVCache(C.Structure):
-    _fields_ = [("k_pages", C.c_void_p), ("v_pages", C.c_void_p), ("num_pages", C.c_int32)]
+    _fields_ = [("k_pages", C.c_void_p), ("v_pages", C.c_void_p), ("num_pages", C.c_int32), ("dtype", C.c_int32),
+                ("k_scale", C.c_float), ("v_scale", C.c_float)]
+
+
+class QuantPool:
+    """A cache pool of 8-bit codes (torch uint8 or float8_e4m3fn tensor [num_pages, P, n_kv, d]) and its scale."""
+
+    def __init__(self, codes, scale: float):
+        self.codes, self.scale = codes, float(scale)
+
+    def data_ptr(self):
+        return self.codes.data_ptr()
+
+    @property
+    def shape(self):
+        return self.codes.shape
 
 
 WEIGHT_NAMES = ("w_in_norm", "w_qkv", "w_o", "w_post_norm", "w_gate_up", "w_down")
@@ -184,7 +199,11 @@ def _desc(batch):
 
 
 def _cache(k_pages, v_pages) -> KVCache:
-    return KVCache(k_pages.data_ptr(), v_pages.data_ptr(), k_pages.shape[0])
+    if isinstance(k_pages, QuantPool) != isinstance(v_pages, QuantPool):
+        raise TypeError("both pools must be 16-bit tensors or both QuantPool")
+    if isinstance(k_pages, QuantPool):
+        return KVCache(k_pages.data_ptr(), v_pages.data_ptr(), k_pages.shape[0], 1, k_pages.scale, v_pages.scale)
+    return KVCache(k_pages.data_ptr(), v_pages.data_ptr(), k_pages.shape[0], 0, 1.0, 1.0)
 
 
 # ---- entry points, same names as the C ABI ------------------------------------------------

@@ -24,6 +24,26 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
 }
 __device__ __forceinline__ uint32_t f32_to_bf16_bits(float f) { return pack_bf16x2(f, 0.f) & 0xffffu; }
 
+// Four fp32 values -> four 8-bit floating point codes (1-4-3 bits, bias 7), round to nearest even, in memory order.
+// Magnitudes are limited to 448, the format's largest, before the conversion, so that its own overflow rule never
+// matters.
+__device__ __forceinline__ uint32_t pack_fp8x4(float a, float b, float c, float d) {
+    a = __builtin_amdgcn_fmed3f(a, -448.0f, 448.0f);
+    b = __builtin_amdgcn_fmed3f(b, -448.0f, 448.0f);
+    c = __builtin_amdgcn_fmed3f(c, -448.0f, 448.0f);
+    d = __builtin_amdgcn_fmed3f(d, -448.0f, 448.0f);
+    int r = __builtin_amdgcn_cvt_pk_fp8_f32(a, b, 0, false);
+    r = __builtin_amdgcn_cvt_pk_fp8_f32(c, d, r, true);
+    return (uint32_t)r;
+}
+
+// Eight such codes (8 bytes) -> eight bf16 values (every code is a bf16 number: four significant bits).
+__device__ __forceinline__ uint4 fp8x8_to_bf16x8(uint2 raw) {
+    const f32x2_t a = __builtin_amdgcn_cvt_pk_f32_fp8((int)raw.x, false), b = __builtin_amdgcn_cvt_pk_f32_fp8((int)raw.x, true);
+    const f32x2_t c = __builtin_amdgcn_cvt_pk_f32_fp8((int)raw.y, false), d = __builtin_amdgcn_cvt_pk_f32_fp8((int)raw.y, true);
+    return make_uint4(pack_bf16x2(a[0], a[1]), pack_bf16x2(b[0], b[1]), pack_bf16x2(c[0], c[1]), pack_bf16x2(d[0], d[1]));
+}
+
 // silu(gate) * up = gate * up / (1 + e^-gate) with the hardware exponential and reciprocal (about one unit in the
 // last place each, far below the bf16 rounding of the result); a full-precision division would cost ten instructions.
 __device__ __forceinline__ float silu_mul(float gate, float up) {

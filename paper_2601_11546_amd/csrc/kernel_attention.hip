@@ -51,7 +51,8 @@ struct AttnArgs {
     int32_t max_blocks, page_shift, page_mask;
     int32_t q_pitch, n_q, n_kv, group;
     int32_t dec_by_head;   // decode workgroups take four adjacent kv heads of one token (n_kv % 4 == 0)
-    float scale_log2;  // log2(e) / sqrt(d)
+    float scale_log2;  // log2(e) / sqrt(d), times the key pool's scale when the cache is quantised
+    float v_scale;     // the value pool's scale (1 for 16-bit pools): applied where a row is normalised
 };
 
 // Per-lane running softmax state of one query row (shared by lanes l and l ^ 32, which hold
@@ -101,7 +102,7 @@ __device__ __forceinline__ void state_store(const RowState<D>& st, const AttnArg
                 *reinterpret_cast<float4*>(po + 32 * td + 8 * q4) =
                     make_float4(st.o[td][4 * q4], st.o[td][4 * q4 + 1], st.o[td][4 * q4 + 2], st.o[td][4 * q4 + 3]);
     } else {
-        const float inv = 1.0f / l_tot;
+        const float inv = p.v_scale / l_tot;
         uint16_t* orow = p.out + row_id * D + 4 * g;
 #pragma unroll
         for (int td = 0; td < D / 32; ++td)
@@ -152,7 +153,10 @@ __device__ __forceinline__ void dma16_ptr_nt(const void* gptr, uint32_t lds_addr
 
 typedef short short4_t __attribute__((ext_vector_type(4)));
 
-template <int D>
+// FP8: the pools hold one byte per element (8-bit codes).  A block then goes global -> registers -> LDS: each lane loads
+// the 8 bytes of the chunk it would have received directly, widens them to bf16 (exact) and stores the 16 bytes where the
+// direct load would have put them, so that everything behind the staging is the 16-bit kernel.
+template <int D, bool FP8>
 __device__ __forceinline__ void attn_tile_body(const AttnArgs& p, int item_idx, int kvh) {
     using SM = TileSmem<D>;
     constexpr int BLOCK_N = SM::BLOCK_N;
@@ -218,11 +222,36 @@ __device__ __forceinline__ void attn_tile_body(const AttnArgs& p, int item_idx, 
             dma16_ptr(p.v_pages + off + ((lslot ^ vswz<D>(row)) << 3), base + SM::K_BYTES + j * 4096);
         }
     };
+    uint2 k_raw[IT], v_raw[IT];   // FP8 only: the block on its way through registers
+    auto load_raw = [&](const int64_t (&slots)[IT]) {
+        const uint8_t* k8 = reinterpret_cast<const uint8_t*>(p.k_pages);
+        const uint8_t* v8 = reinterpret_cast<const uint8_t*>(p.v_pages);
+#pragma unroll
+        for (int j = 0; j < IT; ++j) {
+            const int row = (4 * j + wave) * RPI + lrow;
+            const int64_t off = (slots[j] * p.n_kv + kvh) * D;
+            k_raw[j] = *reinterpret_cast<const uint2*>(k8 + off + ((lslot ^ kswz<D>(row)) << 3));
+            v_raw[j] = *reinterpret_cast<const uint2*>(v8 + off + ((lslot ^ vswz<D>(row)) << 3));
+        }
+    };
+    auto store_raw = [&](int buf) {
+        unsigned char* base = smem + buf * SM::STAGE + wave * 1024 + lane * 16;
+#pragma unroll
+        for (int j = 0; j < IT; ++j) {
+            *reinterpret_cast<uint4*>(base + j * 4096) = fp8x8_to_bf16x8(k_raw[j]);
+            *reinterpret_cast<uint4*>(base + SM::K_BYTES + j * 4096) = fp8x8_to_bf16x8(v_raw[j]);
+        }
+    };
 
     const int n_blocks = (it.key_end - it.key_begin + BLOCK_N - 1) / BLOCK_N;
     if (n_blocks > 0) {
         lookup(it.key_begin, slot_cur);
-        issue(0, slot_cur);
+        if (FP8) {
+            load_raw(slot_cur);
+            store_raw(0);
+        } else {
+            issue(0, slot_cur);
+        }
         lookup(min(it.key_begin + BLOCK_N, last_key), slot_nxt);
     }
     // Operand addresses inside a stage that do not change from block to block.  K: key row
@@ -318,10 +347,13 @@ __device__ __forceinline__ void attn_tile_body(const AttnArgs& p, int item_idx, 
     for (int b = 0; b < n_blocks; ++b) {
         const int kb0 = it.key_begin + b * BLOCK_N;
         // this block has landed for every wave, and every wave is done with the other buffer
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        if (!FP8) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
         if (b + 1 < n_blocks) {
-            issue((b + 1) & 1, slot_nxt);
+            if (FP8)
+                load_raw(slot_nxt);                               // into registers; stored behind this block's arithmetic
+            else
+                issue((b + 1) & 1, slot_nxt);
             lookup(min(kb0 + 2 * BLOCK_N, last_key), slot_nxt);   // consumed one iteration later
         }
         if (wave_active && kb0 < wave_klim_max) {
@@ -335,6 +367,8 @@ __device__ __forceinline__ void attn_tile_body(const AttnArgs& p, int item_idx, 
             softmax(sc1, masked, kb0 + 32, pf);
             weighted_values(1, stage, pf);
         }
+        // the other buffer is free since the barrier above: every wave had finished the previous block before it
+        if (FP8 && b + 1 < n_blocks) store_raw((b + 1) & 1);
     }
     if (valid) state_store<D>(st, p, it, row_id, g);
 }
@@ -362,7 +396,7 @@ struct DecodeSmem {
 template <int D>
 __device__ __forceinline__ int dvswz(int row) { return D == 128 ? 2 * (row & 7) : 2 * ((row >> 1) & 3); }
 
-template <int D>
+template <int D, bool FP8>
 __device__ __forceinline__ void attn_decode_body(const AttnArgs& p, const AttnItem* items, int n_items, int w) {
     using SM = DecodeSmem<D>;
     constexpr int CH = D / 8;                 // 16-byte chunks per K/V row
@@ -446,6 +480,28 @@ __device__ __forceinline__ void attn_decode_body(const AttnArgs& p, const AttnIt
             dma16_ptr_nt(p.v_pages + off + ((lslot ^ dvswz<D>(row)) << 3), lds0 + SM::K_BYTES + j * 1024);
         }
     };
+    uint2 k_raw[IT], v_raw[IT];   // FP8 only (see attn_tile_body): the block on its way through registers
+    auto load_raw = [&]() {
+        const uint8_t* k8 = reinterpret_cast<const uint8_t*>(p.k_pages);
+        const uint8_t* v8 = reinterpret_cast<const uint8_t*>(p.v_pages);
+#pragma unroll
+        for (int j = 0; j < IT; ++j) {
+            const int row = j * RPI + lrow;
+            const int64_t off = (slots[j] * p.n_kv + kvh) * D;
+            // read once: non-temporal, as the direct loads of the 16-bit path
+            const uint64_t kk = __builtin_nontemporal_load(reinterpret_cast<const uint64_t*>(k8 + off + ((lslot ^ kswz<D>(row)) << 3)));
+            const uint64_t vv = __builtin_nontemporal_load(reinterpret_cast<const uint64_t*>(v8 + off + ((lslot ^ dvswz<D>(row)) << 3)));
+            k_raw[j] = make_uint2((uint32_t)kk, (uint32_t)(kk >> 32));
+            v_raw[j] = make_uint2((uint32_t)vv, (uint32_t)(vv >> 32));
+        }
+    };
+    auto store_raw = [&]() {
+#pragma unroll
+        for (int j = 0; j < IT; ++j) {
+            *reinterpret_cast<uint4*>(sk + j * 1024 + lane * 16) = fp8x8_to_bf16x8(k_raw[j]);
+            *reinterpret_cast<uint4*>(sk + SM::K_BYTES + j * 1024 + lane * 16) = fp8x8_to_bf16x8(v_raw[j]);
+        }
+    };
     // operand addresses: K fragment (t, ks) = key row 16 t + l16, chunk 4 ks + gq; the transposing V read
     // (td, half) points lane (gq, s = l16) at key 16 half + 4 gq + s / 4 and d = 16 td + 4 (s % 4)
     uint32_t k_off[KS], v_off[TD];
@@ -463,12 +519,22 @@ __device__ __forceinline__ void attn_decode_body(const AttnArgs& p, const AttnIt
     const int n_blocks = (it.key_end - it.key_begin + SM::BLOCK_N - 1) / SM::BLOCK_N;
     if (n_blocks > 0) {
         lookup(it.key_begin);
-        issue();
+        if (FP8) load_raw(); else issue();
         if (n_blocks > 1) lookup(it.key_begin + SM::BLOCK_N);
     }
     for (int b = 0; b < n_blocks; ++b) {
         const int kb0 = it.key_begin + b * SM::BLOCK_N;
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the block has landed
+        if (FP8) {
+            // the block's bytes are in registers: widen them into this wave's LDS rows (the reads below follow the
+            // stores in the wave's own LDS queue), then start the next block's loads
+            store_raw();
+            if (b + 1 < n_blocks) {
+                load_raw();
+                if (b + 2 < n_blocks) lookup(kb0 + 2 * SM::BLOCK_N);
+            }
+        } else {
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the block has landed
+        }
 
         // S^T = K Q^T for two 16-key tiles; lane holds keys kb0 + 16 t + 4 gq + r of query row l16
         f32x4_t s[2];
@@ -491,7 +557,7 @@ __device__ __forceinline__ void attn_decode_body(const AttnArgs& p, const AttnIt
         }
         // everything of this block is in registers: the next block may overwrite the buffer
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-        if (b + 1 < n_blocks) {
+        if (!FP8 && b + 1 < n_blocks) {
             issue();
             if (b + 2 < n_blocks) lookup(kb0 + 2 * SM::BLOCK_N);
         }
@@ -546,7 +612,7 @@ __device__ __forceinline__ void attn_decode_body(const AttnArgs& p, const AttnIt
             *reinterpret_cast<float4*>(po + 16 * td) = make_float4(o_acc[td][0], o_acc[td][1], o_acc[td][2], o_acc[td][3]);
         return;
     }
-    const float inv = 1.0f / l_tot;
+    const float inv = p.v_scale / l_tot;
     uint16_t* orow = p.out + row_id * D + 4 * gq;
 #pragma unroll
     for (int td = 0; td < TD; ++td)
@@ -578,33 +644,33 @@ __global__ void __launch_bounds__(256) attn_merge_kernel(AttnArgs p) {
         L = L * a + w * ml.y;
         o.x = o.x * a + w * v.x; o.y = o.y * a + w * v.y; o.z = o.z * a + w * v.z; o.w = o.w * a + w * v.w;
     }
-    const float inv = 1.0f / L;
+    const float inv = p.v_scale / L;
     *reinterpret_cast<uint2*>(p.out + ((int64_t)mi.tok * p.n_q + hq) * D + d0) =
         make_uint2(pack_bf16x2(o.x * inv, o.y * inv), pack_bf16x2(o.z * inv, o.w * inv));
 }
 
-template <int D>
+template <int D, bool FP8>
 __global__ void __launch_bounds__(256, 2) attn_tile_kernel(AttnArgs p) {
-    attn_tile_body<D>(p, blockIdx.x, blockIdx.y);
+    attn_tile_body<D, FP8>(p, blockIdx.x, blockIdx.y);
 }
 
-template <int D>
+template <int D, bool FP8>
 __global__ void __launch_bounds__(256, 2) attn_decode_kernel(AttnArgs p) {
-    attn_decode_body<D>(p, p.items, p.n_items, blockIdx.x);
+    attn_decode_body<D, FP8>(p, p.items, p.n_items, blockIdx.x);
 }
 
 // Prefill rows (row-tiled items) and decode rows (wave items) over their own keys in ONE launch: the two
 // item lists are independent, each alone leaves part of the chip idle at its end, and both need the same
 // registers and LDS.  Workgroups [0, n_items n_kv) take the tiled items (the longer ones), the rest the
 // decode items, four per workgroup.
-template <int D>
+template <int D, bool FP8>
 __global__ void __launch_bounds__(256, 2) attn_own_keys_kernel(AttnArgs p) {
     const int n_tile_wg = p.n_items * p.n_kv;
     const int b = blockIdx.x;
     if (b < n_tile_wg) {
-        attn_tile_body<D>(p, b % p.n_items, b / p.n_items);
+        attn_tile_body<D, FP8>(p, b % p.n_items, b / p.n_items);
     } else {
-        attn_decode_body<D>(p, p.items_b, p.n_items_b, b - n_tile_wg);
+        attn_decode_body<D, FP8>(p, p.items_b, p.n_items_b, b - n_tile_wg);
     }
 }
 
@@ -612,7 +678,7 @@ inline int decode_wgs(const AttnArgs& p, int n_items) {
     return p.dec_by_head ? n_items * (p.n_kv >> 2) : (n_items + 3) / 4 * p.n_kv;
 }
 
-template <int D>
+template <int D, bool FP8>
 hipError_t launch_d(const AttnArgs& base, const AttnItem* items, int32_t n_items, const AttnItem* items_b,
                     int32_t n_items_b, bool decode, hipStream_t s) {
     constexpr int tile_smem = 2 * TileSmem<D>::STAGE, dec_smem = 4 * DecodeSmem<D>::WAVE_BYTES;
@@ -621,13 +687,13 @@ hipError_t launch_d(const AttnArgs& base, const AttnItem* items, int32_t n_items
     static std::once_flag once;
     static hipError_t attr_status = hipSuccess;
     std::call_once(once, [] {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_tile_kernel<D>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_tile_kernel<D, FP8>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, tile_smem);
         if (e == hipSuccess)
-            e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_decode_kernel<D>),
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_decode_kernel<D, FP8>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, dec_smem);
         if (e == hipSuccess)
-            e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_own_keys_kernel<D>),
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_own_keys_kernel<D, FP8>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, both_smem);
         attr_status = e;
     });
@@ -638,11 +704,11 @@ hipError_t launch_d(const AttnArgs& base, const AttnItem* items, int32_t n_items
     p.items_b = items_b;
     p.n_items_b = n_items_b;
     if (items_b)
-        attn_own_keys_kernel<D><<<dim3(n_items * p.n_kv + decode_wgs(p, n_items_b)), dim3(256), both_smem, s>>>(p);
+        attn_own_keys_kernel<D, FP8><<<dim3(n_items * p.n_kv + decode_wgs(p, n_items_b)), dim3(256), both_smem, s>>>(p);
     else if (decode)
-        attn_decode_kernel<D><<<dim3(decode_wgs(p, n_items)), dim3(256), dec_smem, s>>>(p);
+        attn_decode_kernel<D, FP8><<<dim3(decode_wgs(p, n_items)), dim3(256), dec_smem, s>>>(p);
     else
-        attn_tile_kernel<D><<<dim3(n_items, p.n_kv), dim3(256), tile_smem, s>>>(p);
+        attn_tile_kernel<D, FP8><<<dim3(n_items, p.n_kv), dim3(256), tile_smem, s>>>(p);
     return hipGetLastError();
 }
 
@@ -650,7 +716,7 @@ hipError_t launch_d(const AttnArgs& base, const AttnItem* items, int32_t n_items
 
 hipError_t launch_attention(const BatchDev& b, const relserve_layer& L, const void* q, int32_t q_pitch,
                             const void* k_pages, const void* v_pages, void* out, float* part_o, float* part_ml,
-                            hipStream_t s, relserve_layer* prof) {
+                            hipStream_t s, relserve_layer* prof, KvFormat kv) {
     AttnArgs p{};
     p.attn_tok = b.attn_tok;
     p.tok_pos = b.tok_pos;
@@ -669,13 +735,18 @@ hipError_t launch_attention(const BatchDev& b, const relserve_layer& L, const vo
     p.n_kv = L.cfg.n_kv_heads;
     p.group = L.group;
     p.dec_by_head = L.cfg.n_kv_heads % 4 == 0 ? 1 : 0;
-    p.scale_log2 = (float)(1.4426950408889634 / sqrt((double)L.cfg.head_dim));
+    // a quantised key reads back as code x k_scale: the scale moves into the score's factor, the value pool's to the end
+    p.scale_log2 = (float)(1.4426950408889634 / sqrt((double)L.cfg.head_dim) * (double)kv.k_scale);
+    p.v_scale = kv.v_scale;
     const bool d128 = L.cfg.head_dim == 128;
     hipError_t e = hipSuccess;
     auto launch = [&](int slot, const AttnItem* items, int32_t n, const AttnItem* items_b, int32_t n_b, bool decode) {
         if (e != hipSuccess || n == 0) return;
         profile_mark(prof, slot, s, true);
-        e = d128 ? launch_d<128>(p, items, n, items_b, n_b, decode, s) : launch_d<64>(p, items, n, items_b, n_b, decode, s);
+        if (kv.fp8)
+            e = d128 ? launch_d<128, true>(p, items, n, items_b, n_b, decode, s) : launch_d<64, true>(p, items, n, items_b, n_b, decode, s);
+        else
+            e = d128 ? launch_d<128, false>(p, items, n, items_b, n_b, decode, s) : launch_d<64, false>(p, items, n, items_b, n_b, decode, s);
         profile_mark(prof, slot, s, false);
     };
     p.T = b.T;

@@ -47,6 +47,8 @@ struct GemmArgs {
     uint16_t* k_pages;
     uint16_t* v_pages;
     int32_t n_q, n_kv;
+    int32_t kv_fp8;          // the pools hold 8-bit codes of x * k_inv / x * v_inv (one byte per element)
+    float k_inv, v_inv;
     // split-K (skinny and mid-size T): workgroup b handles tile b % tiles and k steps [split * k_per_split, ...)
     // of that tile and stores its partial sums to slab `split` of accum [n_splits][T, N] fp32; the finish
     // kernel adds the slabs in split order
@@ -165,9 +167,16 @@ __device__ __forceinline__ void gemm_epilogue(const f32x16_t (&acc)[BN / (32 * W
                                 lo[j] = a * co[j] - b * si[j];
                                 hi[j] = a * si[j] + b * co[j];
                             }
-                            *reinterpret_cast<uint2*>(dst + i) = make_uint2(pack_bf16x2(lo[0], lo[1]), pack_bf16x2(lo[2], lo[3]));
-                            *reinterpret_cast<uint2*>(dst + i + D / 2) =
-                                make_uint2(pack_bf16x2(hi[0], hi[1]), pack_bf16x2(hi[2], hi[3]));
+                            if (p.kv_fp8 && head >= p.n_q) {   // quantised cache: one byte per element, quantised from fp32
+                                uint8_t* dst8 = reinterpret_cast<uint8_t*>(p.k_pages) + slot * kv_dim + (head - p.n_q) * D + i;
+                                const float s = p.k_inv;
+                                *reinterpret_cast<uint32_t*>(dst8) = pack_fp8x4(lo[0] * s, lo[1] * s, lo[2] * s, lo[3] * s);
+                                *reinterpret_cast<uint32_t*>(dst8 + D / 2) = pack_fp8x4(hi[0] * s, hi[1] * s, hi[2] * s, hi[3] * s);
+                            } else {
+                                *reinterpret_cast<uint2*>(dst + i) = make_uint2(pack_bf16x2(lo[0], lo[1]), pack_bf16x2(lo[2], lo[3]));
+                                *reinterpret_cast<uint2*>(dst + i + D / 2) =
+                                    make_uint2(pack_bf16x2(hi[0], hi[1]), pack_bf16x2(hi[2], hi[3]));
+                            }
                             // every register is taken by the accumulators: keep the scheduler from starting the
                             // next quads' table loads early (they would spill)
                             __builtin_amdgcn_sched_barrier(0);
@@ -181,8 +190,15 @@ __device__ __forceinline__ void gemm_epilogue(const f32x16_t (&acc)[BN / (32 * W
                         for (int q = 0; q < 4; ++q) {
                             const int i = 32 * tl + 8 * q + 4 * g;
                             const f32x16_t& a = acc[hh * TPH + tl][tm];
-                            *reinterpret_cast<uint2*>(dst + i) = make_uint2(pack_bf16x2(a[4 * q], a[4 * q + 1]),
-                                                                            pack_bf16x2(a[4 * q + 2], a[4 * q + 3]));
+                            if (p.kv_fp8) {
+                                const float s = p.v_inv;
+                                *reinterpret_cast<uint32_t*>(reinterpret_cast<uint8_t*>(p.v_pages) + slot * kv_dim +
+                                                             (head - p.n_q - p.n_kv) * D + i) =
+                                    pack_fp8x4(a[4 * q] * s, a[4 * q + 1] * s, a[4 * q + 2] * s, a[4 * q + 3] * s);
+                            } else {
+                                *reinterpret_cast<uint2*>(dst + i) = make_uint2(pack_bf16x2(a[4 * q], a[4 * q + 1]),
+                                                                                pack_bf16x2(a[4 * q + 2], a[4 * q + 3]));
+                            }
                             __builtin_amdgcn_sched_barrier(0);
                         }
                     }
@@ -763,6 +779,13 @@ __global__ void __launch_bounds__(256) gemm_finish_kernel(GemmArgs p) {
                 l2[j] = a[j] * co[j] - b[j] * si[j];
                 h2[j] = a[j] * si[j] + b[j] * co[j];
             }
+            if (p.kv_fp8 && head >= p.n_q) {
+                uint8_t* dst8 = reinterpret_cast<uint8_t*>(p.k_pages) + slot * kv_dim + (head - p.n_q) * 2 * HALF + i0;
+                const float s = p.k_inv;
+                *reinterpret_cast<uint32_t*>(dst8) = pack_fp8x4(l2[0] * s, l2[1] * s, l2[2] * s, l2[3] * s);
+                *reinterpret_cast<uint32_t*>(dst8 + HALF) = pack_fp8x4(h2[0] * s, h2[1] * s, h2[2] * s, h2[3] * s);
+                return;
+            }
             uint16_t* dst = head < p.n_q ? static_cast<uint16_t*>(p.out) + (int64_t)t * (p.n_q * 2 * HALF) + head * 2 * HALF
                                          : p.k_pages + slot * kv_dim + (head - p.n_q) * 2 * HALF;
             *reinterpret_cast<uint2*>(dst + i0) = make_uint2(pack_bf16x2(l2[0], l2[1]), pack_bf16x2(l2[2], l2[3]));
@@ -770,7 +793,13 @@ __global__ void __launch_bounds__(256) gemm_finish_kernel(GemmArgs p) {
         } else {
             const int c = (u - rot_units) * 4;
             const float4 v = slab_sum(row + (p.n_q + p.n_kv) * 2 * HALF + c, stride, p.n_splits);
-            *reinterpret_cast<uint2*>(p.v_pages + slot * kv_dim + c) = make_uint2(pack_bf16x2(v.x, v.y), pack_bf16x2(v.z, v.w));
+            if (p.kv_fp8) {
+                const float s = p.v_inv;
+                *reinterpret_cast<uint32_t*>(reinterpret_cast<uint8_t*>(p.v_pages) + slot * kv_dim + c) =
+                    pack_fp8x4(v.x * s, v.y * s, v.z * s, v.w * s);
+            } else {
+                *reinterpret_cast<uint2*>(p.v_pages + slot * kv_dim + c) = make_uint2(pack_bf16x2(v.x, v.y), pack_bf16x2(v.z, v.w));
+            }
         }
     } else {
         const int q_per_row = p.N / 4;
@@ -1113,7 +1142,7 @@ hipError_t launch_qkv_d(const GemmArgs& p, hipStream_t s) {
 
 hipError_t launch_qkv_rope_append(const BatchDev& b, const relserve_layer& L, const void* h, const void* w_qkv,
                                   void* q_out, void* k_pages, void* v_pages, hipStream_t s, float* accum,
-                                  bool w_packed) {
+                                  bool w_packed, KvFormat kv) {
     if (b.T == 0) return hipSuccess;
     const int32_t K = L.cfg.hidden;
     if ((int64_t)b.T * K >= ((int64_t)1 << 31) || (int64_t)L.qkv_dim * K >= ((int64_t)1 << 31))
@@ -1133,6 +1162,9 @@ hipError_t launch_qkv_rope_append(const BatchDev& b, const relserve_layer& L, co
     p.v_pages = static_cast<uint16_t*>(v_pages);
     p.n_q = L.cfg.n_q_heads;
     p.n_kv = L.cfg.n_kv_heads;
+    p.kv_fp8 = kv.fp8 ? 1 : 0;
+    p.k_inv = (float)(1.0 / (double)kv.k_scale);      // reciprocal in double, rounded once
+    p.v_inv = (float)(1.0 / (double)kv.v_scale);
     p.accum = accum;
     if (skinny_applies(p.T, p.N, p.K, accum))
         return L.cfg.head_dim == 128 ? launch_skinny<EPI_QKV_ROPE, 128>(p, s) : launch_skinny<EPI_QKV_ROPE, 64>(p, s);

@@ -81,8 +81,21 @@ int32_t static_scratch(void** out) {
     return RELSERVE_OK;
 }
 
-int32_t check_cache(const relserve_batch* b, const relserve_kv_cache& cache) {
+KvFormat kv_format(const relserve_kv_cache& cache) {
+    KvFormat f;
+    f.fp8 = cache.dtype == RELSERVE_KV_FP8;
+    if (f.fp8) f.k_scale = cache.k_scale, f.v_scale = cache.v_scale;
+    return f;
+}
+
+int32_t check_cache(const relserve_batch* b, const relserve_kv_cache& cache, bool fp8_ok = true) {
     if (!cache.k_pages || !cache.v_pages) return RELSERVE_ERR_NULL_POINTER;
+    if (cache.dtype != RELSERVE_KV_BF16 && cache.dtype != RELSERVE_KV_FP8) return RELSERVE_ERR_BAD_ARGUMENT;
+    if (cache.dtype == RELSERVE_KV_FP8) {
+        if (!fp8_ok) return RELSERVE_ERR_BAD_ARGUMENT;
+        if (!(cache.k_scale > 0.0f) || !(cache.v_scale > 0.0f) || !std::isfinite(cache.k_scale) || !std::isfinite(cache.v_scale))
+            return RELSERVE_ERR_BAD_ARGUMENT;
+    }
     if (cache.num_pages < b->dev.num_pages) return RELSERVE_ERR_MISMATCH;
     return RELSERVE_OK;
 }
@@ -497,7 +510,7 @@ int32_t relserve_kv_append(const relserve_layer* L, const relserve_batch* b, con
                            relserve_kv_cache cache, void* stream) {
     drop_stale_hip_error();
     if (int32_t rc = check_pair(L, b)) return rc;
-    if (int32_t rc = check_cache(b, cache)) return rc;
+    if (int32_t rc = check_cache(b, cache, false)) return rc;
     if (b->dev.T == 0) return RELSERVE_OK;
     if (!k || !v) return RELSERVE_ERR_NULL_POINTER;
     hipError_t e = launch_kv_append(b->dev, k, v, cache.k_pages, cache.v_pages, L->kv_dim,
@@ -563,7 +576,7 @@ int32_t relserve_rope_append(const relserve_layer* L, const relserve_batch* b, v
                              relserve_kv_cache cache, void* stream) {
     drop_stale_hip_error();
     if (int32_t rc = check_pair(L, b)) return rc;
-    if (int32_t rc = check_cache(b, cache)) return rc;
+    if (int32_t rc = check_cache(b, cache, false)) return rc;
     if (b->dev.T == 0) return RELSERVE_OK;
     if (!qkv) return RELSERVE_ERR_NULL_POINTER;
     hipError_t e = launch_rope_append(b->dev, *L, qkv, cache.k_pages, cache.v_pages, static_cast<hipStream_t>(stream));
@@ -578,7 +591,7 @@ int32_t relserve_qkv_rope_append(const relserve_layer* L, const relserve_batch* 
     if (b->dev.T == 0) return RELSERVE_OK;
     if (!h || !w_qkv || !q_out) return RELSERVE_ERR_NULL_POINTER;
     hipError_t e = launch_qkv_rope_append(b->dev, *L, h, w_qkv, q_out, cache.k_pages, cache.v_pages,
-                                          static_cast<hipStream_t>(stream));
+                                          static_cast<hipStream_t>(stream), nullptr, false, kv_format(cache));
     return e == hipSuccess ? RELSERVE_OK : RELSERVE_ERR_HIP;
 }
 
@@ -595,7 +608,7 @@ int32_t relserve_attention(const relserve_layer* L, const relserve_batch* b, con
     Workspace w = carve(*L, b->dev.T, workspace);
     if (w.total > workspace_bytes) return RELSERVE_ERR_WORKSPACE;
     hipError_t e = launch_attention(b->dev, *L, q, q_pitch, cache.k_pages, cache.v_pages, out, w.part_o,
-                                    w.part_ml, static_cast<hipStream_t>(stream), nullptr);
+                                    w.part_ml, static_cast<hipStream_t>(stream), nullptr, kv_format(cache));
     return e == hipSuccess ? RELSERVE_OK : RELSERVE_ERR_HIP;
 }
 
@@ -631,11 +644,12 @@ int32_t relserve_layer_step(const relserve_layer* L, const relserve_batch* b, co
     float* accum = w.accum;
     run(S_NORM1, [&] { return launch_rmsnorm(x, false, wt->w_in_norm, c.rms_eps, T, c.hidden, w.h, s); });
     run(S_QKV, [&] {
-        return launch_qkv_rope_append(b->dev, *L, w.h, wt->w_qkv, w.q, cache.k_pages, cache.v_pages, s, accum, packed);
+        return launch_qkv_rope_append(b->dev, *L, w.h, wt->w_qkv, w.q, cache.k_pages, cache.v_pages, s, accum, packed,
+                                      kv_format(cache));
     });
     if (e == hipSuccess)
         e = launch_attention(b->dev, *L, w.q, L->q_dim, cache.k_pages, cache.v_pages, w.attn, w.part_o,
-                             w.part_ml, s, prof);
+                             w.part_ml, s, prof, kv_format(cache));
     run(S_O, [&] { return launch_linear(w.attn, wt->w_o, T, c.hidden, L->q_dim, 1, x, w.x1, s, accum, packed); });
     run(S_NORM2, [&] { return launch_rmsnorm(w.x1, true, wt->w_post_norm, c.rms_eps, T, c.hidden, w.h, s); });
     run(S_GU, [&] {

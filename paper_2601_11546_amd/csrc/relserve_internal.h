@@ -127,14 +127,19 @@ hipError_t launch_linear(const void* a, const void* w, int32_t T, int32_t N, int
 // w [N, K] row-major -> the tiled streaming layout (ceil(N / 256) * 256 * K elements), K % 64 == 0
 hipError_t launch_pack_weight(const void* w, int32_t N, int32_t K, void* out, hipStream_t s);
 // q/k/v projection with rotary embedding and KV append fused into the epilogue: q_out [T, n_q d] bf16.
+// How the cache pools store an element: 16-bit, or an 8-bit code of x / scale (relserve_kv_cache).
+struct KvFormat {
+    bool fp8 = false;
+    float k_scale = 1.0f, v_scale = 1.0f;
+};
 hipError_t launch_qkv_rope_append(const BatchDev& b, const relserve_layer& L, const void* h, const void* w_qkv,
                                   void* q_out, void* k_pages, void* v_pages, hipStream_t s, float* accum = nullptr,
-                                  bool w_packed = false);
+                                  bool w_packed = false, KvFormat kv = KvFormat{});
 // Attention passes; part_o [T + split_slot_cap(T), n_q, d] fp32 and part_ml [.., n_q, 2] fp32 hold the prefix partials
 // (rows of the tokens) and the chunk partials of split decode rows (rows T + slot).
 hipError_t launch_attention(const BatchDev& b, const relserve_layer& L, const void* q, int32_t q_pitch,
                             const void* k_pages, const void* v_pages, void* out, float* part_o,
-                            float* part_ml, hipStream_t s, relserve_layer* prof);
+                            float* part_ml, hipStream_t s, relserve_layer* prof, KvFormat kv = KvFormat{});
 
 void profile_mark(relserve_layer* L, int slot, hipStream_t s, bool begin);
 

@@ -35,15 +35,23 @@ def assert_close(got: np.ndarray, want: np.ndarray, what: str, max_abs=MAX_ABS, 
 class GpuLayer:
     """One layer's device state: weights, cache pools, workspace."""
 
-    def __init__(self, rs, shape, weights_bits: dict, k_pages_bits, v_pages_bits, max_tokens: int, packed: bool = False):
+    def __init__(self, rs, shape, weights_bits: dict, k_pages_bits, v_pages_bits, max_tokens: int, packed: bool = False,
+                 kv_scales=None):
+        """kv_scales = (k_scale, v_scale): the pools are uint8 arrays of 8-bit codes (the quantised cache variant)."""
         self.rs = rs
         self.shape = shape
         self.layer = rs.relserve_layer_create(shape)
         self.weights = {k: dev_bf16(v) for k, v in weights_bits.items()}
         if packed:   # the four matrices in the library's tiled streaming layout
             self.weights = rs.pack_layer_weights(self.weights)
-        self.k_pages = dev_bf16(k_pages_bits)
-        self.v_pages = dev_bf16(v_pages_bits)
+        if kv_scales is None:
+            self.k_pages = dev_bf16(k_pages_bits)
+            self.v_pages = dev_bf16(v_pages_bits)
+        else:
+            self.k_codes = torch.from_numpy(np.ascontiguousarray(k_pages_bits)).cuda()
+            self.v_codes = torch.from_numpy(np.ascontiguousarray(v_pages_bits)).cuda()
+            self.k_pages = rs.QuantPool(self.k_codes, kv_scales[0])
+            self.v_pages = rs.QuantPool(self.v_codes, kv_scales[1])
         self.workspace = torch.empty(rs.relserve_workspace_bytes(self.layer, max_tokens), dtype=torch.uint8, device="cuda")
 
     def step(self, batch, x_bits):
@@ -75,3 +83,31 @@ def assert_bf16_neighbours(got_bits: np.ndarray, want_bits: np.ndarray, what: st
     exact = float(np.mean(got_bits == want_bits))
     assert exact >= min_exact, f"{what}: only {exact:.4f} of the entries are bit-equal"
     return exact
+
+
+E4M3_VALUES = None
+
+
+def e4m3_values():
+    """The 256 values of the 8-bit format, from torch's type (NaN codes as NaN)."""
+    global E4M3_VALUES
+    if E4M3_VALUES is None:
+        E4M3_VALUES = torch.arange(256, dtype=torch.uint8).view(torch.float8_e4m3fn).float().numpy()
+    return E4M3_VALUES
+
+
+def assert_codes_neighbours(got: np.ndarray, want: np.ndarray, what: str, min_exact: float):
+    """Two tensors of 8-bit codes quantised from nearly equal fp32 values: most are equal, the rest are adjacent
+    representable values (a value next to a rounding boundary went the other way)."""
+    vals = e4m3_values()
+    g, w = vals[got].astype(np.float64), vals[want].astype(np.float64)
+    assert np.isfinite(g).all(), what
+    step = 2.0 ** (np.floor(np.log2(np.maximum(np.maximum(np.abs(g), np.abs(w)), 2.0 ** -6))) - 3)    # spacing at the larger magnitude
+    # values near zero sit on a much finer grid than the deviation of the two sides before quantisation
+    # (1.6e-3 of the tensor's RMS, as for the 16-bit cache): six standard deviations of it on top of the one step
+    bad = np.abs(g - w) > 1.001 * step + 1e-2 * np.sqrt(np.mean(w * w))
+    assert not bad.any(), f"{what}: {int(bad.sum())} codes more than one step apart"
+    exact = float(np.mean(got == want))
+    assert exact >= min_exact, f"{what}: only {exact:.4f} of the codes are equal"
+    return exact
+

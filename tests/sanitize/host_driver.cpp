@@ -21,8 +21,8 @@ int64_t gemm_scratch_floats(int64_t T, int64_t n_max) { return T <= SKINNY_MAX_T
 void gemm_force_plan(int, int) {}
 hipError_t launch_linear(const void*, const void*, int32_t, int32_t, int32_t, int32_t, const void*, void*, hipStream_t, float*, bool) { return hipSuccess; }
 hipError_t launch_pack_weight(const void*, int32_t, int32_t, void*, hipStream_t) { return hipSuccess; }
-hipError_t launch_qkv_rope_append(const BatchDev&, const relserve_layer&, const void*, const void*, void*, void*, void*, hipStream_t, float*, bool) { return hipSuccess; }
-hipError_t launch_attention(const BatchDev&, const relserve_layer&, const void*, int32_t, const void*, const void*, void*, float*, float*, hipStream_t, relserve_layer*) { return hipSuccess; }
+hipError_t launch_qkv_rope_append(const BatchDev&, const relserve_layer&, const void*, const void*, void*, void*, void*, hipStream_t, float*, bool, KvFormat) { return hipSuccess; }
+hipError_t launch_attention(const BatchDev&, const relserve_layer&, const void*, int32_t, const void*, const void*, void*, float*, float*, hipStream_t, relserve_layer*, KvFormat) { return hipSuccess; }
 hipError_t launch_peak_mfma(float*, int32_t, hipStream_t) { return hipSuccess; }
 hipError_t launch_peak_stream(const void*, int64_t, uint32_t*, hipStream_t) { return hipSuccess; }
 }  // namespace relserve

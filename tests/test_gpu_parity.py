@@ -9,7 +9,7 @@ import torch
 
 from paper_2601_11546_amd import workloads as W
 from tests.flows import gather_kv, make_flow, run_flow
-from tests.gpu_harness import GpuLayer, assert_bf16_neighbours, assert_close, dev_bf16, host_bits, host_f32
+from tests.gpu_harness import GpuLayer, assert_bf16_neighbours, assert_close, assert_codes_neighbours, dev_bf16, e4m3_values, host_bits, host_f32
 
 pytestmark = pytest.mark.gpu
 
@@ -820,6 +820,193 @@ def test_greedy_sample_is_bit_exact(rs, oracle, rows, vocab):
     rs.relserve_greedy_sample(torch.from_numpy(logits).cuda(), out)
     torch.cuda.synchronize()
     np.testing.assert_array_equal(out.cpu().numpy(), want)
+
+
+# ---------------------------------------------------------------------------
+# quantised cache: pools of 8-bit codes (one byte per cached element) with one scale per pool
+# ---------------------------------------------------------------------------
+KV_SCALES = (2.0 ** -4, 2.0 ** -5)
+
+
+@pytest.mark.parametrize("shape,n_req", [(W.TINY, 7), (W.TINY_GQA, 7), (W.TINY_D128, 7), (W.LayerShape(512, 4, 2, 128, 256), 40),
+                                         (W.LayerShape(512, 4, 2, 128, 256), 300)], ids=["mha", "gqa", "d128", "d128_wide", "d128_tiles"])
+def test_quantised_cache_append_in_the_projection_epilogue(rs, oracle, shape, n_req):
+    """q/k/v projection + rotation + append into 8-bit pools: same bf16 inputs on both sides, quantised once from fp32, so
+    nearly every stored code equals the oracle's (the format's rounding included: this also pins the conversion
+    instruction to the 1-4-3 format with bias 7); bytes outside the written slots stay as they were."""
+    if n_req == 7:
+        b = W.workload_tiny_prefix(shape=shape).batch
+    else:
+        rng0 = np.random.default_rng(3)
+        ql = rng0.integers(1, 40, n_req)
+        b = W.build_batch(shape, ql, ql + rng0.integers(0, 300, n_req), seed=4)
+    rng = np.random.default_rng(12)
+    h_bits = W.f32_to_bf16_bits(rng.standard_normal((b.T, shape.hidden), dtype=np.float32))
+    w_bits = W.f32_to_bf16_bits(rng.standard_normal((shape.qkv_dim, shape.hidden), dtype=np.float32) * 0.05)
+    k8, v8 = W.make_cache_fp8(shape, b.num_pages, 13)
+    kd, vd = torch.from_numpy(k8).cuda(), torch.from_numpy(v8).cuda()
+    ks, vs = 2.0 ** -3, 0.3                                     # one scale a power of two, one not
+    layer = rs.relserve_layer_create(shape)
+    pb = rs.relserve_batch_prepare(layer, b)
+    q_out = torch.zeros(b.T, shape.q_dim, dtype=torch.bfloat16, device="cuda")
+    rs.relserve_qkv_rope_append(layer, pb, dev_bf16(h_bits), dev_bf16(w_bits), q_out, rs.QuantPool(kd, ks), rs.QuantPool(vd, vs))
+    torch.cuda.synchronize()
+    qkv = oracle.linear(w_bits, W.bf16_bits_to_f32(h_bits))
+    d, nq, nkv = shape.head_dim, shape.n_q_heads, shape.n_kv_heads
+    pos = np.concatenate([np.arange(p, p + q) for p, q in zip(b.past, b.q_len)])
+    for t in range(b.T):
+        for hd in range(nq + nkv):
+            qkv[t, hd * d:(hd + 1) * d] = oracle.rope(qkv[t, hd * d:(hd + 1) * d], int(pos[t]), shape.rope_base)
+    k_inv, v_inv = np.float32(1.0 / np.float64(np.float32(ks))), np.float32(1.0 / np.float64(np.float32(vs)))
+    quant = np.vectorize(oracle.f32_to_e4m3, otypes=[np.uint8])
+    want_k = quant(qkv[:, nq * d:(nq + nkv) * d] * k_inv)
+    want_v = quant(qkv[:, (nq + nkv) * d:] * v_inv)
+    slots = rs.relserve_batch_slots(shape, b)
+    gk, gv = kd.cpu().numpy().reshape(-1, nkv * d), vd.cpu().numpy().reshape(-1, nkv * d)
+    ek = assert_codes_neighbours(gk[slots], want_k, "k codes", min_exact=0.99)
+    ev = assert_codes_neighbours(gv[slots], want_v, "v codes", min_exact=0.99)
+    print(f"[parity] quantised append: equal codes k {ek:.4f} v {ev:.4f}", flush=True)
+    assert_bf16_neighbours(host_bits(q_out), W.f32_to_bf16_bits(qkv[:, :nq * d]), "q", min_exact=0.98)
+    mask = np.ones(gk.shape[0], bool)
+    mask[slots] = False
+    np.testing.assert_array_equal(gk[mask], k8.reshape(-1, nkv * d)[mask])
+    np.testing.assert_array_equal(gv[mask], v8.reshape(-1, nkv * d)[mask])
+
+
+def test_quantised_cache_saturates_at_the_largest_magnitude(rs, oracle):
+    """A scale far too small for the data: every code is the largest magnitude with the value's sign, as the oracle's."""
+    shape = W.TINY_D128
+    b = W.workload_tiny(shape=shape).batch
+    rng = np.random.default_rng(5)
+    h_bits = W.f32_to_bf16_bits(rng.standard_normal((b.T, shape.hidden), dtype=np.float32))
+    w_bits = W.f32_to_bf16_bits(rng.standard_normal((shape.qkv_dim, shape.hidden), dtype=np.float32) * 0.05)
+    k8, v8 = W.make_cache_fp8(shape, b.num_pages, 6)
+    kd, vd = torch.from_numpy(k8).cuda(), torch.from_numpy(v8).cuda()
+    layer = rs.relserve_layer_create(shape)
+    pb = rs.relserve_batch_prepare(layer, b)
+    q_out = torch.zeros(b.T, shape.q_dim, dtype=torch.bfloat16, device="cuda")
+    rs.relserve_qkv_rope_append(layer, pb, dev_bf16(h_bits), dev_bf16(w_bits), q_out, rs.QuantPool(kd, 1e-6), rs.QuantPool(vd, 1e-6))
+    torch.cuda.synchronize()
+    slots = rs.relserve_batch_slots(shape, b)
+    gv = vd.cpu().numpy().reshape(-1, shape.kv_dim)[slots]
+    v = oracle.linear(w_bits, W.bf16_bits_to_f32(h_bits))[:, shape.q_dim + shape.kv_dim:]
+    big = np.abs(v) > 1e-3
+    assert ((gv & 0x7f)[big] == 0x7e).all() and (((gv >> 7) == 1) == (v < 0))[big].all()
+
+
+@pytest.mark.parametrize("make", [W.workload_tiny, W.workload_tiny_prefix, W.workload_tiny_long_prefixes])
+@pytest.mark.parametrize("shape", [W.TINY, W.TINY_GQA, W.TINY_D128, W.TINY_G5, W.TINY_G3_D128], ids=["mha", "gqa", "d128", "g5", "g3d128"])
+def test_attention_stage_quantised_cache(rs, oracle, make, shape):
+    """Attention reading 8-bit pools: both sides read the same codes, so the 16-bit bar applies unchanged."""
+    b = make(shape=shape).batch
+    rng = np.random.default_rng(10)
+    q_bits = W.f32_to_bf16_bits(rng.standard_normal((b.T, shape.q_dim), dtype=np.float32))
+    k8, v8 = W.make_cache_fp8(shape, b.num_pages, 11)
+    ks, vs = 2.0 ** -3, 0.07
+    layer = rs.relserve_layer_create(shape)
+    pb = rs.relserve_batch_prepare(layer, b)
+    ws = torch.empty(rs.relserve_workspace_bytes(layer, b.T), dtype=torch.uint8, device="cuda")
+    out = torch.zeros(b.T, shape.q_dim, dtype=torch.bfloat16, device="cuda")
+    rs.relserve_attention(layer, pb, dev_bf16(q_bits), shape.q_dim, rs.QuantPool(torch.from_numpy(k8).cuda(), ks),
+                          rs.QuantPool(torch.from_numpy(v8).cuda(), vs), out, ws)
+    torch.cuda.synchronize()
+    got = host_f32(out)
+    qf = W.bf16_bits_to_f32(q_bits)
+    t = 0
+    for r in range(b.num_reqs):
+        for j in range(b.q_len[r]):
+            want = oracle.attention_token_fp8kv(shape, b, r, int(b.past[r]) + j, qf[t].reshape(shape.n_q_heads, -1), k8, v8, ks, vs)
+            assert_close(got[t], want.reshape(-1), f"attention req {r} tok {j}", max_abs=2e-2, rel_l2=1e-2)
+            t += 1
+
+
+def _quantised_step(rs, oracle, wl, reqs=None, max_prefill_rows=None, packed=False):
+    """Whole step over 8-bit pools against the oracle's quantised step (sampled requests when reqs is given)."""
+    shape, b = wl.shape, wl.batch
+    print(f"[case] quantised cache, {wl.name}: T={b.T} reqs={b.num_reqs}", flush=True)
+    weights = wl.weights()
+    x = W.make_activations(b.T, shape.hidden, wl.seed)
+    k8, v8 = W.make_cache_fp8(shape, b.num_pages, wl.seed)
+    gl = GpuLayer(rs, shape, weights, k8, v8, b.T, packed=packed, kv_scales=KV_SCALES)
+    y = host_f32(gl.step(b, x))
+    sub, rows, sel = b, np.arange(b.T), None
+    if reqs is not None:
+        sub, rows = b.select(reqs), b.token_rows(reqs)
+        if max_prefill_rows is not None and len(rows) > max_prefill_rows:
+            rng = np.random.default_rng(1)
+            keep = set(int(sub.q_start[i + 1]) - 1 for i in range(sub.num_reqs)) | set(rng.choice(len(rows), max_prefill_rows, replace=False).tolist())
+            sel = np.array(sorted(keep), np.int32)
+    res = oracle.layer_step(shape, sub, weights, x[rows], k8, v8, rows=sel, kv_scales=KV_SCALES)
+    got = y[rows] if sel is None else y[rows][sel]
+    xin = W.bf16_bits_to_f32(x[rows] if sel is None else x[rows][sel])
+    # the 16-bit bar; where |y| >= 4 the bf16 rounding of the output alone is up to 1.6e-2, so there the absolute bound is
+    # that half unit plus 1e-2
+    err, rel = assert_close(got, res.y_f32, wl.name + " quantised cache", max_abs=1.0)
+    half_ulp = 2.0 ** (np.floor(np.log2(np.maximum(np.abs(res.y_f32.astype(np.float64)), 2.0 ** -20))) - 8)
+    assert (np.abs(got - res.y_f32) <= np.maximum(2e-2, half_ulp + 1e-2)).all(), (wl.name, err)
+    # the layer's own contribution, at the 16-bit bar: both sides quantise from bf16 inputs and fp32 sums, so all but a
+    # few codes in ten thousand agree (checked below)
+    # (full-size shapes only: on the tiny ones the contribution is as small as the bf16 rounding of y itself)
+    drel = float(np.linalg.norm(got - res.y_f32) / np.linalg.norm(res.y_f32 - xin))
+    if reqs is not None:
+        assert_close(got - xin, res.y_f32 - xin, wl.name + " quantised cache (y - x)", max_abs=1.0, rel_l2=1e-2)   # absolute: above
+    slots = rs.relserve_batch_slots(shape, sub)
+    nkv, d = shape.n_kv_heads, shape.head_dim
+    ek = assert_codes_neighbours(gl.k_codes.cpu().numpy().reshape(-1, nkv, d)[slots], k8.reshape(-1, nkv, d)[slots], "appended k codes", 0.98)
+    ev = assert_codes_neighbours(gl.v_codes.cpu().numpy().reshape(-1, nkv, d)[slots], v8.reshape(-1, nkv, d)[slots], "appended v codes", 0.98)
+    print(f"[parity] {wl.name} quantised cache: max-abs {err:.3e} rel-L2 {rel:.3e}; y-x rel-L2 {drel:.3e}; equal codes k {ek:.4f} v {ev:.4f}",
+          flush=True)
+    return gl, k8, v8
+
+
+@pytest.mark.parametrize("make", [W.workload_tiny, W.workload_tiny_prefix, W.workload_tiny_long_prefixes])
+@pytest.mark.parametrize("shape", [W.TINY, W.TINY_GQA, W.TINY_D128, W.TINY_G5], ids=["mha", "gqa", "d128", "g5"])
+def test_layer_step_tiny_quantised_cache(rs, oracle, make, shape):
+    wl = make(shape=shape)
+    gl, k8, v8 = _quantised_step(rs, oracle, wl)
+    # untouched bytes stay untouched
+    slots = rs.relserve_batch_slots(shape, wl.batch)
+    k0, _ = W.make_cache_fp8(shape, wl.batch.num_pages, wl.seed)
+    mask = np.ones(k0.shape[0] * shape.page_size, bool)
+    mask[slots] = False
+    np.testing.assert_array_equal(gl.k_codes.cpu().numpy().reshape(-1, shape.kv_dim)[mask], k0.reshape(-1, shape.kv_dim)[mask])
+
+
+def test_quantised_cache_long_and_ragged_decode_rows(rs, oracle):
+    shape = W.TINY_GQA
+    P = shape.page_size
+    pl = 4 * P
+    b = W.build_batch(shape, [1, 1, 1, 1, 1, 1, 7], [4096, 129, pl + 1500, pl + 333, 17, 193, 50], [-1, -1, 0, 0, -1, -1, -1], [pl],
+                      seed=79, name="long_ragged_decode")
+    _quantised_step(rs, oracle, W.Workload(b.name, shape, b, 1079))
+
+
+def test_full_size_quantised_cache_decode128_13b(rs, oracle):
+    _quantised_step(rs, oracle, W.workload_decode_plus_chunk_13b(0), [0, 64, 127], packed=True)
+
+
+def test_full_size_quantised_cache_relquery_13b(rs, oracle):
+    _quantised_step(rs, oracle, W.workload_relquery_13b(), [0, 15, 16, 99, 199], packed=True)
+
+
+def test_full_size_quantised_cache_decode_heavy_70b(rs, oracle):
+    _quantised_step(rs, oracle, W.workload_decode_heavy_70b(), [0, 64, 130, 255, 256], max_prefill_rows=16, packed=True)
+
+
+def test_quantised_cache_is_refused_where_it_is_not_served(rs):
+    shape = W.TINY
+    b = W.workload_tiny().batch
+    layer = rs.relserve_layer_create(shape)
+    pb = rs.relserve_batch_prepare(layer, b)
+    k8, v8 = W.make_cache_fp8(shape, b.num_pages, 1)
+    kd, vd = torch.from_numpy(k8).cuda(), torch.from_numpy(v8).cuda()
+    k = torch.zeros(b.T, shape.n_kv_heads, shape.head_dim, dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(rs.RelserveError):
+        rs.relserve_kv_append(layer, pb, k, k, rs.QuantPool(kd, 0.1), rs.QuantPool(vd, 0.1))
+    with pytest.raises(rs.RelserveError):           # a scale that is not positive
+        rs.relserve_qkv_rope_append(layer, pb, k, k, k, rs.QuantPool(kd, 0.0), rs.QuantPool(vd, 0.1))
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(kd.cpu().numpy(), k8)
 
 
 def test_two_host_threads_step_concurrently(rs):

@@ -42,6 +42,7 @@ MUTANTS = [
     ("quantised_scale_dropped_on_read", "return oracle_e4m3_to_f32(((const uint8_t*)pages)[idx]) * scale;", "return oracle_e4m3_to_f32(((const uint8_t*)pages)[idx]);"),
     ("quantised_v_with_k_scale", "v_pages[(size_t)slot * row + i] = oracle_f32_to_e4m3(src[row + i] * v_inv);", "v_pages[(size_t)slot * row + i] = oracle_f32_to_e4m3(src[row + i] * k_inv);"),
     ("quantised_k_before_rotation_slot", "k_pages[(size_t)slot * row + i] = oracle_f32_to_e4m3(src[i] * k_inv);", "k_pages[(size_t)slot * row + i] = oracle_f32_to_e4m3(src[i] * k_scale);"),
+    ("quantised_inputs_not_rounded", "for (size_t i = 0; i < (size_t)T * H; ++i) h[i] = oracle_bf16_to_f32(oracle_f32_to_bf16(h[i]));", ";"),
     ("softmax_unnormalised", "out[(size_t)a * d + i] = (float)(o[i] / denom);", "out[(size_t)a * d + i] = (float)(o[i]);"),
 ]
 

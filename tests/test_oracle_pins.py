@@ -563,6 +563,7 @@ def test_quantised_cache_layer_step(oracle):
     res = oracle.layer_step(shape, b, weights, x, k8, v8, kv_scales=(ks, vs))
     # what must have been written: pieces that are pinned on their own
     h = oracle.rmsnorm(W.bf16_bits_to_f32(x), weights["w_in_norm"], shape.rms_eps)
+    h = W.bf16_bits_to_f32(W.f32_to_bf16_bits(h))                            # R15: bf16 inputs to the projection in this variant
     qkv = oracle.linear(weights["w_qkv"], h)
     d, nq, nkv, P = shape.head_dim, shape.n_q_heads, shape.n_kv_heads, shape.page_size
     pos = np.concatenate([np.arange(p, p + q) for p, q in zip(b.past, b.q_len)])

@@ -54,8 +54,9 @@ def build_workload(name: str):
     return wl
 
 
-def algorithmic_counts(shape, batch) -> dict:
-    """FLOPs and HBM bytes one step must do/move, counted from the definition."""
+def algorithmic_counts(shape, batch, kv_elem_bytes: int = 2) -> dict:
+    """FLOPs and HBM bytes one step must do/move, counted from the definition (kv_elem_bytes: 2 for the 16-bit
+    cache, 1 for the quantised one)."""
     T, H, I = batch.T, shape.hidden, shape.mlp_dim
     d, nq, nkv = shape.head_dim, shape.n_q_heads, shape.n_kv_heads
     gemm = {"gemm_qkv_rope_append": 2 * T * shape.qkv_dim * H, "gemm_o": 2 * T * H * shape.q_dim,
@@ -64,7 +65,7 @@ def algorithmic_counts(shape, batch) -> dict:
     visible = int(sum(int(q) * int(p) + int(q) * (int(q) + 1) // 2 for q, p in zip(q_len, past)))
     attn_flops = 4 * d * nq * visible
     # unique KV bytes: a shared prefix once per group, every other cached key/value once
-    kv_tok = 2 * nkv * d * 2
+    kv_tok = 2 * nkv * d * kv_elem_bytes
     pl = batch.prefix_len
     grouped = [p for p in range(len(pl)) if int((batch.prefix_id == p).sum()) >= 2]
     uniq_tokens = int(sum(int(pl[p]) for p in grouped))
@@ -267,12 +268,13 @@ def _stats(ms: list) -> dict:
             "repeats": len(a)}
 
 
-def measure_layer_step(rs, W, torch, args, wl, host_draws: bool) -> dict:
+def measure_layer_step(rs, W, torch, args, wl, host_draws: bool, kv_fp8: bool = False) -> dict:
     """Times the layer step of one workload.  host_draws: weights, cache and activations are the seeded host draws the
     parity tests use (needed for the oracle leg); otherwise they are drawn on the device from the same distributions."""
     shape, b = wl.shape, wl.batch
-    counts = algorithmic_counts(shape, b)
+    counts = algorithmic_counts(shape, b, 1 if kv_fp8 else 2)
     H, I, qd = shape.hidden, shape.mlp_dim, shape.n_q_heads * shape.head_dim
+    assert not (kv_fp8 and host_draws), "the quantised-cache variant is timed on device draws"
 
     def dev(bits):
         return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).cuda().view(torch.bfloat16)
@@ -301,6 +303,11 @@ def measure_layer_step(rs, W, torch, args, wl, host_draws: bool) -> dict:
                  "w_o": randn(H, qd, std=res_std), "w_post_norm": randn(H, std=0.02, mean=1.0),
                  "w_gate_up": randn(2 * I, H, std=0.02), "w_down": randn(H, I, std=res_std)}, randn(*pool), randn(*pool))
         x = randn(b.T, H)
+        if kv_fp8:   # pools of 8-bit codes: exponent fields 0..11 (magnitudes under 32 code units), random signs
+            def codes():
+                c = torch.randint(0, 96, pool, generator=g, device="cuda", dtype=torch.uint8)
+                return c | (torch.randint(0, 2, pool, generator=g, device="cuda", dtype=torch.uint8) << 7)
+            base = (base[0], codes(), codes())
     # set 0 holds the draws; the other sets are row-rotated device copies of it (same values and
     # distribution at other addresses), which keeps set-up time short
     sets = []
@@ -320,6 +327,9 @@ def measure_layer_step(rs, W, torch, args, wl, host_draws: bool) -> dict:
     prepare_ms = (time.perf_counter() - t0) * 1e3
     y = torch.empty_like(x)
     ws = torch.empty(rs.relserve_workspace_bytes(layer, b.T), dtype=torch.uint8, device="cuda")
+
+    if kv_fp8:
+        sets = [(w, rs.QuantPool(k, 2.0 ** -4), rs.QuantPool(v, 2.0 ** -5)) for w, k, v in sets]
 
     def step(i):
         wts, kd, vd = sets[i % n_sets]
@@ -416,11 +426,11 @@ def measure_layer_step(rs, W, torch, args, wl, host_draws: bool) -> dict:
         "metric": "mixed_batch_layer_step_tokens_per_s", "value": round(b.T / (ms_step * 1e-3), 1), "unit": "tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_step, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": wl.name, "layer": f"H{shape.hidden} q{shape.n_q_heads}/kv{shape.n_kv_heads}x{shape.head_dim} "
+        "config": {"workload": wl.name + ("_fp8kv" if kv_fp8 else ""), "layer": f"H{shape.hidden} q{shape.n_q_heads}/kv{shape.n_kv_heads}x{shape.head_dim} "
                    f"I{shape.mlp_dim} P{shape.page_size}", "query_tokens": b.T, "requests": b.num_reqs,
                    "prefill_rows": int((b.q_len > 1).sum()), "decode_rows": int((b.q_len == 1).sum()),
                    "layer_sets_rotated": n_sets, "weight_layout": "packed" if packed else "row-major",
-                   "batch_info": pb.info},
+                   "kv_cache": "8-bit codes, one scale per pool" if kv_fp8 else "bf16", "batch_info": pb.info},
         "ms_per_step_stats": stats,
         "roofline": roofline,
         "step": {"tflops": round(step_tflops, 1), "frac_mfma_peak": round(step_tflops / PEAK_BF16_TFLOPS, 4),
@@ -458,6 +468,7 @@ def main() -> None:
                          "relserve_model_step on a 4-layer model of the 13B layer shape; the clock is the measured GPU time")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-peak-probes", action="store_true", help="skip the MFMA issue loop and the streaming read")
+    ap.add_argument("--kv-fp8", action="store_true", help="time the quantised-cache variant (8-bit K/V pools) of the workload")
     ap.add_argument("--repeats", type=int, default=9, help="how many times the K timed steps are repeated (median, p10, p90)")
     ap.add_argument("--no-regimes", action="store_true",
                     help="headline workload only (by default the line also carries the prefill-only and the decode-only regimes)")
@@ -497,21 +508,22 @@ def main() -> None:
         print(json.dumps(duration_model.run(steps=max(1, min(args.steps, 10)), warmup=max(1, min(args.warmup, 3)))))
         return
     wl = build_workload(args.workload)
-    res = measure_layer_step(rs, W, torch, args, wl, host_draws=True)
+    res = measure_layer_step(rs, W, torch, args, wl, host_draws=not args.kv_fp8, kv_fp8=args.kv_fp8)
     out = res["line"]
-    if not args.no_regimes and args.workload == "relquery_13b":
-        # the two regimes the roofline targets are stated on, each with its own roofline object
+    if not args.no_regimes and args.workload == "relquery_13b" and not args.kv_fp8:
+        # the two regimes the roofline targets are stated on, each with its own roofline object, and the decode-dominated
+        # one on the quantised-cache variant
         out["regimes"] = {}
-        for name in ("prefill_only_13b", "decode128_13b", "decode_only_70b"):
-            r = measure_layer_step(rs, W, torch, args, build_workload(name), host_draws=False)["line"]
-            out["regimes"][name] = {"ms_per_step": r["ms_per_step"], "ms_per_step_stats": r["ms_per_step_stats"],
+        for name, fp8 in (("prefill_only_13b", False), ("decode128_13b", False), ("decode_only_70b", False), ("decode128_13b", True)):
+            r = measure_layer_step(rs, W, torch, args, build_workload(name), host_draws=False, kv_fp8=fp8)["line"]
+            out["regimes"][name + ("_fp8kv" if fp8 else "")] = {"ms_per_step": r["ms_per_step"], "ms_per_step_stats": r["ms_per_step_stats"],
                                     "tokens_per_s": r["value"], "query_tokens": r["config"]["query_tokens"],
                                     "requests": r["config"]["requests"], "layer": r["config"]["layer"],
                                     "data": "synthetic (drawn on the device)", "roofline": r["roofline"], "step": r["step"],
                                     "kernels": r["kernels"]}
     if not args.no_peak_probes:
         out["measured_peaks"] = peak_probes(rs, torch)
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and not args.kv_fp8:
         budget = args.cpu_tokens or max(8, int(1.6e11 / (2 * wl.shape.params)))   # about 160 GFLOP of dense work, ~10 s
         out["cpu_baseline"] = cpu_baseline(wl, res["weights0"], res["x_bits"], budget)
         out["cpu_baseline"]["tiny_single_thread"] = cpu_baseline_tiny_single_thread()

@@ -175,6 +175,28 @@ def peak_probes(rs, torch) -> dict:
             "note": "random bf16 operands, 16 independent accumulators per wave; 4 GiB read with 16-byte non-temporal loads"}
 
 
+def stream_patterns(rs, torch) -> dict:
+    """A 4 GiB read of HBM in five access patterns (relserve_peak_probe_stream_pattern): what the choice of the
+    non-temporal hint for bytes that are read once rests on."""
+    names = ["grid-stride, plain 16-byte loads", "32 KB pieces per workgroup, plain loads", "32 KB pieces, non-temporal loads",
+             "32 KB pieces direct to LDS, plain", "32 KB pieces direct to LDS, non-temporal"]
+    sink = torch.zeros(64, dtype=torch.float32, device="cuda")
+    buf = torch.empty(1 << 32, dtype=torch.uint8, device="cuda")
+    buf.view(torch.int32).random_()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    out = {}
+    for pat, name in enumerate(names):
+        best = 0.0
+        for _ in range(5):
+            e0.record()
+            rs.relserve_peak_probe_stream_pattern(buf, buf.numel(), pat, sink)
+            e1.record()
+            torch.cuda.synchronize()
+            best = max(best, buf.numel() / (e0.elapsed_time(e1) * 1e-3) / 1e9)
+        out[name] = round(best, 1)
+    return {"metric": "stream_read_gbs", "bytes": buf.numel(), "best_of": 5, "patterns": out}
+
+
 def model_step_bench(args, rs, W, torch) -> dict:
     """The model step (Sec. 2.3 "LLM Inference": embedding, layer stack, output layer on the last hidden states)
     at full depth.  Weights and caches are drawn on the device (a 40-layer 13B stack with 128 contexts of 1024
@@ -468,6 +490,8 @@ def main() -> None:
                          "relserve_model_step on a 4-layer model of the 13B layer shape; the clock is the measured GPU time")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-peak-probes", action="store_true", help="skip the MFMA issue loop and the streaming read")
+    ap.add_argument("--stream-patterns", action="store_true",
+                    help="instead of the benchmark line: a 4 GiB read of HBM in five access patterns (GB/s each)")
     ap.add_argument("--kv-fp8", action="store_true", help="time the quantised-cache variant (8-bit K/V pools) of the workload")
     ap.add_argument("--repeats", type=int, default=9, help="how many times the K timed steps are repeated (median, p10, p90)")
     ap.add_argument("--no-regimes", action="store_true",
@@ -486,6 +510,9 @@ def main() -> None:
 
     assert torch.cuda.is_available(), "bench.py needs an MI355X"
     torch.cuda.set_device(0)
+    if args.stream_patterns:
+        print(json.dumps(stream_patterns(rs, torch)))
+        return
     if args.model_layers > 0:
         print(json.dumps(model_step_bench(args, rs, W, torch)))
         return

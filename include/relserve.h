@@ -396,6 +396,11 @@ int32_t relserve_prefill_candidate(const int32_t* utok, int32_t n, int64_t token
  * times the launches on `stream`. */
 int32_t relserve_peak_probe_mfma(void* sink, int32_t iters, double* flops, void* stream);
 int32_t relserve_peak_probe_stream(const void* src, size_t bytes, void* sink, void* stream);
+/* The read patterns relserve_peak_probe_stream's was chosen from, for the record of that choice: pattern 0 = grid-stride
+ * walk with plain 16-byte loads; 1 = 32 KB pieces per workgroup, plain loads; 2 = the same with the non-temporal hint
+ * (= relserve_peak_probe_stream); 3 / 4 = the pieces loaded directly into LDS without / with the hint (the form the GEMM and
+ * attention kernels use).  bytes >= 32768. */
+int32_t relserve_peak_probe_stream_pattern(const void* src, size_t bytes, int32_t pattern, void* sink, void* stream);
 
 /* ---- test hook (the only one; not part of the serving interface) ----
  * Forces the tile shape and the tail split of every later GEMM launch of this process, so that tests can

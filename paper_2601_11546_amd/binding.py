@@ -33,7 +33,7 @@ EXPORTS = ["relserve_version", "relserve_strerror", "relserve_config_validate", 
            "relserve_layer_step", "relserve_layer_step_static", "relserve_static_scratch_bytes", "relserve_model_workspace_bytes", "relserve_model_step", "relserve_greedy_sample", "relserve_rmsnorm", "relserve_linear", "relserve_rope_append",
            "relserve_qkv_rope_append",
            "relserve_attention", "relserve_profile_slot_name", "relserve_profile_enable", "relserve_profile_read",
-           "relserve_debug_force_gemm_plan", "relserve_peak_probe_mfma", "relserve_peak_probe_stream",
+           "relserve_debug_force_gemm_plan", "relserve_peak_probe_mfma", "relserve_peak_probe_stream", "relserve_peak_probe_stream_pattern",
            "relserve_packed_weight_elems", "relserve_pack_weight", "relserve_linear_packed",
            "relserve_duration_fit", "relserve_duration_predict", "relserve_batch_decompose", "relserve_pem_estimate",
            "relserve_aba_decide", "relserve_starved_priority", "relserve_static_priority", "relserve_utok_estimate",
@@ -148,6 +148,7 @@ for _n, _a in {
     "relserve_debug_force_gemm_plan": [C.c_int32, C.c_int32],
     "relserve_peak_probe_mfma": [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p],
     "relserve_peak_probe_stream": [C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p],
+    "relserve_peak_probe_stream_pattern": [C.c_void_p, C.c_size_t, C.c_int32, C.c_void_p, C.c_void_p],
     "relserve_profile_read": [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32],
     "relserve_duration_fit": [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p],
     "relserve_duration_predict": [C.c_void_p, C.c_double, C.c_void_p],
@@ -418,6 +419,11 @@ def relserve_peak_probe_mfma(sink, iters: int, stream=None) -> float:
 
 def relserve_peak_probe_stream(src, nbytes: int, sink, stream=None) -> None:
     _check(_lib.relserve_peak_probe_stream(_ptr(src), int(nbytes), _ptr(sink), _stream(stream)), "relserve_peak_probe_stream")
+
+
+def relserve_peak_probe_stream_pattern(src, nbytes: int, pattern: int, sink, stream=None) -> None:
+    _check(_lib.relserve_peak_probe_stream_pattern(_ptr(src), int(nbytes), int(pattern), _ptr(sink), _stream(stream)),
+           "relserve_peak_probe_stream_pattern")
 
 
 def relserve_debug_force_gemm_plan(tile: int = -1, tail_splits: int = 0) -> None:

@@ -60,7 +60,72 @@ __global__ void __launch_bounds__(256) stream_read_kernel(const u32x4_t* src, in
     if (acc == 0x9e3779b9u) sink[0] = acc;   // keeps the loads alive
 }
 
+// The other read patterns the choice above was made from (relserve_peak_probe_stream_pattern).
+// 0: grid-stride walk, eight plain 16-byte loads in flight per thread.
+__global__ void __launch_bounds__(256) stream_stride_kernel(const u32x4_t* src, int64_t n16, uint32_t* sink) {
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    uint32_t acc = 0;
+    for (; i + 7 * stride < n16; i += 8 * stride) {
+        u32x4_t v[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) v[j] = src[i + j * stride];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc ^= v[j].x ^ v[j].y ^ v[j].z ^ v[j].w;
+    }
+    if (acc == 0x9e3779b9u) sink[0] = acc;
+}
+// 1: 32 KB pieces per workgroup as stream_read_kernel, plain loads.
+__global__ void __launch_bounds__(256) stream_pieces_plain_kernel(const u32x4_t* src, int64_t n16, uint32_t* sink) {
+    constexpr int U = 8;
+    const int64_t per = 256 * U, n_pieces = n16 / per;
+    uint32_t acc = 0;
+    for (int64_t c = blockIdx.x; c < n_pieces; c += gridDim.x) {
+        const u32x4_t* p = src + c * per + threadIdx.x;
+        u32x4_t v[U];
+#pragma unroll
+        for (int j = 0; j < U; ++j) v[j] = p[j * 256];
+#pragma unroll
+        for (int j = 0; j < U; ++j) acc ^= v[j].x ^ v[j].y ^ v[j].z ^ v[j].w;
+    }
+    if (acc == 0x9e3779b9u) sink[0] = acc;
+}
+// 3 / 4: the same pieces loaded directly into LDS (what the GEMM and attention kernels do), without / with the hint.
+template <bool NT>
+__global__ void __launch_bounds__(256) stream_lds_kernel(const u32x4_t* src, int64_t n16, uint32_t* sink) {
+    constexpr int U = 8;
+    __shared__ __align__(16) unsigned char smem[U * 4096];
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem + wave * U * 1024;
+    const int64_t per = 256 * U, n_pieces = n16 / per;
+    for (int64_t c = blockIdx.x; c < n_pieces; c += gridDim.x) {
+        const u32x4_t* p = src + c * per + wave * 64 * U + lane;
+#pragma unroll
+        for (int j = 0; j < U; ++j) {
+            if (NT)
+                asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off nt" ::"v"(p + j * 64), "s"(lds0 + j * 1024) : "memory");
+            else
+                asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(p + j * 64), "s"(lds0 + j * 1024) : "memory");
+        }
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    }
+    if (smem[threadIdx.x] == 0x77 && n16 < 0) sink[0] = 1;
+}
+
 }  // namespace
+
+hipError_t launch_peak_stream_pattern(const void* src, int64_t bytes, int32_t pattern, uint32_t* sink, hipStream_t s) {
+    const u32x4_t* p = static_cast<const u32x4_t*>(src);
+    switch (pattern) {
+        case 0: stream_stride_kernel<<<dim3(2048), dim3(256), 0, s>>>(p, bytes / 16, sink); break;
+        case 1: stream_pieces_plain_kernel<<<dim3(512), dim3(256), 0, s>>>(p, bytes / 16, sink); break;
+        case 2: stream_read_kernel<<<dim3(512), dim3(256), 0, s>>>(p, bytes / 16, sink); break;
+        case 3: stream_lds_kernel<false><<<dim3(512), dim3(256), 0, s>>>(p, bytes / 16, sink); break;
+        case 4: stream_lds_kernel<true><<<dim3(512), dim3(256), 0, s>>>(p, bytes / 16, sink); break;
+        default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
 
 hipError_t launch_peak_mfma(float* sink, int32_t iters, hipStream_t s) {
     mfma_issue_kernel<<<dim3(256), dim3(256), 0, s>>>(sink, iters, 7u);

@@ -752,6 +752,16 @@ int32_t relserve_peak_probe_stream(const void* src, size_t bytes, void* sink, vo
                : RELSERVE_ERR_HIP;
 }
 
+int32_t relserve_peak_probe_stream_pattern(const void* src, size_t bytes, int32_t pattern, void* sink, void* stream) {
+    drop_stale_hip_error();
+    if (!src || !sink) return RELSERVE_ERR_NULL_POINTER;
+    if (bytes < 32768 || (reinterpret_cast<uintptr_t>(src) % 16) || pattern < 0 || pattern > 4) return RELSERVE_ERR_BAD_ARGUMENT;
+    return launch_peak_stream_pattern(src, (int64_t)bytes, pattern, static_cast<uint32_t*>(sink), static_cast<hipStream_t>(stream)) ==
+                   hipSuccess
+               ? RELSERVE_OK
+               : RELSERVE_ERR_HIP;
+}
+
 int32_t relserve_debug_force_gemm_plan(int32_t tile, int32_t tail_splits) {
     if (tile < -1 || tile > 4 || tail_splits < 0 || tail_splits > 8) return RELSERVE_ERR_BAD_ARGUMENT;
     gemm_force_plan(tile, tail_splits);

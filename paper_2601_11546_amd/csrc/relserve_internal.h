@@ -146,5 +146,6 @@ void profile_mark(relserve_layer* L, int slot, hipStream_t s, bool begin);
 // Peak probes (kernels_peaks.hip): 256 workgroups x 4 waves x iters x 16 MFMAs of 32768 flop; a read of `bytes`.
 hipError_t launch_peak_mfma(float* sink, int32_t iters, hipStream_t s);
 hipError_t launch_peak_stream(const void* src, int64_t bytes, uint32_t* sink, hipStream_t s);
+hipError_t launch_peak_stream_pattern(const void* src, int64_t bytes, int32_t pattern, uint32_t* sink, hipStream_t s);
 
 }  // namespace relserve

@@ -25,6 +25,7 @@ hipError_t launch_qkv_rope_append(const BatchDev&, const relserve_layer&, const 
 hipError_t launch_attention(const BatchDev&, const relserve_layer&, const void*, int32_t, const void*, const void*, void*, float*, float*, hipStream_t, relserve_layer*, KvFormat) { return hipSuccess; }
 hipError_t launch_peak_mfma(float*, int32_t, hipStream_t) { return hipSuccess; }
 hipError_t launch_peak_stream(const void*, int64_t, uint32_t*, hipStream_t) { return hipSuccess; }
+hipError_t launch_peak_stream_pattern(const void*, int64_t, int32_t, uint32_t*, hipStream_t) { return hipSuccess; }
 }  // namespace relserve
 
 static uint64_t g_rng = 0x9e3779b97f4a7c15ull;

@@ -426,8 +426,10 @@ def measure_layer_step(rs, W, torch, args, wl, host_draws: bool, kv_fp8: bool = 
     traffic, traffic_source = None, None
     tpath = os.path.join(ROOT, "profiles", "traffic.json")
     key = wl.extra.get("bench_key")
+    traffic_step = None
     if os.path.exists(tpath) and key:
-        traffic = json.load(open(tpath)).get(key, {}).get(dom)
+        recorded = json.load(open(tpath)).get(key + ("_fp8kv" if kv_fp8 else ""), {})
+        traffic, traffic_step = recorded.get(dom), recorded.get("whole_step")
         if traffic is not None:
             traffic_source = "recorded: profiles/traffic.json (rocprofv3 --pmc FETCH_SIZE + WRITE_SIZE of an earlier run of this command)"
     dk = kernels[dom]
@@ -437,13 +439,13 @@ def measure_layer_step(rs, W, torch, args, wl, host_draws: bool, kv_fp8: bool = 
                     "unit": "GB/s", "frac": round(dom_bytes / (dk["avg_ms"] * 1e-3) / 1e9 / PEAK_HBM_GBS, 4), "traffic": traffic,
                     "traffic_source": traffic_source, "kernel": dom, "bytes_per_launch": dom_bytes, "avg_launch_ms": dk["avg_ms"],
                     "whole_step": {"achieved": round(step_gbs, 1), "frac": round(step_gbs / PEAK_HBM_GBS, 4),
-                                   "bytes": counts["bytes_total"]}}
+                                   "bytes": counts["bytes_total"], "traffic": traffic_step}}
     else:
         roofline = {"bound": "mfma", "achieved": dk["tflops"], "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                     "frac": dk["frac_mfma_peak"], "traffic": traffic, "traffic_source": traffic_source, "kernel": dom,
                     "flops_per_launch": counts["gemm_flops"][dom], "avg_launch_ms": dk["avg_ms"],
                     "whole_step": {"achieved": round(step_tflops, 1), "frac": round(step_tflops / PEAK_BF16_TFLOPS, 4),
-                                   "flops": counts["flops_total"]}}
+                                   "flops": counts["flops_total"], "traffic": traffic_step}}
     line = {
         "metric": "mixed_batch_layer_step_tokens_per_s", "value": round(b.T / (ms_step * 1e-3), 1), "unit": "tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_step, 4),

@@ -9,6 +9,31 @@ MAX_ABS = 2e-2     # spec tolerance: bf16 in, fp32 accumulate
 REL_L2 = 1e-2
 
 
+# The full-size cases draw a few GB of normals per workload; consecutive tests that differ only in the launch plan
+# or the weight layout use the same workload, so the last draw is kept (one entry each: bounded memory).
+_last_cache = {}
+_last_weights = {}
+
+
+def gen_cache(shape, num_pages: int, seed: int):
+    """W.make_cache(shape, num_pages, seed), as fresh copies (the oracle and the tests write into the pools)."""
+    key = (shape, num_pages, seed)
+    if key not in _last_cache:
+        _last_cache.clear()
+        _last_cache[key] = W.make_cache(shape, num_pages, seed)
+    k, v = _last_cache[key]
+    return k.copy(), v.copy()
+
+
+def gen_weights(wl) -> dict:
+    """wl.weights() (read-only by convention: no test writes into a weight array)."""
+    key = (wl.shape, wl.seed, wl.n_layers)
+    if key not in _last_weights:
+        _last_weights.clear()
+        _last_weights[key] = wl.weights()
+    return _last_weights[key]
+
+
 def dev_bf16(bits: np.ndarray) -> torch.Tensor:
     return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).cuda().view(torch.bfloat16)
 

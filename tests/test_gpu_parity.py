@@ -9,7 +9,8 @@ import torch
 
 from paper_2601_11546_amd import workloads as W
 from tests.flows import gather_kv, make_flow, run_flow
-from tests.gpu_harness import GpuLayer, assert_bf16_neighbours, assert_close, assert_codes_neighbours, dev_bf16, e4m3_values, host_bits, host_f32
+from tests.gpu_harness import (GpuLayer, assert_bf16_neighbours, assert_close, assert_codes_neighbours, dev_bf16, e4m3_values, gen_cache,
+                               gen_weights, host_bits, host_f32)
 
 pytestmark = pytest.mark.gpu
 
@@ -325,15 +326,18 @@ def test_multi_step_flow_matches_oracle(rs, oracle, shape):
 # full-size configurations, checked on sampled requests (the oracle recomputes the
 # sampled requests as a sub-batch over the same cache: requests are independent)
 # ---------------------------------------------------------------------------
+_oracle_memo = {}
+
+
 def _sampled_parity(rs, oracle, wl, reqs, max_prefill_rows=None, packed=False, plain_init=False):
     if plain_init:      # N(0, 0.02) for every projection instead of the depth-scaled residual writers
         from dataclasses import replace
         wl = replace(wl, name=wl.name + "_plain_init", n_layers=0)
     shape, b = wl.shape, wl.batch
     print(f"[case] {wl.name}: T={b.T} reqs={b.num_reqs} sampled={list(reqs)}", flush=True)
-    weights = wl.weights()
+    weights = gen_weights(wl)
     x = W.make_activations(b.T, shape.hidden, wl.seed)
-    kp, vp = W.make_cache(shape, b.num_pages, wl.seed)
+    kp, vp = gen_cache(shape, b.num_pages, wl.seed)
     gl = GpuLayer(rs, shape, weights, kp, vp, b.T, packed=packed)
     y = host_f32(gl.step(b, x))
     sub = b.select(reqs)
@@ -346,21 +350,27 @@ def _sampled_parity(rs, oracle, wl, reqs, max_prefill_rows=None, packed=False, p
         keep |= set(int(sub.q_start[i]) for i in range(sub.num_reqs))
         keep |= set(rng.choice(len(rows), max_prefill_rows, replace=False).tolist())
         sel = np.array(sorted(keep), np.int32)
-    res = oracle.layer_step(shape, sub, weights, x[rows], kp, vp, rows=sel)
+    # the oracle's side depends on the workload and the sample alone, not on the launch plan or the weight layout
+    slots = rs.relserve_batch_slots(shape, sub)
+    nkv, d = shape.n_kv_heads, shape.head_dim
+    memo_key = (wl.name, wl.seed, wl.n_layers, tuple(reqs), max_prefill_rows)
+    if memo_key not in _oracle_memo:
+        res = oracle.layer_step(shape, sub, weights, x[rows], kp, vp, rows=sel)
+        _oracle_memo.clear()
+        _oracle_memo[memo_key] = (res.y_f32, kp.reshape(-1, nkv, d)[slots].copy(), vp.reshape(-1, nkv, d)[slots].copy())
+    want_y, want_k, want_v = _oracle_memo[memo_key]
     got = y[rows] if sel is None else y[rows][sel]
     xin = W.bf16_bits_to_f32(x[rows] if sel is None else x[rows][sel])
     if plain_init:
-        _plain_init_criterion(got, res.y_f32, xin, wl.name)
+        _plain_init_criterion(got, want_y, xin, wl.name)
         return
-    err, rel = assert_close(got, res.y_f32, wl.name)
+    err, rel = assert_close(got, want_y, wl.name)
     # the layer's own contribution (residual input removed), so that the copied stream cannot mask an error
-    derr, drel = assert_close(got - xin, res.y_f32 - xin, wl.name + " (y - x)", max_abs=2e-2, rel_l2=1e-2)
+    derr, drel = assert_close(got - xin, want_y - xin, wl.name + " (y - x)", max_abs=2e-2, rel_l2=1e-2)
     print(f"[parity] {wl.name}: max-abs {err:.3e} rel-L2 {rel:.3e}; y-x rel-L2 {drel:.3e} on {got.shape[0]} rows", flush=True)
     # appended slots of the sampled requests hold what the oracle wrote (to bf16 rounding)
-    slots = rs.relserve_batch_slots(shape, sub)
-    nkv, d = shape.n_kv_heads, shape.head_dim
-    ek = assert_bf16_neighbours(host_bits(gl.k_pages).reshape(-1, nkv, d)[slots], kp.reshape(-1, nkv, d)[slots], "appended k", min_exact=0.5)
-    ev = assert_bf16_neighbours(host_bits(gl.v_pages).reshape(-1, nkv, d)[slots], vp.reshape(-1, nkv, d)[slots], "appended v", min_exact=0.5)
+    ek = assert_bf16_neighbours(host_bits(gl.k_pages).reshape(-1, nkv, d)[slots], want_k, "appended k", min_exact=0.5)
+    ev = assert_bf16_neighbours(host_bits(gl.v_pages).reshape(-1, nkv, d)[slots], want_v, "appended v", min_exact=0.5)
     print(f"[parity] {wl.name}: appended k / v bit-equal fractions {ek:.4f} / {ev:.4f}", flush=True)
 
 
@@ -497,11 +507,11 @@ def test_layer_step_is_bitwise_repeatable(rs, make):
     wl = make()
     shape, b = wl.shape, wl.batch
     print(f"[case] repeatable {wl.name}: T={b.T}", flush=True)
-    weights = wl.weights()
+    weights = gen_weights(wl)
     x = W.make_activations(b.T, shape.hidden, wl.seed)
     outs = []
     for _ in range(2):
-        kp, vp = W.make_cache(shape, b.num_pages, wl.seed)
+        kp, vp = gen_cache(shape, b.num_pages, wl.seed)
         gl = GpuLayer(rs, shape, weights, kp, vp, b.T, packed=True)
         y = host_bits(gl.step(b, x))
         outs.append((y, host_bits(gl.k_pages), host_bits(gl.v_pages)))

@@ -109,6 +109,59 @@ void oracle_linear(const uint16_t* W, int32_t N, int32_t K,
     }
 }
 
+/* R16: codes of in[i] / scale: round to nearest even in the 8-bit format, magnitudes above 448 become 448;
+ * the reciprocal of the scale is formed in double and rounded to fp32, the product is an fp32 product. */
+void oracle_quantise(const float* in, int64_t n, float scale, uint8_t* codes)
+{
+    float inv = (float)(1.0 / (double)scale);
+    for (int64_t i = 0; i < n; ++i) codes[i] = oracle_f32_to_e4m3(in[i] * inv);
+}
+
+/* R16: out[t, n] = (sum_k value(Wc[n, k]) * value(in_c[t, k])) * (a_scale * s_w[n]); the products of two 8-bit
+ * values are exact in fp32, the sum runs in acc_t, the two scales are multiplied in fp32 first. */
+void oracle_linear_w8a8(const uint8_t* Wc, const float* s_w, int32_t N, int32_t K,
+                        const uint8_t* in_c, float a_scale, int32_t n_rows, float* out)
+{
+    float lut[256];
+    for (int i = 0; i < 256; ++i) lut[i] = oracle_e4m3_to_f32((uint8_t)i);
+    /* the values of the input codes, once (a table look-up, no arithmetic) */
+    float* xv = (float*)malloc(sizeof(float) * ((size_t)n_rows * K + 1));
+    for (size_t i = 0; i < (size_t)n_rows * K; ++i) xv[i] = lut[in_c[i]];
+#pragma omp parallel
+    {
+        float* wv = (float*)malloc(sizeof(float) * ((size_t)K + 1));
+#pragma omp for schedule(static)
+        for (int32_t n = 0; n < N; ++n) {
+            for (int32_t k = 0; k < K; ++k) wv[k] = lut[Wc[(size_t)n * K + k]];
+            const float scale = a_scale * s_w[n];
+            for (int32_t t = 0; t < n_rows; ++t) {
+                const float* xr = xv + (size_t)t * K;
+                acc_t acc = 0;
+#pragma omp simd reduction(+ : acc)
+                for (int32_t k = 0; k < K; ++k)
+                    acc += (acc_t)wv[k] * (acc_t)xr[k];
+                out[(size_t)t * N + n] = (float)acc * scale;
+            }
+        }
+        free(wv);
+    }
+    free(xv);
+}
+
+/* One projection of the layer: 16-bit weights on fp32 inputs, or (R16) 8-bit codes on quantised inputs. */
+static void project(const uint16_t* W, const uint8_t* Wc, const float* s_w, float a_scale,
+                    int32_t N, int32_t K, const float* in, int32_t n_rows, float* out)
+{
+    if (!Wc) {
+        oracle_linear(W, N, K, in, n_rows, out);
+        return;
+    }
+    uint8_t* codes = (uint8_t*)malloc((size_t)n_rows * K + 1);
+    oracle_quantise(in, (int64_t)n_rows * K, a_scale, codes);
+    oracle_linear_w8a8(Wc, s_w, N, K, codes, a_scale, n_rows, out);
+    free(codes);
+}
+
 /* R3: (v_i, v_{i+d/2}) rotated by angle pos * base^(-2i/d) */
 void oracle_rope(float* vec, int32_t d, int32_t pos, float base)
 {
@@ -238,6 +291,7 @@ static int32_t kv_append_fp8(const oracle_config* c, const oracle_batch* b, cons
 static int32_t layer_step(const oracle_config* c, const oracle_batch* b,
                           const oracle_weights* w, const uint16_t* x,
                           void* k_pages, void* v_pages, int32_t num_pages, int fp8, float k_scale, float v_scale,
+                          const oracle_weights_w8a8* q8,
                           const int32_t* rows, int32_t n_rows,
                           float* y_f32, uint16_t* y_bf16,
                           float* tap_attn_out, float* tap_x1)
@@ -273,10 +327,10 @@ static int32_t layer_step(const oracle_config* c, const oracle_batch* b,
     /* 1. input norm (R2), 2. q/k/v (Eq. 3) for every token of the batch */
     float* h = (float*)malloc(sizeof(float) * (size_t)T * H);
     oracle_rmsnorm(xf, w->w_in_norm, c->rms_eps, T, H, h);
-    if (fp8)    /* R15: the quantisation decision is taken in the kernel's precision: bf16 inputs, fp32 sums */
+    if (fp8 && !q8)    /* R15: the quantisation decision is taken in the kernel's precision: bf16 inputs, fp32 sums */
         for (size_t i = 0; i < (size_t)T * H; ++i) h[i] = oracle_bf16_to_f32(oracle_f32_to_bf16(h[i]));
     float* qkv = (float*)malloc(sizeof(float) * (size_t)T * qkv_dim);
-    oracle_linear(w->w_qkv, qkv_dim, H, h, T, qkv);
+    project(w->w_qkv, q8 ? q8->w_qkv : NULL, q8 ? q8->s_qkv : NULL, q8 ? q8->a_qkv : 0.0f, qkv_dim, H, h, T, qkv);
     free(h);
 
     /* 3. rotary embedding on q and k (R3), 4. round k, v to bf16 and append (R5, R9) */
@@ -320,7 +374,9 @@ static int32_t layer_step(const oracle_config* c, const oracle_batch* b,
 
     /* 6. W_o (Eq. 5) and the residual (R1) */
     float* x1 = (float*)malloc(sizeof(float) * (size_t)n_out * H);
-    oracle_linear(w->w_o, H, q_dim, attn, n_out, x1);
+    if (q8)     /* R16: the attention output exists as bf16 before it is quantised */
+        for (size_t i = 0; i < (size_t)n_out * q_dim; ++i) attn[i] = oracle_bf16_to_f32(oracle_f32_to_bf16(attn[i]));
+    project(w->w_o, q8 ? q8->w_o : NULL, q8 ? q8->s_o : NULL, q8 ? q8->a_o : 0.0f, H, q_dim, attn, n_out, x1);
     free(attn);
     for (int32_t i = 0; i < n_out; ++i)
         for (int32_t j = 0; j < H; ++j)
@@ -332,7 +388,7 @@ static int32_t layer_step(const oracle_config* c, const oracle_batch* b,
     float* h2 = (float*)malloc(sizeof(float) * (size_t)n_out * H);
     oracle_rmsnorm(x1, w->w_post_norm, c->rms_eps, n_out, H, h2);
     float* gu = (float*)malloc(sizeof(float) * (size_t)n_out * 2 * I);
-    oracle_linear(w->w_gate_up, 2 * I, H, h2, n_out, gu);
+    project(w->w_gate_up, q8 ? q8->w_gate_up : NULL, q8 ? q8->s_gate_up : NULL, q8 ? q8->a_gate_up : 0.0f, 2 * I, H, h2, n_out, gu);
     free(h2);
     float* act = (float*)malloc(sizeof(float) * (size_t)n_out * I);
     for (int32_t i = 0; i < n_out; ++i)
@@ -342,7 +398,7 @@ static int32_t layer_step(const oracle_config* c, const oracle_batch* b,
         }
     free(gu);
     float* mlp = (float*)malloc(sizeof(float) * (size_t)n_out * H);
-    oracle_linear(w->w_down, H, I, act, n_out, mlp);
+    project(w->w_down, q8 ? q8->w_down : NULL, q8 ? q8->s_down : NULL, q8 ? q8->a_down : 0.0f, H, I, act, n_out, mlp);
     free(act);
 
     /* 8. y = x1 + mlp, fp32 and (optionally) rounded to bf16 */
@@ -362,7 +418,7 @@ int32_t oracle_layer_step(const oracle_config* c, const oracle_batch* b,
                           float* y_f32, uint16_t* y_bf16,
                           float* tap_attn_out, float* tap_x1)
 {
-    return layer_step(c, b, w, x, k_pages, v_pages, num_pages, 0, 1.0f, 1.0f, rows, n_rows, y_f32, y_bf16, tap_attn_out, tap_x1);
+    return layer_step(c, b, w, x, k_pages, v_pages, num_pages, 0, 1.0f, 1.0f, NULL, rows, n_rows, y_f32, y_bf16, tap_attn_out, tap_x1);
 }
 
 int32_t oracle_layer_step_fp8kv(const oracle_config* c, const oracle_batch* b,
@@ -373,7 +429,21 @@ int32_t oracle_layer_step_fp8kv(const oracle_config* c, const oracle_batch* b,
                                 float* tap_attn_out, float* tap_x1)
 {
     if (!(k_scale > 0.0f) || !(v_scale > 0.0f)) return -7;
-    return layer_step(c, b, w, x, k_pages, v_pages, num_pages, 1, k_scale, v_scale, rows, n_rows, y_f32, y_bf16, tap_attn_out, tap_x1);
+    return layer_step(c, b, w, x, k_pages, v_pages, num_pages, 1, k_scale, v_scale, NULL, rows, n_rows, y_f32, y_bf16, tap_attn_out, tap_x1);
+}
+
+int32_t oracle_layer_step_w8a8(const oracle_config* c, const oracle_batch* b,
+                               const oracle_weights_w8a8* q8, const uint16_t* x,
+                               void* k_pages, void* v_pages, int32_t num_pages, int32_t kv_fp8, float k_scale, float v_scale,
+                               const int32_t* rows, int32_t n_rows,
+                               float* y_f32, uint16_t* y_bf16,
+                               float* tap_attn_out, float* tap_x1)
+{
+    if (!(q8->a_qkv > 0.0f) || !(q8->a_o > 0.0f) || !(q8->a_gate_up > 0.0f) || !(q8->a_down > 0.0f)) return -7;
+    if (kv_fp8 && (!(k_scale > 0.0f) || !(v_scale > 0.0f))) return -7;
+    oracle_weights w = {q8->w_in_norm, NULL, NULL, q8->w_post_norm, NULL, NULL};
+    return layer_step(c, b, &w, x, k_pages, v_pages, num_pages, kv_fp8 ? 1 : 0, kv_fp8 ? k_scale : 1.0f, kv_fp8 ? v_scale : 1.0f,
+                      q8, rows, n_rows, y_f32, y_bf16, tap_attn_out, tap_x1);
 }
 
 /* Embedding -> n_layers x layer step -> final norm -> output layer on each request's last token */

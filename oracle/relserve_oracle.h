@@ -49,6 +49,17 @@
  *       rounded to bf16 before the q/k/v projection (bf16 inputs, fp32 sums); otherwise two correct
  *       implementations would disagree on the ~5 % of codes whose value lies next to a rounding boundary.
  *       Everything else is unchanged.
+ *   R16 quantised projections (a variant; the paper runs 16-bit models): each of the four projection matrices
+ *       holds 8-bit codes (the format of R15) of W[n, :] / s_w[n] with one fp32 scale per output row, and the
+ *       input of each projection is quantised to codes of a / s_a with one scale per projection, given by the
+ *       caller (static, as an engine calibrates it offline): code = round-to-nearest-even(a * (1 / s_a)),
+ *       magnitudes above 448 become 448, the reciprocal formed in double and rounded to fp32.
+ *       out[t, n] = (sum_k value(a_code[t, k]) * value(w_code[n, k])) * (s_a * s_w[n]); the products are exact in
+ *       fp32, the sum is an fp32 sum, the two scales are multiplied first.  What is quantised: the normed
+ *       activations from their fp32 values (both norms); the attention output after its rounding to bf16 (it
+ *       exists as bf16 between the attention and W_o); silu(g) * u from its fp32 value.  With R16 the bf16
+ *       rounding of R15 before the q/k/v projection does not apply (its input is the codes).  Residuals, norms,
+ *       rotary embedding, attention and the cache are unchanged.
  *
  * Precision: inputs, weights and the cache hold bf16 bit patterns (uint16_t);
  * all arithmetic is fp32 with acc_t accumulators (float, or double when built
@@ -139,6 +150,25 @@ void oracle_attention_token_fp8kv(const oracle_config* c, const oracle_batch* b,
                                   const uint8_t* k_pages, const uint8_t* v_pages, float k_scale, float v_scale,
                                   float* out);
 
+/* R16: quantised projections. */
+typedef struct {
+    const uint16_t* w_in_norm;    /* [H] bf16 */
+    const uint8_t*  w_qkv;        /* [(n_h + 2 n_kv) d, H] codes */
+    const float*    s_qkv;        /* [(n_h + 2 n_kv) d] scale of each output row */
+    const uint8_t*  w_o;          /* [H, n_h d] */
+    const float*    s_o;          /* [H] */
+    const uint16_t* w_post_norm;  /* [H] bf16 */
+    const uint8_t*  w_gate_up;    /* [2 I, H] */
+    const float*    s_gate_up;    /* [2 I] */
+    const uint8_t*  w_down;       /* [H, I] */
+    const float*    s_down;       /* [H] */
+    float a_qkv, a_o, a_gate_up, a_down;   /* scale of each projection's input */
+} oracle_weights_w8a8;
+
+void oracle_quantise(const float* in, int64_t n, float scale, uint8_t* codes);
+void oracle_linear_w8a8(const uint8_t* Wc, const float* s_w, int32_t N, int32_t K,
+                        const uint8_t* in_c, float a_scale, int32_t n_rows, float* out);
+
 /* The whole step.  x: [T, H] bf16.  The cache is updated in place for every
  * token of the batch.  rows/n_rows select which token rows get the rest of the
  * layer (NULL/0 = all T, in order); y_f32 [n_out, H] and optional y_bf16 are
@@ -160,6 +190,16 @@ int32_t oracle_layer_step_fp8kv(const oracle_config* c, const oracle_batch* b,
                                 const int32_t* rows, int32_t n_rows,
                                 float* y_f32, uint16_t* y_bf16,
                                 float* tap_attn_out, float* tap_x1);
+
+/* oracle_layer_step with the quantised projections of R16, over a 16-bit cache (kv_fp8 = 0: pools of bf16, the
+ * scales are ignored) or the quantised cache of R15 (kv_fp8 = 1: pools of codes).  Returns -7 for a scale that
+ * is not positive. */
+int32_t oracle_layer_step_w8a8(const oracle_config* c, const oracle_batch* b,
+                               const oracle_weights_w8a8* q8, const uint16_t* x,
+                               void* k_pages, void* v_pages, int32_t num_pages, int32_t kv_fp8, float k_scale, float v_scale,
+                               const int32_t* rows, int32_t n_rows,
+                               float* y_f32, uint16_t* y_bf16,
+                               float* tap_attn_out, float* tap_x1);
 
 /* A stack of identical-shape layers between an embedding table and an output
  * layer (Sec. 2.3 "LLM Inference": embedding layer, Transformer layers, output

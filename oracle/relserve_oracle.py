@@ -50,6 +50,12 @@ class _Weights(C.Structure):
                 ("w_in_norm", "w_qkv", "w_o", "w_post_norm", "w_gate_up", "w_down")]
 
 
+class _WeightsW8A8(C.Structure):
+    _fields_ = ([(n, C.c_void_p) for n in ("w_in_norm", "w_qkv", "s_qkv", "w_o", "s_o", "w_post_norm", "w_gate_up", "s_gate_up",
+                                            "w_down", "s_down")]
+                + [(n, C.c_float) for n in ("a_qkv", "a_o", "a_gate_up", "a_down")])
+
+
 class _Model(C.Structure):
     _fields_ = [("n_layers", C.c_int32), ("vocab", C.c_int32), ("embedding", C.c_void_p),
                 ("layers", C.c_void_p), ("w_final_norm", C.c_void_p), ("w_lm_head", C.c_void_p)]
@@ -108,6 +114,13 @@ class Oracle:
         L.oracle_layer_step_fp8kv.restype = C.c_int32
         L.oracle_layer_step_fp8kv.argtypes = ([C.c_void_p] * 6 + [C.c_int32, C.c_float, C.c_float, C.c_void_p, C.c_int32]
                                               + [C.c_void_p] * 4)
+        L.oracle_quantise.restype = None
+        L.oracle_quantise.argtypes = [C.c_void_p, C.c_int64, C.c_float, C.c_void_p]
+        L.oracle_linear_w8a8.restype = None
+        L.oracle_linear_w8a8.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_float, C.c_int32, C.c_void_p]
+        L.oracle_layer_step_w8a8.restype = C.c_int32
+        L.oracle_layer_step_w8a8.argtypes = ([C.c_void_p] * 6 + [C.c_int32, C.c_int32, C.c_float, C.c_float, C.c_void_p, C.c_int32]
+                                             + [C.c_void_p] * 4)
         L.oracle_greedy_sample.restype = None
         L.oracle_greedy_sample.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p]
 
@@ -198,13 +211,39 @@ class Oracle:
         del keep
         return out
 
+    def quantise(self, values: np.ndarray, scale: float) -> np.ndarray:
+        values = _chk(np.ascontiguousarray(values), np.float32, "values")
+        codes = np.empty(values.shape, np.uint8)
+        self.lib.oracle_quantise(_ptr(values), values.size, float(scale), _ptr(codes))
+        return codes
+
+    def linear_w8a8(self, w_codes: np.ndarray, s_w: np.ndarray, in_codes: np.ndarray, a_scale: float) -> np.ndarray:
+        w_codes = _chk(np.ascontiguousarray(w_codes), np.uint8, "W codes")
+        s_w = _chk(np.ascontiguousarray(s_w), np.float32, "row scales")
+        in_codes = _chk(np.ascontiguousarray(in_codes), np.uint8, "input codes")
+        n, k = w_codes.shape
+        assert in_codes.shape[1] == k and s_w.shape == (n,)
+        out = np.empty((in_codes.shape[0], n), np.float32)
+        self.lib.oracle_linear_w8a8(_ptr(w_codes), _ptr(s_w), n, k, _ptr(in_codes), float(a_scale), in_codes.shape[0], _ptr(out))
+        return out
+
     def layer_step(self, shape, batch, weights: dict, x_bits, k_pages, v_pages, rows=None, kv_scales=None) -> StepResult:
         """One layer step; k_pages / v_pages are updated in place.  kv_scales = (k_scale, v_scale) selects the
-        quantised cache: the pools are then uint8 arrays of 8-bit codes."""
+        quantised cache: the pools are then uint8 arrays of 8-bit codes.  Weights with a key "s_qkv" select the
+        quantised projections: w_qkv / w_o / w_gate_up / w_down are uint8 codes, s_* their fp32 row scales, a_* the
+        scale of each projection's input."""
         cfg = self._cfg(shape)
         b, keep = self._batch(batch)
-        wk = {k: _chk(np.ascontiguousarray(v), np.uint16, k) for k, v in weights.items()}
-        w = _Weights(*[_ptr(wk[n]) for n, _ in _Weights._fields_])
+        w8a8 = "s_qkv" in weights
+        if w8a8:
+            dt = {"w_in_norm": np.uint16, "w_post_norm": np.uint16, "w_qkv": np.uint8, "w_o": np.uint8, "w_gate_up": np.uint8,
+                  "w_down": np.uint8, "s_qkv": np.float32, "s_o": np.float32, "s_gate_up": np.float32, "s_down": np.float32}
+            wk = {k: _chk(np.ascontiguousarray(weights[k]), t, k) for k, t in dt.items()}
+            w = _WeightsW8A8(*[_ptr(wk[n]) for n, t in _WeightsW8A8._fields_ if t is C.c_void_p],
+                             *[float(weights[n]) for n, t in _WeightsW8A8._fields_ if t is C.c_float])
+        else:
+            wk = {k: _chk(np.ascontiguousarray(v), np.uint16, k) for k, v in weights.items()}
+            w = _Weights(*[_ptr(wk[n]) for n, _ in _Weights._fields_])
         x_bits = _chk(np.ascontiguousarray(x_bits), np.uint16, "x")
         pool_dtype = np.uint16 if kv_scales is None else np.uint8
         _chk(k_pages, pool_dtype, "k_pages")
@@ -220,7 +259,12 @@ class Oracle:
         x1 = np.empty((n_out, shape.hidden), np.float32)
         tail = (_ptr(rows) if rows is not None and len(rows) else None, 0 if rows is None else len(rows),
                 _ptr(y), _ptr(yb), _ptr(attn), _ptr(x1))
-        if kv_scales is None:
+        if w8a8:
+            ks, vs = (1.0, 1.0) if kv_scales is None else kv_scales
+            rc = self.lib.oracle_layer_step_w8a8(C.byref(cfg), C.byref(b), C.byref(w), _ptr(x_bits),
+                                                 _ptr(k_pages), _ptr(v_pages), k_pages.shape[0],
+                                                 0 if kv_scales is None else 1, float(ks), float(vs), *tail)
+        elif kv_scales is None:
             rc = self.lib.oracle_layer_step(C.byref(cfg), C.byref(b), C.byref(w), _ptr(x_bits),
                                             _ptr(k_pages), _ptr(v_pages), k_pages.shape[0], *tail)
         else:

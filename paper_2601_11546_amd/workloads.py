@@ -201,6 +201,47 @@ def make_weights(shape: LayerShape, seed: int, n_layers: int = 0) -> dict:
             "w_post_norm": norm(), "w_gate_up": proj(2 * I, H), "w_down": proj(H, I, out_std)}
 
 
+def e4m3_code_values() -> np.ndarray:
+    """Value of each of the 256 codes of the 8-bit floating point format (1 sign, 4 exponent, 3 mantissa bits, bias 7;
+    0x7f / 0xff are NaN).  A format table, no arithmetic of the method."""
+    c = np.arange(256)
+    e, m = (c >> 3) & 15, c & 7
+    mag = np.where(e == 0, m * 2.0 ** -9, (8 + m) * 2.0 ** (e - 10.0))
+    v = np.where(c & 128, -mag, mag).astype(np.float32)
+    v[[0x7F, 0xFF]] = np.nan
+    return v
+
+
+def nearest_e4m3_codes(a: np.ndarray) -> np.ndarray:
+    """Codes whose values are nearest to the entries of `a` (magnitudes above 448 give 448).  Used to DRAW inputs
+    (weight codes); which way a tie falls does not matter here."""
+    mags = e4m3_code_values()[:0x7F].astype(np.float64)            # 0 .. 448, increasing with the code
+    mid = (mags[1:] + mags[:-1]) / 2
+    a = np.asarray(a, np.float32)
+    code = np.searchsorted(mid, np.abs(a).astype(np.float64)).astype(np.uint8)
+    return code | (np.signbit(a).astype(np.uint8) << 7)
+
+
+# Scales of the four projections' inputs in the quantised-projection variant (static, per tensor, as an engine would
+# calibrate them offline): normed activations have unit RMS (room for 8 sigma); attention outputs are averages of
+# values (room for 6); silu(g) * u has RMS ~1 with a long tail (room for 24).
+W8A8_INPUT_SCALES = {"a_qkv": 8.0 / 448.0, "a_o": 6.0 / 448.0, "a_gate_up": 8.0 / 448.0, "a_down": 24.0 / 448.0}
+
+
+def make_weights_w8a8(shape: LayerShape, seed: int, n_layers: int = 0) -> dict:
+    """The layer of make_weights with its four projections as 8-bit codes: each output row is scaled so that its
+    largest magnitude maps to 448 (s_* = the fp32 scale of every row), the norm weights stay bf16."""
+    w = make_weights(shape, seed, n_layers)
+    out = {"w_in_norm": w["w_in_norm"], "w_post_norm": w["w_post_norm"], **{k: np.float32(v) for k, v in W8A8_INPUT_SCALES.items()}}
+    for name in ("qkv", "o", "gate_up", "down"):
+        f = bf16_bits_to_f32(w["w_" + name])
+        s = (np.abs(f).max(axis=1) / np.float32(448.0)).astype(np.float32)
+        s[s == 0] = np.float32(1.0)
+        out["w_" + name] = nearest_e4m3_codes(f / s[:, None])
+        out["s_" + name] = s
+    return out
+
+
 def make_model(shape: LayerShape, n_layers: int, vocab: int, seed: int, scaled: bool = True) -> dict:
     """Random-init stack: embedding ~N(0, 1) (so that the residual stream has unit scale like the
     activations of the single-layer workloads), layers as make_weights, output layer ~N(0, 0.02)."""

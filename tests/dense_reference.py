@@ -37,18 +37,35 @@ def dense_model_logits(shape, model, token_ids):
     return F.linear(h, _t(model["w_lm_head"]))[0]
 
 
-def dense_layer(shape, weights, x_bits, round_kv_bf16=True, kv_override=None):
+def dense_layer(shape, weights, x_bits, round_kv_bf16=True, kv_override=None, quantise=None, code_values=None):
     """x_bits: [L, H] one request's whole sequence.  Returns dict of fp64 tensors.
 
     kv_override: optional (k, v) fp64 tensors [L, n_kv, d] used instead of the
     recomputed keys/values (lets a test feed the oracle's cached bits back in).
+    quantise / code_values: the caller's fp32 -> 8-bit codes and codes -> fp64 conversions (through the library's
+    own 8-bit type); then `weights` holds codes w_*, row scales s_* and input scales a_* and every projection is
+    (codes of the input) x (codes of the weights) x (input scale x row scale).
     """
     H, d, nh, nkv = shape.hidden, shape.head_dim, shape.n_q_heads, shape.n_kv_heads
     x = _t(x_bits)
     L = x.shape[0]
-    w = {k: _t(v) for k, v in weights.items()}
+    if quantise is None:
+        w = {k: _t(v) for k, v in weights.items()}
+
+        def proj(a, name, round_bf16=False):
+            return F.linear(a, w["w_" + name])
+    else:
+        w = {k: _t(weights[k]) for k in ("w_in_norm", "w_post_norm")}
+
+        def proj(a, name, round_bf16=False):
+            if round_bf16:
+                a = a.to(torch.float32).to(torch.bfloat16)
+            s_a = float(weights["a_" + name])
+            codes = quantise(a.to(torch.float32), s_a)
+            out = F.linear(code_values(codes), code_values(weights["w_" + name]))
+            return out * torch.from_numpy(weights["s_" + name].astype(np.float64))[None, :] * float(np.float32(s_a))
     h = F.rms_norm(x, (H,), w["w_in_norm"], eps=shape.rms_eps)
-    qkv = F.linear(h, w["w_qkv"])
+    qkv = proj(h, "qkv")
     q = qkv[:, :nh * d].reshape(L, nh, d)
     k = qkv[:, nh * d:(nh + nkv) * d].reshape(L, nkv, d)
     v = qkv[:, (nh + nkv) * d:].reshape(L, nkv, d)
@@ -67,10 +84,10 @@ def dense_layer(shape, weights, x_bits, round_kv_bf16=True, kv_override=None):
     o = F.scaled_dot_product_attention(q.transpose(0, 1)[None], kk.transpose(0, 1)[None],
                                        vv.transpose(0, 1)[None], is_causal=True)[0]
     o = o.transpose(0, 1).reshape(L, nh * d)
-    x1 = x + F.linear(o, w["w_o"])
+    x1 = x + proj(o, "o", round_bf16=True)
     h2 = F.rms_norm(x1, (H,), w["w_post_norm"], eps=shape.rms_eps)
-    gu = F.linear(h2, w["w_gate_up"])
+    gu = proj(h2, "gate_up")
     I = shape.mlp_dim
     act = F.silu(gu[:, :I]) * gu[:, I:]
-    y = x1 + F.linear(act, w["w_down"])
+    y = x1 + proj(act, "down")
     return {"y": y, "x1": x1, "attn_out": o, "k": k_own, "v": v_own, "q": q}

@@ -43,6 +43,16 @@ MUTANTS = [
     ("quantised_v_with_k_scale", "v_pages[(size_t)slot * row + i] = oracle_f32_to_e4m3(src[row + i] * v_inv);", "v_pages[(size_t)slot * row + i] = oracle_f32_to_e4m3(src[row + i] * k_inv);"),
     ("quantised_k_before_rotation_slot", "k_pages[(size_t)slot * row + i] = oracle_f32_to_e4m3(src[i] * k_inv);", "k_pages[(size_t)slot * row + i] = oracle_f32_to_e4m3(src[i] * k_scale);"),
     ("quantised_inputs_not_rounded", "for (size_t i = 0; i < (size_t)T * H; ++i) h[i] = oracle_bf16_to_f32(oracle_f32_to_bf16(h[i]));", ";"),
+    ("w8a8_row_scale_dropped", "const float scale = a_scale * s_w[n];", "const float scale = a_scale;"),
+    ("w8a8_input_scale_dropped", "const float scale = a_scale * s_w[n];", "const float scale = s_w[n];"),
+    ("w8a8_scale_of_the_next_row", "const float scale = a_scale * s_w[n];", "const float scale = a_scale * s_w[(n + 1) % N];"),
+    ("w8a8_quantiser_multiplies_by_the_scale", "codes[i] = oracle_f32_to_e4m3(in[i] * inv);", "codes[i] = oracle_f32_to_e4m3(in[i] * scale);"),
+    ("w8a8_weights_transposed", "wv[k] = lut[Wc[(size_t)n * K + k]];", "wv[k] = lut[Wc[(size_t)k * N + n]];"),
+    ("w8a8_attention_output_not_rounded", "for (size_t i = 0; i < (size_t)n_out * q_dim; ++i) attn[i] = oracle_bf16_to_f32(oracle_f32_to_bf16(attn[i]));", ";"),
+    ("w8a8_down_input_with_the_gate_up_scale", "q8 ? q8->a_down : 0.0f, H, I, act", "q8 ? q8->a_gate_up : 0.0f, H, I, act"),
+    ("w8a8_o_input_with_the_qkv_scale", "q8 ? q8->a_o : 0.0f, H, q_dim, attn", "q8 ? q8->a_qkv : 0.0f, H, q_dim, attn"),
+    ("w8a8_gate_up_rows_with_the_qkv_row_scales", "q8 ? q8->s_gate_up : NULL", "q8 ? q8->s_qkv : NULL"),
+    ("w8a8_cache_inputs_rounded_as_in_the_16_bit_variant", "if (fp8 && !q8)", "if (fp8 || q8)"),
     ("softmax_unnormalised", "out[(size_t)a * d + i] = (float)(o[i] / denom);", "out[(size_t)a * d + i] = (float)(o[i]);"),
 ]
 

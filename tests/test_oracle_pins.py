@@ -612,6 +612,145 @@ def test_quantised_cache_layer_step(oracle):
     assert np.linalg.norm(res.y_f32 - y16) / np.linalg.norm(y16) < 3e-2
 
 
+# ---------------------------------------------------------------------------
+# quantised projections (reading R16 of the oracle header)
+# ---------------------------------------------------------------------------
+def _codes_to_f64(codes: np.ndarray) -> torch.Tensor:
+    """Values of 8-bit codes through the library's own type."""
+    return torch.from_numpy(codes.copy()).view(torch.float8_e4m3fn).to(torch.float64)
+
+
+def _torch_quantise(values: torch.Tensor, scale: float) -> np.ndarray:
+    """fp32 values -> codes of values / scale through the library's conversion (which does not saturate: clamp first)."""
+    inv = np.float32(1.0 / np.float64(scale))
+    scaled = (values.to(torch.float32) * torch.tensor(inv)).clamp(-448.0, 448.0)
+    return scaled.to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+
+
+def test_quantise_matches_the_library_type(oracle):
+    rng = np.random.default_rng(70)
+    vals = (rng.standard_normal(20000) * 10.0 ** rng.integers(-4, 3, 20000)).astype(np.float32)
+    for scale in (1.0, 0.0133, 3.7, 8.0 / 448.0):
+        got = oracle.quantise(vals, scale)
+        np.testing.assert_array_equal(got, _torch_quantise(torch.from_numpy(vals), scale))
+    # beyond the range: the largest magnitude, with the sign
+    np.testing.assert_array_equal(oracle.quantise(np.array([1e6, -1e6, 449.0 * 0.5], np.float32), 0.5), [0x7e, 0xfe, 0x7e])
+    assert oracle.quantise(np.array([1.0], np.float32), 2.0)[0] == oracle.f32_to_e4m3(0.5)      # divides by the scale
+
+
+def test_linear_w8a8_matches_matmul_of_the_code_values(oracle):
+    rng = np.random.default_rng(71)
+    N, K, T = 37, 192, 11
+    wc = W.nearest_e4m3_codes(rng.standard_normal((N, K)).astype(np.float32) * 100)
+    xc = W.nearest_e4m3_codes(rng.standard_normal((T, K)).astype(np.float32) * 30)
+    s_w = (0.5 + rng.random(N)).astype(np.float32) * np.float32(1e-3)
+    a = 0.037
+    got = oracle.linear_w8a8(wc, s_w, xc, a)
+    want = F.linear(_codes_to_f64(xc), _codes_to_f64(wc)) * torch.from_numpy(s_w.astype(np.float64))[None, :] * float(np.float32(a))
+    np.testing.assert_allclose(got, want.numpy(), rtol=2e-6, atol=1e-9)
+    # small whole numbers: every product and sum is exact, the result is the integer dot product times the scales
+    vals = W.e4m3_code_values()
+    small = np.array([c for c in range(256) if np.isfinite(vals[c]) and vals[c] == np.round(vals[c]) and abs(vals[c]) <= 16], np.uint8)
+    wc = small[rng.integers(0, len(small), (N, 64))]
+    xc = small[rng.integers(0, len(small), (T, 64))]
+    ints = vals[xc].astype(np.int64) @ vals[wc].astype(np.int64).T
+    got = oracle.linear_w8a8(wc, np.full(N, 0.25, np.float32), xc, 2.0)
+    np.testing.assert_array_equal(got, (ints * 0.5).astype(np.float32))
+    # which index the row scale follows: a matrix that picks input k(n) for output n
+    pick = rng.integers(0, 64, N)
+    wc = np.zeros((N, 64), np.uint8)
+    wc[np.arange(N), pick] = 0x38                                    # the code of 1.0
+    got = oracle.linear_w8a8(wc, s_w, xc, 1.0)
+    np.testing.assert_array_equal(got, vals[xc][:, pick] * s_w[None, :])
+
+
+_W8A8_SHAPE = W.LayerShape(256, 4, 2, 64, 384)
+_W8A8_SCALES = {"a_qkv": 0.019, "a_o": 0.0071, "a_gate_up": 0.023, "a_down": 0.041}     # all different: a swap shows
+
+
+def _w8a8_weights(seed):
+    w = W.make_weights_w8a8(_W8A8_SHAPE, seed)
+    w.update({k: np.float32(v) for k, v in _W8A8_SCALES.items()})
+    return w
+
+
+def test_layer_step_w8a8_is_the_composition_of_pinned_pieces(oracle):
+    """The step with quantised projections, re-assembled here from the oracle's separately pinned pieces (norm,
+    quantiser, code matmul, rotary embedding, append, attention): pins WHAT is quantised with WHICH scale."""
+    shape = _W8A8_SHAPE
+    wl = W.workload_tiny_prefix(shape=shape)
+    b = wl.batch
+    w = _w8a8_weights(72)
+    x = W.make_activations(b.T, shape.hidden, 73)
+    kp, vp = W.make_cache(shape, b.num_pages, 74)
+    k1, v1 = kp.copy(), vp.copy()
+    res = oracle.layer_step(shape, b, w, x, kp, vp)
+    d, nh, nkv, I = shape.head_dim, shape.n_q_heads, shape.n_kv_heads, shape.mlp_dim
+    xf = W.bf16_bits_to_f32(x)
+    h = oracle.rmsnorm(xf, w["w_in_norm"], shape.rms_eps)
+    qkv = oracle.linear_w8a8(w["w_qkv"], w["s_qkv"], oracle.quantise(h, w["a_qkv"]), w["a_qkv"])
+    tok_req = np.repeat(np.arange(b.num_reqs), np.diff(b.q_start))
+    tok_pos = np.concatenate([np.arange(b.ctx_len[r] - (b.q_start[r + 1] - b.q_start[r]), b.ctx_len[r]) for r in range(b.num_reqs)])
+    for t in range(b.T):
+        for a in range(nh + nkv):
+            qkv[t, a * d:(a + 1) * d] = oracle.rope(qkv[t, a * d:(a + 1) * d], int(tok_pos[t]), shape.rope_base)
+    kb = W.f32_to_bf16_bits(qkv[:, nh * d:(nh + nkv) * d]).reshape(b.T, nkv, d)
+    vb = W.f32_to_bf16_bits(qkv[:, (nh + nkv) * d:]).reshape(b.T, nkv, d)
+    oracle.kv_append(shape, b, kb, vb, k1, v1)
+    np.testing.assert_array_equal(k1, kp)
+    np.testing.assert_array_equal(v1, vp)
+    attn = np.stack([oracle.attention_token(shape, b, int(tok_req[t]), int(tok_pos[t]), qkv[t, :nh * d].reshape(nh, d), k1, v1).reshape(-1)
+                     for t in range(b.T)])
+    np.testing.assert_array_equal(res.attn_out, attn)
+    attn16 = W.bf16_bits_to_f32(W.f32_to_bf16_bits(attn))            # it exists as bf16 before it is quantised
+    x1 = xf + oracle.linear_w8a8(w["w_o"], w["s_o"], oracle.quantise(attn16, w["a_o"]), w["a_o"])
+    np.testing.assert_array_equal(res.x1, x1)
+    h2 = oracle.rmsnorm(x1, w["w_post_norm"], shape.rms_eps)
+    gu = oracle.linear_w8a8(w["w_gate_up"], w["s_gate_up"], oracle.quantise(h2, w["a_gate_up"]), w["a_gate_up"])
+    g, u = gu[:, :I].astype(np.float64), gu[:, I:].astype(np.float64)
+    act = (g / (1.0 + np.exp(-g)) * u).astype(np.float32)
+    codes = oracle.quantise(act, w["a_down"])
+    mine = oracle.linear_w8a8(w["w_down"], w["s_down"], codes, w["a_down"])
+    # silu in fp64 here, fp32 there: an activation next to a rounding boundary may take the neighbouring code
+    np.testing.assert_allclose(res.y_f32, x1 + mine, rtol=0, atol=2e-3)
+    assert np.mean(np.abs(res.y_f32 - (x1 + mine)) > 1e-6) < 0.3
+
+
+def test_layer_step_w8a8_matches_dense_recompute_through_library_types(oracle):
+    """The same step on contiguous sequences with torch's own 8-bit type and fp64 matmuls.  Codes are decided in fp32
+    there and in fp64 here, so a few inputs fall on the other side of a rounding boundary: a tolerance, far below
+    the effect of any wiring mistake (which the composition pin above catches exactly)."""
+    shape = _W8A8_SHAPE
+    w = _w8a8_weights(75)
+    L = 40
+    flow = make_flow(shape, [L, 23], [[(0, L), (1, 23)]], seed=76)
+    kp, vp = W.make_cache(shape, flow.num_pages, 77)
+    ys = run_flow(flow, lambda bb, xx: oracle.layer_step(shape, bb, w, xx, kp, vp).y_f32)
+    for r, n in enumerate([L, 23]):
+        want = dense_layer(shape, w, flow.x_full[r], quantise=_torch_quantise, code_values=_codes_to_f64)["y"].numpy()
+        got = ys[r]
+        rel = np.linalg.norm(got - want) / np.linalg.norm(want)
+        xin = W.bf16_bits_to_f32(flow.x_full[r])
+        crel = np.linalg.norm(got - want) / np.linalg.norm(want - xin)
+        print(f"request {r}: rel {rel:.2e}, on the layer's contribution {crel:.2e}")
+        assert rel < 1e-4 and crel < 2e-3, (r, rel, crel)
+
+
+def test_layer_step_w8a8_saturates_and_rejects_bad_scales(oracle):
+    shape = _W8A8_SHAPE
+    wl = W.workload_tiny(shape=shape)
+    b = wl.batch
+    w = _w8a8_weights(78)
+    x = W.make_activations(b.T, shape.hidden, 79)
+    kp, vp = W.make_cache(shape, b.num_pages, 80)
+    base = oracle.layer_step(shape, b, w, x, kp.copy(), vp.copy()).y_f32
+    tiny = dict(w, a_qkv=np.float32(1e-3))      # every normed activation beyond 0.448 becomes 0.448: a different, finite output
+    sat = oracle.layer_step(shape, b, tiny, x, kp.copy(), vp.copy()).y_f32
+    assert np.isfinite(sat).all() and np.abs(sat - base).max() > 1e-2
+    with pytest.raises(ValueError):
+        oracle.layer_step(shape, b, dict(w, a_o=np.float32(0.0)), x, kp.copy(), vp.copy())
+
+
 def test_golden_tiny_layer_step_is_stable():
     """The frozen oracle outputs (written by tests/golden/make_golden.py) still hold."""
     import os

@@ -204,6 +204,40 @@ int32_t relserve_layer_step_static(const relserve_layer* layer, const relserve_b
                                    const relserve_layer_weights* weights,
                                    const void* x, void* y, relserve_kv_cache cache, void* stream);
 
+/* The layer step with quantised projections (a variant beside the paper's 16-bit models, Sec. 5.1
+ * "Models"; the four dense maps are Eq. 3, W_o of Eq. 5 and the two of the feed-forward block).
+ * Each projection matrix holds 8-bit floating point codes (1 sign, 4 exponent, 3 mantissa bits, bias 7,
+ * largest magnitude 448) of W[n, :] / s[n] with one fp32 scale per output row; the input of each projection is
+ * quantised with one scale per projection, given by the caller (static, as an engine calibrates it offline):
+ * code = round-to-nearest-even(a * (1 / a_scale)), magnitudes above 448 become 448.  A projection is
+ * out[t, n] = (sum_k value(a_code[t, k]) * value(w_code[n, k])) * (a_scale * s[n]), products exact, fp32 sums.
+ * What is quantised: the normed activations (from fp32), the attention output (after its rounding to bf16),
+ * silu(g) * u (from fp32).  Norms, rotary embedding, attention, residuals and the cache are those of
+ * relserve_layer_step; the cache may be 16-bit or quantised.
+ * Pointers are device memory.  w_*: uint8 [out, in] row-major, or (packed != 0) relserve_pack_weight applied to
+ * the matrix seen as [out, in / 2] two-byte units.  s_*: fp32 [out].  hidden, n_q_heads * head_dim and mlp_dim
+ * must be multiples of 128 (RELSERVE_ERR_BAD_ARGUMENT otherwise); scales must be positive and finite. */
+typedef struct {
+    const void* w_in_norm;     /* [H] bf16 */
+    const void* w_qkv;         /* [(n_q + 2 n_kv) d, H] codes */
+    const float* s_qkv;        /* [(n_q + 2 n_kv) d] */
+    const void* w_o;           /* [H, n_q d] */
+    const float* s_o;          /* [H] */
+    const void* w_post_norm;   /* [H] bf16 */
+    const void* w_gate_up;     /* [2 I, H], gate rows then up rows */
+    const float* s_gate_up;    /* [2 I] */
+    const void* w_down;        /* [H, I] */
+    const float* s_down;       /* [H] */
+    float a_qkv, a_o, a_gate_up, a_down;   /* scale of each projection's input */
+    int32_t packed;
+} relserve_layer_weights_w8a8;
+
+/* Arguments, workspace (relserve_workspace_bytes), ownership and errors as relserve_layer_step. */
+int32_t relserve_layer_step_w8a8(const relserve_layer* layer, const relserve_batch* batch,
+                                 const relserve_layer_weights_w8a8* weights,
+                                 const void* x, void* y, relserve_kv_cache cache,
+                                 void* workspace, size_t workspace_bytes, void* stream);
+
 /* A stack of n_layers identical-shape layers between an embedding table and an
  * output layer (Sec. 2.3 "LLM Inference": the output layer turns the final
  * hidden representation of a request's LAST token into next-token logits).
@@ -246,6 +280,19 @@ int32_t relserve_greedy_sample(const void* logits, int32_t n_rows, int32_t vocab
  * x_is_f32 == 0, else fp32; out bf16. */
 int32_t relserve_rmsnorm(const void* x, int32_t x_is_f32, const void* w, float eps,
                          int32_t n_rows, int32_t hidden, void* out, void* stream);
+
+/* Stages of the quantised-projection variant.  relserve_rmsnorm_codes: relserve_rmsnorm whose output is uint8
+ * codes of the normed value / scale (taken from the fp32 value).  relserve_quantise_bf16: codes [n] of a bf16
+ * array / scale (n a multiple of 8).  relserve_linear_w8a8: relserve_linear on codes a [T, K], w [N, K] (row-major,
+ * or packed as described at relserve_layer_weights_w8a8) with row scales w_scale [N] and input scale a_scale;
+ * K a multiple of 128; epilogues as relserve_linear (the residuals and 16-bit outputs unchanged); out_scale > 0
+ * with epilogue 3 stores uint8 codes of silu(g) * u / out_scale instead of bf16. */
+int32_t relserve_rmsnorm_codes(const void* x, int32_t x_is_f32, const void* w, float eps,
+                               int32_t n_rows, int32_t hidden, float scale, void* out, void* stream);
+int32_t relserve_quantise_bf16(const void* in, int64_t n, float scale, void* codes, void* stream);
+int32_t relserve_linear_w8a8(const void* a, const void* w, const float* w_scale, float a_scale,
+                             int32_t T, int32_t N, int32_t K, int32_t epilogue, const void* residual, void* out,
+                             float out_scale, int32_t packed, void* stream);
 
 /* out[T, N] = a[T, K] * w[N, K]^T (Eq. 3 and every other dense map), bf16 in,
  * fp32 accumulate.  epilogue: 0 = store bf16; 1 = add residual (bf16 [T, N],

@@ -37,7 +37,8 @@ EXPORTS = ["relserve_version", "relserve_strerror", "relserve_config_validate", 
            "relserve_packed_weight_elems", "relserve_pack_weight", "relserve_linear_packed",
            "relserve_duration_fit", "relserve_duration_predict", "relserve_batch_decompose", "relserve_pem_estimate",
            "relserve_aba_decide", "relserve_starved_priority", "relserve_static_priority", "relserve_utok_estimate",
-           "relserve_priority_reuse", "relserve_prefill_candidate"]
+           "relserve_priority_reuse", "relserve_prefill_candidate",
+           "relserve_layer_step_w8a8", "relserve_rmsnorm_codes", "relserve_quantise_bf16", "relserve_linear_w8a8"]
 
 
 class RelserveError(RuntimeError):
@@ -85,6 +86,12 @@ class LayerWeights(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in WEIGHT_NAMES] + [("packed", C.c_int32)]
 
 
+class LayerWeightsW8A8(C.Structure):
+    _fields_ = ([(n, C.c_void_p) for n in ("w_in_norm", "w_qkv", "s_qkv", "w_o", "s_o", "w_post_norm", "w_gate_up", "s_gate_up",
+                                            "w_down", "s_down")]
+                + [(n, C.c_float) for n in ("a_qkv", "a_o", "a_gate_up", "a_down")] + [("packed", C.c_int32)])
+
+
 class Model(C.Structure):
     _fields_ = [("n_layers", C.c_int32), ("vocab", C.c_int32), ("embedding", C.c_void_p), ("layers", C.c_void_p),
                 ("caches", C.c_void_p), ("w_final_norm", C.c_void_p), ("w_lm_head", C.c_void_p)]
@@ -129,6 +136,13 @@ for _n, _a in {
                             C.c_void_p, C.c_size_t, C.c_void_p],
     "relserve_layer_step_static": [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, KVCache, C.c_void_p],
     "relserve_static_scratch_bytes": [C.c_void_p],
+    "relserve_layer_step_w8a8": [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, KVCache,
+                                 C.c_void_p, C.c_size_t, C.c_void_p],
+    "relserve_rmsnorm_codes": [C.c_void_p, C.c_int32, C.c_void_p, C.c_float, C.c_int32, C.c_int32, C.c_float, C.c_void_p,
+                               C.c_void_p],
+    "relserve_quantise_bf16": [C.c_void_p, C.c_int64, C.c_float, C.c_void_p, C.c_void_p],
+    "relserve_linear_w8a8": [C.c_void_p, C.c_void_p, C.c_void_p, C.c_float, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
+                             C.c_void_p, C.c_void_p, C.c_float, C.c_int32, C.c_void_p],
     "relserve_model_workspace_bytes": [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p],
     "relserve_model_step": [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t,
                             C.c_void_p],
@@ -320,6 +334,57 @@ def relserve_layer_step_static(layer, pbatch, weights: dict, x, y, k_pages, v_pa
     wt = _weights(weights)
     _check(_lib.relserve_layer_step_static(layer.handle, pbatch.handle, C.byref(wt), _ptr(x), _ptr(y),
                                            _cache(k_pages, v_pages), _stream(stream)), "relserve_layer_step_static")
+
+
+def _weights_w8a8(w: dict) -> LayerWeightsW8A8:
+    """w: codes w_* (uint8), row scales s_* (fp32), norm weights (bf16) as device tensors, input scales a_* as numbers."""
+    return LayerWeightsW8A8(*[w[n].data_ptr() for n, t in LayerWeightsW8A8._fields_ if t is C.c_void_p],
+                            *[float(w[n]) for n, t in LayerWeightsW8A8._fields_ if t is C.c_float],
+                            int(bool(w.get("packed", False))))
+
+
+def relserve_layer_step_w8a8(layer, pbatch, weights: dict, x, y, k_pages, v_pages, workspace, stream=None) -> None:
+    wt = _weights_w8a8(weights)
+    _check(_lib.relserve_layer_step_w8a8(layer.handle, pbatch.handle, C.byref(wt), _ptr(x), _ptr(y),
+                                         _cache(k_pages, v_pages), _ptr(workspace),
+                                         workspace.numel() * workspace.element_size(), _stream(stream)),
+           "relserve_layer_step_w8a8")
+
+
+def relserve_rmsnorm_codes(x, w, eps: float, scale: float, out, stream=None) -> None:
+    import torch
+    _check(_lib.relserve_rmsnorm_codes(_ptr(x), int(x.dtype == torch.float32), _ptr(w), float(eps), x.shape[0],
+                                       x.shape[1], float(scale), _ptr(out), _stream(stream)), "relserve_rmsnorm_codes")
+
+
+def relserve_quantise_bf16(values, scale: float, codes, stream=None) -> None:
+    _check(_lib.relserve_quantise_bf16(_ptr(values), values.numel(), float(scale), _ptr(codes), _stream(stream)),
+           "relserve_quantise_bf16")
+
+
+def relserve_linear_w8a8(a, w, w_scale, a_scale: float, epilogue: int, residual, out, out_scale: float = 0.0, n: int = 0,
+                         stream=None) -> None:
+    """a [T, K], w [N, K] uint8 codes (n > 0: w is packed and has n rows), w_scale [N] fp32."""
+    _check(_lib.relserve_linear_w8a8(_ptr(a), _ptr(w), _ptr(w_scale), float(a_scale), a.shape[0], int(n) if n else w.shape[0],
+                                     a.shape[1], int(epilogue), _ptr(residual), _ptr(out), float(out_scale), int(n > 0),
+                                     _stream(stream)), "relserve_linear_w8a8")
+
+
+def pack_codes(w):
+    """An [N, K] uint8 code matrix in the packed layout: relserve_pack_weight on its rows seen as K / 2 two-byte units."""
+    import torch
+    n, k = w.shape
+    packed = torch.empty(relserve_packed_weight_elems(n, k // 2) * 2, dtype=torch.uint8, device=w.device)
+    _check(_lib.relserve_pack_weight(_ptr(w), n, k // 2, _ptr(packed), _stream(None)), "relserve_pack_weight")
+    return packed
+
+
+def pack_layer_weights_w8a8(weights: dict) -> dict:
+    out = dict(weights)
+    for name in MATRIX_NAMES:
+        out[name] = pack_codes(weights[name])
+    out["packed"] = True
+    return out
 
 
 def relserve_static_scratch_bytes() -> int:

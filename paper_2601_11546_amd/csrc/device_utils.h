@@ -9,6 +9,7 @@ namespace relserve {
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
 typedef float f32x16_t __attribute__((ext_vector_type(16)));
+typedef int i32x8_t __attribute__((ext_vector_type(8)));
 typedef float f32x4_t __attribute__((ext_vector_type(4)));
 
 __device__ __forceinline__ float bf16_lo(uint32_t packed) { return __uint_as_float(packed << 16); }
@@ -62,6 +63,12 @@ __device__ __forceinline__ bf16x8_t as_bf16x8(uint4 u) { return __builtin_bit_ca
 // B[8 (l / 32) ..+7][l % 32]; accumulator register r holds D[8 (r / 4) + 4 (l / 32) + r % 4][l % 32].
 __device__ __forceinline__ f32x16_t mfma_32x32x16(bf16x8_t a, bf16x8_t b, f32x16_t c) {
     return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+
+// 32x32x64 product of 8-bit floating point codes (1-4-3 bits, both operands), fp32 accumulate: lane (l32, g) supplies
+// row l32 and 32 of the 64 k values (half g) of each operand.  The scale operands are zero: the unscaled instruction.
+__device__ __forceinline__ f32x16_t mfma_32x32x64_f8(i32x8_t a, i32x8_t b, f32x16_t c) {
+    return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, c, 0, 0, 0, 0, 0, 0);
 }
 
 }  // namespace relserve

@@ -61,6 +61,14 @@ struct GemmArgs {
     // epilogue.
     int32_t tail_tiles, tail_splits;
     float* tail_buf;
+    // quantised projections: a and w hold 8-bit codes (one byte per element; K then counts PAIRS of codes, so that a row
+    // is K * 2 bytes as in the 16-bit case), the sums are scaled by a_scale * w_scale[n], and a SwiGLU output is
+    // stored as codes of value * out_inv
+    int32_t f8;
+    const float* w_scale;
+    float a_scale;
+    int32_t out_f8;
+    float out_inv;
 };
 
 // Test hook (relserve_debug_force_gemm_plan): tile candidate (index into kTiles) and tail splits every launch
@@ -103,12 +111,22 @@ __device__ __forceinline__ void tile_coords(int t, int tiles_m, int tiles_n, int
 // 32 tn + 8 (r / 4) + 4 g + r % 4 of the wave's feature range and token 32 tm + l32 of its token range.
 // TMX of the wave's BM / (32 WGM) rows of accumulator tiles are held in acc, starting at row tm_base (the GEMM kernels
 // hold all of them; the tail finish kernel one per workgroup, which lets several workgroups share a CU).
-template <int BM, int BN, int EPI, int D, int WGM = 2, int WGN = 2, int TMX = BM / (32 * WGM)>
+// SC: the sums are products of 8-bit codes and take the factor a_scale * w_scale[feature] as they are read.
+template <int BM, int BN, int EPI, int D, int WGM = 2, int WGN = 2, int TMX = BM / (32 * WGM), bool SC = false>
 __device__ __forceinline__ void gemm_epilogue(const f32x16_t (&acc)[BN / (32 * WGN)][TMX], const GemmArgs& p,
                                               int tile_m, int tile_n, int wm, int wn, int l32, int g, int tm_base = 0,
                                               int split = 0) {
     constexpr int TM = TMX, TN = BN / (32 * WGN);
     const int t0 = tile_m * BM + 32 * tm_base;
+    // factors of the 4 consecutive features n .. n + 3 (n a multiple of 4 below the feature count)
+    auto scale4 = [&](int n) -> float4 {
+        if constexpr (SC) {
+            const float4 w = *reinterpret_cast<const float4*>(p.w_scale + n);
+            return make_float4(w.x * p.a_scale, w.y * p.a_scale, w.z * p.a_scale, w.w * p.a_scale);
+        } else {
+            return make_float4(1.f, 1.f, 1.f, 1.f);
+        }
+    };
     if (EPI == EPI_SLAB) {
         // Split-K partial sums -> this split's slab.  These tiles were accumulated with the operands
         // swapped: register r holds token 8 (r / 4) + 4 g + r % 4 and feature l32, so one store
@@ -159,11 +177,14 @@ __device__ __forceinline__ void gemm_epilogue(const f32x16_t (&acc)[BN / (32 * W
                             const float4 c01 = *reinterpret_cast<const float4*>(cs + i);
                             const float4 c23 = *reinterpret_cast<const float4*>(cs + i + 2);
                             const float co[4] = {c01.x, c01.z, c23.x, c23.z}, si[4] = {c01.y, c01.w, c23.y, c23.w};
+                            const float4 sa4 = scale4(head * D + i), sb4 = scale4(head * D + i + D / 2);
+                            const float sa[4] = {sa4.x, sa4.y, sa4.z, sa4.w}, sb[4] = {sb4.x, sb4.y, sb4.z, sb4.w};
                             float lo[4], hi[4];
 #pragma unroll
                             for (int j = 0; j < 4; ++j) {
-                                const float a = acc[hh * TPH + tl][tm][4 * q + j];
-                                const float b = acc[hh * TPH + tl + TPH / 2][tm][4 * q + j];
+                                float a = acc[hh * TPH + tl][tm][4 * q + j];
+                                float b = acc[hh * TPH + tl + TPH / 2][tm][4 * q + j];
+                                if constexpr (SC) a *= sa[j], b *= sb[j];
                                 lo[j] = a * co[j] - b * si[j];
                                 hi[j] = a * si[j] + b * co[j];
                             }
@@ -189,7 +210,11 @@ __device__ __forceinline__ void gemm_epilogue(const f32x16_t (&acc)[BN / (32 * W
 #pragma unroll
                         for (int q = 0; q < 4; ++q) {
                             const int i = 32 * tl + 8 * q + 4 * g;
-                            const f32x16_t& a = acc[hh * TPH + tl][tm];
+                            f32x16_t a = acc[hh * TPH + tl][tm];
+                            if constexpr (SC) {
+                                const float4 sv = scale4(head * D + i);
+                                a[4 * q] *= sv.x; a[4 * q + 1] *= sv.y; a[4 * q + 2] *= sv.z; a[4 * q + 3] *= sv.w;
+                            }
                             if (p.kv_fp8) {
                                 const float s = p.v_inv;
                                 *reinterpret_cast<uint32_t*>(reinterpret_cast<uint8_t*>(p.v_pages) + slot * kv_dim +
@@ -212,10 +237,19 @@ __device__ __forceinline__ void gemm_epilogue(const f32x16_t (&acc)[BN / (32 * W
                     const int i = tile_n * (BN / 2) + wn * (BN / (2 * WGN)) + 32 * tn + 8 * q + 4 * g;
                     if (i >= p.n_half) continue;  // n_half is a multiple of 8, i of 4: whole quad in or out
                     float o[4];
+                    const float4 sg4 = scale4(i), su4 = scale4(p.n_half + i);
+                    const float sg[4] = {sg4.x, sg4.y, sg4.z, sg4.w}, su[4] = {su4.x, su4.y, su4.z, su4.w};
 #pragma unroll
                     for (int j = 0; j < 4; ++j) {
-                        const float gate = acc[tn][tm][4 * q + j], up = acc[tn + TN / 2][tm][4 * q + j];
+                        float gate = acc[tn][tm][4 * q + j], up = acc[tn + TN / 2][tm][4 * q + j];
+                        if constexpr (SC) gate *= sg[j], up *= su[j];
                         o[j] = silu_mul(gate, up);
+                    }
+                    if (SC && p.out_f8) {   // the down projection reads codes
+                        const float s = p.out_inv;
+                        *reinterpret_cast<uint32_t*>(static_cast<uint8_t*>(p.out) + (int64_t)t * p.n_half + i) =
+                            pack_fp8x4(o[0] * s, o[1] * s, o[2] * s, o[3] * s);
+                        continue;
                     }
                     uint2 st = make_uint2(pack_bf16x2(o[0], o[1]), pack_bf16x2(o[2], o[3]));
                     *reinterpret_cast<uint2*>(static_cast<uint16_t*>(p.out) + (int64_t)t * p.n_half + i) = st;
@@ -232,6 +266,10 @@ __device__ __forceinline__ void gemm_epilogue(const f32x16_t (&acc)[BN / (32 * W
                     float v[4];
 #pragma unroll
                     for (int j = 0; j < 4; ++j) v[j] = acc[tn][tm][4 * q + j];
+                    if constexpr (SC) {
+                        const float4 sc = scale4(n);
+                        v[0] *= sc.x; v[1] *= sc.y; v[2] *= sc.z; v[3] *= sc.w;
+                    }
                     if (EPI == EPI_RES_BF16_OUT_F32) {
                         uint2 r = make_uint2(0, 0);  // no residual given: plain fp32 output
                         if (p.residual) r = *reinterpret_cast<const uint2*>(static_cast<const uint16_t*>(p.residual) + o);
@@ -401,7 +439,11 @@ __device__ __forceinline__ void dma16(const void* base, uint32_t voff, uint32_t 
 // WGM x WGN = grid of waves over the tile (4 or 8 waves; 8 waves = two per SIMD, each with a quarter
 // of the registers, so that one wave's MFMAs cover the other's memory-instruction issue).
 // WNT: the weights are loaded with the non-temporal hint (launches in which no other workgroup reads them again).
-template <int BM, int BN, int EPI, int D, int BKD, int NS, int WGM = 2, int WGN = 2, bool WNT = false>
+// F8: both operands hold 8-bit codes.  Nothing changes in how bytes travel (K counts pairs of codes, a stage row is
+// still 128 bytes); a k step covers 32 bytes of every row instead of 16, as one 32x32x64 MFMA whose operand is the
+// two adjacent 16-byte chunks (2 ks' + g) * 2, + 1 of the row for k half g (both operands alike, so which codes
+// meet which is fixed), and the epilogue applies the scales.
+template <int BM, int BN, int EPI, int D, int BKD, int NS, int WGM = 2, int WGN = 2, bool WNT = false, bool F8 = false>
 __global__ void __launch_bounds__(64 * WGM * WGN) gemm_dma_kernel(GemmArgs p) {
     constexpr int NW = WGM * WGN;
     constexpr int TM = BM / (32 * WGM), TN = BN / (32 * WGN);
@@ -410,9 +452,10 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_dma_kernel(GemmArgs p) {
     constexpr int RPI = 1024 / ROWB;                     // rows one 1 KB wave load covers
     constexpr int A_IT = BM / (NW * RPI), W_IT = BN / (NW * RPI);
     constexpr int A_BYTES = BM * ROWB, W_BYTES = BN * ROWB, STAGE = A_BYTES + W_BYTES;
-    constexpr int KSTEPS = BKD / 16;
+    constexpr int KSTEPS = F8 ? BKD / 32 : BKD / 16;
     constexpr int LOADS = A_IT + W_IT;                   // wave loads per stage
     static_assert(BKD == 64 || BKD == 32, "stage depth");
+    static_assert(!F8 || BKD == 64, "the fragment double buffer needs an even number of k steps per stage");
     static_assert((NS - 1) * LOADS < 64, "vmcnt field");
     static_assert(EPI != EPI_SWIGLU || TN % 2 == 0, "SwiGLU needs gate and up tiles in one wave");
     static_assert(EPI != EPI_QKV_ROPE || (BN / WGN == 128 && (D == 64 || D == 128)), "a wave must own whole heads");
@@ -516,14 +559,23 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_dma_kernel(GemmArgs p) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[tn][tm][r] = 0.f;
 
-    bf16x8_t wf[2][TN], af[2][TM];
+    using frag_t = std::conditional_t<F8, i32x8_t, bf16x8_t>;
+    frag_t wf[2][TN], af[2][TM];
+    auto read_frag = [&](const unsigned char* row, int ks) __attribute__((always_inline)) -> frag_t {
+        if constexpr (F8) {
+            const uint4 lo = *reinterpret_cast<const uint4*>(row + (((4 * ks + 2 * g) ^ swz) << 4));
+            const uint4 hi = *reinterpret_cast<const uint4*>(row + (((4 * ks + 2 * g + 1) ^ swz) << 4));
+            return i32x8_t{(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, (int)hi.z, (int)hi.w};
+        } else {
+            return as_bf16x8(*reinterpret_cast<const uint4*>(row + (((2 * ks + g) ^ swz) << 4)));
+        }
+    };
     auto load_frags = [&](int buf, int stage, int ks) __attribute__((always_inline)) {
         const unsigned char* st = smem + stage * STAGE;
-        const int ch = ((2 * ks + g) ^ swz) << 4;
 #pragma unroll
-        for (int tn = 0; tn < TN; ++tn) wf[buf][tn] = as_bf16x8(*reinterpret_cast<const uint4*>(st + w_rd[tn] + ch));
+        for (int tn = 0; tn < TN; ++tn) wf[buf][tn] = read_frag(st + w_rd[tn], ks);
 #pragma unroll
-        for (int tm = 0; tm < TM; ++tm) af[buf][tm] = as_bf16x8(*reinterpret_cast<const uint4*>(st + a_rd[tm] + ch));
+        for (int tm = 0; tm < TM; ++tm) af[buf][tm] = read_frag(st + a_rd[tm], ks);
     };
 
     // k range of this workgroup (the whole K unless the launch splits it)
@@ -542,16 +594,19 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_dma_kernel(GemmArgs p) {
     load_frags(0, 0, 0);
     auto mfma_one = [&](int buf, int i) __attribute__((always_inline)) {   // i-th of the TN * TM products of a k step
         const int tn = i / TM, tm = i % TM;
-        acc[tn][tm] = EPI == EPI_SLAB ? mfma_32x32x16(af[buf][tm], wf[buf][tn], acc[tn][tm])
-                                        : mfma_32x32x16(wf[buf][tn], af[buf][tm], acc[tn][tm]);
+        if constexpr (F8)
+            acc[tn][tm] = EPI == EPI_SLAB ? mfma_32x32x64_f8(af[buf][tm], wf[buf][tn], acc[tn][tm])
+                                            : mfma_32x32x64_f8(wf[buf][tn], af[buf][tm], acc[tn][tm]);
+        else
+            acc[tn][tm] = EPI == EPI_SLAB ? mfma_32x32x16(af[buf][tm], wf[buf][tn], acc[tn][tm])
+                                            : mfma_32x32x16(wf[buf][tn], af[buf][tm], acc[tn][tm]);
     };
     auto load_frag_one = [&](int buf, int stage, int ks, int i) __attribute__((always_inline)) {   // i-th of the TN + TM fragment reads of a k step
         const unsigned char* st = smem + stage * STAGE;
-        const int ch = ((2 * ks + g) ^ swz) << 4;
         if (i < TN)
-            wf[buf][i] = as_bf16x8(*reinterpret_cast<const uint4*>(st + w_rd[i] + ch));
+            wf[buf][i] = read_frag(st + w_rd[i], ks);
         else
-            af[buf][i - TN] = as_bf16x8(*reinterpret_cast<const uint4*>(st + a_rd[i - TN] + ch));
+            af[buf][i - TN] = read_frag(st + a_rd[i - TN], ks);
     };
     // Source of the refill in progress (set at a hand-over): the k slice's first byte in both operands and the
     // freed stage's LDS address, so that a load costs its own two instructions plus one scalar add.
@@ -690,13 +745,13 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_dma_kernel(GemmArgs p) {
                 }
         return;
     }
-    gemm_epilogue<BM, BN, EPI, D, WGM, WGN>(acc, p, tile_m, tile_n, wm, wn, l32, g, 0, split);
+    gemm_epilogue<BM, BN, EPI, D, WGM, WGN, BM / (32 * WGM), F8>(acc, p, tile_m, tile_n, wm, wn, l32, g, 0, split);
 }
 
 // Second half of a tail split: workgroup (tail tile, row tm of accumulator tiles) has the thread layout of
 // the GEMM workgroup that wrote the slabs, adds its part of the tile's slabs in split order (so the sum
 // does not depend on scheduling) and runs the GEMM's own epilogue on it.
-template <int BM, int BN, int EPI, int D, int WGM, int WGN>
+template <int BM, int BN, int EPI, int D, int WGM, int WGN, bool SC = false>
 __global__ void __launch_bounds__(64 * WGM * WGN) gemm_tail_finish_kernel(GemmArgs p) {
     constexpr int NW = WGM * WGN, NT = 64 * NW, TM = BM / (32 * WGM), TN = BN / (32 * WGN), AREA4 = BM * BN / 4;
     typedef float vec4_t __attribute__((ext_vector_type(4)));
@@ -726,7 +781,7 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_tail_finish_kernel(GemmAr
 #pragma unroll
                 for (int e = 0; e < 4; ++e) acc[tn][0][4 * c + e] += v[tn][c][e];
     }
-    gemm_epilogue<BM, BN, EPI, D, WGM, WGN, 1>(acc, p, tile_m, tile_n, wm, wn, l32, g, tm_sel);
+    gemm_epilogue<BM, BN, EPI, D, WGM, WGN, 1, SC>(acc, p, tile_m, tile_n, wm, wn, l32, g, tm_sel);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -742,6 +797,15 @@ __device__ __forceinline__ float4 slab_sum(const float* first, int64_t slab_stri
     return v;
 }
 
+// sums of products of 8-bit codes take the factor a_scale * w_scale[n .. n + 3] (w_scale is null for 16-bit operands)
+__device__ __forceinline__ float4 code_scale(float4 v, const GemmArgs& p, int n) {
+    if (p.w_scale) {
+        const float4 w = *reinterpret_cast<const float4*>(p.w_scale + n);
+        v.x *= w.x * p.a_scale; v.y *= w.y * p.a_scale; v.z *= w.z * p.a_scale; v.w *= w.w * p.a_scale;
+    }
+    return v;
+}
+
 template <int EPI, int D>
 __global__ void __launch_bounds__(256) gemm_finish_kernel(GemmArgs p) {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -750,9 +814,14 @@ __global__ void __launch_bounds__(256) gemm_finish_kernel(GemmArgs p) {
         const int q_per_row = p.n_half / 4;
         if (i >= (int64_t)p.T * q_per_row) return;
         const int t = (int)(i / q_per_row), c = (int)(i % q_per_row) * 4;
-        const float4 gt = slab_sum(p.accum + (int64_t)t * p.N + c, stride, p.n_splits);
-        const float4 up = slab_sum(p.accum + (int64_t)t * p.N + p.n_half + c, stride, p.n_splits);
+        const float4 gt = code_scale(slab_sum(p.accum + (int64_t)t * p.N + c, stride, p.n_splits), p, c);
+        const float4 up = code_scale(slab_sum(p.accum + (int64_t)t * p.N + p.n_half + c, stride, p.n_splits), p, p.n_half + c);
         const float o0 = silu_mul(gt.x, up.x), o1 = silu_mul(gt.y, up.y), o2 = silu_mul(gt.z, up.z), o3 = silu_mul(gt.w, up.w);
+        if (p.out_f8) {
+            const float sc = p.out_inv;
+            *reinterpret_cast<uint32_t*>(static_cast<uint8_t*>(p.out) + (int64_t)t * p.n_half + c) = pack_fp8x4(o0 * sc, o1 * sc, o2 * sc, o3 * sc);
+            return;
+        }
         *reinterpret_cast<uint2*>(static_cast<uint16_t*>(p.out) + (int64_t)t * p.n_half + c) =
             make_uint2(pack_bf16x2(o0, o1), pack_bf16x2(o2, o3));
     } else if (EPI == EPI_QKV_ROPE) {
@@ -767,8 +836,8 @@ __global__ void __launch_bounds__(256) gemm_finish_kernel(GemmArgs p) {
         const float* row = p.accum + (int64_t)t * p.N;
         if (u < rot_units) {
             const int head = u / (HALF / 4), i0 = (u % (HALF / 4)) * 4;
-            const float4 lo = slab_sum(row + head * 2 * HALF + i0, stride, p.n_splits);
-            const float4 hi = slab_sum(row + head * 2 * HALF + HALF + i0, stride, p.n_splits);
+            const float4 lo = code_scale(slab_sum(row + head * 2 * HALF + i0, stride, p.n_splits), p, head * 2 * HALF + i0);
+            const float4 hi = code_scale(slab_sum(row + head * 2 * HALF + HALF + i0, stride, p.n_splits), p, head * 2 * HALF + HALF + i0);
             const float2* cs = p.rope_cs + (int64_t)t * HALF + i0;
             const float4 c01 = *reinterpret_cast<const float4*>(cs), c23 = *reinterpret_cast<const float4*>(cs + 2);
             const float a[4] = {lo.x, lo.y, lo.z, lo.w}, b[4] = {hi.x, hi.y, hi.z, hi.w};
@@ -792,7 +861,7 @@ __global__ void __launch_bounds__(256) gemm_finish_kernel(GemmArgs p) {
             *reinterpret_cast<uint2*>(dst + HALF + i0) = make_uint2(pack_bf16x2(h2[0], h2[1]), pack_bf16x2(h2[2], h2[3]));
         } else {
             const int c = (u - rot_units) * 4;
-            const float4 v = slab_sum(row + (p.n_q + p.n_kv) * 2 * HALF + c, stride, p.n_splits);
+            const float4 v = code_scale(slab_sum(row + (p.n_q + p.n_kv) * 2 * HALF + c, stride, p.n_splits), p, (p.n_q + p.n_kv) * 2 * HALF + c);
             if (p.kv_fp8) {
                 const float s = p.v_inv;
                 *reinterpret_cast<uint32_t*>(reinterpret_cast<uint8_t*>(p.v_pages) + slot * kv_dim + c) =
@@ -805,7 +874,7 @@ __global__ void __launch_bounds__(256) gemm_finish_kernel(GemmArgs p) {
         const int q_per_row = p.N / 4;
         if (i >= (int64_t)p.T * q_per_row) return;
         const int64_t o = i * 4;
-        float4 v = slab_sum(p.accum + o, stride, p.n_splits);
+        float4 v = code_scale(slab_sum(p.accum + o, stride, p.n_splits), p, (int)(i % q_per_row) * 4);
         if (EPI == EPI_RES_BF16_OUT_F32) {
             if (p.residual) {
                 const uint2 r = *reinterpret_cast<const uint2*>(static_cast<const uint16_t*>(p.residual) + o);
@@ -831,17 +900,21 @@ hipError_t launch_split(GemmArgs p, int splits, hipStream_t s) {
     constexpr int NS = BM + BN <= 192 ? 6 : BM + BN <= 256 ? 4 : BM + BN <= 320 ? 4 : BM + BN <= 384 ? 3 : 2;
     constexpr int smem = NS * (BM + BN) * 64 * 2;
     static_assert(smem <= 160 * 1024, "ring exceeds the LDS");
-    static std::once_flag once;
-    static hipError_t attr_status = hipSuccess;
-    if (hipError_t e = allow_smem_once(once, attr_status, &gemm_dma_kernel<BM, BN, EPI_SLAB, 0, 64, NS, 2, 2, WNT>, smem)) return e;
     p.tiles_m = (p.T + BM - 1) / BM;
     p.tiles_n = (p.N + BN - 1) / BN;
     const int nk = p.K / 64;
     p.k_per_split = (nk + splits - 1) / splits;
     splits = (nk + p.k_per_split - 1) / p.k_per_split;   // no empty split: the finish kernel reads every slab
     p.n_splits = splits;
-    gemm_dma_kernel<BM, BN, EPI_SLAB, 0, 64, NS, 2, 2, WNT><<<dim3(p.tiles_m * p.tiles_n * splits), dim3(256), smem, s>>>(p);
-    hipError_t e = hipGetLastError();
+    auto go = [&](auto f8) -> hipError_t {
+        constexpr bool F8 = decltype(f8)::value;
+        static std::once_flag once;
+        static hipError_t attr_status = hipSuccess;
+        if (hipError_t e = allow_smem_once(once, attr_status, &gemm_dma_kernel<BM, BN, EPI_SLAB, 0, 64, NS, 2, 2, WNT, F8>, smem)) return e;
+        gemm_dma_kernel<BM, BN, EPI_SLAB, 0, 64, NS, 2, 2, WNT, F8><<<dim3(p.tiles_m * p.tiles_n * splits), dim3(256), smem, s>>>(p);
+        return hipGetLastError();
+    };
+    hipError_t e = p.f8 ? go(std::true_type{}) : go(std::false_type{});
     if (e != hipSuccess) return e;
     int64_t units;
     if (EPI == EPI_SWIGLU)
@@ -872,15 +945,19 @@ hipError_t launch_skinny_whole(GemmArgs p, hipStream_t s) {
     constexpr int NS = BM + BN <= 192 ? 6 : BM + BN <= 256 ? 4 : BM + BN <= 384 ? 3 : 2;
     constexpr int smem = NS * (BM + BN) * BKD * 2;
     static_assert(smem <= 160 * 1024, "ring exceeds the LDS");
-    static std::once_flag once;
-    static hipError_t attr_status = hipSuccess;
-    if (hipError_t e = allow_smem_once(once, attr_status, &gemm_dma_kernel<BM, BN, EPI, D, BKD, NS, 2, 2, WNT>, smem)) return e;
     p.tiles_m = (p.T + BM - 1) / BM;
     p.tiles_n = EPI == EPI_SWIGLU ? (p.n_half + BN / 2 - 1) / (BN / 2) : (p.N + BN - 1) / BN;
     p.tail_tiles = 0;
     p.tail_splits = 1;
-    gemm_dma_kernel<BM, BN, EPI, D, BKD, NS, 2, 2, WNT><<<dim3(p.tiles_m * p.tiles_n), dim3(256), smem, s>>>(p);
-    return hipGetLastError();
+    auto go = [&](auto f8) -> hipError_t {
+        constexpr bool F8 = decltype(f8)::value;
+        static std::once_flag once;
+        static hipError_t attr_status = hipSuccess;
+        if (hipError_t e = allow_smem_once(once, attr_status, &gemm_dma_kernel<BM, BN, EPI, D, BKD, NS, 2, 2, WNT, F8>, smem)) return e;
+        gemm_dma_kernel<BM, BN, EPI, D, BKD, NS, 2, 2, WNT, F8><<<dim3(p.tiles_m * p.tiles_n), dim3(256), smem, s>>>(p);
+        return hipGetLastError();
+    };
+    return p.f8 ? go(std::true_type{}) : go(std::false_type{});
 }
 
 template <int EPI, int D>
@@ -945,36 +1022,43 @@ hipError_t launch_cfg(const GemmArgs& base, hipStream_t s, const Plan& plan = Pl
     // 128 x 256 tiles are one workgroup per CU either way, so they take the third stage that fits (144 KB)
     constexpr int DMA_BK = 64, DMA_NS = (BM == 128 && BN == 256) ? 3 : 2;
     constexpr int dma_smem = DMA_NS * (BM + BN) * DMA_BK * 2;
-    static std::once_flag once_generic, once_dma;
-    static hipError_t st_generic = hipSuccess, st_dma = hipSuccess;
-    if (hipError_t e = allow_smem_once(once_generic, st_generic, &gemm_bf16_kernel<BM, BN, EPI, D>, smem)) return e;
-    if (hipError_t e = allow_smem_once(once_dma, st_dma, &gemm_dma_kernel<BM, BN, EPI, D, DMA_BK, DMA_NS, WGM, WGN>, dma_smem))
-        return e;
     const int tiles = p.tiles_m * p.tiles_n;
-    if (p.K % 64 == 0) {
-        int grid = tiles;
-        if (plan.tail_tiles > 0 && plan.splits > 1 && p.accum && p.T > SKINNY_MAX_T) {
-            const int nk = p.K / 64;
-            p.k_per_split = (nk + plan.splits - 1) / plan.splits;
-            p.tail_splits = (nk + p.k_per_split - 1) / p.k_per_split;   // no empty split
-            p.tail_tiles = std::min(plan.tail_tiles, tiles);
-            p.tail_buf = p.accum;
-            if ((int64_t)p.tail_tiles * p.tail_splits * BM * BN > kTailFloats)
-                return hipErrorInvalidValue;   // a plan that does not fit the scratch: choose_plan never makes one
-            grid = tiles - p.tail_tiles + p.tail_tiles * p.tail_splits;
-        }
-        gemm_dma_kernel<BM, BN, EPI, D, DMA_BK, DMA_NS, WGM, WGN>
+    if (p.K % 64 != 0) {
+        if (p.f8) return hipErrorInvalidValue;   // codes go through the direct-to-LDS kernel only
+        static std::once_flag once_generic;
+        static hipError_t st_generic = hipSuccess;
+        if (hipError_t e = allow_smem_once(once_generic, st_generic, &gemm_bf16_kernel<BM, BN, EPI, D>, smem)) return e;
+        gemm_bf16_kernel<BM, BN, EPI, D><<<dim3(tiles), dim3(256), smem, s>>>(p);
+        return hipGetLastError();
+    }
+    int grid = tiles;
+    if (plan.tail_tiles > 0 && plan.splits > 1 && p.accum && p.T > SKINNY_MAX_T) {
+        const int nk = p.K / 64;
+        p.k_per_split = (nk + plan.splits - 1) / plan.splits;
+        p.tail_splits = (nk + p.k_per_split - 1) / p.k_per_split;   // no empty split
+        p.tail_tiles = std::min(plan.tail_tiles, tiles);
+        p.tail_buf = p.accum;
+        if ((int64_t)p.tail_tiles * p.tail_splits * BM * BN > kTailFloats)
+            return hipErrorInvalidValue;   // a plan that does not fit the scratch: choose_plan never makes one
+        grid = tiles - p.tail_tiles + p.tail_tiles * p.tail_splits;
+    }
+    auto go = [&](auto f8) -> hipError_t {
+        constexpr bool F8 = decltype(f8)::value;
+        static std::once_flag once_dma;
+        static hipError_t st_dma = hipSuccess;
+        if (hipError_t e = allow_smem_once(once_dma, st_dma, &gemm_dma_kernel<BM, BN, EPI, D, DMA_BK, DMA_NS, WGM, WGN, false, F8>, dma_smem))
+            return e;
+        gemm_dma_kernel<BM, BN, EPI, D, DMA_BK, DMA_NS, WGM, WGN, false, F8>
             <<<dim3(grid), dim3(64 * WGM * WGN), dma_smem, s>>>(p);
         if (p.tail_tiles > 0) {
             hipError_t e = hipGetLastError();
             if (e != hipSuccess) return e;
-            gemm_tail_finish_kernel<BM, BN, EPI, D, WGM, WGN>
+            gemm_tail_finish_kernel<BM, BN, EPI, D, WGM, WGN, F8>
                 <<<dim3(p.tail_tiles * (BM / (32 * WGM))), dim3(64 * WGM * WGN), 0, s>>>(p);
         }
-    } else {
-        gemm_bf16_kernel<BM, BN, EPI, D><<<dim3(tiles), dim3(256), smem, s>>>(p);
-    }
-    return hipGetLastError();
+        return hipGetLastError();
+    };
+    return p.f8 ? go(std::true_type{}) : go(std::false_type{});
 }
 
 // Tile choice.  A launch runs ceil(tiles / resident workgroups) rounds; the cost of a round is the
@@ -1082,8 +1166,21 @@ hipError_t launch_pack_weight(const void* w, int32_t N, int32_t K, void* out, hi
 }
 
 
+// 8-bit operands: the kernels see rows of K / 2 two-byte units (same bytes, same layouts) and the scales
+static hipError_t set_codes(GemmArgs& p, const CodeScales* codes) {
+    if (!codes) return hipSuccess;
+    if (p.K % 128 || !codes->w_scale || !(codes->a_scale > 0.0f)) return hipErrorInvalidValue;
+    p.f8 = 1;
+    p.K /= 2;
+    p.w_scale = codes->w_scale;
+    p.a_scale = codes->a_scale;
+    p.out_f8 = codes->out_scale > 0.0f ? 1 : 0;
+    p.out_inv = p.out_f8 ? (float)(1.0 / (double)codes->out_scale) : 0.0f;   // reciprocal in double, rounded once
+    return hipSuccess;
+}
+
 hipError_t launch_linear(const void* a, const void* w, int32_t T, int32_t N, int32_t K, int32_t epilogue,
-                         const void* residual, void* out, hipStream_t s, float* accum, bool w_packed) {
+                         const void* residual, void* out, hipStream_t s, float* accum, bool w_packed, const CodeScales* codes) {
     if (T == 0) return hipSuccess;
     if ((int64_t)T * K >= ((int64_t)1 << 31) || (int64_t)N * K >= ((int64_t)1 << 31)) return hipErrorInvalidValue;
     if (epilogue != EPI_SWIGLU && (N % 4)) return hipErrorInvalidValue;
@@ -1100,6 +1197,8 @@ hipError_t launch_linear(const void* a, const void* w, int32_t T, int32_t N, int
     p.K = K;
     p.n_half = N / 2;
     p.accum = accum;
+    if (hipError_t e = set_codes(p, codes)) return e;
+    K = p.K;
     if (skinny_applies(T, N, K, accum)) {
         switch (epilogue) {
             case EPI_BF16: return launch_skinny<EPI_BF16, 0>(p, s);
@@ -1142,7 +1241,7 @@ hipError_t launch_qkv_d(const GemmArgs& p, hipStream_t s) {
 
 hipError_t launch_qkv_rope_append(const BatchDev& b, const relserve_layer& L, const void* h, const void* w_qkv,
                                   void* q_out, void* k_pages, void* v_pages, hipStream_t s, float* accum,
-                                  bool w_packed, KvFormat kv) {
+                                  bool w_packed, KvFormat kv, const CodeScales* codes) {
     if (b.T == 0) return hipSuccess;
     const int32_t K = L.cfg.hidden;
     if ((int64_t)b.T * K >= ((int64_t)1 << 31) || (int64_t)L.qkv_dim * K >= ((int64_t)1 << 31))
@@ -1166,6 +1265,7 @@ hipError_t launch_qkv_rope_append(const BatchDev& b, const relserve_layer& L, co
     p.k_inv = (float)(1.0 / (double)kv.k_scale);      // reciprocal in double, rounded once
     p.v_inv = (float)(1.0 / (double)kv.v_scale);
     p.accum = accum;
+    if (hipError_t e = set_codes(p, codes)) return e;
     if (skinny_applies(p.T, p.N, p.K, accum))
         return L.cfg.head_dim == 128 ? launch_skinny<EPI_QKV_ROPE, 128>(p, s) : launch_skinny<EPI_QKV_ROPE, 64>(p, s);
     return L.cfg.head_dim == 128 ? launch_qkv_d<128>(p, s) : launch_qkv_d<64>(p, s);

@@ -30,7 +30,7 @@ hipError_t launch_rope_table(const int32_t* tok_pos, const float* inv_freq_dev, 
 template <bool IN_F32>
 __global__ void __launch_bounds__(256) rmsnorm_kernel(const void* __restrict__ xv, const uint16_t* __restrict__ w,
                                                       float eps, int32_t H, uint16_t* __restrict__ out,
-                                                      const int32_t* __restrict__ row_index) {
+                                                      const int32_t* __restrict__ row_index, float code_inv) {
     const int64_t orow = blockIdx.x;
     const int64_t row = row_index ? row_index[orow] : orow;  // optional gather of the input row
     const int tid = threadIdx.x;
@@ -63,6 +63,16 @@ __global__ void __launch_bounds__(256) rmsnorm_kernel(const void* __restrict__ x
         float v[8];
         load8(c, v);
         const uint4 wu = *reinterpret_cast<const uint4*>(w + (int64_t)c * 8);
+        if (code_inv > 0.0f) {   // quantised projections read 8-bit codes of the normed value / scale, taken from fp32
+            const float s = code_inv;
+            uint2 o8;
+            o8.x = pack_fp8x4(v[0] * inv * bf16_lo(wu.x) * s, v[1] * inv * bf16_hi(wu.x) * s, v[2] * inv * bf16_lo(wu.y) * s,
+                              v[3] * inv * bf16_hi(wu.y) * s);
+            o8.y = pack_fp8x4(v[4] * inv * bf16_lo(wu.z) * s, v[5] * inv * bf16_hi(wu.z) * s, v[6] * inv * bf16_lo(wu.w) * s,
+                              v[7] * inv * bf16_hi(wu.w) * s);
+            *reinterpret_cast<uint2*>(reinterpret_cast<uint8_t*>(out) + orow * H + (int64_t)c * 8) = o8;
+            continue;
+        }
         uint4 o;
         o.x = pack_bf16x2(v[0] * inv * bf16_lo(wu.x), v[1] * inv * bf16_hi(wu.x));
         o.y = pack_bf16x2(v[2] * inv * bf16_lo(wu.y), v[3] * inv * bf16_hi(wu.y));
@@ -73,14 +83,36 @@ __global__ void __launch_bounds__(256) rmsnorm_kernel(const void* __restrict__ x
 }
 
 hipError_t launch_rmsnorm(const void* x, bool x_is_f32, const void* w, float eps, int32_t rows, int32_t H,
-                          void* out, hipStream_t s, const int32_t* row_index) {
+                          void* out, hipStream_t s, const int32_t* row_index, float code_scale) {
     if (rows == 0) return hipSuccess;
+    const float code_inv = code_scale > 0.0f ? (float)(1.0 / (double)code_scale) : 0.0f;   // reciprocal in double, rounded once
     if (x_is_f32)
         rmsnorm_kernel<true><<<dim3(rows), dim3(256), 0, s>>>(x, static_cast<const uint16_t*>(w), eps, H,
-                                                              static_cast<uint16_t*>(out), row_index);
+                                                              static_cast<uint16_t*>(out), row_index, code_inv);
     else
         rmsnorm_kernel<false><<<dim3(rows), dim3(256), 0, s>>>(x, static_cast<const uint16_t*>(w), eps, H,
-                                                               static_cast<uint16_t*>(out), row_index);
+                                                               static_cast<uint16_t*>(out), row_index, code_inv);
+    return hipGetLastError();
+}
+
+// ---- bf16 -> 8-bit codes of value / scale (the attention output on its way into a quantised W_o) ------------
+__global__ void __launch_bounds__(256) quantise_bf16_kernel(const uint4* __restrict__ in, int64_t n8, float inv,
+                                                            uint2* __restrict__ codes) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n8) return;
+    const uint4 u = in[i];
+    uint2 o;
+    o.x = pack_fp8x4(bf16_lo(u.x) * inv, bf16_hi(u.x) * inv, bf16_lo(u.y) * inv, bf16_hi(u.y) * inv);
+    o.y = pack_fp8x4(bf16_lo(u.z) * inv, bf16_hi(u.z) * inv, bf16_lo(u.w) * inv, bf16_hi(u.w) * inv);
+    codes[i] = o;
+}
+
+hipError_t launch_quantise_bf16(const void* in, int64_t n, float scale, void* codes, hipStream_t s) {
+    if (n == 0) return hipSuccess;
+    if (n % 8 || !(scale > 0.0f)) return hipErrorInvalidValue;
+    const int64_t n8 = n / 8;
+    quantise_bf16_kernel<<<dim3((unsigned)((n8 + 255) / 256)), dim3(256), 0, s>>>(
+        static_cast<const uint4*>(in), n8, (float)(1.0 / (double)scale), static_cast<uint2*>(codes));
     return hipGetLastError();
 }
 

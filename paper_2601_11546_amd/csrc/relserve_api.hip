@@ -17,8 +17,8 @@ inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
 const char* const kSlotNames[RELSERVE_PROFILE_SLOTS] = {
     "rmsnorm_in", "gemm_qkv_rope_append", "attn_own_keys", "attn_prefix", "attn_tile", "attn_split",
-    "gemm_o",     "rmsnorm_post", "gemm_gate_up", "gemm_down",  "attn_merge", "unused"};
-enum { S_NORM1 = 0, S_QKV, S_ATTN_OWN, S_ATTN_PREFIX, S_ATTN_TILE, S_ATTN_SPLIT, S_O, S_NORM2, S_GU, S_DOWN, S_ATTN_MERGE };
+    "gemm_o",     "rmsnorm_post", "gemm_gate_up", "gemm_down",  "attn_merge", "quantise_attn"};
+enum { S_NORM1 = 0, S_QKV, S_ATTN_OWN, S_ATTN_PREFIX, S_ATTN_TILE, S_ATTN_SPLIT, S_O, S_NORM2, S_GU, S_DOWN, S_ATTN_MERGE, S_QUANT };
 
 struct Workspace {
     char* h;         // [T, H] bf16 (normed activations; reused for the post norm)
@@ -656,6 +656,93 @@ int32_t relserve_layer_step(const relserve_layer* L, const relserve_batch* b, co
         return launch_linear(w.h, wt->w_gate_up, T, 2 * c.mlp_dim, c.hidden, 3, nullptr, w.act, s, accum, packed);
     });
     run(S_DOWN, [&] { return launch_linear(w.act, wt->w_down, T, c.hidden, c.mlp_dim, 2, w.x1, y, s, accum, packed); });
+    return e == hipSuccess ? RELSERVE_OK : RELSERVE_ERR_HIP;
+}
+
+int32_t relserve_layer_step_w8a8(const relserve_layer* L, const relserve_batch* b, const relserve_layer_weights_w8a8* wt,
+                                 const void* x, void* y, relserve_kv_cache cache, void* workspace,
+                                 size_t workspace_bytes, void* stream) {
+    drop_stale_hip_error();
+    if (int32_t rc = check_pair(L, b)) return rc;
+    if (!wt) return RELSERVE_ERR_NULL_POINTER;
+    if (int32_t rc = check_cache(b, cache)) return rc;
+    const relserve_layer_config& c = L->cfg;
+    if (c.hidden % 128 || L->q_dim % 128 || c.mlp_dim % 128) return RELSERVE_ERR_BAD_ARGUMENT;
+    for (float a : {wt->a_qkv, wt->a_o, wt->a_gate_up, wt->a_down})
+        if (!(a > 0.0f) || !std::isfinite(a)) return RELSERVE_ERR_BAD_ARGUMENT;
+    const int32_t T = b->dev.T;
+    if (T == 0) return RELSERVE_OK;
+    if (!x || !y || !wt->w_in_norm || !wt->w_qkv || !wt->w_o || !wt->w_post_norm || !wt->w_gate_up || !wt->w_down ||
+        !wt->s_qkv || !wt->s_o || !wt->s_gate_up || !wt->s_down)
+        return RELSERVE_ERR_NULL_POINTER;
+    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) % kAlign)) return RELSERVE_ERR_WORKSPACE;
+    Workspace w = carve(*L, T, workspace);   // the 16-bit step's buffers hold the codes too (half of each is used)
+    if (w.total > workspace_bytes) return RELSERVE_ERR_WORKSPACE;
+    const bool packed = wt->packed != 0;
+
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    relserve_layer* prof = L->profile ? const_cast<relserve_layer*>(L) : nullptr;
+    hipError_t e = hipSuccess;
+    auto run = [&](int slot, auto&& launch) {
+        if (e != hipSuccess) return;
+        profile_mark(prof, slot, s, true);
+        e = launch();
+        profile_mark(prof, slot, s, false);
+    };
+    float* accum = w.accum;
+    const CodeScales qkv{wt->s_qkv, wt->a_qkv, 0.0f}, o{wt->s_o, wt->a_o, 0.0f}, gu{wt->s_gate_up, wt->a_gate_up, wt->a_down},
+        down{wt->s_down, wt->a_down, 0.0f};
+    run(S_NORM1, [&] { return launch_rmsnorm(x, false, wt->w_in_norm, c.rms_eps, T, c.hidden, w.h, s, nullptr, wt->a_qkv); });
+    run(S_QKV, [&] {
+        return launch_qkv_rope_append(b->dev, *L, w.h, wt->w_qkv, w.q, cache.k_pages, cache.v_pages, s, accum, packed,
+                                      kv_format(cache), &qkv);
+    });
+    if (e == hipSuccess)
+        e = launch_attention(b->dev, *L, w.q, L->q_dim, cache.k_pages, cache.v_pages, w.attn, w.part_o,
+                             w.part_ml, s, prof, kv_format(cache));
+    // the attention output exists as bf16; its codes go where the rotated queries were (read by now)
+    run(S_QUANT, [&] { return launch_quantise_bf16(w.attn, (int64_t)T * L->q_dim, wt->a_o, w.q, s); });
+    run(S_O, [&] { return launch_linear(w.q, wt->w_o, T, c.hidden, L->q_dim, 1, x, w.x1, s, accum, packed, &o); });
+    run(S_NORM2, [&] { return launch_rmsnorm(w.x1, true, wt->w_post_norm, c.rms_eps, T, c.hidden, w.h, s, nullptr, wt->a_gate_up); });
+    run(S_GU, [&] {
+        return launch_linear(w.h, wt->w_gate_up, T, 2 * c.mlp_dim, c.hidden, 3, nullptr, w.act, s, accum, packed, &gu);
+    });
+    run(S_DOWN, [&] { return launch_linear(w.act, wt->w_down, T, c.hidden, c.mlp_dim, 2, w.x1, y, s, accum, packed, &down); });
+    return e == hipSuccess ? RELSERVE_OK : RELSERVE_ERR_HIP;
+}
+
+int32_t relserve_rmsnorm_codes(const void* x, int32_t x_is_f32, const void* w, float eps, int32_t n_rows,
+                               int32_t hidden, float scale, void* out, void* stream) {
+    drop_stale_hip_error();
+    if (n_rows < 0 || hidden <= 0 || hidden % 8 || !(scale > 0.0f) || !std::isfinite(scale)) return RELSERVE_ERR_BAD_ARGUMENT;
+    if (n_rows == 0) return RELSERVE_OK;
+    if (!x || !w || !out) return RELSERVE_ERR_NULL_POINTER;
+    hipError_t e = launch_rmsnorm(x, x_is_f32 != 0, w, eps, n_rows, hidden, out, static_cast<hipStream_t>(stream), nullptr, scale);
+    return e == hipSuccess ? RELSERVE_OK : RELSERVE_ERR_HIP;
+}
+
+int32_t relserve_quantise_bf16(const void* in, int64_t n, float scale, void* codes, void* stream) {
+    drop_stale_hip_error();
+    if (n < 0 || n % 8 || !(scale > 0.0f) || !std::isfinite(scale)) return RELSERVE_ERR_BAD_ARGUMENT;
+    if (n == 0) return RELSERVE_OK;
+    if (!in || !codes) return RELSERVE_ERR_NULL_POINTER;
+    return launch_quantise_bf16(in, n, scale, codes, static_cast<hipStream_t>(stream)) == hipSuccess ? RELSERVE_OK : RELSERVE_ERR_HIP;
+}
+
+int32_t relserve_linear_w8a8(const void* a, const void* w, const float* w_scale, float a_scale, int32_t T, int32_t N,
+                             int32_t K, int32_t epilogue, const void* residual, void* out, float out_scale,
+                             int32_t packed, void* stream) {
+    drop_stale_hip_error();
+    if (T < 0 || N <= 0 || K <= 0 || K % 128 || epilogue < 0 || epilogue > 3) return RELSERVE_ERR_BAD_ARGUMENT;
+    if (epilogue != 3 && N % 4) return RELSERVE_ERR_BAD_ARGUMENT;
+    if (epilogue == 3 && N % 16) return RELSERVE_ERR_BAD_ARGUMENT;
+    if (!(a_scale > 0.0f) || !std::isfinite(a_scale) || out_scale < 0.0f || !std::isfinite(out_scale)) return RELSERVE_ERR_BAD_ARGUMENT;
+    if (out_scale > 0.0f && epilogue != 3) return RELSERVE_ERR_BAD_ARGUMENT;
+    if (T == 0) return RELSERVE_OK;
+    if (!a || !w || !w_scale || !out) return RELSERVE_ERR_NULL_POINTER;
+    if (epilogue == 2 && !residual) return RELSERVE_ERR_NULL_POINTER;
+    const CodeScales codes{w_scale, a_scale, out_scale};
+    hipError_t e = launch_linear(a, w, T, N, K, epilogue, residual, out, static_cast<hipStream_t>(stream), nullptr, packed != 0, &codes);
     return e == hipSuccess ? RELSERVE_OK : RELSERVE_ERR_HIP;
 }
 

@@ -108,8 +108,9 @@ constexpr int ATTN_SPLIT_ROWS = 16;   // query heads per kv head the decode kern
 // ---- kernel launchers (each enqueues on `s` and returns the launch status) ----------------
 hipError_t launch_rope_table(const int32_t* tok_pos, const float* inv_freq_dev, int32_t T, int32_t half,
                              float2* out, hipStream_t s);
+// code_scale > 0: out holds 8-bit codes of the normed value / code_scale instead of bf16
 hipError_t launch_rmsnorm(const void* x, bool x_is_f32, const void* w, float eps, int32_t rows, int32_t H,
-                          void* out, hipStream_t s, const int32_t* row_index = nullptr);
+                          void* out, hipStream_t s, const int32_t* row_index = nullptr, float code_scale = 0.0f);
 hipError_t launch_embedding(const int32_t* ids, const void* table, int32_t vocab, int32_t H, int32_t T, void* out,
                             hipStream_t s);
 hipError_t launch_greedy_sample(const float* logits, int32_t n_rows, int32_t vocab, int32_t* next_token, hipStream_t s);
@@ -122,8 +123,16 @@ hipError_t launch_rope_append(const BatchDev& b, const relserve_layer& L, void* 
 // ones split K over workgroups (partial tiles written there, summed by a second kernel).
 int64_t gemm_scratch_floats(int64_t T, int64_t n_max);
 void gemm_force_plan(int cand, int splits);   // test hook, see relserve_debug_force_gemm_plan
+// Quantised projection: a [T, K] and w [N, K] hold 8-bit codes (K % 128 == 0); the sums take the factor
+// a_scale * w_scale[n]; out_scale > 0 makes a SwiGLU epilogue store codes of value / out_scale.
+struct CodeScales {
+    const float* w_scale = nullptr;   // [N] device
+    float a_scale = 1.0f;
+    float out_scale = 0.0f;
+};
 hipError_t launch_linear(const void* a, const void* w, int32_t T, int32_t N, int32_t K, int32_t epilogue,
-                         const void* residual, void* out, hipStream_t s, float* accum = nullptr, bool w_packed = false);
+                         const void* residual, void* out, hipStream_t s, float* accum = nullptr, bool w_packed = false,
+                         const CodeScales* codes = nullptr);
 // w [N, K] row-major -> the tiled streaming layout (ceil(N / 256) * 256 * K elements), K % 64 == 0
 hipError_t launch_pack_weight(const void* w, int32_t N, int32_t K, void* out, hipStream_t s);
 // q/k/v projection with rotary embedding and KV append fused into the epilogue: q_out [T, n_q d] bf16.
@@ -134,7 +143,9 @@ struct KvFormat {
 };
 hipError_t launch_qkv_rope_append(const BatchDev& b, const relserve_layer& L, const void* h, const void* w_qkv,
                                   void* q_out, void* k_pages, void* v_pages, hipStream_t s, float* accum = nullptr,
-                                  bool w_packed = false, KvFormat kv = KvFormat{});
+                                  bool w_packed = false, KvFormat kv = KvFormat{}, const CodeScales* codes = nullptr);
+// bf16 [n] -> 8-bit codes of value / scale (n % 8 == 0)
+hipError_t launch_quantise_bf16(const void* in, int64_t n, float scale, void* codes, hipStream_t s);
 // Attention passes; part_o [T + split_slot_cap(T), n_q, d] fp32 and part_ml [.., n_q, 2] fp32 hold the prefix partials
 // (rows of the tokens) and the chunk partials of split decode rows (rows T + slot).
 hipError_t launch_attention(const BatchDev& b, const relserve_layer& L, const void* q, int32_t q_pitch,

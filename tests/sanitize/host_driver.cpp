@@ -12,16 +12,17 @@
 
 namespace relserve {
 hipError_t launch_rope_table(const int32_t*, const float*, int32_t, int32_t, float2*, hipStream_t) { return hipSuccess; }
-hipError_t launch_rmsnorm(const void*, bool, const void*, float, int32_t, int32_t, void*, hipStream_t, const int32_t*) { return hipSuccess; }
+hipError_t launch_rmsnorm(const void*, bool, const void*, float, int32_t, int32_t, void*, hipStream_t, const int32_t*, float) { return hipSuccess; }
+hipError_t launch_quantise_bf16(const void*, int64_t, float, void*, hipStream_t) { return hipSuccess; }
 hipError_t launch_embedding(const int32_t*, const void*, int32_t, int32_t, int32_t, void*, hipStream_t) { return hipSuccess; }
 hipError_t launch_greedy_sample(const float*, int32_t, int32_t, int32_t*, hipStream_t) { return hipSuccess; }
 hipError_t launch_kv_append(const BatchDev&, const void*, const void*, void*, void*, int32_t, hipStream_t) { return hipSuccess; }
 hipError_t launch_rope_append(const BatchDev&, const relserve_layer&, void*, void*, void*, hipStream_t) { return hipSuccess; }
 int64_t gemm_scratch_floats(int64_t T, int64_t n_max) { return T <= SKINNY_MAX_T ? (T * n_max > 256 * 128 * 256 ? T * n_max : 256 * 128 * 256) : GEMM_TAIL_FLOATS; }
 void gemm_force_plan(int, int) {}
-hipError_t launch_linear(const void*, const void*, int32_t, int32_t, int32_t, int32_t, const void*, void*, hipStream_t, float*, bool) { return hipSuccess; }
+hipError_t launch_linear(const void*, const void*, int32_t, int32_t, int32_t, int32_t, const void*, void*, hipStream_t, float*, bool, const CodeScales*) { return hipSuccess; }
 hipError_t launch_pack_weight(const void*, int32_t, int32_t, void*, hipStream_t) { return hipSuccess; }
-hipError_t launch_qkv_rope_append(const BatchDev&, const relserve_layer&, const void*, const void*, void*, void*, void*, hipStream_t, float*, bool, KvFormat) { return hipSuccess; }
+hipError_t launch_qkv_rope_append(const BatchDev&, const relserve_layer&, const void*, const void*, void*, void*, void*, hipStream_t, float*, bool, KvFormat, const CodeScales*) { return hipSuccess; }
 hipError_t launch_attention(const BatchDev&, const relserve_layer&, const void*, int32_t, const void*, const void*, void*, float*, float*, hipStream_t, relserve_layer*, KvFormat) { return hipSuccess; }
 hipError_t launch_peak_mfma(float*, int32_t, hipStream_t) { return hipSuccess; }
 hipError_t launch_peak_stream(const void*, int64_t, uint32_t*, hipStream_t) { return hipSuccess; }

@@ -23,7 +23,7 @@ def rs():
 def test_library_exports_every_declared_symbol(rs):
     header = open(os.path.join(ROOT, "include", "relserve.h")).read()
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
-    declared = set(re.findall(r"\b(relserve_[a-z_]+)\s*\(", header))
+    declared = set(re.findall(r"\b(relserve_[a-z0-9_]+)\s*\(", header))
     assert len(declared) >= 18
     lib = C.CDLL(rs.LIB_PATH)
     for name in sorted(declared):

@@ -24,6 +24,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
+PEAK_FP8_TFLOPS = 5000.0    # MI355X dense fp8 MFMA (the quantised-projection variant)
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 
 
@@ -54,9 +55,10 @@ def build_workload(name: str):
     return wl
 
 
-def algorithmic_counts(shape, batch, kv_elem_bytes: int = 2) -> dict:
+def algorithmic_counts(shape, batch, kv_elem_bytes: int = 2, w_elem_bytes: int = 2) -> dict:
     """FLOPs and HBM bytes one step must do/move, counted from the definition (kv_elem_bytes: 2 for the 16-bit
-    cache, 1 for the quantised one)."""
+    cache, 1 for the quantised one; w_elem_bytes: 2 for 16-bit projections, 1 for the quantised ones, whose inputs
+    are one byte per element too)."""
     T, H, I = batch.T, shape.hidden, shape.mlp_dim
     d, nq, nkv = shape.head_dim, shape.n_q_heads, shape.n_kv_heads
     gemm = {"gemm_qkv_rope_append": 2 * T * shape.qkv_dim * H, "gemm_o": 2 * T * H * shape.q_dim,
@@ -74,14 +76,15 @@ def algorithmic_counts(shape, batch, kv_elem_bytes: int = 2) -> dict:
         own = int(batch.ctx_len[r]) - (int(pl[batch.prefix_id[r]]) if batch.prefix_id[r] in grouped else 0)
         own_tokens["decode" if q_len[r] == 1 else "prefill"] += own
     uniq_tokens += own_tokens["decode"] + own_tokens["prefill"]
-    weights = shape.params * 2
+    wb = w_elem_bytes
+    weights = shape.params * wb
     bytes_total = weights + uniq_tokens * kv_tok + 2 * T * H * 2 + T * kv_tok
     qd = nq * d
     # bytes one launch of each GEMM must move: its weights, its input, its output, its residual input
-    gemm_bytes = {"gemm_qkv_rope_append": 2 * (shape.qkv_dim * H + T * H + T * shape.qkv_dim),
-                  "gemm_o": 2 * (H * qd + T * qd + T * H) + 4 * T * H,
-                  "gemm_gate_up": 2 * (2 * I * H + T * H + T * I),
-                  "gemm_down": 2 * (H * I + T * I + T * H) + 4 * T * H}
+    gemm_bytes = {"gemm_qkv_rope_append": wb * (shape.qkv_dim * H + T * H) + 2 * T * shape.qkv_dim,
+                  "gemm_o": wb * (H * qd + T * qd) + 2 * T * H + 4 * T * H,
+                  "gemm_gate_up": wb * (2 * I * H + T * H + T * I),
+                  "gemm_down": wb * (H * I + T * I) + 2 * T * H + 4 * T * H}
     return {"gemm_flops": gemm, "gemm_bytes": gemm_bytes, "attn_flops": attn_flops, "flops_total": sum(gemm.values()) + attn_flops,
             "weight_bytes": weights, "kv_unique_bytes": uniq_tokens * kv_tok, "bytes_total": bytes_total,
             "kv_decode_own_bytes": own_tokens["decode"] * kv_tok, "kv_prefill_own_bytes": own_tokens["prefill"] * kv_tok,
@@ -290,20 +293,22 @@ def _stats(ms: list) -> dict:
             "repeats": len(a)}
 
 
-def measure_layer_step(rs, W, torch, args, wl, host_draws: bool, kv_fp8: bool = False) -> dict:
+def measure_layer_step(rs, W, torch, args, wl, host_draws: bool, kv_fp8: bool = False, w8a8: bool = False) -> dict:
     """Times the layer step of one workload.  host_draws: weights, cache and activations are the seeded host draws the
-    parity tests use (needed for the oracle leg); otherwise they are drawn on the device from the same distributions."""
+    parity tests use (needed for the oracle leg); otherwise they are drawn on the device from the same distributions.
+    w8a8: the quantised-projection variant (8-bit codes of the same weight distribution, one scale per output row)."""
     shape, b = wl.shape, wl.batch
-    counts = algorithmic_counts(shape, b, 1 if kv_fp8 else 2)
+    counts = algorithmic_counts(shape, b, 1 if kv_fp8 else 2, 1 if w8a8 else 2)
     H, I, qd = shape.hidden, shape.mlp_dim, shape.n_q_heads * shape.head_dim
-    assert not (kv_fp8 and host_draws), "the quantised-cache variant is timed on device draws"
+    assert not ((kv_fp8 or w8a8) and host_draws), "the quantised variants are timed on device draws"
+    peak_tflops = PEAK_FP8_TFLOPS if w8a8 else PEAK_BF16_TFLOPS
 
     def dev(bits):
         return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).cuda().view(torch.bfloat16)
 
     # enough sets that the rotating working set exceeds the 256 MB last-level cache several times
     n_sets = args.layer_sets or max(2, min(4, int(np.ceil(2.5e9 / counts["weight_bytes"]))))
-    packed = not args.row_major_weights and all(v % 64 == 0 for v in (H, qd, I))
+    packed = not args.row_major_weights and all(v % (128 if w8a8 else 64) == 0 for v in (H, qd, I))
     weights0 = x_bits = None
     pool = (b.num_pages, shape.page_size, shape.n_kv_heads, shape.head_dim)
     if host_draws:
@@ -330,13 +335,22 @@ def measure_layer_step(rs, W, torch, args, wl, host_draws: bool, kv_fp8: bool = 
                 c = torch.randint(0, 96, pool, generator=g, device="cuda", dtype=torch.uint8)
                 return c | (torch.randint(0, 2, pool, generator=g, device="cuda", dtype=torch.uint8) << 7)
             base = (base[0], codes(), codes())
+        if w8a8:     # each matrix as codes of W[n, :] / s[n], s[n] = the row's largest magnitude / 448
+            q = {"w_in_norm": base[0]["w_in_norm"], "w_post_norm": base[0]["w_post_norm"], **W.W8A8_INPUT_SCALES}
+            for name in ("qkv", "o", "gate_up", "down"):
+                wf = base[0].pop("w_" + name).float()
+                sc = wf.abs().amax(dim=1) / 448.0
+                q["w_" + name] = (wf / sc[:, None]).clamp(-448.0, 448.0).to(torch.float8_e4m3fn).view(torch.uint8)
+                q["s_" + name] = sc.contiguous()
+                del wf
+            base = (q, base[1], base[2])
     # set 0 holds the draws; the other sets are row-rotated device copies of it (same values and
     # distribution at other addresses), which keeps set-up time short
     sets = []
     for i in range(n_sets):
-        wts = base[0] if i == 0 else {k: torch.roll(v, 7 * i, 0) for k, v in base[0].items()}
+        wts = base[0] if i == 0 else {k: (torch.roll(v, 7 * i, 0) if torch.is_tensor(v) else v) for k, v in base[0].items()}
         if packed:   # one-time conversion at model load (relserve_pack_weight); the row-major copy is dropped
-            wts = rs.pack_layer_weights(wts)
+            wts = rs.pack_layer_weights_w8a8(wts) if w8a8 else rs.pack_layer_weights(wts)
         sets.append((wts,
                      base[1] if i == 0 else torch.roll(base[1].view(-1, base[1].shape[-1]), 5 * i, 0).view(base[1].shape).contiguous(),
                      base[2] if i == 0 else torch.roll(base[2].view(-1, base[2].shape[-1]), 5 * i, 0).view(base[2].shape).contiguous()))
@@ -353,9 +367,11 @@ def measure_layer_step(rs, W, torch, args, wl, host_draws: bool, kv_fp8: bool = 
     if kv_fp8:
         sets = [(w, rs.QuantPool(k, 2.0 ** -4), rs.QuantPool(v, 2.0 ** -5)) for w, k, v in sets]
 
+    layer_step = rs.relserve_layer_step_w8a8 if w8a8 else rs.relserve_layer_step
+
     def step(i):
         wts, kd, vd = sets[i % n_sets]
-        rs.relserve_layer_step(layer, pb, wts, x, y, kd, vd, ws)
+        layer_step(layer, pb, wts, x, y, kd, vd, ws)
 
     for i in range(args.warmup):
         step(i)
@@ -407,7 +423,7 @@ def measure_layer_step(rs, W, torch, args, wl, host_draws: bool, kv_fp8: bool = 
         k = {"avg_ms": round(avg_ms, 4), "launches": v["launches"]}
         if name in counts["gemm_flops"]:
             k["tflops"] = round(counts["gemm_flops"][name] / (avg_ms * 1e-3) / 1e12, 1)
-            k["frac_mfma_peak"] = round(k["tflops"] / PEAK_BF16_TFLOPS, 4)
+            k["frac_mfma_peak"] = round(k["tflops"] / peak_tflops, 4)
             k["gbs"] = round(counts["gemm_bytes"][name] / (avg_ms * 1e-3) / 1e9, 1)
             k["frac_hbm_peak"] = round(k["gbs"] / PEAK_HBM_GBS, 4)
         elif kv_bytes.get(name):
@@ -422,13 +438,13 @@ def measure_layer_step(rs, W, torch, args, wl, host_draws: bool, kv_fp8: bool = 
 
     step_tflops = counts["flops_total"] / (ms_step * 1e-3) / 1e12
     step_gbs = counts["bytes_total"] / (ms_step * 1e-3) / 1e9
-    hbm_bound = (counts["bytes_total"] / (PEAK_HBM_GBS * 1e9)) > (counts["flops_total"] / (PEAK_BF16_TFLOPS * 1e12))
+    hbm_bound = (counts["bytes_total"] / (PEAK_HBM_GBS * 1e9)) > (counts["flops_total"] / (peak_tflops * 1e12))
     traffic, traffic_source = None, None
     tpath = os.path.join(ROOT, "profiles", "traffic.json")
     key = wl.extra.get("bench_key")
     traffic_step = None
     if os.path.exists(tpath) and key:
-        recorded = json.load(open(tpath)).get(key + ("_fp8kv" if kv_fp8 else ""), {})
+        recorded = json.load(open(tpath)).get(key + ("_w8a8" if w8a8 else "") + ("_fp8kv" if kv_fp8 else ""), {})
         traffic, traffic_step = recorded.get(dom), recorded.get("whole_step")
         if traffic is not None:
             traffic_source = "recorded: profiles/traffic.json (rocprofv3 --pmc FETCH_SIZE + WRITE_SIZE of an earlier run of this command)"
@@ -441,23 +457,24 @@ def measure_layer_step(rs, W, torch, args, wl, host_draws: bool, kv_fp8: bool = 
                     "whole_step": {"achieved": round(step_gbs, 1), "frac": round(step_gbs / PEAK_HBM_GBS, 4),
                                    "bytes": counts["bytes_total"], "traffic": traffic_step}}
     else:
-        roofline = {"bound": "mfma", "achieved": dk["tflops"], "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+        roofline = {"bound": "mfma", "achieved": dk["tflops"], "peak": peak_tflops, "unit": "TFLOP/s",
                     "frac": dk["frac_mfma_peak"], "traffic": traffic, "traffic_source": traffic_source, "kernel": dom,
                     "flops_per_launch": counts["gemm_flops"][dom], "avg_launch_ms": dk["avg_ms"],
-                    "whole_step": {"achieved": round(step_tflops, 1), "frac": round(step_tflops / PEAK_BF16_TFLOPS, 4),
+                    "whole_step": {"achieved": round(step_tflops, 1), "frac": round(step_tflops / peak_tflops, 4),
                                    "flops": counts["flops_total"], "traffic": traffic_step}}
     line = {
         "metric": "mixed_batch_layer_step_tokens_per_s", "value": round(b.T / (ms_step * 1e-3), 1), "unit": "tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_step, 4),
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": wl.name + ("_fp8kv" if kv_fp8 else ""), "layer": f"H{shape.hidden} q{shape.n_q_heads}/kv{shape.n_kv_heads}x{shape.head_dim} "
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "fp8 (1-4-3) projections, bf16 elsewhere" if w8a8 else "bf16", "data": "synthetic",
+        "config": {"workload": wl.name + ("_w8a8" if w8a8 else "") + ("_fp8kv" if kv_fp8 else ""),
+                   "projections": "8-bit codes, one scale per output row and per input tensor" if w8a8 else "bf16", "layer": f"H{shape.hidden} q{shape.n_q_heads}/kv{shape.n_kv_heads}x{shape.head_dim} "
                    f"I{shape.mlp_dim} P{shape.page_size}", "query_tokens": b.T, "requests": b.num_reqs,
                    "prefill_rows": int((b.q_len > 1).sum()), "decode_rows": int((b.q_len == 1).sum()),
                    "layer_sets_rotated": n_sets, "weight_layout": "packed" if packed else "row-major",
                    "kv_cache": "8-bit codes, one scale per pool" if kv_fp8 else "bf16", "batch_info": pb.info},
         "ms_per_step_stats": stats,
         "roofline": roofline,
-        "step": {"tflops": round(step_tflops, 1), "frac_mfma_peak": round(step_tflops / PEAK_BF16_TFLOPS, 4),
+        "step": {"tflops": round(step_tflops, 1), "frac_mfma_peak": round(step_tflops / peak_tflops, 4),
                  "algorithmic_gbs": round(step_gbs, 1), "frac_hbm_peak": round(step_gbs / PEAK_HBM_GBS, 4),
                  "ms_per_step_without_events": round(float(np.median(plain)), 4),
                  "batch_prepare_ms": round(prepare_ms, 3)},
@@ -495,6 +512,7 @@ def main() -> None:
     ap.add_argument("--stream-patterns", action="store_true",
                     help="instead of the benchmark line: a 4 GiB read of HBM in five access patterns (GB/s each)")
     ap.add_argument("--kv-fp8", action="store_true", help="time the quantised-cache variant (8-bit K/V pools) of the workload")
+    ap.add_argument("--w8a8", action="store_true", help="time the quantised-projection variant (8-bit codes for the four matrices and their inputs)")
     ap.add_argument("--repeats", type=int, default=9, help="how many times the K timed steps are repeated (median, p10, p90)")
     ap.add_argument("--no-regimes", action="store_true",
                     help="headline workload only (by default the line also carries the prefill-only and the decode-only regimes)")
@@ -537,22 +555,24 @@ def main() -> None:
         print(json.dumps(duration_model.run(steps=max(1, min(args.steps, 10)), warmup=max(1, min(args.warmup, 3)))))
         return
     wl = build_workload(args.workload)
-    res = measure_layer_step(rs, W, torch, args, wl, host_draws=not args.kv_fp8, kv_fp8=args.kv_fp8)
+    variant = args.kv_fp8 or args.w8a8
+    res = measure_layer_step(rs, W, torch, args, wl, host_draws=not variant, kv_fp8=args.kv_fp8, w8a8=args.w8a8)
     out = res["line"]
-    if not args.no_regimes and args.workload == "relquery_13b" and not args.kv_fp8:
+    if not args.no_regimes and args.workload == "relquery_13b" and not variant:
         # the two regimes the roofline targets are stated on, each with its own roofline object, and the decode-dominated
         # one on the quantised-cache variant
         out["regimes"] = {}
-        for name, fp8 in (("prefill_only_13b", False), ("decode128_13b", False), ("decode_only_70b", False), ("decode128_13b", True)):
-            r = measure_layer_step(rs, W, torch, args, build_workload(name), host_draws=False, kv_fp8=fp8)["line"]
-            out["regimes"][name + ("_fp8kv" if fp8 else "")] = {"ms_per_step": r["ms_per_step"], "ms_per_step_stats": r["ms_per_step_stats"],
+        for name, fp8, q8 in (("prefill_only_13b", False, False), ("decode128_13b", False, False), ("decode_only_70b", False, False),
+                              ("decode128_13b", True, False), ("prefill_only_13b", False, True), ("decode128_13b", True, True)):
+            r = measure_layer_step(rs, W, torch, args, build_workload(name), host_draws=False, kv_fp8=fp8, w8a8=q8)["line"]
+            out["regimes"][name + ("_w8a8" if q8 else "") + ("_fp8kv" if fp8 else "")] = {"ms_per_step": r["ms_per_step"], "ms_per_step_stats": r["ms_per_step_stats"],
                                     "tokens_per_s": r["value"], "query_tokens": r["config"]["query_tokens"],
                                     "requests": r["config"]["requests"], "layer": r["config"]["layer"],
                                     "data": "synthetic (drawn on the device)", "roofline": r["roofline"], "step": r["step"],
                                     "kernels": r["kernels"]}
     if not args.no_peak_probes:
         out["measured_peaks"] = peak_probes(rs, torch)
-    if not args.no_cpu_baseline and not args.kv_fp8:
+    if not args.no_cpu_baseline and not variant:
         budget = args.cpu_tokens or max(8, int(1.6e11 / (2 * wl.shape.params)))   # about 160 GFLOP of dense work, ~10 s
         out["cpu_baseline"] = cpu_baseline(wl, res["weights0"], res["x_bits"], budget)
         out["cpu_baseline"]["tiny_single_thread"] = cpu_baseline_tiny_single_thread()

@@ -212,6 +212,16 @@ def _step_criterion(got, want, xin, what, sens=None):
     return crel
 
 
+_weights_memo = {}
+
+
+def _weights_13b():
+    """One draw of the quantised 13B layer for all full-size 13B cases (the weights do not depend on the batch)."""
+    if "13b" not in _weights_memo:
+        _weights_memo["13b"] = W.make_weights_w8a8(W.LLAMA_13B, 4242, 40)
+    return _weights_memo["13b"]
+
+
 def _w8a8_step(rs, oracle, shape, wl, weights, reqs=None, max_prefill_rows=None, packed=False, kv_scales=None, eps=None):
     b = wl.batch
     x = W.make_activations(b.T, shape.hidden, wl.seed)
@@ -282,19 +292,20 @@ def test_layer_step_w8a8_skinny_and_mid_size_batches(rs, oracle):
 def test_full_size_w8a8_relquery_13b(rs, oracle):
     wl = W.workload_relquery_13b()
     print(f"[case] w8a8 {wl.name}: T={wl.batch.T}", flush=True)
-    _w8a8_step(rs, oracle, wl.shape, wl, W.make_weights_w8a8(wl.shape, wl.seed, wl.n_layers), reqs=[0, 15, 16, 99, 199], packed=True, eps=1e-3)
+    _w8a8_step(rs, oracle, wl.shape, wl, _weights_13b(), reqs=[0, 15, 16, 99, 199], packed=True, eps=1e-3)
 
 
 def test_full_size_w8a8_decode128_13b(rs, oracle):
     wl = W.workload_decode_plus_chunk_13b(0)
     print(f"[case] w8a8 {wl.name}: T={wl.batch.T}", flush=True)
-    _w8a8_step(rs, oracle, wl.shape, wl, W.make_weights_w8a8(wl.shape, wl.seed, wl.n_layers), reqs=[0, 64, 127], packed=True, eps=1e-3)
+    _w8a8_step(rs, oracle, wl.shape, wl, _weights_13b(), reqs=[0, 64, 127], packed=True, eps=1e-3)
 
 
 def test_full_size_w8a8_prefill_only_13b(rs, oracle):
     wl = W.workload_prefill_only_13b()
     print(f"[case] w8a8 {wl.name}: T={wl.batch.T}", flush=True)
-    _w8a8_step(rs, oracle, wl.shape, wl, W.make_weights_w8a8(wl.shape, wl.seed, wl.n_layers), reqs=[0, 63], max_prefill_rows=24, packed=True, eps=1e-3)
+    _w8a8_step(rs, oracle, wl.shape, wl, _weights_13b(), reqs=[0, 63], max_prefill_rows=24, packed=True, eps=1e-3)
+    _weights_memo.clear()
 
 
 def test_full_size_w8a8_decode_heavy_70b_quantised_cache(rs, oracle):

@@ -29,8 +29,11 @@ def gen_weights(wl) -> dict:
     """wl.weights() (read-only by convention: no test writes into a weight array)."""
     key = (wl.shape, wl.seed, wl.n_layers)
     if key not in _last_weights:
-        _last_weights.clear()
+        while len(_last_weights) >= 3:                      # the three most recent layers (at most ~4 GB)
+            _last_weights.pop(next(iter(_last_weights)))
         _last_weights[key] = wl.weights()
+    else:
+        _last_weights[key] = _last_weights.pop(key)         # most recently used last
     return _last_weights[key]
 
 

@@ -622,15 +622,6 @@ def test_model_step_tiny(rs, oracle, shape):
     _model_case(rs, oracle, shape, W.workload_tiny(shape=shape).batch, 2, 1000, 91, False, "model step tiny")
 
 
-def test_model_step_13b_two_layer_slice(rs, oracle):
-    """Two layers of the 13B-shaped stack with the 32000-entry vocabulary: 128 decode rows of
-    context 1024 plus a 128-token prefill chunk; checked on sampled requests."""
-    wl = W.workload_decode_plus_chunk_13b(128)
-    reqs = [0, 77, 127, 128]
-    print(f"[case] 2-layer 13B model step, requests {reqs} of {wl.batch.num_reqs}", flush=True)
-    _model_case(rs, oracle, wl.shape, wl.batch.select(reqs), 2, 32000, 92, True, "model step 13B x2")
-
-
 # The full batch of the composition sweep (128 decode rows of context 1024 plus one prefill chunk of 0 / 512 / 1024 /
 # 2048 / 4096 tokens) through relserve_model_step on a 2-layer slice of the 13B stack with the 32000-entry
 # vocabulary.  The GPU runs the WHOLE batch (T = 128 ... 4224, logits for all 128 or 129 requests); the oracle
@@ -934,7 +925,7 @@ def _quantised_step(rs, oracle, wl, reqs=None, max_prefill_rows=None, packed=Fal
     """Whole step over 8-bit pools against the oracle's quantised step (sampled requests when reqs is given)."""
     shape, b = wl.shape, wl.batch
     print(f"[case] quantised cache, {wl.name}: T={b.T} reqs={b.num_reqs}", flush=True)
-    weights = wl.weights()
+    weights = gen_weights(wl)
     x = W.make_activations(b.T, shape.hidden, wl.seed)
     k8, v8 = W.make_cache_fp8(shape, b.num_pages, wl.seed)
     gl = GpuLayer(rs, shape, weights, k8, v8, b.T, packed=packed, kv_scales=KV_SCALES)

@@ -449,7 +449,9 @@ def measure_layer_step(rs, W, torch, args, wl, host_draws: bool, kv_fp8: bool = 
         if traffic is not None:
             traffic_source = "recorded: profiles/traffic.json (rocprofv3 --pmc FETCH_SIZE + WRITE_SIZE of an earlier run of this command)"
     dk = kernels[dom]
-    if hbm_bound:      # the dominant kernel against the bytes it must move, and the whole step beside it
+    if hbm_bound or dom not in counts["gemm_flops"]:
+        # the dominant kernel against the bytes it must move, and the whole step beside it (also when an attention kernel
+        # dominates a step whose GEMMs make it matrix-bound as a whole: that kernel's own bound is its K/V stream)
         dom_bytes = counts["gemm_bytes"].get(dom) or kv_bytes.get(dom) or 0
         roofline = {"bound": "hbm", "achieved": round(dom_bytes / (dk["avg_ms"] * 1e-3) / 1e9, 1), "peak": PEAK_HBM_GBS,
                     "unit": "GB/s", "frac": round(dom_bytes / (dk["avg_ms"] * 1e-3) / 1e9 / PEAK_HBM_GBS, 4), "traffic": traffic,

@@ -174,6 +174,30 @@ int main() {
         EXPECT(relserve_batch_validate(&cfg, &e) == RELSERVE_ERR_NULL_POINTER);
     }
 
+    // ---- quantised-projection stages: every argument rule has its status before anything is launched
+    {
+        unsigned char buf[64] = {0};
+        float sc[16] = {1.f};
+        EXPECT(relserve_linear_w8a8(buf, buf, sc, 1.0f, 4, 8, 128, 1, nullptr, buf, 0.0f, 0, nullptr) == RELSERVE_OK);       // stub launcher
+        EXPECT(relserve_linear_w8a8(buf, buf, sc, 1.0f, 4, 8, 192, 1, nullptr, buf, 0.0f, 0, nullptr) == RELSERVE_ERR_BAD_ARGUMENT);
+        EXPECT(relserve_linear_w8a8(buf, buf, sc, 0.0f, 4, 8, 128, 1, nullptr, buf, 0.0f, 0, nullptr) == RELSERVE_ERR_BAD_ARGUMENT);
+        EXPECT(relserve_linear_w8a8(buf, buf, sc, -1.0f, 4, 8, 128, 1, nullptr, buf, 0.0f, 0, nullptr) == RELSERVE_ERR_BAD_ARGUMENT);
+        EXPECT(relserve_linear_w8a8(buf, buf, sc, 1.0f, 4, 8, 128, 1, nullptr, buf, 1.0f, 0, nullptr) == RELSERVE_ERR_BAD_ARGUMENT);   // codes out: SwiGLU only
+        EXPECT(relserve_linear_w8a8(buf, buf, sc, 1.0f, 4, 6, 128, 0, nullptr, buf, 0.0f, 0, nullptr) == RELSERVE_ERR_BAD_ARGUMENT);
+        EXPECT(relserve_linear_w8a8(buf, buf, sc, 1.0f, 4, 24, 128, 3, nullptr, buf, 0.0f, 0, nullptr) == RELSERVE_ERR_BAD_ARGUMENT);
+        EXPECT(relserve_linear_w8a8(buf, buf, nullptr, 1.0f, 4, 8, 128, 1, nullptr, buf, 0.0f, 0, nullptr) == RELSERVE_ERR_NULL_POINTER);
+        EXPECT(relserve_linear_w8a8(buf, buf, sc, 1.0f, 4, 8, 128, 2, nullptr, buf, 0.0f, 0, nullptr) == RELSERVE_ERR_NULL_POINTER);   // fp32 residual missing
+        EXPECT(relserve_linear_w8a8(nullptr, nullptr, nullptr, 1.0f, 0, 8, 128, 1, nullptr, nullptr, 0.0f, 0, nullptr) == RELSERVE_OK);   // no tokens
+        EXPECT(relserve_quantise_bf16(buf, 16, 1.0f, buf, nullptr) == RELSERVE_OK);
+        EXPECT(relserve_quantise_bf16(buf, 12, 1.0f, buf, nullptr) == RELSERVE_ERR_BAD_ARGUMENT);
+        EXPECT(relserve_quantise_bf16(buf, 16, 0.0f, buf, nullptr) == RELSERVE_ERR_BAD_ARGUMENT);
+        EXPECT(relserve_quantise_bf16(nullptr, 16, 1.0f, buf, nullptr) == RELSERVE_ERR_NULL_POINTER);
+        EXPECT(relserve_rmsnorm_codes(buf, 0, buf, 1e-5f, 2, 8, 1.0f, buf, nullptr) == RELSERVE_OK);
+        EXPECT(relserve_rmsnorm_codes(buf, 0, buf, 1e-5f, 2, 12, 1.0f, buf, nullptr) == RELSERVE_ERR_BAD_ARGUMENT);
+        EXPECT(relserve_rmsnorm_codes(buf, 0, buf, 1e-5f, 2, 8, -2.0f, buf, nullptr) == RELSERVE_ERR_BAD_ARGUMENT);
+        EXPECT(relserve_layer_step_w8a8(layer, nullptr, nullptr, buf, buf, relserve_kv_cache{}, buf, 64, nullptr) == RELSERVE_ERR_NULL_POINTER);
+    }
+
     // ---- scheduler arithmetic: random arguments, invalid ones included
     relserve_duration_model mp{2.2e-5, 8.6e-3, 0, 0}, md{4.0e-5, 6.6e-3, 0, 0};
     for (int iter = 0; iter < 3000; ++iter) {

@@ -80,6 +80,34 @@ int main(void) {
         int32_t next_tok[5];
         oracle_greedy_sample(logits, 5, V, next_tok);
         for (int r = 0; r < 5; ++r) EXPECT(next_tok[r] >= 0 && next_tok[r] < V);
+        /* the quantised variants on exactly sized buffers: 8-bit pools, then 8-bit projections over 16-bit and 8-bit pools */
+        {
+            const size_t pool = (size_t)num_pages * P * kvd;
+            uint8_t* k8 = (uint8_t*)malloc(pool);
+            uint8_t* v8 = (uint8_t*)malloc(pool);
+            for (size_t i = 0; i < pool; ++i) k8[i] = (uint8_t)(rnd() % 0x60), v8[i] = (uint8_t)(0x80 | (rnd() % 0x60));
+            EXPECT(oracle_layer_step_fp8kv(&c, &b, &w, x, k8, v8, num_pages, 0.05f, 0.04f, rows, 3, ys, NULL, NULL, NULL) == 0);
+            EXPECT(oracle_layer_step_fp8kv(&c, &b, &w, x, k8, v8, num_pages, 0.0f, 0.04f, rows, 3, ys, NULL, NULL, NULL) == -7);
+            const size_t n_w[4] = {(size_t)(qd + 2 * kvd) * H, (size_t)H * qd, (size_t)2 * I * H, (size_t)H * I};
+            const int n_rows_w[4] = {qd + 2 * kvd, H, 2 * I, H};
+            uint8_t* wc[4];
+            float* sw[4];
+            for (int m = 0; m < 4; ++m) {
+                wc[m] = (uint8_t*)malloc(n_w[m]);
+                sw[m] = (float*)malloc(sizeof(float) * (size_t)n_rows_w[m]);
+                for (size_t i = 0; i < n_w[m]; ++i) wc[m][i] = (uint8_t)((rnd() % 0x70) | ((rnd() & 1) << 7));
+                for (int i = 0; i < n_rows_w[m]; ++i) sw[m][i] = 1e-3f * (1.0f + 0.5f * rnd_unit());
+            }
+            oracle_weights_w8a8 q8 = {w.w_in_norm, wc[0], sw[0], wc[1], sw[1], w.w_post_norm, wc[2], sw[2], wc[3], sw[3],
+                                      0.02f, 0.01f, 0.02f, 0.05f};
+            EXPECT(oracle_layer_step_w8a8(&c, &b, &q8, x, kp, vp, num_pages, 0, 1.0f, 1.0f, NULL, 0, y, yb, attn, x1) == 0);
+            for (int i = 0; i < T * H; ++i) EXPECT(isfinite(y[i]));
+            EXPECT(oracle_layer_step_w8a8(&c, &b, &q8, x, k8, v8, num_pages, 1, 0.05f, 0.04f, rows, 3, ys, NULL, NULL, NULL) == 0);
+            q8.a_o = 0.0f;
+            EXPECT(oracle_layer_step_w8a8(&c, &b, &q8, x, kp, vp, num_pages, 0, 1.0f, 1.0f, rows, 3, ys, NULL, NULL, NULL) == -7);
+            for (int m = 0; m < 4; ++m) { free(wc[m]); free(sw[m]); }
+            free(k8); free(v8);
+        }
         free(bt); free((void*)w.w_in_norm); free((void*)w.w_qkv); free((void*)w.w_o); free((void*)w.w_post_norm);
         free((void*)w.w_gate_up); free((void*)w.w_down); free(x); free(kp); free(vp); free(y); free(yb); free(attn); free(x1);
         free(ys); free(k); free(slots); free(emb); free(head); free(ids); free(kp2); free(vp2); free(logits); free(hidden);

@@ -447,7 +447,7 @@ int32_t oracle_layer_step_w8a8(const oracle_config* c, const oracle_batch* b,
 }
 
 /* Embedding -> n_layers x layer step -> final norm -> output layer on each request's last token */
-int32_t oracle_model_step(const oracle_config* c, const oracle_model* m, const oracle_batch* b,
+static int32_t model_step(const oracle_config* c, const oracle_model* m, const oracle_weights_w8a8* q8, const oracle_batch* b,
                           const int32_t* token_ids, uint16_t* const* k_pages, uint16_t* const* v_pages,
                           int32_t num_pages, float* logits, uint16_t* hidden_out)
 {
@@ -460,7 +460,9 @@ int32_t oracle_model_step(const oracle_config* c, const oracle_model* m, const o
         memcpy(x + (size_t)t * H, m->embedding + (size_t)token_ids[t] * H, sizeof(uint16_t) * (size_t)H);
     }
     for (int32_t l = 0; l < m->n_layers; ++l) {      /* R11: x <- bf16(layer(x)) */
-        int32_t rc = oracle_layer_step(c, b, &m->layers[l], x, k_pages[l], v_pages[l], num_pages,
+        int32_t rc = q8 ? oracle_layer_step_w8a8(c, b, &q8[l], x, (void*)k_pages[l], (void*)v_pages[l], num_pages, 0, 1.0f, 1.0f,
+                                                 NULL, 0, y, /* rounded stream */ x, NULL, NULL)
+                        : oracle_layer_step(c, b, &m->layers[l], x, k_pages[l], v_pages[l], num_pages,
                                        NULL, 0, y, x, NULL, NULL);
         if (rc) { free(x); free(y); return rc; }
     }
@@ -475,6 +477,23 @@ int32_t oracle_model_step(const oracle_config* c, const oracle_model* m, const o
     oracle_linear(m->w_lm_head, m->vocab, H, normed, b->num_reqs, logits);
     free(last); free(normed); free(x); free(y);
     return 0;
+}
+
+int32_t oracle_model_step(const oracle_config* c, const oracle_model* m, const oracle_batch* b,
+                          const int32_t* token_ids, uint16_t* const* k_pages, uint16_t* const* v_pages,
+                          int32_t num_pages, float* logits, uint16_t* hidden_out)
+{
+    return model_step(c, m, NULL, b, token_ids, k_pages, v_pages, num_pages, logits, hidden_out);
+}
+
+/* The stack with quantised projections (R16) in every layer; embedding, final norm and output layer stay 16-bit. */
+int32_t oracle_model_step_w8a8(const oracle_config* c, const oracle_model* m, const oracle_weights_w8a8* layers,
+                               const oracle_batch* b, const int32_t* token_ids,
+                               uint16_t* const* k_pages, uint16_t* const* v_pages,
+                               int32_t num_pages, float* logits, uint16_t* hidden_out)
+{
+    if (!layers) return -2;
+    return model_step(c, m, layers, b, token_ids, k_pages, v_pages, num_pages, logits, hidden_out);
 }
 
 /* Greedy decoding: the next token of a request is the vocabulary entry with the largest logit.

@@ -235,6 +235,13 @@ int32_t oracle_acc_is_f64(void);
 /* Threads the parallel loops (oracle_linear, the per-token attention loop) use. */
 int32_t oracle_num_threads(void);
 
+/* oracle_model_step with the quantised projections of R16 in every layer (layers [m->n_layers]; m->layers is not
+ * read); embedding, final norm and output layer are the 16-bit ones of m; 16-bit cache pools. */
+int32_t oracle_model_step_w8a8(const oracle_config* c, const oracle_model* m, const oracle_weights_w8a8* layers,
+                               const oracle_batch* b, const int32_t* token_ids,
+                               uint16_t* const* k_pages, uint16_t* const* v_pages,
+                               int32_t num_pages, float* logits, uint16_t* hidden_out);
+
 #ifdef __cplusplus
 }
 #endif

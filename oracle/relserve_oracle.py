@@ -121,6 +121,8 @@ class Oracle:
         L.oracle_layer_step_w8a8.restype = C.c_int32
         L.oracle_layer_step_w8a8.argtypes = ([C.c_void_p] * 6 + [C.c_int32, C.c_int32, C.c_float, C.c_float, C.c_void_p, C.c_int32]
                                              + [C.c_void_p] * 4)
+        L.oracle_model_step_w8a8.restype = C.c_int32
+        L.oracle_model_step_w8a8.argtypes = [C.c_void_p] * 7 + [C.c_int32, C.c_void_p, C.c_void_p]
         L.oracle_greedy_sample.restype = None
         L.oracle_greedy_sample.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p]
 
@@ -227,6 +229,15 @@ class Oracle:
         self.lib.oracle_linear_w8a8(_ptr(w_codes), _ptr(s_w), n, k, _ptr(in_codes), float(a_scale), in_codes.shape[0], _ptr(out))
         return out
 
+    @staticmethod
+    def _w8a8_struct(weights: dict):
+        dt = {"w_in_norm": np.uint16, "w_post_norm": np.uint16, "w_qkv": np.uint8, "w_o": np.uint8, "w_gate_up": np.uint8,
+              "w_down": np.uint8, "s_qkv": np.float32, "s_o": np.float32, "s_gate_up": np.float32, "s_down": np.float32}
+        wk = {k: _chk(np.ascontiguousarray(weights[k]), t, k) for k, t in dt.items()}
+        w = _WeightsW8A8(*[_ptr(wk[n]) for n, t in _WeightsW8A8._fields_ if t is C.c_void_p],
+                         *[float(weights[n]) for n, t in _WeightsW8A8._fields_ if t is C.c_float])
+        return w, wk
+
     def layer_step(self, shape, batch, weights: dict, x_bits, k_pages, v_pages, rows=None, kv_scales=None) -> StepResult:
         """One layer step; k_pages / v_pages are updated in place.  kv_scales = (k_scale, v_scale) selects the
         quantised cache: the pools are then uint8 arrays of 8-bit codes.  Weights with a key "s_qkv" select the
@@ -236,11 +247,7 @@ class Oracle:
         b, keep = self._batch(batch)
         w8a8 = "s_qkv" in weights
         if w8a8:
-            dt = {"w_in_norm": np.uint16, "w_post_norm": np.uint16, "w_qkv": np.uint8, "w_o": np.uint8, "w_gate_up": np.uint8,
-                  "w_down": np.uint8, "s_qkv": np.float32, "s_o": np.float32, "s_gate_up": np.float32, "s_down": np.float32}
-            wk = {k: _chk(np.ascontiguousarray(weights[k]), t, k) for k, t in dt.items()}
-            w = _WeightsW8A8(*[_ptr(wk[n]) for n, t in _WeightsW8A8._fields_ if t is C.c_void_p],
-                             *[float(weights[n]) for n, t in _WeightsW8A8._fields_ if t is C.c_float])
+            w, wk = self._w8a8_struct(weights)
         else:
             wk = {k: _chk(np.ascontiguousarray(v), np.uint16, k) for k, v in weights.items()}
             w = _Weights(*[_ptr(wk[n]) for n, _ in _Weights._fields_])
@@ -282,24 +289,32 @@ class Oracle:
         cfg = self._cfg(shape)
         b, keep = self._batch(batch)
         n_layers = len(model["layers"])
-        lw = (_Weights * n_layers)()
+        w8a8 = n_layers > 0 and "s_qkv" in model["layers"][0]     # quantised projections in every layer
+        lw = ((_WeightsW8A8 if w8a8 else _Weights) * n_layers)()
         keep_w = []
         for i, wd in enumerate(model["layers"]):
-            wk = {k: _chk(np.ascontiguousarray(v), np.uint16, k) for k, v in wd.items()}
+            if w8a8:
+                lw[i], wk = self._w8a8_struct(wd)
+            else:
+                wk = {k: _chk(np.ascontiguousarray(v), np.uint16, k) for k, v in wd.items()}
+                lw[i] = _Weights(*[_ptr(wk[n]) for n, _ in _Weights._fields_])
             keep_w.append(wk)
-            lw[i] = _Weights(*[_ptr(wk[n]) for n, _ in _Weights._fields_])
         emb = _chk(np.ascontiguousarray(model["embedding"]), np.uint16, "embedding")
         fin = _chk(np.ascontiguousarray(model["w_final_norm"]), np.uint16, "w_final_norm")
         head = _chk(np.ascontiguousarray(model["w_lm_head"]), np.uint16, "w_lm_head")
-        m = _Model(n_layers, emb.shape[0], _ptr(emb), C.cast(lw, C.c_void_p), _ptr(fin), _ptr(head))
+        m = _Model(n_layers, emb.shape[0], _ptr(emb), None if w8a8 else C.cast(lw, C.c_void_p), _ptr(fin), _ptr(head))
         ids = _chk(np.ascontiguousarray(token_ids, dtype=np.int32), np.int32, "token_ids")
         kp = (C.c_void_p * n_layers)(*[_chk(a, np.uint16, "k_pages").ctypes.data for a in k_pages])
         vp = (C.c_void_p * n_layers)(*[_chk(a, np.uint16, "v_pages").ctypes.data for a in v_pages])
         T = int(batch.q_start[-1])
         logits = np.empty((len(batch.ctx_len), emb.shape[0]), np.float32)
         hidden = np.empty((T, shape.hidden), np.uint16)
-        rc = self.lib.oracle_model_step(C.byref(cfg), C.byref(m), C.byref(b), _ptr(ids), kp, vp,
-                                        k_pages[0].shape[0], _ptr(logits), _ptr(hidden))
+        if w8a8:
+            rc = self.lib.oracle_model_step_w8a8(C.byref(cfg), C.byref(m), C.cast(lw, C.c_void_p), C.byref(b), _ptr(ids), kp, vp,
+                                                 k_pages[0].shape[0], _ptr(logits), _ptr(hidden))
+        else:
+            rc = self.lib.oracle_model_step(C.byref(cfg), C.byref(m), C.byref(b), _ptr(ids), kp, vp,
+                                            k_pages[0].shape[0], _ptr(logits), _ptr(hidden))
         if rc:
             raise ValueError(f"oracle_model_step rc={rc}")
         del keep, keep_w

@@ -254,6 +254,13 @@ def make_model(shape: LayerShape, n_layers: int, vocab: int, seed: int, scaled: 
     return {"embedding": emb, "layers": layers, "w_final_norm": fin, "w_lm_head": head}
 
 
+def make_model_w8a8(shape: LayerShape, n_layers: int, vocab: int, seed: int, scaled: bool = True) -> dict:
+    """make_model with every layer as make_weights_w8a8 (embedding, final norm and output layer stay bf16)."""
+    m = make_model(shape, 0, vocab, seed, scaled)
+    m["layers"] = [make_weights_w8a8(shape, seed + 101 * (i + 1), n_layers if scaled else 0) for i in range(n_layers)]
+    return m
+
+
 def make_token_ids(T: int, vocab: int, seed: int) -> np.ndarray:
     return np.random.default_rng(seed + 4242).integers(0, vocab, T).astype(np.int32)
 

@@ -53,6 +53,7 @@ MUTANTS = [
     ("w8a8_o_input_with_the_qkv_scale", "q8 ? q8->a_o : 0.0f, H, q_dim, attn", "q8 ? q8->a_qkv : 0.0f, H, q_dim, attn"),
     ("w8a8_gate_up_rows_with_the_qkv_row_scales", "q8 ? q8->s_gate_up : NULL", "q8 ? q8->s_qkv : NULL"),
     ("w8a8_cache_inputs_rounded_as_in_the_16_bit_variant", "if (fp8 && !q8)", "if (fp8 || q8)"),
+    ("w8a8_stack_reuses_the_first_layer", "oracle_layer_step_w8a8(c, b, &q8[l], x,", "oracle_layer_step_w8a8(c, b, &q8[0], x,"),
     ("softmax_unnormalised", "out[(size_t)a * d + i] = (float)(o[i] / denom);", "out[(size_t)a * d + i] = (float)(o[i]);"),
 ]
 

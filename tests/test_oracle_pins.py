@@ -751,6 +751,32 @@ def test_layer_step_w8a8_saturates_and_rejects_bad_scales(oracle):
         oracle.layer_step(shape, b, dict(w, a_o=np.float32(0.0)), x, kp.copy(), vp.copy())
 
 
+def test_model_step_w8a8_is_the_composition_of_pinned_pieces(oracle):
+    """The stack with quantised projections == embedding rows -> the (pinned) quantised layer step per layer, its output
+    rounded to bf16 -> 16-bit final norm and output layer on each request's last row.  Exact."""
+    shape = _W8A8_SHAPE
+    n_layers, vocab = 3, 89
+    model = W.make_model_w8a8(shape, n_layers, vocab, seed=84, scaled=False)
+    for l, layer in enumerate(model["layers"]):                 # different input scales per layer: a mixed-up layer shows
+        layer.update({k: np.float32(v * (1.0 + 0.1 * l)) for k, v in _W8A8_SCALES.items()})
+    wl = W.workload_tiny_prefix(shape=shape)
+    b = wl.batch
+    ids = W.make_token_ids(b.T, vocab, 85)
+    pools = [W.make_cache(shape, b.num_pages, 86 + l) for l in range(n_layers)]
+    ks, vs = [k.copy() for k, _ in pools], [v.copy() for _, v in pools]
+    logits, hidden = oracle.model_step(shape, b, model, ids, ks, vs)
+    x = model["embedding"][ids]
+    ks2, vs2 = [k.copy() for k, _ in pools], [v.copy() for _, v in pools]
+    for l in range(n_layers):
+        x = oracle.layer_step(shape, b, model["layers"][l], x, ks2[l], vs2[l]).y_bf16
+    np.testing.assert_array_equal(hidden, x)
+    last = W.bf16_bits_to_f32(x[b.q_start[1:] - 1])
+    np.testing.assert_array_equal(logits, oracle.linear(model["w_lm_head"], oracle.rmsnorm(last, model["w_final_norm"], shape.rms_eps)))
+    for l in range(n_layers):
+        np.testing.assert_array_equal(ks[l], ks2[l])
+        np.testing.assert_array_equal(vs[l], vs2[l])
+
+
 def test_golden_tiny_layer_step_is_stable():
     """The frozen oracle outputs (written by tests/golden/make_golden.py) still hold."""
     import os

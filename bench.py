@@ -220,7 +220,11 @@ def model_step_bench(args, rs, W, torch) -> dict:
     for _ in range(n_layers):
         w = {"w_in_norm": randn(H, std=0.02, mean=1.0), "w_qkv": randn(qkv, H, std=0.02), "w_o": randn(H, qd, std=res_std),
              "w_post_norm": randn(H, std=0.02, mean=1.0), "w_gate_up": randn(2 * I, H, std=0.02), "w_down": randn(H, I, std=res_std)}
-        layers.append(w if args.row_major_weights else rs.pack_layer_weights(w))
+        if args.w8a8:
+            w = quantise_layer_on_device(torch, W, w)
+            layers.append(w if args.row_major_weights else rs.pack_layer_weights_w8a8(w))
+        else:
+            layers.append(w if args.row_major_weights else rs.pack_layer_weights(w))
         caches.append((randn(*pool), randn(*pool)))
     model = {"embedding": randn(vocab, H), "layers": layers, "caches": caches, "w_final_norm": randn(H, std=0.02, mean=1.0),
              "w_lm_head": randn(vocab, H, std=0.02)}
@@ -239,18 +243,20 @@ def model_step_bench(args, rs, W, torch) -> dict:
     torch.cuda.synchronize()
     ms = (time.perf_counter() - t0) / steps * 1e3
     assert bool(torch.isfinite(logits).all())
-    c = algorithmic_counts(shape, b)
+    c = algorithmic_counts(shape, b, 2, 1 if args.w8a8 else 2)
+    peak = PEAK_FP8_TFLOPS if args.w8a8 else PEAK_BF16_TFLOPS
     flops = n_layers * c["flops_total"] + 2 * b.num_reqs * vocab * H
     nbytes = n_layers * c["bytes_total"] + (vocab * H + b.T * H) * 2
     hbm = torch.cuda.max_memory_allocated() / 1e9
     return {"metric": "model_step_tokens_per_s", "value": round(b.T / (ms * 1e-3), 1), "unit": "tokens/s", "n_gpus": 1,
             "steps": steps, "warmup": warm, "ms_per_step": round(ms, 3), "higher_is_better": True, "scaling": "weak",
-            "vs_baseline": None, "dtype": "bf16", "data": "synthetic (drawn on the device)",
-            "config": {"workload": f"model_step_{wl.name}", "layers": n_layers, "vocab": vocab, "query_tokens": b.T,
+            "vs_baseline": None, "dtype": "fp8 (1-4-3) projections, bf16 elsewhere" if args.w8a8 else "bf16",
+            "data": "synthetic (drawn on the device)",
+            "config": {"workload": f"model_step_{wl.name}" + ("_w8a8" if args.w8a8 else ""), "layers": n_layers, "vocab": vocab, "query_tokens": b.T,
                        "requests": b.num_reqs, "weight_layout": "row-major" if args.row_major_weights else "packed",
                        "hbm_allocated_gb": round(hbm, 1)},
             "step": {"ms_per_layer": round(ms / n_layers, 4), "tflops": round(flops / (ms * 1e-3) / 1e12, 1),
-                     "frac_mfma_peak": round(flops / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
+                     "frac_mfma_peak": round(flops / (ms * 1e-3) / 1e12 / peak, 4),
                      "algorithmic_gbs": round(nbytes / (ms * 1e-3) / 1e9, 1),
                      "frac_hbm_peak": round(nbytes / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)}}
 
@@ -284,6 +290,19 @@ def serve_gpu(rs, W) -> dict:
             "trace": "80 relQueries per run, 1-100 requests each, templates 256-1024 tokens, suffixes 30-120, output 5 or 50 tokens",
             "prefix_cache": {"tokens_served_from_cache": worker.cache.hits, "tokens_computed": worker.cache.misses},
             "results": rows}
+
+
+def quantise_layer_on_device(torch, W, w: dict) -> dict:
+    """A layer's four bf16 matrices as 8-bit codes of W[n, :] / s[n], s[n] = the row's largest magnitude / 448 (device
+    tensors; the norm weights stay bf16; static input scales from workloads.W8A8_INPUT_SCALES)."""
+    q = {"w_in_norm": w["w_in_norm"], "w_post_norm": w["w_post_norm"], **W.W8A8_INPUT_SCALES}
+    for name in ("qkv", "o", "gate_up", "down"):
+        wf = w["w_" + name].float()
+        sc = wf.abs().amax(dim=1) / 448.0
+        q["w_" + name] = (wf / sc[:, None]).clamp(-448.0, 448.0).to(torch.float8_e4m3fn).view(torch.uint8)
+        q["s_" + name] = sc.contiguous()
+        del wf
+    return q
 
 
 def _stats(ms: list) -> dict:
@@ -335,15 +354,8 @@ def measure_layer_step(rs, W, torch, args, wl, host_draws: bool, kv_fp8: bool = 
                 c = torch.randint(0, 96, pool, generator=g, device="cuda", dtype=torch.uint8)
                 return c | (torch.randint(0, 2, pool, generator=g, device="cuda", dtype=torch.uint8) << 7)
             base = (base[0], codes(), codes())
-        if w8a8:     # each matrix as codes of W[n, :] / s[n], s[n] = the row's largest magnitude / 448
-            q = {"w_in_norm": base[0]["w_in_norm"], "w_post_norm": base[0]["w_post_norm"], **W.W8A8_INPUT_SCALES}
-            for name in ("qkv", "o", "gate_up", "down"):
-                wf = base[0].pop("w_" + name).float()
-                sc = wf.abs().amax(dim=1) / 448.0
-                q["w_" + name] = (wf / sc[:, None]).clamp(-448.0, 448.0).to(torch.float8_e4m3fn).view(torch.uint8)
-                q["s_" + name] = sc.contiguous()
-                del wf
-            base = (q, base[1], base[2])
+        if w8a8:
+            base = (quantise_layer_on_device(torch, W, base[0]), base[1], base[2])
     # set 0 holds the draws; the other sets are row-rotated device copies of it (same values and
     # distribution at other addresses), which keeps set-up time short
     sets = []

@@ -267,6 +267,14 @@ int32_t relserve_model_step(const relserve_layer* layer, const relserve_batch* b
                             const relserve_model* model, const int32_t* token_ids, void* logits,
                             void* workspace, size_t workspace_bytes, void* stream);
 
+/* relserve_model_step with the quantised projections of relserve_layer_step_w8a8 in every layer: `layers` is a HOST
+ * array of model->n_layers entries (model->layers is not read); the embedding table, the final norm and the output
+ * layer are the 16-bit ones of `model`; caches as in relserve_model_step.  Workspace: relserve_model_workspace_bytes. */
+int32_t relserve_model_step_w8a8(const relserve_layer* layer, const relserve_batch* batch,
+                                 const relserve_model* model, const relserve_layer_weights_w8a8* layers,
+                                 const int32_t* token_ids, void* logits,
+                                 void* workspace, size_t workspace_bytes, void* stream);
+
 /* Greedy decoding after the output layer (Sec. 2.3 "LLM Inference": the output layer's result for a
  * request's last token determines its next token): next_token[r] = the vocabulary entry with the largest
  * logit of row r, the lowest id among equal largest ones; NaN entries never win, a row without any number

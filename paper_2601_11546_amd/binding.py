@@ -38,7 +38,7 @@ EXPORTS = ["relserve_version", "relserve_strerror", "relserve_config_validate", 
            "relserve_duration_fit", "relserve_duration_predict", "relserve_batch_decompose", "relserve_pem_estimate",
            "relserve_aba_decide", "relserve_starved_priority", "relserve_static_priority", "relserve_utok_estimate",
            "relserve_priority_reuse", "relserve_prefill_candidate",
-           "relserve_layer_step_w8a8", "relserve_rmsnorm_codes", "relserve_quantise_bf16", "relserve_linear_w8a8"]
+           "relserve_layer_step_w8a8", "relserve_model_step_w8a8", "relserve_rmsnorm_codes", "relserve_quantise_bf16", "relserve_linear_w8a8"]
 
 
 class RelserveError(RuntimeError):
@@ -146,6 +146,8 @@ for _n, _a in {
     "relserve_model_workspace_bytes": [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p],
     "relserve_model_step": [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t,
                             C.c_void_p],
+    "relserve_model_step_w8a8": [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t,
+                                 C.c_void_p],
     "relserve_greedy_sample": [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p],
     "relserve_rmsnorm": [C.c_void_p, C.c_int32, C.c_void_p, C.c_float, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p],
     "relserve_linear": [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_void_p,
@@ -402,10 +404,19 @@ def relserve_model_workspace_bytes(layer: Layer, max_tokens: int, max_reqs: int)
 
 def relserve_model_step(layer, pbatch, model: dict, token_ids, logits, workspace, stream=None) -> None:
     """model = {"embedding", "layers": [weights dict], "caches": [(k_pages, v_pages)], "w_final_norm", "w_lm_head"}
-    of torch tensors."""
+    of torch tensors.  Layers whose dicts carry row scales ("s_qkv") run with quantised projections."""
     n = len(model["layers"])
-    lw = (LayerWeights * n)(*[_weights(w) for w in model["layers"]])
+    w8a8 = n > 0 and "s_qkv" in model["layers"][0]
     lc = (KVCache * n)(*[_cache(k, v) for k, v in model["caches"]])
+    if w8a8:
+        lw = (LayerWeightsW8A8 * n)(*[_weights_w8a8(w) for w in model["layers"]])
+        m = Model(n, model["embedding"].shape[0], model["embedding"].data_ptr(), None,
+                  C.cast(lc, C.c_void_p), model["w_final_norm"].data_ptr(), model["w_lm_head"].data_ptr())
+        _check(_lib.relserve_model_step_w8a8(layer.handle, pbatch.handle, C.byref(m), C.cast(lw, C.c_void_p), _ptr(token_ids),
+                                             _ptr(logits), _ptr(workspace), workspace.numel() * workspace.element_size(),
+                                             _stream(stream)), "relserve_model_step_w8a8")
+        return
+    lw = (LayerWeights * n)(*[_weights(w) for w in model["layers"]])
     m = Model(n, model["embedding"].shape[0], model["embedding"].data_ptr(), C.cast(lw, C.c_void_p),
               C.cast(lc, C.c_void_p), model["w_final_norm"].data_ptr(), model["w_lm_head"].data_ptr())
     _check(_lib.relserve_model_step(layer.handle, pbatch.handle, C.byref(m), _ptr(token_ids), _ptr(logits),

@@ -770,21 +770,24 @@ int32_t relserve_model_workspace_bytes(const relserve_layer* L, int32_t max_toke
     return RELSERVE_OK;
 }
 
-int32_t relserve_model_step(const relserve_layer* L, const relserve_batch* b, const relserve_model* m,
-                            const int32_t* token_ids, void* logits, void* workspace, size_t workspace_bytes,
-                            void* stream) {
-    drop_stale_hip_error();
+namespace {
+// q8 != nullptr: every layer runs relserve_layer_step_w8a8 on q8[l] instead of relserve_layer_step on m->layers[l]
+int32_t model_step(const relserve_layer* L, const relserve_batch* b, const relserve_model* m,
+                   const relserve_layer_weights_w8a8* q8, const int32_t* token_ids, void* logits, void* workspace,
+                   size_t workspace_bytes, void* stream) {
     if (int32_t rc = check_pair(L, b)) return rc;
     if (!m) return RELSERVE_ERR_NULL_POINTER;
     if (m->n_layers < 0 || m->vocab <= 0 || m->vocab % 4) return RELSERVE_ERR_BAD_ARGUMENT;
     const int32_t T = b->dev.T, B = b->dev.num_reqs, H = L->cfg.hidden;
     if (T == 0) return RELSERVE_OK;
     if (!token_ids || !logits || !m->embedding || !m->w_final_norm || !m->w_lm_head) return RELSERVE_ERR_NULL_POINTER;
-    if (m->n_layers > 0 && (!m->layers || !m->caches)) return RELSERVE_ERR_NULL_POINTER;
+    if (m->n_layers > 0 && ((!q8 && !m->layers) || !m->caches)) return RELSERVE_ERR_NULL_POINTER;
     for (int32_t l = 0; l < m->n_layers; ++l) {
-        const relserve_layer_weights& w = m->layers[l];
-        if (!w.w_in_norm || !w.w_qkv || !w.w_o || !w.w_post_norm || !w.w_gate_up || !w.w_down)
-            return RELSERVE_ERR_NULL_POINTER;
+        if (!q8) {
+            const relserve_layer_weights& w = m->layers[l];
+            if (!w.w_in_norm || !w.w_qkv || !w.w_o || !w.w_post_norm || !w.w_gate_up || !w.w_down)
+                return RELSERVE_ERR_NULL_POINTER;
+        }
         if (int32_t rc = check_cache(b, m->caches[l])) return rc;
     }
     if ((int64_t)m->vocab * H >= ((int64_t)1 << 31)) return RELSERVE_ERR_TOO_LARGE;
@@ -797,14 +800,32 @@ int32_t relserve_model_step(const relserve_layer* L, const relserve_batch* b, co
 
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (launch_embedding(token_ids, m->embedding, m->vocab, H, T, x, s) != hipSuccess) return RELSERVE_ERR_HIP;
-    for (int32_t l = 0; l < m->n_layers; ++l)   // the residual stream stays in x, rounded to bf16 between layers
-        if (int32_t rc = relserve_layer_step(L, b, &m->layers[l], x, x, m->caches[l], workspace, layer_ws, stream))
-            return rc;
+    for (int32_t l = 0; l < m->n_layers; ++l) {   // the residual stream stays in x, rounded to bf16 between layers
+        const int32_t rc = q8 ? relserve_layer_step_w8a8(L, b, &q8[l], x, x, m->caches[l], workspace, layer_ws, stream)
+                              : relserve_layer_step(L, b, &m->layers[l], x, x, m->caches[l], workspace, layer_ws, stream);
+        if (rc) return rc;
+    }
     if (launch_rmsnorm(x, false, m->w_final_norm, L->cfg.rms_eps, B, H, h_last, s, b->dev.last_tok) != hipSuccess)
         return RELSERVE_ERR_HIP;
     if (launch_linear(h_last, m->w_lm_head, B, m->vocab, H, 1, nullptr, logits, s) != hipSuccess)
         return RELSERVE_ERR_HIP;
     return RELSERVE_OK;
+}
+}  // namespace
+
+int32_t relserve_model_step(const relserve_layer* L, const relserve_batch* b, const relserve_model* m,
+                            const int32_t* token_ids, void* logits, void* workspace, size_t workspace_bytes,
+                            void* stream) {
+    drop_stale_hip_error();
+    return model_step(L, b, m, nullptr, token_ids, logits, workspace, workspace_bytes, stream);
+}
+
+int32_t relserve_model_step_w8a8(const relserve_layer* L, const relserve_batch* b, const relserve_model* m,
+                                 const relserve_layer_weights_w8a8* layers, const int32_t* token_ids, void* logits,
+                                 void* workspace, size_t workspace_bytes, void* stream) {
+    drop_stale_hip_error();
+    if (!layers) return RELSERVE_ERR_NULL_POINTER;
+    return model_step(L, b, m, layers, token_ids, logits, workspace, workspace_bytes, stream);
 }
 
 int32_t relserve_greedy_sample(const void* logits, int32_t n_rows, int32_t vocab, int32_t* next_token, void* stream) {

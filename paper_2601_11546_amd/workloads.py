@@ -254,10 +254,11 @@ def make_model(shape: LayerShape, n_layers: int, vocab: int, seed: int, scaled: 
     return {"embedding": emb, "layers": layers, "w_final_norm": fin, "w_lm_head": head}
 
 
-def make_model_w8a8(shape: LayerShape, n_layers: int, vocab: int, seed: int, scaled: bool = True) -> dict:
-    """make_model with every layer as make_weights_w8a8 (embedding, final norm and output layer stay bf16)."""
+def make_model_w8a8(shape: LayerShape, n_layers: int, vocab: int, seed: int, scaled: bool = True, depth: int = 0) -> dict:
+    """make_model with every layer as make_weights_w8a8 (embedding, final norm and output layer stay bf16).  depth: the
+    depth of the stack the n_layers are a slice of (sets the scale of the projections that write the stream)."""
     m = make_model(shape, 0, vocab, seed, scaled)
-    m["layers"] = [make_weights_w8a8(shape, seed + 101 * (i + 1), n_layers if scaled else 0) for i in range(n_layers)]
+    m["layers"] = [make_weights_w8a8(shape, seed + 101 * (i + 1), (depth or n_layers) if scaled else 0) for i in range(n_layers)]
     return m
 
 

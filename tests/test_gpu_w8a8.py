@@ -313,3 +313,74 @@ def test_full_size_w8a8_decode_heavy_70b_quantised_cache(rs, oracle):
     print(f"[case] w8a8 {wl.name}: T={wl.batch.T}", flush=True)
     _w8a8_step(rs, oracle, wl.shape, wl, W.make_weights_w8a8(wl.shape, wl.seed, wl.n_layers), reqs=[0, 64, 130, 255, 256],
                max_prefill_rows=16, packed=True, kv_scales=(0.05, 0.05), eps=2e-3)
+
+
+# ---------------------------------------------------------------------------
+# the layer stack with quantised projections
+# ---------------------------------------------------------------------------
+def _dev_w8a8(w):
+    return {k: (dev_bf16(v) if v.dtype == np.uint16 else _dev(v)) if isinstance(v, np.ndarray) and v.ndim else float(v) for k, v in w.items()}
+
+
+def _w8a8_model_case(rs, oracle, shape, batch, reqs, n_layers, vocab, seed, scaled, what, rel_bound, depth=0):
+    """The GPU runs the whole batch; the oracle recomputes the sampled requests (requests are independent).  Logits are
+    dot products over a stream that crossed n_layers quantised layers on both sides: rel-L2 within rel_bound (the
+    caller's multiple of what one layer's parity allows, times sqrt(n_layers)); the largest deviation within the
+    largest of N values of a deviation of that RMS; the next token equal wherever the oracle's lead exceeds twice the
+    deviation."""
+    model = W.make_model_w8a8(shape, n_layers, vocab, seed, scaled=scaled, depth=depth)
+    ids = W.make_token_ids(batch.T, vocab, seed)
+    caches = [W.make_cache(shape, batch.num_pages, seed + 7 * l) for l in range(n_layers)]
+    gm = {"embedding": dev_bf16(model["embedding"]), "layers": [rs.pack_layer_weights_w8a8(_dev_w8a8(w)) for w in model["layers"]],
+          "caches": [(dev_bf16(k), dev_bf16(v)) for k, v in caches],
+          "w_final_norm": dev_bf16(model["w_final_norm"]), "w_lm_head": dev_bf16(model["w_lm_head"])}
+    layer = rs.relserve_layer_create(shape)
+    pb = rs.relserve_batch_prepare(layer, batch)
+    ws = torch.empty(rs.relserve_model_workspace_bytes(layer, batch.T, batch.num_reqs), dtype=torch.uint8, device="cuda")
+    logits = torch.full((batch.num_reqs, vocab), float("nan"), dtype=torch.float32, device="cuda")
+    rs.relserve_model_step(layer, pb, gm, torch.from_numpy(ids).cuda(), logits, ws)
+    torch.cuda.synchronize()
+    got = logits.cpu().numpy()
+    assert np.isfinite(got).all()
+    sub, rows = (batch, np.arange(batch.T)) if reqs is None else (batch.select(reqs), batch.token_rows(reqs))
+    ks, vs = [k for k, _ in caches], [v for _, v in caches]
+    want, _ = oracle.model_step(shape, sub, model, ids[rows], ks, vs)
+    got = got if reqs is None else got[reqs]
+    g, w = got.astype(np.float64), want.astype(np.float64)
+    rel = float(np.linalg.norm(g - w) / np.linalg.norm(w))
+    err = float(np.abs(g - w).max())
+    rms = float(np.sqrt(np.mean(w * w)))
+    bound = float(np.sqrt(2.0 * np.log(w.size))) * rel_bound * rms
+    top2 = np.sort(w, axis=1)[:, -2:]
+    clear = (top2[:, 1] - top2[:, 0]) > 2 * err
+    print(f"[parity] {what}: logits rel-L2 {rel:.3e} (bound {rel_bound:.1e}), max-abs {err:.3e} (bound {bound:.3e}, RMS {rms:.2f}), "
+          f"{int(clear.sum())} of {len(clear)} next tokens decided", flush=True)
+    assert rel <= rel_bound and err <= bound, (what, rel, err, bound)
+    assert (g.argmax(1)[clear] == w.argmax(1)[clear]).all()
+    # layer 0 appends projections of the same codes on both sides
+    slots = rs.relserve_batch_slots(shape, sub)
+    nkv, d = shape.n_kv_heads, shape.head_dim
+    assert_bf16_neighbours(host_bits(gm["caches"][0][0]).reshape(-1, nkv, d)[slots], ks[0].reshape(-1, nkv, d)[slots],
+                           "layer 0 appended k", min_exact=0.95, slack=0.1)
+
+
+@pytest.mark.parametrize("name", ["mha", "gqa", "d128"])
+def test_model_step_w8a8_tiny(rs, oracle, name):
+    shape = SHAPES[name]
+    # one tiny layer's output agrees to ~2e-3 (its contribution is small next to the stream): 1e-2 over three
+    _w8a8_model_case(rs, oracle, shape, W.workload_tiny_prefix(shape=shape).batch, None, 3, 212, 94, False, f"w8a8 model step tiny_prefix {name}", 1e-2)
+    _w8a8_model_case(rs, oracle, shape, W.workload_tiny(shape=shape).batch, None, 2, 1000, 95, False, f"w8a8 model step tiny {name}", 1e-2)
+
+
+def test_model_step_w8a8_13b_two_layer_slice(rs, oracle):
+    """Two quantised layers out of the 40-layer 13B-shaped stack (the projections that write the stream scaled for that
+    depth, as in the layer tests): 128 decode rows of context 1024 plus a 128-token prefill chunk, on sampled requests.
+    One such layer's output agrees with the oracle to 5-7e-3 (what the oracle itself shows under the perturbation the
+    attention parity allows, see the layer tests).  A deviation eps at the input of the next layer puts a share
+    eps / 0.09 of its codes one step off, hence ~0.09 sqrt(eps / 0.09) = 2.3 % on its contribution, which is a third of
+    the stream: 0.8 % of its output; both together ~1e-2, bound 2.5e-2.  (Stacks of quantised layers amplify: with
+    projections scaled for a depth of 2, i.e. contributions larger than the stream, the same two layers are 5e-2 apart.)"""
+    wl = W.workload_decode_plus_chunk_13b(128)
+    reqs = [0, 127, 128]
+    print(f"[case] w8a8 2-layer 13B model step, requests {reqs} of {wl.batch.num_reqs}", flush=True)
+    _w8a8_model_case(rs, oracle, wl.shape, wl.batch, reqs, 2, 8192, 96, True, "w8a8 model step 13B x2", 2.5e-2, depth=40)

@@ -471,14 +471,25 @@ __device__ __forceinline__ void attn_decode_body(const AttnArgs& p, const AttnIt
             slots[j] = ((int64_t)bt[key >> p.page_shift] << p.page_shift) + (key & p.page_mask);
         }
     };
-    auto issue = [&]() {
+    auto issue_k = [&]() {
 #pragma unroll
         for (int j = 0; j < IT; ++j) {
             const int row = j * RPI + lrow;
             const int64_t off = (slots[j] * p.n_kv + kvh) * D;
             dma16_ptr_nt(p.k_pages + off + ((lslot ^ kswz<D>(row)) << 3), lds0 + j * 1024);
+        }
+    };
+    auto issue_v = [&]() {
+#pragma unroll
+        for (int j = 0; j < IT; ++j) {
+            const int row = j * RPI + lrow;
+            const int64_t off = (slots[j] * p.n_kv + kvh) * D;
             dma16_ptr_nt(p.v_pages + off + ((lslot ^ dvswz<D>(row)) << 3), lds0 + SM::K_BYTES + j * 1024);
         }
+    };
+    auto issue = [&]() {
+        issue_k();
+        issue_v();
     };
     uint2 k_raw[IT], v_raw[IT];   // FP8 only (see attn_tile_body): the block on its way through registers
     auto load_raw = [&]() {
@@ -538,14 +549,22 @@ __device__ __forceinline__ void attn_decode_body(const AttnArgs& p, const AttnIt
 
         // S^T = K Q^T for two 16-key tiles; lane holds keys kb0 + 16 t + 4 gq + r of query row l16
         f32x4_t s[2];
+        bf16x8_t kf[2][KS];
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks)
+                kf[t][ks] = as_bf16x8(*reinterpret_cast<const uint4*>(sk + k_off[ks] + t * 16 * SM::ROWB));
+        if (!FP8) {
+            // the keys are in registers: the next block's keys may overwrite them while the values are still being read
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+            if (b + 1 < n_blocks) issue_k();
+        }
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
             s[t] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks) {
-                const bf16x8_t kf = as_bf16x8(*reinterpret_cast<const uint4*>(sk + k_off[ks] + t * 16 * SM::ROWB));
-                s[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf, qf[ks], s[t], 0, 0, 0);
-            }
+            for (int ks = 0; ks < KS; ++ks) s[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[t][ks], qf[ks], s[t], 0, 0, 0);
         }
         // the block's 32 key rows of V, as the operand of O^T += V^T P^T (rows d = 16 td + l16)
         bf16x8_t vf[TD];
@@ -558,7 +577,7 @@ __device__ __forceinline__ void attn_decode_body(const AttnArgs& p, const AttnIt
         // everything of this block is in registers: the next block may overwrite the buffer
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
         if (!FP8 && b + 1 < n_blocks) {
-            issue();
+            issue_v();
             if (b + 2 < n_blocks) lookup(kb0 + 2 * SM::BLOCK_N);
         }
         const bool need_mask = kb0 + SM::BLOCK_N > klim;

@@ -135,6 +135,29 @@ def test_linear_w8a8_swiglu_epilogue(rs, oracle, T, I, K, packed):
     print(f"[parity] swiglu w8a8 T={T} I={I} K={K}: {exact:.5f} of the codes equal", flush=True)
 
 
+@pytest.mark.parametrize("tile", [0, 1, 2, 3, 4], ids=["256x256", "192x256", "128x256", "128x128", "64x128"])
+def test_linear_w8a8_every_tile_shape(rs, oracle, tile):
+    """Each tile shape's 8-bit instantiation, forced through the test hook, on a ragged problem (plain and SwiGLU)."""
+    rng = np.random.default_rng(40 + tile)
+    T, N, K = 333, 1168, 640
+    a, w = _codes(rng, (T, K), 40), _codes(rng, (N, K), 120)
+    s_w = ((0.5 + rng.random(N)) * 1e-3).astype(np.float32)
+    want = oracle.linear_w8a8(w, s_w, a, 0.03)
+    rms = float(np.sqrt(np.mean(want.astype(np.float64) ** 2)))
+    out = torch.full((T, N), float("nan"), dtype=torch.float32, device="cuda")
+    out16 = torch.zeros((T, N // 2), dtype=torch.bfloat16, device="cuda")
+    rs.relserve_debug_force_gemm_plan(tile, 0)
+    try:
+        rs.relserve_linear_w8a8(_dev(a), rs.pack_codes(_dev(w)), _dev(s_w), 0.03, 1, None, out, n=N)
+        rs.relserve_linear_w8a8(_dev(a), _dev(w), _dev(s_w), 0.03, 3, None, out16)
+        torch.cuda.synchronize()
+    finally:
+        rs.relserve_debug_force_gemm_plan(-1, 0)
+    assert_close(host_f32(out), want, f"tile {tile}", max_abs=5e-4 * rms, rel_l2=1e-4)
+    g, u = want[:, :N // 2].astype(np.float64), want[:, N // 2:].astype(np.float64)
+    assert_bf16_neighbours(host_bits(out16), W.f32_to_bf16_bits((g / (1.0 + np.exp(-g)) * u).astype(np.float32)), f"tile {tile} swiglu", min_exact=0.97)
+
+
 def test_linear_w8a8_refuses_what_it_cannot_serve(rs):
     a = torch.zeros((4, 192), dtype=torch.uint8, device="cuda")
     w = torch.zeros((8, 192), dtype=torch.uint8, device="cuda")

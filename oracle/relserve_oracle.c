@@ -321,7 +321,7 @@ static int32_t layer_step(const oracle_config* c, const oracle_batch* b,
     if (T == 0) { free(tok_req); free(tok_pos); return 0; }
 
     /* widen x */
-    float* xf = (float*)malloc(sizeof(float) * (size_t)T * H);
+    float* xf = (float*)calloc((size_t)T * H, sizeof(float));
     for (size_t i = 0; i < (size_t)T * H; ++i) xf[i] = oracle_bf16_to_f32(x[i]);
 
     /* 1. input norm (R2), 2. q/k/v (Eq. 3) for every token of the batch */

@@ -64,3 +64,51 @@ def test_static_scratch_layer_step_matches_workspace_entry_point(oracle):
     assert e.value.status == -12
     torch.cuda.synchronize()
     assert float(y.float().abs().max()) == 0.0
+
+
+def test_static_scratch_layer_step_replays_from_a_graph():
+    """What the allocation-free entry point is for: the step captured into a HIP graph (kernels only: no allocation, no
+    memset, no host synchronisation) and replayed, with the program's own eager work between the replays; every replay
+    gives the bits of the eager call on the same inputs."""
+    from paper_2601_11546_amd import binding as rs
+    shape = W.LLAMA_13B
+    weights = W.make_weights(shape, 1021, n_layers=40)
+    wd = rs.pack_layer_weights({k: dev_bf16(v) for k, v in weights.items()})
+    b = W.workload_relquery_13b(seed=1022, n_rows=96, n_prefill=2).batch
+    layer = rs.relserve_layer_create(shape)
+    pb = rs.relserve_batch_prepare(layer, b)
+    kp, vp = W.make_cache(shape, b.num_pages, 1023)
+    k0, v0 = dev_bf16(kp), dev_bf16(vp)
+    xs = [dev_bf16(W.make_activations(b.T, shape.hidden, 1024 + i)) for i in range(3)]
+
+    def eager(x):
+        kd, vd, y = k0.clone(), v0.clone(), torch.empty_like(x)
+        rs.relserve_layer_step_static(layer, pb, wd, x, y, kd, vd)
+        torch.cuda.synchronize()
+        return host_bits(y), host_bits(kd)
+    want = [eager(x) for x in xs]            # also the warm-up: kernel attributes and the scratch address are set here
+    # static buffers of the graph
+    x_in, y_out, kd, vd = torch.empty_like(xs[0]), torch.empty_like(xs[0]), k0.clone(), v0.clone()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        x_in.copy_(xs[0])
+        rs.relserve_layer_step_static(layer, pb, wd, x_in, y_out, kd, vd)     # once more on the capture stream, uncaptured
+        torch.cuda.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            rs.relserve_layer_step_static(layer, pb, wd, x_in, y_out, kd, vd)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    for rep in range(2):
+        for i, x in enumerate(xs):
+            kd.copy_(k0)
+            vd.copy_(v0)
+            x_in.copy_(x)
+            y_out.zero_()
+            graph.replay()
+            torch.cuda.synchronize()
+            assert np.array_equal(host_bits(y_out), want[i][0]), (rep, i)
+            assert np.array_equal(host_bits(kd), want[i][1]), (rep, i)
+            eager(xs[(i + 1) % 3])      # eager work on the same scratch array between replays
+    pb.close()

@@ -221,7 +221,8 @@ def model_step_bench(args, rs, W, torch) -> dict:
         w = {"w_in_norm": randn(H, std=0.02, mean=1.0), "w_qkv": randn(qkv, H, std=0.02), "w_o": randn(H, qd, std=res_std),
              "w_post_norm": randn(H, std=0.02, mean=1.0), "w_gate_up": randn(2 * I, H, std=0.02), "w_down": randn(H, I, std=res_std)}
         if args.w8a8:
-            w = quantise_layer_on_device(torch, W, w)
+            from paper_2601_11546_amd import duration_model
+            w = duration_model.quantise_layer_on_device(torch, w)
             layers.append(w if args.row_major_weights else rs.pack_layer_weights_w8a8(w))
         else:
             layers.append(w if args.row_major_weights else rs.pack_layer_weights(w))
@@ -292,19 +293,6 @@ def serve_gpu(rs, W) -> dict:
             "results": rows}
 
 
-def quantise_layer_on_device(torch, W, w: dict) -> dict:
-    """A layer's four bf16 matrices as 8-bit codes of W[n, :] / s[n], s[n] = the row's largest magnitude / 448 (device
-    tensors; the norm weights stay bf16; static input scales from workloads.W8A8_INPUT_SCALES)."""
-    q = {"w_in_norm": w["w_in_norm"], "w_post_norm": w["w_post_norm"], **W.W8A8_INPUT_SCALES}
-    for name in ("qkv", "o", "gate_up", "down"):
-        wf = w["w_" + name].float()
-        sc = wf.abs().amax(dim=1) / 448.0
-        q["w_" + name] = (wf / sc[:, None]).clamp(-448.0, 448.0).to(torch.float8_e4m3fn).view(torch.uint8)
-        q["s_" + name] = sc.contiguous()
-        del wf
-    return q
-
-
 def _stats(ms: list) -> dict:
     a = np.sort(np.asarray(ms, np.float64))
     return {"median": round(float(np.median(a)), 4), "p10": round(float(np.percentile(a, 10)), 4),
@@ -355,7 +343,8 @@ def measure_layer_step(rs, W, torch, args, wl, host_draws: bool, kv_fp8: bool = 
                 return c | (torch.randint(0, 2, pool, generator=g, device="cuda", dtype=torch.uint8) << 7)
             base = (base[0], codes(), codes())
         if w8a8:
-            base = (quantise_layer_on_device(torch, W, base[0]), base[1], base[2])
+            from paper_2601_11546_amd import duration_model
+            base = (duration_model.quantise_layer_on_device(torch, base[0]), base[1], base[2])
     # set 0 holds the draws; the other sets are row-rotated device copies of it (same values and
     # distribution at other addresses), which keeps set-up time short
     sets = []
@@ -566,7 +555,7 @@ def main() -> None:
         return
     if args.duration_model:
         from paper_2601_11546_amd import duration_model
-        print(json.dumps(duration_model.run(steps=max(1, min(args.steps, 10)), warmup=max(1, min(args.warmup, 3)))))
+        print(json.dumps(duration_model.run(steps=max(1, min(args.steps, 10)), warmup=max(1, min(args.warmup, 3)), w8a8=args.w8a8)))
         return
     wl = build_workload(args.workload)
     variant = args.kv_fp8 or args.w8a8

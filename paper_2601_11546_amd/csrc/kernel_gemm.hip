@@ -1044,17 +1044,22 @@ hipError_t launch_cfg(const GemmArgs& base, hipStream_t s, const Plan& plan = Pl
     }
     auto go = [&](auto f8) -> hipError_t {
         constexpr bool F8 = decltype(f8)::value;
+        // 8-bit operands on the largest tile: eight waves (two per SIMD, each with half the registers), so that one
+        // wave's MFMAs cover the other's waits for its loads.  That kernel is bound by load latency (matrix pipes 58 %
+        // busy with four waves); the 16-bit one is bound by the power limit and loses with eight waves (measured both).
+        constexpr int GM = (F8 && BM == 256 && BN == 256) ? 4 : WGM;
+        constexpr int GN = WGN;
         static std::once_flag once_dma;
         static hipError_t st_dma = hipSuccess;
-        if (hipError_t e = allow_smem_once(once_dma, st_dma, &gemm_dma_kernel<BM, BN, EPI, D, DMA_BK, DMA_NS, WGM, WGN, false, F8>, dma_smem))
+        if (hipError_t e = allow_smem_once(once_dma, st_dma, &gemm_dma_kernel<BM, BN, EPI, D, DMA_BK, DMA_NS, GM, GN, false, F8>, dma_smem))
             return e;
-        gemm_dma_kernel<BM, BN, EPI, D, DMA_BK, DMA_NS, WGM, WGN, false, F8>
-            <<<dim3(grid), dim3(64 * WGM * WGN), dma_smem, s>>>(p);
+        gemm_dma_kernel<BM, BN, EPI, D, DMA_BK, DMA_NS, GM, GN, false, F8>
+            <<<dim3(grid), dim3(64 * GM * GN), dma_smem, s>>>(p);
         if (p.tail_tiles > 0) {
             hipError_t e = hipGetLastError();
             if (e != hipSuccess) return e;
-            gemm_tail_finish_kernel<BM, BN, EPI, D, WGM, WGN, F8>
-                <<<dim3(p.tail_tiles * (BM / (32 * WGM))), dim3(64 * WGM * WGN), 0, s>>>(p);
+            gemm_tail_finish_kernel<BM, BN, EPI, D, GM, GN, F8>
+                <<<dim3(p.tail_tiles * (BM / (32 * GM))), dim3(64 * GM * GN), 0, s>>>(p);
         }
         return hipGetLastError();
     };

@@ -953,8 +953,9 @@ hipError_t launch_skinny_whole(GemmArgs p, hipStream_t s) {
         constexpr bool F8 = decltype(f8)::value;
         static std::once_flag once;
         static hipError_t attr_status = hipSuccess;
-        if (hipError_t e = allow_smem_once(once, attr_status, &gemm_dma_kernel<BM, BN, EPI, D, BKD, NS, 2, 2, WNT, F8>, smem)) return e;
-        gemm_dma_kernel<BM, BN, EPI, D, BKD, NS, 2, 2, WNT, F8><<<dim3(p.tiles_m * p.tiles_n), dim3(256), smem, s>>>(p);
+        constexpr int GM = (F8 && BM == 256 && BN == 256) ? 4 : 2;   // eight waves for the largest 8-bit tile, as in launch_cfg
+        if (hipError_t e = allow_smem_once(once, attr_status, &gemm_dma_kernel<BM, BN, EPI, D, BKD, NS, GM, 2, WNT, F8>, smem)) return e;
+        gemm_dma_kernel<BM, BN, EPI, D, BKD, NS, GM, 2, WNT, F8><<<dim3(p.tiles_m * p.tiles_n), dim3(64 * GM * 2), smem, s>>>(p);
         return hipGetLastError();
     };
     return p.f8 ? go(std::true_type{}) : go(std::false_type{});

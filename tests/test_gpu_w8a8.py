@@ -407,3 +407,21 @@ def test_model_step_w8a8_13b_two_layer_slice(rs, oracle):
     reqs = [0, 127, 128]
     print(f"[case] w8a8 2-layer 13B model step, requests {reqs} of {wl.batch.num_reqs}", flush=True)
     _w8a8_model_case(rs, oracle, wl.shape, wl.batch, reqs, 2, 8192, 96, True, "w8a8 model step 13B x2", 2.5e-2, depth=40)
+
+
+def test_layer_step_w8a8_is_bitwise_repeatable(rs):
+    """The quantised step has no atomics and no arrival-order sums either: two runs give the same bits, output and cache."""
+    wl = W.workload_relquery_13b()
+    shape, b = wl.shape, wl.batch
+    weights = _weights_13b()
+    x = W.make_activations(b.T, shape.hidden, wl.seed)
+    outs = []
+    for _ in range(2):
+        kp, vp = gen_cache(shape, b.num_pages, wl.seed)
+        gl = GpuLayer(rs, shape, weights, kp, vp, b.T, packed=True)
+        y = host_bits(gl.step(b, x))
+        outs.append((y, host_bits(gl.k_pages), host_bits(gl.v_pages)))
+        del gl
+    _weights_memo.clear()
+    for a, c in zip(outs[0], outs[1]):
+        assert np.array_equal(a, c)

@@ -777,6 +777,25 @@ def test_model_step_w8a8_is_the_composition_of_pinned_pieces(oracle):
         np.testing.assert_array_equal(vs[l], vs2[l])
 
 
+def test_layer_step_w8a8_keeps_the_memoisation_invariant(oracle):
+    """Static scales quantise every token by itself, so the cache stays a pure memo (Sec. 2.3 "KV Cache") under the
+    quantised projections too: a prompt processed token by token, in two chunks or in one pass gives the same outputs
+    and the same cache, exactly."""
+    shape = _W8A8_SHAPE
+    w = _w8a8_weights(88)
+    L = 29
+    outs = []
+    for sched in ([[(0, L)]], [[(0, 1)] for _ in range(L)], [[(0, 13)], [(0, 16)]]):
+        flow = make_flow(shape, [L], sched, seed=89)
+        kp, vp = W.make_cache(shape, flow.num_pages, 90)
+        ys = run_flow(flow, lambda bb, xx: oracle.layer_step(shape, bb, w, xx, kp, vp).y_f32)
+        outs.append((ys[0], kp, vp))
+    for y, kp, vp in outs[1:]:
+        np.testing.assert_array_equal(y, outs[0][0])
+        np.testing.assert_array_equal(kp, outs[0][1])
+        np.testing.assert_array_equal(vp, outs[0][2])
+
+
 def test_golden_tiny_layer_step_is_stable():
     """The frozen oracle outputs (written by tests/golden/make_golden.py) still hold."""
     import os

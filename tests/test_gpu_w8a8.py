@@ -425,3 +425,24 @@ def test_layer_step_w8a8_is_bitwise_repeatable(rs):
     _weights_memo.clear()
     for a, c in zip(outs[0], outs[1]):
         assert np.array_equal(a, c)
+
+
+@pytest.mark.parametrize("name", ["mha", "gqa"])
+def test_multi_step_flow_w8a8_matches_oracle(rs, oracle, name):
+    """Chunked prefill, a shared prefix written by one request and read by others, then decode steps, all with quantised
+    projections: every step's output against the oracle run on its own cache (each side reads the keys it wrote itself)."""
+    shape = SHAPES[name]
+    P = shape.page_size
+    pl = 2 * P
+    seq = [pl + 70, pl + 9, pl + 40, 150]
+    sched = [[(0, pl + 30), (3, 100)], [(0, 40), (1, 8), (2, 40), (3, 49)], [(1, 1), (3, 1)]]
+    from tests.flows import make_flow, run_flow
+    flow = make_flow(shape, seq, sched, seed=64, shared_prefix=(pl, [0, 1, 2]), start=[0, pl, pl, 0])
+    weights = W.make_weights_w8a8(shape, 65)
+    kp, vp = W.make_cache(shape, flow.num_pages, 66)
+    gl = GpuLayer(rs, shape, weights, kp, vp, 256)
+    ys_gpu = run_flow(flow, lambda b, x: host_f32(gl.step(b, x)))
+    ys_ora = run_flow(flow, lambda b, x: oracle.layer_step(shape, b, weights, x, kp, vp).y_f32)
+    for r in range(len(seq)):
+        lo = flow.start[r]
+        assert_close(ys_gpu[r][lo:], ys_ora[r][lo:], f"w8a8 flow request {r}")

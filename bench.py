@@ -262,15 +262,15 @@ def model_step_bench(args, rs, W, torch) -> dict:
                      "frac_hbm_peak": round(nbytes / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)}}
 
 
-def serve_gpu(rs, W) -> dict:
+def serve_gpu(rs, W, w8a8: bool = False) -> dict:
     """The scheduler loop with its batches executed on the GPU (Sec. 4.1): FCFS against the RelServe policy."""
     from paper_2601_11546_amd import duration_model, scheduler, serving
     layers, vocab = 4, 32000
-    fit = duration_model.run(n_prefill=32, decode_sizes=(1, 16, 32, 64, 96, 128, 160, 192, 224, 256), steps=3, warmup=1)
+    fit = duration_model.run(n_prefill=32, decode_sizes=(1, 16, 32, 64, 96, 128, 160, 192, 224, 256), steps=3, warmup=1, w8a8=w8a8)
     mp = {k: fit["prefill"]["uncached_tokens"][k] * layers for k in ("alpha", "beta")}     # what the policy predicts with
     md = {k: fit["decode"]["requests"][k] * layers for k in ("alpha", "beta")}
     lim = scheduler.Limits(cap=65536, max_num_seqs=256, max_num_batched_tokens=8192)
-    worker = serving.GpuWorker(W.LLAMA_13B, layers, vocab, num_pages=6144, max_tokens=8192 + 1200, max_reqs=256, seed=5)
+    worker = serving.GpuWorker(W.LLAMA_13B, layers, vocab, num_pages=6144, max_tokens=8192 + 1200, max_reqs=256, seed=5, w8a8=w8a8)
     rows = []
     for rate in (20.0, 40.0, 60.0, 80.0):
         trace = scheduler.poisson_trace(80, rate, seed=int(rate))
@@ -287,7 +287,8 @@ def serve_gpu(rs, W) -> dict:
         row["ratio"] = round(row["fcfs_mean_latency_s"] / row["relserve_mean_latency_s"], 3)
         rows.append(row)
     return {"metric": "mean_relquery_latency_s", "clock": "sum of the measured GPU durations of the executed batches",
-            "model": f"13B layer shape x {layers} layers, vocab {vocab}, random-init", "prefill_model": mp, "decode_model": md,
+            "model": f"13B layer shape x {layers} layers, vocab {vocab}, random-init" + (", quantised projections" if w8a8 else ""),
+            "prefill_model": mp, "decode_model": md,
             "trace": "80 relQueries per run, 1-100 requests each, templates 256-1024 tokens, suffixes 30-120, output 5 or 50 tokens",
             "prefix_cache": {"tokens_served_from_cache": worker.cache.hits, "tokens_computed": worker.cache.misses},
             "results": rows}
@@ -540,7 +541,7 @@ def main() -> None:
         print(json.dumps(model_step_bench(args, rs, W, torch)))
         return
     if args.serve_gpu:
-        print(json.dumps(serve_gpu(rs, W)))
+        print(json.dumps(serve_gpu(rs, W, args.w8a8)))
         return
     if args.serve_sim:
         from paper_2601_11546_amd import duration_model, scheduler

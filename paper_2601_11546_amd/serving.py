@@ -29,7 +29,7 @@ def token_ids(template: int, rid: int, req: int, first: int, n: int, prefix: int
 
 class GpuWorker:
     def __init__(self, shape: W.LayerShape, n_layers: int, vocab: int, num_pages: int, max_tokens: int, max_reqs: int,
-                 seed: int = 0, keep_logits: bool = False):
+                 seed: int = 0, keep_logits: bool = False, w8a8: bool = False):
         import torch
         self.torch, self.shape, self.vocab, self.n_layers = torch, shape, vocab, n_layers
         g = torch.Generator(device="cuda")
@@ -44,6 +44,9 @@ class GpuWorker:
         layers = [{"w_in_norm": randn(H, std=0.02, mean=1.0), "w_qkv": randn(shape.qkv_dim, H, std=0.02),
                    "w_o": randn(H, qd, std=res_std), "w_post_norm": randn(H, std=0.02, mean=1.0),
                    "w_gate_up": randn(2 * I, H, std=0.02), "w_down": randn(H, I, std=res_std)} for _ in range(n_layers)]
+        if w8a8:     # the quantised-projection variant of every layer (the model step then runs relserve_model_step_w8a8)
+            from .duration_model import quantise_layer_on_device
+            layers = [quantise_layer_on_device(torch, w) for w in layers]
         self.model = {"embedding": randn(vocab, H), "layers": layers,
                       "caches": [(torch.zeros(pool, dtype=torch.bfloat16, device="cuda"),
                                   torch.zeros(pool, dtype=torch.bfloat16, device="cuda")) for _ in range(n_layers)],

@@ -906,6 +906,8 @@ hipError_t launch_split(GemmArgs p, int splits, hipStream_t s) {
     p.k_per_split = (nk + splits - 1) / splits;
     splits = (nk + p.k_per_split - 1) / p.k_per_split;   // no empty split: the finish kernel reads every slab
     p.n_splits = splits;
+    // the slabs [split][T, N] have to fit what the workspace reserves (a lower bound of it: this projection's own N)
+    if ((int64_t)splits * p.T * p.N > gemm_scratch_floats(p.T, p.N)) return hipErrorInvalidValue;
     auto go = [&](auto f8) -> hipError_t {
         constexpr bool F8 = decltype(f8)::value;
         static std::once_flag once;

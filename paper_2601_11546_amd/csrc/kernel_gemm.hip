@@ -94,15 +94,28 @@ __device__ __forceinline__ int remap_xcd(int bid, int num) {
     return xcd < rem ? xcd * (per + 1) + idx : rem * (per + 1) + (xcd - rem) * per + idx;
 }
 
-// Tile order inside an XCD's run: token tiles fastest within panels of GROUP_M token tiles, then
+// Tile order inside an XCD's run: token tiles fastest within panels of about GROUP_M token tiles, then
 // feature tiles, then the next panel.  The ~32 tiles an XCD works on at a time then cover about
 // GROUP_M token tiles x 32 / GROUP_M feature tiles, so that its L2 serves ~12 distinct operand
-// slices per k step instead of 33 when the batch has many token tiles.
+// slices per k step instead of 33 when the batch has many token tiles.  The token tiles are divided
+// evenly over the panels (9 token tiles: panels of 5 and 4, not of 8 and 1 -- a panel of one token tile
+// shares nothing but its activation slice).
 constexpr int GROUP_M = 8;
 __device__ __forceinline__ void tile_coords(int t, int tiles_m, int tiles_n, int& tile_m, int& tile_n) {
-    const int per_group = GROUP_M * tiles_n;
-    const int first_m = (t / per_group) * GROUP_M, in_group = t % per_group;
-    const int gsz = min(tiles_m - first_m, GROUP_M);
+    const int n_panels = (tiles_m + GROUP_M - 1) / GROUP_M;
+    const int base = tiles_m / n_panels, extra = tiles_m % n_panels;   // the first `extra` panels hold base + 1 token tiles
+    const int big = (base + 1) * tiles_n;
+    int first_m, gsz, in_group;
+    if (t < extra * big) {
+        gsz = base + 1;
+        first_m = (t / big) * gsz;
+        in_group = t % big;
+    } else {
+        const int u = t - extra * big, per = base * tiles_n;
+        gsz = base;
+        first_m = extra * (base + 1) + (u / per) * base;
+        in_group = u % per;
+    }
     tile_m = first_m + in_group % gsz;
     tile_n = in_group / gsz;
 }

@@ -204,32 +204,42 @@ __device__ __forceinline__ void attn_tile_body(const AttnArgs& p, int item_idx, 
     const int last_key = it.key_end - 1;
     const int lrow = lane / CH, lslot = lane % CH;
     const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem;
-    int64_t slot_cur[IT], slot_nxt[IT];
-    auto lookup = [&](int kb0, int64_t (&slots)[IT]) {   // block-table entries of this lane's rows
+    // A lookup keeps the page numbers as they were loaded; the slot arithmetic waits until the block is issued, one
+    // iteration later.  (The compiler places the wait for a load in front of its first use, and it does not count the
+    // direct-to-LDS loads, which sit in inline assembly: arithmetic on a page number straight after the lookup would
+    // wait for every load issued before it -- the next block's keys and values -- and undo the double buffer.)
+    struct Pages { int32_t page[IT]; int kb0; };
+    Pages pg_cur, pg_nxt;
+    auto lookup = [&](int kb0, Pages& pg) {   // block-table entries of this lane's rows
+        pg.kb0 = kb0;
 #pragma unroll
         for (int j = 0; j < IT; ++j) {
             const int key = min(kb0 + (4 * j + wave) * RPI + lrow, last_key);
-            slots[j] = ((int64_t)bt[key >> p.page_shift] << p.page_shift) + (key & p.page_mask);
+            pg.page[j] = bt[key >> p.page_shift];
         }
     };
-    auto issue = [&](int buf, const int64_t (&slots)[IT]) {
+    auto slot_of = [&](const Pages& pg, int j) -> int64_t {
+        const int key = min(pg.kb0 + (4 * j + wave) * RPI + lrow, last_key);
+        return ((int64_t)pg.page[j] << p.page_shift) + (key & p.page_mask);
+    };
+    auto issue = [&](int buf, const Pages& pg) {
         const uint32_t base = lds0 + buf * SM::STAGE + wave * 1024;
 #pragma unroll
         for (int j = 0; j < IT; ++j) {
             const int row = (4 * j + wave) * RPI + lrow;
-            const int64_t off = (slots[j] * p.n_kv + kvh) * D;
+            const int64_t off = (slot_of(pg, j) * p.n_kv + kvh) * D;
             dma16_ptr(p.k_pages + off + ((lslot ^ kswz<D>(row)) << 3), base + j * 4096);
             dma16_ptr(p.v_pages + off + ((lslot ^ vswz<D>(row)) << 3), base + SM::K_BYTES + j * 4096);
         }
     };
     uint2 k_raw[IT], v_raw[IT];   // FP8 only: the block on its way through registers
-    auto load_raw = [&](const int64_t (&slots)[IT]) {
+    auto load_raw = [&](const Pages& pg) {
         const uint8_t* k8 = reinterpret_cast<const uint8_t*>(p.k_pages);
         const uint8_t* v8 = reinterpret_cast<const uint8_t*>(p.v_pages);
 #pragma unroll
         for (int j = 0; j < IT; ++j) {
             const int row = (4 * j + wave) * RPI + lrow;
-            const int64_t off = (slots[j] * p.n_kv + kvh) * D;
+            const int64_t off = (slot_of(pg, j) * p.n_kv + kvh) * D;
             k_raw[j] = *reinterpret_cast<const uint2*>(k8 + off + ((lslot ^ kswz<D>(row)) << 3));
             v_raw[j] = *reinterpret_cast<const uint2*>(v8 + off + ((lslot ^ vswz<D>(row)) << 3));
         }
@@ -245,14 +255,16 @@ __device__ __forceinline__ void attn_tile_body(const AttnArgs& p, int item_idx, 
 
     const int n_blocks = (it.key_end - it.key_begin + BLOCK_N - 1) / BLOCK_N;
     if (n_blocks > 0) {
-        lookup(it.key_begin, slot_cur);
+        lookup(it.key_begin, pg_cur);
+#pragma unroll
+        for (int j = 0; j < IT; ++j) asm volatile("" ::"v"(pg_cur.page[j]));   // all of them before the first direct load (see the loop)
         if (FP8) {
-            load_raw(slot_cur);
+            load_raw(pg_cur);
             store_raw(0);
         } else {
-            issue(0, slot_cur);
+            issue(0, pg_cur);
         }
-        lookup(min(it.key_begin + BLOCK_N, last_key), slot_nxt);
+        lookup(min(it.key_begin + BLOCK_N, last_key), pg_nxt);
     }
     // Operand addresses inside a stage that do not change from block to block.  K: key row
     // 32 t + l32, chunk (2 ks + g) ^ kswz (the swizzle only depends on l32).  V: the transposing read
@@ -276,15 +288,20 @@ __device__ __forceinline__ void attn_tile_body(const AttnArgs& p, int item_idx, 
     // The three phases of a 32-key tile.  The block loop issues the score MFMAs of BOTH tiles first, so
     // that the second tile's MFMAs (and later the first tile's P V MFMAs) run while the VALU does the
     // other tile's softmax.
-    auto scores = [&](int t, const unsigned char* stage) {
+    // Operand reads are issued in batches ahead of the MFMAs that use them, with explicit waits: left to itself the
+    // compiler keeps one fragment in flight (read, wait, MFMA, read, ...) to save registers, and every MFMA then
+    // waits out an LDS round trip.
+    auto read_k = [&](int t, const unsigned char* stage, bf16x8_t (&kf)[D / 16]) {
+#pragma unroll
+        for (int ks = 0; ks < D / 16; ++ks)
+            kf[ks] = as_bf16x8(*reinterpret_cast<const uint4*>(stage + k_off[ks] + t * 32 * SM::ROWB));
+    };
+    auto scores = [&](const bf16x8_t (&kf)[D / 16]) {
         f32x16_t sc;
 #pragma unroll
         for (int r = 0; r < 16; ++r) sc[r] = 0.f;
 #pragma unroll
-        for (int ks = 0; ks < D / 16; ++ks) {
-            const bf16x8_t kf = as_bf16x8(*reinterpret_cast<const uint4*>(stage + k_off[ks] + t * 32 * SM::ROWB));
-            sc = mfma_32x32x16(kf, qf[ks], sc);
-        }
+        for (int ks = 0; ks < D / 16; ++ks) sc = mfma_32x32x16(kf[ks], qf[ks], sc);
         return sc;
     };
     auto softmax = [&](f32x16_t& sc, bool masked, int key0, bf16x8_t (&pf)[2]) {
@@ -330,7 +347,7 @@ __device__ __forceinline__ void attn_tile_body(const AttnArgs& p, int item_idx, 
     };
     // Element e of lane group g's probabilities is key 32 t + 16 h + 8 (e / 4) + 4 g + e % 4; the two
     // transposing reads fetch those keys.
-    auto weighted_values = [&](int t, const unsigned char* stage, const bf16x8_t (&pf)[2]) {
+    auto read_v = [&](int t, const unsigned char* stage, bf16x8_t (&vf)[D / 32][2]) {
         typedef short short8_t __attribute__((ext_vector_type(8)));
         typedef short4_t __attribute__((address_space(3))) * lds_v4;
 #pragma unroll
@@ -341,31 +358,56 @@ __device__ __forceinline__ void attn_tile_body(const AttnArgs& p, int item_idx, 
                 const short4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(a0));
                 const short4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(a0 + 8 * SM::ROWB));
                 const short8_t v8 = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-                st.o[td] = mfma_32x32x16(__builtin_bit_cast(bf16x8_t, v8), pf[h], st.o[td]);
+                vf[td][h] = __builtin_bit_cast(bf16x8_t, v8);
             }
+    };
+    auto weighted_values = [&](const bf16x8_t (&vf)[D / 32][2], const bf16x8_t (&pf)[2]) {
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+#pragma unroll
+            for (int td = 0; td < D / 32; ++td) st.o[td] = mfma_32x32x16(vf[td][h], pf[h], st.o[td]);
     };
     for (int b = 0; b < n_blocks; ++b) {
         const int kb0 = it.key_begin + b * BLOCK_N;
         // this block has landed for every wave, and every wave is done with the other buffer
         if (!FP8) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        // the page numbers looked up during the previous iteration count as used from here on: the compiler's own
+        // waits for them (it does not see the direct-to-LDS loads) all fall here, where nothing is in flight, and
+        // not between the loads issued below
+#pragma unroll
+        for (int j = 0; j < IT; ++j) asm volatile("" ::"v"(pg_nxt.page[j]));
         __syncthreads();
         if (b + 1 < n_blocks) {
             if (FP8)
-                load_raw(slot_nxt);                               // into registers; stored behind this block's arithmetic
+                load_raw(pg_nxt);                               // into registers; stored behind this block's arithmetic
             else
-                issue((b + 1) & 1, slot_nxt);
-            lookup(min(kb0 + 2 * BLOCK_N, last_key), slot_nxt);   // consumed one iteration later
+                issue((b + 1) & 1, pg_nxt);
+            lookup(min(kb0 + 2 * BLOCK_N, last_key), pg_nxt);   // consumed one iteration later
         }
         if (wave_active && kb0 < wave_klim_max) {
             const unsigned char* stage = smem + (b & 1) * SM::STAGE;
             const bool masked = __builtin_amdgcn_readfirstlane(kb0 + BLOCK_N > wave_klim_min);
-            f32x16_t sc0 = scores(0, stage);
-            f32x16_t sc1 = scores(1, stage);
-            bf16x8_t pf[2];
+            bf16x8_t kf0[D / 16], kf1[D / 16], vf[D / 32][2], pf[2];
+            read_k(0, stage, kf0);
+            read_k(1, stage, kf1);
+            __builtin_amdgcn_sched_barrier(0);     // (MFMAs are no memory operations: only this keeps them behind the batch)
+            asm volatile("s_waitcnt lgkmcnt(%0)" ::"n"(D / 16) : "memory");    // the first tile's keys (LDS reads return in order)
+            f32x16_t sc0 = scores(kf0);
+            __builtin_amdgcn_sched_barrier(0);
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+            read_v(0, stage, vf);                  // land while the second tile's scores and the first tile's softmax run
+            __builtin_amdgcn_sched_barrier(0);
+            f32x16_t sc1 = scores(kf1);
+            __builtin_amdgcn_sched_barrier(0);
             softmax(sc0, masked, kb0, pf);
-            weighted_values(0, stage, pf);
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+            weighted_values(vf, pf);
+            __builtin_amdgcn_sched_barrier(0);
+            read_v(1, stage, vf);                  // behind the MFMAs that read the first tile's values
+            __builtin_amdgcn_sched_barrier(0);
             softmax(sc1, masked, kb0 + 32, pf);
-            weighted_values(1, stage, pf);
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+            weighted_values(vf, pf);
         }
         // the other buffer is free since the barrier above: every wave had finished the previous block before it
         if (FP8 && b + 1 < n_blocks) store_raw((b + 1) & 1);
@@ -463,19 +505,26 @@ __device__ __forceinline__ void attn_decode_body(const AttnArgs& p, const AttnIt
     const int32_t* bt = p.block_table + (int64_t)it.bt_req * p.max_blocks;
     const int last_key = it.key_end - 1;
     const int lrow = lane / CH, lslot = lane % CH;
-    int64_t slots[IT];
+    // page numbers as loaded; the slot arithmetic waits until the block is issued (see the tiled kernel's lookup)
+    int32_t pg[IT];
+    int pg_kb0 = 0;
     auto lookup = [&](int kb0) {
+        pg_kb0 = kb0;
 #pragma unroll
         for (int j = 0; j < IT; ++j) {
             const int key = min(kb0 + j * RPI + lrow, last_key);
-            slots[j] = ((int64_t)bt[key >> p.page_shift] << p.page_shift) + (key & p.page_mask);
+            pg[j] = bt[key >> p.page_shift];
         }
+    };
+    auto slot_of = [&](int j) -> int64_t {
+        const int key = min(pg_kb0 + j * RPI + lrow, last_key);
+        return ((int64_t)pg[j] << p.page_shift) + (key & p.page_mask);
     };
     auto issue_k = [&]() {
 #pragma unroll
         for (int j = 0; j < IT; ++j) {
             const int row = j * RPI + lrow;
-            const int64_t off = (slots[j] * p.n_kv + kvh) * D;
+            const int64_t off = (slot_of(j) * p.n_kv + kvh) * D;
             dma16_ptr_nt(p.k_pages + off + ((lslot ^ kswz<D>(row)) << 3), lds0 + j * 1024);
         }
     };
@@ -483,7 +532,7 @@ __device__ __forceinline__ void attn_decode_body(const AttnArgs& p, const AttnIt
 #pragma unroll
         for (int j = 0; j < IT; ++j) {
             const int row = j * RPI + lrow;
-            const int64_t off = (slots[j] * p.n_kv + kvh) * D;
+            const int64_t off = (slot_of(j) * p.n_kv + kvh) * D;
             dma16_ptr_nt(p.v_pages + off + ((lslot ^ dvswz<D>(row)) << 3), lds0 + SM::K_BYTES + j * 1024);
         }
     };
@@ -498,7 +547,7 @@ __device__ __forceinline__ void attn_decode_body(const AttnArgs& p, const AttnIt
 #pragma unroll
         for (int j = 0; j < IT; ++j) {
             const int row = j * RPI + lrow;
-            const int64_t off = (slots[j] * p.n_kv + kvh) * D;
+            const int64_t off = (slot_of(j) * p.n_kv + kvh) * D;
             // read once: non-temporal, as the direct loads of the 16-bit path
             const uint64_t kk = __builtin_nontemporal_load(reinterpret_cast<const uint64_t*>(k8 + off + ((lslot ^ kswz<D>(row)) << 3)));
             const uint64_t vv = __builtin_nontemporal_load(reinterpret_cast<const uint64_t*>(v8 + off + ((lslot ^ dvswz<D>(row)) << 3)));
@@ -530,6 +579,8 @@ __device__ __forceinline__ void attn_decode_body(const AttnArgs& p, const AttnIt
     const int n_blocks = (it.key_end - it.key_begin + SM::BLOCK_N - 1) / SM::BLOCK_N;
     if (n_blocks > 0) {
         lookup(it.key_begin);
+#pragma unroll
+        for (int j = 0; j < IT; ++j) asm volatile("" ::"v"(pg[j]));   // all of them before the first direct load (see the loop)
         if (FP8) load_raw(); else issue();
         if (n_blocks > 1) lookup(it.key_begin + SM::BLOCK_N);
     }
@@ -545,6 +596,8 @@ __device__ __forceinline__ void attn_decode_body(const AttnArgs& p, const AttnIt
             }
         } else {
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the block has landed
+#pragma unroll
+            for (int j = 0; j < IT; ++j) asm volatile("" ::"v"(pg[j]));   // the compiler's waits for the page numbers fall here
         }
 
         // S^T = K Q^T for two 16-key tiles; lane holds keys kb0 + 16 t + 4 gq + r of query row l16
